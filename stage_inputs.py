@@ -1,0 +1,227 @@
+"""Seeded synthetic inputs for the stage-verifier tests and benchmark.
+
+This module only *generates inputs*: stage descriptors, random weights, activations,
+loss gradients, and the corrupted submissions ("attacks") that a dishonest stage
+worker would send.  It holds none of the verifier's arithmetic (no block forward or
+backward, no distance statistic, no flag rule) so that the CPU oracle and the HIP
+library can both be fed from it without sharing any of the method's code.
+
+Attack shapes follow the paper's "Attack Variants" paragraph (Problem Statement):
+scaling x -> alpha*x, random sign flips, bias (additive Gaussian noise) and the
+constant (zeros) attack.  Workload shapes are the five benchmark configurations of
+this repository (tiny / small / medium / large / sweep).
+
+Everything is numpy; values destined for a bf16 stage are rounded to
+bf16-representable fp32 here so that both consumers see bit-identical inputs.
+"""
+from __future__ import annotations
+
+import dataclasses
+import math
+from typing import Dict, List, Optional, Tuple
+
+import numpy as np
+
+
+# --------------------------------------------------------------------------- descriptors
+@dataclasses.dataclass(frozen=True)
+class StageDesc:
+    """Hyper-parameters of one pipeline stage (n_blocks identical pre-norm blocks)."""
+    n_blocks: int
+    d_model: int
+    n_heads: int
+    n_kv_heads: int
+    ffn_hidden: int
+    mlp: str = "swiglu"          # "swiglu" | "gelu"
+    norm: str = "rms"            # "rms" | "ln"
+    rope: bool = True
+    causal: bool = True
+    norm_eps: float = 1e-5
+    rope_theta: float = 500000.0
+    dtype: str = "bf16"          # "bf16" | "f32"
+
+    @property
+    def head_dim(self) -> int:
+        return self.d_model // self.n_heads
+
+
+@dataclasses.dataclass(frozen=True)
+class Workload:
+    name: str
+    desc: StageDesc
+    batch: int
+    seq: int
+    tau: float
+    n_claims: int
+    backward: bool = False
+
+
+TINY = Workload("tiny", StageDesc(1, 128, 4, 4, 512, mlp="gelu", norm="ln", rope=False,
+                                  causal=True, dtype="f32"), batch=2, seq=64, tau=1e-3, n_claims=8)
+SMALL = Workload("small", StageDesc(2, 1024, 16, 16, 2816), batch=8, seq=512, tau=2e-2, n_claims=64)
+MEDIUM = Workload("medium", StageDesc(4, 2048, 16, 16, 5632), batch=8, seq=1024, tau=2e-2,
+                  n_claims=10, backward=True)
+LARGE = Workload("large", StageDesc(4, 4096, 32, 8, 14336), batch=4, seq=2048, tau=2e-2, n_claims=32)
+
+
+def sweep_point(seq: int, batch: int) -> Workload:
+    return Workload(f"sweep_s{seq}_b{batch}", StageDesc(1, 4096, 32, 8, 14336), batch=batch, seq=seq,
+                    tau=2e-2, n_claims=128, backward=True)
+
+
+WORKLOADS: Dict[str, Workload] = {w.name: w for w in (TINY, SMALL, MEDIUM, LARGE)}
+
+
+# --------------------------------------------------------------------------- bf16 helpers
+def round_to_bf16(x: np.ndarray) -> np.ndarray:
+    """Round fp32 values to the nearest bf16 (ties to even); result stays fp32."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    u = x.view(np.uint32).astype(np.uint64)
+    lsb = (u >> 16) & 1
+    u = (u + 0x7FFF + lsb) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).reshape(x.shape)
+
+
+def to_stage_dtype(x: np.ndarray, dtype: str) -> np.ndarray:
+    x = np.asarray(x, dtype=np.float32)
+    return round_to_bf16(x) if dtype == "bf16" else x
+
+
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """uint16 bit patterns of already bf16-representable fp32 values."""
+    return (np.ascontiguousarray(x, dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32)
+
+
+# --------------------------------------------------------------------------- generators
+def _rng(seed: int, stream: int) -> np.random.Generator:
+    return np.random.Generator(np.random.Philox(key=[int(seed), int(stream)]))
+
+
+def make_weights(desc: StageDesc, seed: int = 0) -> List[Dict[str, Optional[np.ndarray]]]:
+    """Per-block weights.  Matrices ~ N(0, 0.02^2) stored [out, in]; norm gains
+    1 + 0.1 N(0,1) and LayerNorm biases 0.02 N(0,1) so that they are exercised."""
+    D, hd = desc.d_model, desc.head_dim
+    Hq, Hkv, F = desc.n_heads * hd, desc.n_kv_heads * hd, desc.ffn_hidden
+    blocks = []
+    for b in range(desc.n_blocks):
+        g = _rng(seed, 1000 + b)
+
+        def mat(o, i):
+            return to_stage_dtype(0.02 * g.standard_normal((o, i), dtype=np.float32), desc.dtype)
+
+        def vec(n, mean, std):
+            return to_stage_dtype(mean + std * g.standard_normal(n, dtype=np.float32), desc.dtype)
+
+        w = dict(wq=mat(Hq, D), wk=mat(Hkv, D), wv=mat(Hkv, D), wo=mat(D, Hq))
+        if desc.mlp == "swiglu":
+            w.update(w_gate=mat(F, D), w_up=mat(F, D), w_down=mat(D, F))
+        else:
+            w.update(w_gate=None, w_up=mat(F, D), w_down=mat(D, F))
+        w.update(norm1_g=vec(D, 1.0, 0.1), norm2_g=vec(D, 1.0, 0.1))
+        if desc.norm == "ln":
+            w.update(norm1_b=vec(D, 0.0, 0.02), norm2_b=vec(D, 0.0, 0.02))
+        else:
+            w.update(norm1_b=None, norm2_b=None)
+        blocks.append(w)
+    return blocks
+
+
+def make_activations(desc: StageDesc, batch: int, seq: int, seed: int, micro_batch: int = 0) -> np.ndarray:
+    """Stage input h_s ~ N(0,1), shape [batch, seq, d_model]."""
+    g = _rng(seed, 2000 + micro_batch)
+    return to_stage_dtype(g.standard_normal((batch, seq, desc.d_model), dtype=np.float32), desc.dtype)
+
+
+def make_output_grad(desc: StageDesc, batch: int, seq: int, seed: int, micro_batch: int = 0,
+                     std: float = 1e-3) -> np.ndarray:
+    """Loss gradient at the stage output, g_{s+1} ~ N(0, std^2)."""
+    g = _rng(seed, 3000 + micro_batch)
+    return to_stage_dtype(std * g.standard_normal((batch, seq, desc.d_model), dtype=np.float32), desc.dtype)
+
+
+# --------------------------------------------------------------------------- submissions
+def honest_claim(reference: np.ndarray, dtype: str) -> np.ndarray:
+    """What an honest worker sends: the true signal in the stage's storage dtype."""
+    return to_stage_dtype(np.asarray(reference, dtype=np.float32), dtype)
+
+
+def attack_scale(x: np.ndarray, alpha: float, dtype: str) -> np.ndarray:
+    return to_stage_dtype(np.float32(alpha) * np.asarray(x, np.float32), dtype)
+
+
+def attack_noise(x: np.ndarray, rel_std: float, seed: int, dtype: str) -> np.ndarray:
+    """Bias-addition attack with sigma = rel_std * RMS(x)."""
+    x = np.asarray(x, np.float32)
+    rms = float(np.sqrt(np.mean(np.square(x, dtype=np.float64))))
+    eps = _rng(seed, 4000).standard_normal(x.shape, dtype=np.float32)
+    return to_stage_dtype(x + np.float32(rel_std * rms) * eps, dtype)
+
+
+def attack_sign_channels(x: np.ndarray, frac: float, seed: int, dtype: str) -> Tuple[np.ndarray, np.ndarray]:
+    """Flip the sign of ceil(frac*D) feature channels (chosen without replacement) on every token."""
+    x = np.array(x, dtype=np.float32, copy=True)
+    D = x.shape[-1]
+    n = int(math.ceil(frac * D))
+    ch = np.sort(_rng(seed, 5000).permutation(D)[:n])
+    x[..., ch] = -x[..., ch]
+    return to_stage_dtype(x, dtype), ch
+
+
+def attack_zero(x: np.ndarray, dtype: str) -> np.ndarray:
+    return np.zeros_like(np.asarray(x, np.float32))
+
+
+def attack_tokens(x: np.ndarray, frac: float, kind: str, seed: int, dtype: str) -> Tuple[np.ndarray, np.ndarray]:
+    """Corrupt only ceil(frac*T) random tokens of x [.., D] (flattened token index returned).
+    kind: "noise" (0.1 * token RMS), "scale" (x1.5), "neg" (x-1), "zero"."""
+    x = np.array(x, dtype=np.float32, copy=True)
+    flat = x.reshape(-1, x.shape[-1])
+    T = flat.shape[0]
+    n = int(math.ceil(frac * T))
+    g = _rng(seed, 6000)
+    tok = np.sort(g.permutation(T)[:n])
+    if kind == "noise":
+        rms = np.sqrt(np.mean(np.square(flat[tok], dtype=np.float64), axis=1, keepdims=True)).astype(np.float32)
+        flat[tok] += 0.1 * rms * g.standard_normal((n, flat.shape[1]), dtype=np.float32)
+    elif kind == "scale":
+        flat[tok] *= np.float32(1.5)
+    elif kind == "neg":
+        flat[tok] *= np.float32(-1.0)
+    elif kind == "zero":
+        flat[tok] = 0.0
+    else:
+        raise ValueError(kind)
+    return to_stage_dtype(x, dtype), tok
+
+
+def small_claim_plan(n_claims: int = 64, seed: int = 0) -> List[str]:
+    """Small config: 10 % scaled by 1.5, 10 % sign-flipped on 5 % of channels, rest honest."""
+    n_bad = int(round(0.1 * n_claims))
+    kinds = ["honest"] * n_claims
+    order = _rng(seed, 7000).permutation(n_claims)
+    for i in order[:n_bad]:
+        kinds[int(i)] = "scale"
+    for i in order[n_bad:2 * n_bad]:
+        kinds[int(i)] = "sign"
+    return kinds
+
+
+def make_claim(kind: str, reference: np.ndarray, dtype: str, seed: int) -> np.ndarray:
+    """One submission of the given kind manufactured from the true signal `reference`."""
+    if kind == "honest":
+        return honest_claim(reference, dtype)
+    if kind == "scale":
+        return attack_scale(reference, 1.5, dtype)
+    if kind == "noise":
+        return attack_noise(reference, 0.1, seed, dtype)
+    if kind == "sign":
+        return attack_sign_channels(reference, 0.05, seed, dtype)[0]
+    if kind == "zero":
+        return attack_zero(reference, dtype)
+    if kind.startswith("tok_"):
+        return attack_tokens(reference, 0.01, kind[4:], seed, dtype)[0]
+    raise ValueError(kind)
