@@ -1,0 +1,196 @@
+#!/usr/bin/env python3
+"""Benchmark of the stage-verifier hot path on one MI355X.
+
+One step = one stage check of one micro-batch through the C ABI: recompute the stage on the
+worker's input (all blocks), then score the claimed output (and, for fwd+bwd workloads, the
+claimed input gradient) and flag it.  Inputs, weights and claims are synthetic, generated on
+the device before the timed region (shapes of the benchmark configs; claims are the device
+recomputation with 1 % of tokens corrupted, so the flag path does real work).
+
+Prints ONE JSON line with the verified tokens/s, the MFMA roofline of the dominant kernel (the
+gate/up projection GEMM, timed with HIP events on the launch stream during the timed steps)
+and the CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="large", help="tiny|small|medium|large|sweep_s<S>_b<B>")
+    ap.add_argument("--mode", default=None, choices=[None, "fwd", "fwdbwd"], help="default: the workload's own")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--plain", action="store_true", help="run the plain (non-MFMA) kernels")
+    return ap.parse_args()
+
+
+def get_workload(name):
+    import stage_inputs as si
+    if name in si.WORKLOADS:
+        return si.WORKLOADS[name]
+    if name.startswith("sweep_s"):
+        s, b = name[len("sweep_s"):].split("_b")
+        return si.sweep_point(int(s), int(b))
+    raise SystemExit(f"unknown workload {name}")
+
+
+def device_weights(desc, torch):
+    """Random-init weights of the stage's shapes, generated on the device (N(0, 0.02^2) matrices)."""
+    dt = torch.bfloat16 if desc.dtype == "bf16" else torch.float32
+    g = torch.Generator(device="cuda").manual_seed(0)
+    D, hd = desc.d_model, desc.head_dim
+    Hq, Hkv, F = desc.n_heads * hd, desc.n_kv_heads * hd, desc.ffn_hidden
+
+    def mat(o, i):
+        return (0.02 * torch.randn((o, i), generator=g, device="cuda", dtype=torch.float32)).to(dt)
+
+    def vec(mean, std):
+        return (mean + std * torch.randn(D, generator=g, device="cuda", dtype=torch.float32)).to(dt)
+
+    blocks = []
+    for _ in range(desc.n_blocks):
+        w = dict(wq=mat(Hq, D), wk=mat(Hkv, D), wv=mat(Hkv, D), wo=mat(D, Hq), w_up=mat(F, D), w_down=mat(D, F),
+                 w_gate=mat(F, D) if desc.mlp == "swiglu" else None, norm1_g=vec(1.0, 0.1), norm2_g=vec(1.0, 0.1),
+                 norm1_b=vec(0.0, 0.02) if desc.norm == "ln" else None, norm2_b=vec(0.0, 0.02) if desc.norm == "ln" else None)
+        blocks.append(w)
+    return blocks
+
+
+def corrupt_tokens(x, torch, frac=0.01):
+    """Claim manufactured on the device: the recomputation with `frac` of the tokens scaled by 1.5."""
+    c = x.clone()
+    flat = c.view(-1, c.shape[-1])
+    n = max(1, int(frac * flat.shape[0]))
+    idx = torch.randperm(flat.shape[0], device=x.device, generator=torch.Generator(device="cuda").manual_seed(1))[:n]
+    flat[idx] = (flat[idx].float() * 1.5).to(c.dtype)
+    return c
+
+
+def cpu_baseline(wl, wdev, h_in, g_out, backward):
+    """The oracle as it stands, on one sequence of the micro-batch (stage work is independent per sequence)."""
+    import numpy as np
+    from oracle import stage_oracle as so
+    w = [{k: (None if v is None else v.float().cpu().numpy()) for k, v in b.items()} for b in wdev]
+    h = h_in[:1].float().cpu().numpy()
+    t0 = time.perf_counter()
+    if backward:
+        so.stage_backward(h, g_out[:1].float().cpu().numpy(), w, wl.desc)
+    else:
+        so.stage_forward(h, w, wl.desc)
+    dt = time.perf_counter() - t0
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count()])
+    except Exception:
+        cores = os.cpu_count()
+    return {"value": wl.seq / dt, "unit": "verified tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"1 of {wl.batch} sequences ({wl.seq} tokens) through all {wl.desc.n_blocks} blocks, "
+                      f"{'fwd+bwd' if backward else 'fwd'}, numpy float64, {dt:.1f} s"}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path (every stage check is "
+                         "independent per micro-batch; see DESIGN.md for how it would shard). Use --gpus 1.")
+    import torch
+    import paper_2603_03592_amd as sv
+    wl = get_workload(a.workload)
+    backward = wl.backward if a.mode is None else (a.mode == "fwdbwd")
+    desc, B, S = wl.desc, wl.batch, wl.seq
+    T = B * S
+    torch.cuda.set_device(0)
+    dt = torch.bfloat16 if desc.dtype == "bf16" else torch.float32
+    wdev = device_weights(desc, torch)
+    g = torch.Generator(device="cuda").manual_seed(2)
+    h_in = torch.randn((B, S, desc.d_model), generator=g, device="cuda", dtype=torch.float32).to(dt)
+    g_out = (1e-3 * torch.randn((B, S, desc.d_model), generator=g, device="cuda", dtype=torch.float32)).to(dt)
+
+    ver = sv.Verifier(desc, T, S, backward=backward, plain_kernels=a.plain)
+    wc = ver.pack_weights(wdev)
+    tau = {"rel_l2": wl.tau}
+    if backward:
+        first = ver.verify_backward(wc, h_in, g_out, want_g_hat=True, want_h_hat=True)
+        claim_h, claim_g = corrupt_tokens(first["h_hat"], torch), corrupt_tokens(first["g_hat"], torch)
+    else:
+        first = ver.verify_forward(wc, h_in, want_h_hat=True)
+        claim_h, claim_g = corrupt_tokens(first["h_hat"], torch), None
+    res = torch.empty((2, 32), dtype=torch.uint8, device="cuda")
+    h_hat = torch.empty_like(h_in) if backward else None
+    dcode = 1 if desc.dtype == "bf16" else 0
+    tau_c = (sv.binding.C.c_float * 4)(wl.tau, 0, 0, 0)
+    stream = torch.cuda.current_stream().cuda_stream
+    L = sv.lib
+
+    def step():
+        if backward:
+            # one pass recomputes forward and backward; the gradient claim is scored inside the call,
+            # the activation claim against the recomputed stage output it hands back
+            st = L.sv_verify_backward(ver._ctx, wc, h_in.data_ptr(), g_out.data_ptr(), B, S, claim_g.data_ptr(), 1, tau_c, 1,
+                                      None, h_hat.data_ptr(), None, res[1:].data_ptr(), stream)
+            assert st == 0, L.sv_last_error(ver._ctx)
+            st = L.sv_score_and_flag(ver._ctx, claim_h.data_ptr(), 0, 1, h_hat.data_ptr(), 0, dcode, dcode, T, desc.d_model, 1,
+                                     tau_c, 1, None, res.data_ptr(), stream)
+            assert st == 0, L.sv_last_error(ver._ctx)
+        else:
+            st = L.sv_verify_forward(ver._ctx, wc, h_in.data_ptr(), B, S, claim_h.data_ptr(), 1, tau_c, 1, None, None,
+                                     res.data_ptr(), stream)
+            assert st == 0, L.sv_last_error(ver._ctx)
+
+    for _ in range(a.warmup):
+        step()
+    torch.cuda.synchronize()
+    ver.profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    prof = ver.profile_read()
+    ver.profile_enable(False)
+    flags = ver.read_results(res)["flag"]
+    assert flags[0] == 1 and (not backward or flags[1] == 1), "the corrupted claims must be flagged"
+
+    ms_step = 1e3 * wall / a.steps
+    tot_flop = sum(p["flop"] for p in prof.values()) / a.steps
+    tot_ms = sum(p["ms"] for p in prof.values()) / a.steps
+    dom = max((k for k in prof if k.startswith(("gemm", "bwd_gemm"))), key=lambda k: prof[k]["flop"])
+    d = prof[dom]
+    achieved = d["flop"] / (d["ms"] * 1e-3) / 1e12 if d["ms"] > 0 else 0.0
+    out = {
+        "metric": "verified tokens/sec per stage check" + (" (fwd+bwd)" if backward else " (fwd)"),
+        "value": T / (ms_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": desc.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "n_blocks": desc.n_blocks, "d_model": desc.d_model, "n_heads": desc.n_heads,
+                   "n_kv_heads": desc.n_kv_heads, "ffn_hidden": desc.ffn_hidden, "micro_batch": B, "seq_len": S,
+                   "check": "fwd+bwd" if backward else "fwd", "claims_per_step": 1, "kernels": "plain" if a.plain else "mfma"},
+        "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "launch_ms": d["ms"] / max(d["launches"], 1), "flop_per_launch": d["flop"] / max(d["launches"], 1)},
+        "recompute": {"flop_per_step": tot_flop, "tflops": tot_flop / (ms_step * 1e-3) / 1e12,
+                      "frac_of_bf16_mfma_peak": tot_flop / (ms_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                      "kernel_ms_per_step": tot_ms,
+                      "per_op_ms": {k: round(v["ms"] / a.steps, 4) for k, v in prof.items() if v["launches"]},
+                      "per_op_tflops": {k: round(v["flop"] / (v["ms"] * 1e-3) / 1e12, 1) for k, v in prof.items() if v["flop"] and v["ms"] > 0}},
+    }
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, wdev, h_in, g_out, backward)
+    ver.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

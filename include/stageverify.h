@@ -1,0 +1,183 @@
+/*
+ * stageverify.h -- C ABI of the MI355X (gfx950) stage verifier.
+ *
+ * A verifier node sits between two pipeline stages and checks what a stage worker
+ * submits: activations h^(s) = f_s(h^(s-1); theta^(s)) on the forward pass and
+ * activation gradients g^(s) = dL/dh^(s-1) on the backward pass (paper, Problem
+ * Statement, "Threat Model" paragraph and Def. threat_model).  This library is the
+ * data-parallel part of that node:
+ *
+ *   sv_verify_forward   recompute f_s on the worker's own micro-batch (duplicate-work
+ *                       verification, "Proposed Method" paragraph / FAQ Q9) and score the
+ *                       claimed h^(s) against it;
+ *   sv_verify_backward  recompute the forward, then the input-gradient backward from the
+ *                       downstream gradient, and score the claimed g^(s) (a backward request
+ *                       carries the stage input again: SWARM appendix, trainer description);
+ *   sv_score_and_flag   the test statistic Gamma = Omega(signal, reference) and the flag rule
+ *                       Gamma > tau (Eq. test_statistic) for the distance family of the
+ *                       paragraph "Choice of Distance Measure" (mean absolute difference,
+ *                       normalised Euclidean, sign flip ratio) plus a per-token relative L2;
+ *                       the reference is any tensor: a recomputation or the EMA m_{t-1};
+ *   sv_ema_update       Eq. momentum_def over the un-flagged submissions (R_clean of
+ *                       Alg. momentum_verification).
+ *
+ * Conventions
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller; row-major, the feature
+ *     dimension innermost.  Activations are [B, S, D] (T = B*S tokens), weights [out, in].
+ *     The library never frees or keeps a caller pointer after the stream work it enqueued.
+ *   - Every call is asynchronous on `stream` (a hipStream_t passed as void*; NULL = the null
+ *     stream) and returns after enqueueing.  Results are written to device memory.
+ *   - Errors are returned as sv_status; sv_last_error(ctx) gives a text.  Shapes a kernel
+ *     does not support are rejected with SV_EUNSUPPORTED, never mis-computed.
+ *   - A context is bound to the device current at sv_create, owns only its workspace, and
+ *     is not thread-safe: use one context per stream.
+ */
+#ifndef STAGEVERIFY_H
+#define STAGEVERIFY_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct sv_ctx sv_ctx;
+
+typedef enum { SV_OK = 0, SV_EINVAL = 1, SV_EUNSUPPORTED = 2, SV_ENOMEM = 3, SV_EHIP = 4 } sv_status;
+typedef enum { SV_F32 = 0, SV_BF16 = 1 } sv_dtype;
+typedef enum { SV_MLP_GELU = 0, SV_MLP_SWIGLU = 1 } sv_mlp;
+typedef enum { SV_NORM_LN = 0, SV_NORM_RMS = 1 } sv_norm;
+typedef enum { SV_REDUCE_GLOBAL = 0, SV_REDUCE_MAX_TOKEN = 1 } sv_reduce;
+
+/* metric indices into score[] / tau[] and their mask bits (1 << index) */
+enum { SV_IDX_RELL2 = 0, SV_IDX_L1 = 1, SV_IDX_ZL2 = 2, SV_IDX_SFR = 3 };
+enum { SV_M_RELL2 = 1, SV_M_L1 = 2, SV_M_ZL2 = 4, SV_M_SFR = 8 };
+
+/* sv_create flags */
+enum {
+  SV_FLAG_BACKWARD = 1,       /* also allocate what sv_verify_backward needs                       */
+  SV_FLAG_PLAIN_KERNELS = 2   /* run the plain fp32-math kernels for every dtype (validation aid)  */
+};
+
+/* One pipeline stage = n_blocks identical pre-norm decoder blocks
+ *   x1 = x + Attn(Norm1(x)) Wo^T,  y = x1 + MLP(Norm2(x1)).
+ * Attention: n_heads query heads of width d_model/n_heads, n_kv_heads key/value heads
+ * (query head h reads kv head h / (n_heads/n_kv_heads)), softmax scale 1/sqrt(head_dim),
+ * optional causal mask, optional RoPE on interleaved pairs (2i, 2i+1) with angle
+ * p * rope_theta^(-2i/head_dim) at in-sequence position p.  No linear biases.            */
+typedef struct {
+  int32_t n_blocks, d_model, n_heads, n_kv_heads, ffn_hidden;
+  int32_t mlp;        /* sv_mlp  */
+  int32_t norm;       /* sv_norm */
+  int32_t rope;       /* 0 | 1   */
+  int32_t causal;     /* 0 | 1   */
+  float   norm_eps;
+  float   rope_theta;
+  int32_t dtype;      /* sv_dtype: storage type of activations, weights, claims */
+} sv_stage_desc;
+
+/* Weights of one block, device pointers in the stage dtype, matrices [out, in] row-major. */
+typedef struct {
+  const void *wq;      /* [n_heads*hd,    d_model] */
+  const void *wk;      /* [n_kv_heads*hd, d_model] */
+  const void *wv;      /* [n_kv_heads*hd, d_model] */
+  const void *wo;      /* [d_model, n_heads*hd]    */
+  const void *w_gate;  /* [ffn, d_model]  SwiGLU only; NULL for the GELU MLP      */
+  const void *w_up;    /* [ffn, d_model]  (fc1 of the GELU MLP)                   */
+  const void *w_down;  /* [d_model, ffn]  (fc2 of the GELU MLP)                   */
+  const void *norm1_g; /* [d_model] */
+  const void *norm1_b; /* [d_model] LayerNorm only; NULL for RMSNorm              */
+  const void *norm2_g;
+  const void *norm2_b;
+} sv_block_weights;
+
+/* Verdict for one submission (device memory, 32 bytes). */
+typedef struct {
+  float    score[4];        /* by SV_IDX_*; metrics not in the mask are still computed          */
+  uint32_t flag;            /* 1 iff score[i] > tau[i] for some enabled metric i (strict '>')   */
+  uint32_t metric_mask;     /* echo of the request                                               */
+  float    max_token_rell2; /* max over tokens of ||c_t - r_t|| / max(||r_t||, 1e-30)            */
+  int32_t  argmax_token;    /* lowest token index attaining it                                   */
+} sv_result;
+
+/* Host-only check of a descriptor against what the kernels support.  No GPU needed.
+ * Returns SV_OK, SV_EINVAL (malformed) or SV_EUNSUPPORTED; `msg` (may be NULL) receives a
+ * NUL-terminated explanation of at most msg_len bytes.                                     */
+sv_status sv_check_desc(const sv_stage_desc *desc, uint32_t flags, char *msg, int32_t msg_len);
+
+/* Workspace bytes sv_create would allocate on the device (host-only arithmetic).            */
+int64_t sv_workspace_bytes(const sv_stage_desc *desc, int64_t max_tokens, int32_t max_seq, uint32_t flags);
+
+/* Create a context on the current device for micro-batches of at most max_tokens = B*S
+ * tokens and sequences of at most max_seq tokens.  Allocates the workspace (hipMalloc).   */
+sv_status sv_create(const sv_stage_desc *desc, int64_t max_tokens, int32_t max_seq, uint32_t flags,
+                    sv_ctx **out);
+void sv_destroy(sv_ctx *ctx);
+const char *sv_last_error(const sv_ctx *ctx);  /* ctx may be NULL: last error of a failed sv_create */
+
+/* Forward check.  w: host array of n_blocks sv_block_weights (device pointers inside).
+ * h_in [B,S,D] stage input.  claimed_h (nullable) [B,S,D]: scored against the recomputation
+ * with metric_mask / tau[4] / reduce; then result_dev (device, 1 element) must be non-NULL.
+ * h_hat_out (nullable) receives the recomputed stage output [B,S,D] in the stage dtype.
+ * token_scores_out (nullable) receives the per-token relative L2, [B*S] float.              */
+sv_status sv_verify_forward(sv_ctx *ctx, const sv_block_weights *w, const void *h_in, int32_t B, int32_t S,
+                            const void *claimed_h, uint32_t metric_mask, const float *tau, int32_t reduce,
+                            void *h_hat_out, float *token_scores_out, sv_result *result_dev, void *stream);
+
+/* Backward check.  Recomputes the forward from h_in keeping what backward needs, then the
+ * gradient with respect to h_in from g_out = dL/d(stage output) [B,S,D]; no weight gradients.
+ * claimed_g (nullable) is scored against it.  g_hat_out / h_hat_out (nullable) receive the
+ * recomputed input gradient / stage output.  Needs SV_FLAG_BACKWARD at sv_create.           */
+sv_status sv_verify_backward(sv_ctx *ctx, const sv_block_weights *w, const void *h_in, const void *g_out,
+                             int32_t B, int32_t S, const void *claimed_g, uint32_t metric_mask,
+                             const float *tau, int32_t reduce, void *g_hat_out, void *h_hat_out,
+                             float *token_scores_out, sv_result *result_dev, void *stream);
+
+/* Stand-alone statistic for n_claims submissions [T, D] (claim i at claims + i*claim_stride
+ * elements) against references (ref + i*ref_stride elements; ref_stride 0 = one shared
+ * reference, e.g. the EMA).  results_dev: n_claims sv_result.  token_scores_out (nullable):
+ * [n_claims, T] float.  ctx is required (it owns the partial-sum scratch); its stage
+ * descriptor is not consulted, so any context of the device serves.  D must be a multiple
+ * of 8; T * D of one claim must fit int64 and T <= 2^31-1.                                  */
+sv_status sv_score_and_flag(sv_ctx *ctx, const void *claims, int64_t claim_stride, int32_t n_claims,
+                            const void *ref, int64_t ref_stride, int32_t claim_dtype, int32_t ref_dtype,
+                            int64_t T, int32_t D, uint32_t metric_mask, const float *tau, int32_t reduce,
+                            float *token_scores_out, sv_result *results_dev, void *stream);
+
+/* m [T, D] float, in place:  m <- beta m + (1-beta) mean_{i: flags[i]==0} claim_i ; unchanged
+ * when every claim is flagged.  flags_dev: n_claims bytes on the device (e.g. copied from
+ * sv_result.flag), NULL = all clean.                                                        */
+sv_status sv_ema_update(sv_ctx *ctx, float *m, const void *claims, int64_t claim_stride, int32_t n_claims,
+                        int32_t claim_dtype, const uint8_t *flags_dev, int64_t T, int32_t D, float beta,
+                        void *stream);
+
+/* Per-operation timing with HIP events recorded on the caller's stream around each launch.
+ * sv_profile_enable(ctx, 1) clears the accumulators and starts recording; (ctx, 0) stops.
+ * sv_profile_read waits for the recorded events and returns, per operation class, the summed
+ * kernel time in ms, the algorithmic FLOP (2 M N K per product, causal attention at half the
+ * dense count) and the number of launches.  Recording adds two event records per launch.    */
+enum {
+  SV_OP_NORM = 0, SV_OP_GEMM_QKV, SV_OP_ROPE, SV_OP_ATTN, SV_OP_GEMM_O, SV_OP_GEMM_GATEUP, SV_OP_GEMM_DOWN,
+  SV_OP_SCORE, SV_OP_BWD_GEMM_DA, SV_OP_BWD_GEMM_DN2, SV_OP_BWD_NORM, SV_OP_BWD_GEMM_DO, SV_OP_BWD_ATTN,
+  SV_OP_BWD_ROPE, SV_OP_BWD_GEMM_DN1, SV_OP_COUNT
+};
+typedef struct {
+  double  ms[SV_OP_COUNT];
+  double  flop[SV_OP_COUNT];
+  int64_t launches[SV_OP_COUNT];
+} sv_profile;
+sv_status sv_profile_enable(sv_ctx *ctx, int32_t on);
+sv_status sv_profile_read(sv_ctx *ctx, sv_profile *out);
+
+/* Tuning and test aid: one bf16 product C[M,N] = A[M,K] * op(B) on the MFMA GEMM kernels that
+ * the block recompute uses (fp32 accumulation, bf16 result).  b_is_kn = 0: B stored [N,K]
+ * (C = A B^T); 1: B stored [K,N] (C = A B).  tile: 0 = automatic, 1 = 256x256, 2 = 128x128.
+ * Returns SV_EUNSUPPORTED for shapes outside the kernels' limits (N % 128, K % 64, 16-byte
+ * aligned rows).  No context is needed.                                                      */
+sv_status sv_gemm_bf16(const void *A, int64_t lda, const void *B, int64_t ldb, int32_t b_is_kn, void *C, int64_t ldc,
+                       int32_t M, int32_t N, int32_t K, int32_t tile, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STAGEVERIFY_H */

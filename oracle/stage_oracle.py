@@ -268,20 +268,22 @@ def scores(claim, ref, reduce="max_token"):
     else:
         raise ValueError(reduce)
     out["l1"] = float(np.sum(np.abs(c - r)) / n)
-    sc, sr = np.std(c), np.std(r)
-    if sc == 0.0 and sr == 0.0:
+    const_c, const_r = bool(np.max(c) == np.min(c)), bool(np.max(r) == np.min(r))
+    if const_c and const_r:
         out["zl2"] = 0.0
-    elif sc == 0.0 or sr == 0.0:
+    elif const_c or const_r:
         out["zl2"] = 2.0
     else:
-        out["zl2"] = float(np.mean(((c - np.mean(c)) / sc - (r - np.mean(r)) / sr) ** 2))
+        out["zl2"] = float(np.mean(((c - np.mean(c)) / np.std(c) - (r - np.mean(r)) / np.std(r)) ** 2))
     out["sfr"] = float(np.count_nonzero(_sgn(c) != _sgn(r)) / n)
     return out
 
 
 def flag(score_by_metric, tau_by_metric):
-    """Flag when any enabled metric is strictly above its threshold."""
-    return any(score_by_metric[m] > tau_by_metric[m] for m in tau_by_metric)
+    """Flag when any enabled metric is strictly above its threshold.  A score that is not a
+    number (a submission carrying NaN/inf) cannot be shown to be within the threshold and is
+    flagged too: the rule is "not (Gamma <= tau)", which equals "Gamma > tau" on the reals."""
+    return any(not (score_by_metric[m] <= tau_by_metric[m]) for m in tau_by_metric)
 
 
 def ema_update(m, signals, flags, beta):

@@ -1,0 +1,262 @@
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libstageverify.so")
+
+SV_OK, SV_EINVAL, SV_EUNSUPPORTED, SV_ENOMEM, SV_EHIP = range(5)
+SV_F32, SV_BF16 = 0, 1
+SV_MLP_GELU, SV_MLP_SWIGLU = 0, 1
+SV_NORM_LN, SV_NORM_RMS = 0, 1
+SV_REDUCE_GLOBAL, SV_REDUCE_MAX_TOKEN = 0, 1
+SV_FLAG_BACKWARD, SV_FLAG_PLAIN_KERNELS = 1, 2
+METRIC_NAMES = ("rel_l2", "l1", "zl2", "sfr")
+METRIC_BITS = {n: 1 << i for i, n in enumerate(METRIC_NAMES)}
+_STATUS = {1: "SV_EINVAL", 2: "SV_EUNSUPPORTED", 3: "SV_ENOMEM", 4: "SV_EHIP"}
+
+
+class SVError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"{_STATUS.get(status, status)}: {msg}")
+        self.status = status
+
+
+class StageDescC(C.Structure):
+    _fields_ = [("n_blocks", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("ffn_hidden", C.c_int32), ("mlp", C.c_int32), ("norm", C.c_int32), ("rope", C.c_int32),
+                ("causal", C.c_int32), ("norm_eps", C.c_float), ("rope_theta", C.c_float), ("dtype", C.c_int32)]
+
+
+_WNAMES = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "norm1_g", "norm1_b", "norm2_g", "norm2_b")
+
+
+class BlockWeightsC(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _WNAMES]
+
+
+OP_NAMES = ("norm", "gemm_qkv", "rope", "attn", "gemm_o", "gemm_gateup", "gemm_down", "score", "bwd_gemm_da",
+            "bwd_gemm_dn2", "bwd_norm", "bwd_gemm_do", "bwd_attn", "bwd_rope", "bwd_gemm_dn1")
+
+
+class ProfileC(C.Structure):
+    _fields_ = [("ms", C.c_double * len(OP_NAMES)), ("flop", C.c_double * len(OP_NAMES)),
+                ("launches", C.c_int64 * len(OP_NAMES))]
+
+
+RESULT_DTYPE = np.dtype([("score", np.float32, (4,)), ("flag", np.uint32), ("metric_mask", np.uint32),
+                         ("max_token_rell2", np.float32), ("argmax_token", np.int32)])
+assert RESULT_DTYPE.itemsize == 32
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2603_03592_amd.build` "
+                          "(there is no CPU fallback)")
+    L = C.CDLL(LIB_PATH)
+    vp, i32, i64, u32, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint32, C.c_float
+    L.sv_check_desc.restype = C.c_int
+    L.sv_check_desc.argtypes = [C.POINTER(StageDescC), u32, C.c_char_p, i32]
+    L.sv_workspace_bytes.restype = i64
+    L.sv_workspace_bytes.argtypes = [C.POINTER(StageDescC), i64, i32, u32]
+    L.sv_create.restype = C.c_int
+    L.sv_create.argtypes = [C.POINTER(StageDescC), i64, i32, u32, C.POINTER(vp)]
+    L.sv_destroy.restype = None
+    L.sv_destroy.argtypes = [vp]
+    L.sv_last_error.restype = C.c_char_p
+    L.sv_last_error.argtypes = [vp]
+    L.sv_verify_forward.restype = C.c_int
+    L.sv_verify_forward.argtypes = [vp, C.POINTER(BlockWeightsC), vp, i32, i32, vp, u32, C.POINTER(f32), i32, vp, vp, vp, vp]
+    L.sv_verify_backward.restype = C.c_int
+    L.sv_verify_backward.argtypes = [vp, C.POINTER(BlockWeightsC), vp, vp, i32, i32, vp, u32, C.POINTER(f32), i32, vp, vp, vp, vp, vp]
+    L.sv_score_and_flag.restype = C.c_int
+    L.sv_score_and_flag.argtypes = [vp, vp, i64, i32, vp, i64, i32, i32, i64, i32, u32, C.POINTER(f32), i32, vp, vp, vp]
+    L.sv_ema_update.restype = C.c_int
+    L.sv_ema_update.argtypes = [vp, vp, vp, i64, i32, i32, vp, i64, i32, f32, vp]
+    L.sv_profile_enable.restype = C.c_int
+    L.sv_profile_enable.argtypes = [vp, i32]
+    L.sv_profile_read.restype = C.c_int
+    L.sv_profile_read.argtypes = [vp, C.POINTER(ProfileC)]
+    L.sv_gemm_bf16.restype = C.c_int
+    L.sv_gemm_bf16.argtypes = [vp, i64, vp, i64, i32, vp, i64, i32, i32, i32, i32, vp]
+    return L
+
+
+lib = _load()
+
+
+def sv_gemm_bf16(a, b, b_is_kn: bool = False, tile: int = 0, out=None):
+    """C = a @ b.T (b stored [N,K]) or a @ b (b stored [K,N]) on the MFMA GEMM kernels; bf16 device tensors."""
+    import torch
+    M, K = a.shape
+    N = b.shape[1] if b_is_kn else b.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.bfloat16, device=a.device)
+    st = lib.sv_gemm_bf16(a.data_ptr(), a.stride(0), b.data_ptr(), b.stride(0), int(b_is_kn), out.data_ptr(), out.stride(0),
+                          M, N, K, tile, torch.cuda.current_stream().cuda_stream)
+    if st != SV_OK:
+        raise SVError(st, "sv_gemm_bf16")
+    return out
+
+
+def _desc_c(desc) -> StageDescC:
+    return StageDescC(int(desc.n_blocks), int(desc.d_model), int(desc.n_heads), int(desc.n_kv_heads), int(desc.ffn_hidden),
+                      SV_MLP_SWIGLU if desc.mlp == "swiglu" else SV_MLP_GELU,
+                      SV_NORM_RMS if desc.norm == "rms" else SV_NORM_LN, int(bool(desc.rope)), int(bool(desc.causal)),
+                      float(desc.norm_eps), float(desc.rope_theta), SV_BF16 if desc.dtype == "bf16" else SV_F32)
+
+
+def sv_check_desc(desc, flags: int = 0):
+    buf = C.create_string_buffer(256)
+    d = _desc_c(desc)
+    st = lib.sv_check_desc(C.byref(d), flags, buf, 256)
+    return st, buf.value.decode()
+
+
+def sv_workspace_bytes(desc, max_tokens: int, max_seq: int, flags: int = 0) -> int:
+    d = _desc_c(desc)
+    return int(lib.sv_workspace_bytes(C.byref(d), max_tokens, max_seq, flags))
+
+
+def _tau_array(tau) -> "C.Array":
+    if isinstance(tau, dict):
+        vals = [float(tau.get(n, 0.0)) for n in METRIC_NAMES]
+    else:
+        vals = [float(t) for t in tau]
+    return (C.c_float * 4)(*vals)
+
+
+def _mask(metrics) -> int:
+    if isinstance(metrics, int):
+        return metrics
+    m = 0
+    for n in metrics:
+        m |= METRIC_BITS[n]
+    return m
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _dt(t) -> int:
+    import torch
+    if t.dtype == torch.bfloat16:
+        return SV_BF16
+    if t.dtype == torch.float32:
+        return SV_F32
+    raise TypeError(f"unsupported tensor dtype {t.dtype}")
+
+
+class Verifier:
+    """One sv_ctx.  Tensors are torch tensors on the context's device, contiguous, in the stage dtype."""
+
+    def __init__(self, desc, max_tokens: int, max_seq: int, backward: bool = False, plain_kernels: bool = False):
+        import torch
+        self.torch = torch
+        self.desc = desc
+        self.tdtype = torch.bfloat16 if desc.dtype == "bf16" else torch.float32
+        self.flags = (SV_FLAG_BACKWARD if backward else 0) | (SV_FLAG_PLAIN_KERNELS if plain_kernels else 0)
+        self._ctx = C.c_void_p()
+        d = _desc_c(desc)
+        st = lib.sv_create(C.byref(d), max_tokens, max_seq, self.flags, C.byref(self._ctx))
+        if st != SV_OK:
+            raise SVError(st, lib.sv_last_error(None).decode())
+
+    def close(self):
+        if getattr(self, "_ctx", None) is not None and self._ctx.value:
+            lib.sv_destroy(self._ctx)
+            self._ctx = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ------------------------------------------------------------------ helpers
+    def _check(self, st: int):
+        if st != SV_OK:
+            raise SVError(st, lib.sv_last_error(self._ctx).decode())
+
+    def _stream(self) -> int:
+        return self.torch.cuda.current_stream().cuda_stream
+
+    def pack_weights(self, blocks: Sequence[Dict[str, object]]):
+        """Host array of sv_block_weights from per-block dicts of device tensors (kept alive by the caller)."""
+        arr = (BlockWeightsC * len(blocks))()
+        for i, b in enumerate(blocks):
+            for n in _WNAMES:
+                t = b.get(n)
+                if t is not None:
+                    assert t.is_cuda and t.is_contiguous() and t.dtype == self.tdtype, n
+                setattr(arr[i], n, _ptr(t))
+        return arr
+
+    def _results(self, n: int):
+        return self.torch.empty((n, 32), dtype=self.torch.uint8, device="cuda")
+
+    @staticmethod
+    def read_results(res_dev) -> np.ndarray:
+        return res_dev.cpu().numpy().view(RESULT_DTYPE).reshape(-1)
+
+    def profile_enable(self, on: bool = True):
+        self._check(lib.sv_profile_enable(self._ctx, int(on)))
+
+    def profile_read(self) -> Dict[str, Dict[str, float]]:
+        p = ProfileC()
+        self._check(lib.sv_profile_read(self._ctx, C.byref(p)))
+        return {n: dict(ms=p.ms[i], flop=p.flop[i], launches=int(p.launches[i])) for i, n in enumerate(OP_NAMES)}
+
+    # ------------------------------------------------------------------ entry points
+    def verify_forward(self, weights_c, h_in, claimed_h=None, metrics=("rel_l2",), tau=(0, 0, 0, 0), reduce="max_token",
+                       want_h_hat=False, want_token_scores=False):
+        B, S, D = h_in.shape
+        torch = self.torch
+        h_hat = torch.empty_like(h_in) if want_h_hat else None
+        tok = torch.empty(B * S, dtype=torch.float32, device=h_in.device) if (want_token_scores and claimed_h is not None) else None
+        res = self._results(1) if claimed_h is not None else None
+        self._check(lib.sv_verify_forward(self._ctx, weights_c, _ptr(h_in), B, S, _ptr(claimed_h), _mask(metrics), _tau_array(tau),
+                                          SV_REDUCE_MAX_TOKEN if reduce == "max_token" else SV_REDUCE_GLOBAL,
+                                          _ptr(h_hat), _ptr(tok), _ptr(res), self._stream()))
+        return dict(result=res, h_hat=h_hat, token_scores=tok)
+
+    def verify_backward(self, weights_c, h_in, g_out, claimed_g=None, metrics=("rel_l2",), tau=(0, 0, 0, 0), reduce="max_token",
+                        want_g_hat=False, want_h_hat=False, want_token_scores=False):
+        B, S, D = h_in.shape
+        torch = self.torch
+        g_hat = torch.empty_like(h_in) if want_g_hat else None
+        h_hat = torch.empty_like(h_in) if want_h_hat else None
+        tok = torch.empty(B * S, dtype=torch.float32, device=h_in.device) if (want_token_scores and claimed_g is not None) else None
+        res = self._results(1) if claimed_g is not None else None
+        self._check(lib.sv_verify_backward(self._ctx, weights_c, _ptr(h_in), _ptr(g_out), B, S, _ptr(claimed_g), _mask(metrics),
+                                           _tau_array(tau), SV_REDUCE_MAX_TOKEN if reduce == "max_token" else SV_REDUCE_GLOBAL,
+                                           _ptr(g_hat), _ptr(h_hat), _ptr(tok), _ptr(res), self._stream()))
+        return dict(result=res, g_hat=g_hat, h_hat=h_hat, token_scores=tok)
+
+    def score_and_flag(self, claims, ref, metrics=("rel_l2",), tau=(0, 0, 0, 0), reduce="max_token", want_token_scores=False):
+        """claims [n, T, D] (or [n, B, S, D]); ref [T, D] shared or [n, T, D] per claim."""
+        torch = self.torch
+        n, D = claims.shape[0], claims.shape[-1]
+        T = claims[0].numel() // D
+        shared = ref.numel() == T * D
+        assert claims.is_contiguous() and ref.is_contiguous()
+        tok = torch.empty((n, T), dtype=torch.float32, device=claims.device) if want_token_scores else None
+        res = self._results(n)
+        self._check(lib.sv_score_and_flag(self._ctx, _ptr(claims), T * D, n, _ptr(ref), 0 if shared else T * D, _dt(claims), _dt(ref),
+                                          T, D, _mask(metrics), _tau_array(tau),
+                                          SV_REDUCE_MAX_TOKEN if reduce == "max_token" else SV_REDUCE_GLOBAL,
+                                          _ptr(tok), _ptr(res), self._stream()))
+        return dict(result=res, token_scores=tok)
+
+    def ema_update(self, m, claims, flags_dev, beta: float):
+        """m [T, D] float32 updated in place from claims [n, T, D]; flags_dev: uint8 [n] on the device or None."""
+        n, D = claims.shape[0], claims.shape[-1]
+        T = claims[0].numel() // D
+        assert m.dtype == self.torch.float32 and m.numel() == T * D and m.is_contiguous() and claims.is_contiguous()
+        self._check(lib.sv_ema_update(self._ctx, _ptr(m), _ptr(claims), T * D, n, _dt(claims), _ptr(flags_dev), T, D, float(beta),
+                                      self._stream()))
+        return m

@@ -1,0 +1,503 @@
+// C ABI of the stage verifier: context, workspace carving, and the launch sequences of the
+// block forward (recompute of f_s) and of the input-gradient backward.  No tensor arithmetic
+// happens on the host; the only host-computed table is the RoPE cos/sin table built once at
+// sv_create.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <vector>
+
+#include "common.h"
+
+using namespace sv;
+
+namespace {
+
+thread_local char g_create_error[256] = "";
+
+struct BlockStash {   // what one block's backward reads (backward mode only)
+  void *x1, *qkv, *o, *gate, *up;
+  float* lse;
+};
+
+struct Arena {
+  char* base = nullptr;
+  size_t off = 0;
+  void* take(size_t bytes) {
+    off = (off + 255) & ~size_t(255);
+    void* p = base ? base + off : nullptr;
+    off += bytes;
+    return p;
+  }
+};
+
+constexpr int64_t kScoreScratchElems = 1 << 18;   // ScorePartial records (20 MiB)
+
+}  // namespace
+
+struct sv_ctx {
+  sv_stage_desc d;
+  uint32_t flags;
+  int64_t max_tokens;
+  int32_t max_seq;
+  int device;
+  int es;            // element size of the stage dtype
+  int hd, Dq, Dkv, Dqkv;
+  void* ws;
+  size_t ws_bytes;
+  // forward
+  void *xbuf[2], *n, *qkv, *o, *x1, *act;
+  float* lse;
+  // backward
+  std::vector<void*> xs;           // outputs of blocks 0..L-2 (inputs of blocks 1..L-1)
+  std::vector<BlockStash> stash;
+  void *dres[2], *dn, *dx1, *dgate, *dup, *dout, *dqkv;
+  float* delta;
+  ScorePartial* score_scratch;
+  float* rope_cs;
+  char err[256];
+  // optional per-operation event timing
+  bool prof_on = false;
+  struct ProfRec { int op; hipEvent_t a, b; };
+  std::vector<ProfRec> prof_recs;
+  std::vector<hipEvent_t> prof_pool;
+  sv_profile prof_acc;
+};
+
+namespace {
+
+void set_err(sv_ctx* c, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(c ? c->err : g_create_error, 256, fmt, ap);
+  va_end(ap);
+}
+
+sv_status check_desc_impl(const sv_stage_desc* d, uint32_t flags, char* msg, int msg_len) {
+  auto fail = [&](sv_status s, const char* m) {
+    if (msg && msg_len > 0) snprintf(msg, (size_t)msg_len, "%s", m);
+    return s;
+  };
+  if (!d) return fail(SV_EINVAL, "descriptor is NULL");
+  if (d->n_blocks < 1 || d->d_model < 1 || d->n_heads < 1 || d->n_kv_heads < 1 || d->ffn_hidden < 1)
+    return fail(SV_EINVAL, "n_blocks, d_model, n_heads, n_kv_heads and ffn_hidden must be positive");
+  if (d->mlp != SV_MLP_GELU && d->mlp != SV_MLP_SWIGLU) return fail(SV_EINVAL, "unknown mlp kind");
+  if (d->norm != SV_NORM_LN && d->norm != SV_NORM_RMS) return fail(SV_EINVAL, "unknown norm kind");
+  if (d->dtype != SV_F32 && d->dtype != SV_BF16) return fail(SV_EINVAL, "unknown dtype");
+  if (!(d->norm_eps >= 0.0f)) return fail(SV_EINVAL, "norm_eps must be >= 0");
+  if (d->rope && !(d->rope_theta > 0.0f)) return fail(SV_EINVAL, "rope_theta must be > 0");
+  if (flags & ~(uint32_t)(SV_FLAG_BACKWARD | SV_FLAG_PLAIN_KERNELS)) return fail(SV_EINVAL, "unknown flag bits");
+  if (d->d_model % d->n_heads) return fail(SV_EINVAL, "d_model must be a multiple of n_heads");
+  if (d->n_heads % d->n_kv_heads) return fail(SV_EINVAL, "n_heads must be a multiple of n_kv_heads");
+  const int hd = d->d_model / d->n_heads;
+  if (hd != 8 && hd != 16 && hd != 32 && hd != 64 && hd != 128)
+    return fail(SV_EUNSUPPORTED, "head_dim must be one of 8, 16, 32, 64, 128");
+  if (d->d_model % 8 || d->ffn_hidden % 8) return fail(SV_EUNSUPPORTED, "d_model and ffn_hidden must be multiples of 8");
+  if (msg && msg_len > 0) msg[0] = 0;
+  return SV_OK;
+}
+
+// Carve (or, with a null base, just size) the workspace.
+size_t carve(sv_ctx* c, char* base) {
+  const sv_stage_desc& d = c->d;
+  const size_t T = (size_t)c->max_tokens, es = (size_t)c->es;
+  const size_t D = d.d_model, F = d.ffn_hidden, L = d.n_blocks;
+  const size_t lse_n = (size_t)d.n_heads * T;
+  const bool bwd = c->flags & SV_FLAG_BACKWARD;
+  Arena a; a.base = base;
+  c->rope_cs = (float*)a.take((size_t)c->max_seq * (c->hd / 2) * 2 * sizeof(float));
+  c->score_scratch = (ScorePartial*)a.take(kScoreScratchElems * sizeof(ScorePartial));
+  c->xbuf[0] = a.take(T * D * es);
+  c->xbuf[1] = a.take(T * D * es);
+  c->n = a.take(T * D * es);
+  c->act = a.take(T * F * es);
+  c->xs.clear(); c->stash.clear();
+  if (!bwd) {
+    c->qkv = a.take(T * c->Dqkv * es);
+    c->o = a.take(T * c->Dq * es);
+    c->x1 = a.take(T * D * es);
+    c->lse = (float*)a.take(lse_n * sizeof(float));
+  } else {
+    for (size_t l = 0; l + 1 < L; ++l) c->xs.push_back(a.take(T * D * es));
+    for (size_t l = 0; l < L; ++l) {
+      BlockStash s;
+      s.x1 = a.take(T * D * es);
+      s.qkv = a.take(T * c->Dqkv * es);
+      s.o = a.take(T * c->Dq * es);
+      s.gate = d.mlp == SV_MLP_SWIGLU ? a.take(T * F * es) : nullptr;
+      s.up = a.take(T * F * es);
+      s.lse = (float*)a.take(lse_n * sizeof(float));
+      c->stash.push_back(s);
+    }
+    c->qkv = c->stash[0].qkv; c->o = c->stash[0].o; c->x1 = c->stash[0].x1; c->lse = c->stash[0].lse;
+    c->dres[0] = a.take(T * D * es);
+    c->dres[1] = a.take(T * D * es);
+    c->dn = a.take(T * D * es);
+    c->dx1 = a.take(T * D * es);
+    c->dgate = a.take(T * F * es);
+    c->dup = d.mlp == SV_MLP_SWIGLU ? a.take(T * F * es) : nullptr;
+    c->dout = a.take(T * c->Dq * es);
+    c->dqkv = a.take(T * c->Dqkv * es);
+    c->delta = (float*)a.take(lse_n * sizeof(float));
+  }
+  return a.off + 256;
+}
+
+void init_ctx_fields(sv_ctx* c, const sv_stage_desc* desc, int64_t max_tokens, int32_t max_seq, uint32_t flags) {
+  c->d = *desc; c->flags = flags; c->max_tokens = max_tokens; c->max_seq = max_seq;
+  c->es = desc->dtype == SV_BF16 ? 2 : 4;
+  c->hd = desc->d_model / desc->n_heads;
+  c->Dq = desc->n_heads * c->hd;
+  c->Dkv = desc->n_kv_heads * c->hd;
+  c->Dqkv = c->Dq + 2 * c->Dkv;
+  c->ws = nullptr; c->ws_bytes = 0; c->err[0] = 0;
+}
+
+#define SV_HIP(c, call)                                                        \
+  do {                                                                         \
+    hipError_t e_ = (call);                                                    \
+    if (e_ != hipSuccess) {                                                    \
+      set_err(c, "%s failed: %s", #call, hipGetErrorString(e_));               \
+      return SV_EHIP;                                                          \
+    }                                                                          \
+  } while (0)
+
+// Launch `call` for operation class `op`; with profiling on, bracket it with events on `st`.
+#define SV_OP(c, op, flop_, st, call)                                          \
+  do {                                                                         \
+    hipEvent_t ea_ = nullptr, eb_ = nullptr;                                   \
+    if ((c)->prof_on) {                                                        \
+      ea_ = take_event(c); eb_ = take_event(c);                                \
+      if (!ea_ || !eb_) { set_err(c, "hipEventCreate failed"); return SV_EHIP; } \
+      SV_HIP(c, hipEventRecord(ea_, st));                                      \
+    }                                                                          \
+    SV_HIP(c, call);                                                           \
+    if ((c)->prof_on) {                                                        \
+      SV_HIP(c, hipEventRecord(eb_, st));                                      \
+      (c)->prof_recs.push_back(sv_ctx::ProfRec{op, ea_, eb_});                 \
+      (c)->prof_acc.flop[op] += (double)(flop_);                               \
+      (c)->prof_acc.launches[op] += 1;                                         \
+    }                                                                          \
+  } while (0)
+
+hipEvent_t take_event(sv_ctx* c) {
+  if (!c->prof_pool.empty()) { hipEvent_t e = c->prof_pool.back(); c->prof_pool.pop_back(); return e; }
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
+
+inline char* at(void* p, int64_t elems, int es) { return (char*)p + elems * es; }
+inline const char* at(const void* p, int64_t elems, int es) { return (const char*)p + elems * es; }
+
+hipError_t gemm(sv_ctx* c, const GemmArgs& a, hipStream_t st) {
+  if (c->d.dtype == SV_BF16 && !(c->flags & SV_FLAG_PLAIN_KERNELS) && mfma_gemm_supported(a)) return mfma_gemm(a, st);
+  return plain_gemm(a, c->d.dtype, st);
+}
+
+GemmArgs nt(int M, int N, int K, const void* A, int64_t lda, const void* W, void* C, int64_t ldc, int epi) {
+  GemmArgs g; memset(&g, 0, sizeof(g));
+  g.M = M; g.N = N; g.nseg = 1; g.seg[0] = GemmSeg{A, lda, W, (int64_t)K, K};
+  g.b_is_kn = 0; g.epi = epi; g.C = C; g.ldc = ldc;
+  return g;
+}
+
+// One block forward: x -> y.  st_ (nullable) receives what backward needs.
+sv_status block_forward(sv_ctx* c, const sv_block_weights& w, const void* x, void* y, int B, int S, BlockStash* keep, hipStream_t st) {
+  const sv_stage_desc& d = c->d;
+  const int T = B * S, D = d.d_model, F = d.ffn_hidden, es = c->es, dt = d.dtype;
+  void* qkv = keep ? keep->qkv : c->qkv;
+  void* o = keep ? keep->o : c->o;
+  void* x1 = keep ? keep->x1 : c->x1;
+  float* lse = keep ? keep->lse : c->lse;
+
+  const double Td = T, attn_flop = (d.causal ? 2.0 : 4.0) * B * d.n_heads * (double)S * S * c->hd;
+  SV_OP(c, SV_OP_NORM, 0, st, plain_norm_fwd(x, w.norm1_g, w.norm1_b, c->n, T, D, d.norm, d.norm_eps, dt, st));
+  SV_OP(c, SV_OP_GEMM_QKV, 2.0 * Td * c->Dq * D, st, gemm(c, nt(T, c->Dq, D, c->n, D, w.wq, qkv, c->Dqkv, EPI_STORE), st));
+  SV_OP(c, SV_OP_GEMM_QKV, 2.0 * Td * c->Dkv * D, st, gemm(c, nt(T, c->Dkv, D, c->n, D, w.wk, at(qkv, c->Dq, es), c->Dqkv, EPI_STORE), st));
+  SV_OP(c, SV_OP_GEMM_QKV, 2.0 * Td * c->Dkv * D, st, gemm(c, nt(T, c->Dkv, D, c->n, D, w.wv, at(qkv, c->Dq + c->Dkv, es), c->Dqkv, EPI_STORE), st));
+  if (d.rope) SV_OP(c, SV_OP_ROPE, 0, st, plain_rope(qkv, c->Dqkv, T, S, d.n_heads, d.n_kv_heads, c->hd, c->rope_cs, 0, dt, st));
+  SV_OP(c, SV_OP_ATTN, attn_flop, st, plain_attn_fwd(qkv, c->Dqkv, o, lse, B, S, d.n_heads, d.n_kv_heads, c->hd, d.causal, dt, st));
+  {
+    GemmArgs g = nt(T, D, c->Dq, o, c->Dq, w.wo, x1, D, EPI_RESID);
+    g.R = x; g.ldr = D;
+    SV_OP(c, SV_OP_GEMM_O, 2.0 * Td * D * c->Dq, st, gemm(c, g, st));
+  }
+  SV_OP(c, SV_OP_NORM, 0, st, plain_norm_fwd(x1, w.norm2_g, w.norm2_b, c->n, T, D, d.norm, d.norm_eps, dt, st));
+  if (d.mlp == SV_MLP_SWIGLU) {
+    GemmArgs g = nt(T, F, D, c->n, D, w.w_gate, c->act, F, EPI_SWIGLU);
+    g.B2 = w.w_up; g.ldb2 = D;
+    if (keep) { g.C2 = keep->gate; g.C3 = keep->up; }
+    SV_OP(c, SV_OP_GEMM_GATEUP, 4.0 * Td * F * D, st, gemm(c, g, st));
+  } else {
+    GemmArgs g = nt(T, F, D, c->n, D, w.w_up, c->act, F, EPI_GELU);
+    if (keep) g.C2 = keep->up;
+    SV_OP(c, SV_OP_GEMM_GATEUP, 2.0 * Td * F * D, st, gemm(c, g, st));
+  }
+  {
+    GemmArgs g = nt(T, D, F, c->act, F, w.w_down, y, D, EPI_RESID);
+    g.R = x1; g.ldr = D;
+    SV_OP(c, SV_OP_GEMM_DOWN, 2.0 * Td * D * F, st, gemm(c, g, st));
+  }
+  return SV_OK;
+}
+
+GemmArgs nn(int M, int N, void* C, int64_t ldc, int epi) {
+  GemmArgs g; memset(&g, 0, sizeof(g));
+  g.M = M; g.N = N; g.nseg = 0; g.b_is_kn = 1; g.epi = epi; g.C = C; g.ldc = ldc;
+  return g;
+}
+void add_seg(GemmArgs& g, const void* A, int64_t lda, const void* W, int64_t ldw, int K) {
+  g.seg[g.nseg++] = GemmSeg{A, lda, W, ldw, K};
+}
+
+// One block backward: dy = dL/dy -> dx = dL/dx, reading the block input x and its stash.
+sv_status block_backward(sv_ctx* c, const sv_block_weights& w, const void* x, const BlockStash& k, const void* dy, void* dx, int B, int S,
+                         hipStream_t st) {
+  const sv_stage_desc& d = c->d;
+  const int T = B * S, D = d.d_model, F = d.ffn_hidden, es = c->es, dt = d.dtype;
+  const double Td = T, attn_flop = (d.causal ? 2.0 : 4.0) * B * d.n_heads * (double)S * S * c->hd;
+  if (d.mlp == SV_MLP_SWIGLU) {
+    GemmArgs g = nn(T, F, c->dgate, F, EPI_SWIGLU_BWD);          // da = dy Wd, then through silu(g)*u
+    add_seg(g, dy, D, w.w_down, F, D);
+    g.C2 = c->dup; g.R = k.gate; g.R2 = k.up; g.ldr = F;
+    SV_OP(c, SV_OP_BWD_GEMM_DA, 2.0 * Td * F * D, st, gemm(c, g, st));
+    GemmArgs h = nn(T, D, c->dn, D, EPI_STORE);                  // dn2 = dG Wg + dU Wu
+    add_seg(h, c->dgate, F, w.w_gate, D, F);
+    add_seg(h, c->dup, F, w.w_up, D, F);
+    SV_OP(c, SV_OP_BWD_GEMM_DN2, 4.0 * Td * F * D, st, gemm(c, h, st));
+  } else {
+    GemmArgs g = nn(T, F, c->dgate, F, EPI_GELU_BWD);
+    add_seg(g, dy, D, w.w_down, F, D);
+    g.R = k.up; g.ldr = F;
+    SV_OP(c, SV_OP_BWD_GEMM_DA, 2.0 * Td * F * D, st, gemm(c, g, st));
+    GemmArgs h = nn(T, D, c->dn, D, EPI_STORE);
+    add_seg(h, c->dgate, F, w.w_up, D, F);
+    SV_OP(c, SV_OP_BWD_GEMM_DN2, 2.0 * Td * F * D, st, gemm(c, h, st));
+  }
+  SV_OP(c, SV_OP_BWD_NORM, 0, st, plain_norm_bwd_add(c->dn, k.x1, w.norm2_g, dy, c->dx1, T, D, d.norm, d.norm_eps, dt, st));
+  {
+    GemmArgs g = nn(T, c->Dq, c->dout, c->Dq, EPI_STORE);        // do = dx1 Wo
+    add_seg(g, c->dx1, D, w.wo, c->Dq, D);
+    SV_OP(c, SV_OP_BWD_GEMM_DO, 2.0 * Td * D * c->Dq, st, gemm(c, g, st));
+  }
+  SV_OP(c, SV_OP_BWD_ATTN, 2.5 * attn_flop, st, plain_attn_bwd(k.qkv, c->Dqkv, k.o, c->dout, k.lse, c->delta, c->dqkv, B, S, d.n_heads, d.n_kv_heads, c->hd, d.causal, dt, st));
+  if (d.rope) SV_OP(c, SV_OP_BWD_ROPE, 0, st, plain_rope(c->dqkv, c->Dqkv, T, S, d.n_heads, d.n_kv_heads, c->hd, c->rope_cs, 1, dt, st));
+  {
+    GemmArgs g = nn(T, D, c->dn, D, EPI_STORE);                  // dn1 = dq Wq + dk Wk + dv Wv
+    add_seg(g, c->dqkv, c->Dqkv, w.wq, D, c->Dq);
+    add_seg(g, at(c->dqkv, c->Dq, es), c->Dqkv, w.wk, D, c->Dkv);
+    add_seg(g, at(c->dqkv, c->Dq + c->Dkv, es), c->Dqkv, w.wv, D, c->Dkv);
+    SV_OP(c, SV_OP_BWD_GEMM_DN1, 2.0 * Td * D * c->Dqkv, st, gemm(c, g, st));
+  }
+  SV_OP(c, SV_OP_BWD_NORM, 0, st, plain_norm_bwd_add(c->dn, x, w.norm1_g, c->dx1, dx, T, D, d.norm, d.norm_eps, dt, st));
+  return SV_OK;
+}
+
+sv_status check_call(sv_ctx* c, const sv_block_weights* w, const void* h_in, int B, int S, const void* claim, const float* tau,
+                     int reduce, sv_result* res) {
+  if (!c) return SV_EINVAL;
+  if (!w || !h_in) { set_err(c, "weights and h_in must be non-NULL"); return SV_EINVAL; }
+  if (B < 1 || S < 1) { set_err(c, "B and S must be positive"); return SV_EINVAL; }
+  if ((int64_t)B * S > c->max_tokens || S > c->max_seq) {
+    set_err(c, "B*S=%lld or S=%d exceeds the context limits (%lld tokens, seq %d)", (long long)B * S, S, (long long)c->max_tokens, c->max_seq);
+    return SV_EINVAL;
+  }
+  if (claim && (!res || !tau)) { set_err(c, "a claim needs result_dev and tau"); return SV_EINVAL; }
+  if (reduce != SV_REDUCE_GLOBAL && reduce != SV_REDUCE_MAX_TOKEN) { set_err(c, "unknown reduce"); return SV_EINVAL; }
+  for (int l = 0; l < c->d.n_blocks; ++l) {
+    const sv_block_weights& b = w[l];
+    const bool mats = b.wq && b.wk && b.wv && b.wo && b.w_up && b.w_down && b.norm1_g && b.norm2_g;
+    const bool gate = c->d.mlp == SV_MLP_SWIGLU ? b.w_gate != nullptr : true;
+    const bool bias = c->d.norm == SV_NORM_LN ? (b.norm1_b && b.norm2_b) : true;
+    if (!mats || !gate || !bias) { set_err(c, "block %d: a required weight pointer is NULL", l); return SV_EINVAL; }
+  }
+  return SV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+sv_status sv_check_desc(const sv_stage_desc* desc, uint32_t flags, char* msg, int32_t msg_len) {
+  return check_desc_impl(desc, flags, msg, msg_len);
+}
+
+int64_t sv_workspace_bytes(const sv_stage_desc* desc, int64_t max_tokens, int32_t max_seq, uint32_t flags) {
+  if (check_desc_impl(desc, flags, nullptr, 0) != SV_OK || max_tokens < 1 || max_seq < 1) return -1;
+  sv_ctx tmp;
+  init_ctx_fields(&tmp, desc, max_tokens, max_seq, flags);
+  return (int64_t)carve(&tmp, nullptr);
+}
+
+sv_status sv_create(const sv_stage_desc* desc, int64_t max_tokens, int32_t max_seq, uint32_t flags, sv_ctx** out) {
+  if (!out) { set_err(nullptr, "out is NULL"); return SV_EINVAL; }
+  *out = nullptr;
+  char msg[200];
+  sv_status s = check_desc_impl(desc, flags, msg, sizeof(msg));
+  if (s != SV_OK) { set_err(nullptr, "%s", msg); return s; }
+  if (max_tokens < 1 || max_seq < 1 || max_tokens > 0x7fffffffLL) { set_err(nullptr, "max_tokens / max_seq out of range"); return SV_EINVAL; }
+  sv_ctx* c = new sv_ctx();
+  init_ctx_fields(c, desc, max_tokens, max_seq, flags);
+  c->ws_bytes = carve(c, nullptr);
+  hipError_t e = hipGetDevice(&c->device);
+  if (e == hipSuccess) e = hipMalloc(&c->ws, c->ws_bytes);
+  if (e != hipSuccess) {
+    set_err(nullptr, "workspace of %zu bytes: %s", c->ws_bytes, hipGetErrorString(e));
+    delete c;
+    return e == hipErrorOutOfMemory ? SV_ENOMEM : SV_EHIP;
+  }
+  carve(c, (char*)c->ws);
+  // RoPE table in double on the host: (cos, sin) of p * theta^(-2i/hd)
+  const int half = c->hd / 2;
+  std::vector<float> cs((size_t)max_seq * half * 2);
+  for (int p = 0; p < max_seq; ++p)
+    for (int i = 0; i < half; ++i) {
+      const double ang = (double)p * pow((double)desc->rope_theta, -2.0 * i / (double)c->hd);
+      cs[((size_t)p * half + i) * 2] = (float)cos(ang);
+      cs[((size_t)p * half + i) * 2 + 1] = (float)sin(ang);
+    }
+  e = hipMemcpy(c->rope_cs, cs.data(), cs.size() * sizeof(float), hipMemcpyHostToDevice);
+  if (e != hipSuccess) {
+    set_err(nullptr, "uploading the RoPE table: %s", hipGetErrorString(e));
+    (void)hipFree(c->ws);
+    delete c;
+    return SV_EHIP;
+  }
+  *out = c;
+  return SV_OK;
+}
+
+void sv_destroy(sv_ctx* c) {
+  if (!c) return;
+  for (auto& r : c->prof_recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+  for (auto e : c->prof_pool) (void)hipEventDestroy(e);
+  if (c->ws) (void)hipFree(c->ws);
+  delete c;
+}
+
+sv_status sv_profile_enable(sv_ctx* c, int32_t on) {
+  if (!c) return SV_EINVAL;
+  if (on) {
+    for (auto& r : c->prof_recs) { c->prof_pool.push_back(r.a); c->prof_pool.push_back(r.b); }
+    c->prof_recs.clear();
+    memset(&c->prof_acc, 0, sizeof(c->prof_acc));
+  }
+  c->prof_on = on != 0;
+  return SV_OK;
+}
+
+sv_status sv_profile_read(sv_ctx* c, sv_profile* out) {
+  if (!c || !out) return SV_EINVAL;
+  for (auto& r : c->prof_recs) {
+    SV_HIP(c, hipEventSynchronize(r.b));
+    float ms = 0.0f;
+    SV_HIP(c, hipEventElapsedTime(&ms, r.a, r.b));
+    c->prof_acc.ms[r.op] += ms;
+    c->prof_pool.push_back(r.a); c->prof_pool.push_back(r.b);
+  }
+  c->prof_recs.clear();
+  *out = c->prof_acc;
+  return SV_OK;
+}
+
+const char* sv_last_error(const sv_ctx* c) { return c ? c->err : g_create_error; }
+
+sv_status sv_verify_forward(sv_ctx* c, const sv_block_weights* w, const void* h_in, int32_t B, int32_t S, const void* claimed_h,
+                            uint32_t metric_mask, const float* tau, int32_t reduce, void* h_hat_out, float* token_scores_out,
+                            sv_result* result_dev, void* stream) {
+  sv_status s = check_call(c, w, h_in, B, S, claimed_h, tau, reduce, result_dev);
+  if (s != SV_OK) return s;
+  hipStream_t st = (hipStream_t)stream;
+  const int L = c->d.n_blocks;
+  const bool bwd = c->flags & SV_FLAG_BACKWARD;
+  const void* x = h_in;
+  void* y = nullptr;
+  for (int l = 0; l < L; ++l) {
+    if (l == L - 1) y = h_hat_out ? h_hat_out : c->xbuf[l & 1];
+    else y = bwd ? c->xs[l] : c->xbuf[l & 1];
+    s = block_forward(c, w[l], x, y, B, S, nullptr, st);
+    if (s != SV_OK) return s;
+    x = y;
+  }
+  if (claimed_h)
+    SV_OP(c, SV_OP_SCORE, 0, st, launch_score(claimed_h, 0, 1, y, 0, c->d.dtype, c->d.dtype, (int64_t)B * S, c->d.d_model, metric_mask, tau, reduce,
+                           token_scores_out, result_dev, c->score_scratch, kScoreScratchElems, st));
+  return SV_OK;
+}
+
+sv_status sv_verify_backward(sv_ctx* c, const sv_block_weights* w, const void* h_in, const void* g_out, int32_t B, int32_t S,
+                             const void* claimed_g, uint32_t metric_mask, const float* tau, int32_t reduce, void* g_hat_out,
+                             void* h_hat_out, float* token_scores_out, sv_result* result_dev, void* stream) {
+  sv_status s = check_call(c, w, h_in, B, S, claimed_g, tau, reduce, result_dev);
+  if (s != SV_OK) return s;
+  if (!(c->flags & SV_FLAG_BACKWARD)) { set_err(c, "context was created without SV_FLAG_BACKWARD"); return SV_EINVAL; }
+  if (!g_out) { set_err(c, "g_out must be non-NULL"); return SV_EINVAL; }
+  hipStream_t st = (hipStream_t)stream;
+  const int L = c->d.n_blocks;
+  const void* x = h_in;
+  for (int l = 0; l < L; ++l) {
+    void* y = (l == L - 1) ? (h_hat_out ? h_hat_out : c->xbuf[0]) : c->xs[l];
+    s = block_forward(c, w[l], x, y, B, S, &c->stash[l], st);
+    if (s != SV_OK) return s;
+    x = y;
+  }
+  const void* dy = g_out;
+  void* dx = nullptr;
+  for (int l = L - 1; l >= 0; --l) {
+    dx = (l == 0 && g_hat_out) ? g_hat_out : c->dres[l & 1];
+    const void* xin = l == 0 ? h_in : c->xs[l - 1];
+    s = block_backward(c, w[l], xin, c->stash[l], dy, dx, B, S, st);
+    if (s != SV_OK) return s;
+    dy = dx;
+  }
+  if (claimed_g)
+    SV_OP(c, SV_OP_SCORE, 0, st, launch_score(claimed_g, 0, 1, dx, 0, c->d.dtype, c->d.dtype, (int64_t)B * S, c->d.d_model, metric_mask, tau, reduce,
+                           token_scores_out, result_dev, c->score_scratch, kScoreScratchElems, st));
+  return SV_OK;
+}
+
+sv_status sv_score_and_flag(sv_ctx* c, const void* claims, int64_t claim_stride, int32_t n_claims, const void* ref, int64_t ref_stride,
+                            int32_t claim_dtype, int32_t ref_dtype, int64_t T, int32_t D, uint32_t metric_mask, const float* tau,
+                            int32_t reduce, float* token_scores_out, sv_result* results_dev, void* stream) {
+  if (!c) return SV_EINVAL;
+  if (n_claims < 0 || T < 0 || D < 1) { set_err(c, "negative size"); return SV_EINVAL; }
+  if (n_claims == 0 || T == 0) return SV_OK;
+  if (!claims || !ref || !results_dev || !tau) { set_err(c, "claims, ref, tau and results_dev must be non-NULL"); return SV_EINVAL; }
+  if ((claim_dtype != SV_F32 && claim_dtype != SV_BF16) || (ref_dtype != SV_F32 && ref_dtype != SV_BF16)) { set_err(c, "unknown dtype"); return SV_EINVAL; }
+  if (reduce != SV_REDUCE_GLOBAL && reduce != SV_REDUCE_MAX_TOKEN) { set_err(c, "unknown reduce"); return SV_EINVAL; }
+  if (D % 8) { set_err(c, "D must be a multiple of 8"); return SV_EUNSUPPORTED; }
+  if (T > 0x7fffffffLL || claim_stride < 0 || ref_stride < 0) { set_err(c, "T or a stride is out of range"); return SV_EINVAL; }
+  if ((T + kScoreTokensPerWG - 1) / kScoreTokensPerWG > kScoreScratchElems) { set_err(c, "T too large for the score scratch"); return SV_EUNSUPPORTED; }
+  SV_HIP(c, launch_score(claims, claim_stride, n_claims, ref, ref_stride, claim_dtype, ref_dtype, T, D, metric_mask, tau, reduce,
+                         token_scores_out, results_dev, c->score_scratch, kScoreScratchElems, (hipStream_t)stream));
+  return SV_OK;
+}
+
+sv_status sv_ema_update(sv_ctx* c, float* m, const void* claims, int64_t claim_stride, int32_t n_claims, int32_t claim_dtype,
+                        const uint8_t* flags_dev, int64_t T, int32_t D, float beta, void* stream) {
+  if (!c) return SV_EINVAL;
+  if (n_claims < 0 || T < 0 || D < 1) { set_err(c, "negative size"); return SV_EINVAL; }
+  if (n_claims == 0 || T == 0) return SV_OK;
+  if (!m || !claims) { set_err(c, "m and claims must be non-NULL"); return SV_EINVAL; }
+  if (claim_dtype != SV_F32 && claim_dtype != SV_BF16) { set_err(c, "unknown dtype"); return SV_EINVAL; }
+  if (!(beta >= 0.0f && beta < 1.0f)) { set_err(c, "beta must be in [0, 1)"); return SV_EINVAL; }
+  if (D % 8) { set_err(c, "D must be a multiple of 8"); return SV_EUNSUPPORTED; }
+  if (claim_stride < 0) { set_err(c, "negative stride"); return SV_EINVAL; }
+  SV_HIP(c, launch_ema(m, claims, claim_stride, n_claims, claim_dtype, flags_dev, T, D, beta, (hipStream_t)stream));
+  return SV_OK;
+}
+
+sv_status sv_gemm_bf16(const void* A, int64_t lda, const void* B, int64_t ldb, int32_t b_is_kn, void* Cout, int64_t ldc, int32_t M,
+                       int32_t N, int32_t K, int32_t tile, void* stream) {
+  if (!A || !B || !Cout || M < 1 || N < 1 || K < 1 || tile < 0 || tile > 2) return SV_EINVAL;
+  GemmArgs g; memset(&g, 0, sizeof(g));
+  g.M = M; g.N = N; g.nseg = 1; g.seg[0] = GemmSeg{A, lda, B, ldb, K};
+  g.b_is_kn = b_is_kn ? 1 : 0; g.epi = EPI_STORE; g.C = Cout; g.ldc = ldc;
+  if (!mfma_gemm_supported(g) || (tile == 1 && N % 256)) return SV_EUNSUPPORTED;
+  return mfma_gemm(g, (hipStream_t)stream, tile) == hipSuccess ? SV_OK : SV_EHIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,147 @@
+// Shared device helpers for the stage-verifier kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "stageverify.h"
+
+namespace sv {
+
+typedef __bf16 bf16;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16 v) { return static_cast<float>(v); }
+template <typename E> __device__ __forceinline__ E from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return static_cast<bf16>(v); }  // RNE
+
+// 8 consecutive elements (16-byte aligned for bf16, 32-byte for float) as floats.
+__device__ __forceinline__ void load8(const bf16* p, float (&o)[8]) {
+  bf16x8 v = *reinterpret_cast<const bf16x8*>(p);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) o[i] = static_cast<float>(v[i]);
+}
+__device__ __forceinline__ void load8(const float* p, float (&o)[8]) {
+  f32x4 a = *reinterpret_cast<const f32x4*>(p);
+  f32x4 b = *reinterpret_cast<const f32x4*>(p + 4);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { o[i] = a[i]; o[4 + i] = b[i]; }
+}
+__device__ __forceinline__ void store8(bf16* p, const float (&v)[8]) {
+  bf16x8 o;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) o[i] = static_cast<bf16>(v[i]);
+  *reinterpret_cast<bf16x8*>(p) = o;
+}
+__device__ __forceinline__ void store8(float* p, const float (&v)[8]) {
+  f32x4 a, b;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { a[i] = v[i]; b[i] = v[4 + i]; }
+  *reinterpret_cast<f32x4*>(p) = a;
+  *reinterpret_cast<f32x4*>(p + 4) = b;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// Sum over a 256-thread workgroup; every thread gets the result.  `red` holds >= 4 floats.
+__device__ __forceinline__ float block_sum_256(float v, float* red) {
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return red[0] + red[1] + red[2] + red[3];
+}
+
+__device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
+__device__ __forceinline__ float silu_grad_f(float z) {
+  float s = 1.0f / (1.0f + __expf(-z));
+  return s * (1.0f + z * (1.0f - s));
+}
+__device__ __forceinline__ float gelu_f(float z) { return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f)); }
+__device__ __forceinline__ float gelu_grad_f(float z) {
+  return 0.5f * (1.0f + erff(z * 0.70710678118654752f)) + z * __expf(-0.5f * z * z) * 0.39894228040143268f;
+}
+
+}  // namespace sv
+
+// ----------------------------------------------------------------------------------------
+// Host-side launch interfaces between the translation units (all enqueue on `st`).
+namespace sv {
+
+struct ScorePartial {   // per (claim, token tile)
+  double s[8];          // sum c, sum r, sum c^2, sum r^2, sum d, sum |d|, sum d^2, #sign mismatches
+  float max_rel;        // max over the tile's tokens of the per-token relative L2
+  int32_t argmax;       // token index of that maximum (lowest on ties)
+  int32_t bad;          // a non-finite per-token value was seen
+  int32_t pad;
+};
+constexpr int kScoreTokensPerWG = 16;
+
+// score.hip
+hipError_t launch_score(const void* claims, int64_t claim_stride, int n_claims, const void* ref, int64_t ref_stride,
+                        int claim_dtype, int ref_dtype, int64_t T, int D, uint32_t mask, const float* tau4,
+                        int reduce, float* token_scores, sv_result* results, ScorePartial* scratch,
+                        int64_t scratch_elems, hipStream_t st);
+hipError_t launch_ema(float* m, const void* claims, int64_t claim_stride, int n_claims, int claim_dtype,
+                      const uint8_t* flags, int64_t T, int D, float beta, hipStream_t st);
+
+// One K-segment of a (possibly multi-segment) product  C = sum_seg A_seg * op(B_seg).
+struct GemmSeg {
+  const void* A; int64_t lda;   // [M, K] row-major
+  const void* B; int64_t ldb;   // NT: [N, K] row-major;  NN: [K, N] row-major
+  int K;
+};
+enum EpiMode {
+  EPI_STORE = 0,        // C = acc
+  EPI_RESID = 1,        // C = acc + R
+  EPI_GELU = 2,         // C = gelu(acc); if C2: C2 = acc (pre-activation)
+  EPI_SWIGLU = 3,       // dual product (B, B2): C = silu(g) * u; if C2/C3: C2 = g, C3 = u
+  EPI_SWIGLU_BWD = 4,   // da = acc: C = da * U * silu'(G), C2 = da * silu(G)   (G = R, U = R2)
+  EPI_GELU_BWD = 5      // C = acc * gelu'(R)
+};
+struct GemmArgs {
+  int M, N;               // output [M, N]
+  int nseg; GemmSeg seg[3];
+  const void* B2; int64_t ldb2;   // second weight of the dual product (EPI_SWIGLU), same shape as seg[0].B
+  int b_is_kn;            // 0: NT (B stored [N,K]);  1: NN (B stored [K,N])
+  int epi;
+  void* C; int64_t ldc;
+  void* C2; void* C3;     // same leading dimension as C
+  const void* R; const void* R2; int64_t ldr;
+};
+
+// kernels_plain.hip: any shape, fp32 math, E = float | bf16 by `dtype`
+hipError_t plain_gemm(const GemmArgs& a, int dtype, hipStream_t st);
+hipError_t plain_norm_fwd(const void* x, const void* g, const void* b, void* out, int64_t T, int D, int kind, float eps,
+                          int dtype, hipStream_t st);
+// out = dres + d/dx [ Norm(x) ] applied to dn
+hipError_t plain_norm_bwd_add(const void* dn, const void* x, const void* g, const void* dres, void* out, int64_t T, int D,
+                              int kind, float eps, int dtype, hipStream_t st);
+// in-place rotation of the q and k parts of qkv [T, ld]; positions = token index mod S
+hipError_t plain_rope(void* qkv, int64_t ld, int64_t T, int S, int n_q_heads, int n_kv_heads, int hd, const float* cs_table,
+                      int inverse, int dtype, hipStream_t st);
+hipError_t plain_attn_fwd(const void* qkv, int64_t ld, void* o, float* lse, int B, int S, int H, int Hkv, int hd, int causal,
+                          int dtype, hipStream_t st);
+hipError_t plain_attn_bwd(const void* qkv, int64_t ld, const void* o, const void* dout, const float* lse, float* delta,
+                          void* dqkv, int B, int S, int H, int Hkv, int hd, int causal, int dtype, hipStream_t st);
+
+// gemm_mfma.hip: bf16 only; returns hipErrorInvalidValue if the shape is outside its limits
+bool mfma_gemm_supported(const GemmArgs& a);
+hipError_t mfma_gemm(const GemmArgs& a, hipStream_t st, int tile = 0);   // tile: 0 auto, 1 = 256x256, 2 = 128x128
+
+}  // namespace sv

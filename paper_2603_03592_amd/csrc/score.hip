@@ -1,0 +1,226 @@
+// Check statistics between submissions and a reference point, the flag rule, and the EMA
+// reference update.  All three kernels are streaming (HBM-bound) passes.
+//
+//   score_tokens_kernel : one pass over claim and reference.  Per token it forms the sums the
+//                         whole distance family needs (Omega_L1, Omega_L2, Omega_SFR of the
+//                         paragraph "Choice of Distance Measure", and the per-token relative
+//                         L2), then folds 16 tokens into one partial record.
+//   score_finalize_kernel: deterministic reduction of the records of one submission, the
+//                         scores, and the flag Gamma > tau (Eq. test_statistic; a submission
+//                         is flagged when any enabled metric exceeds its threshold).
+//   ema_update_kernel   : Eq. momentum_def over the un-flagged submissions.
+#include "common.h"
+
+namespace sv {
+
+namespace {
+
+constexpr int kTPW = kScoreTokensPerWG / 4;  // tokens per wave
+
+template <typename EC, typename ER>
+__global__ __launch_bounds__(256) void score_tokens_kernel(const EC* __restrict__ claims, int64_t claim_stride,
+                                                           const ER* __restrict__ ref, int64_t ref_stride, int64_t T, int D,
+                                                           int n_claims, int tiles_per_claim, float* __restrict__ token_scores,
+                                                           ScorePartial* __restrict__ partials) {
+  // claim index varies fastest so that workgroups running together share the reference rows
+  const int claim = blockIdx.x % n_claims;
+  const int tile = blockIdx.x / n_claims;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const EC* cbase = claims + (int64_t)claim * claim_stride;
+  const ER* rbase = ref + (int64_t)claim * ref_stride;
+
+  double acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  float best = -1.0f;
+  int best_t = 0, bad = 0;
+
+  for (int i = 0; i < kTPW; ++i) {
+    const int64_t t = (int64_t)tile * kScoreTokensPerWG + i * 4 + wave;
+    if (t >= T) break;  // uniform per wave
+    const EC* c = cbase + t * D;
+    const ER* r = rbase + t * D;
+    float sc = 0, sr = 0, scc = 0, srr = 0, sd = 0, sad = 0, sdd = 0, ns = 0;
+#pragma unroll 4
+    for (int k = lane * 8; k < D; k += 512) {
+      float cv[8], rv[8];
+      load8(c + k, cv);
+      load8(r + k, rv);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float a = cv[j], b = rv[j], d = a - b;
+        sc += a; sr += b; scc += a * a; srr += b * b;
+        sd += d; sad += fabsf(d); sdd += d * d;
+        const int sa = (a > 0.0f) - (a < 0.0f), sb = (b > 0.0f) - (b < 0.0f);
+        ns += (sa != sb) ? 1.0f : 0.0f;
+      }
+    }
+    sc = wave_sum(sc); sr = wave_sum(sr); scc = wave_sum(scc); srr = wave_sum(srr);
+    sd = wave_sum(sd); sad = wave_sum(sad); sdd = wave_sum(sdd); ns = wave_sum(ns);
+    const float rel = sqrtf(sdd) / fmaxf(sqrtf(srr), 1e-30f);
+    if (lane == 0 && token_scores) token_scores[(int64_t)claim * T + t] = rel;
+    acc[0] += sc; acc[1] += sr; acc[2] += scc; acc[3] += srr;
+    acc[4] += sd; acc[5] += sad; acc[6] += sdd; acc[7] += ns;
+    if (!(rel <= 3.0e38f)) bad = 1;           // NaN or inf
+    else if (rel > best) { best = rel; best_t = (int)t; }
+  }
+
+  __shared__ double s_acc[4][8];
+  __shared__ float s_best[4];
+  __shared__ int s_bt[4], s_bad[4];
+  if (lane == 0) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) s_acc[wave][j] = acc[j];
+    s_best[wave] = best; s_bt[wave] = best_t; s_bad[wave] = bad;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    ScorePartial p;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) p.s[j] = s_acc[0][j] + s_acc[1][j] + s_acc[2][j] + s_acc[3][j];
+    float b = -1.0f; int bt = 0, bd = 0;
+    for (int w = 0; w < 4; ++w) {
+      bd |= s_bad[w];
+      if (s_best[w] > b || (s_best[w] == b && s_best[w] >= 0.0f && s_bt[w] < bt)) { b = s_best[w]; bt = s_bt[w]; }
+    }
+    p.max_rel = b; p.argmax = bt; p.bad = bd; p.pad = 0;
+    partials[(int64_t)claim * tiles_per_claim + tile] = p;
+  }
+}
+
+struct Tau4 { float v[4]; };
+
+__global__ __launch_bounds__(256) void score_finalize_kernel(const ScorePartial* __restrict__ partials, int tiles_per_claim,
+                                                             int64_t T, int D, uint32_t mask, Tau4 tau, int reduce,
+                                                             sv_result* __restrict__ results) {
+  const int claim = blockIdx.x, tid = threadIdx.x;
+  const ScorePartial* p = partials + (int64_t)claim * tiles_per_claim;
+  double acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  float best = -1.0f; int bt = 0, bad = 0;
+  for (int i = tid; i < tiles_per_claim; i += 256) {     // tiles visited in increasing order
+    const ScorePartial q = p[i];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] += q.s[j];
+    bad |= q.bad;
+    if (q.max_rel > best) { best = q.max_rel; bt = q.argmax; }
+  }
+  __shared__ double s_acc[256][8];
+  __shared__ float s_best[256];
+  __shared__ int s_bt[256], s_bad[256];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) s_acc[tid][j] = acc[j];
+  s_best[tid] = best; s_bt[tid] = bt; s_bad[tid] = bad;
+  __syncthreads();
+  for (int stride = 128; stride > 0; stride >>= 1) {     // fixed tree: run-to-run identical
+    if (tid < stride) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) s_acc[tid][j] += s_acc[tid + stride][j];
+      s_bad[tid] |= s_bad[tid + stride];
+      const float o = s_best[tid + stride];
+      if (o > s_best[tid] || (o == s_best[tid] && s_bt[tid + stride] < s_bt[tid])) { s_best[tid] = o; s_bt[tid] = s_bt[tid + stride]; }
+    }
+    __syncthreads();
+  }
+  if (tid == 0) {
+    const double n = (double)T * (double)D;
+    const double Sc = s_acc[0][0], Sr = s_acc[0][1], Scc = s_acc[0][2], Srr = s_acc[0][3];
+    const double Sd = s_acc[0][4], Sad = s_acc[0][5], Sdd = s_acc[0][6], Ns = s_acc[0][7];
+    const double nan = __longlong_as_double(0x7ff8000000000000LL);
+    double sc[4];
+    const double grel = sqrt(Sdd) / fmax(sqrt(Srr), 1e-30);
+    const double mrel = s_bad[0] ? nan : (double)fmaxf(s_best[0], 0.0f);
+    sc[SV_IDX_RELL2] = (reduce == SV_REDUCE_MAX_TOKEN) ? mrel : grel;
+    sc[SV_IDX_L1] = Sad / n;
+    // z-scored L2 = 2 (1 - rho) = (var_d - (sd_c - sd_r)^2) / (sd_c sd_r): no cancellation for rho ~ 1
+    const double mc = Sc / n, mr = Sr / n, md = Sd / n;
+    const double vc = Scc / n - mc * mc, vr = Srr / n - mr * mr, vd = fmax(Sdd / n - md * md, 0.0);
+    const bool const_c = !(vc > 1e-10 * (Scc / n)), const_r = !(vr > 1e-10 * (Srr / n));
+    if (Scc != Scc || Srr != Srr) sc[SV_IDX_ZL2] = nan;
+    else if (const_c && const_r) sc[SV_IDX_ZL2] = 0.0;
+    else if (const_c || const_r) sc[SV_IDX_ZL2] = 2.0;
+    else {
+      const double a = sqrt(vc), b = sqrt(vr);
+      sc[SV_IDX_ZL2] = fmax(vd - (a - b) * (a - b), 0.0) / (a * b);
+    }
+    sc[SV_IDX_SFR] = Ns / n;
+    sv_result r;
+    uint32_t flag = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      r.score[i] = (float)sc[i];
+      if (((mask >> i) & 1u) && !(r.score[i] <= tau.v[i])) flag = 1;   // strict '>'; non-finite scores are flagged
+    }
+    r.flag = flag; r.metric_mask = mask;
+    r.max_token_rell2 = (float)mrel; r.argmax_token = s_bt[0];
+    results[claim] = r;
+  }
+}
+
+template <typename E>
+__global__ __launch_bounds__(256) void ema_update_kernel(float* __restrict__ m, const E* __restrict__ claims, int64_t claim_stride,
+                                                         int n_claims, const uint8_t* __restrict__ flags, int64_t n_vec, float beta) {
+  const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  int n_clean = 0;
+  for (int i = 0; i < n_claims; ++i) n_clean += (flags == nullptr || flags[i] == 0) ? 1 : 0;
+  if (v >= n_vec || n_clean == 0) return;   // every submission flagged: the EMA is left as it is
+  float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  for (int i = 0; i < n_claims; ++i) {
+    if (flags != nullptr && flags[i] != 0) continue;
+    float x[8];
+    load8(claims + (int64_t)i * claim_stride + v * 8, x);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] += x[j];
+  }
+  float mv[8];
+  load8(m + v * 8, mv);
+  const float w = (1.0f - beta) / (float)n_clean;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) mv[j] = beta * mv[j] + w * acc[j];
+  store8(m + v * 8, mv);
+}
+
+}  // namespace
+
+hipError_t launch_score(const void* claims, int64_t claim_stride, int n_claims, const void* ref, int64_t ref_stride,
+                        int claim_dtype, int ref_dtype, int64_t T, int D, uint32_t mask, const float* tau4, int reduce,
+                        float* token_scores, sv_result* results, ScorePartial* scratch, int64_t scratch_elems,
+                        hipStream_t st) {
+  if (n_claims <= 0 || T <= 0) return hipSuccess;
+  const int64_t tiles = (T + kScoreTokensPerWG - 1) / kScoreTokensPerWG;
+  int64_t per_launch = scratch_elems / tiles;
+  if (per_launch < 1) return hipErrorInvalidValue;
+  if (per_launch * tiles > 0x7fffffffLL) per_launch = 0x7fffffffLL / tiles;
+  Tau4 tau;
+  for (int i = 0; i < 4; ++i) tau.v[i] = tau4 ? tau4[i] : 0.0f;
+  const int64_t csz = claim_dtype == SV_BF16 ? 2 : 4, rsz = ref_dtype == SV_BF16 ? 2 : 4;
+  for (int64_t c0 = 0; c0 < n_claims; c0 += per_launch) {
+    const int nc = (int)((n_claims - c0 < per_launch) ? (n_claims - c0) : per_launch);
+    const char* cp = (const char*)claims + c0 * claim_stride * csz;
+    const char* rp = (const char*)ref + c0 * ref_stride * rsz;
+    float* ts = token_scores ? token_scores + c0 * T : nullptr;
+    const dim3 grid((unsigned)(tiles * nc)), block(256);
+#define SV_LAUNCH_SCORE(EC, ER)                                                                                   \
+  hipLaunchKernelGGL((score_tokens_kernel<EC, ER>), grid, block, 0, st, (const EC*)cp, claim_stride, (const ER*)rp, \
+                     ref_stride, T, D, nc, (int)tiles, ts, scratch)
+    if (claim_dtype == SV_BF16 && ref_dtype == SV_BF16) SV_LAUNCH_SCORE(bf16, bf16);
+    else if (claim_dtype == SV_BF16) SV_LAUNCH_SCORE(bf16, float);
+    else if (ref_dtype == SV_BF16) SV_LAUNCH_SCORE(float, bf16);
+    else SV_LAUNCH_SCORE(float, float);
+#undef SV_LAUNCH_SCORE
+    hipLaunchKernelGGL(score_finalize_kernel, dim3(nc), dim3(256), 0, st, scratch, (int)tiles, T, D, mask, tau, reduce,
+                       results + c0);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_ema(float* m, const void* claims, int64_t claim_stride, int n_claims, int claim_dtype,
+                      const uint8_t* flags, int64_t T, int D, float beta, hipStream_t st) {
+  if (n_claims <= 0 || T <= 0) return hipSuccess;
+  const int64_t n_vec = T * D / 8;
+  const dim3 grid((unsigned)((n_vec + 255) / 256)), block(256);
+  if (claim_dtype == SV_BF16)
+    hipLaunchKernelGGL(ema_update_kernel<bf16>, grid, block, 0, st, m, (const bf16*)claims, claim_stride, n_claims, flags, n_vec, beta);
+  else
+    hipLaunchKernelGGL(ema_update_kernel<float>, grid, block, 0, st, m, (const float*)claims, claim_stride, n_claims, flags, n_vec, beta);
+  return hipGetLastError();
+}
+
+}  // namespace sv

@@ -1,0 +1,61 @@
+"""CPU-only checks of the C ABI: the library loads, exports every declared symbol, and its
+host-side argument checks behave as the header says.  No compute call is made."""
+import ctypes
+import dataclasses
+import os
+import re
+
+import pytest
+
+import paper_2603_03592_amd as sv
+import stage_inputs as si
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "stageverify.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sv_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = declared_functions()
+    assert {"sv_create", "sv_destroy", "sv_verify_forward", "sv_verify_backward", "sv_score_and_flag",
+            "sv_ema_update", "sv_check_desc", "sv_workspace_bytes", "sv_last_error", "sv_gemm_bf16"} <= set(names)
+    lib = ctypes.CDLL(sv.LIB_PATH)
+    for n in names:
+        assert getattr(lib, n) is not None, n
+
+
+def test_result_struct_is_32_bytes():
+    assert sv.RESULT_DTYPE.itemsize == 32
+    assert sv.RESULT_DTYPE.fields["flag"][1] == 16 and sv.RESULT_DTYPE.fields["argmax_token"][1] == 28
+
+
+@pytest.mark.parametrize("wl", [si.TINY, si.SMALL, si.MEDIUM, si.LARGE, si.sweep_point(4096, 16)], ids=lambda w: w.name)
+def test_benchmark_stages_are_supported(wl):
+    st, msg = sv.sv_check_desc(wl.desc, 1 if wl.backward else 0)
+    assert st == 0, msg
+    fwd = sv.sv_workspace_bytes(wl.desc, wl.batch * wl.seq, wl.seq, 0)
+    bwd = sv.sv_workspace_bytes(wl.desc, wl.batch * wl.seq, wl.seq, 1)
+    assert 0 < fwd < bwd < 64 * 2 ** 30
+    assert sv.sv_workspace_bytes(wl.desc, 2 * wl.batch * wl.seq, wl.seq, 0) > fwd
+
+
+def test_malformed_and_unsupported_descriptors_are_rejected():
+    d = si.SMALL.desc
+    bad = [
+        (dataclasses.replace(d, n_heads=24), 1, "multiple of n_heads"),        # 1024 % 24
+        (dataclasses.replace(d, n_kv_heads=5), 1, "multiple of n_kv_heads"),
+        (dataclasses.replace(d, n_blocks=0), 1, "positive"),
+        (dataclasses.replace(d, d_model=1008, n_heads=14, n_kv_heads=14), 2, "head_dim"),     # hd = 72
+        (dataclasses.replace(d, ffn_hidden=2812), 2, "multiples of 8"),
+        (dataclasses.replace(d, rope_theta=0.0), 1, "rope_theta"),
+    ]
+    for desc, status, frag in bad:
+        st, msg = sv.sv_check_desc(desc)
+        assert st == status and frag in msg, (desc, st, msg)
+        assert sv.sv_workspace_bytes(desc, 128, 64) == -1
+    st, msg = sv.sv_check_desc(d, flags=64)
+    assert st == 1 and "flag" in msg

@@ -1,0 +1,183 @@
+"""GPU parity of the recompute (sv_verify_forward / sv_verify_backward) against the CPU oracle
+on small stages: element-wise relative L2 of the recomputed activations / gradients, and flag
+decisions bit-exact outside a +-5 % band around the threshold.
+
+Tolerances are the ones the benchmark definition states: relative L2 <= 1e-4 for fp32 stages
+and <= 2e-2 for bf16 stages (the oracle keeps fp64 throughout, the bf16 path rounds every
+stored intermediate to bf16)."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+import stage_inputs as si
+from oracle import stage_oracle as so
+from gpu_util import dev, dev_weights, host, rel_l2
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def run_stage(desc, B, S, seed, backward, plain=False, weight_scale=1.0, grad_std=1e-3):
+    import paper_2603_03592_amd as sv
+    w = si.make_weights(desc, seed)
+    if weight_scale != 1.0:
+        for b in w:
+            for k in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down"):
+                if b[k] is not None:
+                    b[k] = si.to_stage_dtype(b[k] * np.float32(weight_scale), desc.dtype)
+    h = si.make_activations(desc, B, S, seed)
+    g = si.make_output_grad(desc, B, S, seed, std=grad_std)
+    ver = sv.Verifier(desc, B * S, S, backward=backward, plain_kernels=plain)
+    wd = dev_weights(w, desc.dtype)
+    wc = ver.pack_weights(wd)
+    if backward:
+        out = ver.verify_backward(wc, dev(h, desc.dtype), dev(g, desc.dtype), want_g_hat=True, want_h_hat=True)
+        want_h, want_g = so.stage_backward(h, g, w, desc)
+        got = host(out["h_hat"]), host(out["g_hat"])
+    else:
+        out = ver.verify_forward(wc, dev(h, desc.dtype), want_h_hat=True)
+        want_h, want_g = so.stage_forward(h, w, desc), None
+        got = host(out["h_hat"]), None
+    ver.close()
+    return got, (want_h, want_g), h
+
+
+LLAMA_F32 = si.StageDesc(2, 64, 4, 2, 96, dtype="f32")                       # GQA, RoPE, SwiGLU, RMSNorm
+GPT_F32 = si.StageDesc(2, 48, 3, 3, 80, mlp="gelu", norm="ln", rope=False, dtype="f32")
+BIDIR_F32 = si.StageDesc(1, 32, 4, 1, 40, causal=False, dtype="f32")       # hd 8, multi-query, no mask
+MFMA_BF16 = si.StageDesc(2, 256, 4, 2, 384)                                  # every GEMM on the matrix cores
+MFMA_GELU = si.StageDesc(1, 256, 2, 2, 512, mlp="gelu", norm="ln", rope=False)
+
+
+@pytest.mark.parametrize("desc,B,S", [(LLAMA_F32, 3, 37), (GPT_F32, 2, 70), (BIDIR_F32, 2, 33), (si.TINY.desc, 2, 64)],
+                         ids=["llama_f32", "gpt_f32", "bidir_f32", "tiny"])
+@pytest.mark.parametrize("backward", [False, True], ids=["fwd", "bwd"])
+def test_fp32_stage_matches_oracle(desc, B, S, backward):
+    (gh, gg), (wh, wg), h = run_stage(desc, B, S, seed=1, backward=backward, weight_scale=4.0, grad_std=1.0)
+    assert rel_l2(gh, wh) <= TOL["f32"]
+    assert np.max(so.token_rel_l2(gh, wh)) <= 2 * TOL["f32"]
+    assert rel_l2(wh, h) > 0.05                       # the stage is not close to the identity
+    if backward:
+        assert rel_l2(gg, wg) <= TOL["f32"]
+
+
+@pytest.mark.parametrize("desc,B,S", [(MFMA_BF16, 3, 80), (MFMA_GELU, 2, 136), (dataclasses.replace(LLAMA_F32, dtype="bf16"), 3, 37)],
+                         ids=["mfma_swiglu", "mfma_gelu", "odd_shape_bf16"])
+@pytest.mark.parametrize("backward", [False, True], ids=["fwd", "bwd"])
+@pytest.mark.parametrize("plain", [False, True], ids=["mfma", "plain"])
+def test_bf16_stage_matches_oracle(desc, B, S, backward, plain):
+    (gh, gg), (wh, wg), h = run_stage(desc, B, S, seed=2, backward=backward, plain=plain, weight_scale=2.0)
+    assert rel_l2(gh, wh) <= TOL["bf16"]
+    assert np.max(so.token_rel_l2(gh, wh)) <= TOL["bf16"]
+    if backward:
+        assert rel_l2(gg, wg) <= TOL["bf16"]
+
+
+def test_forward_on_a_backward_context_and_sequence_independence():
+    import paper_2603_03592_amd as sv
+    desc = MFMA_BF16
+    w = si.make_weights(desc, 3)
+    ver = sv.Verifier(desc, 4 * 96, 96, backward=True)
+    wd = dev_weights(w, desc.dtype)
+    wc = ver.pack_weights(wd)
+    h = si.make_activations(desc, 4, 96, 3)
+    full = host(ver.verify_forward(wc, dev(h, "bf16"), want_h_hat=True)["h_hat"])
+    one = host(ver.verify_forward(wc, dev(h[2:3], "bf16"), want_h_hat=True)["h_hat"])
+    np.testing.assert_array_equal(full[2:3], one)     # same kernels, same tiles per sequence row
+    ver.close()
+
+
+def test_tiny_config_eight_submissions():
+    """Benchmark config 1: fp32, 8 submissions of h on 8 micro-batches, 2 with additive noise of
+    0.1 x RMS; threshold 1e-3 on the per-token relative L2."""
+    import paper_2603_03592_amd as sv
+    wl = si.TINY
+    w = si.make_weights(wl.desc, 0)
+    ver = sv.Verifier(wl.desc, wl.batch * wl.seq, wl.seq)
+    wd = dev_weights(w, "f32")
+    wc = ver.pack_weights(wd)
+    bad = {2, 5}
+    for i in range(wl.n_claims):
+        h = si.make_activations(wl.desc, wl.batch, wl.seq, seed=0, micro_batch=i)
+        ref = so.stage_forward(h, w, wl.desc)
+        claim = si.make_claim("noise" if i in bad else "honest", ref, "f32", seed=i)
+        out = ver.verify_forward(wc, dev(h, "f32"), dev(claim, "f32"), metrics=("rel_l2",), tau={"rel_l2": wl.tau},
+                                 want_h_hat=True, want_token_scores=True)
+        res = ver.read_results(out["result"])[0]
+        assert rel_l2(host(out["h_hat"]), ref) <= 1e-4
+        want = so.scores(claim, ref)["rel_l2"]
+        assert bool(res["flag"]) == (i in bad) == so.flag({"rel_l2": want}, {"rel_l2": wl.tau})
+        if i in bad:
+            assert res["score"][0] == pytest.approx(want, rel=1e-3)
+            assert 0.05 < want < 0.2
+        else:
+            assert res["score"][0] < 0.05 * wl.tau       # honest fp32 submissions sit far below the threshold
+    ver.close()
+
+
+def test_corruptions_flagged_honest_not_bf16_forward_and_backward():
+    """Spec invariants on a bf16 stage: honest submissions of h and g score below the threshold,
+    every injected corruption above it; flags equal the oracle's outside the +-5 % band."""
+    import paper_2603_03592_amd as sv
+    desc, B, S, tau = MFMA_BF16, 2, 128, 2e-2
+    w = si.make_weights(desc, 7)
+    for b in w:
+        for k in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down"):
+            b[k] = si.to_stage_dtype(b[k] * np.float32(2.0), "bf16")
+    h = si.make_activations(desc, B, S, 7)
+    g = si.make_output_grad(desc, B, S, 7)
+    want_h, want_g = so.stage_backward(h, g, w, desc)
+    ver = sv.Verifier(desc, B * S, S, backward=True)
+    wd = dev_weights(w, "bf16")
+    wc = ver.pack_weights(wd)
+    hd_, gd_ = dev(h, "bf16"), dev(g, "bf16")
+    kinds = ["honest", "noise", "scale", "sign", "zero", "tok_noise", "tok_neg"]
+    for signal, ref in (("h", want_h), ("g", want_g)):
+        for i, kind in enumerate(kinds):
+            claim = si.make_claim(kind, ref, "bf16", seed=i)
+            if signal == "h":
+                out = ver.verify_forward(wc, hd_, dev(claim, "bf16"), tau={"rel_l2": tau})
+            else:
+                out = ver.verify_backward(wc, hd_, gd_, dev(claim, "bf16"), tau={"rel_l2": tau})
+            res = ver.read_results(out["result"])[0]
+            oracle_score = so.scores(claim, ref)["rel_l2"]
+            assert so.flag({"rel_l2": oracle_score}, {"rel_l2": tau}) == (kind != "honest")
+            if abs(oracle_score / tau - 1) > 0.05:
+                assert bool(res["flag"]) == (kind != "honest"), (signal, kind, res, oracle_score)
+            if kind == "honest":
+                assert res["score"][0] < 0.95 * tau, (signal, res)
+    # the "identity attack" (forwarding the input unchanged) must be caught as well
+    out = ver.verify_forward(wc, hd_, hd_, tau={"rel_l2": tau})
+    assert ver.read_results(out["result"])[0]["flag"] == 1
+    ver.close()
+
+
+def test_limits_are_errors():
+    import paper_2603_03592_amd as sv
+    ver = sv.Verifier(MFMA_BF16, 256, 64)
+    w = dev_weights(si.make_weights(MFMA_BF16, 0), "bf16")
+    wc = ver.pack_weights(w)
+    h = dev(si.make_activations(MFMA_BF16, 2, 128, 0), "bf16")
+    with pytest.raises(sv.SVError, match="exceeds"):
+        ver.verify_forward(wc, h)                                       # S = 128 > max_seq
+    with pytest.raises(sv.SVError, match="BACKWARD"):
+        ver.verify_backward(wc, h[:, :64].contiguous(), h[:, :64].contiguous())
+    ver.close()
+
+
+@pytest.mark.parametrize("kn", [False, True], ids=["nt", "nn"])
+@pytest.mark.parametrize("tile", [1, 2], ids=["256x256", "128x128"])
+def test_mfma_gemm_against_fp64_product(kn, tile):
+    """The GEMM kernels alone, several tiles plus a ragged row tail, against numpy in float64."""
+    import paper_2603_03592_amd as sv
+    g = np.random.default_rng(11)
+    M, N, K = 600, 512, 320
+    a = si.round_to_bf16(g.standard_normal((M, K)).astype(np.float32))
+    b = si.round_to_bf16(g.standard_normal((K, N) if kn else (N, K)).astype(np.float32))
+    got = host(sv.sv_gemm_bf16(dev(a, "bf16"), dev(b, "bf16"), b_is_kn=kn, tile=tile))
+    want = a.astype(np.float64) @ (b.astype(np.float64) if kn else b.astype(np.float64).T)
+    # one bf16 rounding of an fp32-accumulated sum: relative 2^-9 per element at most
+    np.testing.assert_allclose(got, want, rtol=2 ** -8, atol=2e-2)
+    assert rel_l2(got, want) < 3e-3

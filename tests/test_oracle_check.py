@@ -157,3 +157,14 @@ def test_momentum_deviation_lemma_bound():
         m_nom = m_nom_next
         assert np.linalg.norm(m_obs - m_nom) <= n_bad / d * eps * (1 + 1e-12)
     assert np.linalg.norm(m_obs - m_nom) > 0
+
+
+def test_non_finite_submission_is_flagged_and_constant_signals_have_no_zscore():
+    r = ref_signal(T=8, D=8)
+    c = r.copy()
+    c[2, 3] = np.nan
+    assert so.flag(so.scores(c, r), {"rel_l2": 1e9})
+    assert so.flag(so.scores(c, r, "global"), {"l1": 1e9})
+    ones = -np.ones_like(r) * 0.1                      # the constant attack with a value that does not sum exactly
+    assert so.scores(ones, r)["zl2"] == 2.0
+    assert so.scores(ones, ones * 3)["zl2"] == 0.0
