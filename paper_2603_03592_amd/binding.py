@@ -5,6 +5,7 @@ import os
 from typing import Dict, List, Optional, Sequence
 
 import numpy as np
+import torch  # noqa: F401  -- first: the library must bind to the HIP runtime torch has loaded (one runtime per process)
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libstageverify.so")
 
