@@ -197,6 +197,13 @@ hipError_t gemm(sv_ctx* c, const GemmArgs& a, hipStream_t st) {
   return plain_gemm(a, c->d.dtype, st);
 }
 
+hipError_t attn_fwd(sv_ctx* c, const void* qkv, void* o, float* lse, int B, int S, hipStream_t st) {
+  const sv_stage_desc& d = c->d;
+  if (d.dtype == SV_BF16 && !(c->flags & SV_FLAG_PLAIN_KERNELS) && mfma_attn_supported(S, d.n_heads, d.n_kv_heads, c->hd, c->Dqkv))
+    return mfma_attn_fwd(qkv, c->Dqkv, o, lse, B, S, d.n_heads, d.n_kv_heads, c->hd, d.causal, st);
+  return plain_attn_fwd(qkv, c->Dqkv, o, lse, B, S, d.n_heads, d.n_kv_heads, c->hd, d.causal, d.dtype, st);
+}
+
 GemmArgs nt(int M, int N, int K, const void* A, int64_t lda, const void* W, void* C, int64_t ldc, int epi) {
   GemmArgs g; memset(&g, 0, sizeof(g));
   g.M = M; g.N = N; g.nseg = 1; g.seg[0] = GemmSeg{A, lda, W, (int64_t)K, K};
@@ -219,7 +226,7 @@ sv_status block_forward(sv_ctx* c, const sv_block_weights& w, const void* x, voi
   SV_OP(c, SV_OP_GEMM_QKV, 2.0 * Td * c->Dkv * D, st, gemm(c, nt(T, c->Dkv, D, c->n, D, w.wk, at(qkv, c->Dq, es), c->Dqkv, EPI_STORE), st));
   SV_OP(c, SV_OP_GEMM_QKV, 2.0 * Td * c->Dkv * D, st, gemm(c, nt(T, c->Dkv, D, c->n, D, w.wv, at(qkv, c->Dq + c->Dkv, es), c->Dqkv, EPI_STORE), st));
   if (d.rope) SV_OP(c, SV_OP_ROPE, 0, st, plain_rope(qkv, c->Dqkv, T, S, d.n_heads, d.n_kv_heads, c->hd, c->rope_cs, 0, dt, st));
-  SV_OP(c, SV_OP_ATTN, attn_flop, st, plain_attn_fwd(qkv, c->Dqkv, o, lse, B, S, d.n_heads, d.n_kv_heads, c->hd, d.causal, dt, st));
+  SV_OP(c, SV_OP_ATTN, attn_flop, st, attn_fwd(c, qkv, o, lse, B, S, st));
   {
     GemmArgs g = nt(T, D, c->Dq, o, c->Dq, w.wo, x1, D, EPI_RESID);
     g.R = x; g.ldr = D;

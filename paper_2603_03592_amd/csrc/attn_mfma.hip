@@ -1,0 +1,222 @@
+// Causal / full softmax attention of the block recompute on the gfx950 matrix cores
+// (bf16 inputs, fp32 scores, softmax statistics and accumulation; head_dim 64 or 128; GQA).
+//
+// Forward: one workgroup = 128 queries of one (sequence, query head); each of its 4 waves owns
+// 32 queries.  Keys/values stream through LDS in tiles of 64, double buffered.  Per tile a wave
+// computes the TRANSPOSED score block S^T = K Q^T with v_mfma_f32_32x32x16_bf16 (keys in the
+// MFMA row dimension, queries in the column dimension), so every lane owns one query column:
+// the running maximum, the running sum and the rescale factor of the online softmax are
+// per-lane scalars and only one cross-lane exchange (lane ^ 32) per tile is needed.  The
+// probabilities then feed O^T += V^T P^T directly from registers: the accumulator layout of
+// S^T is a valid B-operand layout once the 16 keys of an MFMA are taken in the order
+// {0-3, 8-11 | 4-7, 12-15}; V is transposed into LDS in exactly that key order (4x8 register
+// transposes on the way in), so a V^T fragment is one 16-byte LDS read.
+#include "common.h"
+
+namespace sv {
+namespace {
+
+constexpr int BQ = 128, BKV = 64;
+
+__device__ __forceinline__ int swz8(int row) { return (row ^ (row >> 3)) & 7; }
+
+template <int HD, bool CAUSAL>
+__global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16* __restrict__ qkv, int64_t ld, bf16* __restrict__ o,
+                                                            float* __restrict__ lse, int S, int H, int Hkv, float scale_log2e) {
+  constexpr int KCH = HD / 8;                       // 16-byte chunks per K row
+  constexpr int KROW = HD * 2;                      // bytes per K row in LDS
+  constexpr int KSTAGE = BKV * KROW, VSTAGE = HD * 128, STAGE = KSTAGE + VSTAGE;
+  constexpr int KPT = BKV * KCH / 256;              // K chunks per thread
+  constexpr int VUNITS = (BKV / 4) * KCH;           // (key quad, d group) units of the V tile
+  constexpr int NKK = HD / 16, NDB = HD / 32;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+
+  const int nqt = (S + BQ - 1) / BQ;
+  const int qt = nqt - 1 - (int)blockIdx.x;         // longest rows first
+  const int h = blockIdx.y, b = blockIdx.z, kvh = h / (H / Hkv);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l31 = lane & 31, half = lane >> 5;
+  const int q0 = qt * BQ, wq0 = q0 + wave * 32;
+  const int Dq = H * HD, Dkv = Hkv * HD;
+  const bf16* qbase = qkv + (int64_t)b * S * ld + (int64_t)h * HD;
+  const bf16* kbase = qkv + (int64_t)b * S * ld + Dq + (int64_t)kvh * HD;
+  const bf16* vbase = kbase + Dkv;
+
+  bf16x8 qf[NKK];
+  {
+    const int qrow = min(wq0 + l31, S - 1);
+#pragma unroll
+    for (int kk = 0; kk < NKK; ++kk) qf[kk] = *reinterpret_cast<const bf16x8*>(qbase + (int64_t)qrow * ld + kk * 16 + half * 8);
+  }
+
+  const int nkv = (S + BKV - 1) / BKV;
+  const int ntiles = CAUSAL ? min((q0 + BQ + BKV - 1) / BKV, nkv) : nkv;
+
+  bf16x8 kreg[KPT], vreg[4];
+  const bool vactive = tid < VUNITS;
+  const int v_dg = tid % KCH, v_kq = tid / KCH;     // d group (8 wide), key quad (4 keys)
+  auto load_tile = [&](int j) {
+    const int k0 = j * BKV;
+#pragma unroll
+    for (int i = 0; i < KPT; ++i) {
+      const int e = tid + i * 256, r = e / KCH, c = e % KCH;
+      kreg[i] = *reinterpret_cast<const bf16x8*>(kbase + (int64_t)min(k0 + r, S - 1) * ld + c * 8);
+    }
+    if (vactive) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        vreg[i] = *reinterpret_cast<const bf16x8*>(vbase + (int64_t)min(k0 + v_kq * 4 + i, S - 1) * ld + v_dg * 8);
+    }
+  };
+  auto store_tile = [&](int stage) {
+    char* ks = smem + stage * STAGE;
+    char* vs = ks + KSTAGE;
+#pragma unroll
+    for (int i = 0; i < KPT; ++i) {
+      const int e = tid + i * 256, r = e / KCH, c = e % KCH;
+      *reinterpret_cast<bf16x8*>(ks + r * KROW + (((c & ~7) | ((c ^ r) & 7)) << 4)) = kreg[i];
+    }
+    if (vactive) {
+      typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+      typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+      u32x4 in[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) in[i] = __builtin_bit_cast(u32x4, vreg[i]);
+      const int g = v_kq >> 2, qd = v_kq & 3;
+      const int chunk = 2 * g + (qd & 1), sub = (qd >> 1) * 8;
+#pragma unroll
+      for (int dd = 0; dd < 8; ++dd) {               // feature v_dg*8 + dd: 4 keys -> 8 bytes
+        const uint32_t sel = (dd & 1) ? 0x07060302u : 0x05040100u;
+        u32x2 ov;
+        ov[0] = __builtin_amdgcn_perm(in[1][dd >> 1], in[0][dd >> 1], sel);
+        ov[1] = __builtin_amdgcn_perm(in[3][dd >> 1], in[2][dd >> 1], sel);
+        const int d = v_dg * 8 + dd;
+        *reinterpret_cast<u32x2*>(vs + d * 128 + ((chunk ^ swz8(d)) << 4) + sub) = ov;
+      }
+    }
+  };
+
+  f32x16 oacc[NDB];
+#pragma unroll
+  for (int i = 0; i < NDB; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[i][r] = 0.0f;
+  float m_run = -INFINITY, l_run = 0.0f;             // in units of log2: scores are scaled by scale*log2(e)
+  const int myq = wq0 + l31;
+
+  load_tile(0);
+  store_tile(0);
+  __syncthreads();
+
+  for (int j = 0; j < ntiles; ++j) {
+    const bool more = j + 1 < ntiles;
+    if (more) load_tile(j + 1);
+    const int k0 = j * BKV;
+    const bool wave_active = !CAUSAL || k0 <= wq0 + 31;
+    if (wave_active) {
+      const char* ks = smem + (j & 1) * STAGE;
+      const char* vs = ks + KSTAGE;
+      f32x16 s[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[t][r] = 0.0f;
+        const int krow = t * 32 + l31;
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk) {
+          const int c = kk * 2 + half;
+          const bf16x8 kf = *reinterpret_cast<const bf16x8*>(ks + krow * KROW + (((c & ~7) | ((c ^ krow) & 7)) << 4));
+          s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s[t], 0, 0, 0);
+        }
+      }
+      // mask (diagonal tiles and the ragged key tail), then the online softmax update
+      const bool need_mask = (CAUSAL && k0 + BKV - 1 > wq0) || (k0 + BKV > S);
+      float mx = -INFINITY;
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          if (need_mask) {
+            const int key = k0 + t * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+            if ((CAUSAL && key > myq) || key >= S) s[t][r] = -INFINITY;
+          }
+          mx = fmaxf(mx, s[t][r]);
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m_run, mx * scale_log2e);
+      const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
+      m_run = m_new;
+      float psum = 0.0f;
+      bf16x8 pf[4];
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float p = __builtin_amdgcn_exp2f(fmaf(s[t][r], scale_log2e, -m_new));
+          psum += p;
+          pf[t * 2 + (r >> 3)][r & 7] = (bf16)p;
+        }
+      l_run = l_run * corr + psum;
+#pragma unroll
+      for (int i = 0; i < NDB; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[i][r] *= corr;
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) {
+          const int d = db * 32 + l31;
+          const bf16x8 vf = *reinterpret_cast<const bf16x8*>(vs + d * 128 + (((2 * g + half) ^ swz8(d)) << 4));
+          oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[g], oacc[db], 0, 0, 0);
+        }
+    }
+    if (more) store_tile((j + 1) & 1);
+    __syncthreads();
+  }
+
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  if (myq < S) {
+    const float inv = 1.0f / l_tot;
+    bf16* orow = o + ((int64_t)b * S + myq) * Dq + (int64_t)h * HD;
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        bf16x4 pk;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) pk[i] = (bf16)(oacc[db][g4 * 4 + i] * inv);
+        *reinterpret_cast<bf16x4*>(orow + db * 32 + g4 * 8 + half * 4) = pk;
+      }
+    if (half == 0) lse[((int64_t)b * H + h) * S + myq] = (m_run + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994531f;
+  }
+}
+
+}  // namespace
+
+bool mfma_attn_supported(int S, int H, int Hkv, int hd, int64_t ld) {
+  return (hd == 64 || hd == 128) && S >= 1 && H % Hkv == 0 && ld % 8 == 0;
+}
+
+hipError_t mfma_attn_fwd(const void* qkv, int64_t ld, void* o, float* lse, int B, int S, int H, int Hkv, int hd, int causal, hipStream_t st) {
+  if (!mfma_attn_supported(S, H, Hkv, hd, ld)) return hipErrorInvalidValue;
+  if (B <= 0) return hipSuccess;
+  const dim3 grid((S + BQ - 1) / BQ, H, B), block(256);
+  const float c = 1.4426950408889634f / sqrtf((float)hd);
+#define SV_ATTN_LAUNCH(HDV, CZ)                                                                                         \
+  do {                                                                                                                  \
+    auto kern = attn_fwd_mfma_kernel<HDV, CZ>;                                                                          \
+    constexpr int lds = 2 * (BKV * HDV * 2 + HDV * 128);                                                                \
+    static bool configured = false;                                                                                     \
+    if (!configured) {                                                                                                  \
+      hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);           \
+      if (e != hipSuccess) return e;                                                                                    \
+      configured = true;                                                                                                \
+    }                                                                                                                   \
+    hipLaunchKernelGGL(kern, grid, block, lds, st, (const bf16*)qkv, ld, (bf16*)o, lse, S, H, Hkv, c);                  \
+  } while (0)
+  if (hd == 128) { if (causal) SV_ATTN_LAUNCH(128, true); else SV_ATTN_LAUNCH(128, false); }
+  else { if (causal) SV_ATTN_LAUNCH(64, true); else SV_ATTN_LAUNCH(64, false); }
+#undef SV_ATTN_LAUNCH
+  return hipGetLastError();
+}
+
+}  // namespace sv

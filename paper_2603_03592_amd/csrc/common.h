@@ -144,4 +144,9 @@ hipError_t plain_attn_bwd(const void* qkv, int64_t ld, const void* o, const void
 bool mfma_gemm_supported(const GemmArgs& a);
 hipError_t mfma_gemm(const GemmArgs& a, hipStream_t st, int tile = 0);   // tile: 0 auto, 1 = 256x256, 2 = 128x128
 
+// attn_mfma.hip: bf16, head_dim 64 | 128
+bool mfma_attn_supported(int S, int H, int Hkv, int hd, int64_t ld);
+hipError_t mfma_attn_fwd(const void* qkv, int64_t ld, void* o, float* lse, int B, int S, int H, int Hkv, int hd, int causal,
+                         hipStream_t st);
+
 }  // namespace sv
