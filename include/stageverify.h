@@ -159,7 +159,7 @@ sv_status sv_ema_update(sv_ctx *ctx, float *m, const void *claims, int64_t claim
 enum {
   SV_OP_NORM = 0, SV_OP_GEMM_QKV, SV_OP_ROPE, SV_OP_ATTN, SV_OP_GEMM_O, SV_OP_GEMM_GATEUP, SV_OP_GEMM_DOWN,
   SV_OP_SCORE, SV_OP_BWD_GEMM_DA, SV_OP_BWD_GEMM_DN2, SV_OP_BWD_NORM, SV_OP_BWD_GEMM_DO, SV_OP_BWD_ATTN,
-  SV_OP_BWD_ROPE, SV_OP_BWD_GEMM_DN1, SV_OP_COUNT
+  SV_OP_BWD_ROPE, SV_OP_BWD_GEMM_DN1, SV_OP_BWD_WTRANSPOSE, SV_OP_COUNT
 };
 typedef struct {
   double  ms[SV_OP_COUNT];
@@ -171,7 +171,8 @@ sv_status sv_profile_read(sv_ctx *ctx, sv_profile *out);
 
 /* Tuning and test aid: one bf16 product C[M,N] = A[M,K] * op(B) on the MFMA GEMM kernels that
  * the block recompute uses (fp32 accumulation, bf16 result).  b_is_kn = 0: B stored [N,K]
- * (C = A B^T); 1: B stored [K,N] (C = A B).  tile: 0 = automatic, 1 = 256x256, 2 = 128x128.
+ * (C = A B^T); 1: B stored [K,N] (C = A B).  tile: 0 = automatic, 1 = 256x256 (direct-to-LDS
+ * loads when B is [N,K]), 2 = 128x128, 3 = 256x256 with register-staged loads.
  * Returns SV_EUNSUPPORTED for shapes outside the kernels' limits (N % 128, K % 64, 16-byte
  * aligned rows).  No context is needed.                                                      */
 sv_status sv_gemm_bf16(const void *A, int64_t lda, const void *B, int64_t ldb, int32_t b_is_kn, void *C, int64_t ldc,

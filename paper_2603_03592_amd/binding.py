@@ -40,7 +40,7 @@ class BlockWeightsC(C.Structure):
 
 
 OP_NAMES = ("norm", "gemm_qkv", "rope", "attn", "gemm_o", "gemm_gateup", "gemm_down", "score", "bwd_gemm_da",
-            "bwd_gemm_dn2", "bwd_norm", "bwd_gemm_do", "bwd_attn", "bwd_rope", "bwd_gemm_dn1")
+            "bwd_gemm_dn2", "bwd_norm", "bwd_gemm_do", "bwd_attn", "bwd_rope", "bwd_gemm_dn1", "bwd_wtranspose")
 
 
 class ProfileC(C.Structure):

@@ -54,6 +54,7 @@ struct sv_ctx {
   std::vector<void*> xs;           // outputs of blocks 0..L-2 (inputs of blocks 1..L-1)
   std::vector<BlockStash> stash;
   void *dres[2], *dn, *dx1, *dgate, *dup, *dout, *dqkv;
+  void *wqT, *wkT, *wvT, *woT, *wgT, *wuT, *wdT;   // one block's weights transposed to [in, out] (bf16 MFMA path)
   float* delta;
   ScorePartial* score_scratch;
   float* rope_cs;
@@ -141,6 +142,12 @@ size_t carve(sv_ctx* c, char* base) {
     c->dout = a.take(T * c->Dq * es);
     c->dqkv = a.take(T * c->Dqkv * es);
     c->delta = (float*)a.take(lse_n * sizeof(float));
+    c->wqT = c->wkT = c->wvT = c->woT = c->wgT = c->wuT = c->wdT = nullptr;
+    if (d.dtype == SV_BF16 && !(c->flags & SV_FLAG_PLAIN_KERNELS)) {
+      c->wqT = a.take(D * c->Dq * es); c->wkT = a.take(D * c->Dkv * es); c->wvT = a.take(D * c->Dkv * es);
+      c->woT = a.take(D * c->Dq * es); c->wuT = a.take(D * F * es); c->wdT = a.take(D * F * es);
+      c->wgT = d.mlp == SV_MLP_SWIGLU ? a.take(D * F * es) : nullptr;
+    }
   }
   return a.off + 256;
 }
@@ -266,37 +273,60 @@ sv_status block_backward(sv_ctx* c, const sv_block_weights& w, const void* x, co
   const sv_stage_desc& d = c->d;
   const int T = B * S, D = d.d_model, F = d.ffn_hidden, es = c->es, dt = d.dtype;
   const double Td = T, attn_flop = (d.causal ? 2.0 : 4.0) * B * d.n_heads * (double)S * S * c->hd;
+  // On the bf16 matrix-core path the [out, in] weights are first transposed to [in, out], so that
+  // every backward product dY * W is again an "activations times [N, K] weights" product and runs
+  // on the same direct-to-LDS kernel as the forward (the transposes move 2 x weight bytes through
+  // HBM, a few percent of the backward GEMM time).
+  const bool wt = c->wqT != nullptr;
+  if (wt) {
+    SV_OP(c, SV_OP_BWD_WTRANSPOSE, 0, st, plain_transpose(w.w_down, c->wdT, D, F, dt, st));
+    SV_OP(c, SV_OP_BWD_WTRANSPOSE, 0, st, plain_transpose(w.w_up, c->wuT, F, D, dt, st));
+    if (d.mlp == SV_MLP_SWIGLU) SV_OP(c, SV_OP_BWD_WTRANSPOSE, 0, st, plain_transpose(w.w_gate, c->wgT, F, D, dt, st));
+    SV_OP(c, SV_OP_BWD_WTRANSPOSE, 0, st, plain_transpose(w.wo, c->woT, D, c->Dq, dt, st));
+    SV_OP(c, SV_OP_BWD_WTRANSPOSE, 0, st, plain_transpose(w.wq, c->wqT, c->Dq, D, dt, st));
+    SV_OP(c, SV_OP_BWD_WTRANSPOSE, 0, st, plain_transpose(w.wk, c->wkT, c->Dkv, D, dt, st));
+    SV_OP(c, SV_OP_BWD_WTRANSPOSE, 0, st, plain_transpose(w.wv, c->wvT, c->Dkv, D, dt, st));
+  }
+  // product dY [T, K] * W [K, N] with W given as stored ([K, N]) or transposed ([N, K])
+  auto seg = [&](GemmArgs& g, const void* A, int64_t lda, const void* W, const void* WT, int K, int N) {
+    if (wt) add_seg(g, A, lda, WT, K, K); else add_seg(g, A, lda, W, N, K);
+  };
+  auto args = [&](int N, void* Cout, int64_t ldc, int epi) {
+    GemmArgs g = nn(T, N, Cout, ldc, epi);
+    g.b_is_kn = wt ? 0 : 1;
+    return g;
+  };
   if (d.mlp == SV_MLP_SWIGLU) {
-    GemmArgs g = nn(T, F, c->dgate, F, EPI_SWIGLU_BWD);          // da = dy Wd, then through silu(g)*u
-    add_seg(g, dy, D, w.w_down, F, D);
+    GemmArgs g = args(F, c->dgate, F, EPI_SWIGLU_BWD);           // da = dy Wd, then through silu(g)*u
+    seg(g, dy, D, w.w_down, c->wdT, D, F);
     g.C2 = c->dup; g.R = k.gate; g.R2 = k.up; g.ldr = F;
     SV_OP(c, SV_OP_BWD_GEMM_DA, 2.0 * Td * F * D, st, gemm(c, g, st));
-    GemmArgs h = nn(T, D, c->dn, D, EPI_STORE);                  // dn2 = dG Wg + dU Wu
-    add_seg(h, c->dgate, F, w.w_gate, D, F);
-    add_seg(h, c->dup, F, w.w_up, D, F);
+    GemmArgs h = args(D, c->dn, D, EPI_STORE);                   // dn2 = dG Wg + dU Wu
+    seg(h, c->dgate, F, w.w_gate, c->wgT, F, D);
+    seg(h, c->dup, F, w.w_up, c->wuT, F, D);
     SV_OP(c, SV_OP_BWD_GEMM_DN2, 4.0 * Td * F * D, st, gemm(c, h, st));
   } else {
-    GemmArgs g = nn(T, F, c->dgate, F, EPI_GELU_BWD);
-    add_seg(g, dy, D, w.w_down, F, D);
+    GemmArgs g = args(F, c->dgate, F, EPI_GELU_BWD);
+    seg(g, dy, D, w.w_down, c->wdT, D, F);
     g.R = k.up; g.ldr = F;
     SV_OP(c, SV_OP_BWD_GEMM_DA, 2.0 * Td * F * D, st, gemm(c, g, st));
-    GemmArgs h = nn(T, D, c->dn, D, EPI_STORE);
-    add_seg(h, c->dgate, F, w.w_up, D, F);
+    GemmArgs h = args(D, c->dn, D, EPI_STORE);
+    seg(h, c->dgate, F, w.w_up, c->wuT, F, D);
     SV_OP(c, SV_OP_BWD_GEMM_DN2, 2.0 * Td * F * D, st, gemm(c, h, st));
   }
   SV_OP(c, SV_OP_BWD_NORM, 0, st, plain_norm_bwd_add(c->dn, k.x1, w.norm2_g, dy, c->dx1, T, D, d.norm, d.norm_eps, dt, st));
   {
-    GemmArgs g = nn(T, c->Dq, c->dout, c->Dq, EPI_STORE);        // do = dx1 Wo
-    add_seg(g, c->dx1, D, w.wo, c->Dq, D);
+    GemmArgs g = args(c->Dq, c->dout, c->Dq, EPI_STORE);         // do = dx1 Wo
+    seg(g, c->dx1, D, w.wo, c->woT, D, c->Dq);
     SV_OP(c, SV_OP_BWD_GEMM_DO, 2.0 * Td * D * c->Dq, st, gemm(c, g, st));
   }
   SV_OP(c, SV_OP_BWD_ATTN, 2.5 * attn_flop, st, plain_attn_bwd(k.qkv, c->Dqkv, k.o, c->dout, k.lse, c->delta, c->dqkv, B, S, d.n_heads, d.n_kv_heads, c->hd, d.causal, dt, st));
   if (d.rope) SV_OP(c, SV_OP_BWD_ROPE, 0, st, plain_rope(c->dqkv, c->Dqkv, T, S, d.n_heads, d.n_kv_heads, c->hd, c->rope_cs, 1, dt, st));
   {
-    GemmArgs g = nn(T, D, c->dn, D, EPI_STORE);                  // dn1 = dq Wq + dk Wk + dv Wv
-    add_seg(g, c->dqkv, c->Dqkv, w.wq, D, c->Dq);
-    add_seg(g, at(c->dqkv, c->Dq, es), c->Dqkv, w.wk, D, c->Dkv);
-    add_seg(g, at(c->dqkv, c->Dq + c->Dkv, es), c->Dqkv, w.wv, D, c->Dkv);
+    GemmArgs g = args(D, c->dn, D, EPI_STORE);                   // dn1 = dq Wq + dk Wk + dv Wv
+    seg(g, c->dqkv, c->Dqkv, w.wq, c->wqT, c->Dq, D);
+    seg(g, at(c->dqkv, c->Dq, es), c->Dqkv, w.wk, c->wkT, c->Dkv, D);
+    seg(g, at(c->dqkv, c->Dq + c->Dkv, es), c->Dqkv, w.wv, c->wvT, c->Dkv, D);
     SV_OP(c, SV_OP_BWD_GEMM_DN1, 2.0 * Td * D * c->Dqkv, st, gemm(c, g, st));
   }
   SV_OP(c, SV_OP_BWD_NORM, 0, st, plain_norm_bwd_add(c->dn, x, w.norm1_g, c->dx1, dx, T, D, d.norm, d.norm_eps, dt, st));
@@ -499,11 +529,11 @@ sv_status sv_ema_update(sv_ctx* c, float* m, const void* claims, int64_t claim_s
 
 sv_status sv_gemm_bf16(const void* A, int64_t lda, const void* B, int64_t ldb, int32_t b_is_kn, void* Cout, int64_t ldc, int32_t M,
                        int32_t N, int32_t K, int32_t tile, void* stream) {
-  if (!A || !B || !Cout || M < 1 || N < 1 || K < 1 || tile < 0 || tile > 2) return SV_EINVAL;
+  if (!A || !B || !Cout || M < 1 || N < 1 || K < 1 || tile < 0 || tile > 3) return SV_EINVAL;
   GemmArgs g; memset(&g, 0, sizeof(g));
   g.M = M; g.N = N; g.nseg = 1; g.seg[0] = GemmSeg{A, lda, B, ldb, K};
   g.b_is_kn = b_is_kn ? 1 : 0; g.epi = EPI_STORE; g.C = Cout; g.ldc = ldc;
-  if (!mfma_gemm_supported(g) || (tile == 1 && N % 256)) return SV_EUNSUPPORTED;
+  if (!mfma_gemm_supported(g) || ((tile == 1 || tile == 3) && N % 256)) return SV_EUNSUPPORTED;
   return mfma_gemm(g, (hipStream_t)stream, tile) == hipSuccess ? SV_OK : SV_EHIP;
 }
 

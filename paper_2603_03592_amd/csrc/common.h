@@ -140,6 +140,8 @@ hipError_t plain_attn_fwd(const void* qkv, int64_t ld, void* o, float* lse, int 
 hipError_t plain_attn_bwd(const void* qkv, int64_t ld, const void* o, const void* dout, const float* lse, float* delta,
                           void* dqkv, int B, int S, int H, int Hkv, int hd, int causal, int dtype, hipStream_t st);
 
+hipError_t plain_transpose(const void* src, void* dst, int R, int C, int dtype, hipStream_t st);
+
 // gemm_mfma.hip: bf16 only; returns hipErrorInvalidValue if the shape is outside its limits
 bool mfma_gemm_supported(const GemmArgs& a);
 hipError_t mfma_gemm(const GemmArgs& a, hipStream_t st, int tile = 0);   // tile: 0 auto, 1 = 256x256, 2 = 128x128

@@ -262,6 +262,181 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(GemmA
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// 256x256x64 NT kernel with direct global->LDS loads (global_load_lds, 16 bytes per lane).
+//
+// Each wave instruction copies 64 x 16 bytes to one contiguous 1 KB block of LDS = 8 tile rows;
+// the XOR swizzle is applied by choosing WHICH global chunk each lane fetches, so the LDS image
+// is the same swizzled layout the fragment reads expect and no VGPR staging or ds_write is
+// needed.  Two LDS stages; the 16 loads a wave owes for slice k+1 are issued two at a time
+// between groups of four MFMAs during the first half of slice k (an issue burst would idle the
+// matrix pipe: one wave per SIMD), and fragment reads for the next 16-wide k step are
+// interleaved the same way, double buffered in registers.  The loop is rotated so that the one
+// full wait + barrier per slice sits at the loop top: after it the compiler's counter tracking
+// is exact and no other wait stalls the MFMA stream.
+template <int EPI>
+__global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tiles_m, int tiles_n) {
+  constexpr bool DUAL = EPI == EPI_SWIGLU;
+  constexpr int BM = 256, BN = 256, STAGE = (BM + BN) * 128, MI = 4, NI = 4;
+  constexpr int NOUT = DUAL ? 128 : 256;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+
+  const int nblk = tiles_m * tiles_n;
+  const int per_xcd = (nblk + 7) >> 3;
+  const int pid = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (pid >= nblk) return;
+  const int in_group = kGroupM * tiles_n;
+  const int first_m = (pid / in_group) * kGroupM;
+  const int gsz = min(tiles_m - first_m, kGroupM);
+  const int tile_m = first_m + (pid % in_group) % gsz;
+  const int tile_n = (pid % in_group) / gsz;
+  const int m0 = tile_m * BM, n0 = tile_n * NOUT;
+
+  const int tid = threadIdx.x, lane = tid & 63, l31 = lane & 31, lhi = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), wm = wave & 1, wn = wave >> 1;
+
+  // ---- DMA side: slice being fetched = (dseg, dk); a wave owns 8 row groups of each operand
+  int dseg = 0, dk = 0;
+  const char *gA, *gB, *gB2;
+  unsigned voffA[8], voffB[8];
+  auto set_segment = [&]() {
+    const GemmSeg& sg = a.seg[dseg];
+    gA = (const char*)((const bf16*)sg.A + (int64_t)m0 * sg.lda);
+    gB = (const char*)((const bf16*)sg.B + (int64_t)n0 * sg.ldb);
+    gB2 = DUAL ? (const char*)((const bf16*)a.B2 + (int64_t)n0 * a.ldb2) : gB;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int r = (wave + 4 * i) * 8 + (lane >> 3), c = (lane & 7) ^ swz(r);
+      const int ra = min(r, a.M - 1 - m0);                    // ragged row tail: re-read the last row
+      voffA[i] = (unsigned)((int64_t)ra * sg.lda + c * 8) * 2u;
+      if (DUAL) voffB[i] = (unsigned)((int64_t)(r & 127) * (i >= 4 ? a.ldb2 : sg.ldb) + c * 8) * 2u;
+      else voffB[i] = (unsigned)((int64_t)r * sg.ldb + c * 8) * 2u;
+    }
+  };
+  auto dma = [&](int stage, int j) {                          // j: 0..7 activation rows, 8..15 weight rows
+    const int i = j & 7;
+    const char* g = (j < 8 ? gA : ((DUAL && i >= 4) ? gB2 : gB)) + (int64_t)dk * 2;
+    const unsigned off = j < 8 ? voffA[i] : voffB[i];
+    char* dst = smem + stage * STAGE + (j < 8 ? 0 : BM * 128) + (wave + 4 * i) * 1024;
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(g + off),
+                                     (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+  };
+  auto advance = [&]() {
+    dk += BK;
+    if (dk >= a.seg[dseg].K && dseg + 1 < a.nseg) { dk = 0; ++dseg; set_segment(); }
+  };
+
+  int nslices = 0;
+  for (int s = 0; s < a.nseg; ++s) nslices += a.seg[s].K / BK;
+
+  int xrow[MI], wrow[NI];
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi) xrow[mi] = wm * 128 + mi * 32 + l31;
+#pragma unroll
+  for (int ni = 0; ni < NI; ++ni) wrow[ni] = (DUAL ? (ni < 2 ? wn * 64 + ni * 32 : 128 + wn * 64 + (ni - 2) * 32) : wn * 128 + ni * 32) + l31;
+
+  f32x16 acc[NI][MI];
+#pragma unroll
+  for (int i = 0; i < NI; ++i)
+#pragma unroll
+    for (int j = 0; j < MI; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+#define SV_SB __builtin_amdgcn_sched_barrier(0)
+  // One 16-wide k step: MFMAs on (xc, wc); fragments (rstage, rkk) are read into (xn, wn_) and the
+  // DMAs [d0, d0 + 8) of slice `dstage` are issued, both spread over the four MFMA groups.
+  auto step = [&](bf16x8 (&xc)[MI], bf16x8 (&wc)[NI], bf16x8 (&xn)[MI], bf16x8 (&wn_)[NI], bool do_read, int rstage, int rkk,
+                  bool do_dma, int dstage, int d0) {
+    const char* xs = smem + rstage * STAGE;
+    const char* ws = xs + BM * 128;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      if (do_read) {
+        xn[g] = *reinterpret_cast<const bf16x8*>(xs + lds_off(xrow[g], rkk * 2 + lhi));
+        wn_[g] = *reinterpret_cast<const bf16x8*>(ws + lds_off(wrow[g], rkk * 2 + lhi));
+      }
+      if (do_dma) { dma(dstage, d0 + 2 * g); dma(dstage, d0 + 2 * g + 1); }
+      SV_SB;
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi) acc[g][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wc[g], xc[mi], acc[g][mi], 0, 0, 0);
+      SV_SB;
+    }
+  };
+
+  bf16x8 xf0[MI], wf0[NI], xf1[MI], wf1[NI];
+  set_segment();
+#pragma unroll
+  for (int j = 0; j < 16; ++j) dma(0, j);
+  advance();
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
+  if (nslices > 1) {
+#pragma unroll
+    for (int j = 0; j < 16; ++j) dma(1, j);
+    advance();
+  }
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    xf0[g] = *reinterpret_cast<const bf16x8*>(smem + lds_off(xrow[g], lhi));
+    wf0[g] = *reinterpret_cast<const bf16x8*>(smem + BM * 128 + lds_off(wrow[g], lhi));
+  }
+  step(xf0, wf0, xf1, wf1, true, 0, 1, false, 0, 0);
+  step(xf1, wf1, xf0, wf0, true, 0, 2, false, 0, 0);
+  step(xf0, wf0, xf1, wf1, true, 0, 3, false, 0, 0);
+  for (int kt = 1; kt < nslices; ++kt) {
+    const int st = kt & 1;
+    __builtin_amdgcn_s_waitcnt(0);     // my DMAs of slice kt have landed, my fragment reads of slice kt-1 are done
+    __syncthreads();                   // ... and so have everybody's: stage st is complete, stage st^1 is free
+    SV_SB;
+    const bool more = kt + 1 < nslices;
+    step(xf1, wf1, xf0, wf0, true, st, 0, more, st ^ 1, 0);     // MFMAs of (kt-1, k step 3)
+    step(xf0, wf0, xf1, wf1, true, st, 1, more, st ^ 1, 8);
+    if (more) advance();
+    step(xf1, wf1, xf0, wf0, true, st, 2, false, 0, 0);
+    step(xf0, wf0, xf1, wf1, true, st, 3, false, 0, 0);
+  }
+  step(xf1, wf1, xf0, wf0, false, 0, 0, false, 0, 0);
+#undef SV_SB
+
+  constexpr int NIO = DUAL ? 2 : 4;
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi) {
+    const int m = m0 + wm * 128 + mi * 32 + l31;
+    if (m >= a.M) continue;
+#pragma unroll
+    for (int ni = 0; ni < NIO; ++ni) {
+      const int nb = n0 + wn * (DUAL ? 64 : 128) + ni * 32 + lhi * 4;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        float v[4], u[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          v[i] = acc[ni][mi][q * 4 + i];
+          u[i] = DUAL ? acc[ni + NIO][mi][q * 4 + i] : 0.0f;
+        }
+        epilogue4<EPI>(a, m, nb + q * 8, v, u);
+      }
+    }
+  }
+}
+
+template <int EPI>
+hipError_t launch_dma(const GemmArgs& a, hipStream_t st) {
+  auto kern = gemm_mfma_dma_kernel<EPI>;
+  constexpr int lds = 2 * 512 * 128;
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  const int tiles_m = (a.M + 255) / 256, tiles_n = a.N / (EPI == EPI_SWIGLU ? 128 : 256);
+  const int per_xcd = (tiles_m * tiles_n + 7) / 8;
+  hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(256), lds, st, a, tiles_m, tiles_n);
+  return hipGetLastError();
+}
+
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool KN, int EPI>
 hipError_t launch_cfg(const GemmArgs& a, hipStream_t st) {
   using C = Cfg<BM, BN, WAVES_M, WAVES_N, KN, EPI == EPI_SWIGLU>;
@@ -295,8 +470,8 @@ bool mfma_gemm_supported(const GemmArgs& a) {
   if (a.M < 1 || a.nseg < 1 || a.nseg > 3) return false;
   const bool dual = a.epi == EPI_SWIGLU;
   if (dual && (a.b_is_kn || a.nseg != 1 || !a.B2 || a.ldb2 % 8 || !aligned16(a.B2))) return false;
-  if (a.b_is_kn ? (a.epi != EPI_STORE && a.epi != EPI_SWIGLU_BWD && a.epi != EPI_GELU_BWD)
-                : (a.epi != EPI_STORE && a.epi != EPI_RESID && a.epi != EPI_GELU && a.epi != EPI_SWIGLU)) return false;
+  if (a.epi < EPI_STORE || a.epi > EPI_GELU_BWD) return false;
+  if (a.b_is_kn && (a.epi == EPI_RESID || a.epi == EPI_GELU || a.epi == EPI_SWIGLU)) return false;
   if ((a.epi == EPI_RESID || a.epi == EPI_SWIGLU_BWD || a.epi == EPI_GELU_BWD) && !a.R) return false;
   if (a.epi == EPI_SWIGLU_BWD && (!a.R2 || !a.C2)) return false;
   if (a.N % (dual ? 64 : 128)) return false;
@@ -312,14 +487,32 @@ bool mfma_gemm_supported(const GemmArgs& a) {
 
 hipError_t mfma_gemm(const GemmArgs& a, hipStream_t st, int tile) {
   if (!mfma_gemm_supported(a)) return hipErrorInvalidValue;
-  if (tile == 1 && a.N % (a.epi == EPI_SWIGLU ? 128 : 256)) return hipErrorInvalidValue;
-  const bool big = tile == 1 || (tile == 0 && use_big_tile(a));
+  if ((tile == 1 || tile == 3) && a.N % (a.epi == EPI_SWIGLU ? 128 : 256)) return hipErrorInvalidValue;
+  const bool big = tile == 1 || tile == 3 || (tile == 0 && use_big_tile(a));
+  if (!a.b_is_kn && big && tile != 3) {
+    // the DMA offsets are 32-bit byte offsets within a 256-row panel
+    bool fits = true;
+    for (int s = 0; s < a.nseg; ++s) fits = fits && 256 * a.seg[s].lda * 2 < (int64_t)1 << 32 && 256 * a.seg[s].ldb * 2 < (int64_t)1 << 32;
+    if (fits) {
+      switch (a.epi) {
+        case EPI_STORE: return launch_dma<EPI_STORE>(a, st);
+        case EPI_RESID: return launch_dma<EPI_RESID>(a, st);
+        case EPI_GELU: return launch_dma<EPI_GELU>(a, st);
+        case EPI_SWIGLU: return launch_dma<EPI_SWIGLU>(a, st);
+        case EPI_SWIGLU_BWD: return launch_dma<EPI_SWIGLU_BWD>(a, st);
+        case EPI_GELU_BWD: return launch_dma<EPI_GELU_BWD>(a, st);
+        default: return hipErrorInvalidValue;
+      }
+    }
+  }
   if (!a.b_is_kn) {
     switch (a.epi) {
       case EPI_STORE: return big ? launch_cfg<256, 256, 2, 2, false, EPI_STORE>(a, st) : launch_cfg<128, 128, 2, 2, false, EPI_STORE>(a, st);
       case EPI_RESID: return big ? launch_cfg<256, 256, 2, 2, false, EPI_RESID>(a, st) : launch_cfg<128, 128, 2, 2, false, EPI_RESID>(a, st);
       case EPI_GELU: return big ? launch_cfg<256, 256, 2, 2, false, EPI_GELU>(a, st) : launch_cfg<128, 128, 2, 2, false, EPI_GELU>(a, st);
       case EPI_SWIGLU: return big ? launch_cfg<256, 256, 2, 2, false, EPI_SWIGLU>(a, st) : launch_cfg<128, 128, 2, 2, false, EPI_SWIGLU>(a, st);
+      case EPI_SWIGLU_BWD: return big ? launch_cfg<256, 256, 2, 2, false, EPI_SWIGLU_BWD>(a, st) : launch_cfg<128, 128, 2, 2, false, EPI_SWIGLU_BWD>(a, st);
+      case EPI_GELU_BWD: return big ? launch_cfg<256, 256, 2, 2, false, EPI_GELU_BWD>(a, st) : launch_cfg<128, 128, 2, 2, false, EPI_GELU_BWD>(a, st);
       default: return hipErrorInvalidValue;
     }
   }

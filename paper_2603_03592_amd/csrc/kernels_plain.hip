@@ -381,7 +381,29 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_plain_kernel(const E* __rest
   }
 }
 
+// ------------------------------------------------------------------------------------ transpose
+// dst[c][r] = src[r][c] for a row-major [R, C] matrix: 64x64 tiles through LDS (row pitch 65).
+template <typename E>
+__global__ __launch_bounds__(256) void transpose_kernel(const E* __restrict__ src, E* __restrict__ dst, int R, int C) {
+  __shared__ E tile[64][65];
+  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int i = ty; i < 64; i += 4)
+    if (r0 + i < R && c0 + tx < C) tile[i][tx] = src[(int64_t)(r0 + i) * C + c0 + tx];
+  __syncthreads();
+  for (int i = ty; i < 64; i += 4)
+    if (c0 + i < C && r0 + tx < R) dst[(int64_t)(c0 + i) * R + r0 + tx] = tile[tx][i];
+}
+
 }  // namespace
+
+hipError_t plain_transpose(const void* src, void* dst, int R, int C, int dtype, hipStream_t st) {
+  if (R <= 0 || C <= 0) return hipSuccess;
+  const dim3 grid((C + 63) / 64, (R + 63) / 64), block(256);
+  if (dtype == SV_BF16) hipLaunchKernelGGL(transpose_kernel<bf16>, grid, block, 0, st, (const bf16*)src, (bf16*)dst, R, C);
+  else hipLaunchKernelGGL(transpose_kernel<float>, grid, block, 0, st, (const float*)src, (float*)dst, R, C);
+  return hipGetLastError();
+}
 
 // ------------------------------------------------------------------------------------ launchers
 hipError_t plain_gemm(const GemmArgs& a, int dtype, hipStream_t st) {

@@ -1,0 +1,149 @@
+"""GPU parity at the benchmark configurations' full sizes, in the launch configuration bench.py
+times (same context limits, same kernels): recomputed activations / gradients against the CPU
+oracle, and the flag decisions for the configurations' claim mixes.
+
+The oracle needs roughly 1 s (Small) to 90 s (Large) per distinct micro-batch on the GPU machine's
+host cores, so each configuration uses few distinct micro-batches and manufactures all of its
+submissions from the oracle's output for those:
+  Small  : 8 micro-batches x 8 submissions = 64 (10 % scaled x1.5, 10 % sign-flipped on 5 % of channels)
+  Medium : 1 micro-batch, forward + backward; 10 gradient submissions, 2 corrupted (zeroed / noise)
+  Large  : 1 micro-batch; 32 submissions, 8 corrupted on 1 % of the tokens only
+  Sweep  : the S=512, B=1 point, forward + backward
+"""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+import stage_inputs as si
+from oracle import stage_oracle as so
+from gpu_util import dev, dev_weights, host, rel_l2
+
+
+def _flag_check(res, claim, ref, tau, expect_bad, tag):
+    want = so.scores(claim, ref)["rel_l2"]
+    assert so.flag({"rel_l2": want}, {"rel_l2": tau}) == expect_bad, (tag, want)
+    if abs(want / tau - 1.0) > 0.05:                       # bit-exact outside the +-5 % band
+        assert bool(res["flag"]) == expect_bad, (tag, res, want)
+    return want
+
+
+def test_small_config_64_submissions():
+    import paper_2603_03592_amd as sv
+    wl = si.SMALL
+    w = si.make_weights(wl.desc, 0)
+    ver = sv.Verifier(wl.desc, wl.batch * wl.seq, wl.seq)
+    wd = dev_weights(w, "bf16")
+    wc = ver.pack_weights(wd)
+    kinds = si.small_claim_plan(64, seed=0)
+    assert kinds.count("scale") == 6 and kinds.count("sign") == 6
+    worst_honest, n = 0.0, 0
+    for mb in range(8):
+        h = si.make_activations(wl.desc, wl.batch, wl.seq, seed=0, micro_batch=mb)
+        ref = so.stage_forward(h, w, wl.desc)
+        hd = dev(h, "bf16")
+        out = ver.verify_forward(wc, hd, want_h_hat=True)
+        got = host(out["h_hat"])
+        assert rel_l2(got, ref) <= 2e-2 and np.max(so.token_rel_l2(got, ref)) <= 2e-2
+        for j in range(8):
+            kind = kinds[mb * 8 + j]
+            claim = si.make_claim(kind, ref, "bf16", seed=mb * 8 + j)
+            res = ver.read_results(ver.verify_forward(wc, hd, dev(claim, "bf16"), tau={"rel_l2": wl.tau})["result"])[0]
+            _flag_check(res, claim, ref, wl.tau, kind != "honest", (mb, j, kind))
+            if kind == "honest":
+                worst_honest = max(worst_honest, float(res["score"][0]))
+            n += 1
+    assert n == 64
+    assert worst_honest < 0.95 * wl.tau, worst_honest        # honest submissions keep clear of the band
+    print(f"small: worst honest per-token score {worst_honest:.3e} (tau {wl.tau})")
+    ver.close()
+
+
+def test_medium_config_forward_backward():
+    import paper_2603_03592_amd as sv
+    wl = si.MEDIUM
+    w = si.make_weights(wl.desc, 0)
+    h = si.make_activations(wl.desc, wl.batch, wl.seq, seed=0)
+    g = si.make_output_grad(wl.desc, wl.batch, wl.seq, seed=0)
+    ref_h, ref_g = so.stage_backward(h, g, w, wl.desc)
+    ver = sv.Verifier(wl.desc, wl.batch * wl.seq, wl.seq, backward=True)
+    wd = dev_weights(w, "bf16")
+    wc = ver.pack_weights(wd)
+    hd, gd = dev(h, "bf16"), dev(g, "bf16")
+    out = ver.verify_backward(wc, hd, gd, want_g_hat=True, want_h_hat=True)
+    gh, gg = host(out["h_hat"]), host(out["g_hat"])
+    assert rel_l2(gh, ref_h) <= 2e-2 and np.max(so.token_rel_l2(gh, ref_h)) <= 2e-2
+    assert rel_l2(gg, ref_g) <= 2e-2
+    print(f"medium: rel-L2 h {rel_l2(gh, ref_h):.3e} g {rel_l2(gg, ref_g):.3e} worst token g {np.max(so.token_rel_l2(gg, ref_g)):.3e}")
+    # activation gradients are three orders of magnitude smaller than activations
+    assert np.sqrt(np.mean(ref_g ** 2)) < 1e-2 * np.sqrt(np.mean(ref_h ** 2))
+    kinds = ["honest"] * 10
+    kinds[3], kinds[7] = "zero", "noise"
+    for i, kind in enumerate(kinds):
+        claim = si.make_claim(kind, ref_g, "bf16", seed=i)
+        res = ver.read_results(ver.verify_backward(wc, hd, gd, dev(claim, "bf16"), tau={"rel_l2": wl.tau})["result"])[0]
+        _flag_check(res, claim, ref_g, wl.tau, kind != "honest", (i, kind))
+        if kind == "honest":
+            assert res["score"][0] < 0.95 * wl.tau, res
+    claim = si.make_claim("honest", ref_h, "bf16", 0)
+    res = ver.read_results(ver.verify_forward(wc, hd, dev(claim, "bf16"), tau={"rel_l2": wl.tau})["result"])[0]
+    _flag_check(res, claim, ref_h, wl.tau, False, "h honest")
+    ver.close()
+
+
+def test_large_config_32_submissions_token_corruption():
+    import paper_2603_03592_amd as sv
+    wl = si.LARGE
+    w = si.make_weights(wl.desc, 0)
+    h = si.make_activations(wl.desc, wl.batch, wl.seq, seed=0)
+    ref = so.stage_forward(h, w, wl.desc)
+    ver = sv.Verifier(wl.desc, wl.batch * wl.seq, wl.seq)
+    wd = dev_weights(w, "bf16")
+    wc = ver.pack_weights(wd)
+    hd = dev(h, "bf16")
+    got = host(ver.verify_forward(wc, hd, want_h_hat=True)["h_hat"])
+    tok = so.token_rel_l2(got, ref)
+    print(f"large: rel-L2 {rel_l2(got, ref):.3e} worst token {tok.max():.3e}")
+    assert rel_l2(got, ref) <= 2e-2 and tok.max() <= 2e-2
+    bad_kinds = ["tok_noise", "tok_scale", "tok_neg", "tok_zero"]
+    kinds = ["honest"] * 32
+    for i, slot in enumerate(range(1, 32, 4)):             # 8 of 32 corrupted
+        kinds[slot] = bad_kinds[i % 4]
+    worst_honest = 0.0
+    for i, kind in enumerate(kinds):
+        claim = si.make_claim(kind, ref, "bf16", seed=i)
+        out = ver.verify_forward(wc, hd, dev(claim, "bf16"), tau={"rel_l2": wl.tau}, want_token_scores=True)
+        res = ver.read_results(out["result"])[0]
+        _flag_check(res, claim, ref, wl.tau, kind != "honest", (i, kind))
+        if kind == "honest":
+            worst_honest = max(worst_honest, float(res["score"][0]))
+        else:
+            # only the corrupted 1 % of the tokens stand out
+            ts = host(out["token_scores"])
+            n_bad = int(np.sum(ts > wl.tau))
+            assert n_bad == 82, (kind, n_bad)
+    assert worst_honest < 0.95 * wl.tau, worst_honest
+    print(f"large: worst honest per-token score {worst_honest:.3e} (tau {wl.tau})")
+    ver.close()
+
+
+def test_sweep_point_forward_backward():
+    import paper_2603_03592_amd as sv
+    wl = si.sweep_point(512, 1)
+    w = si.make_weights(wl.desc, 1)
+    h = si.make_activations(wl.desc, wl.batch, wl.seq, seed=1)
+    g = si.make_output_grad(wl.desc, wl.batch, wl.seq, seed=1)
+    ref_h, ref_g = so.stage_backward(h, g, w, wl.desc)
+    ver = sv.Verifier(wl.desc, wl.batch * wl.seq, wl.seq, backward=True)
+    wd = dev_weights(w, "bf16")
+    wc = ver.pack_weights(wd)
+    out = ver.verify_backward(wc, dev(h, "bf16"), dev(g, "bf16"), want_g_hat=True, want_h_hat=True)
+    assert rel_l2(host(out["h_hat"]), ref_h) <= 2e-2
+    assert rel_l2(host(out["g_hat"]), ref_g) <= 2e-2
+    # 128 concurrent submissions scored in one call against the recomputation (shared reference)
+    import torch
+    kinds = (["honest"] * 5 + ["noise", "scale", "sign"]) * 16
+    claims = torch.stack([dev(si.make_claim(k, ref_h, "bf16", i), "bf16") for i, k in enumerate(kinds)])
+    res = ver.read_results(ver.score_and_flag(claims, out["h_hat"], tau={"rel_l2": wl.tau})["result"])
+    assert [int(f) for f in res["flag"]] == [int(k != "honest") for k in kinds]
+    ver.close()
