@@ -211,6 +211,13 @@ hipError_t attn_fwd(sv_ctx* c, const void* qkv, void* o, float* lse, int B, int 
   return plain_attn_fwd(qkv, c->Dqkv, o, lse, B, S, d.n_heads, d.n_kv_heads, c->hd, d.causal, d.dtype, st);
 }
 
+hipError_t attn_bwd(sv_ctx* c, const BlockStash& k, int B, int S, hipStream_t st) {
+  const sv_stage_desc& d = c->d;
+  if (d.dtype == SV_BF16 && !(c->flags & SV_FLAG_PLAIN_KERNELS) && mfma_attn_supported(S, d.n_heads, d.n_kv_heads, c->hd, c->Dqkv))
+    return mfma_attn_bwd(k.qkv, c->Dqkv, k.o, c->dout, k.lse, c->delta, c->dqkv, B, S, d.n_heads, d.n_kv_heads, c->hd, d.causal, st);
+  return plain_attn_bwd(k.qkv, c->Dqkv, k.o, c->dout, k.lse, c->delta, c->dqkv, B, S, d.n_heads, d.n_kv_heads, c->hd, d.causal, d.dtype, st);
+}
+
 GemmArgs nt(int M, int N, int K, const void* A, int64_t lda, const void* W, void* C, int64_t ldc, int epi) {
   GemmArgs g; memset(&g, 0, sizeof(g));
   g.M = M; g.N = N; g.nseg = 1; g.seg[0] = GemmSeg{A, lda, W, (int64_t)K, K};
@@ -320,7 +327,7 @@ sv_status block_backward(sv_ctx* c, const sv_block_weights& w, const void* x, co
     seg(g, c->dx1, D, w.wo, c->woT, D, c->Dq);
     SV_OP(c, SV_OP_BWD_GEMM_DO, 2.0 * Td * D * c->Dq, st, gemm(c, g, st));
   }
-  SV_OP(c, SV_OP_BWD_ATTN, 2.5 * attn_flop, st, plain_attn_bwd(k.qkv, c->Dqkv, k.o, c->dout, k.lse, c->delta, c->dqkv, B, S, d.n_heads, d.n_kv_heads, c->hd, d.causal, dt, st));
+  SV_OP(c, SV_OP_BWD_ATTN, 2.5 * attn_flop, st, attn_bwd(c, k, B, S, st));
   if (d.rope) SV_OP(c, SV_OP_BWD_ROPE, 0, st, plain_rope(c->dqkv, c->Dqkv, T, S, d.n_heads, d.n_kv_heads, c->hd, c->rope_cs, 1, dt, st));
   {
     GemmArgs g = args(D, c->dn, D, EPI_STORE);                   // dn1 = dq Wq + dk Wk + dv Wv

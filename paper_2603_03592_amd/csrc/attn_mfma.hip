@@ -190,6 +190,333 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16* __restri
   }
 }
 
+
+// ------------------------------------------------------------------------------------------
+// Backward.  With P = softmax(S), dP = dO V^T, dS = P o (dP - delta), delta_i = sum_d dO_id O_id:
+//   dQ = dS K / sqrt(hd),  dK = dS^T Q / sqrt(hd),  dV = P^T dO.
+// Two kernels, no atomics (results are run-to-run identical):
+//   dq kernel : one workgroup per 128 queries, walks the key tiles like the forward.  S^T and
+//               dP^T = V dO^T are formed with keys in the MFMA row dimension so that lse and
+//               delta are per-lane scalars; dS^T feeds dQ^T += K^T dS^T from registers (K is
+//               also kept transposed in LDS, same key order trick as V in the forward).
+//   dkv kernel: one workgroup per 128 keys of a kv head, walks the query tiles of every query
+//               head of the group.  Here S = Q K^T and dP = dO V^T are formed with QUERIES in
+//               the row dimension, so each lane owns a key column and P, dS feed
+//               dV^T += dO^T P and dK^T += Q^T dS from registers; Q and dO are staged in LDS
+//               both row-major and transposed.
+// Staging pattern shared by both: a thread loads 4 consecutive rows x 8 features (4 x 16 bytes),
+// writes them row-major as they are and transposed as 8 x 8-byte pieces.
+
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
+
+// row-major tile: rows of HD bf16, 16-byte chunks swizzled by the row
+template <int HD>
+__device__ __forceinline__ int rm_off(int row, int chunk) { return row * (HD * 2) + (((chunk & ~7) | ((chunk ^ row) & 7)) << 4); }
+// transposed tile: row = feature d (128 bytes = 64 rows of the source, in the MFMA key order), 8-byte piece of source-row quad rq
+__device__ __forceinline__ int tr_off(int d, int rq) {
+  const int g = rq >> 2, qd = rq & 3;
+  return d * 128 + (((2 * g + (qd & 1)) ^ swz8(d)) << 4) + (qd >> 1) * 8;
+}
+__device__ __forceinline__ int tr_frag_off(int d, int g, int half) { return d * 128 + (((2 * g + half) ^ swz8(d)) << 4); }
+
+template <int HD, bool ROWMAJOR, bool TRANSPOSED>
+__device__ __forceinline__ void stage_quad(char* rm, char* tr, const bf16x8 (&reg)[4], int rq, int dg) {
+  if (ROWMAJOR) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) *reinterpret_cast<bf16x8*>(rm + rm_off<HD>(rq * 4 + i, dg)) = reg[i];
+  }
+  if (TRANSPOSED) {
+    u32x4_t in[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) in[i] = __builtin_bit_cast(u32x4_t, reg[i]);
+#pragma unroll
+    for (int dd = 0; dd < 8; ++dd) {
+      const uint32_t sel = (dd & 1) ? 0x07060302u : 0x05040100u;
+      u32x2_t ov;
+      ov[0] = __builtin_amdgcn_perm(in[1][dd >> 1], in[0][dd >> 1], sel);
+      ov[1] = __builtin_amdgcn_perm(in[3][dd >> 1], in[2][dd >> 1], sel);
+      *reinterpret_cast<u32x2_t*>(tr + tr_off(dg * 8 + dd, rq)) = ov;
+    }
+  }
+}
+
+template <int HD, bool CAUSAL>
+__global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16* __restrict__ qkv, int64_t ld, const bf16* __restrict__ o,
+                                                               const bf16* __restrict__ dout, const float* __restrict__ lse,
+                                                               float* __restrict__ delta, bf16* __restrict__ dqkv, int S, int H, int Hkv,
+                                                               float scale) {
+  constexpr int KCH = HD / 8, NKK = HD / 16, NDB = HD / 32;
+  constexpr int TILE = BKV * HD * 2;                 // bytes of one 64-row tile (row-major or transposed)
+  constexpr int STAGE = 3 * TILE;                    // K row-major, V row-major, K transposed
+  constexpr int UNITS = (BKV / 4) * KCH;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int nqt = (S + BQ - 1) / BQ;
+  const int qt = nqt - 1 - (int)blockIdx.x;
+  const int h = blockIdx.y, b = blockIdx.z, kvh = h / (H / Hkv);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l31 = lane & 31, half = lane >> 5;
+  const int q0 = qt * BQ, wq0 = q0 + wave * 32, myq = wq0 + l31;
+  const int Dq = H * HD, Dkv = Hkv * HD;
+  const float c2 = scale * 1.4426950408889634f;
+  const int qrow = min(myq, S - 1);
+  const bf16* kbase = qkv + (int64_t)b * S * ld + Dq + (int64_t)kvh * HD;
+  const bf16* vbase = kbase + Dkv;
+
+  bf16x8 qf[NKK], dof[NKK];
+  float dl = 0.0f;
+  {
+    const bf16* qp = qkv + ((int64_t)b * S + qrow) * ld + (int64_t)h * HD;
+    const bf16* op = o + ((int64_t)b * S + qrow) * Dq + (int64_t)h * HD;
+    const bf16* dp = dout + ((int64_t)b * S + qrow) * Dq + (int64_t)h * HD;
+#pragma unroll
+    for (int kk = 0; kk < NKK; ++kk) {
+      qf[kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16 + half * 8);
+      dof[kk] = *reinterpret_cast<const bf16x8*>(dp + kk * 16 + half * 8);
+      const bf16x8 of = *reinterpret_cast<const bf16x8*>(op + kk * 16 + half * 8);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) dl = fmaf((float)dof[kk][e], (float)of[e], dl);
+    }
+  }
+  dl += __shfl_xor(dl, 32, 64);
+  const int64_t li = ((int64_t)b * H + h) * S + qrow;
+  const float lse2 = lse[li] * 1.4426950408889634f;
+  if (myq < S && half == 0) delta[li] = dl;
+
+  const int nkv = (S + BKV - 1) / BKV;
+  const int ntiles = CAUSAL ? min((q0 + BQ + BKV - 1) / BKV, nkv) : nkv;
+  const bool active = tid < UNITS;
+  const int u_dg = tid % KCH, u_rq = tid / KCH;
+  bf16x8 kreg[4], vreg[4];
+  auto load_tile = [&](int j) {
+    if (!active) return;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int64_t row = min(j * BKV + u_rq * 4 + i, S - 1);
+      kreg[i] = *reinterpret_cast<const bf16x8*>(kbase + row * ld + u_dg * 8);
+      vreg[i] = *reinterpret_cast<const bf16x8*>(vbase + row * ld + u_dg * 8);
+    }
+  };
+  auto store_tile = [&](int stage) {
+    if (!active) return;
+    char* base = smem + stage * STAGE;
+    stage_quad<HD, true, true>(base, base + 2 * TILE, kreg, u_rq, u_dg);
+    stage_quad<HD, true, false>(base + TILE, nullptr, vreg, u_rq, u_dg);
+  };
+
+  f32x16 dq[NDB];
+#pragma unroll
+  for (int i = 0; i < NDB; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dq[i][r] = 0.0f;
+
+  load_tile(0);
+  store_tile(0);
+  __syncthreads();
+  for (int j = 0; j < ntiles; ++j) {
+    const bool more = j + 1 < ntiles;
+    if (more) load_tile(j + 1);
+    const int k0 = j * BKV;
+    if (!CAUSAL || k0 <= wq0 + 31) {
+      const char* ks = smem + (j & 1) * STAGE;
+      const char* vs = ks + TILE;
+      const char* kt = ks + 2 * TILE;
+      f32x16 s[2], dp[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { s[t][r] = 0.0f; dp[t][r] = 0.0f; }
+        const int krow = t * 32 + l31;
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk) {
+          const bf16x8 kf = *reinterpret_cast<const bf16x8*>(ks + rm_off<HD>(krow, kk * 2 + half));
+          const bf16x8 vf = *reinterpret_cast<const bf16x8*>(vs + rm_off<HD>(krow, kk * 2 + half));
+          s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s[t], 0, 0, 0);
+          dp[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, dof[kk], dp[t], 0, 0, 0);
+        }
+      }
+      const bool need_mask = (CAUSAL && k0 + BKV - 1 > wq0) || (k0 + BKV > S);
+      bf16x8 dsf[4];
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float p = __builtin_amdgcn_exp2f(fmaf(s[t][r], c2, -lse2));
+          if (need_mask) {
+            const int key = k0 + t * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+            if ((CAUSAL && key > myq) || key >= S) p = 0.0f;
+          }
+          dsf[t * 2 + (r >> 3)][r & 7] = (bf16)(p * (dp[t][r] - dl));
+        }
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) {
+          const bf16x8 ktf = *reinterpret_cast<const bf16x8*>(kt + tr_frag_off(db * 32 + l31, g, half));
+          dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf, dsf[g], dq[db], 0, 0, 0);
+        }
+    }
+    if (more) store_tile((j + 1) & 1);
+    __syncthreads();
+  }
+  if (myq < S) {
+    bf16* out = dqkv + ((int64_t)b * S + myq) * ld + (int64_t)h * HD;
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        bf16x4 pk;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) pk[i] = (bf16)(dq[db][g4 * 4 + i] * scale);
+        *reinterpret_cast<bf16x4*>(out + db * 32 + g4 * 8 + half * 4) = pk;
+      }
+  }
+}
+
+template <int HD, bool CAUSAL>
+__global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __restrict__ qkv, int64_t ld, const bf16* __restrict__ dout,
+                                                                const float* __restrict__ lse, const float* __restrict__ delta,
+                                                                bf16* __restrict__ dqkv, int S, int H, int Hkv, float scale) {
+  constexpr int KCH = HD / 8, NKK = HD / 16, NDB = HD / 32;
+  constexpr int TILE = 64 * HD * 2;
+  constexpr int STAGE = 4 * TILE + 512;              // Q rm, dO rm, Q^T, dO^T, lse2[64], delta[64]
+  constexpr int UNITS = 16 * KCH;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int kvh = blockIdx.y, b = blockIdx.z, G = H / Hkv;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l31 = lane & 31, half = lane >> 5;
+  const int k0 = blockIdx.x * 128, wk0 = k0 + wave * 32, mykey = wk0 + l31;
+  const int Dq = H * HD, Dkv = Hkv * HD;
+  const float c2 = scale * 1.4426950408889634f;
+  const int krow = min(mykey, S - 1);
+
+  bf16x8 kf[NKK], vf[NKK];
+  {
+    const bf16* kp = qkv + ((int64_t)b * S + krow) * ld + Dq + (int64_t)kvh * HD;
+#pragma unroll
+    for (int kk = 0; kk < NKK; ++kk) {
+      kf[kk] = *reinterpret_cast<const bf16x8*>(kp + kk * 16 + half * 8);
+      vf[kk] = *reinterpret_cast<const bf16x8*>(kp + Dkv + kk * 16 + half * 8);
+    }
+  }
+  const int qstart = CAUSAL ? (k0 / 64) * 64 : 0;
+  const int nq = (S - qstart + 63) / 64;             // query tiles per head
+  const int ntiles = nq * G;
+  const bool active = tid < UNITS;
+  const int u_dg = tid % KCH, u_rq = tid / KCH;
+  bf16x8 qreg[4], dreg[4];
+  float lreg = 0.0f, dlreg = 0.0f;
+  auto load_tile = [&](int j) {
+    const int h = kvh * G + j / nq, q0 = qstart + (j % nq) * 64;
+    if (active) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int64_t tok = (int64_t)b * S + min(q0 + u_rq * 4 + i, S - 1);
+        qreg[i] = *reinterpret_cast<const bf16x8*>(qkv + tok * ld + (int64_t)h * HD + u_dg * 8);
+        dreg[i] = *reinterpret_cast<const bf16x8*>(dout + tok * Dq + (int64_t)h * HD + u_dg * 8);
+      }
+    }
+    if (tid < 64) {
+      const int64_t li = ((int64_t)b * H + h) * S + min(q0 + tid, S - 1);
+      lreg = lse[li] * 1.4426950408889634f;
+      dlreg = delta[li];
+    }
+  };
+  auto store_tile = [&](int stage) {
+    char* base = smem + stage * STAGE;
+    if (active) {
+      stage_quad<HD, true, true>(base, base + 2 * TILE, qreg, u_rq, u_dg);
+      stage_quad<HD, true, true>(base + TILE, base + 3 * TILE, dreg, u_rq, u_dg);
+    }
+    if (tid < 64) {
+      reinterpret_cast<float*>(base + 4 * TILE)[tid] = lreg;
+      reinterpret_cast<float*>(base + 4 * TILE + 256)[tid] = dlreg;
+    }
+  };
+
+  f32x16 dk[NDB], dv[NDB];
+#pragma unroll
+  for (int i = 0; i < NDB; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { dk[i][r] = 0.0f; dv[i][r] = 0.0f; }
+
+  if (ntiles > 0) {
+    load_tile(0);
+    store_tile(0);
+  }
+  __syncthreads();
+  for (int j = 0; j < ntiles; ++j) {
+    const bool more = j + 1 < ntiles;
+    if (more) load_tile(j + 1);
+    const int q0 = qstart + (j % nq) * 64;
+    if (!CAUSAL || q0 + 63 >= wk0) {
+      const char* qs = smem + (j & 1) * STAGE;
+      const char* ds_ = qs + TILE;
+      const char* qt = qs + 2 * TILE;
+      const char* dt = qs + 3 * TILE;
+      const float* ls = reinterpret_cast<const float*>(qs + 4 * TILE);
+      const float* dls = ls + 64;
+      f32x16 s[2], dp[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { s[t][r] = 0.0f; dp[t][r] = 0.0f; }
+        const int row = t * 32 + l31;
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk) {
+          const bf16x8 qf = *reinterpret_cast<const bf16x8*>(qs + rm_off<HD>(row, kk * 2 + half));
+          const bf16x8 df = *reinterpret_cast<const bf16x8*>(ds_ + rm_off<HD>(row, kk * 2 + half));
+          s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kf[kk], s[t], 0, 0, 0);
+          dp[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(df, vf[kk], dp[t], 0, 0, 0);
+        }
+      }
+      const bool need_mask = (CAUSAL && q0 < wk0 + 31) || (q0 + 64 > S);
+      bf16x8 pf[4], dsf[4];
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const int qq = t * 32 + 8 * r4 + 4 * half;           // 4 consecutive queries of this register quad
+          const f32x4 l4 = *reinterpret_cast<const f32x4*>(ls + qq);
+          const f32x4 d4 = *reinterpret_cast<const f32x4*>(dls + qq);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int r = r4 * 4 + i;
+            float p = __builtin_amdgcn_exp2f(fmaf(s[t][r], c2, -l4[i]));
+            if (need_mask) {
+              const int q = q0 + qq + i;
+              if ((CAUSAL && q < mykey) || q >= S) p = 0.0f;
+            }
+            pf[t * 2 + (r >> 3)][r & 7] = (bf16)p;
+            dsf[t * 2 + (r >> 3)][r & 7] = (bf16)(p * (dp[t][r] - d4[i]));
+          }
+        }
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) {
+          const bf16x8 dtf = *reinterpret_cast<const bf16x8*>(dt + tr_frag_off(db * 32 + l31, g, half));
+          const bf16x8 qtf = *reinterpret_cast<const bf16x8*>(qt + tr_frag_off(db * 32 + l31, g, half));
+          dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dtf, pf[g], dv[db], 0, 0, 0);
+          dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qtf, dsf[g], dk[db], 0, 0, 0);
+        }
+    }
+    if (more) store_tile((j + 1) & 1);
+    __syncthreads();
+  }
+  if (mykey < S) {
+    bf16* out = dqkv + ((int64_t)b * S + mykey) * ld + Dq + (int64_t)kvh * HD;
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        bf16x4 pk, pv;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { pk[i] = (bf16)(dk[db][g4 * 4 + i] * scale); pv[i] = (bf16)dv[db][g4 * 4 + i]; }
+        *reinterpret_cast<bf16x4*>(out + db * 32 + g4 * 8 + half * 4) = pk;
+        *reinterpret_cast<bf16x4*>(out + Dkv + db * 32 + g4 * 8 + half * 4) = pv;
+      }
+  }
+}
+
 }  // namespace
 
 bool mfma_attn_supported(int S, int H, int Hkv, int hd, int64_t ld) {
@@ -216,6 +543,36 @@ hipError_t mfma_attn_fwd(const void* qkv, int64_t ld, void* o, float* lse, int B
   if (hd == 128) { if (causal) SV_ATTN_LAUNCH(128, true); else SV_ATTN_LAUNCH(128, false); }
   else { if (causal) SV_ATTN_LAUNCH(64, true); else SV_ATTN_LAUNCH(64, false); }
 #undef SV_ATTN_LAUNCH
+  return hipGetLastError();
+}
+
+
+hipError_t mfma_attn_bwd(const void* qkv, int64_t ld, const void* o, const void* dout, const float* lse, float* delta, void* dqkv, int B,
+                         int S, int H, int Hkv, int hd, int causal, hipStream_t st) {
+  if (!mfma_attn_supported(S, H, Hkv, hd, ld)) return hipErrorInvalidValue;
+  if (B <= 0) return hipSuccess;
+  const dim3 gq((S + BQ - 1) / BQ, H, B), gk((S + 127) / 128, Hkv, B), block(256);
+  const float scale = 1.0f / sqrtf((float)hd);
+#define SV_ATTN_BWD_LAUNCH(HDV, CZ)                                                                                     \
+  do {                                                                                                                  \
+    auto kq = attn_bwd_dq_mfma_kernel<HDV, CZ>;                                                                         \
+    auto kk = attn_bwd_dkv_mfma_kernel<HDV, CZ>;                                                                        \
+    constexpr int lq = 2 * 3 * (64 * HDV * 2), lk = 2 * (4 * 64 * HDV * 2 + 512);                                       \
+    static bool configured = false;                                                                                     \
+    if (!configured) {                                                                                                  \
+      hipError_t e = hipFuncSetAttribute((const void*)kq, hipFuncAttributeMaxDynamicSharedMemorySize, lq);              \
+      if (e == hipSuccess) e = hipFuncSetAttribute((const void*)kk, hipFuncAttributeMaxDynamicSharedMemorySize, lk);    \
+      if (e != hipSuccess) return e;                                                                                    \
+      configured = true;                                                                                                \
+    }                                                                                                                   \
+    hipLaunchKernelGGL(kq, gq, block, lq, st, (const bf16*)qkv, ld, (const bf16*)o, (const bf16*)dout, lse, delta,      \
+                       (bf16*)dqkv, S, H, Hkv, scale);                                                                  \
+    hipLaunchKernelGGL(kk, gk, block, lk, st, (const bf16*)qkv, ld, (const bf16*)dout, lse, delta, (bf16*)dqkv, S, H,   \
+                       Hkv, scale);                                                                                     \
+  } while (0)
+  if (hd == 128) { if (causal) SV_ATTN_BWD_LAUNCH(128, true); else SV_ATTN_BWD_LAUNCH(128, false); }
+  else { if (causal) SV_ATTN_BWD_LAUNCH(64, true); else SV_ATTN_BWD_LAUNCH(64, false); }
+#undef SV_ATTN_BWD_LAUNCH
   return hipGetLastError();
 }
 

@@ -150,5 +150,7 @@ hipError_t mfma_gemm(const GemmArgs& a, hipStream_t st, int tile = 0);   // tile
 bool mfma_attn_supported(int S, int H, int Hkv, int hd, int64_t ld);
 hipError_t mfma_attn_fwd(const void* qkv, int64_t ld, void* o, float* lse, int B, int S, int H, int Hkv, int hd, int causal,
                          hipStream_t st);
+hipError_t mfma_attn_bwd(const void* qkv, int64_t ld, const void* o, const void* dout, const float* lse, float* delta, void* dqkv,
+                         int B, int S, int H, int Hkv, int hd, int causal, hipStream_t st);
 
 }  // namespace sv
