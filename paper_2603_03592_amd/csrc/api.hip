@@ -211,10 +211,17 @@ hipError_t attn_fwd(sv_ctx* c, const void* qkv, void* o, float* lse, int B, int 
   return plain_attn_fwd(qkv, c->Dqkv, o, lse, B, S, d.n_heads, d.n_kv_heads, c->hd, d.causal, d.dtype, st);
 }
 
+bool attn_on_mfma(const sv_ctx* c, int S) {
+  const sv_stage_desc& d = c->d;
+  return d.dtype == SV_BF16 && !(c->flags & SV_FLAG_PLAIN_KERNELS) && mfma_attn_supported(S, d.n_heads, d.n_kv_heads, c->hd, c->Dqkv);
+}
+
+// the MFMA kernels also undo RoPE on dq, dk; the plain ones leave that to a separate pass
 hipError_t attn_bwd(sv_ctx* c, const BlockStash& k, int B, int S, hipStream_t st) {
   const sv_stage_desc& d = c->d;
-  if (d.dtype == SV_BF16 && !(c->flags & SV_FLAG_PLAIN_KERNELS) && mfma_attn_supported(S, d.n_heads, d.n_kv_heads, c->hd, c->Dqkv))
-    return mfma_attn_bwd(k.qkv, c->Dqkv, k.o, c->dout, k.lse, c->delta, c->dqkv, B, S, d.n_heads, d.n_kv_heads, c->hd, d.causal, st);
+  if (attn_on_mfma(c, S))
+    return mfma_attn_bwd(k.qkv, c->Dqkv, k.o, c->dout, k.lse, c->delta, c->dqkv, B, S, d.n_heads, d.n_kv_heads, c->hd, d.causal,
+                         d.rope ? c->rope_cs : nullptr, st);
   return plain_attn_bwd(k.qkv, c->Dqkv, k.o, c->dout, k.lse, c->delta, c->dqkv, B, S, d.n_heads, d.n_kv_heads, c->hd, d.causal, d.dtype, st);
 }
 
@@ -236,10 +243,20 @@ sv_status block_forward(sv_ctx* c, const sv_block_weights& w, const void* x, voi
 
   const double Td = T, attn_flop = (d.causal ? 2.0 : 4.0) * B * d.n_heads * (double)S * S * c->hd;
   SV_OP(c, SV_OP_NORM, 0, st, plain_norm_fwd(x, w.norm1_g, w.norm1_b, c->n, T, D, d.norm, d.norm_eps, dt, st));
-  SV_OP(c, SV_OP_GEMM_QKV, 2.0 * Td * c->Dq * D, st, gemm(c, nt(T, c->Dq, D, c->n, D, w.wq, qkv, c->Dqkv, EPI_STORE), st));
-  SV_OP(c, SV_OP_GEMM_QKV, 2.0 * Td * c->Dkv * D, st, gemm(c, nt(T, c->Dkv, D, c->n, D, w.wk, at(qkv, c->Dq, es), c->Dqkv, EPI_STORE), st));
-  SV_OP(c, SV_OP_GEMM_QKV, 2.0 * Td * c->Dkv * D, st, gemm(c, nt(T, c->Dkv, D, c->n, D, w.wv, at(qkv, c->Dq + c->Dkv, es), c->Dqkv, EPI_STORE), st));
-  if (d.rope) SV_OP(c, SV_OP_ROPE, 0, st, plain_rope(qkv, c->Dqkv, T, S, d.n_heads, d.n_kv_heads, c->hd, c->rope_cs, 0, dt, st));
+  {
+    // one launch over the concatenated [q | k | v] columns with RoPE in the epilogue when the kernel can do it
+    GemmArgs f = nt(T, c->Dqkv, D, c->n, D, w.wq, qkv, c->Dqkv, d.rope ? EPI_ROPE : EPI_STORE);
+    f.nbcol = 3; f.Bcol[0] = w.wq; f.Bcol[1] = w.wk; f.Bcol[2] = w.wv; f.ncol[0] = c->Dq; f.ncol[1] = c->Dkv; f.ncol[2] = c->Dkv;
+    f.rope_cs = c->rope_cs; f.rope_S = S; f.rope_hd = c->hd; f.rope_cols = c->Dq + c->Dkv;
+    if (dt == SV_BF16 && !(c->flags & SV_FLAG_PLAIN_KERNELS) && mfma_gemm_supported(f)) {
+      SV_OP(c, SV_OP_GEMM_QKV, 2.0 * Td * c->Dqkv * D, st, mfma_gemm(f, st));
+    } else {
+      SV_OP(c, SV_OP_GEMM_QKV, 2.0 * Td * c->Dq * D, st, gemm(c, nt(T, c->Dq, D, c->n, D, w.wq, qkv, c->Dqkv, EPI_STORE), st));
+      SV_OP(c, SV_OP_GEMM_QKV, 2.0 * Td * c->Dkv * D, st, gemm(c, nt(T, c->Dkv, D, c->n, D, w.wk, at(qkv, c->Dq, es), c->Dqkv, EPI_STORE), st));
+      SV_OP(c, SV_OP_GEMM_QKV, 2.0 * Td * c->Dkv * D, st, gemm(c, nt(T, c->Dkv, D, c->n, D, w.wv, at(qkv, c->Dq + c->Dkv, es), c->Dqkv, EPI_STORE), st));
+      if (d.rope) SV_OP(c, SV_OP_ROPE, 0, st, plain_rope(qkv, c->Dqkv, T, S, d.n_heads, d.n_kv_heads, c->hd, c->rope_cs, 0, dt, st));
+    }
+  }
   SV_OP(c, SV_OP_ATTN, attn_flop, st, attn_fwd(c, qkv, o, lse, B, S, st));
   {
     GemmArgs g = nt(T, D, c->Dq, o, c->Dq, w.wo, x1, D, EPI_RESID);
@@ -328,7 +345,8 @@ sv_status block_backward(sv_ctx* c, const sv_block_weights& w, const void* x, co
     SV_OP(c, SV_OP_BWD_GEMM_DO, 2.0 * Td * D * c->Dq, st, gemm(c, g, st));
   }
   SV_OP(c, SV_OP_BWD_ATTN, 2.5 * attn_flop, st, attn_bwd(c, k, B, S, st));
-  if (d.rope) SV_OP(c, SV_OP_BWD_ROPE, 0, st, plain_rope(c->dqkv, c->Dqkv, T, S, d.n_heads, d.n_kv_heads, c->hd, c->rope_cs, 1, dt, st));
+  if (d.rope && !attn_on_mfma(c, S))
+    SV_OP(c, SV_OP_BWD_ROPE, 0, st, plain_rope(c->dqkv, c->Dqkv, T, S, d.n_heads, d.n_kv_heads, c->hd, c->rope_cs, 1, dt, st));
   {
     GemmArgs g = args(D, c->dn, D, EPI_STORE);                   // dn1 = dq Wq + dk Wk + dv Wv
     seg(g, c->dqkv, c->Dqkv, w.wq, c->wqT, c->Dq, D);

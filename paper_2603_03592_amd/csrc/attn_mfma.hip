@@ -220,6 +220,18 @@ __device__ __forceinline__ int tr_off(int d, int rq) {
 }
 __device__ __forceinline__ int tr_frag_off(int d, int g, int half) { return d * 128 + (((2 * g + half) ^ swz8(d)) << 4); }
 
+// Inverse RoPE of 4 consecutive features d..d+3 (two pairs) of the token at in-sequence position p:
+// (a, b) -> (a cos + b sin, -a sin + b cos), the transpose of the forward rotation.
+template <int HD>
+__device__ __forceinline__ void unrope4(float (&v)[4], const float* __restrict__ cs, int p, int d) {
+  const f32x4 t = *reinterpret_cast<const f32x4*>(cs + ((int64_t)p * (HD / 2) + (d >> 1)) * 2);
+  const float a0 = v[0], b0 = v[1], a1 = v[2], b1 = v[3];
+  v[0] = a0 * t[0] + b0 * t[1];
+  v[1] = b0 * t[0] - a0 * t[1];
+  v[2] = a1 * t[2] + b1 * t[3];
+  v[3] = b1 * t[2] - a1 * t[3];
+}
+
 template <int HD, bool ROWMAJOR, bool TRANSPOSED>
 __device__ __forceinline__ void stage_quad(char* rm, char* tr, const bf16x8 (&reg)[4], int rq, int dg) {
   if (ROWMAJOR) {
@@ -245,7 +257,7 @@ template <int HD, bool CAUSAL>
 __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16* __restrict__ qkv, int64_t ld, const bf16* __restrict__ o,
                                                                const bf16* __restrict__ dout, const float* __restrict__ lse,
                                                                float* __restrict__ delta, bf16* __restrict__ dqkv, int S, int H, int Hkv,
-                                                               float scale) {
+                                                               float scale, const float* __restrict__ rope_cs) {
   constexpr int KCH = HD / 8, NKK = HD / 16, NDB = HD / 32;
   constexpr int TILE = BKV * HD * 2;                 // bytes of one 64-row tile (row-major or transposed)
   constexpr int STAGE = 3 * TILE;                    // K row-major, V row-major, K transposed
@@ -364,9 +376,13 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16* __res
     for (int db = 0; db < NDB; ++db)
 #pragma unroll
       for (int g4 = 0; g4 < 4; ++g4) {
+        float v[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = dq[db][g4 * 4 + i] * scale;
+        if (rope_cs) unrope4<HD>(v, rope_cs, myq, db * 32 + g4 * 8 + half * 4);
         bf16x4 pk;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) pk[i] = (bf16)(dq[db][g4 * 4 + i] * scale);
+        for (int i = 0; i < 4; ++i) pk[i] = (bf16)v[i];
         *reinterpret_cast<bf16x4*>(out + db * 32 + g4 * 8 + half * 4) = pk;
       }
   }
@@ -375,7 +391,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16* __res
 template <int HD, bool CAUSAL>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __restrict__ qkv, int64_t ld, const bf16* __restrict__ dout,
                                                                 const float* __restrict__ lse, const float* __restrict__ delta,
-                                                                bf16* __restrict__ dqkv, int S, int H, int Hkv, float scale) {
+                                                                bf16* __restrict__ dqkv, int S, int H, int Hkv, float scale,
+                                                                const float* __restrict__ rope_cs) {
   constexpr int KCH = HD / 8, NKK = HD / 16, NDB = HD / 32;
   constexpr int TILE = 64 * HD * 2;
   constexpr int STAGE = 4 * TILE + 512;              // Q rm, dO rm, Q^T, dO^T, lse2[64], delta[64]
@@ -508,9 +525,13 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
     for (int db = 0; db < NDB; ++db)
 #pragma unroll
       for (int g4 = 0; g4 < 4; ++g4) {
+        float v[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = dk[db][g4 * 4 + i] * scale;
+        if (rope_cs) unrope4<HD>(v, rope_cs, mykey, db * 32 + g4 * 8 + half * 4);
         bf16x4 pk, pv;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) { pk[i] = (bf16)(dk[db][g4 * 4 + i] * scale); pv[i] = (bf16)dv[db][g4 * 4 + i]; }
+        for (int i = 0; i < 4; ++i) { pk[i] = (bf16)v[i]; pv[i] = (bf16)dv[db][g4 * 4 + i]; }
         *reinterpret_cast<bf16x4*>(out + db * 32 + g4 * 8 + half * 4) = pk;
         *reinterpret_cast<bf16x4*>(out + Dkv + db * 32 + g4 * 8 + half * 4) = pv;
       }
@@ -548,7 +569,7 @@ hipError_t mfma_attn_fwd(const void* qkv, int64_t ld, void* o, float* lse, int B
 
 
 hipError_t mfma_attn_bwd(const void* qkv, int64_t ld, const void* o, const void* dout, const float* lse, float* delta, void* dqkv, int B,
-                         int S, int H, int Hkv, int hd, int causal, hipStream_t st) {
+                         int S, int H, int Hkv, int hd, int causal, const float* rope_cs, hipStream_t st) {
   if (!mfma_attn_supported(S, H, Hkv, hd, ld)) return hipErrorInvalidValue;
   if (B <= 0) return hipSuccess;
   const dim3 gq((S + BQ - 1) / BQ, H, B), gk((S + 127) / 128, Hkv, B), block(256);
@@ -566,9 +587,9 @@ hipError_t mfma_attn_bwd(const void* qkv, int64_t ld, const void* o, const void*
       configured = true;                                                                                                \
     }                                                                                                                   \
     hipLaunchKernelGGL(kq, gq, block, lq, st, (const bf16*)qkv, ld, (const bf16*)o, (const bf16*)dout, lse, delta,      \
-                       (bf16*)dqkv, S, H, Hkv, scale);                                                                  \
+                       (bf16*)dqkv, S, H, Hkv, scale, rope_cs);                                                         \
     hipLaunchKernelGGL(kk, gk, block, lk, st, (const bf16*)qkv, ld, (const bf16*)dout, lse, delta, (bf16*)dqkv, S, H,   \
-                       Hkv, scale);                                                                                     \
+                       Hkv, scale, rope_cs);                                                                            \
   } while (0)
   if (hd == 128) { if (causal) SV_ATTN_BWD_LAUNCH(128, true); else SV_ATTN_BWD_LAUNCH(128, false); }
   else { if (causal) SV_ATTN_BWD_LAUNCH(64, true); else SV_ATTN_BWD_LAUNCH(64, false); }

@@ -112,7 +112,8 @@ enum EpiMode {
   EPI_GELU = 2,         // C = gelu(acc); if C2: C2 = acc (pre-activation)
   EPI_SWIGLU = 3,       // dual product (B, B2): C = silu(g) * u; if C2/C3: C2 = g, C3 = u
   EPI_SWIGLU_BWD = 4,   // da = acc: C = da * U * silu'(G), C2 = da * silu(G)   (G = R, U = R2)
-  EPI_GELU_BWD = 5      // C = acc * gelu'(R)
+  EPI_GELU_BWD = 5,     // C = acc * gelu'(R)
+  EPI_ROPE = 6          // C = acc with columns < rope_cols rotated pairwise by the RoPE angle of token (row % rope_S)
 };
 struct GemmArgs {
   int M, N;               // output [M, N]
@@ -123,6 +124,11 @@ struct GemmArgs {
   void* C; int64_t ldc;
   void* C2; void* C3;     // same leading dimension as C
   const void* R; const void* R2; int64_t ldr;
+  // optional: output columns split over up to 3 weight matrices (single K segment, [N,K] weights):
+  // columns [0, ncol[0]) use Bcol[0], the next ncol[1] use Bcol[1], ... (all with leading dimension seg[0].ldb)
+  int nbcol; const void* Bcol[3]; int ncol[3];
+  // EPI_ROPE: (cos, sin) table [rope_S][rope_hd / 2][2] of floats
+  const float* rope_cs; int rope_S, rope_hd, rope_cols;
 };
 
 // kernels_plain.hip: any shape, fp32 math, E = float | bf16 by `dtype`
@@ -150,7 +156,8 @@ hipError_t mfma_gemm(const GemmArgs& a, hipStream_t st, int tile = 0);   // tile
 bool mfma_attn_supported(int S, int H, int Hkv, int hd, int64_t ld);
 hipError_t mfma_attn_fwd(const void* qkv, int64_t ld, void* o, float* lse, int B, int S, int H, int Hkv, int hd, int causal,
                          hipStream_t st);
+// rope_cs != nullptr: dq and dk are rotated back (inverse RoPE) before they are stored
 hipError_t mfma_attn_bwd(const void* qkv, int64_t ld, const void* o, const void* dout, const float* lse, float* delta, void* dqkv,
-                         int B, int S, int H, int Hkv, int hd, int causal, hipStream_t st);
+                         int B, int S, int H, int Hkv, int hd, int causal, const float* rope_cs, hipStream_t st);
 
 }  // namespace sv

@@ -84,6 +84,19 @@ __device__ __forceinline__ void epilogue4(const GemmArgs& a, int m, int n, const
       }
       *reinterpret_cast<bf16x4*>((bf16*)a.C2 + ic) = p;
     } break;
+    case EPI_ROPE: {
+      if (n < a.rope_cols) {
+        const int half = a.rope_hd >> 1, p = m % a.rope_S, i0 = (n % a.rope_hd) >> 1;
+        const f32x4 cs = *reinterpret_cast<const f32x4*>(a.rope_cs + ((int64_t)p * half + i0) * 2);   // cos_i, sin_i, cos_i+1, sin_i+1
+        o[0] = v[0] * cs[0] - v[1] * cs[1];
+        o[1] = v[0] * cs[1] + v[1] * cs[0];
+        o[2] = v[2] * cs[2] - v[3] * cs[3];
+        o[3] = v[2] * cs[3] + v[3] * cs[2];
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[i] = v[i];
+      }
+    } break;
     default: {  // EPI_GELU_BWD
       const bf16x4 r = *reinterpret_cast<const bf16x4*>((const bf16*)a.R + ir);
 #pragma unroll
@@ -302,7 +315,13 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
   auto set_segment = [&]() {
     const GemmSeg& sg = a.seg[dseg];
     gA = (const char*)((const bf16*)sg.A + (int64_t)m0 * sg.lda);
-    gB = (const char*)((const bf16*)sg.B + (int64_t)n0 * sg.ldb);
+    if (!DUAL && a.nbcol > 0) {
+      int start = 0, j = 0;
+      while (j + 1 < a.nbcol && n0 >= start + a.ncol[j]) { start += a.ncol[j]; ++j; }
+      gB = (const char*)((const bf16*)a.Bcol[j] + (int64_t)(n0 - start) * sg.ldb);
+    } else {
+      gB = (const char*)((const bf16*)sg.B + (int64_t)n0 * sg.ldb);
+    }
     gB2 = DUAL ? (const char*)((const bf16*)a.B2 + (int64_t)n0 * a.ldb2) : gB;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -470,7 +489,15 @@ bool mfma_gemm_supported(const GemmArgs& a) {
   if (a.M < 1 || a.nseg < 1 || a.nseg > 3) return false;
   const bool dual = a.epi == EPI_SWIGLU;
   if (dual && (a.b_is_kn || a.nseg != 1 || !a.B2 || a.ldb2 % 8 || !aligned16(a.B2))) return false;
-  if (a.epi < EPI_STORE || a.epi > EPI_GELU_BWD) return false;
+  if (a.epi < EPI_STORE || a.epi > EPI_ROPE) return false;
+  if (a.nbcol > 0 || a.epi == EPI_ROPE) {
+    // fused QKV form: served by the 256x256 direct-to-LDS kernel only
+    if (a.b_is_kn || a.nseg != 1 || a.nbcol > 3 || a.N % 256 || !use_big_tile(a)) return false;
+    int tot = 0;
+    for (int j = 0; j < a.nbcol; ++j) { if (a.ncol[j] % 256 || !aligned16(a.Bcol[j])) return false; tot += a.ncol[j]; }
+    if (a.nbcol > 0 && tot != a.N) return false;
+    if (a.epi == EPI_ROPE && (!a.rope_cs || a.rope_hd % 4 || a.rope_cols % 4 || a.rope_S < 1)) return false;
+  }
   if (a.b_is_kn && (a.epi == EPI_RESID || a.epi == EPI_GELU || a.epi == EPI_SWIGLU)) return false;
   if ((a.epi == EPI_RESID || a.epi == EPI_SWIGLU_BWD || a.epi == EPI_GELU_BWD) && !a.R) return false;
   if (a.epi == EPI_SWIGLU_BWD && (!a.R2 || !a.C2)) return false;
@@ -501,10 +528,12 @@ hipError_t mfma_gemm(const GemmArgs& a, hipStream_t st, int tile) {
         case EPI_SWIGLU: return launch_dma<EPI_SWIGLU>(a, st);
         case EPI_SWIGLU_BWD: return launch_dma<EPI_SWIGLU_BWD>(a, st);
         case EPI_GELU_BWD: return launch_dma<EPI_GELU_BWD>(a, st);
+        case EPI_ROPE: return launch_dma<EPI_ROPE>(a, st);
         default: return hipErrorInvalidValue;
       }
     }
   }
+  if (a.nbcol > 0 || a.epi == EPI_ROPE) return hipErrorInvalidValue;   // only the direct-to-LDS kernel implements these
   if (!a.b_is_kn) {
     switch (a.epi) {
       case EPI_STORE: return big ? launch_cfg<256, 256, 2, 2, false, EPI_STORE>(a, st) : launch_cfg<128, 128, 2, 2, false, EPI_STORE>(a, st);
