@@ -33,6 +33,8 @@ def parse():
     ap.add_argument("--mode", default=None, choices=[None, "fwd", "fwdbwd"], help="default: the workload's own")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--plain", action="store_true", help="run the plain (non-MFMA) kernels")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run three 1 GiB device copies (a kernel of known traffic, to scale rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
 
 
@@ -100,6 +102,19 @@ def cpu_baseline(wl, wdev, h_in, g_out, backward):
                       f"{'fwd+bwd' if backward else 'fwd'}, numpy float64, {dt:.1f} s"}
 
 
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary (FETCH_SIZE and
+    WRITE_SIZE runs scaled by a copy of known size), or None when no summary covers this workload/kernel."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_{kernel}_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -149,6 +164,13 @@ def main():
                                      res.data_ptr(), stream)
             assert st == 0, L.sv_last_error(ver._ctx)
 
+    if a.copy_calibration:
+        src = torch.empty(1 << 29, dtype=torch.bfloat16, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(a.warmup):
         step()
     torch.cuda.synchronize()
@@ -178,7 +200,7 @@ def main():
                    "n_kv_heads": desc.n_kv_heads, "ffn_hidden": desc.ffn_hidden, "micro_batch": B, "seq_len": S,
                    "check": "fwd+bwd" if backward else "fwd", "claims_per_step": 1, "kernels": "plain" if a.plain else "mfma"},
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": measured_traffic(wl.name, dom),
                      "launch_ms": d["ms"] / max(d["launches"], 1), "flop_per_launch": d["flop"] / max(d["launches"], 1)},
         "recompute": {"flop_per_step": tot_flop, "tflops": tot_flop / (ms_step * 1e-3) / 1e12,
                       "frac_of_bf16_mfma_peak": tot_flop / (ms_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
