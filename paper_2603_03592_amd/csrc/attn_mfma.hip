@@ -21,7 +21,7 @@ constexpr int BQ = 128, BKV = 64;
 __device__ __forceinline__ int swz8(int row) { return (row ^ (row >> 3)) & 7; }
 
 template <int HD, bool CAUSAL>
-__global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16* __restrict__ qkv, int64_t ld, bf16* __restrict__ o,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_fwd_mfma_kernel(const bf16* __restrict__ qkv, int64_t ld, bf16* __restrict__ o,
                                                             float* __restrict__ lse, int S, int H, int Hkv, float scale_log2e) {
   constexpr int KCH = HD / 8;                       // 16-byte chunks per K row
   constexpr int KROW = HD * 2;                      // bytes per K row in LDS
@@ -156,10 +156,12 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16* __restri
           pf[t * 2 + (r >> 3)][r & 7] = (bf16)p;
         }
       l_run = l_run * corr + psum;
+      if (__builtin_amdgcn_ballot_w64(corr != 1.0f) != 0) {     // the running maximum of some query moved: rescale
 #pragma unroll
-      for (int i = 0; i < NDB; ++i)
+        for (int i = 0; i < NDB; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[i][r] *= corr;
+          for (int r = 0; r < 16; ++r) oacc[i][r] *= corr;
+      }
 #pragma unroll
       for (int g = 0; g < 4; ++g)
 #pragma unroll

@@ -46,21 +46,37 @@ struct Cfg {
   static_assert(!KN || WCH % 8 == 0, "a [K,N] operand is staged in whole 8x8 blocks per thread");
 };
 
-// 4 consecutive output features of one token row.
+// Epilogue on 4 consecutive output features of one token row, in two phases so that a caller can
+// issue all loads of a row block before the first store (the output and the residual / gate / up
+// buffers may alias as far as the compiler knows, so loads are never hoisted over stores for us).
+struct EpiIn { bf16x4 r, r2; f32x4 cs; };
+
 template <int EPI>
-__device__ __forceinline__ void epilogue4(const GemmArgs& a, int m, int n, const float (&v)[4], const float (&u)[4]) {
-  const int64_t ic = (int64_t)m * a.ldc + n, ir = (int64_t)m * a.ldr + n;
+__device__ __forceinline__ void epilogue_load4(const GemmArgs& a, int m, int n, EpiIn& in) {
+  const int64_t ir = (int64_t)m * a.ldr + n;
+  if (EPI == EPI_RESID || EPI == EPI_SWIGLU_BWD || EPI == EPI_GELU_BWD) in.r = *reinterpret_cast<const bf16x4*>((const bf16*)a.R + ir);
+  if (EPI == EPI_SWIGLU_BWD) in.r2 = *reinterpret_cast<const bf16x4*>((const bf16*)a.R2 + ir);
+  if (EPI == EPI_ROPE && n < a.rope_cols) {      // cos_i, sin_i, cos_i+1, sin_i+1 of the two feature pairs
+    const int half = a.rope_hd >> 1, p = m % a.rope_S, i0 = (n % a.rope_hd) >> 1;
+    in.cs = *reinterpret_cast<const f32x4*>(a.rope_cs + ((int64_t)p * half + i0) * 2);
+  }
+}
+
+template <int EPI>
+__device__ __forceinline__ void epilogue_apply4(const GemmArgs& a, int m, int n, const float (&v)[4], const float (&u)[4], const EpiIn& in) {
+  const int64_t ic = (int64_t)m * a.ldc + n;
+  const bf16x4& r = in.r;
+  const bf16x4& r2 = in.r2;
   float o[4];
   switch (EPI) {
     case EPI_STORE:
 #pragma unroll
       for (int i = 0; i < 4; ++i) o[i] = v[i];
       break;
-    case EPI_RESID: {
-      const bf16x4 r = *reinterpret_cast<const bf16x4*>((const bf16*)a.R + ir);
+    case EPI_RESID:
 #pragma unroll
       for (int i = 0; i < 4; ++i) o[i] = v[i] + (float)r[i];
-    } break;
+      break;
     case EPI_GELU: {
       if (a.C2) { bf16x4 p; for (int i = 0; i < 4; ++i) p[i] = (bf16)v[i]; *reinterpret_cast<bf16x4*>((bf16*)a.C2 + ic) = p; }
 #pragma unroll
@@ -73,21 +89,18 @@ __device__ __forceinline__ void epilogue4(const GemmArgs& a, int m, int n, const
       for (int i = 0; i < 4; ++i) o[i] = silu_f(v[i]) * u[i];
     } break;
     case EPI_SWIGLU_BWD: {
-      const bf16x4 g = *reinterpret_cast<const bf16x4*>((const bf16*)a.R + ir);
-      const bf16x4 w = *reinterpret_cast<const bf16x4*>((const bf16*)a.R2 + ir);
       bf16x4 p;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const float gf = (float)g[i];
-        o[i] = v[i] * (float)w[i] * silu_grad_f(gf);
+        const float gf = (float)r[i];
+        o[i] = v[i] * (float)r2[i] * silu_grad_f(gf);
         p[i] = (bf16)(v[i] * silu_f(gf));
       }
       *reinterpret_cast<bf16x4*>((bf16*)a.C2 + ic) = p;
     } break;
     case EPI_ROPE: {
       if (n < a.rope_cols) {
-        const int half = a.rope_hd >> 1, p = m % a.rope_S, i0 = (n % a.rope_hd) >> 1;
-        const f32x4 cs = *reinterpret_cast<const f32x4*>(a.rope_cs + ((int64_t)p * half + i0) * 2);   // cos_i, sin_i, cos_i+1, sin_i+1
+        const f32x4 cs = in.cs;
         o[0] = v[0] * cs[0] - v[1] * cs[1];
         o[1] = v[0] * cs[1] + v[1] * cs[0];
         o[2] = v[2] * cs[2] - v[3] * cs[3];
@@ -97,16 +110,39 @@ __device__ __forceinline__ void epilogue4(const GemmArgs& a, int m, int n, const
         for (int i = 0; i < 4; ++i) o[i] = v[i];
       }
     } break;
-    default: {  // EPI_GELU_BWD
-      const bf16x4 r = *reinterpret_cast<const bf16x4*>((const bf16*)a.R + ir);
+    default:  // EPI_GELU_BWD
 #pragma unroll
       for (int i = 0; i < 4; ++i) o[i] = v[i] * gelu_grad_f((float)r[i]);
-    } break;
+      break;
   }
   bf16x4 p;
 #pragma unroll
   for (int i = 0; i < 4; ++i) p[i] = (bf16)o[i];
   *reinterpret_cast<bf16x4*>((bf16*)a.C + ic) = p;
+}
+
+// The accumulators of one 32-row block of a wave tile: NIO feature blocks of 32, `up` = the second
+// half of a dual product.  All loads first, then compute and store.
+template <int EPI, int NIO, int NI, int MI>
+__device__ __forceinline__ void epilogue_rows(const GemmArgs& a, const f32x16 (&acc)[NI][MI], int mi, int m, int nbase) {
+  if (m >= a.M) return;
+  EpiIn in[NIO][4];
+#pragma unroll
+  for (int ni = 0; ni < NIO; ++ni)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) epilogue_load4<EPI>(a, m, nbase + ni * 32 + q * 8, in[ni][q]);
+#pragma unroll
+  for (int ni = 0; ni < NIO; ++ni)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      float v[4], u[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        v[i] = acc[ni][mi][q * 4 + i];
+        u[i] = (EPI == EPI_SWIGLU) ? acc[ni + (NIO < NI ? NIO : 0)][mi][q * 4 + i] : 0.0f;
+      }
+      epilogue_apply4<EPI>(a, m, nbase + ni * 32 + q * 8, v, u, in[ni][q]);
+    }
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool KN, int EPI>
@@ -255,24 +291,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(GemmA
   // quad q, output features 8q + 4*(lane>>5) .. +3 of each 32-feature block.
   constexpr int NIO = DUAL ? C::NI / 2 : C::NI;
 #pragma unroll
-  for (int mi = 0; mi < C::MI; ++mi) {
-    const int m = m0 + wm * C::WTM + mi * 32 + l31;
-    if (m >= a.M) continue;
-#pragma unroll
-    for (int ni = 0; ni < NIO; ++ni) {
-      const int nb = n0 + wn * (DUAL ? C::WTN / 2 : C::WTN) + ni * 32 + lhi * 4;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        float v[4], u[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          v[i] = acc[ni][mi][q * 4 + i];
-          u[i] = DUAL ? acc[ni + NIO][mi][q * 4 + i] : 0.0f;
-        }
-        epilogue4<EPI>(a, m, nb + q * 8, v, u);
-      }
-    }
-  }
+  for (int mi = 0; mi < C::MI; ++mi)
+    epilogue_rows<EPI, NIO, C::NI, C::MI>(a, acc, mi, m0 + wm * C::WTM + mi * 32 + l31, n0 + wn * (DUAL ? C::WTN / 2 : C::WTN) + lhi * 4);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -420,24 +440,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
 
   constexpr int NIO = DUAL ? 2 : 4;
 #pragma unroll
-  for (int mi = 0; mi < MI; ++mi) {
-    const int m = m0 + wm * 128 + mi * 32 + l31;
-    if (m >= a.M) continue;
-#pragma unroll
-    for (int ni = 0; ni < NIO; ++ni) {
-      const int nb = n0 + wn * (DUAL ? 64 : 128) + ni * 32 + lhi * 4;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        float v[4], u[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          v[i] = acc[ni][mi][q * 4 + i];
-          u[i] = DUAL ? acc[ni + NIO][mi][q * 4 + i] : 0.0f;
-        }
-        epilogue4<EPI>(a, m, nb + q * 8, v, u);
-      }
-    }
-  }
+  for (int mi = 0; mi < MI; ++mi)
+    epilogue_rows<EPI, NIO, NI, MI>(a, acc, mi, m0 + wm * 128 + mi * 32 + l31, n0 + wn * (DUAL ? 64 : 128) + lhi * 4);
 }
 
 template <int EPI>
