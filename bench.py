@@ -33,6 +33,9 @@ def parse():
     ap.add_argument("--mode", default=None, choices=[None, "fwd", "fwdbwd"], help="default: the workload's own")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--plain", action="store_true", help="run the plain (non-MFMA) kernels")
+    ap.add_argument("--score-bench", action="store_true",
+                    help="instead of the stage check, time the stand-alone scoring pass (128 submissions against one shared "
+                         "reference) and the EMA update, and report them against the HBM roofline")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three 1 GiB device copies (a kernel of known traffic, to scale rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
@@ -115,11 +118,69 @@ def measured_traffic(workload, kernel):
     return None
 
 
+def score_bench(a):
+    """HBM-bound half of the verifier: Gamma = Omega(h, reference) for 128 concurrent submissions of the large
+    stage's signal shape [8192, 4096] bf16 against one shared reference (the paper's EMA mode, or one
+    recomputation shared by many workers), then the EMA update over the un-flagged ones."""
+    import torch
+    import paper_2603_03592_amd as sv
+    import stage_inputs as si
+    T, D, n = 8192, 4096, 128
+    torch.cuda.set_device(0)
+    ver = sv.Verifier(si.TINY.desc, 128, 64)
+    g = torch.Generator(device="cuda").manual_seed(0)
+    ref = torch.randn((T, D), generator=g, device="cuda", dtype=torch.float32)
+    claims = torch.empty((n, T, D), dtype=torch.bfloat16, device="cuda")
+    for i in range(n):
+        claims[i] = (ref * (1.5 if i % 8 == 3 else 1.0)).to(torch.bfloat16)
+    m = ref.clone()
+    refb = ref.to(torch.bfloat16)
+    tau = {"rel_l2": 2e-2, "l1": 0.05, "zl2": 0.01, "sfr": 0.02}
+
+    def timed(fn, steps):
+        for _ in range(2):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps
+
+    out = {}
+    ms = timed(lambda: out.update(r=ver.score_and_flag(claims, refb, metrics=("rel_l2", "l1", "zl2", "sfr"), tau=tau)), a.steps)
+    flags = ver.read_results(out["r"]["result"])["flag"]
+    assert [int(f) for f in flags] == [int(i % 8 == 3) for i in range(n)]
+    score_bytes = n * T * D * 2 + T * D * 2 + n * T * 4            # claims + the shared reference once (+ nothing else of size)
+    ms_lite = timed(lambda: ver.score_and_flag(claims, refb, metrics=("rel_l2",), tau=tau), a.steps)
+    fl = out["r"]["result"].view(torch.int32)[:, 4].to(torch.uint8).contiguous()
+    ms_ema = timed(lambda: ver.ema_update(m, claims, fl, 0.9), a.steps)
+    n_clean = int((fl == 0).sum())
+    ema_bytes = n_clean * T * D * 2 + 2 * T * D * 4
+    res = {
+        "metric": "scored tokens/sec (stand-alone statistic, 128 submissions, shared reference)", "value": n * T / (ms * 1e-3),
+        "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": 2, "ms_per_step": ms, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "score_128x8192x4096", "claims": n, "tokens": T, "d_model": D, "metrics": "rel_l2,l1,zl2,sfr"},
+        "roofline": {"bound": "hbm", "kernel": "score_tokens_kernel", "achieved": score_bytes / (ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+                     "unit": "GB/s", "frac": score_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None},
+        "rel_l2_only": {"ms": ms_lite, "achieved_GBs": score_bytes / (ms_lite * 1e-3) / 1e9,
+                        "frac": score_bytes / (ms_lite * 1e-3) / 1e9 / PEAK_HBM_GBS},
+        "ema": {"ms": ms_ema, "clean": n_clean, "achieved_GBs": ema_bytes / (ms_ema * 1e-3) / 1e9,
+                "frac": ema_bytes / (ms_ema * 1e-3) / 1e9 / PEAK_HBM_GBS},
+    }
+    ver.close()
+    print(json.dumps(res))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
         raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path (every stage check is "
                          "independent per micro-batch; see DESIGN.md for how it would shard). Use --gpus 1.")
+    if a.score_bench:
+        return score_bench(a)
     import torch
     import paper_2603_03592_amd as sv
     wl = get_workload(a.workload)

@@ -93,7 +93,7 @@ typedef struct {
 
 /* Verdict for one submission (device memory, 32 bytes). */
 typedef struct {
-  float    score[4];        /* by SV_IDX_*; metrics not in the mask are still computed          */
+  float    score[4];        /* by SV_IDX_*; the relative L2 always, the others only if in the mask (else 0) */
   uint32_t flag;            /* 1 iff score[i] > tau[i] for some enabled metric i (strict '>')   */
   uint32_t metric_mask;     /* echo of the request                                               */
   float    max_token_rell2; /* max over tokens of ||c_t - r_t|| / max(||r_t||, 1e-30)            */
@@ -146,7 +146,7 @@ sv_status sv_score_and_flag(sv_ctx *ctx, const void *claims, int64_t claim_strid
 
 /* m [T, D] float, in place:  m <- beta m + (1-beta) mean_{i: flags[i]==0} claim_i ; unchanged
  * when every claim is flagged.  flags_dev: n_claims bytes on the device (e.g. copied from
- * sv_result.flag), NULL = all clean.                                                        */
+ * sv_result.flag), NULL = all clean.  n_claims <= 1024.                                      */
 sv_status sv_ema_update(sv_ctx *ctx, float *m, const void *claims, int64_t claim_stride, int32_t n_claims,
                         int32_t claim_dtype, const uint8_t *flags_dev, int64_t T, int32_t D, float beta,
                         void *stream);

@@ -548,6 +548,7 @@ sv_status sv_ema_update(sv_ctx* c, float* m, const void* claims, int64_t claim_s
   if (!(beta >= 0.0f && beta < 1.0f)) { set_err(c, "beta must be in [0, 1)"); return SV_EINVAL; }
   if (D % 8) { set_err(c, "D must be a multiple of 8"); return SV_EUNSUPPORTED; }
   if (claim_stride < 0) { set_err(c, "negative stride"); return SV_EINVAL; }
+  if (n_claims > 1024) { set_err(c, "at most 1024 submissions per EMA update"); return SV_EUNSUPPORTED; }
   SV_HIP(c, launch_ema(m, claims, claim_stride, n_claims, claim_dtype, flags_dev, T, D, beta, (hipStream_t)stream));
   return SV_OK;
 }

@@ -17,7 +17,10 @@ namespace {
 
 constexpr int kTPW = kScoreTokensPerWG / 4;  // tokens per wave
 
-template <typename EC, typename ER>
+// NEED_L1 / NEED_Z / NEED_SFR prune the sums a launch does not need (the statistic family is
+// requested by mask): with only the relative L2 enabled a token costs two FMAs per element and the
+// pass is bound by HBM; with all eight sums it is bound by the vector ALUs (about 18 ops/element).
+template <typename EC, typename ER, bool NEED_L1, bool NEED_Z, bool NEED_SFR>
 __global__ __launch_bounds__(256) void score_tokens_kernel(const EC* __restrict__ claims, int64_t claim_stride,
                                                            const ER* __restrict__ ref, int64_t ref_stride, int64_t T, int D,
                                                            int n_claims, int tiles_per_claim, float* __restrict__ token_scores,
@@ -38,27 +41,42 @@ __global__ __launch_bounds__(256) void score_tokens_kernel(const EC* __restrict_
     if (t >= T) break;  // uniform per wave
     const EC* c = cbase + t * D;
     const ER* r = rbase + t * D;
-    float sc = 0, sr = 0, scc = 0, srr = 0, sd = 0, sad = 0, sdd = 0, ns = 0;
-#pragma unroll 4
-    for (int k = lane * 8; k < D; k += 512) {
-      float cv[8], rv[8];
-      load8(c + k, cv);
-      load8(r + k, rv);
+    float sc = 0, sr = 0, scc = 0, srr = 0, sad = 0, sdd = 0;
+    int nsi = 0;
+    auto accumulate = [&](const float (&cv)[8], const float (&rv)[8]) {
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         const float a = cv[j], b = rv[j], d = a - b;
-        sc += a; sr += b; scc += a * a; srr += b * b;
-        sd += d; sad += fabsf(d); sdd += d * d;
-        const int sa = (a > 0.0f) - (a < 0.0f), sb = (b > 0.0f) - (b < 0.0f);
-        ns += (sa != sb) ? 1.0f : 0.0f;
+        srr = fmaf(b, b, srr); sdd = fmaf(d, d, sdd);
+        if (NEED_Z) { sc += a; sr += b; scc = fmaf(a, a, scc); }
+        if (NEED_L1) sad += fabsf(d);
+        // sign(a) != sign(b) with sign(0) = 0: the two signs agree iff both "positive" and both "negative" tests agree
+        if (NEED_SFR) nsi += (int)(((a > 0.0f) != (b > 0.0f)) | ((a < 0.0f) != (b < 0.0f)));
       }
+    };
+    int k = lane * 8;
+    for (; k + 1536 < D; k += 2048) {                 // four 16-byte loads of each operand in flight per lane
+      float c0[8], c1[8], c2[8], c3[8], r0[8], r1[8], r2[8], r3[8];
+      load8(c + k, c0); load8(c + k + 512, c1); load8(c + k + 1024, c2); load8(c + k + 1536, c3);
+      load8(r + k, r0); load8(r + k + 512, r1); load8(r + k + 1024, r2); load8(r + k + 1536, r3);
+      accumulate(c0, r0); accumulate(c1, r1); accumulate(c2, r2); accumulate(c3, r3);
     }
-    sc = wave_sum(sc); sr = wave_sum(sr); scc = wave_sum(scc); srr = wave_sum(srr);
-    sd = wave_sum(sd); sad = wave_sum(sad); sdd = wave_sum(sdd); ns = wave_sum(ns);
+    for (; k < D; k += 512) {
+      float cv[8], rv[8];
+      load8(c + k, cv);
+      load8(r + k, rv);
+      accumulate(cv, rv);
+    }
+    srr = wave_sum(srr); sdd = wave_sum(sdd);
+    if (NEED_Z) { sc = wave_sum(sc); sr = wave_sum(sr); scc = wave_sum(scc); }
+    if (NEED_L1) sad = wave_sum(sad);
+    float ns = 0.0f;
+    if (NEED_SFR) ns = wave_sum((float)nsi);      // at most D / 64 per lane: exact in fp32
     const float rel = sqrtf(sdd) / fmaxf(sqrtf(srr), 1e-30f);
     if (lane == 0 && token_scores) token_scores[(int64_t)claim * T + t] = rel;
     acc[0] += sc; acc[1] += sr; acc[2] += scc; acc[3] += srr;
-    acc[4] += sd; acc[5] += sad; acc[6] += sdd; acc[7] += ns;
+    acc[4] += (double)sc - (double)sr;            // sum of differences, only used for the mean of d in the z-scored L2
+    acc[5] += sad; acc[6] += sdd; acc[7] += ns;
     if (!(rel <= 3.0e38f)) bad = 1;           // NaN or inf
     else if (rel > best) { best = rel; best_t = (int)t; }
   }
@@ -145,7 +163,8 @@ __global__ __launch_bounds__(256) void score_finalize_kernel(const ScorePartial*
     uint32_t flag = 0;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      r.score[i] = (float)sc[i];
+      const bool on = ((mask >> i) & 1u) || i == SV_IDX_RELL2;         // the relative L2 is always formed
+      r.score[i] = on ? (float)sc[i] : 0.0f;
       if (((mask >> i) & 1u) && !(r.score[i] <= tau.v[i])) flag = 1;   // strict '>'; non-finite scores are flagged
     }
     r.flag = flag; r.metric_mask = mask;
@@ -157,15 +176,34 @@ __global__ __launch_bounds__(256) void score_finalize_kernel(const ScorePartial*
 template <typename E>
 __global__ __launch_bounds__(256) void ema_update_kernel(float* __restrict__ m, const E* __restrict__ claims, int64_t claim_stride,
                                                          int n_claims, const uint8_t* __restrict__ flags, int64_t n_vec, float beta) {
+  // the un-flagged submissions of this step, compacted once per workgroup
+  __shared__ int clean[1024];
+  __shared__ int s_n;
+  if (threadIdx.x == 0) {
+    int n = 0;
+    for (int i = 0; i < n_claims && n < 1024; ++i)
+      if (flags == nullptr || flags[i] == 0) clean[n++] = i;
+    s_n = n;
+  }
+  __syncthreads();
+  const int n_clean = s_n;
   const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  int n_clean = 0;
-  for (int i = 0; i < n_claims; ++i) n_clean += (flags == nullptr || flags[i] == 0) ? 1 : 0;
   if (v >= n_vec || n_clean == 0) return;   // every submission flagged: the EMA is left as it is
   float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  for (int i = 0; i < n_claims; ++i) {
-    if (flags != nullptr && flags[i] != 0) continue;
+  const E* base = claims + v * 8;
+  int i = 0;
+  for (; i + 3 < n_clean; i += 4) {
+    float x0[8], x1[8], x2[8], x3[8];
+    load8(base + (int64_t)clean[i] * claim_stride, x0);
+    load8(base + (int64_t)clean[i + 1] * claim_stride, x1);
+    load8(base + (int64_t)clean[i + 2] * claim_stride, x2);
+    load8(base + (int64_t)clean[i + 3] * claim_stride, x3);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] += (x0[j] + x1[j]) + (x2[j] + x3[j]);
+  }
+  for (; i < n_clean; ++i) {
     float x[8];
-    load8(claims + (int64_t)i * claim_stride + v * 8, x);
+    load8(base + (int64_t)clean[i] * claim_stride, x);
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] += x[j];
   }
@@ -197,14 +235,24 @@ hipError_t launch_score(const void* claims, int64_t claim_stride, int n_claims, 
     const char* rp = (const char*)ref + c0 * ref_stride * rsz;
     float* ts = token_scores ? token_scores + c0 * T : nullptr;
     const dim3 grid((unsigned)(tiles * nc)), block(256);
-#define SV_LAUNCH_SCORE(EC, ER)                                                                                   \
-  hipLaunchKernelGGL((score_tokens_kernel<EC, ER>), grid, block, 0, st, (const EC*)cp, claim_stride, (const ER*)rp, \
-                     ref_stride, T, D, nc, (int)tiles, ts, scratch)
+#define SV_LAUNCH_SCORE3(EC, ER, L1, Z, SFR)                                                                           \
+  hipLaunchKernelGGL((score_tokens_kernel<EC, ER, L1, Z, SFR>), grid, block, 0, st, (const EC*)cp, claim_stride,          \
+                     (const ER*)rp, ref_stride, T, D, nc, (int)tiles, ts, scratch)
+#define SV_LAUNCH_SCORE(EC, ER)                                                                                          \
+  do {                                                                                                                   \
+    const bool l1 = mask & SV_M_L1, z = mask & SV_M_ZL2, sfr = mask & SV_M_SFR;                                          \
+    if (!l1 && !z && !sfr) SV_LAUNCH_SCORE3(EC, ER, false, false, false);                                                \
+    else if (l1 && !z && !sfr) SV_LAUNCH_SCORE3(EC, ER, true, false, false);                                             \
+    else if (!l1 && !z && sfr) SV_LAUNCH_SCORE3(EC, ER, false, false, true);                                             \
+    else if (!l1 && z && !sfr) SV_LAUNCH_SCORE3(EC, ER, false, true, false);                                             \
+    else SV_LAUNCH_SCORE3(EC, ER, true, true, true);                                                                     \
+  } while (0)
     if (claim_dtype == SV_BF16 && ref_dtype == SV_BF16) SV_LAUNCH_SCORE(bf16, bf16);
     else if (claim_dtype == SV_BF16) SV_LAUNCH_SCORE(bf16, float);
     else if (ref_dtype == SV_BF16) SV_LAUNCH_SCORE(float, bf16);
     else SV_LAUNCH_SCORE(float, float);
 #undef SV_LAUNCH_SCORE
+#undef SV_LAUNCH_SCORE3
     hipLaunchKernelGGL(score_finalize_kernel, dim3(nc), dim3(256), 0, st, scratch, (int)tiles, T, D, mask, tau, reduce,
                        results + c0);
   }
