@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--score-bench", action="store_true",
                     help="instead of the stage check, time the stand-alone scoring pass (128 submissions against one shared "
                          "reference) and the EMA update, and report them against the HBM roofline")
+    ap.add_argument("--sweep", action="store_true",
+                    help="run the throughput sweep (single block, d_model 4096, seq x micro-batch grid, fwd+bwd) and print one "
+                         "JSON line per point")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three 1 GiB device copies (a kernel of known traffic, to scale rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
@@ -181,6 +184,14 @@ def main():
                          "independent per micro-batch; see DESIGN.md for how it would shard). Use --gpus 1.")
     if a.score_bench:
         return score_bench(a)
+    if a.sweep:
+        import subprocess
+        for s_ in (512, 2048, 4096):
+            for b_ in (1, 4, 16):
+                r = subprocess.run([sys.executable, os.path.abspath(__file__), "--workload", f"sweep_s{s_}_b{b_}", "--steps", str(a.steps),
+                                    "--warmup", str(a.warmup), "--no-cpu-baseline"], capture_output=True, text=True)
+                print(r.stdout.strip() if r.returncode == 0 else json.dumps({"workload": f"sweep_s{s_}_b{b_}", "error": r.stderr[-300:]}), flush=True)
+        return
     import torch
     import paper_2603_03592_amd as sv
     wl = get_workload(a.workload)

@@ -256,7 +256,7 @@ __device__ __forceinline__ void stage_quad(char* rm, char* tr, const bf16x8 (&re
 }
 
 template <int HD, bool CAUSAL>
-__global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16* __restrict__ qkv, int64_t ld, const bf16* __restrict__ o,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dq_mfma_kernel(const bf16* __restrict__ qkv, int64_t ld, const bf16* __restrict__ o,
                                                                const bf16* __restrict__ dout, const float* __restrict__ lse,
                                                                float* __restrict__ delta, bf16* __restrict__ dqkv, int S, int H, int Hkv,
                                                                float scale, const float* __restrict__ rope_cs) {
@@ -334,40 +334,39 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16* __res
       const char* ks = smem + (j & 1) * STAGE;
       const char* vs = ks + TILE;
       const char* kt = ks + 2 * TILE;
-      f32x16 s[2], dp[2];
+      const bool need_mask = (CAUSAL && k0 + BKV - 1 > wq0) || (k0 + BKV > S);
+      // one 32-key block at a time, to keep only 32 score registers live
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
+        f32x16 s, dp;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { s[t][r] = 0.0f; dp[t][r] = 0.0f; }
+        for (int r = 0; r < 16; ++r) { s[r] = 0.0f; dp[r] = 0.0f; }
         const int krow = t * 32 + l31;
 #pragma unroll
         for (int kk = 0; kk < NKK; ++kk) {
           const bf16x8 kf = *reinterpret_cast<const bf16x8*>(ks + rm_off<HD>(krow, kk * 2 + half));
           const bf16x8 vf = *reinterpret_cast<const bf16x8*>(vs + rm_off<HD>(krow, kk * 2 + half));
-          s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s[t], 0, 0, 0);
-          dp[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, dof[kk], dp[t], 0, 0, 0);
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s, 0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, dof[kk], dp, 0, 0, 0);
         }
-      }
-      const bool need_mask = (CAUSAL && k0 + BKV - 1 > wq0) || (k0 + BKV > S);
-      bf16x8 dsf[4];
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
+        bf16x8 dsf[2];
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          float p = __builtin_amdgcn_exp2f(fmaf(s[t][r], c2, -lse2));
+          float p = __builtin_amdgcn_exp2f(fmaf(s[r], c2, -lse2));
           if (need_mask) {
             const int key = k0 + t * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
             if ((CAUSAL && key > myq) || key >= S) p = 0.0f;
           }
-          dsf[t * 2 + (r >> 3)][r & 7] = (bf16)(p * (dp[t][r] - dl));
+          dsf[r >> 3][r & 7] = (bf16)(p * (dp[r] - dl));
         }
 #pragma unroll
-      for (int g = 0; g < 4; ++g)
+        for (int g2 = 0; g2 < 2; ++g2)
 #pragma unroll
-        for (int db = 0; db < NDB; ++db) {
-          const bf16x8 ktf = *reinterpret_cast<const bf16x8*>(kt + tr_frag_off(db * 32 + l31, g, half));
-          dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf, dsf[g], dq[db], 0, 0, 0);
-        }
+          for (int db = 0; db < NDB; ++db) {
+            const bf16x8 ktf = *reinterpret_cast<const bf16x8*>(kt + tr_frag_off(db * 32 + l31, t * 2 + g2, half));
+            dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf, dsf[g2], dq[db], 0, 0, 0);
+          }
+      }
     }
     if (more) store_tile((j + 1) & 1);
     __syncthreads();

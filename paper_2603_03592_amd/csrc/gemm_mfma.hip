@@ -121,18 +121,17 @@ __device__ __forceinline__ void epilogue_apply4(const GemmArgs& a, int m, int n,
   *reinterpret_cast<bf16x4*>((bf16*)a.C + ic) = p;
 }
 
-// The accumulators of one 32-row block of a wave tile: NIO feature blocks of 32, `up` = the second
-// half of a dual product.  All loads first, then compute and store.
+// The accumulators of one 32-row block of a wave tile: NIO feature blocks of 32 (the second half of the
+// accumulator blocks is the `up` product of a dual launch).  Per feature block: its four loads first,
+// then compute and store.
 template <int EPI, int NIO, int NI, int MI>
 __device__ __forceinline__ void epilogue_rows(const GemmArgs& a, const f32x16 (&acc)[NI][MI], int mi, int m, int nbase) {
   if (m >= a.M) return;
-  EpiIn in[NIO][4];
 #pragma unroll
-  for (int ni = 0; ni < NIO; ++ni)
+  for (int ni = 0; ni < NIO; ++ni) {
+    EpiIn in[4];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) epilogue_load4<EPI>(a, m, nbase + ni * 32 + q * 8, in[ni][q]);
-#pragma unroll
-  for (int ni = 0; ni < NIO; ++ni)
+    for (int q = 0; q < 4; ++q) epilogue_load4<EPI>(a, m, nbase + ni * 32 + q * 8, in[q]);
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       float v[4], u[4];
@@ -141,8 +140,9 @@ __device__ __forceinline__ void epilogue_rows(const GemmArgs& a, const f32x16 (&
         v[i] = acc[ni][mi][q * 4 + i];
         u[i] = (EPI == EPI_SWIGLU) ? acc[ni + (NIO < NI ? NIO : 0)][mi][q * 4 + i] : 0.0f;
       }
-      epilogue_apply4<EPI>(a, m, nbase + ni * 32 + q * 8, v, u, in[ni][q]);
+      epilogue_apply4<EPI>(a, m, nbase + ni * 32 + q * 8, v, u, in[q]);
     }
+  }
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool KN, int EPI>
@@ -314,39 +314,47 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
   constexpr int NOUT = DUAL ? 128 : 256;
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
+  // Persistent workgroups: workgroup b works on the virtual block ids b, b + gridDim.x, ...; a virtual id
+  // maps to a tile so that ids congruent mod 8 (one XCD) walk a contiguous run of tiles in groups of
+  // kGroupM row tiles.  gridDim.x is a multiple of 8, so a workgroup stays on its XCD's run.
   const int nblk = tiles_m * tiles_n;
   const int per_xcd = (nblk + 7) >> 3;
-  const int pid = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-  if (pid >= nblk) return;
-  const int in_group = kGroupM * tiles_n;
-  const int first_m = (pid / in_group) * kGroupM;
-  const int gsz = min(tiles_m - first_m, kGroupM);
-  const int tile_m = first_m + (pid % in_group) % gsz;
-  const int tile_n = (pid % in_group) / gsz;
-  const int m0 = tile_m * BM, n0 = tile_n * NOUT;
+  auto tile_of = [&](int vb, int& m0, int& n0) -> bool {
+    if (vb >= per_xcd * 8) return false;
+    const int pid = (vb & 7) * per_xcd + (vb >> 3);
+    if (pid >= nblk) return false;
+    const int in_group = kGroupM * tiles_n;
+    const int first_m = (pid / in_group) * kGroupM;
+    const int gsz = min(tiles_m - first_m, kGroupM);
+    m0 = (first_m + (pid % in_group) % gsz) * BM;
+    n0 = ((pid % in_group) / gsz) * NOUT;
+    return true;
+  };
 
   const int tid = threadIdx.x, lane = tid & 63, l31 = lane & 31, lhi = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), wm = wave & 1, wn = wave >> 1;
 
-  // ---- DMA side: slice being fetched = (dseg, dk); a wave owns 8 row groups of each operand
-  int dseg = 0, dk = 0;
+  // ---- DMA side: one continuous stream of slices across this workgroup's tiles, always one slice
+  // ahead of the multiply.  State: virtual block d_vb (tile d_m0, d_n0), segment dseg, offset dk.
+  int d_vb = blockIdx.x, d_m0 = 0, d_n0 = 0, dseg = 0, dk = 0;
+  bool d_valid = tile_of(d_vb, d_m0, d_n0);
   const char *gA, *gB, *gB2;
   unsigned voffA[8], voffB[8];
   auto set_segment = [&]() {
     const GemmSeg& sg = a.seg[dseg];
-    gA = (const char*)((const bf16*)sg.A + (int64_t)m0 * sg.lda);
+    gA = (const char*)((const bf16*)sg.A + (int64_t)d_m0 * sg.lda);
     if (!DUAL && a.nbcol > 0) {
       int start = 0, j = 0;
-      while (j + 1 < a.nbcol && n0 >= start + a.ncol[j]) { start += a.ncol[j]; ++j; }
-      gB = (const char*)((const bf16*)a.Bcol[j] + (int64_t)(n0 - start) * sg.ldb);
+      while (j + 1 < a.nbcol && d_n0 >= start + a.ncol[j]) { start += a.ncol[j]; ++j; }
+      gB = (const char*)((const bf16*)a.Bcol[j] + (int64_t)(d_n0 - start) * sg.ldb);
     } else {
-      gB = (const char*)((const bf16*)sg.B + (int64_t)n0 * sg.ldb);
+      gB = (const char*)((const bf16*)sg.B + (int64_t)d_n0 * sg.ldb);
     }
-    gB2 = DUAL ? (const char*)((const bf16*)a.B2 + (int64_t)n0 * a.ldb2) : gB;
+    gB2 = DUAL ? (const char*)((const bf16*)a.B2 + (int64_t)d_n0 * a.ldb2) : gB;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int r = (wave + 4 * i) * 8 + (lane >> 3), c = (lane & 7) ^ swz(r);
-      const int ra = min(r, a.M - 1 - m0);                    // ragged row tail: re-read the last row
+      const int ra = min(r, a.M - 1 - d_m0);                  // ragged row tail: re-read the last row
       voffA[i] = (unsigned)((int64_t)ra * sg.lda + c * 8) * 2u;
       if (DUAL) voffB[i] = (unsigned)((int64_t)(r & 127) * (i >= 4 ? a.ldb2 : sg.ldb) + c * 8) * 2u;
       else voffB[i] = (unsigned)((int64_t)r * sg.ldb + c * 8) * 2u;
@@ -360,9 +368,15 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(g + off),
                                      (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
   };
-  auto advance = [&]() {
+  auto advance = [&]() {                                      // to the next slice of the stream
     dk += BK;
-    if (dk >= a.seg[dseg].K && dseg + 1 < a.nseg) { dk = 0; ++dseg; set_segment(); }
+    if (dk < a.seg[dseg].K) return;
+    dk = 0;
+    if (dseg + 1 < a.nseg) { ++dseg; set_segment(); return; }
+    dseg = 0;
+    d_vb += gridDim.x;
+    d_valid = tile_of(d_vb, d_m0, d_n0);
+    if (d_valid) set_segment();
   };
 
   int nslices = 0;
@@ -375,16 +389,10 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
   for (int ni = 0; ni < NI; ++ni) wrow[ni] = (DUAL ? (ni < 2 ? wn * 64 + ni * 32 : 128 + wn * 64 + (ni - 2) * 32) : wn * 128 + ni * 32) + l31;
 
   f32x16 acc[NI][MI];
-#pragma unroll
-  for (int i = 0; i < NI; ++i)
-#pragma unroll
-    for (int j = 0; j < MI; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
 #define SV_SB __builtin_amdgcn_sched_barrier(0)
   // One 16-wide k step: MFMAs on (xc, wc); fragments (rstage, rkk) are read into (xn, wn_) and the
-  // DMAs [d0, d0 + 8) of slice `dstage` are issued, both spread over the four MFMA groups.
+  // DMAs [d0, d0 + 8) of the stream's next slice are issued into dstage, both spread over the four MFMA groups.
   auto step = [&](bf16x8 (&xc)[MI], bf16x8 (&wc)[NI], bf16x8 (&xn)[MI], bf16x8 (&wn_)[NI], bool do_read, int rstage, int rkk,
                   bool do_dma, int dstage, int d0) {
     const char* xs = smem + rstage * STAGE;
@@ -403,45 +411,108 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
     }
   };
 
+  if (!d_valid) return;
   bf16x8 xf0[MI], wf0[NI], xf1[MI], wf1[NI];
   set_segment();
 #pragma unroll
-  for (int j = 0; j < 16; ++j) dma(0, j);
+  for (int j = 0; j < 16; ++j) dma(0, j);                     // slice 0 of the first tile
   advance();
-  __builtin_amdgcn_s_waitcnt(0);
-  __syncthreads();
-  if (nslices > 1) {
-#pragma unroll
-    for (int j = 0; j < 16; ++j) dma(1, j);
-    advance();
-  }
-#pragma unroll
-  for (int g = 0; g < 4; ++g) {
-    xf0[g] = *reinterpret_cast<const bf16x8*>(smem + lds_off(xrow[g], lhi));
-    wf0[g] = *reinterpret_cast<const bf16x8*>(smem + BM * 128 + lds_off(wrow[g], lhi));
-  }
-  step(xf0, wf0, xf1, wf1, true, 0, 1, false, 0, 0);
-  step(xf1, wf1, xf0, wf0, true, 0, 2, false, 0, 0);
-  step(xf0, wf0, xf1, wf1, true, 0, 3, false, 0, 0);
-  for (int kt = 1; kt < nslices; ++kt) {
-    const int st = kt & 1;
-    __builtin_amdgcn_s_waitcnt(0);     // my DMAs of slice kt have landed, my fragment reads of slice kt-1 are done
-    __syncthreads();                   // ... and so have everybody's: stage st is complete, stage st^1 is free
-    SV_SB;
-    const bool more = kt + 1 < nslices;
-    step(xf1, wf1, xf0, wf0, true, st, 0, more, st ^ 1, 0);     // MFMAs of (kt-1, k step 3)
-    step(xf0, wf0, xf1, wf1, true, st, 1, more, st ^ 1, 8);
-    if (more) advance();
-    step(xf1, wf1, xf0, wf0, true, st, 2, false, 0, 0);
-    step(xf0, wf0, xf1, wf1, true, st, 3, false, 0, 0);
-  }
-  step(xf1, wf1, xf0, wf0, false, 0, 0, false, 0, 0);
-#undef SV_SB
+  int par = 0;                                                // LDS stage of the current tile's slice 0
 
-  constexpr int NIO = DUAL ? 2 : 4;
+  int m0, n0;
+  for (int vb = blockIdx.x; tile_of(vb, m0, n0); vb += gridDim.x) {
 #pragma unroll
-  for (int mi = 0; mi < MI; ++mi)
-    epilogue_rows<EPI, NIO, NI, MI>(a, acc, mi, m0 + wm * 128 + mi * 32 + l31, n0 + wn * (DUAL ? 64 : 128) + lhi * 4);
+    for (int i = 0; i < NI; ++i)
+#pragma unroll
+      for (int j = 0; j < MI; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+    // ---- slice 0 (its loads were issued during the previous tile's last slice, or above)
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    SV_SB;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      xf0[g] = *reinterpret_cast<const bf16x8*>(smem + par * STAGE + lds_off(xrow[g], lhi));
+      wf0[g] = *reinterpret_cast<const bf16x8*>(smem + par * STAGE + BM * 128 + lds_off(wrow[g], lhi));
+    }
+    step(xf0, wf0, xf1, wf1, true, par, 1, d_valid, par ^ 1, 0);
+    step(xf1, wf1, xf0, wf0, true, par, 2, d_valid, par ^ 1, 8);
+    if (d_valid) advance();
+    step(xf0, wf0, xf1, wf1, true, par, 3, false, 0, 0);
+    for (int kt = 1; kt < nslices; ++kt) {
+      const int st = (par + kt) & 1;
+      __builtin_amdgcn_s_waitcnt(0);   // my DMAs of slice kt have landed, my fragment reads of slice kt-1 are done
+      __syncthreads();                 // ... and so have everybody's: stage st is complete, stage st^1 is free
+      SV_SB;
+      step(xf1, wf1, xf0, wf0, true, st, 0, d_valid, st ^ 1, 0);     // MFMAs of (kt-1, k step 3)
+      step(xf0, wf0, xf1, wf1, true, st, 1, d_valid, st ^ 1, 8);
+      if (d_valid) advance();
+      step(xf1, wf1, xf0, wf0, true, st, 2, false, 0, 0);
+      step(xf0, wf0, xf1, wf1, true, st, 3, false, 0, 0);
+    }
+    step(xf1, wf1, xf0, wf0, false, 0, 0, false, 0, 0);
+
+    // ---- epilogue through LDS (the next tile's slice 0 is landing in the other stage meanwhile).
+    // In the accumulator layout a lane owns one token row and scattered groups of 4 features, so a
+    // store instruction would touch 32 rows with 16 bytes each; the memory pipeline then takes ~11 us
+    // per tile.  Each wave instead writes its 32 x 128 fp32 block into its own 16 KB patch of the
+    // stage that was just consumed (16-byte chunks XOR-swizzled by the row: conflict-free both ways)
+    // and reads it back so that 16 consecutive lanes cover 128 contiguous bytes of an output row;
+    // every global access of the epilogue (result, residual, gate / up) becomes a full-line run.
+    const int sl = (par + nslices - 1) & 1;
+    par = (par + nslices) & 1;
+    __syncthreads();                                   // everybody is done reading stage sl
+    char* patch = smem + sl * STAGE + wave * 16384;
+    const int er = lane >> 4, ec4 = lane & 15;         // read-back: row er of each group of 4 rows, 16-byte chunk ec4 (and 16 + ec4)
+    constexpr int NIO = DUAL ? 2 : 4;
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          f32x4 v;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) v[i] = acc[ni][mi][q * 4 + i];
+          const int chunk = ni * 8 + q * 2 + lhi;      // features 4*chunk .. +3 of the wave's 128
+          *reinterpret_cast<f32x4*>(patch + l31 * 512 + ((chunk ^ l31) << 4)) = v;
+        }
+      __builtin_amdgcn_s_waitcnt(0xc07f);              // lgkmcnt(0): the patch is complete before it is read back
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int it = 0; it < 8; it += 2) {
+        // two rows per lane and trip: all of their loads are issued before the first store
+        float lo[2][4], hi[2][4];
+        EpiIn in_lo[2], in_hi[2];
+        int mrow[2];
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+          const int row = (it + k) * 4 + er;
+          mrow[k] = m0 + wm * 128 + mi * 32 + row;
+          const f32x4 a_lo = *reinterpret_cast<const f32x4*>(patch + row * 512 + ((ec4 ^ row) << 4));
+          const f32x4 a_hi = *reinterpret_cast<const f32x4*>(patch + row * 512 + (((16 + ec4) ^ row) << 4));
+#pragma unroll
+          for (int i = 0; i < 4; ++i) { lo[k][i] = a_lo[i]; hi[k][i] = a_hi[i]; }
+          if (mrow[k] < a.M) {
+            if (DUAL) epilogue_load4<EPI>(a, mrow[k], n0 + wn * 64 + ec4 * 4, in_lo[k]);
+            else { epilogue_load4<EPI>(a, mrow[k], n0 + wn * 128 + ec4 * 4, in_lo[k]); epilogue_load4<EPI>(a, mrow[k], n0 + wn * 128 + 64 + ec4 * 4, in_hi[k]); }
+          }
+        }
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+          if (mrow[k] >= a.M) continue;
+          if (DUAL) epilogue_apply4<EPI>(a, mrow[k], n0 + wn * 64 + ec4 * 4, lo[k], hi[k], in_lo[k]);   // patch columns 0..63: gate, 64..127: up
+          else {
+            epilogue_apply4<EPI>(a, mrow[k], n0 + wn * 128 + ec4 * 4, lo[k], hi[k], in_lo[k]);
+            epilogue_apply4<EPI>(a, mrow[k], n0 + wn * 128 + 64 + ec4 * 4, hi[k], lo[k], in_hi[k]);
+          }
+        }
+      }
+    }
+    (void)NIO;
+  }
+#undef SV_SB
 }
 
 template <int EPI>
@@ -456,7 +527,16 @@ hipError_t launch_dma(const GemmArgs& a, hipStream_t st) {
   }
   const int tiles_m = (a.M + 255) / 256, tiles_n = a.N / (EPI == EPI_SWIGLU ? 128 : 256);
   const int per_xcd = (tiles_m * tiles_n + 7) / 8;
-  hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(256), lds, st, a, tiles_m, tiles_n);
+  static int n_cu = 0;                                   // one persistent workgroup per CU (128 KB of LDS each)
+  if (n_cu == 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return hipErrorUnknown;
+    n_cu = (prop.multiProcessorCount / 8) * 8;
+    if (n_cu < 8) n_cu = 8;
+  }
+  const int grid = per_xcd * 8 < n_cu ? per_xcd * 8 : n_cu;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, a, tiles_m, tiles_n);
   return hipGetLastError();
 }
 
