@@ -1,0 +1,180 @@
+"""CPU oracle for the verifier's remaining statistic and its decision policy -- TEST
+INFRASTRUCTURE, not a product path.
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import this file.
+It shares no code with the HIP / C++ library.
+
+What it defines (float64, plain numpy, one function per passage):
+
+* sliced_wasserstein      -- Omega_SW of the paragraph "Choice of Distance Measure": the mean
+                             over random unit directions u of the 1-Wasserstein distance
+                             between the projections of the two signals onto u.
+* percentiles / tukey_flag-- q1, q2, q3 of a history window and the fence test of
+                             Eq. tukey_fences (flag iff |Gamma - q2| >= k (q3 - q1)).
+* adaptive_iqr            -- Alg. adaptive_iqr: widen / narrow the multiplier k until the
+                             fraction of the history outside the fences matches the target
+                             false-positive rate, then enforce a minimum distance from the median.
+* StagePolicy             -- the bookkeeping of Alg. activation_verification /
+                             Alg. gradient_verification for one stage: violation counters with
+                             forgiveness, bans (after c violations, or at once for a deviation
+                             100 times the fence half-width), the history of clean deviations,
+                             the per-iteration tainted set and its ">50 % flagged" reset.
+
+Readings where the paper is silent or at odds with itself (the same list is in the design notes):
+  - the samples of the two distributions are the T token vectors in R^D; L directions are an
+    input (drawn by the caller from N(0, I) and normalised); with equal sample counts the
+    1-Wasserstein distance of two empirical distributions on the line is the mean absolute
+    difference of the sorted samples;
+  - percentiles use linear interpolation between order statistics (position (n-1) p);
+  - "outside [lower, upper]" is strict (x < lower or x > upper);
+  - "FP-rate << alpha" is read as FP-rate < alpha / 10;
+  - the multiplier carried into a call is the one the previous call returned (k_0 on the first);
+  - the history is cut to its last l VALUES (the algorithm's slice), not l iterations;
+  - the flag test uses the bounds Alg. adaptive_iqr returned: flagged iff
+    Gamma <= lower or Gamma >= upper (the ">=" of Eq. tukey_fences); before any history exists
+    nothing is flagged;
+  - ">>" in the ban rule: |Gamma - q2| >= 100 k IQR for some metric;
+  - forgiveness: after T_forgiveness consecutive clean steps the counter drops by one and the
+    streak starts again.
+
+Pins: tests/test_oracle_sentinel.py.  Parts with no pin ("parity unpinned"): none.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+F64 = np.float64
+
+
+# ------------------------------------------------------------------ sliced Wasserstein
+def sliced_wasserstein(claim, ref, directions):
+    """Omega_SW(claim, ref).  claim, ref: [T, D] (leading dims are flattened into T);
+    directions: [L, D].  Returns the mean over the L directions of W1 between the projected
+    sample sets."""
+    d = np.asarray(directions, dtype=F64)
+    c = np.asarray(claim, dtype=F64).reshape(-1, d.shape[1])
+    r = np.asarray(ref, dtype=F64).reshape(-1, d.shape[1])
+    pc = c @ d.T                                  # [T, L]: sample t projected on direction l
+    pr = r @ d.T
+    w1 = np.mean(np.abs(np.sort(pc, axis=0) - np.sort(pr, axis=0)), axis=0)
+    return float(np.mean(w1))
+
+
+# ------------------------------------------------------------------ Tukey fences
+def percentiles(history):
+    """25th, 50th and 75th percentiles with linear interpolation between order statistics."""
+    h = np.sort(np.asarray(history, dtype=F64))
+    n = h.shape[0]
+    out = []
+    for p in (0.25, 0.5, 0.75):
+        pos = (n - 1) * p
+        lo = int(np.floor(pos))
+        hi = min(lo + 1, n - 1)
+        out.append(h[lo] + (h[hi] - h[lo]) * (pos - lo))
+    return tuple(out)
+
+
+def tukey_flag(gamma, q1, q2, q3, k):
+    """Eq. tukey_fences."""
+    return bool(abs(gamma - q2) >= k * (q3 - q1))
+
+
+def _fp_rate(h, lower, upper):
+    return float(np.mean((h < lower) | (h > upper)))
+
+
+def adaptive_iqr(history, k_prev, alpha, grow, shrink, n_max, min_dist_mult, eps):
+    """Alg. adaptive_iqr.  Returns (lower, upper, k)."""
+    h = np.asarray(history, dtype=F64)
+    q1, q2, q3 = percentiles(h)
+    iqr = max(q3 - q1, eps)
+    k = float(k_prev)
+    lower, upper = q2 - k * iqr, q2 + k * iqr
+    fp = _fp_rate(h, lower, upper)
+    it = 0
+    while fp > alpha and it < n_max:              # too many benign values outside: widen
+        k *= grow
+        lower, upper = q2 - k * iqr, q2 + k * iqr
+        fp = _fp_rate(h, lower, upper)
+        it += 1
+    it = 0
+    while fp < alpha / 10.0 and it < n_max:       # far fewer than the target: narrow
+        k *= shrink
+        lower, upper = q2 - k * iqr, q2 + k * iqr
+        fp = _fp_rate(h, lower, upper)
+        it += 1
+    d_min = abs(q2) * min_dist_mult
+    lower = min(lower, q2 - d_min)
+    upper = max(upper, q2 + d_min)
+    return lower, upper, k
+
+
+# ------------------------------------------------------------------ per-stage policy
+class StagePolicy:
+    """State one verifier keeps for one stage and one signal kind (Alg. momentum_verification's
+    v_r, B_s, H_l plus the fences of every metric)."""
+
+    def __init__(self, n_workers, n_metrics, *, c=5, t_forgive=100, window=100, k0=1.5, alpha=0.01,
+                 grow=1.1, shrink=0.9, n_max=10, min_dist_mult=0.0, eps=1e-3, severe=100.0):
+        self.d, self.m = n_workers, n_metrics
+        self.c, self.t_forgive, self.window = c, t_forgive, window
+        self.alpha, self.grow, self.shrink, self.n_max = alpha, grow, shrink, n_max
+        self.min_dist_mult, self.eps, self.severe = min_dist_mult, eps, severe
+        self.v = [0] * n_workers
+        self.streak = [0] * n_workers
+        self.banned = [False] * n_workers
+        self.hist = [[] for _ in range(n_metrics)]
+        self.k = [float(k0)] * n_metrics
+        self.lower = [-np.inf] * n_metrics
+        self.upper = [np.inf] * n_metrics
+        self.q2 = [0.0] * n_metrics
+        self.iqr = [np.inf] * n_metrics
+
+    def _update_fences(self):
+        for i in range(self.m):
+            self.hist[i] = self.hist[i][-self.window:]
+            if not self.hist[i]:
+                continue
+            lo, up, k = adaptive_iqr(self.hist[i], self.k[i], self.alpha, self.grow, self.shrink,
+                                     self.n_max, self.min_dist_mult, self.eps)
+            q1, q2, q3 = percentiles(self.hist[i])
+            self.lower[i], self.upper[i], self.k[i] = lo, up, k
+            self.q2[i], self.iqr[i] = q2, max(q3 - q1, self.eps)
+
+    def warmup(self, gamma):
+        """Warm-up iteration: every worker's deviation enters the history, nothing is flagged."""
+        g = np.asarray(gamma, dtype=F64)
+        for r in range(self.d):
+            for i in range(self.m):
+                self.hist[i].append(float(g[r, i]))
+        self._update_fences()
+
+    def step(self, gamma, skip=None):
+        """One verified iteration.  gamma [d, m]; skip[r] true for workers that are not examined
+        (already tainted by another stage in this iteration, or absent).  Returns the list of
+        workers tainted at this stage."""
+        g = np.asarray(gamma, dtype=F64)
+        tainted = []
+        for r in range(self.d):
+            if self.banned[r] or (skip is not None and skip[r]):
+                continue
+            violated = any((not (g[r, i] > self.lower[i])) or (not (g[r, i] < self.upper[i])) for i in range(self.m))
+            if violated:
+                self.v[r] += 1
+                self.streak[r] = 0
+                tainted.append(r)
+                severe = any(abs(g[r, i] - self.q2[i]) >= self.severe * self.k[i] * self.iqr[i] for i in range(self.m))
+                if self.v[r] >= self.c or severe:
+                    self.banned[r] = True
+            else:
+                for i in range(self.m):
+                    self.hist[i].append(float(g[r, i]))
+                self.streak[r] += 1
+                if self.streak[r] >= self.t_forgive:
+                    self.v[r] = max(0, self.v[r] - 1)
+                    self.streak[r] = 0
+        self._update_fences()
+        active = self.d - sum(self.banned)
+        if len(tainted) > 0.5 * active:
+            tainted = []
+        return tainted

@@ -144,6 +144,15 @@ def make_output_grad(desc: StageDesc, batch: int, seq: int, seed: int, micro_bat
 
 
 # --------------------------------------------------------------------------- submissions
+def make_directions(d_model: int, n_dirs: int, seed: int = 0) -> np.ndarray:
+    """Projection directions for the sliced Wasserstein statistic: n_dirs draws from N(0, I_D),
+    scaled to unit length, then rounded to bf16 (the library takes them in bf16; both consumers see
+    the same rounded values, whose length differs from 1 by at most 2^-9 relative)."""
+    u = _rng(seed, 50).standard_normal((n_dirs, d_model))
+    u /= np.linalg.norm(u, axis=1, keepdims=True)
+    return round_to_bf16(u.astype(np.float32))
+
+
 def honest_claim(reference: np.ndarray, dtype: str) -> np.ndarray:
     """What an honest worker sends: the true signal in the stage's storage dtype."""
     return to_stage_dtype(np.asarray(reference, dtype=np.float32), dtype)

@@ -1,0 +1,228 @@
+"""Pins for oracle/sentinel_oracle.py: sliced Wasserstein distance, Tukey fences, the adaptive
+multiplier of Alg. adaptive_iqr and the violation / ban bookkeeping of Alg. activation_verification.
+Every expected value here comes from a closed form, a brute force over permutations, a library
+routine that works differently (CDF integration), or a hand-worked example."""
+import itertools
+
+import numpy as np
+import pytest
+from scipy.stats import wasserstein_distance
+
+from oracle import sentinel_oracle as so
+
+
+def _dirs(L, D, seed):
+    u = np.random.default_rng(seed).standard_normal((L, D))
+    return u / np.linalg.norm(u, axis=1, keepdims=True)
+
+
+# ------------------------------------------------------------------ sliced Wasserstein
+def test_sw_one_dimension_matches_cdf_integration():
+    rng = np.random.default_rng(0)
+    a, b = rng.standard_normal(37), 0.5 + 1.7 * rng.standard_normal(37)
+    want = wasserstein_distance(a, b)                      # integrates |F_a - F_b|
+    got = so.sliced_wasserstein(a[:, None], b[:, None], np.ones((1, 1)))
+    assert got == pytest.approx(want, rel=1e-12)
+
+
+def test_sw_equals_optimal_matching_cost_by_brute_force():
+    rng = np.random.default_rng(1)
+    T, D, L = 6, 3, 4
+    a, b, u = rng.standard_normal((T, D)), rng.standard_normal((T, D)) * 2 + 0.3, _dirs(L, D, 2)
+    total = 0.0
+    for l in range(L):
+        pa, pb = a @ u[l], b @ u[l]
+        total += min(np.mean(np.abs(pa - pb[list(p)])) for p in itertools.permutations(range(T)))
+    assert so.sliced_wasserstein(a, b, u) == pytest.approx(total / L, rel=1e-12)
+
+
+def test_sw_closed_forms_and_invariances():
+    rng = np.random.default_rng(3)
+    T, D, L = 50, 8, 16
+    r, u = rng.standard_normal((T, D)), _dirs(L, D, 4)
+    assert so.sliced_wasserstein(r, r, u) == 0.0
+    # translation of every sample by v: each projection shifts by v.u
+    v = rng.standard_normal(D)
+    assert so.sliced_wasserstein(r + v, r, u) == pytest.approx(np.mean(np.abs(u @ v)), rel=1e-12)
+    # positive scaling keeps the order of the projected samples
+    assert so.sliced_wasserstein(1.5 * r, r, u) == pytest.approx(0.5 * np.mean(np.abs(r @ u.T)), rel=1e-12)
+    # a distance between sample SETS: permuting the tokens of one side changes nothing
+    c = r + 0.1 * rng.standard_normal((T, D))
+    base = so.sliced_wasserstein(c, r, u)
+    assert so.sliced_wasserstein(c[rng.permutation(T)], r, u) == pytest.approx(base, rel=1e-12)
+    assert so.sliced_wasserstein(r, c, u) == pytest.approx(base, rel=1e-12)            # symmetric
+    # ... while negating the samples of a symmetric-looking cloud is NOT seen as an element-wise change
+    assert so.sliced_wasserstein(-r, r, u) < np.mean(np.abs(r @ u.T))
+    # triangle inequality per direction carries over to the mean
+    d2 = r + rng.standard_normal((T, D))
+    assert so.sliced_wasserstein(c, d2, u) <= so.sliced_wasserstein(c, r, u) + so.sliced_wasserstein(r, d2, u) + 1e-12
+    # leading dimensions are flattened into samples
+    assert so.sliced_wasserstein(c.reshape(5, 10, D), r.reshape(5, 10, D), u) == pytest.approx(base, rel=1e-15)
+
+
+def test_sw_direction_axis_is_the_feature_axis():
+    # two samples in R^2, one direction e_x: only the x coordinates matter
+    a = np.array([[0.0, 100.0], [1.0, -100.0]])
+    b = np.array([[3.0, 0.0], [2.0, 0.0]])
+    assert so.sliced_wasserstein(a, b, np.array([[1.0, 0.0]])) == pytest.approx(2.0)     # sorted x: (0,1) vs (2,3)
+    assert so.sliced_wasserstein(a, b, np.array([[0.0, 1.0]])) == pytest.approx(100.0)   # sorted y: (-100,100) vs (0,0)
+
+
+# ------------------------------------------------------------------ percentiles / fences
+def test_percentiles_textbook_cases():
+    assert so.percentiles(range(1, 10)) == (3.0, 5.0, 7.0)
+    assert so.percentiles([4, 1, 3, 2]) == pytest.approx((1.75, 2.5, 3.25))
+    assert so.percentiles([7.0]) == (7.0, 7.0, 7.0)
+    h = np.random.default_rng(5).standard_normal(101)
+    assert so.percentiles(h) == pytest.approx(tuple(np.percentile(h, [25, 50, 75])))
+    hs = np.sort(h)
+    assert so.percentiles(h) == (hs[25], hs[50], hs[75])         # n = 101: exact order statistics
+
+
+def test_tukey_fence_is_inclusive_and_centred_on_the_median():
+    q1, q2, q3 = 3.0, 5.0, 7.0
+    assert so.tukey_flag(11.0, q1, q2, q3, 1.5)                    # |11 - 5| = 6 = 1.5 * 4
+    assert so.tukey_flag(-1.0, q1, q2, q3, 1.5)
+    assert not so.tukey_flag(10.999, q1, q2, q3, 1.5)
+    assert not so.tukey_flag(5.0, q1, q2, q3, 1.5)
+
+
+# ------------------------------------------------------------------ Alg. adaptive_iqr
+def test_adaptive_iqr_hand_worked_example():
+    """history 0..100: q1, q2, q3 = 25, 50, 75, IQR 50.  k0 = 0.5 -> fences [25, 75], 50 of 101
+    outside (0.495 > 0.2) -> k = 0.75 -> [12.5, 87.5], 26 outside (0.257 > 0.2) -> k = 1.125 ->
+    nothing outside.  Then 0 < 0.02: shrink by 0.8 -> k = 0.9 -> [5, 95], 10 outside (0.099), stop."""
+    lo, up, k = so.adaptive_iqr(np.arange(101.0), 0.5, alpha=0.2, grow=1.5, shrink=0.8, n_max=10,
+                                min_dist_mult=0.0, eps=1e-3)
+    assert k == pytest.approx(0.9) and lo == pytest.approx(5.0) and up == pytest.approx(95.0)
+
+
+def test_adaptive_iqr_keeps_k_inside_the_band():
+    # 1 of 21 values outside the fences: 0.0476 lies in [alpha/10, alpha] for alpha = 0.1: k stays
+    h = np.concatenate([np.linspace(-1, 1, 20), [50.0]])
+    lo, up, k = so.adaptive_iqr(h, 1.5, alpha=0.1, grow=1.1, shrink=0.9, n_max=10, min_dist_mult=0.0, eps=1e-6)
+    q1, q2, q3 = so.percentiles(h)
+    assert k == 1.5 and lo == pytest.approx(q2 - 1.5 * (q3 - q1)) and up == pytest.approx(q2 + 1.5 * (q3 - q1))
+
+
+def test_adaptive_iqr_widening_is_minimal_and_bounded():
+    h = np.random.default_rng(6).standard_normal(400)
+    q1, q2, q3 = so.percentiles(h)
+    iqr = q3 - q1
+    alpha, grow = 0.01, 1.1
+    lo, up, k = so.adaptive_iqr(h, 0.5, alpha, grow, 1.0 - 1e-12, n_max=50, min_dist_mult=0.0, eps=1e-9)
+    # shrink factor ~1 makes the narrowing phase a no-op: k is k0 * grow^j for the smallest j that works
+    j = round(np.log(k / 0.5) / np.log(grow))
+    assert k == pytest.approx(0.5 * grow ** j, rel=1e-9) and j >= 1
+    outside = lambda kk: np.mean(np.abs(h - q2) > kk * iqr)
+    assert outside(0.5 * grow ** j) <= alpha < outside(0.5 * grow ** (j - 1))
+    # the iteration cap binds
+    _, _, k3 = so.adaptive_iqr(h, 0.5, alpha, grow, 1.0 - 1e-12, n_max=3, min_dist_mult=0.0, eps=1e-9)
+    assert k3 == pytest.approx(0.5 * grow ** 3, rel=1e-9)
+
+
+def test_adaptive_iqr_degenerate_history_and_minimum_distance():
+    # constant history: IQR = eps, nothing ever outside, the narrowing loop runs n_max times
+    lo, up, k = so.adaptive_iqr(np.full(30, 10.0), 3.0, alpha=0.01, grow=1.1, shrink=0.9, n_max=10,
+                                min_dist_mult=0.0, eps=0.01)
+    assert k == pytest.approx(3.0 * 0.9 ** 10)
+    assert lo == pytest.approx(10.0 - k * 0.01) and up == pytest.approx(10.0 + k * 0.01)
+    # minimum distance |q2| * Lambda from the median overrides tighter fences, never looser ones
+    lo, up, _ = so.adaptive_iqr(np.full(30, 10.0), 3.0, 0.01, 1.1, 0.9, 10, min_dist_mult=0.35, eps=0.01)
+    assert lo == pytest.approx(6.5) and up == pytest.approx(13.5)
+    lo, up, k = so.adaptive_iqr(np.full(30, -10.0), 3.0, 0.01, 1.1, 0.9, 0, min_dist_mult=0.001, eps=1.0)
+    assert (lo, up, k) == pytest.approx((-13.0, -7.0, 3.0))
+
+
+# ------------------------------------------------------------------ violation counters, bans, taint
+def _policy(**kw):
+    # eps = 1000 pins IQR to 1000; n_max = 0 freezes k = 1: the fences are median -/+ 1000
+    args = dict(c=5, t_forgive=100, window=10_000, k0=1.0, alpha=0.01, grow=1.1, shrink=0.9, n_max=0,
+                min_dist_mult=0.0, eps=1000.0)
+    args.update(kw)
+    p = so.StagePolicy(4, 2, **args)
+    p.warmup(np.full((4, 2), 50.0))
+    return p
+
+
+def test_policy_nothing_flagged_before_history_exists():
+    p = so.StagePolicy(3, 1)
+    assert p.step(np.array([[1e9], [0.0], [-1e9]])) == []
+    assert p.v == [0, 0, 0] and len(p.hist[0]) == 3
+
+
+def test_policy_ban_after_c_violations_and_fence_is_inclusive():
+    p = _policy()
+    g = np.full((4, 2), 50.0)
+    g[2, 1] = 1050.0                                   # exactly on the upper fence: flagged
+    for it in range(5):
+        assert p.step(g) == [2]
+        assert p.v[2] == it + 1 and p.banned[2] == (it == 4)
+    assert p.step(g) == []                             # a banned worker is no longer examined
+    g[1, 0] = 1049.0                                   # inside
+    assert p.step(g) == [] and p.v[1] == 0
+
+
+def test_policy_severe_deviation_bans_at_once():
+    p = _policy()
+    g = np.full((4, 2), 50.0)
+    g[0, 0] = 50.0 - 100.0 * 1000.0                    # 100 x the fence half-width below the median
+    assert p.step(g) == [0] and p.banned[0] and p.v[0] == 1
+    g[1, 0] = 50.0 + 99_999.0
+    assert p.step(g) == [1] and not p.banned[1]
+
+
+def test_policy_forgiveness_after_consecutive_clean_steps():
+    p = _policy(t_forgive=3)
+    bad, good = np.full((4, 2), 50.0), np.full((4, 2), 50.0)
+    bad[3, 0] = 5000.0
+    p.step(bad); p.step(bad)
+    assert p.v[3] == 2
+    p.step(good); p.step(good)
+    assert p.v[3] == 2                                 # two clean steps: not yet
+    p.step(bad)                                        # streak broken
+    assert p.v[3] == 3
+    p.step(good); p.step(good); p.step(good)
+    assert p.v[3] == 2
+    p.step(good); p.step(good); p.step(good)
+    assert p.v[3] == 1 and p.v[0] == 0                 # counters never go below zero
+
+
+def test_policy_history_takes_clean_values_only_and_majority_flag_clears_taint():
+    p = _policy()
+    n0 = len(p.hist[0])
+    g = np.full((4, 2), 60.0)
+    g[1, 0] = 9999.0
+    assert p.step(g) == [1]
+    assert len(p.hist[0]) == n0 + 3 and 9999.0 not in p.hist[0]
+    # three of four flagged: read as a natural shift, the tainted set is dropped (counters stay)
+    g = np.full((4, 2), 9999.0)
+    g[0] = 60.0
+    assert p.step(g) == []
+    assert p.v == [0, 2, 1, 1]
+    # skip mask: worker 2 is tainted upstream, not examined, its value does not enter the history
+    g = np.full((4, 2), 61.0)
+    g[2] = 9999.0
+    n1 = len(p.hist[1])
+    assert p.step(g, skip=[False, False, True, False]) == []
+    assert p.v[2] == 1 and len(p.hist[1]) == n1 + 3
+
+
+def test_policy_window_and_adaptation_track_a_drifting_statistic():
+    # the minimum-distance multiplier (0.15 |median|, as in the paper's configuration table) keeps the
+    # fences from collapsing onto a history that only ever receives un-flagged values
+    p = so.StagePolicy(8, 1, window=100, k0=1.5, alpha=0.01, grow=1.1, shrink=0.9, n_max=10, eps=1e-4,
+                       min_dist_mult=0.15)
+    rng = np.random.default_rng(7)
+    for t in range(20):
+        p.warmup(1.0 + 0.01 * rng.standard_normal((8, 1)))
+    flagged = 0
+    for t in range(200):                               # slow benign drift of the statistic
+        flagged += len(p.step(1.0 + 0.002 * t + 0.01 * rng.standard_normal((8, 1))))
+    assert len(p.hist[0]) <= 100 + 8
+    assert flagged == 0 and not any(p.banned)
+    assert 1.3 < p.q2[0] < 1.45 and p.lower[0] < 1.4 < p.upper[0]      # the fences followed the drift
+    assert p.upper[0] - p.q2[0] == pytest.approx(0.15 * p.q2[0])         # ... at the minimum distance
+    g = 1.4 + 0.01 * rng.standard_normal((8, 1))
+    g[5] = 3.0
+    assert p.step(g) == [5]
