@@ -52,11 +52,14 @@ typedef enum { SV_REDUCE_GLOBAL = 0, SV_REDUCE_MAX_TOKEN = 1 } sv_reduce;
 /* metric indices into score[] / tau[] and their mask bits (1 << index) */
 enum { SV_IDX_RELL2 = 0, SV_IDX_L1 = 1, SV_IDX_ZL2 = 2, SV_IDX_SFR = 3 };
 enum { SV_M_RELL2 = 1, SV_M_L1 = 2, SV_M_ZL2 = 4, SV_M_SFR = 8 };
+/* mask bit of the sliced Wasserstein statistic (computed by sv_sliced_wasserstein, no score[] slot) */
+enum { SV_M_SW = 16 };
 
 /* sv_create flags */
 enum {
   SV_FLAG_BACKWARD = 1,       /* also allocate what sv_verify_backward needs                       */
-  SV_FLAG_PLAIN_KERNELS = 2   /* run the plain fp32-math kernels for every dtype (validation aid)  */
+  SV_FLAG_PLAIN_KERNELS = 2,  /* run the plain fp32-math kernels for every dtype (validation aid)  */
+  SV_FLAG_SLICED_W = 4        /* also allocate the projection scratch of sv_sliced_wasserstein       */
 };
 
 /* One pipeline stage = n_blocks identical pre-norm decoder blocks
@@ -151,6 +154,30 @@ sv_status sv_ema_update(sv_ctx *ctx, float *m, const void *claims, int64_t claim
                         int32_t claim_dtype, const uint8_t *flags_dev, int64_t T, int32_t D, float beta,
                         void *stream);
 
+/* Sliced Wasserstein statistic (paragraph "Choice of Distance Measure", Omega_SW): the mean over
+ * n_dirs directions u of the 1-Wasserstein distance between the two signals projected on u.  The
+ * samples of a signal are its T token vectors in R^D; both sides have T samples, so W1 on the line
+ * is the mean absolute difference of the sorted projections.
+ *   claims / ref / strides / dtypes : as in sv_score_and_flag (ref_stride 0 = one shared reference,
+ *                  projected and sorted once).
+ *   directions   : device, bf16 [n_dirs, D] row-major, drawn and normalised by the caller (the
+ *                  paper draws them from the unit sphere; they are used as given).
+ *   n_dirs       : a multiple of 32, at most 128.   D: a multiple of 64.   n_claims <= 4096.
+ *   tau          : threshold; a submission is flagged iff not (Omega_SW <= tau).
+ *   sw_out       : device, nullable, [n_claims] float: Omega_SW per submission.
+ *   results_dev  : device, nullable, [n_claims] sv_result that an earlier sv_score_and_flag /
+ *                  sv_verify_* call on the same stream filled: metric_mask gets SV_M_SW and flag is
+ *                  set (never cleared), which keeps the any-metric rule.
+ * Needs a context created with SV_FLAG_SLICED_W and T <= its max_tokens; submissions are processed
+ * in groups that fit the context's projection scratch.  bf16 signals are projected exactly
+ * (bf16 x bf16 products, fp32 accumulation); fp32 signals are split into three bf16 terms first.
+ * Errors: SV_EINVAL (null pointers, negative sizes, context without the flag), SV_EUNSUPPORTED
+ * (n_dirs, D, n_claims or T outside the limits above), SV_EHIP.                                  */
+sv_status sv_sliced_wasserstein(sv_ctx *ctx, const void *claims, int64_t claim_stride, int32_t n_claims,
+                                const void *ref, int64_t ref_stride, int32_t claim_dtype, int32_t ref_dtype,
+                                int64_t T, int32_t D, const void *directions, int32_t n_dirs, float tau,
+                                float *sw_out, sv_result *results_dev, void *stream);
+
 /* Per-operation timing with HIP events recorded on the caller's stream around each launch.
  * sv_profile_enable(ctx, 1) clears the accumulators and starts recording; (ctx, 0) stops.
  * sv_profile_read waits for the recorded events and returns, per operation class, the summed
@@ -159,7 +186,7 @@ sv_status sv_ema_update(sv_ctx *ctx, float *m, const void *claims, int64_t claim
 enum {
   SV_OP_NORM = 0, SV_OP_GEMM_QKV, SV_OP_ROPE, SV_OP_ATTN, SV_OP_GEMM_O, SV_OP_GEMM_GATEUP, SV_OP_GEMM_DOWN,
   SV_OP_SCORE, SV_OP_BWD_GEMM_DA, SV_OP_BWD_GEMM_DN2, SV_OP_BWD_NORM, SV_OP_BWD_GEMM_DO, SV_OP_BWD_ATTN,
-  SV_OP_BWD_ROPE, SV_OP_BWD_GEMM_DN1, SV_OP_BWD_WTRANSPOSE, SV_OP_COUNT
+  SV_OP_BWD_ROPE, SV_OP_BWD_GEMM_DN1, SV_OP_BWD_WTRANSPOSE, SV_OP_SW_PROJECT, SV_OP_SW_SORT, SV_OP_COUNT
 };
 typedef struct {
   double  ms[SV_OP_COUNT];

@@ -14,7 +14,8 @@ SV_F32, SV_BF16 = 0, 1
 SV_MLP_GELU, SV_MLP_SWIGLU = 0, 1
 SV_NORM_LN, SV_NORM_RMS = 0, 1
 SV_REDUCE_GLOBAL, SV_REDUCE_MAX_TOKEN = 0, 1
-SV_FLAG_BACKWARD, SV_FLAG_PLAIN_KERNELS = 1, 2
+SV_FLAG_BACKWARD, SV_FLAG_PLAIN_KERNELS, SV_FLAG_SLICED_W = 1, 2, 4
+SV_M_SW = 16
 METRIC_NAMES = ("rel_l2", "l1", "zl2", "sfr")
 METRIC_BITS = {n: 1 << i for i, n in enumerate(METRIC_NAMES)}
 _STATUS = {1: "SV_EINVAL", 2: "SV_EUNSUPPORTED", 3: "SV_ENOMEM", 4: "SV_EHIP"}
@@ -40,7 +41,8 @@ class BlockWeightsC(C.Structure):
 
 
 OP_NAMES = ("norm", "gemm_qkv", "rope", "attn", "gemm_o", "gemm_gateup", "gemm_down", "score", "bwd_gemm_da",
-            "bwd_gemm_dn2", "bwd_norm", "bwd_gemm_do", "bwd_attn", "bwd_rope", "bwd_gemm_dn1", "bwd_wtranspose")
+            "bwd_gemm_dn2", "bwd_norm", "bwd_gemm_do", "bwd_attn", "bwd_rope", "bwd_gemm_dn1", "bwd_wtranspose",
+            "sw_project", "sw_sort")
 
 
 class ProfileC(C.Structure):
@@ -81,6 +83,8 @@ def _load():
     L.sv_profile_enable.argtypes = [vp, i32]
     L.sv_profile_read.restype = C.c_int
     L.sv_profile_read.argtypes = [vp, C.POINTER(ProfileC)]
+    L.sv_sliced_wasserstein.restype = C.c_int
+    L.sv_sliced_wasserstein.argtypes = [vp, vp, i64, i32, vp, i64, i32, i32, i64, i32, vp, i32, f32, vp, vp, vp]
     L.sv_gemm_bf16.restype = C.c_int
     L.sv_gemm_bf16.argtypes = [vp, i64, vp, i64, i32, vp, i64, i32, i32, i32, i32, vp]
     return L
@@ -155,12 +159,14 @@ def _dt(t) -> int:
 class Verifier:
     """One sv_ctx.  Tensors are torch tensors on the context's device, contiguous, in the stage dtype."""
 
-    def __init__(self, desc, max_tokens: int, max_seq: int, backward: bool = False, plain_kernels: bool = False):
+    def __init__(self, desc, max_tokens: int, max_seq: int, backward: bool = False, plain_kernels: bool = False,
+                 sliced_w: bool = False):
         import torch
         self.torch = torch
         self.desc = desc
         self.tdtype = torch.bfloat16 if desc.dtype == "bf16" else torch.float32
-        self.flags = (SV_FLAG_BACKWARD if backward else 0) | (SV_FLAG_PLAIN_KERNELS if plain_kernels else 0)
+        self.flags = ((SV_FLAG_BACKWARD if backward else 0) | (SV_FLAG_PLAIN_KERNELS if plain_kernels else 0)
+                      | (SV_FLAG_SLICED_W if sliced_w else 0))
         self._ctx = C.c_void_p()
         d = _desc_c(desc)
         st = lib.sv_create(C.byref(d), max_tokens, max_seq, self.flags, C.byref(self._ctx))
@@ -252,6 +258,21 @@ class Verifier:
                                           SV_REDUCE_MAX_TOKEN if reduce == "max_token" else SV_REDUCE_GLOBAL,
                                           _ptr(tok), _ptr(res), self._stream()))
         return dict(result=res, token_scores=tok)
+
+    def sliced_wasserstein(self, claims, ref, directions, tau: float, results=None):
+        """claims [n, T, D]; ref [T, D] shared or [n, T, D]; directions bf16 [L, D].  Returns sw [n] float32 (device);
+        with `results` (the sv_result tensor of an earlier scoring call) the flag is OR-ed into it."""
+        torch = self.torch
+        n, D = claims.shape[0], claims.shape[-1]
+        T = claims[0].numel() // D
+        shared = ref.numel() == T * D
+        assert claims.is_contiguous() and ref.is_contiguous() and directions.is_contiguous()
+        assert directions.dtype == torch.bfloat16 and directions.shape[1] == D
+        sw = torch.empty((n,), dtype=torch.float32, device=claims.device)
+        self._check(lib.sv_sliced_wasserstein(self._ctx, _ptr(claims), T * D, n, _ptr(ref), 0 if shared else T * D, _dt(claims), _dt(ref),
+                                              T, D, _ptr(directions), directions.shape[0], float(tau), _ptr(sw), _ptr(results),
+                                              self._stream()))
+        return sw
 
     def ema_update(self, m, claims, flags_dev, beta: float):
         """m [T, D] float32 updated in place from claims [n, T, D]; flags_dev: uint8 [n] on the device or None."""

@@ -34,6 +34,8 @@ struct Arena {
 };
 
 constexpr int64_t kScoreScratchElems = 1 << 18;   // ScorePartial records (20 MiB)
+constexpr int kSwMaxDirs = 128, kSwMaxClaims = 4096;
+constexpr int kSwSlots = 9;                       // projected tensors (kSwMaxDirs rows each) the scratch holds at max_tokens
 
 }  // namespace
 
@@ -57,6 +59,9 @@ struct sv_ctx {
   void *wqT, *wkT, *wvT, *woT, *wgT, *wuT, *wdT;   // one block's weights transposed to [in, out] (bf16 MFMA path)
   float* delta;
   ScorePartial* score_scratch;
+  float* sw_w1;        // [kSwMaxClaims, kSwMaxDirs] per-direction sums (SV_FLAG_SLICED_W)
+  float* sw_proj;      // kSwSlots * kSwMaxDirs rows of sw_padded_len(max_tokens) floats
+  size_t sw_proj_floats;
   float* rope_cs;
   char err[256];
   // optional per-operation event timing
@@ -89,7 +94,7 @@ sv_status check_desc_impl(const sv_stage_desc* d, uint32_t flags, char* msg, int
   if (d->dtype != SV_F32 && d->dtype != SV_BF16) return fail(SV_EINVAL, "unknown dtype");
   if (!(d->norm_eps >= 0.0f)) return fail(SV_EINVAL, "norm_eps must be >= 0");
   if (d->rope && !(d->rope_theta > 0.0f)) return fail(SV_EINVAL, "rope_theta must be > 0");
-  if (flags & ~(uint32_t)(SV_FLAG_BACKWARD | SV_FLAG_PLAIN_KERNELS)) return fail(SV_EINVAL, "unknown flag bits");
+  if (flags & ~(uint32_t)(SV_FLAG_BACKWARD | SV_FLAG_PLAIN_KERNELS | SV_FLAG_SLICED_W)) return fail(SV_EINVAL, "unknown flag bits");
   if (d->d_model % d->n_heads) return fail(SV_EINVAL, "d_model must be a multiple of n_heads");
   if (d->n_heads % d->n_kv_heads) return fail(SV_EINVAL, "n_heads must be a multiple of n_kv_heads");
   const int hd = d->d_model / d->n_heads;
@@ -110,6 +115,12 @@ size_t carve(sv_ctx* c, char* base) {
   Arena a; a.base = base;
   c->rope_cs = (float*)a.take((size_t)c->max_seq * (c->hd / 2) * 2 * sizeof(float));
   c->score_scratch = (ScorePartial*)a.take(kScoreScratchElems * sizeof(ScorePartial));
+  c->sw_w1 = nullptr; c->sw_proj = nullptr; c->sw_proj_floats = 0;
+  if (c->flags & SV_FLAG_SLICED_W) {
+    c->sw_w1 = (float*)a.take((size_t)kSwMaxClaims * kSwMaxDirs * sizeof(float));
+    c->sw_proj_floats = (size_t)kSwSlots * kSwMaxDirs * (size_t)sw_padded_len(c->max_tokens);
+    c->sw_proj = (float*)a.take(c->sw_proj_floats * sizeof(float));
+  }
   c->xbuf[0] = a.take(T * D * es);
   c->xbuf[1] = a.take(T * D * es);
   c->n = a.take(T * D * es);
@@ -535,6 +546,49 @@ sv_status sv_score_and_flag(sv_ctx* c, const void* claims, int64_t claim_stride,
   if ((T + kScoreTokensPerWG - 1) / kScoreTokensPerWG > kScoreScratchElems) { set_err(c, "T too large for the score scratch"); return SV_EUNSUPPORTED; }
   SV_HIP(c, launch_score(claims, claim_stride, n_claims, ref, ref_stride, claim_dtype, ref_dtype, T, D, metric_mask, tau, reduce,
                          token_scores_out, results_dev, c->score_scratch, kScoreScratchElems, (hipStream_t)stream));
+  return SV_OK;
+}
+
+sv_status sv_sliced_wasserstein(sv_ctx* c, const void* claims, int64_t claim_stride, int32_t n_claims, const void* ref, int64_t ref_stride,
+                                int32_t claim_dtype, int32_t ref_dtype, int64_t T, int32_t D, const void* directions, int32_t L, float tau,
+                                float* sw_out, sv_result* results_dev, void* stream) {
+  if (!c) return SV_EINVAL;
+  if (n_claims < 0 || T < 0 || D < 1 || L < 1) { set_err(c, "negative size"); return SV_EINVAL; }
+  if (!(c->flags & SV_FLAG_SLICED_W)) { set_err(c, "context was created without SV_FLAG_SLICED_W"); return SV_EINVAL; }
+  if (n_claims == 0 || T == 0) return SV_OK;
+  if (!claims || !ref || !directions) { set_err(c, "claims, ref and directions must be non-NULL"); return SV_EINVAL; }
+  if ((claim_dtype != SV_F32 && claim_dtype != SV_BF16) || (ref_dtype != SV_F32 && ref_dtype != SV_BF16)) { set_err(c, "unknown dtype"); return SV_EINVAL; }
+  if (claim_stride < 0 || ref_stride < 0) { set_err(c, "negative stride"); return SV_EINVAL; }
+  if (L % 32 || L > kSwMaxDirs) { set_err(c, "n_dirs must be a multiple of 32, at most %d", kSwMaxDirs); return SV_EUNSUPPORTED; }
+  if (D % 64) { set_err(c, "D must be a multiple of 64"); return SV_EUNSUPPORTED; }
+  if (n_claims > kSwMaxClaims) { set_err(c, "at most %d submissions per call", kSwMaxClaims); return SV_EUNSUPPORTED; }
+  if (T > c->max_tokens) { set_err(c, "T=%lld exceeds the context's max_tokens %lld", (long long)T, (long long)c->max_tokens); return SV_EUNSUPPORTED; }
+  hipStream_t st = (hipStream_t)stream;
+  const int64_t Tpad = sw_padded_len(T);
+  const size_t slot = (size_t)L * (size_t)Tpad;                 // floats of one projected tensor
+  const int64_t n_slots = (int64_t)(c->sw_proj_floats / slot);  // >= kSwSlots by construction
+  const bool shared = ref_stride == 0;
+  const double flop_per = 2.0 * (double)T * D * L;
+  const int ces = claim_dtype == SV_BF16 ? 2 : 4, res = ref_dtype == SV_BF16 ? 2 : 4;
+  if (shared) {
+    SV_OP(c, SV_OP_SW_PROJECT, flop_per, st, launch_sw_project(ref, 0, 1, ref_dtype, directions, L, D, T, Tpad, c->sw_proj, st));
+    SV_OP(c, SV_OP_SW_SORT, 0, st, launch_sw_sort(c->sw_proj, L, T, Tpad, nullptr, 0, L, nullptr, 0, st));
+  }
+  const int group = (int)(shared ? n_slots - 1 : n_slots / 2);
+  for (int first = 0; first < n_claims; first += group) {
+    const int n = n_claims - first < group ? n_claims - first : group;
+    float* pref = c->sw_proj;
+    float* pcl = c->sw_proj + (shared ? slot : (size_t)group * slot);
+    if (!shared) {
+      SV_OP(c, SV_OP_SW_PROJECT, flop_per * n, st,
+            launch_sw_project(at(ref, (int64_t)first * ref_stride, res), ref_stride, n, ref_dtype, directions, L, D, T, Tpad, pref, st));
+      SV_OP(c, SV_OP_SW_SORT, 0, st, launch_sw_sort(pref, n * L, T, Tpad, nullptr, 0, L, nullptr, 0, st));
+    }
+    SV_OP(c, SV_OP_SW_PROJECT, flop_per * n, st,
+          launch_sw_project(at(claims, (int64_t)first * claim_stride, ces), claim_stride, n, claim_dtype, directions, L, D, T, Tpad, pcl, st));
+    SV_OP(c, SV_OP_SW_SORT, 0, st, launch_sw_sort(pcl, n * L, T, Tpad, pref, shared ? 1 : 0, L, c->sw_w1, first * L, st));
+  }
+  SV_HIP(c, launch_sw_finalize(c->sw_w1, n_claims, L, T, tau, sw_out, results_dev, st));
   return SV_OK;
 }
 

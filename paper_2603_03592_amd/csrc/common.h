@@ -100,6 +100,16 @@ hipError_t launch_score(const void* claims, int64_t claim_stride, int n_claims, 
 hipError_t launch_ema(float* m, const void* claims, int64_t claim_stride, int n_claims, int claim_dtype,
                       const uint8_t* flags, int64_t T, int D, float beta, hipStream_t st);
 
+// sw.hip: sliced Wasserstein.  P holds rows of Tpad = sw_padded_len(T) floats, L rows per tensor.
+int64_t sw_padded_len(int64_t T);
+hipError_t launch_sw_project(const void* X, int64_t stride, int count, int dtype, const void* U, int L, int D, int64_t T, int64_t Tpad,
+                             float* P, hipStream_t st);
+// Sort n_seg rows; with ref != nullptr also w1[first_seg + s] = sum_t |row_s[t] - ref_row[t]| (ref rows already sorted).
+hipError_t launch_sw_sort(float* P, int n_seg, int64_t T, int64_t Tpad, const float* ref, int ref_shared, int L, float* w1,
+                          int first_seg, hipStream_t st);
+hipError_t launch_sw_finalize(const float* w1, int n_claims, int L, int64_t T, float tau, float* sw_out, sv_result* results,
+                              hipStream_t st);
+
 // One K-segment of a (possibly multi-segment) product  C = sum_seg A_seg * op(B_seg).
 struct GemmSeg {
   const void* A; int64_t lda;   // [M, K] row-major
