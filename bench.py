@@ -130,7 +130,7 @@ def score_bench(a):
     import stage_inputs as si
     T, D, n = 8192, 4096, 128
     torch.cuda.set_device(0)
-    ver = sv.Verifier(si.TINY.desc, 128, 64)
+    ver = sv.Verifier(si.TINY.desc, T, 64, sliced_w=True)
     g = torch.Generator(device="cuda").manual_seed(0)
     ref = torch.randn((T, D), generator=g, device="cuda", dtype=torch.float32)
     claims = torch.empty((n, T, D), dtype=torch.bfloat16, device="cuda")
@@ -161,6 +161,18 @@ def score_bench(a):
     ms_ema = timed(lambda: ver.ema_update(m, claims, fl, 0.9), a.steps)
     n_clean = int((fl == 0).sum())
     ema_bytes = n_clean * T * D * 2 + 2 * T * D * 4
+    # sliced Wasserstein statistic: 64 directions, the same 128 submissions against the shared reference
+    n_dirs = 64
+    dirs = torch.from_numpy(si.make_directions(D, n_dirs, 0)).cuda().to(torch.bfloat16)
+    sw_out = {}
+    ms_sw = timed(lambda: sw_out.update(v=ver.sliced_wasserstein(claims, refb, dirs, 1e-2)), max(2, a.steps // 4))
+    swv = sw_out["v"].float().cpu().numpy()
+    assert all((swv[i] > 1e-2) == (i % 8 == 3) for i in range(n)), swv[:8]
+    ver.profile_enable(True)
+    ver.sliced_wasserstein(claims, refb, dirs, 1e-2)
+    prof = ver.profile_read()
+    ver.profile_enable(False)
+    sw_bytes = (n + 1) * T * D * 2
     res = {
         "metric": "scored tokens/sec (stand-alone statistic, 128 submissions, shared reference)", "value": n * T / (ms * 1e-3),
         "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": 2, "ms_per_step": ms, "higher_is_better": True,
@@ -170,6 +182,10 @@ def score_bench(a):
                      "unit": "GB/s", "frac": score_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None},
         "rel_l2_only": {"ms": ms_lite, "achieved_GBs": score_bytes / (ms_lite * 1e-3) / 1e9,
                         "frac": score_bytes / (ms_lite * 1e-3) / 1e9 / PEAK_HBM_GBS},
+        "sliced_wasserstein": {"ms": ms_sw, "directions": n_dirs, "achieved_GBs": sw_bytes / (ms_sw * 1e-3) / 1e9,
+                               "frac": sw_bytes / (ms_sw * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                               "project_ms": prof["sw_project"]["ms"], "sort_ms": prof["sw_sort"]["ms"],
+                               "project_GBs": sw_bytes / (prof["sw_project"]["ms"] * 1e-3) / 1e9},
         "ema": {"ms": ms_ema, "clean": n_clean, "achieved_GBs": ema_bytes / (ms_ema * 1e-3) / 1e9,
                 "frac": ema_bytes / (ms_ema * 1e-3) / 1e9 / PEAK_HBM_GBS},
     }

@@ -16,90 +16,138 @@ namespace {
 constexpr int kSortChunkMax = 16384;   // floats sorted in LDS by one workgroup (64 KB)
 
 // ---------------------------------------------------------------------------------------------
-// Projection.  One wave owns 32 tokens and all L = 32 * LB directions; the contraction runs over
-// the feature axis in steps of 16 on v_mfma_f32_32x32x16_bf16 with the directions in the A slot,
-// so a lane ends up with one token (lane & 31) and the directions 8q + 4 (lane >> 5) + r of each
-// block of 32.  Operands go global -> register directly: inside a 64-feature chunk the k index is
-// permuted (lane half h reads the 16-byte pieces 4h .. 4h+3, one per step) so that the four steps
-// of a lane read 64 contiguous bytes of its row; the same permutation is applied to the directions,
-// which leaves the dot product unchanged.
+// Projection.  A workgroup of 4 waves owns 256 tokens (64 per wave, two blocks of 32) and all
+// L = 32 * LB directions; the contraction runs over the feature axis in steps of 16 on
+// v_mfma_f32_32x32x16_bf16 with the directions in the A slot, so a lane ends up with one token
+// (lane & 31) and the directions 8q + 4 (lane >> 5) + r of each block of 32.
+// The signal goes global -> register directly: inside a 64-feature chunk the k index is permuted
+// (lane half h reads the 16-byte pieces 4h .. 4h+3, one per step) so that the four steps of a lane
+// read 64 contiguous bytes of its row; the same permutation is applied to the directions, which
+// leaves the dot product unchanged.  The directions' 64-feature chunk [L, 64] is staged through
+// LDS once per workgroup (double buffered, 16-byte pieces XOR-swizzled by the row) so that L2 sees
+// one read of it per 256 tokens, and the bf16 signal is prefetched one chunk ahead in registers.
 // fp32 signals are split into three bf16 terms (x = hi + mid + lo exactly), three MFMAs per step:
 // every product is exact in fp32, so the result has fp32-accumulation accuracy.
-template <typename E> struct Frag;
-template <> struct Frag<bf16> {
-  bf16x8 v;
-  __device__ __forceinline__ void load(const bf16* p) { v = *reinterpret_cast<const bf16x8*>(p); }
-  template <int LB>
-  __device__ __forceinline__ void mac(const bf16x8 (&u)[LB], f32x16 (&acc)[LB]) const {
+__device__ __forceinline__ int sw_swz(int row) { return (row ^ (row >> 3)) & 7; }
+
+template <int LB>
+__device__ __forceinline__ void mac_bf16(const bf16x8 (&u)[LB], const bf16x8& x, f32x16 (&acc)[LB]) {
 #pragma unroll
-    for (int b = 0; b < LB; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u[b], v, acc[b], 0, 0, 0);
-  }
-};
-template <> struct Frag<float> {
+  for (int b = 0; b < LB; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u[b], x, acc[b], 0, 0, 0);
+}
+
+template <int LB>
+__device__ __forceinline__ void mac_f32(const bf16x8 (&u)[LB], const float* p, f32x16 (&acc)[LB]) {
+  float x[8];
+  load8(p, x);
   bf16x8 hi, mid, lo;
-  __device__ __forceinline__ void load(const float* p) {
-    float x[8];
-    load8(p, x);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const bf16 a = (bf16)x[i];
-      const float r1 = x[i] - (float)a;
-      const bf16 b = (bf16)r1;
-      const float r2 = r1 - (float)b;
-      hi[i] = a; mid[i] = b; lo[i] = (bf16)r2;
-    }
+  for (int i = 0; i < 8; ++i) {
+    const bf16 a = (bf16)x[i];
+    const float r1 = x[i] - (float)a;
+    const bf16 b = (bf16)r1;
+    const float r2 = r1 - (float)b;
+    hi[i] = a; mid[i] = b; lo[i] = (bf16)r2;
   }
-  template <int LB>
-  __device__ __forceinline__ void mac(const bf16x8 (&u)[LB], f32x16 (&acc)[LB]) const {
-#pragma unroll
-    for (int b = 0; b < LB; ++b) {
-      acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u[b], lo, acc[b], 0, 0, 0);
-      acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u[b], mid, acc[b], 0, 0, 0);
-      acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u[b], hi, acc[b], 0, 0, 0);
-    }
-  }
-};
+  mac_bf16<LB>(u, lo, acc);
+  mac_bf16<LB>(u, mid, acc);
+  mac_bf16<LB>(u, hi, acc);
+}
 
 template <typename E, int LB>
 __global__ __launch_bounds__(256) void sw_project_kernel(const E* __restrict__ X, int64_t x_stride, const bf16* __restrict__ U,
                                                          int D, int64_t T, int64_t Tpad, float* __restrict__ P) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l31 = lane & 31, lhi = lane >> 5;
-  const int64_t t0 = ((int64_t)blockIdx.x * 4 + wave) * 32;
-  if (t0 >= Tpad) return;
-  float* out = P + (int64_t)blockIdx.y * (LB * 32) * Tpad;
-  const float inf = __builtin_huge_valf();
-  if (t0 >= T) {                                   // padding rows sort behind every real sample
+  constexpr bool kBf16 = sizeof(E) == 2;
+  __shared__ __attribute__((aligned(16))) char us[2][LB * 32 * 128];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l31 = lane & 31, lhi = lane >> 5;
+  const int64_t t0 = ((int64_t)blockIdx.x * 4 + wave) * 64;
+  const E* xp[2];
+#pragma unroll
+  for (int tb = 0; tb < 2; ++tb) {
+    const int64_t row = min(t0 + tb * 32 + l31, T - 1);          // rows past the end re-read the last one
+    xp[tb] = X + (int64_t)blockIdx.y * x_stride + row * D + lhi * 32;
+  }
+  // staging of the directions' chunk: thread e owns the 16-byte pieces e, e + 256, ... of the [L, 64] tile
+  const bf16* ug[LB];
+  int ul[LB];
+#pragma unroll
+  for (int i = 0; i < LB; ++i) {
+    const int e = tid + 256 * i, r = e >> 3, c = e & 7;
+    ug[i] = U + (int64_t)r * D + c * 8;
+    ul[i] = r * 128 + ((c ^ sw_swz(r)) << 4);
+  }
+  f32x16 acc[2][LB];
+#pragma unroll
+  for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
     for (int b = 0; b < LB; ++b)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) out[(int64_t)(b * 32 + (i >> 2) * 8 + lhi * 4 + (i & 3)) * Tpad + t0 + l31] = inf;
-    return;
+      for (int i = 0; i < 16; ++i) acc[tb][b][i] = 0.0f;
+
+  bf16x8 ureg[LB];
+  bf16x8 xcur[2][4], xnext[2][4];
+#pragma unroll
+  for (int i = 0; i < LB; ++i) *reinterpret_cast<bf16x8*>(us[0] + ul[i]) = *reinterpret_cast<const bf16x8*>(ug[i]);
+  if (kBf16) {
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+      for (int s = 0; s < 4; ++s) xcur[tb][s] = *reinterpret_cast<const bf16x8*>((const bf16*)xp[tb] + s * 8);
   }
-  const int64_t row = min(t0 + l31, T - 1);
-  const E* xp = X + (int64_t)blockIdx.y * x_stride + row * D + lhi * 32;
-  const bf16* up = U + (int64_t)l31 * D + lhi * 32;
-  f32x16 acc[LB];
+  __syncthreads();
+  const int nchunk = D >> 6;
+  for (int kc = 0; kc < nchunk; ++kc) {
+    const int k0 = kc << 6;
+    const bool more = kc + 1 < nchunk;
+    if (more) {
 #pragma unroll
-  for (int b = 0; b < LB; ++b)
+      for (int i = 0; i < LB; ++i) ureg[i] = *reinterpret_cast<const bf16x8*>(ug[i] + k0 + 64);
+      if (kBf16) {
 #pragma unroll
-    for (int i = 0; i < 16; ++i) acc[b][i] = 0.0f;
-  for (int k0 = 0; k0 < D; k0 += 64) {
+        for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+          for (int s = 0; s < 4; ++s) xnext[tb][s] = *reinterpret_cast<const bf16x8*>((const bf16*)xp[tb] + k0 + 64 + s * 8);
+      }
+    }
+    const char* ub = us[kc & 1];
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
-      Frag<E> x;
-      x.load(xp + k0 + s * 8);
       bf16x8 u[LB];
 #pragma unroll
-      for (int b = 0; b < LB; ++b) u[b] = *reinterpret_cast<const bf16x8*>(up + (int64_t)b * 32 * D + k0 + s * 8);
-      x.template mac<LB>(u, acc);
+      for (int b = 0; b < LB; ++b) {
+        const int r = b * 32 + l31;
+        u[b] = *reinterpret_cast<const bf16x8*>(ub + r * 128 + (((lhi * 4 + s) ^ sw_swz(r)) << 4));
+      }
+#pragma unroll
+      for (int tb = 0; tb < 2; ++tb) {
+        if (kBf16) mac_bf16<LB>(u, xcur[tb][s], acc[tb]);
+        else mac_f32<LB>(u, (const float*)xp[tb] + k0 + s * 8, acc[tb]);
+      }
     }
+    if (more) {
+#pragma unroll
+      for (int i = 0; i < LB; ++i) *reinterpret_cast<bf16x8*>(us[(kc + 1) & 1] + ul[i]) = ureg[i];
+      if (kBf16) {
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+          for (int s = 0; s < 4; ++s) xcur[tb][s] = xnext[tb][s];
+      }
+    }
+    __syncthreads();
   }
-  const bool live = t0 + l31 < T;
+  float* out = P + (int64_t)blockIdx.y * (LB * 32) * Tpad;
+  const float inf = __builtin_huge_valf();                       // padding sorts behind every real sample
 #pragma unroll
-  for (int b = 0; b < LB; ++b)
+  for (int tb = 0; tb < 2; ++tb) {
+    const int64_t t = t0 + tb * 32 + l31;
+    if (t >= Tpad) continue;
 #pragma unroll
-    for (int i = 0; i < 16; ++i)
-      out[(int64_t)(b * 32 + (i >> 2) * 8 + lhi * 4 + (i & 3)) * Tpad + t0 + l31] = live ? acc[b][i] : inf;
+    for (int b = 0; b < LB; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        out[(int64_t)(b * 32 + (i >> 2) * 8 + lhi * 4 + (i & 3)) * Tpad + t] = t < T ? acc[tb][b][i] : inf;
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -196,7 +244,7 @@ __global__ void sw_finalize_kernel(const float* __restrict__ w1, int n_claims, i
 template <typename E>
 hipError_t project_dispatch(const void* X, int64_t stride, int count, const void* U, int L, int D, int64_t T, int64_t Tpad, float* P,
                             hipStream_t st) {
-  dim3 grid((unsigned)((Tpad + 127) / 128), (unsigned)count);
+  dim3 grid((unsigned)((Tpad + 255) / 256), (unsigned)count);
   switch (L / 32) {
     case 1: sw_project_kernel<E, 1><<<grid, 256, 0, st>>>((const E*)X, stride, (const bf16*)U, D, T, Tpad, P); break;
     case 2: sw_project_kernel<E, 2><<<grid, 256, 0, st>>>((const E*)X, stride, (const bf16*)U, D, T, Tpad, P); break;

@@ -147,3 +147,35 @@ def test_sweep_point_forward_backward():
     res = ver.read_results(ver.score_and_flag(claims, out["h_hat"], tau={"rel_l2": wl.tau})["result"])
     assert [int(f) for f in res["flag"]] == [int(k != "honest") for k in kinds]
     ver.close()
+
+
+def test_large_shape_sliced_wasserstein_32_submissions():
+    """Omega_SW at the large configuration's signal shape ([8192, 4096] bf16, 64 directions, 32 submissions against one
+    shared reference): every value against the oracle.  The reference here is a synthetic signal of the stage
+    output's shape (the statistic does not depend on where the reference came from)."""
+    import torch
+    import paper_2603_03592_amd as sv
+    from oracle import sentinel_oracle as sn
+    T, D, L, n = 8192, 4096, 64, 32
+    ver = sv.Verifier(si.TINY.desc, T, 64, sliced_w=True)
+    g = np.random.default_rng(0)
+    ref = si.round_to_bf16((1.3 * g.standard_normal((T, D)) + 0.1).astype(np.float32))
+    u = si.make_directions(D, L, 0)
+    kinds = ["honest"] * n
+    for i, slot in enumerate(range(1, n, 4)):
+        kinds[slot] = ["tok_noise", "scale", "sign", "noise"][i % 4]
+    claims_np = [si.make_claim(k, ref, "bf16", seed=i) for i, k in enumerate(kinds)]
+    claims = torch.stack([dev(c, "bf16") for c in claims_np])
+    sw = host(ver.sliced_wasserstein(claims, dev(ref, "bf16"), dev(u, "bf16"), 1e-2))
+    pr = np.sort(ref.astype(np.float64) @ u.astype(np.float64).T, axis=0)
+    scale = float(np.mean(np.abs(pr)))
+    worst = 0.0
+    for i, c in enumerate(claims_np):
+        pc = np.sort(c.astype(np.float64) @ u.astype(np.float64).T, axis=0)
+        want = float(np.mean(np.abs(pc - pr)))            # sentinel_oracle.sliced_wasserstein with the reference's half hoisted
+        if i < 2:
+            assert want == pytest.approx(sn.sliced_wasserstein(c, ref, u), rel=1e-12)
+        assert abs(sw[i] - want) <= 1e-3 * want + 1e-5 * scale, (i, kinds[i], sw[i], want)
+        worst = max(worst, abs(sw[i] - want) / max(want, 1e-30))
+    print(f"large-shape SW: worst relative difference {worst:.2e}; honest {sw[0]:.3e}, scaled {sw[5]:.3e}")
+    ver.close()
