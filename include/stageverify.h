@@ -178,6 +178,46 @@ sv_status sv_sliced_wasserstein(sv_ctx *ctx, const void *claims, int64_t claim_s
                                 int64_t T, int32_t D, const void *directions, int32_t n_dirs, float tau,
                                 float *sw_out, sv_result *results_dev, void *stream);
 
+/* ---- decision policy (host side: plain double arithmetic on the scalar statistics the kernels emit;
+ *      every pointer below is a HOST pointer and no call touches the GPU) -------------------------
+ * Tukey fences around the median of a history window (Eq. tukey_fences) with the multiplier k
+ * adapted to a target false-positive rate (Alg. adaptive_iqr), and the per-stage bookkeeping of
+ * Alg. activation_verification / Alg. gradient_verification.  Readings: percentiles interpolate
+ * linearly between order statistics; "outside" the fences is strict; the narrowing loop runs while
+ * the outside fraction is below alpha / 10; the history keeps its last `window` VALUES; a deviation
+ * of `severe` (paper: 100) times k * IQR from the median bans at once; after t_forgive consecutive
+ * clean steps a worker's counter drops by one and the streak restarts.                          */
+typedef struct {
+  int32_t c;              /* violations that ban a worker (paper: 5)                               */
+  int32_t t_forgive;      /* consecutive clean steps that take one violation back (paper: 100)      */
+  int32_t window;         /* history length l, in values                                            */
+  int32_t n_max;          /* iteration cap of the widening and of the narrowing loop                */
+  double  k0;             /* initial multiplier                                                     */
+  double  alpha;          /* target false-positive rate                                             */
+  double  grow, shrink;   /* gamma_g >= 1, gamma_s in (0, 1]                                        */
+  double  min_dist_mult;  /* Lambda: the fences keep at least |median| * Lambda from the median     */
+  double  eps;            /* floor of the inter-quartile range                                      */
+  double  severe;         /* immediate-ban factor                                                   */
+} sv_policy_cfg;
+typedef struct sv_policy sv_policy;
+
+/* One run of Alg. adaptive_iqr on history[0..n): returns the fences and the adapted multiplier.    */
+sv_status sv_adaptive_iqr(const double *history, int32_t n, double k_prev, const sv_policy_cfg *cfg,
+                          double *lower, double *upper, double *k_out);
+/* State of one verifier for one stage and one signal kind: n_workers counters, n_metrics histories. */
+sv_status sv_policy_create(int32_t n_workers, int32_t n_metrics, const sv_policy_cfg *cfg, sv_policy **out);
+void      sv_policy_destroy(sv_policy *p);
+/* Warm-up iteration: gamma [n_workers, n_metrics] enters the histories, nothing is flagged.         */
+sv_status sv_policy_warmup(sv_policy *p, const double *gamma);
+/* One verified iteration.  skip (nullable) [n_workers]: workers not examined (tainted by another
+ * stage in this iteration, or absent).  tainted_out [n_workers]: 1 for workers tainted here (all 0
+ * when more than half of the active workers were flagged).  A worker is flagged iff for some metric
+ * not (lower < gamma < upper); before any history exists the fences are infinite.                  */
+sv_status sv_policy_step(sv_policy *p, const double *gamma, const uint8_t *skip, uint8_t *tainted_out);
+/* Any output may be NULL: violations/banned [n_workers]; lower/upper/k/history_len [n_metrics].     */
+sv_status sv_policy_state(const sv_policy *p, int32_t *violations, uint8_t *banned, double *lower,
+                          double *upper, double *k, int32_t *history_len);
+
 /* Per-operation timing with HIP events recorded on the caller's stream around each launch.
  * sv_profile_enable(ctx, 1) clears the accumulators and starts recording; (ctx, 0) stops.
  * sv_profile_read waits for the recorded events and returns, per operation class, the summed

@@ -45,6 +45,12 @@ OP_NAMES = ("norm", "gemm_qkv", "rope", "attn", "gemm_o", "gemm_gateup", "gemm_d
             "sw_project", "sw_sort")
 
 
+class PolicyCfgC(C.Structure):
+    _fields_ = [("c", C.c_int32), ("t_forgive", C.c_int32), ("window", C.c_int32), ("n_max", C.c_int32),
+                ("k0", C.c_double), ("alpha", C.c_double), ("grow", C.c_double), ("shrink", C.c_double),
+                ("min_dist_mult", C.c_double), ("eps", C.c_double), ("severe", C.c_double)]
+
+
 class ProfileC(C.Structure):
     _fields_ = [("ms", C.c_double * len(OP_NAMES)), ("flop", C.c_double * len(OP_NAMES)),
                 ("launches", C.c_int64 * len(OP_NAMES))]
@@ -85,6 +91,19 @@ def _load():
     L.sv_profile_read.argtypes = [vp, C.POINTER(ProfileC)]
     L.sv_sliced_wasserstein.restype = C.c_int
     L.sv_sliced_wasserstein.argtypes = [vp, vp, i64, i32, vp, i64, i32, i32, i64, i32, vp, i32, f32, vp, vp, vp]
+    dp, u8p = C.POINTER(C.c_double), C.POINTER(C.c_uint8)
+    L.sv_adaptive_iqr.restype = C.c_int
+    L.sv_adaptive_iqr.argtypes = [dp, i32, C.c_double, C.POINTER(PolicyCfgC), dp, dp, dp]
+    L.sv_policy_create.restype = C.c_int
+    L.sv_policy_create.argtypes = [i32, i32, C.POINTER(PolicyCfgC), C.POINTER(vp)]
+    L.sv_policy_destroy.restype = None
+    L.sv_policy_destroy.argtypes = [vp]
+    L.sv_policy_warmup.restype = C.c_int
+    L.sv_policy_warmup.argtypes = [vp, dp]
+    L.sv_policy_step.restype = C.c_int
+    L.sv_policy_step.argtypes = [vp, dp, u8p, u8p]
+    L.sv_policy_state.restype = C.c_int
+    L.sv_policy_state.argtypes = [vp, C.POINTER(i32), u8p, dp, dp, dp, C.POINTER(i32)]
     L.sv_gemm_bf16.restype = C.c_int
     L.sv_gemm_bf16.argtypes = [vp, i64, vp, i64, i32, vp, i64, i32, i32, i32, i32, vp]
     return L
@@ -105,6 +124,85 @@ def sv_gemm_bf16(a, b, b_is_kn: bool = False, tile: int = 0, out=None):
     if st != SV_OK:
         raise SVError(st, "sv_gemm_bf16")
     return out
+
+
+def _policy_cfg(c=5, t_forgive=100, window=100, k0=1.5, alpha=0.01, grow=1.1, shrink=0.9, n_max=10, min_dist_mult=0.0,
+                eps=1e-3, severe=100.0) -> PolicyCfgC:
+    return PolicyCfgC(int(c), int(t_forgive), int(window), int(n_max), float(k0), float(alpha), float(grow), float(shrink),
+                      float(min_dist_mult), float(eps), float(severe))
+
+
+def _dbl(a):
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    return a, a.ctypes.data_as(C.POINTER(C.c_double))
+
+
+def adaptive_iqr(history, k_prev, alpha, grow, shrink, n_max, min_dist_mult, eps):
+    """One run of the adaptive-multiplier algorithm on a host array; returns (lower, upper, k)."""
+    h, hp = _dbl(history)
+    cfg = _policy_cfg(alpha=alpha, grow=grow, shrink=shrink, n_max=n_max, min_dist_mult=min_dist_mult, eps=eps)
+    lo, up, k = C.c_double(), C.c_double(), C.c_double()
+    st = lib.sv_adaptive_iqr(hp, h.size, float(k_prev), C.byref(cfg), C.byref(lo), C.byref(up), C.byref(k))
+    if st != SV_OK:
+        raise SVError(st, "sv_adaptive_iqr")
+    return lo.value, up.value, k.value
+
+
+class Policy:
+    """One sv_policy: violation counters, bans, histories and fences of one stage and one signal kind (host side)."""
+
+    def __init__(self, n_workers: int, n_metrics: int, **cfg):
+        self.d, self.m = n_workers, n_metrics
+        self._p = C.c_void_p()
+        c = _policy_cfg(**cfg)
+        st = lib.sv_policy_create(n_workers, n_metrics, C.byref(c), C.byref(self._p))
+        if st != SV_OK:
+            raise SVError(st, "sv_policy_create")
+
+    def close(self):
+        if self._p:
+            lib.sv_policy_destroy(self._p)
+            self._p = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _gamma(self, gamma):
+        g, gp = _dbl(gamma)
+        assert g.shape == (self.d, self.m)
+        return g, gp
+
+    def warmup(self, gamma):
+        g, gp = self._gamma(gamma)
+        st = lib.sv_policy_warmup(self._p, gp)
+        if st != SV_OK:
+            raise SVError(st, "sv_policy_warmup")
+
+    def step(self, gamma, skip=None):
+        """Returns the list of workers tainted at this stage in this iteration."""
+        g, gp = self._gamma(gamma)
+        out = np.zeros(self.d, dtype=np.uint8)
+        sk = None if skip is None else np.ascontiguousarray(skip, dtype=np.uint8)
+        u8p = C.POINTER(C.c_uint8)
+        st = lib.sv_policy_step(self._p, gp, None if sk is None else sk.ctypes.data_as(u8p), out.ctypes.data_as(u8p))
+        if st != SV_OK:
+            raise SVError(st, "sv_policy_step")
+        return [int(r) for r in np.nonzero(out)[0]]
+
+    def state(self):
+        v = np.zeros(self.d, dtype=np.int32)
+        b = np.zeros(self.d, dtype=np.uint8)
+        lo, up, k = (np.zeros(self.m, dtype=np.float64) for _ in range(3))
+        n = np.zeros(self.m, dtype=np.int32)
+        dp, u8p, ip = C.POINTER(C.c_double), C.POINTER(C.c_uint8), C.POINTER(C.c_int32)
+        st = lib.sv_policy_state(self._p, v.ctypes.data_as(ip), b.ctypes.data_as(u8p), lo.ctypes.data_as(dp), up.ctypes.data_as(dp),
+                                 k.ctypes.data_as(dp), n.ctypes.data_as(ip))
+        if st != SV_OK:
+            raise SVError(st, "sv_policy_state")
+        return dict(violations=v, banned=b.astype(bool), lower=lo, upper=up, k=k, history_len=n)
 
 
 def _desc_c(desc) -> StageDescC:

@@ -1,0 +1,81 @@
+"""The library's host-side decision policy (sv_adaptive_iqr, sv_policy_*) against the CPU oracle.
+These calls do no GPU work, so the comparison runs without a device: decisions are compared
+exactly, fences and multipliers to the last bit (both sides do the same double arithmetic)."""
+import numpy as np
+import pytest
+
+import paper_2603_03592_amd as sv
+from oracle import sentinel_oracle as so
+
+CFGS = [  # the activation / gradient columns of the paper's configuration table (first and last model)
+    dict(k0=1.5, alpha=0.01, grow=1.1, shrink=0.9, n_max=10, min_dist_mult=0.35, eps=0.01),
+    dict(k0=3.0, alpha=0.001, grow=1.01, shrink=0.99, n_max=10, min_dist_mult=0.15, eps=0.001),
+    dict(k0=3.0, alpha=0.05, grow=1.01, shrink=0.99, n_max=10, min_dist_mult=0.05, eps=0.0001),
+    dict(k0=1.5, alpha=0.2, grow=1.5, shrink=0.8, n_max=10, min_dist_mult=0.0, eps=1e-3),
+]
+
+
+@pytest.mark.parametrize("cfg", CFGS)
+def test_adaptive_iqr_matches_oracle(cfg):
+    rng = np.random.default_rng(0)
+    for trial in range(40):
+        n = int(rng.integers(1, 300))
+        h = rng.standard_normal(n) * rng.uniform(0.001, 10) + rng.uniform(-5, 5)
+        if trial % 5 == 0:
+            h[: n // 2] = h[0]                                   # many ties
+        if trial % 7 == 0:
+            h[rng.integers(0, n)] += 100.0                       # an outlier
+        k_prev = float(rng.uniform(0.3, 4.0))
+        want = so.adaptive_iqr(h, k_prev, cfg["alpha"], cfg["grow"], cfg["shrink"], cfg["n_max"], cfg["min_dist_mult"], cfg["eps"])
+        got = sv.adaptive_iqr(h, k_prev, cfg["alpha"], cfg["grow"], cfg["shrink"], cfg["n_max"], cfg["min_dist_mult"], cfg["eps"])
+        assert got == want, (trial, got, want)
+
+
+def test_adaptive_iqr_hand_worked_example():
+    lo, up, k = sv.adaptive_iqr(np.arange(101.0), 0.5, alpha=0.2, grow=1.5, shrink=0.8, n_max=10, min_dist_mult=0.0, eps=1e-3)
+    assert k == pytest.approx(0.9) and lo == pytest.approx(5.0) and up == pytest.approx(95.0)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_policy_stream_matches_oracle(seed):
+    """A synthetic stream of per-worker statistics: benign noise with a slow drift, transient glitches, one worker
+    that starts attacking, one severe deviation, non-finite values, skip masks.  Every decision must agree."""
+    rng = np.random.default_rng(seed)
+    d, m = 8, 3
+    cfg = dict(CFGS[seed % len(CFGS)], c=5, t_forgive=int(rng.integers(3, 30)), window=int(rng.integers(20, 200)))
+    ref = so.StagePolicy(d, m, **cfg)
+    lib = sv.Policy(d, m, **cfg)
+    base = np.array([1.0, 0.05, 0.3])
+    for t in range(10):
+        g = base * (1 + 0.02 * rng.standard_normal((d, m)))
+        ref.warmup(g); lib.warmup(g)
+    attacker, start = int(rng.integers(0, d)), int(rng.integers(20, 60))
+    for t in range(150):
+        g = base * (1 + 0.0005 * t) * (1 + 0.02 * rng.standard_normal((d, m)))
+        if t >= start:
+            g[attacker, 1] *= 1.0 + rng.uniform(0.5, 3.0)
+        if rng.random() < 0.1:
+            g[rng.integers(0, d), rng.integers(0, m)] *= 2.5      # transient glitch of an honest worker
+        if t == 70:
+            g[(attacker + 1) % d, 0] = 1e6                        # severe: banned at once
+        if t == 90:
+            g[(attacker + 2) % d, 2] = np.nan
+        skip = (rng.random(d) < 0.1) if t % 4 == 0 else None
+        want = ref.step(g, skip)
+        got = lib.step(g, skip)
+        st = lib.state()
+        assert got == want, (t, got, want)
+        assert list(st["violations"]) == ref.v and list(st["banned"]) == ref.banned, t
+        assert list(st["lower"]) == ref.lower and list(st["upper"]) == ref.upper and list(st["k"]) == ref.k, t
+        assert list(st["history_len"]) == [len(h) for h in ref.hist]
+    assert ref.banned[attacker] and ref.banned[(attacker + 1) % d]
+    lib.close()
+
+
+def test_policy_rejects_bad_configuration():
+    with pytest.raises(sv.SVError):
+        sv.Policy(0, 1)
+    with pytest.raises(sv.SVError):
+        sv.Policy(4, 2, grow=0.5)
+    with pytest.raises(sv.SVError):
+        sv.Policy(4, 2, eps=0.0)
