@@ -209,11 +209,14 @@ sv_status sv_policy_create(int32_t n_workers, int32_t n_metrics, const sv_policy
 void      sv_policy_destroy(sv_policy *p);
 /* Warm-up iteration: gamma [n_workers, n_metrics] enters the histories, nothing is flagged.         */
 sv_status sv_policy_warmup(sv_policy *p, const double *gamma);
-/* One verified iteration.  skip (nullable) [n_workers]: workers not examined (tainted by another
- * stage in this iteration, or absent).  tainted_out [n_workers]: 1 for workers tainted here (all 0
- * when more than half of the active workers were flagged).  A worker is flagged iff for some metric
- * not (lower < gamma < upper); before any history exists the fences are infinite.                  */
-sv_status sv_policy_step(sv_policy *p, const double *gamma, const uint8_t *skip, uint8_t *tainted_out);
+/* One verified iteration.  skip (nullable) [n_workers]: workers not examined (tainted by an earlier
+ * stage in this iteration, or absent).  pre_tainted (nullable) [n_workers]: workers that enter this
+ * stage's tainted set without being examined (tainted downstream, backward pass).  tainted_out
+ * [n_workers]: 1 for workers tainted here (all 0 when more than half of the active workers are in the
+ * set).  A worker is flagged iff for some metric not (lower < gamma < upper); before any history
+ * exists the fences are infinite.  Banned workers are ignored whatever the masks say.               */
+sv_status sv_policy_step(sv_policy *p, const double *gamma, const uint8_t *skip, const uint8_t *pre_tainted,
+                         uint8_t *tainted_out);
 /* Any output may be NULL: violations/banned [n_workers]; lower/upper/k/history_len [n_metrics].     */
 sv_status sv_policy_state(const sv_policy *p, int32_t *violations, uint8_t *banned, double *lower,
                           double *upper, double *k, int32_t *history_len);

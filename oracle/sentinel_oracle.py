@@ -14,6 +14,10 @@ What it defines (float64, plain numpy, one function per passage):
 * adaptive_iqr            -- Alg. adaptive_iqr: widen / narrow the multiplier k until the
                              fraction of the history outside the fences matches the target
                              false-positive rate, then enforce a minimum distance from the median.
+* SentinelStream          -- Alg. momentum_verification end to end on a stream of per-stage signals:
+                             warm-up, Gamma against the EMA, the policy, taint propagation between
+                             stages, gradient replacement (Alg. gradient_replacement), EMA updates
+                             over the clean set.
 * StagePolicy             -- the bookkeeping of Alg. activation_verification /
                              Alg. gradient_verification for one stage: violation counters with
                              forgiveness, bans (after c violations, or at once for a deviation
@@ -149,14 +153,20 @@ class StagePolicy:
                 self.hist[i].append(float(g[r, i]))
         self._update_fences()
 
-    def step(self, gamma, skip=None):
+    def step(self, gamma, skip=None, pre_tainted=None):
         """One verified iteration.  gamma [d, m]; skip[r] true for workers that are not examined
-        (already tainted by another stage in this iteration, or absent).  Returns the list of
-        workers tainted at this stage."""
+        (already tainted by another stage in this iteration, or absent); pre_tainted[r] true for
+        workers that enter this stage's tainted set without being examined (tainted downstream, in
+        the backward pass).  Returns the list of workers tainted at this stage."""
         g = np.asarray(gamma, dtype=F64)
         tainted = []
         for r in range(self.d):
-            if self.banned[r] or (skip is not None and skip[r]):
+            if self.banned[r]:
+                continue
+            if pre_tainted is not None and pre_tainted[r]:
+                tainted.append(r)
+                continue
+            if skip is not None and skip[r]:
                 continue
             violated = any((not (g[r, i] > self.lower[i])) or (not (g[r, i] < self.upper[i])) for i in range(self.m))
             if violated:
@@ -178,3 +188,101 @@ class StagePolicy:
         if len(tainted) > 0.5 * active:
             tainted = []
         return tainted
+
+
+# ------------------------------------------------------------------ the whole verifier loop
+def _sgn(a):
+    return (a > 0).astype(np.int8) - (a < 0).astype(np.int8)
+
+
+def global_scores(x, m):
+    """The paper's statistics of one signal against the reference point, each over the whole
+    flattened signal: relative L2, mean absolute difference, z-scored squared distance, sign flip
+    ratio (sign(0) = 0).  A constant side has no z-score: both constant -> 0, one -> 2."""
+    c, r = np.asarray(x, F64).ravel(), np.asarray(m, F64).ravel()
+    out = {"rel_l2": float(np.sqrt(np.sum((c - r) ** 2)) / max(np.sqrt(np.sum(r * r)), 1e-30)),
+           "l1": float(np.mean(np.abs(c - r)))}
+    cc, cr = bool(np.max(c) == np.min(c)), bool(np.max(r) == np.min(r))
+    if cc and cr:
+        out["zl2"] = 0.0
+    elif cc or cr:
+        out["zl2"] = 2.0
+    else:
+        out["zl2"] = float(np.mean(((c - c.mean()) / c.std() - (r - r.mean()) / r.std()) ** 2))
+    out["sfr"] = float(np.mean(_sgn(c) != _sgn(r)))
+    return out
+
+
+class SentinelStream:
+    """Alg. momentum_verification with its three sub-procedures, for p stages and d workers per
+    stage (worker r of every stage belongs to the same data-parallel pipe).  Signals are handed in
+    stage by stage: forward(s, h) for s = 0 .. p-1, then backward(s, g) for s = p-1 .. 0.
+
+    Readings: Gamma uses the whole-signal form of every statistic; in the forward pass a worker whose
+    pipe was tainted at an earlier stage of this iteration is neither examined nor allowed into the
+    EMA (the text's "pause their deviation statistics"; the listing's R_clean alone would let it in);
+    in the backward pass R_clean is the listing's: everything not tainted at this stage; banned
+    workers are never examined and never enter an EMA; m_0 = 0."""
+
+    METRICS = ("rel_l2", "l1", "zl2", "sfr", "sw")
+
+    def __init__(self, n_stages, n_workers, shape, metrics, directions, beta_h, beta_g, policy_h, policy_g):
+        self.p, self.d, self.shape = n_stages, n_workers, tuple(shape)
+        self.metrics = [m for m in self.METRICS if m in metrics]
+        self.dirs = directions
+        self.beta = {"h": beta_h, "g": beta_g}
+        self.m = {k: [np.zeros(self.shape, F64) for _ in range(n_stages)] for k in "hg"}
+        self.pol = {"h": [StagePolicy(n_workers, len(self.metrics), **policy_h) for _ in range(n_stages)],
+                    "g": [StagePolicy(n_workers, len(self.metrics), **policy_g) for _ in range(n_stages)]}
+        self.tainted = set()          # (stage, worker) pairs of the current iteration
+        self.warm = True
+
+    def begin_iteration(self, warmup):
+        self.tainted = set()
+        self.warm = bool(warmup)
+
+    def gamma(self, signals, m):
+        out = np.zeros((self.d, len(self.metrics)), F64)
+        for r, x in enumerate(signals):
+            sc = global_scores(x, m)
+            if "sw" in self.metrics:
+                sc["sw"] = sliced_wasserstein(x, m, self.dirs)
+            out[r] = [sc[k] for k in self.metrics]
+        return out
+
+    def _ema(self, kind, s, signals, excluded):
+        clean = [np.asarray(x, F64).reshape(self.shape) for x, e in zip(signals, excluded) if not e]
+        if clean:
+            b = self.beta[kind]
+            self.m[kind][s] = b * self.m[kind][s] + (1.0 - b) * sum(clean) / len(clean)
+
+    def forward(self, s, h):
+        """Alg. activation_verification + the EMA update of the main loop.  Returns (tainted here, Gamma)."""
+        pol, g = self.pol["h"][s], self.gamma(h, self.m["h"][s])
+        if self.warm:
+            pol.warmup(g)
+            self._ema("h", s, h, [False] * self.d)
+            return [], g
+        upstream = [any((s2, r) in self.tainted for s2 in range(self.p)) for r in range(self.d)]
+        here = pol.step(g, skip=upstream)
+        self.tainted |= {(s, r) for r in here}
+        excluded = [pol.banned[r] or upstream[r] or r in here for r in range(self.d)]
+        self._ema("h", s, h, excluded)
+        return here, g
+
+    def backward(self, s, grads):
+        """Alg. gradient_verification + Alg. gradient_replacement + the EMA update.  grads: list of d
+        arrays; returns (tainted here, Gamma, grads with the tainted ones replaced by m_{t-1}(g))."""
+        pol, g = self.pol["g"][s], self.gamma(grads, self.m["g"][s])
+        if self.warm:
+            pol.warmup(g)
+            self._ema("g", s, grads, [False] * self.d)
+            return [], g, list(grads)
+        down = [any((s2, r) in self.tainted for s2 in range(s + 1, self.p)) for r in range(self.d)]
+        here = pol.step(g, pre_tainted=down)
+        self.tainted |= {(s, r) for r in here}
+        at_stage = [(s, r) in self.tainted for r in range(self.d)]
+        out = [self.m["g"][s].copy() if at_stage[r] else grads[r] for r in range(self.d)]
+        excluded = [pol.banned[r] or at_stage[r] for r in range(self.d)]
+        self._ema("g", s, grads, excluded)
+        return here, g, out

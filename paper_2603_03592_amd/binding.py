@@ -101,7 +101,7 @@ def _load():
     L.sv_policy_warmup.restype = C.c_int
     L.sv_policy_warmup.argtypes = [vp, dp]
     L.sv_policy_step.restype = C.c_int
-    L.sv_policy_step.argtypes = [vp, dp, u8p, u8p]
+    L.sv_policy_step.argtypes = [vp, dp, u8p, u8p, u8p]
     L.sv_policy_state.restype = C.c_int
     L.sv_policy_state.argtypes = [vp, C.POINTER(i32), u8p, dp, dp, dp, C.POINTER(i32)]
     L.sv_gemm_bf16.restype = C.c_int
@@ -181,13 +181,14 @@ class Policy:
         if st != SV_OK:
             raise SVError(st, "sv_policy_warmup")
 
-    def step(self, gamma, skip=None):
+    def step(self, gamma, skip=None, pre_tainted=None):
         """Returns the list of workers tainted at this stage in this iteration."""
         g, gp = self._gamma(gamma)
         out = np.zeros(self.d, dtype=np.uint8)
-        sk = None if skip is None else np.ascontiguousarray(skip, dtype=np.uint8)
         u8p = C.POINTER(C.c_uint8)
-        st = lib.sv_policy_step(self._p, gp, None if sk is None else sk.ctypes.data_as(u8p), out.ctypes.data_as(u8p))
+        masks = [None if a is None else np.ascontiguousarray(a, dtype=np.uint8) for a in (skip, pre_tainted)]
+        sk, pt = (None if a is None else a.ctypes.data_as(u8p) for a in masks)
+        st = lib.sv_policy_step(self._p, gp, sk, pt, out.ctypes.data_as(u8p))
         if st != SV_OK:
             raise SVError(st, "sv_policy_step")
         return [int(r) for r in np.nonzero(out)[0]]

@@ -121,12 +121,14 @@ sv_status sv_policy_warmup(sv_policy* p, const double* gamma) {
   return SV_OK;
 }
 
-sv_status sv_policy_step(sv_policy* p, const double* gamma, const uint8_t* skip, uint8_t* tainted_out) {
+sv_status sv_policy_step(sv_policy* p, const double* gamma, const uint8_t* skip, const uint8_t* pre_tainted, uint8_t* tainted_out) {
   if (!p || !gamma || !tainted_out) return SV_EINVAL;
   int n_tainted = 0;
   for (int r = 0; r < p->d; ++r) {
     tainted_out[r] = 0;
-    if (p->banned[r] || (skip && skip[r])) continue;
+    if (p->banned[r]) continue;
+    if (pre_tainted && pre_tainted[r]) { tainted_out[r] = 1; ++n_tainted; continue; }
+    if (skip && skip[r]) continue;
     const double* g = gamma + (size_t)r * p->m;
     bool violated = false, severe = false;
     for (int i = 0; i < p->m; ++i) {

@@ -153,6 +153,18 @@ def make_directions(d_model: int, n_dirs: int, seed: int = 0) -> np.ndarray:
     return round_to_bf16(u.astype(np.float32))
 
 
+def stream_signal(kind: str, stage: int, worker: int, t: int, T: int, D: int, dtype: str, seed: int = 0,
+                  drift: float = 1e-3) -> np.ndarray:
+    """Synthetic stand-in for what worker `worker` of pipeline stage `stage` sends at iteration t: a
+    per-stage mean signal that drifts slowly with t plus an independent mini-batch component of
+    half its scale.  kind "h": activations of unit scale; "g": activation gradients of scale 1e-3."""
+    scale = 1.0 if kind == "h" else 1e-3
+    base = _rng(seed, 1000 + 2 * stage + (kind == "g")).standard_normal((T, D))
+    own = _rng(seed, 100_000 + ((t * 64 + stage) * 1024 + worker) * 2 + (kind == "g")).standard_normal((T, D))
+    x = scale * ((1.0 + drift * t) * base + 0.5 * own)
+    return to_stage_dtype(x.astype(np.float32), dtype)
+
+
 def honest_claim(reference: np.ndarray, dtype: str) -> np.ndarray:
     """What an honest worker sends: the true signal in the stage's storage dtype."""
     return to_stage_dtype(np.asarray(reference, dtype=np.float32), dtype)

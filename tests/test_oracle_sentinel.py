@@ -226,3 +226,126 @@ def test_policy_window_and_adaptation_track_a_drifting_statistic():
     g = 1.4 + 0.01 * rng.standard_normal((8, 1))
     g[5] = 3.0
     assert p.step(g) == [5]
+
+
+# ------------------------------------------------------------------ Alg. momentum_verification end to end
+import stage_inputs as si
+
+P, DW, T, D = 3, 6, 32, 64
+POLICY = dict(c=5, t_forgive=100, window=100, k0=1.5, alpha=0.01, grow=1.1, shrink=0.9, n_max=10, min_dist_mult=0.35, eps=1e-4)
+
+
+def _stream(metrics=("rel_l2", "l1", "zl2", "sfr", "sw")):
+    return so.SentinelStream(P, DW, (T, D), metrics, si.make_directions(D, 32, 0), 0.9, 0.8, POLICY, POLICY)
+
+
+def _signals(kind, s, t, attack=None):
+    """attack = (stage, worker, kind): that worker's signal is corrupted; in the forward pass the same
+    pipe's later stages carry a contaminated (noisy) signal as well."""
+    out = [si.stream_signal(kind, s, r, t, T, D, "f32") for r in range(DW)]
+    if attack is not None:
+        a_s, a_r, a_kind = attack
+        if s == a_s:
+            out[a_r] = si.make_claim(a_kind, out[a_r], "f32", seed=t)
+        elif kind == "h" and s > a_s:
+            out[a_r] = si.make_claim("noise", out[a_r] * 1.2, "f32", seed=t)
+    return out
+
+
+def _run(st, t, warm, attack_h=None, attack_g=None):
+    st.begin_iteration(warm)
+    rec = {"h": [], "g": [None] * P, "out": [None] * P, "m_g_before": [m.copy() for m in st.m["g"]]}
+    for s in range(P):
+        rec["h"].append(st.forward(s, _signals("h", s, t, attack_h))[0])
+    for s in reversed(range(P)):
+        g = _signals("g", s, t, attack_g)
+        here, _, out = st.backward(s, g)
+        rec["g"][s], rec["out"][s], rec.setdefault("g_in", {})[s] = here, out, g
+    return rec
+
+
+def test_stream_warmup_ema_closed_form_and_nothing_flagged():
+    st = _stream(metrics=("l1", "sfr"))
+    x = si.stream_signal("h", 0, 0, 0, T, D, "f32").astype(np.float64)
+    for t in range(6):
+        st.begin_iteration(True)
+        here, gam = st.forward(0, [x] * DW)
+        assert here == [] and gam.shape == (DW, 2)
+        np.testing.assert_allclose(st.m["h"][0], (1 - 0.9 ** (t + 1)) * x, rtol=1e-12)
+        # the statistic of x against (1 - beta^t) x: mean |x| beta^t and no sign flips (first step: reference 0)
+        assert gam[0, 0] == pytest.approx(0.9 ** t * np.mean(np.abs(x)), rel=1e-12)
+        assert gam[0, 1] == (1.0 if t == 0 else 0.0)
+    assert len(st.pol["h"][0].hist[0]) == 6 * DW and st.pol["h"][0].v == [0] * DW
+
+
+WARM = 40      # iterations until the EMAs (beta 0.9 / 0.8, m_0 = 0) have converged and the 100-value windows hold settled values
+
+
+def _warm(st):
+    for t in range(WARM):
+        _run(st, t, True)
+
+
+def test_stream_activation_attack_is_caught_and_does_not_cascade():
+    st = _stream()
+    _warm(st)
+    for t in range(WARM, WARM + 2):
+        rec = _run(st, t, False)
+        assert rec["h"] == [[], [], []] and rec["g"] == [[], [], []]
+    m_h1 = st.m["h"][1].copy()
+    attack = (1, 2, "sign")
+    for n_att, t in enumerate(range(WARM + 2, WARM + 7), start=1):
+        rec = _run(st, t, False, attack_h=attack)
+        # caught where it happens; the contaminated later stage of the same pipe is neither examined nor blamed
+        assert rec["h"] == [[], [2], []]
+        assert st.pol["h"][1].v[2] == n_att and st.pol["h"][2].v[2] == 0
+        # the EMA of stage 1 is the mean of the five other workers
+        sig = _signals("h", 1, t, attack)
+        m_h1 = 0.9 * m_h1 + 0.1 * np.mean([np.float64(sig[r]) for r in range(DW) if r != 2], axis=0)
+        np.testing.assert_allclose(st.m["h"][1], m_h1, rtol=1e-12, atol=1e-15)
+        # backward: stage 2 examines the pipe as usual (its gradient is honest here); stage 1 holds the forward
+        # taint and stage 0 sees it as tainted downstream: both hand on the gradient EMA of before this iteration
+        assert rec["g"] == [[2], [], []]
+        for s in (0, 1):
+            assert np.array_equal(rec["out"][s][2], rec["m_g_before"][s])
+            assert all(rec["out"][s][r] is rec["g_in"][s][r] for r in range(DW) if r != 2)
+        assert all(rec["out"][2][r] is rec["g_in"][2][r] for r in range(DW))
+    assert st.pol["h"][1].banned[2]                       # fifth violation
+    assert not st.pol["g"][0].banned[2] and st.pol["g"][0].v[2] == 0    # marked, never examined, never blamed
+    rec = _run(st, WARM + 7, False, attack_h=attack)
+    assert rec["h"][1] == []                              # a banned worker is no longer collected
+
+
+def test_stream_gradient_attack_taints_upstream_stages_only():
+    st = _stream()
+    _warm(st)
+    rec = _run(st, WARM, False, attack_g=(1, 4, "scale"))
+    assert rec["h"] == [[], [], []]
+    assert rec["g"][2] == [] and rec["g"][1] == [4] and rec["g"][0] == [4]
+    assert np.array_equal(rec["out"][1][4], rec["m_g_before"][1]) and np.array_equal(rec["out"][0][4], rec["m_g_before"][0])
+    assert st.pol["g"][1].v[4] == 1 and st.pol["g"][0].v[4] == 0
+    # severe deviation: banned at once
+    rec = _run(st, WARM + 1, False, attack_g=(2, 0, "zero"))
+    big = [x.copy() for x in _signals("g", 2, WARM + 2)]
+    big[3] = big[3] * 1e6
+    st.begin_iteration(False)
+    for s in range(P):
+        st.forward(s, _signals("h", s, WARM + 2))
+    here, gam, out = st.backward(2, big)
+    assert here == [3] and st.pol["g"][2].banned[3] and st.pol["g"][2].v[3] == 1
+
+
+def test_stream_majority_deviation_is_a_distribution_shift():
+    st = _stream(metrics=("l1", "zl2"))
+    _warm(st)
+    st.begin_iteration(False)
+    h = _signals("h", 0, WARM)
+    for r in range(4):                                    # four of six shift together
+        h[r] = h[r] * 1.5
+    m0 = st.m["h"][0].copy()
+    here, _ = st.forward(0, h)
+    assert here == [] and st.tainted == set()
+    assert st.pol["h"][0].v == [1, 1, 1, 1, 0, 0]         # the listing clears the set, not the counters
+    # ... and the listing's clean set then lets nobody in that was flagged: only the two un-flagged enter the EMA? No:
+    # the set was emptied, so every worker of the stage is clean again.
+    np.testing.assert_allclose(st.m["h"][0], 0.9 * m0 + 0.1 * np.mean([np.float64(x) for x in h], axis=0), rtol=1e-12, atol=1e-15)

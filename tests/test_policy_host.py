@@ -61,8 +61,9 @@ def test_policy_stream_matches_oracle(seed):
         if t == 90:
             g[(attacker + 2) % d, 2] = np.nan
         skip = (rng.random(d) < 0.1) if t % 4 == 0 else None
-        want = ref.step(g, skip)
-        got = lib.step(g, skip)
+        pre = (rng.random(d) < (0.6 if t == 120 else 0.1)) if t % 5 == 0 else None
+        want = ref.step(g, skip, pre)
+        got = lib.step(g, skip, pre)
         st = lib.state()
         assert got == want, (t, got, want)
         assert list(st["violations"]) == ref.v and list(st["banned"]) == ref.banned, t
