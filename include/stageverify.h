@@ -221,6 +221,59 @@ sv_status sv_policy_step(sv_policy *p, const double *gamma, const uint8_t *skip,
 sv_status sv_policy_state(const sv_policy *p, int32_t *violations, uint8_t *banned, double *lower,
                           double *upper, double *k, int32_t *history_len);
 
+/* Alg. gradient_replacement: every signal i in [0, n) with mask_dev[i] != 0 is overwritten with the
+ * reference point m [T, D] float (rounded to the signal's dtype); the others are left alone.
+ * signals: device, n tensors [T, D] at signals + i*stride elements; mask_dev: device, n bytes.
+ * D must be a multiple of 8; n <= 65535.                                                          */
+sv_status sv_replace_with_ema(sv_ctx *ctx, void *signals, int64_t stride, int32_t n, int32_t dtype,
+                              const uint8_t *mask_dev, const float *m, int64_t T, int32_t D, void *stream);
+
+/* ---- the whole verifier loop (Alg. momentum_verification with Alg. activation_verification,
+ *      Alg. gradient_verification and Alg. gradient_replacement) for n_stages pipeline stages with
+ *      n_workers workers each; worker r of every stage belongs to data-parallel pipe r.
+ * Per stage and signal kind the object owns an EMA m [T, D] float on the device (m_0 = 0) and a
+ * decision policy on the host.  One iteration is: sv_sentinel_begin_iteration, sv_sentinel_forward for
+ * stage 0 .. n_stages-1, sv_sentinel_backward for stage n_stages-1 .. 0.  A forward / backward call
+ *   1. computes Gamma [n_workers, n_metrics] of the workers' signals against the EMA (whole-signal
+ *      form of every enabled statistic, columns in the order rel-L2, L1, z-scored L2, sign flips, SW),
+ *   2. waits for the stream and runs the policy (warm-up: every value enters the history; else: workers
+ *      of a pipe tainted at an earlier stage of this iteration are not examined (forward), workers of a
+ *      pipe tainted at a later stage are tainted without examination (backward)),
+ *   3. backward only: overwrites the gradient of every worker tainted at this stage in this iteration
+ *      (forward or backward) with the gradient EMA of before this call,
+ *   4. updates the EMA over the clean set: forward -- not banned, pipe not tainted so far in this
+ *      iteration; backward -- not banned, not tainted at this stage.
+ * signals: device, [n_workers, T, D] contiguous; tainted_out: HOST, n_workers bytes; gamma_out: HOST,
+ * nullable, [n_workers, n_metrics] doubles.  `directions` (device, bf16 [n_dirs, D]) must stay valid
+ * while the object lives; SV_M_SW needs a context created with SV_FLAG_SLICED_W and max_tokens >= T.
+ * The context must outlive the object; calls on one object must not overlap.                        */
+typedef struct {
+  int32_t n_stages, n_workers;
+  int64_t T;
+  int32_t D;
+  uint32_t metric_mask;            /* SV_M_RELL2 | SV_M_L1 | SV_M_ZL2 | SV_M_SFR | SV_M_SW, at least one */
+  int32_t n_dirs;
+  const void *directions;
+  float beta_h, beta_g;            /* EMA coefficients of activations / gradients                      */
+  sv_policy_cfg policy_h, policy_g;
+} sv_sentinel_cfg;
+typedef struct sv_sentinel sv_sentinel;
+sv_status sv_sentinel_create(sv_ctx *ctx, const sv_sentinel_cfg *cfg, sv_sentinel **out);
+void      sv_sentinel_destroy(sv_sentinel *s);
+const char *sv_sentinel_last_error(const sv_sentinel *s);
+sv_status sv_sentinel_begin_iteration(sv_sentinel *s, int32_t warmup);
+sv_status sv_sentinel_forward(sv_sentinel *s, int32_t stage, const void *h, int32_t dtype, uint8_t *tainted_out,
+                              double *gamma_out, void *stream);
+sv_status sv_sentinel_backward(sv_sentinel *s, int32_t stage, void *g, int32_t dtype, uint8_t *tainted_out,
+                               double *gamma_out, void *stream);
+/* kind 0 = activations, 1 = gradients.  Any output may be NULL: *ema_dev = the device EMA (owned by the
+ * object); violations/banned [n_workers]; lower/upper/k [n_metrics] (HOST).                          */
+sv_status sv_sentinel_state(const sv_sentinel *s, int32_t stage, int32_t kind, const float **ema_dev,
+                            int32_t *violations, uint8_t *banned, double *lower, double *upper, double *k);
+
+/* Copies the EMA of (stage, kind) to out_host (HOST, T*D floats) after the work queued on `stream`.   */
+sv_status sv_sentinel_read_ema(sv_sentinel *s, int32_t stage, int32_t kind, float *out_host, void *stream);
+
 /* Per-operation timing with HIP events recorded on the caller's stream around each launch.
  * sv_profile_enable(ctx, 1) clears the accumulators and starts recording; (ctx, 0) stops.
  * sv_profile_read waits for the recorded events and returns, per operation class, the summed

@@ -51,6 +51,12 @@ class PolicyCfgC(C.Structure):
                 ("min_dist_mult", C.c_double), ("eps", C.c_double), ("severe", C.c_double)]
 
 
+class SentinelCfgC(C.Structure):
+    _fields_ = [("n_stages", C.c_int32), ("n_workers", C.c_int32), ("T", C.c_int64), ("D", C.c_int32), ("metric_mask", C.c_uint32),
+                ("n_dirs", C.c_int32), ("directions", C.c_void_p), ("beta_h", C.c_float), ("beta_g", C.c_float),
+                ("policy_h", PolicyCfgC), ("policy_g", PolicyCfgC)]
+
+
 class ProfileC(C.Structure):
     _fields_ = [("ms", C.c_double * len(OP_NAMES)), ("flop", C.c_double * len(OP_NAMES)),
                 ("launches", C.c_int64 * len(OP_NAMES))]
@@ -104,6 +110,24 @@ def _load():
     L.sv_policy_step.argtypes = [vp, dp, u8p, u8p, u8p]
     L.sv_policy_state.restype = C.c_int
     L.sv_policy_state.argtypes = [vp, C.POINTER(i32), u8p, dp, dp, dp, C.POINTER(i32)]
+    L.sv_replace_with_ema.restype = C.c_int
+    L.sv_replace_with_ema.argtypes = [vp, vp, i64, i32, i32, vp, vp, i64, i32, vp]
+    L.sv_sentinel_create.restype = C.c_int
+    L.sv_sentinel_create.argtypes = [vp, C.POINTER(SentinelCfgC), C.POINTER(vp)]
+    L.sv_sentinel_destroy.restype = None
+    L.sv_sentinel_destroy.argtypes = [vp]
+    L.sv_sentinel_last_error.restype = C.c_char_p
+    L.sv_sentinel_last_error.argtypes = [vp]
+    L.sv_sentinel_begin_iteration.restype = C.c_int
+    L.sv_sentinel_begin_iteration.argtypes = [vp, i32]
+    L.sv_sentinel_forward.restype = C.c_int
+    L.sv_sentinel_forward.argtypes = [vp, i32, vp, i32, u8p, dp, vp]
+    L.sv_sentinel_backward.restype = C.c_int
+    L.sv_sentinel_backward.argtypes = [vp, i32, vp, i32, u8p, dp, vp]
+    L.sv_sentinel_state.restype = C.c_int
+    L.sv_sentinel_state.argtypes = [vp, i32, i32, C.POINTER(vp), C.POINTER(i32), u8p, dp, dp, dp]
+    L.sv_sentinel_read_ema.restype = C.c_int
+    L.sv_sentinel_read_ema.argtypes = [vp, i32, i32, C.POINTER(f32), vp]
     L.sv_gemm_bf16.restype = C.c_int
     L.sv_gemm_bf16.argtypes = [vp, i64, vp, i64, i32, vp, i64, i32, i32, i32, i32, vp]
     return L
@@ -373,6 +397,14 @@ class Verifier:
                                               self._stream()))
         return sw
 
+    def replace_with_ema(self, signals, mask_dev, m):
+        """signals [n, T, D] updated in place: signal i becomes m (rounded) where mask_dev[i] != 0."""
+        n, D = signals.shape[0], signals.shape[-1]
+        T = signals[0].numel() // D
+        assert signals.is_contiguous() and m.dtype == self.torch.float32 and m.numel() == T * D and mask_dev.dtype == self.torch.uint8
+        self._check(lib.sv_replace_with_ema(self._ctx, _ptr(signals), T * D, n, _dt(signals), _ptr(mask_dev), _ptr(m), T, D, self._stream()))
+        return signals
+
     def ema_update(self, m, claims, flags_dev, beta: float):
         """m [T, D] float32 updated in place from claims [n, T, D]; flags_dev: uint8 [n] on the device or None."""
         n, D = claims.shape[0], claims.shape[-1]
@@ -381,3 +413,75 @@ class Verifier:
         self._check(lib.sv_ema_update(self._ctx, _ptr(m), _ptr(claims), T * D, n, _dt(claims), _ptr(flags_dev), T, D, float(beta),
                                       self._stream()))
         return m
+
+
+METRIC_ORDER = ("rel_l2", "l1", "zl2", "sfr", "sw")
+
+
+class Sentinel:
+    """One sv_sentinel: the verifier loop over n_stages x n_workers with EMAs on the device and the policy on the host."""
+
+    def __init__(self, verifier: Verifier, n_stages: int, n_workers: int, T: int, D: int, metrics, directions=None,
+                 beta_h: float = 0.9, beta_g: float = 0.8, policy_h=None, policy_g=None):
+        self.ver, self.p, self.d, self.T, self.D = verifier, n_stages, n_workers, T, D
+        self.metrics = [m for m in METRIC_ORDER if m in metrics]
+        mask = sum(1 << METRIC_ORDER.index(m) for m in self.metrics)
+        self._dirs = directions                      # kept alive: the library retains the pointer
+        cfg = SentinelCfgC(n_stages, n_workers, T, D, mask, 0 if directions is None else directions.shape[0],
+                           None if directions is None else directions.data_ptr(), beta_h, beta_g,
+                           _policy_cfg(**(policy_h or {})), _policy_cfg(**(policy_g or {})))
+        self._s = C.c_void_p()
+        st = lib.sv_sentinel_create(verifier._ctx, C.byref(cfg), C.byref(self._s))
+        if st != SV_OK:
+            raise SVError(st, "sv_sentinel_create")
+
+    def close(self):
+        if self._s:
+            lib.sv_sentinel_destroy(self._s)
+            self._s = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, st):
+        if st != SV_OK:
+            raise SVError(st, lib.sv_sentinel_last_error(self._s).decode())
+
+    def begin_iteration(self, warmup: bool):
+        self._check(lib.sv_sentinel_begin_iteration(self._s, int(bool(warmup))))
+
+    def _call(self, fn, stage, signals):
+        assert signals.is_contiguous() and signals.shape[0] == self.d and signals[0].numel() == self.T * self.D
+        tainted = np.zeros(self.d, dtype=np.uint8)
+        gamma = np.zeros((self.d, len(self.metrics)), dtype=np.float64)
+        self._check(fn(self._s, stage, _ptr(signals), _dt(signals), tainted.ctypes.data_as(C.POINTER(C.c_uint8)),
+                       gamma.ctypes.data_as(C.POINTER(C.c_double)), self.ver._stream()))
+        return [int(r) for r in np.nonzero(tainted)[0]], gamma
+
+    def forward(self, stage: int, h):
+        """h [n_workers, T, D]; returns (workers tainted at this stage, Gamma)."""
+        return self._call(lib.sv_sentinel_forward, stage, h)
+
+    def backward(self, stage: int, g):
+        """g [n_workers, T, D], tainted workers' gradients are replaced in place; returns (tainted, Gamma)."""
+        return self._call(lib.sv_sentinel_backward, stage, g)
+
+    def state(self, stage: int, kind: str):
+        v = np.zeros(self.d, dtype=np.int32)
+        b = np.zeros(self.d, dtype=np.uint8)
+        lo, up, k = (np.zeros(len(self.metrics), dtype=np.float64) for _ in range(3))
+        ema = C.c_void_p()
+        dp, u8p, ip = C.POINTER(C.c_double), C.POINTER(C.c_uint8), C.POINTER(C.c_int32)
+        self._check(lib.sv_sentinel_state(self._s, stage, 0 if kind == "h" else 1, C.byref(ema), v.ctypes.data_as(ip), b.ctypes.data_as(u8p),
+                                          lo.ctypes.data_as(dp), up.ctypes.data_as(dp), k.ctypes.data_as(dp)))
+        return dict(ema_ptr=ema.value, violations=v, banned=b.astype(bool), lower=lo, upper=up, k=k)
+
+    def ema(self, stage: int, kind: str) -> np.ndarray:
+        """A host copy of the stage's EMA, [T, D] float32."""
+        out = np.empty((self.T, self.D), dtype=np.float32)
+        self._check(lib.sv_sentinel_read_ema(self._s, stage, 0 if kind == "h" else 1, out.ctypes.data_as(C.POINTER(C.c_float)),
+                                             self.ver._stream()))
+        return out

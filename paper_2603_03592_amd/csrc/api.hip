@@ -607,6 +607,19 @@ sv_status sv_ema_update(sv_ctx* c, float* m, const void* claims, int64_t claim_s
   return SV_OK;
 }
 
+sv_status sv_replace_with_ema(sv_ctx* c, void* signals, int64_t stride, int32_t n, int32_t dtype, const uint8_t* mask_dev, const float* m,
+                              int64_t T, int32_t D, void* stream) {
+  if (!c) return SV_EINVAL;
+  if (n < 0 || T < 0 || D < 1 || stride < 0) { set_err(c, "negative size"); return SV_EINVAL; }
+  if (n == 0 || T == 0) return SV_OK;
+  if (!signals || !mask_dev || !m) { set_err(c, "signals, mask_dev and m must be non-NULL"); return SV_EINVAL; }
+  if (dtype != SV_F32 && dtype != SV_BF16) { set_err(c, "unknown dtype"); return SV_EINVAL; }
+  if (D % 8) { set_err(c, "D must be a multiple of 8"); return SV_EUNSUPPORTED; }
+  if (n > 65535) { set_err(c, "at most 65535 signals per call"); return SV_EUNSUPPORTED; }
+  SV_HIP(c, launch_replace(signals, stride, n, dtype, mask_dev, m, T, D, (hipStream_t)stream));
+  return SV_OK;
+}
+
 sv_status sv_gemm_bf16(const void* A, int64_t lda, const void* B, int64_t ldb, int32_t b_is_kn, void* Cout, int64_t ldc, int32_t M,
                        int32_t N, int32_t K, int32_t tile, void* stream) {
   if (!A || !B || !Cout || M < 1 || N < 1 || K < 1 || tile < 0 || tile > 3) return SV_EINVAL;

@@ -100,6 +100,9 @@ hipError_t launch_score(const void* claims, int64_t claim_stride, int n_claims, 
 hipError_t launch_ema(float* m, const void* claims, int64_t claim_stride, int n_claims, int claim_dtype,
                       const uint8_t* flags, int64_t T, int D, float beta, hipStream_t st);
 
+hipError_t launch_replace(void* signals, int64_t stride, int n, int dtype, const uint8_t* mask, const float* m, int64_t T, int D,
+                          hipStream_t st);
+
 // sw.hip: sliced Wasserstein.  P holds rows of Tpad = sw_padded_len(T) floats, L rows per tensor.
 int64_t sw_padded_len(int64_t T);
 hipError_t launch_sw_project(const void* X, int64_t stride, int count, int dtype, const void* U, int L, int D, int64_t T, int64_t Tpad,

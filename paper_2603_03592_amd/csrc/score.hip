@@ -259,6 +259,29 @@ hipError_t launch_score(const void* claims, int64_t claim_stride, int n_claims, 
   return hipGetLastError();
 }
 
+// Alg. gradient_replacement: every signal whose mask byte is set is overwritten with the reference point m
+// (rounded to the signal's dtype); the others are left alone.  One workgroup handles 256 x 8 elements of one signal.
+template <typename E>
+__global__ __launch_bounds__(256) void replace_kernel(E* __restrict__ signals, int64_t stride, const uint8_t* __restrict__ mask,
+                                                      const float* __restrict__ m, int64_t n_vec) {
+  if (mask[blockIdx.y] == 0) return;
+  const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (v >= n_vec) return;
+  float x[8];
+  load8(m + v * 8, x);
+  store8(signals + (int64_t)blockIdx.y * stride + v * 8, x);
+}
+
+hipError_t launch_replace(void* signals, int64_t stride, int n, int dtype, const uint8_t* mask, const float* m, int64_t T, int D,
+                          hipStream_t st) {
+  if (n <= 0 || T <= 0) return hipSuccess;
+  const int64_t n_vec = T * D / 8;
+  const dim3 grid((unsigned)((n_vec + 255) / 256), (unsigned)n), block(256);
+  if (dtype == SV_BF16) hipLaunchKernelGGL(replace_kernel<bf16>, grid, block, 0, st, (bf16*)signals, stride, mask, m, n_vec);
+  else hipLaunchKernelGGL(replace_kernel<float>, grid, block, 0, st, (float*)signals, stride, mask, m, n_vec);
+  return hipGetLastError();
+}
+
 hipError_t launch_ema(float* m, const void* claims, int64_t claim_stride, int n_claims, int claim_dtype,
                       const uint8_t* flags, int64_t T, int D, float beta, hipStream_t st) {
   if (n_claims <= 0 || T <= 0) return hipSuccess;
