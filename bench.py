@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--score-bench", action="store_true",
                     help="instead of the stage check, time the stand-alone scoring pass (128 submissions against one shared "
                          "reference) and the EMA update, and report them against the HBM roofline")
+    ap.add_argument("--loop-bench", action="store_true",
+                    help="instead of the recompute check, time the paper's own verifier loop (statistics against the EMA, policy, "
+                         "gradient replacement, EMA update) for 4 stages x 16 workers of the large stage's signal shape")
     ap.add_argument("--sweep", action="store_true",
                     help="run the throughput sweep (single block, d_model 4096, seq x micro-batch grid, fwd+bwd) and print one "
                          "JSON line per point")
@@ -193,6 +196,62 @@ def score_bench(a):
     print(json.dumps(res))
 
 
+def loop_bench(a):
+    """The paper's verifier loop (EMA reference instead of recomputation): 4 stages x 16 workers, signals [8192, 4096] bf16,
+    all five statistics (64 directions for the sliced Wasserstein distance).  A step is one iteration: forward over the
+    stages, then backward; the signals are resident in HBM (one set per stage and kind, reused every iteration)."""
+    import torch
+    import paper_2603_03592_amd as sv
+    import stage_inputs as si
+    P_, d, T, D = 4, 16, 8192, 4096
+    torch.cuda.set_device(0)
+    ver = sv.Verifier(si.TINY.desc, T, 64, sliced_w=True)
+    dirs = torch.from_numpy(si.make_directions(D, 64, 0)).cuda().to(torch.bfloat16)
+    pol = dict(c=5, t_forgive=100, window=100, k0=1.5, alpha=0.01, grow=1.1, shrink=0.9, n_max=10, min_dist_mult=0.35, eps=1e-4)
+    loop = sv.Sentinel(ver, P_, d, T, D, ("rel_l2", "l1", "zl2", "sfr", "sw"), dirs, 0.9, 0.8, pol, pol)
+    g = torch.Generator(device="cuda").manual_seed(0)
+    sig = {}
+    for kind, scale in (("h", 1.0), ("g", 1e-3)):
+        for s_ in range(P_):
+            base = torch.randn((T, D), generator=g, device="cuda", dtype=torch.float32)
+            x = torch.empty((d, T, D), dtype=torch.bfloat16, device="cuda")
+            for r in range(d):
+                x[r] = (scale * (base + 0.5 * torch.randn((T, D), generator=g, device="cuda", dtype=torch.float32))).to(torch.bfloat16)
+            sig[kind, s_] = x
+
+    def iteration(warm):
+        loop.begin_iteration(warm)
+        flagged = 0
+        for s_ in range(P_):
+            flagged += len(loop.forward(s_, sig["h", s_])[0])
+        for s_ in reversed(range(P_)):
+            flagged += len(loop.backward(s_, sig["g", s_])[0])
+        return flagged
+
+    for _ in range(max(a.warmup, 12)):
+        iteration(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    flagged = 0
+    for _ in range(a.steps):
+        flagged += iteration(False)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / a.steps
+    signals = 2 * P_ * d
+    # bytes one iteration has to move: every signal is read by the score pass, the projection and the EMA update;
+    # every EMA is read by the score pass and the projection and read + written by the update
+    alg = signals * T * D * 2 * 3 + 2 * P_ * T * D * 4 * 4
+    print(json.dumps({
+        "metric": "verified tokens/sec (EMA-reference verifier loop, 4 stages x 16 workers, fwd+bwd signals)",
+        "value": signals * T / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": max(a.warmup, 12),
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "loop_4x16x8192x4096", "stages": P_, "workers": d, "tokens": T, "d_model": D,
+                   "metrics": "rel_l2,l1,zl2,sfr,sw(64)", "flagged_in_timed_steps": flagged},
+        "roofline": {"bound": "hbm", "kernel": "whole iteration (score + projection/sort + EMA)", "achieved": alg / (ms * 1e-3) / 1e9,
+                     "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": alg / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None}}))
+    loop.close(); ver.close()
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -200,6 +259,8 @@ def main():
                          "independent per micro-batch; see DESIGN.md for how it would shard). Use --gpus 1.")
     if a.score_bench:
         return score_bench(a)
+    if a.loop_bench:
+        return loop_bench(a)
     if a.sweep:
         import subprocess
         for s_ in (512, 2048, 4096):
