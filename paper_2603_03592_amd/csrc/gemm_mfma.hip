@@ -397,6 +397,10 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
                   bool do_dma, int dstage, int d0) {
     const char* xs = smem + rstage * STAGE;
     const char* ws = xs + BM * 128;
+    // The fragments this step multiplies were requested during the previous step, the youngest of them four MFMAs
+    // ago: wait for them here, before this step's own requests are queued behind them.
+    __builtin_amdgcn_s_waitcnt(0xc07f);
+    SV_SB;
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       if (do_read) {
@@ -436,8 +440,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
       xf0[g] = *reinterpret_cast<const bf16x8*>(smem + par * STAGE + lds_off(xrow[g], lhi));
       wf0[g] = *reinterpret_cast<const bf16x8*>(smem + par * STAGE + BM * 128 + lds_off(wrow[g], lhi));
     }
-    step(xf0, wf0, xf1, wf1, true, par, 1, d_valid, par ^ 1, 0);
-    step(xf1, wf1, xf0, wf0, true, par, 2, d_valid, par ^ 1, 8);
+    step(xf0, wf0, xf1, wf1, true, par, 1, true, par ^ 1, 0);
+    step(xf1, wf1, xf0, wf0, true, par, 2, true, par ^ 1, 8);
     if (d_valid) advance();
     step(xf0, wf0, xf1, wf1, true, par, 3, false, 0, 0);
     for (int kt = 1; kt < nslices; ++kt) {
@@ -445,8 +449,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
       __builtin_amdgcn_s_waitcnt(0);   // my DMAs of slice kt have landed, my fragment reads of slice kt-1 are done
       __syncthreads();                 // ... and so have everybody's: stage st is complete, stage st^1 is free
       SV_SB;
-      step(xf1, wf1, xf0, wf0, true, st, 0, d_valid, st ^ 1, 0);     // MFMAs of (kt-1, k step 3)
-      step(xf0, wf0, xf1, wf1, true, st, 1, d_valid, st ^ 1, 8);
+      step(xf1, wf1, xf0, wf0, true, st, 0, true, st ^ 1, 0);     // MFMAs of (kt-1, k step 3)
+      step(xf0, wf0, xf1, wf1, true, st, 1, true, st ^ 1, 8);
       if (d_valid) advance();
       step(xf1, wf1, xf0, wf0, true, st, 2, false, 0, 0);
       step(xf0, wf0, xf1, wf1, true, st, 3, false, 0, 0);
