@@ -516,6 +516,9 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
     }
     (void)NIO;
   }
+  // A finished stream keeps re-reading its last slice into the free stage (the loop has no branch for it): every
+  // such load must have landed before the workgroup gives its LDS back.
+  __builtin_amdgcn_s_waitcnt(0);
 #undef SV_SB
 }
 
