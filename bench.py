@@ -42,6 +42,8 @@ def parse():
     ap.add_argument("--sweep", action="store_true",
                     help="run the throughput sweep (single block, d_model 4096, seq x micro-batch grid, fwd+bwd) and print one "
                          "JSON line per point")
+    ap.add_argument("--no-extra", action="store_true",
+                    help="default run only: skip the second measurement (the medium stage's forward + backward check)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three 1 GiB device copies (a kernel of known traffic, to scale rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
@@ -360,6 +362,20 @@ def main():
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, wdev, h_in, g_out, backward)
     ver.close()
+    if wl.name == "large" and a.mode is None and not a.plain and not a.no_extra:
+        # the forward + backward form of the check, on the configuration that defines it (medium stage), in a child process
+        import subprocess
+        del wdev, h_in, first, claim_h, wc
+        torch.cuda.empty_cache()
+        r = subprocess.run([sys.executable, os.path.abspath(__file__), "--workload", "medium", "--steps", str(a.steps), "--warmup",
+                            str(a.warmup), "--no-cpu-baseline"], capture_output=True, text=True)
+        if r.returncode == 0:
+            m = json.loads(r.stdout.strip().splitlines()[-1])
+            out["fwd_bwd_check"] = {"metric": m["metric"], "value": m["value"], "unit": m["unit"], "ms_per_step": m["ms_per_step"],
+                                    "config": m["config"], "roofline": m["roofline"],
+                                    "recompute_tflops": m["recompute"]["tflops"], "per_op_ms": m["recompute"]["per_op_ms"]}
+        else:
+            out["fwd_bwd_check"] = {"error": r.stderr[-300:]}
     print(json.dumps(out))
 
 
