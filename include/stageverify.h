@@ -136,6 +136,15 @@ sv_status sv_verify_backward(sv_ctx *ctx, const sv_block_weights *w, const void 
                              const float *tau, int32_t reduce, void *g_hat_out, void *h_hat_out,
                              float *token_scores_out, sv_result *result_dev, void *stream);
 
+/* Optional, backward contexts on the bf16 matrix-core path: transpose the stage's weight matrices to
+ * [in, out] once (on `stream`) and keep the copies in the context, so that later sv_verify_backward calls
+ * with the SAME sv_block_weights (same pointers) skip their per-call transposes.  The stage parameters
+ * are fixed for a whole training iteration while many micro-batches are checked against them.  The caller
+ * promises that the weight contents do not change until the next sv_prepare_weights call; w = NULL
+ * forgets the copies.  A call with other pointers than the prepared ones transposes per call as before.
+ * No-op for contexts that need no transposed copies.                                               */
+sv_status sv_prepare_weights(sv_ctx *ctx, const sv_block_weights *w, void *stream);
+
 /* Stand-alone statistic for n_claims submissions [T, D] (claim i at claims + i*claim_stride
  * elements) against references (ref + i*ref_stride elements; ref_stride 0 = one shared
  * reference, e.g. the EMA).  results_dev: n_claims sv_result.  token_scores_out (nullable):

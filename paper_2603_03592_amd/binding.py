@@ -128,6 +128,8 @@ def _load():
     L.sv_sentinel_state.argtypes = [vp, i32, i32, C.POINTER(vp), C.POINTER(i32), u8p, dp, dp, dp]
     L.sv_sentinel_read_ema.restype = C.c_int
     L.sv_sentinel_read_ema.argtypes = [vp, i32, i32, C.POINTER(f32), vp]
+    L.sv_prepare_weights.restype = C.c_int
+    L.sv_prepare_weights.argtypes = [vp, C.POINTER(BlockWeightsC), vp]
     L.sv_gemm_bf16.restype = C.c_int
     L.sv_gemm_bf16.argtypes = [vp, i64, vp, i64, i32, vp, i64, i32, i32, i32, i32, vp]
     return L
@@ -325,6 +327,10 @@ class Verifier:
                     assert t.is_cuda and t.is_contiguous() and t.dtype == self.tdtype, n
                 setattr(arr[i], n, _ptr(t))
         return arr
+
+    def prepare_weights(self, weights_c):
+        """Make the backward pass's transposed weight copies once; valid until the weights change (then call again)."""
+        self._check(lib.sv_prepare_weights(self._ctx, weights_c, self._stream()))
 
     def _results(self, n: int):
         return self.torch.empty((n, 32), dtype=self.torch.uint8, device="cuda")

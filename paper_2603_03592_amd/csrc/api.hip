@@ -56,7 +56,9 @@ struct sv_ctx {
   std::vector<void*> xs;           // outputs of blocks 0..L-2 (inputs of blocks 1..L-1)
   std::vector<BlockStash> stash;
   void *dres[2], *dn, *dx1, *dgate, *dup, *dout, *dqkv;
-  void *wqT, *wkT, *wvT, *woT, *wgT, *wuT, *wdT;   // one block's weights transposed to [in, out] (bf16 MFMA path)
+  struct WT { void *wq, *wk, *wv, *wo, *wg, *wu, *wd; };
+  std::vector<WT> wT;                   // per block: the weights transposed to [in, out] (bf16 MFMA path, backward mode)
+  std::vector<sv_block_weights> prepared;   // the weights sv_prepare_weights transposed (empty: none)
   float* delta;
   ScorePartial* score_scratch;
   float* sw_w1;        // [kSwMaxClaims, kSwMaxDirs] per-direction sums (SV_FLAG_SLICED_W)
@@ -153,11 +155,15 @@ size_t carve(sv_ctx* c, char* base) {
     c->dout = a.take(T * c->Dq * es);
     c->dqkv = a.take(T * c->Dqkv * es);
     c->delta = (float*)a.take(lse_n * sizeof(float));
-    c->wqT = c->wkT = c->wvT = c->woT = c->wgT = c->wuT = c->wdT = nullptr;
+    c->wT.clear();
     if (d.dtype == SV_BF16 && !(c->flags & SV_FLAG_PLAIN_KERNELS)) {
-      c->wqT = a.take(D * c->Dq * es); c->wkT = a.take(D * c->Dkv * es); c->wvT = a.take(D * c->Dkv * es);
-      c->woT = a.take(D * c->Dq * es); c->wuT = a.take(D * F * es); c->wdT = a.take(D * F * es);
-      c->wgT = d.mlp == SV_MLP_SWIGLU ? a.take(D * F * es) : nullptr;
+      for (size_t l = 0; l < L; ++l) {
+        sv_ctx::WT t;
+        t.wq = a.take(D * c->Dq * es); t.wk = a.take(D * c->Dkv * es); t.wv = a.take(D * c->Dkv * es);
+        t.wo = a.take(D * c->Dq * es); t.wu = a.take(D * F * es); t.wd = a.take(D * F * es);
+        t.wg = d.mlp == SV_MLP_SWIGLU ? a.take(D * F * es) : nullptr;
+        c->wT.push_back(t);
+      }
     }
   }
   return a.off + 256;
@@ -303,24 +309,37 @@ void add_seg(GemmArgs& g, const void* A, int64_t lda, const void* W, int64_t ldw
 }
 
 // One block backward: dy = dL/dy -> dx = dL/dx, reading the block input x and its stash.
-sv_status block_backward(sv_ctx* c, const sv_block_weights& w, const void* x, const BlockStash& k, const void* dy, void* dx, int B, int S,
+sv_status transpose_block_weights(sv_ctx* c, const sv_block_weights& w, const sv_ctx::WT& t, hipStream_t st) {
+  const sv_stage_desc& d = c->d;
+  const int D = d.d_model, F = d.ffn_hidden, dt = d.dtype;
+  SV_OP(c, SV_OP_BWD_WTRANSPOSE, 0, st, plain_transpose(w.w_down, t.wd, D, F, dt, st));
+  SV_OP(c, SV_OP_BWD_WTRANSPOSE, 0, st, plain_transpose(w.w_up, t.wu, F, D, dt, st));
+  if (d.mlp == SV_MLP_SWIGLU) SV_OP(c, SV_OP_BWD_WTRANSPOSE, 0, st, plain_transpose(w.w_gate, t.wg, F, D, dt, st));
+  SV_OP(c, SV_OP_BWD_WTRANSPOSE, 0, st, plain_transpose(w.wo, t.wo, D, c->Dq, dt, st));
+  SV_OP(c, SV_OP_BWD_WTRANSPOSE, 0, st, plain_transpose(w.wq, t.wq, c->Dq, D, dt, st));
+  SV_OP(c, SV_OP_BWD_WTRANSPOSE, 0, st, plain_transpose(w.wk, t.wk, c->Dkv, D, dt, st));
+  SV_OP(c, SV_OP_BWD_WTRANSPOSE, 0, st, plain_transpose(w.wv, t.wv, c->Dkv, D, dt, st));
+  return SV_OK;
+}
+
+sv_status block_backward(sv_ctx* c, int l, const sv_block_weights& w, const void* x, const BlockStash& k, const void* dy, void* dx, int B, int S,
                          hipStream_t st) {
   const sv_stage_desc& d = c->d;
   const int T = B * S, D = d.d_model, F = d.ffn_hidden, es = c->es, dt = d.dtype;
   const double Td = T, attn_flop = (d.causal ? 2.0 : 4.0) * B * d.n_heads * (double)S * S * c->hd;
-  // On the bf16 matrix-core path the [out, in] weights are first transposed to [in, out], so that
+  // On the bf16 matrix-core path the [out, in] weights are used transposed to [in, out], so that
   // every backward product dY * W is again an "activations times [N, K] weights" product and runs
-  // on the same direct-to-LDS kernel as the forward (the transposes move 2 x weight bytes through
-  // HBM, a few percent of the backward GEMM time).
-  const bool wt = c->wqT != nullptr;
+  // on the same direct-to-LDS kernel as the forward.  The transposed copies are made here (2 x weight
+  // bytes through HBM) unless sv_prepare_weights made them for exactly these weights.
+  const bool wt = !c->wT.empty();
+  sv_ctx::WT t{};
   if (wt) {
-    SV_OP(c, SV_OP_BWD_WTRANSPOSE, 0, st, plain_transpose(w.w_down, c->wdT, D, F, dt, st));
-    SV_OP(c, SV_OP_BWD_WTRANSPOSE, 0, st, plain_transpose(w.w_up, c->wuT, F, D, dt, st));
-    if (d.mlp == SV_MLP_SWIGLU) SV_OP(c, SV_OP_BWD_WTRANSPOSE, 0, st, plain_transpose(w.w_gate, c->wgT, F, D, dt, st));
-    SV_OP(c, SV_OP_BWD_WTRANSPOSE, 0, st, plain_transpose(w.wo, c->woT, D, c->Dq, dt, st));
-    SV_OP(c, SV_OP_BWD_WTRANSPOSE, 0, st, plain_transpose(w.wq, c->wqT, c->Dq, D, dt, st));
-    SV_OP(c, SV_OP_BWD_WTRANSPOSE, 0, st, plain_transpose(w.wk, c->wkT, c->Dkv, D, dt, st));
-    SV_OP(c, SV_OP_BWD_WTRANSPOSE, 0, st, plain_transpose(w.wv, c->wvT, c->Dkv, D, dt, st));
+    t = c->wT[l];
+    const bool ready = (int)c->prepared.size() == d.n_blocks && memcmp(&c->prepared[l], &w, sizeof(w)) == 0;
+    if (!ready) {
+      sv_status s = transpose_block_weights(c, w, t, st);
+      if (s != SV_OK) return s;
+    }
   }
   // product dY [T, K] * W [K, N] with W given as stored ([K, N]) or transposed ([N, K])
   auto seg = [&](GemmArgs& g, const void* A, int64_t lda, const void* W, const void* WT, int K, int N) {
@@ -333,26 +352,26 @@ sv_status block_backward(sv_ctx* c, const sv_block_weights& w, const void* x, co
   };
   if (d.mlp == SV_MLP_SWIGLU) {
     GemmArgs g = args(F, c->dgate, F, EPI_SWIGLU_BWD);           // da = dy Wd, then through silu(g)*u
-    seg(g, dy, D, w.w_down, c->wdT, D, F);
+    seg(g, dy, D, w.w_down, t.wd, D, F);
     g.C2 = c->dup; g.R = k.gate; g.R2 = k.up; g.ldr = F;
     SV_OP(c, SV_OP_BWD_GEMM_DA, 2.0 * Td * F * D, st, gemm(c, g, st));
     GemmArgs h = args(D, c->dn, D, EPI_STORE);                   // dn2 = dG Wg + dU Wu
-    seg(h, c->dgate, F, w.w_gate, c->wgT, F, D);
-    seg(h, c->dup, F, w.w_up, c->wuT, F, D);
+    seg(h, c->dgate, F, w.w_gate, t.wg, F, D);
+    seg(h, c->dup, F, w.w_up, t.wu, F, D);
     SV_OP(c, SV_OP_BWD_GEMM_DN2, 4.0 * Td * F * D, st, gemm(c, h, st));
   } else {
     GemmArgs g = args(F, c->dgate, F, EPI_GELU_BWD);
-    seg(g, dy, D, w.w_down, c->wdT, D, F);
+    seg(g, dy, D, w.w_down, t.wd, D, F);
     g.R = k.up; g.ldr = F;
     SV_OP(c, SV_OP_BWD_GEMM_DA, 2.0 * Td * F * D, st, gemm(c, g, st));
     GemmArgs h = args(D, c->dn, D, EPI_STORE);
-    seg(h, c->dgate, F, w.w_up, c->wuT, F, D);
+    seg(h, c->dgate, F, w.w_up, t.wu, F, D);
     SV_OP(c, SV_OP_BWD_GEMM_DN2, 2.0 * Td * F * D, st, gemm(c, h, st));
   }
   SV_OP(c, SV_OP_BWD_NORM, 0, st, plain_norm_bwd_add(c->dn, k.x1, w.norm2_g, dy, c->dx1, T, D, d.norm, d.norm_eps, dt, st));
   {
     GemmArgs g = args(c->Dq, c->dout, c->Dq, EPI_STORE);         // do = dx1 Wo
-    seg(g, c->dx1, D, w.wo, c->woT, D, c->Dq);
+    seg(g, c->dx1, D, w.wo, t.wo, D, c->Dq);
     SV_OP(c, SV_OP_BWD_GEMM_DO, 2.0 * Td * D * c->Dq, st, gemm(c, g, st));
   }
   SV_OP(c, SV_OP_BWD_ATTN, 2.5 * attn_flop, st, attn_bwd(c, k, B, S, st));
@@ -360,9 +379,9 @@ sv_status block_backward(sv_ctx* c, const sv_block_weights& w, const void* x, co
     SV_OP(c, SV_OP_BWD_ROPE, 0, st, plain_rope(c->dqkv, c->Dqkv, T, S, d.n_heads, d.n_kv_heads, c->hd, c->rope_cs, 1, dt, st));
   {
     GemmArgs g = args(D, c->dn, D, EPI_STORE);                   // dn1 = dq Wq + dk Wk + dv Wv
-    seg(g, c->dqkv, c->Dqkv, w.wq, c->wqT, c->Dq, D);
-    seg(g, at(c->dqkv, c->Dq, es), c->Dqkv, w.wk, c->wkT, c->Dkv, D);
-    seg(g, at(c->dqkv, c->Dq + c->Dkv, es), c->Dqkv, w.wv, c->wvT, c->Dkv, D);
+    seg(g, c->dqkv, c->Dqkv, w.wq, t.wq, c->Dq, D);
+    seg(g, at(c->dqkv, c->Dq, es), c->Dqkv, w.wk, t.wk, c->Dkv, D);
+    seg(g, at(c->dqkv, c->Dq + c->Dkv, es), c->Dqkv, w.wv, t.wv, c->Dkv, D);
     SV_OP(c, SV_OP_BWD_GEMM_DN1, 2.0 * Td * D * c->Dqkv, st, gemm(c, g, st));
   }
   SV_OP(c, SV_OP_BWD_NORM, 0, st, plain_norm_bwd_add(c->dn, x, w.norm1_g, c->dx1, dx, T, D, d.norm, d.norm_eps, dt, st));
@@ -522,13 +541,31 @@ sv_status sv_verify_backward(sv_ctx* c, const sv_block_weights* w, const void* h
   for (int l = L - 1; l >= 0; --l) {
     dx = (l == 0 && g_hat_out) ? g_hat_out : c->dres[l & 1];
     const void* xin = l == 0 ? h_in : c->xs[l - 1];
-    s = block_backward(c, w[l], xin, c->stash[l], dy, dx, B, S, st);
+    s = block_backward(c, l, w[l], xin, c->stash[l], dy, dx, B, S, st);
     if (s != SV_OK) return s;
     dy = dx;
   }
   if (claimed_g)
     SV_OP(c, SV_OP_SCORE, 0, st, launch_score(claimed_g, 0, 1, dx, 0, c->d.dtype, c->d.dtype, (int64_t)B * S, c->d.d_model, metric_mask, tau, reduce,
                            token_scores_out, result_dev, c->score_scratch, kScoreScratchElems, st));
+  return SV_OK;
+}
+
+sv_status sv_prepare_weights(sv_ctx* c, const sv_block_weights* w, void* stream) {
+  if (!c) return SV_EINVAL;
+  c->prepared.clear();
+  if (!w) return SV_OK;                               // forget the prepared copies
+  if (c->wT.empty()) return SV_OK;                     // this context transposes nothing (forward only, fp32 or plain kernels)
+  for (int l = 0; l < c->d.n_blocks; ++l) {
+    const sv_block_weights& b = w[l];
+    if (!(b.wq && b.wk && b.wv && b.wo && b.w_up && b.w_down) || (c->d.mlp == SV_MLP_SWIGLU && !b.w_gate)) {
+      set_err(c, "block %d: a required weight pointer is NULL", l);
+      return SV_EINVAL;
+    }
+    sv_status s = transpose_block_weights(c, b, c->wT[l], (hipStream_t)stream);
+    if (s != SV_OK) return s;
+  }
+  c->prepared.assign(w, w + c->d.n_blocks);
   return SV_OK;
 }
 

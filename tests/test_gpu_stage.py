@@ -184,3 +184,33 @@ def test_mfma_gemm_against_fp64_product(kn, tile):
     # one bf16 rounding of an fp32-accumulated sum: relative 2^-9 per element at most
     np.testing.assert_allclose(got, want, rtol=2 ** -8, atol=2e-2)
     assert rel_l2(got, want) < 3e-3
+
+
+def test_prepared_weights_give_the_same_backward_and_follow_a_weight_update():
+    import torch
+    import paper_2603_03592_amd as sv
+    desc, B, S = MFMA_BF16, 2, 128
+    w = dev_weights(si.make_weights(desc, 0), "bf16")
+    h = dev(si.make_activations(desc, B, S, 0), "bf16")
+    g = dev(si.make_output_grad(desc, B, S, 0), "bf16")
+    ver = sv.Verifier(desc, B * S, S, backward=True)
+    wc = ver.pack_weights(w)
+    base = ver.verify_backward(wc, h, g, want_g_hat=True)["g_hat"].clone()
+    ver.prepare_weights(wc)
+    for _ in range(2):
+        assert torch.equal(ver.verify_backward(wc, h, g, want_g_hat=True)["g_hat"], base)
+    # the stage parameters change in place (an optimizer step): prepare again, the result follows
+    w[1]["w_down"].mul_(0.5)
+    ver.prepare_weights(wc)
+    moved = ver.verify_backward(wc, h, g, want_g_hat=True)["g_hat"].clone()
+    assert not torch.equal(moved, base)
+    ver.prepare_weights(None)                      # forget the copies: per-call transposes again, same numbers
+    assert torch.equal(ver.verify_backward(wc, h, g, want_g_hat=True)["g_hat"], moved)
+    # other weight tensors than the prepared ones are never served from the copies
+    ver.prepare_weights(wc)
+    w2 = dev_weights(si.make_weights(desc, 1), "bf16")
+    wc2 = ver.pack_weights(w2)
+    other = ver.verify_backward(wc2, h, g, want_g_hat=True)["g_hat"].clone()
+    ref_h, ref_g = so.stage_backward(host(h), host(g), si.make_weights(desc, 1), desc)
+    assert rel_l2(host(other), ref_g) <= 2e-2
+    ver.close()
