@@ -126,6 +126,17 @@ def measured_traffic(workload, kernel):
     return None
 
 
+def score_traffic():
+    """HBM bytes per launch of the score pass in the 128-submission bench, from the committed rocprofv3 --pmc summary."""
+    try:
+        for line in open(os.path.join(ROOT, "profiles", "score_bench_hbm_traffic.txt")):
+            if line.startswith("score_traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
 def score_bench(a):
     """HBM-bound half of the verifier: Gamma = Omega(h, reference) for 128 concurrent submissions of the large
     stage's signal shape [8192, 4096] bf16 against one shared reference (the paper's EMA mode, or one
@@ -184,7 +195,7 @@ def score_bench(a):
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "score_128x8192x4096", "claims": n, "tokens": T, "d_model": D, "metrics": "rel_l2,l1,zl2,sfr"},
         "roofline": {"bound": "hbm", "kernel": "score_tokens_kernel", "achieved": score_bytes / (ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
-                     "unit": "GB/s", "frac": score_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None},
+                     "unit": "GB/s", "frac": score_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": score_traffic()},
         "rel_l2_only": {"ms": ms_lite, "achieved_GBs": score_bytes / (ms_lite * 1e-3) / 1e9,
                         "frac": score_bytes / (ms_lite * 1e-3) / 1e9 / PEAK_HBM_GBS},
         "sliced_wasserstein": {"ms": ms_sw, "directions": n_dirs, "achieved_GBs": sw_bytes / (ms_sw * 1e-3) / 1e9,

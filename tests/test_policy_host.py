@@ -7,12 +7,21 @@ import pytest
 import paper_2603_03592_amd as sv
 from oracle import sentinel_oracle as so
 
-CFGS = [  # the activation / gradient columns of the paper's configuration table (first and last model)
-    dict(k0=1.5, alpha=0.01, grow=1.1, shrink=0.9, n_max=10, min_dist_mult=0.35, eps=0.01),
-    dict(k0=3.0, alpha=0.001, grow=1.01, shrink=0.99, n_max=10, min_dist_mult=0.15, eps=0.001),
-    dict(k0=3.0, alpha=0.05, grow=1.01, shrink=0.99, n_max=10, min_dist_mult=0.05, eps=0.0001),
-    dict(k0=1.5, alpha=0.2, grow=1.5, shrink=0.8, n_max=10, min_dist_mult=0.0, eps=1e-3),
-]
+def _paper_configs():
+    """The eight columns of the paper's hyper-parameter table (tests/golden/verification_config.txt)."""
+    import os
+    out = []
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "verification_config.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        name, beta, k0, alpha, n_max, grow, shrink, lam, eps = line.split()
+        out.append(dict(k0=float(k0), alpha=float(alpha), grow=float(grow), shrink=float(shrink), n_max=int(n_max),
+                        min_dist_mult=float(lam), eps=float(eps)))
+    assert len(out) == 8
+    return out
+
+
+CFGS = _paper_configs() + [dict(k0=1.5, alpha=0.2, grow=1.5, shrink=0.8, n_max=10, min_dist_mult=0.0, eps=1e-3)]
 
 
 @pytest.mark.parametrize("cfg", CFGS)
@@ -36,7 +45,7 @@ def test_adaptive_iqr_hand_worked_example():
     assert k == pytest.approx(0.9) and lo == pytest.approx(5.0) and up == pytest.approx(95.0)
 
 
-@pytest.mark.parametrize("seed", range(6))
+@pytest.mark.parametrize("seed", range(9))
 def test_policy_stream_matches_oracle(seed):
     """A synthetic stream of per-worker statistics: benign noise with a slow drift, transient glitches, one worker
     that starts attacking, one severe deviation, non-finite values, skip masks.  Every decision must agree."""
