@@ -19,6 +19,8 @@
 //
 // Workgroup ids are remapped so that each XCD (ids congruent mod 8) works on a contiguous run
 // of tiles, ordered in groups of GROUP_M row tiles, to keep operand panels hot in its L2.
+#include <type_traits>
+
 #include "common.h"
 
 namespace sv {
@@ -469,52 +471,82 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
     __syncthreads();                                   // everybody is done reading stage sl
     char* patch = smem + sl * STAGE + wave * 16384;
     const int er = lane >> 4, ec4 = lane & 15;         // read-back: row er of each group of 4 rows, 16-byte chunk ec4 (and 16 + ec4)
-    constexpr int NIO = DUAL ? 2 : 4;
-#pragma unroll
-    for (int mi = 0; mi < MI; ++mi) {
-#pragma unroll
-      for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          f32x4 v;
-#pragma unroll
-          for (int i = 0; i < 4; ++i) v[i] = acc[ni][mi][q * 4 + i];
-          const int chunk = ni * 8 + q * 2 + lhi;      // features 4*chunk .. +3 of the wave's 128
-          *reinterpret_cast<f32x4*>(patch + l31 * 512 + ((chunk ^ l31) << 4)) = v;
-        }
-      __builtin_amdgcn_s_waitcnt(0xc07f);              // lgkmcnt(0): the patch is complete before it is read back
-      __builtin_amdgcn_wave_barrier();
-#pragma unroll
-      for (int it = 0; it < 8; it += 2) {
-        // two rows per lane and trip: all of their loads are issued before the first store
-        float lo[2][4], hi[2][4];
-        EpiIn in_lo[2], in_hi[2];
-        int mrow[2];
+    int rope_p0 = 0, rope_i0_lo = 0, rope_i0_hi = 0;
+    if (EPI == EPI_ROPE) {
+      const int nlo = n0 + wn * 128 + ec4 * 4, nhi = nlo + 64;
+      rope_p0 = (m0 + wm * 128) % a.rope_S;
+      rope_i0_lo = (nlo % a.rope_hd) >> 1; rope_i0_hi = (nhi % a.rope_hd) >> 1;
+    }
+    // The epilogue's global reads (residual, gate / up, RoPE table) run one trip ahead of its stores: the memory
+    // counter retires in order, so a read issued AFTER a store could only be waited for together with that store's
+    // acknowledgement.  Sixteen trips per tile: row block mi = trip / 4, two rows per lane and trip.  Tiles that lie
+    // inside the M rows run without any per-lane condition (CHECK = false): around divergent branches the compiler's
+    // wait insertion falls back to waiting for (nearly) everything in flight, one memory round trip per store.
+    auto run_epilogue = [&](auto check_tag) {
+      constexpr bool CHECK = decltype(check_tag)::value;
+      auto load_inputs = [&](int trip, EpiIn (&in_lo)[2], EpiIn (&in_hi)[2]) {
+        const int mi = trip >> 2, it = (trip & 3) * 2;
 #pragma unroll
         for (int k = 0; k < 2; ++k) {
           const int row = (it + k) * 4 + er;
-          mrow[k] = m0 + wm * 128 + mi * 32 + row;
-          const f32x4 a_lo = *reinterpret_cast<const f32x4*>(patch + row * 512 + ((ec4 ^ row) << 4));
-          const f32x4 a_hi = *reinterpret_cast<const f32x4*>(patch + row * 512 + (((16 + ec4) ^ row) << 4));
-#pragma unroll
-          for (int i = 0; i < 4; ++i) { lo[k][i] = a_lo[i]; hi[k][i] = a_hi[i]; }
-          if (mrow[k] < a.M) {
-            if (DUAL) epilogue_load4<EPI>(a, mrow[k], n0 + wn * 64 + ec4 * 4, in_lo[k]);
-            else { epilogue_load4<EPI>(a, mrow[k], n0 + wn * 128 + ec4 * 4, in_lo[k]); epilogue_load4<EPI>(a, mrow[k], n0 + wn * 128 + 64 + ec4 * 4, in_hi[k]); }
+          int m = m0 + wm * 128 + mi * 32 + row;
+          if (CHECK) m = min(m, a.M - 1);                // rows past the end read the last row (never stored)
+          if (EPI == EPI_ROPE) {
+            // position of the row in its sequence without a division per row: the wave's first row is reduced once
+            // per tile, the rows of the tile follow it consecutively
+            int p = rope_p0 + mi * 32 + row;
+            if (a.rope_S >= 256) p -= p >= a.rope_S ? a.rope_S : 0; else p %= a.rope_S;
+            in_lo[k].cs = *reinterpret_cast<const f32x4*>(a.rope_cs + ((int64_t)p * (a.rope_hd >> 1) + rope_i0_lo) * 2);
+            in_hi[k].cs = *reinterpret_cast<const f32x4*>(a.rope_cs + ((int64_t)p * (a.rope_hd >> 1) + rope_i0_hi) * 2);
+          } else if (DUAL) {
+            epilogue_load4<EPI>(a, m, n0 + wn * 64 + ec4 * 4, in_lo[k]);
+          } else {
+            epilogue_load4<EPI>(a, m, n0 + wn * 128 + ec4 * 4, in_lo[k]);
+            epilogue_load4<EPI>(a, m, n0 + wn * 128 + 64 + ec4 * 4, in_hi[k]);
           }
         }
+      };
+      constexpr bool kHasInputs = EPI == EPI_RESID || EPI == EPI_SWIGLU_BWD || EPI == EPI_GELU_BWD || EPI == EPI_ROPE;
+      EpiIn in_lo[2][2], in_hi[2][2];                    // [trip parity][row of the pair]
+      if (kHasInputs) load_inputs(0, in_lo[0], in_hi[0]);
+#pragma unroll
+      for (int trip = 0; trip < 16; ++trip) {
+        const int mi = trip >> 2, it = (trip & 3) * 2;
+        if ((trip & 3) == 0) {
+#pragma unroll
+          for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              f32x4 v;
+#pragma unroll
+              for (int i = 0; i < 4; ++i) v[i] = acc[ni][mi][q * 4 + i];
+              const int chunk = ni * 8 + q * 2 + lhi;    // features 4*chunk .. +3 of the wave's 128
+              *reinterpret_cast<f32x4*>(patch + l31 * 512 + ((chunk ^ l31) << 4)) = v;
+            }
+          __builtin_amdgcn_s_waitcnt(0xc07f);            // lgkmcnt(0): the patch is complete before it is read back
+          __builtin_amdgcn_wave_barrier();
+        }
+        if (kHasInputs && trip + 1 < 16) load_inputs(trip + 1, in_lo[(trip + 1) & 1], in_hi[(trip + 1) & 1]);
 #pragma unroll
         for (int k = 0; k < 2; ++k) {
-          if (mrow[k] >= a.M) continue;
-          if (DUAL) epilogue_apply4<EPI>(a, mrow[k], n0 + wn * 64 + ec4 * 4, lo[k], hi[k], in_lo[k]);   // patch columns 0..63: gate, 64..127: up
+          const int row = (it + k) * 4 + er;
+          const int m = m0 + wm * 128 + mi * 32 + row;
+          const f32x4 a_lo = *reinterpret_cast<const f32x4*>(patch + row * 512 + ((ec4 ^ row) << 4));
+          const f32x4 a_hi = *reinterpret_cast<const f32x4*>(patch + row * 512 + (((16 + ec4) ^ row) << 4));
+          float lo[4], hi[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) { lo[i] = a_lo[i]; hi[i] = a_hi[i]; }
+          if (CHECK && m >= a.M) continue;
+          if (DUAL) epilogue_apply4<EPI>(a, m, n0 + wn * 64 + ec4 * 4, lo, hi, in_lo[trip & 1][k]);   // patch columns 0..63: gate, 64..127: up
           else {
-            epilogue_apply4<EPI>(a, mrow[k], n0 + wn * 128 + ec4 * 4, lo[k], hi[k], in_lo[k]);
-            epilogue_apply4<EPI>(a, mrow[k], n0 + wn * 128 + 64 + ec4 * 4, hi[k], lo[k], in_hi[k]);
+            epilogue_apply4<EPI>(a, m, n0 + wn * 128 + ec4 * 4, lo, hi, in_lo[trip & 1][k]);
+            epilogue_apply4<EPI>(a, m, n0 + wn * 128 + 64 + ec4 * 4, hi, lo, in_hi[trip & 1][k]);
           }
         }
       }
-    }
-    (void)NIO;
+    };
+    if (m0 + 256 <= a.M) run_epilogue(std::false_type{});
+    else run_epilogue(std::true_type{});
   }
   // A finished stream keeps re-reading its last slice into the free stage (the loop has no branch for it): every
   // such load must have landed before the workgroup gives its LDS back.
