@@ -35,7 +35,7 @@ struct Arena {
 
 constexpr int64_t kScoreScratchElems = 1 << 18;   // ScorePartial records (20 MiB)
 constexpr int kSwMaxDirs = 128, kSwMaxClaims = 4096;
-constexpr int kSwSlots = 9;                       // projected tensors (kSwMaxDirs rows each) the scratch holds at max_tokens
+constexpr int kSwSlots = 33;                      // projected tensors (kSwMaxDirs rows each) the scratch holds at max_tokens
 
 }  // namespace
 

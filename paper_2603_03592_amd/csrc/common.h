@@ -58,6 +58,11 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
+// Workgroup barrier that orders LDS accesses only: waits for this wave's LDS operations, then s_barrier.  Unlike
+// __syncthreads() it does not wait for global loads in flight (a workgroup fence drains the vector memory counter),
+// so loads prefetched into registers stay in flight across it.  Use only where nothing but LDS is shared between waves.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 // Sum over a 256-thread workgroup; every thread gets the result.  `red` holds >= 4 floats.
 __device__ __forceinline__ float block_sum_256(float v, float* red) {
   v = wave_sum(v);

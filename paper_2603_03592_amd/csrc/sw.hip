@@ -20,12 +20,12 @@ constexpr int kSortChunkMax = 16384;   // floats sorted in LDS by one workgroup 
 // L = 32 * LB directions; the contraction runs over the feature axis in steps of 16 on
 // v_mfma_f32_32x32x16_bf16 with the directions in the A slot, so a lane ends up with one token
 // (lane & 31) and the directions 8q + 4 (lane >> 5) + r of each block of 32.
-// The signal goes global -> register directly: inside a 64-feature chunk the k index is permuted
-// (lane half h reads the 16-byte pieces 4h .. 4h+3, one per step) so that the four steps of a lane
-// read 64 contiguous bytes of its row; the same permutation is applied to the directions, which
-// leaves the dot product unchanged.  The directions' 64-feature chunk [L, 64] is staged through
-// LDS once per workgroup (double buffered, 16-byte pieces XOR-swizzled by the row) so that L2 sees
-// one read of it per 256 tokens, and the bf16 signal is prefetched one chunk ahead in registers.
+// The signal is streamed in chunks of 128 bytes per row (64 bf16 or 32 fp32 features): the
+// [256 rows x 128 B] tile goes global -> LDS with global_load_lds (8 lanes fetch one row's 128
+// contiguous bytes; the 16-byte pieces are XOR-swizzled by choosing which piece a lane fetches),
+// three tiles deep, so that two chunks are always in flight and the wait at the end of a chunk
+// leaves the youngest one outstanding.  The matching [L x chunk] piece of the directions is staged
+// through registers.  Fragments are 16-byte LDS reads, conflict-free with the swizzle.
 // fp32 signals are split into three bf16 terms (x = hi + mid + lo exactly), three MFMAs per step:
 // every product is exact in fp32, so the result has fp32-accumulation accuracy.
 __device__ __forceinline__ int sw_swz(int row) { return (row ^ (row >> 3)) & 7; }
@@ -37,14 +37,13 @@ __device__ __forceinline__ void mac_bf16(const bf16x8 (&u)[LB], const bf16x8& x,
 }
 
 template <int LB>
-__device__ __forceinline__ void mac_f32(const bf16x8 (&u)[LB], const float* p, f32x16 (&acc)[LB]) {
-  float x[8];
-  load8(p, x);
+__device__ __forceinline__ void mac_f32(const bf16x8 (&u)[LB], const f32x4& x0, const f32x4& x1, f32x16 (&acc)[LB]) {
   bf16x8 hi, mid, lo;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    const bf16 a = (bf16)x[i];
-    const float r1 = x[i] - (float)a;
+    const float x = i < 4 ? x0[i] : x1[i - 4];
+    const bf16 a = (bf16)x;
+    const float r1 = x - (float)a;
     const bf16 b = (bf16)r1;
     const float r2 = r1 - (float)b;
     hi[i] = a; mid[i] = b; lo[i] = (bf16)r2;
@@ -54,26 +53,51 @@ __device__ __forceinline__ void mac_f32(const bf16x8 (&u)[LB], const float* p, f
   mac_bf16<LB>(u, hi, acc);
 }
 
+constexpr int kSwTile = 256 * 128;     // bytes of one signal tile in LDS
+
 template <typename E, int LB>
 __global__ __launch_bounds__(256) void sw_project_kernel(const E* __restrict__ X, int64_t x_stride, const bf16* __restrict__ U,
                                                          int D, int64_t T, int64_t Tpad, float* __restrict__ P) {
   constexpr bool kBf16 = sizeof(E) == 2;
-  __shared__ __attribute__((aligned(16))) char us[2][LB * 32 * 128];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l31 = lane & 31, lhi = lane >> 5;
-  const int64_t t0 = ((int64_t)blockIdx.x * 4 + wave) * 64;
-  const E* xp[2];
+  constexpr int KC = 128 / (int)sizeof(E);            // features per chunk
+  constexpr int NSTEP = KC / 16;                      // MFMA k steps per chunk
+  constexpr int UPIECES = KC / 8;                     // 16-byte pieces per direction row and chunk
+  constexpr int UTILE = LB * 32 * 128;                // direction rows keep a 128-byte pitch
+  constexpr int ULOADS = (LB * 32 * UPIECES + 255) / 256;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  char* xs = smem;                                    // 3 signal tiles
+  char* us = smem + 3 * kSwTile;                      // 2 direction chunks
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), l31 = lane & 31, lhi = lane >> 5;
+  const int64_t tile0 = (int64_t)blockIdx.x * 256;
+  const char* xbase = (const char*)(X + (int64_t)blockIdx.y * x_stride);
+  // direct-to-LDS plan: instruction i of this wave covers the tile rows (wave + 4 i) * 8 .. + 7
+  int64_t xoff[8];
 #pragma unroll
-  for (int tb = 0; tb < 2; ++tb) {
-    const int64_t row = min(t0 + tb * 32 + l31, T - 1);          // rows past the end re-read the last one
-    xp[tb] = X + (int64_t)blockIdx.y * x_stride + row * D + lhi * 32;
+  for (int i = 0; i < 8; ++i) {
+    const int r = (wave + 4 * i) * 8 + (lane >> 3), c = (lane & 7) ^ sw_swz(r);
+    xoff[i] = min(tile0 + r, T - 1) * (int64_t)D * (int64_t)sizeof(E) + c * 16;     // rows past the end re-read the last one
   }
-  // staging of the directions' chunk: thread e owns the 16-byte pieces e, e + 256, ... of the [L, 64] tile
-  const bf16* ug[LB];
-  int ul[LB];
+  // Workgroups that run together start at different chunks: with a row pitch that is a multiple of the memory
+  // channels' interleave, everybody reading column chunk kc of its rows at the same time would camp on few channels.
+  const int nchunk = D / KC;
+  const int rot = (int)((blockIdx.x * 5u + blockIdx.y * 3u) % (unsigned)nchunk);
+  auto chunk_of = [&](int kc) { const int c = kc + rot; return c >= nchunk ? c - nchunk : c; };
+  auto dma = [&](int kc, int stage) {
+    const int ck = chunk_of(kc);
 #pragma unroll
-  for (int i = 0; i < LB; ++i) {
-    const int e = tid + 256 * i, r = e >> 3, c = e & 7;
-    ug[i] = U + (int64_t)r * D + c * 8;
+    for (int i = 0; i < 8; ++i)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(xbase + xoff[i] + (int64_t)ck * 128),
+                                       (__attribute__((address_space(3))) void*)(xs + stage * kSwTile + (wave + 4 * i) * 1024), 16, 0, 0);
+  };
+  // staging of the directions' chunk: thread e owns the 16-byte pieces e, e + 256, ... of the [L, KC] tile
+  const bf16* ug[ULOADS];
+  int ul[ULOADS];
+  bool uon[ULOADS];
+#pragma unroll
+  for (int i = 0; i < ULOADS; ++i) {
+    const int e = tid + 256 * i, r = e / UPIECES, c = e % UPIECES;
+    uon[i] = e < LB * 32 * UPIECES;
+    ug[i] = U + (int64_t)(uon[i] ? r : 0) * D + c * 8;
     ul[i] = r * 128 + ((c ^ sw_swz(r)) << 4);
   }
   f32x16 acc[2][LB];
@@ -84,60 +108,61 @@ __global__ __launch_bounds__(256) void sw_project_kernel(const E* __restrict__ X
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[tb][b][i] = 0.0f;
 
-  bf16x8 ureg[LB];
-  bf16x8 xcur[2][4], xnext[2][4];
+  bf16x8 ureg[ULOADS];
 #pragma unroll
-  for (int i = 0; i < LB; ++i) *reinterpret_cast<bf16x8*>(us[0] + ul[i]) = *reinterpret_cast<const bf16x8*>(ug[i]);
-  if (kBf16) {
-#pragma unroll
-    for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-      for (int s = 0; s < 4; ++s) xcur[tb][s] = *reinterpret_cast<const bf16x8*>((const bf16*)xp[tb] + s * 8);
-  }
-  __syncthreads();
-  const int nchunk = D >> 6;
+  for (int i = 0; i < ULOADS; ++i)
+    if (uon[i]) *reinterpret_cast<bf16x8*>(us + ul[i]) = *reinterpret_cast<const bf16x8*>(ug[i] + (int64_t)chunk_of(0) * KC);
+  dma(0, 0);
+  dma(nchunk > 1 ? 1 : 0, 1);                          // a second chunk is always issued: the wait below counts on it
+  asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  int st = 0;                                          // LDS tile of chunk kc
   for (int kc = 0; kc < nchunk; ++kc) {
-    const int k0 = kc << 6;
     const bool more = kc + 1 < nchunk;
     if (more) {
 #pragma unroll
-      for (int i = 0; i < LB; ++i) ureg[i] = *reinterpret_cast<const bf16x8*>(ug[i] + k0 + 64);
-      if (kBf16) {
-#pragma unroll
-        for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-          for (int s = 0; s < 4; ++s) xnext[tb][s] = *reinterpret_cast<const bf16x8*>((const bf16*)xp[tb] + k0 + 64 + s * 8);
-      }
+      for (int i = 0; i < ULOADS; ++i)
+        if (uon[i]) ureg[i] = *reinterpret_cast<const bf16x8*>(ug[i] + (int64_t)chunk_of(kc + 1) * KC);
     }
-    const char* ub = us[kc & 1];
+    const int st2 = st + 2 >= 3 ? st - 1 : st + 2;     // tile of chunk kc + 2: the one chunk kc - 1 was read from
+    dma(kc + 2 < nchunk ? kc + 2 : nchunk - 1, st2);   // past the end: re-read the last chunk (never used)
+    const char* xt = xs + st * kSwTile;
+    const char* ub = us + (kc & 1) * UTILE;
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
+    for (int s = 0; s < NSTEP; ++s) {
       bf16x8 u[LB];
 #pragma unroll
       for (int b = 0; b < LB; ++b) {
         const int r = b * 32 + l31;
-        u[b] = *reinterpret_cast<const bf16x8*>(ub + r * 128 + (((lhi * 4 + s) ^ sw_swz(r)) << 4));
+        u[b] = *reinterpret_cast<const bf16x8*>(ub + r * 128 + (((2 * s + lhi) ^ sw_swz(r)) << 4));
       }
 #pragma unroll
       for (int tb = 0; tb < 2; ++tb) {
-        if (kBf16) mac_bf16<LB>(u, xcur[tb][s], acc[tb]);
-        else mac_f32<LB>(u, (const float*)xp[tb] + k0 + s * 8, acc[tb]);
+        const int r = wave * 64 + tb * 32 + l31;
+        if (kBf16) {
+          const bf16x8 x = *reinterpret_cast<const bf16x8*>(xt + r * 128 + (((2 * s + lhi) ^ sw_swz(r)) << 4));
+          mac_bf16<LB>(u, x, acc[tb]);
+        } else {
+          const int c = 2 * (2 * s + lhi);
+          const f32x4 x0 = *reinterpret_cast<const f32x4*>(xt + r * 128 + ((c ^ sw_swz(r)) << 4));
+          const f32x4 x1 = *reinterpret_cast<const f32x4*>(xt + r * 128 + (((c + 1) ^ sw_swz(r)) << 4));
+          mac_f32<LB>(u, x0, x1, acc[tb]);
+        }
       }
     }
     if (more) {
 #pragma unroll
-      for (int i = 0; i < LB; ++i) *reinterpret_cast<bf16x8*>(us[(kc + 1) & 1] + ul[i]) = ureg[i];
-      if (kBf16) {
-#pragma unroll
-        for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-          for (int s = 0; s < 4; ++s) xcur[tb][s] = xnext[tb][s];
-      }
+      for (int i = 0; i < ULOADS; ++i)
+        if (uon[i]) *reinterpret_cast<bf16x8*>(us + ((kc + 1) & 1) * UTILE + ul[i]) = ureg[i];
     }
-    __syncthreads();
+    // chunk kc + 1 has landed (only the 8 loads of chunk kc + 2 may still be in flight) and this wave is done with
+    // tile st and the directions' buffer; after the barrier that holds for the whole workgroup
+    asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    st = st + 1 >= 3 ? 0 : st + 1;
   }
+  __builtin_amdgcn_s_waitcnt(0);                       // every direct-to-LDS load has landed before the LDS is given back
   float* out = P + (int64_t)blockIdx.y * (LB * 32) * Tpad;
-  const float inf = __builtin_huge_valf();                       // padding sorts behind every real sample
+  const float inf = __builtin_huge_valf();             // padding sorts behind every real sample
+  const int64_t t0 = tile0 + wave * 64;
 #pragma unroll
   for (int tb = 0; tb < 2; ++tb) {
     const int64_t t = t0 + tb * 32 + l31;
@@ -241,17 +266,30 @@ __global__ void sw_finalize_kernel(const float* __restrict__ w1, int n_claims, i
   }
 }
 
+template <typename E, int LB>
+hipError_t project_launch(const void* X, int64_t stride, int count, const void* U, int D, int64_t T, int64_t Tpad, float* P, hipStream_t st) {
+  auto kern = sw_project_kernel<E, LB>;
+  constexpr int lds = 3 * kSwTile + 2 * LB * 32 * 128;
+  static bool configured = false;   // per process; the attribute is per function
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  dim3 grid((unsigned)((Tpad + 255) / 256), (unsigned)count);
+  hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, (const E*)X, stride, (const bf16*)U, D, T, Tpad, P);
+  return hipGetLastError();
+}
+
 template <typename E>
 hipError_t project_dispatch(const void* X, int64_t stride, int count, const void* U, int L, int D, int64_t T, int64_t Tpad, float* P,
                             hipStream_t st) {
-  dim3 grid((unsigned)((Tpad + 255) / 256), (unsigned)count);
   switch (L / 32) {
-    case 1: sw_project_kernel<E, 1><<<grid, 256, 0, st>>>((const E*)X, stride, (const bf16*)U, D, T, Tpad, P); break;
-    case 2: sw_project_kernel<E, 2><<<grid, 256, 0, st>>>((const E*)X, stride, (const bf16*)U, D, T, Tpad, P); break;
-    case 3: sw_project_kernel<E, 3><<<grid, 256, 0, st>>>((const E*)X, stride, (const bf16*)U, D, T, Tpad, P); break;
-    default: sw_project_kernel<E, 4><<<grid, 256, 0, st>>>((const E*)X, stride, (const bf16*)U, D, T, Tpad, P); break;
+    case 1: return project_launch<E, 1>(X, stride, count, U, D, T, Tpad, P, st);
+    case 2: return project_launch<E, 2>(X, stride, count, U, D, T, Tpad, P, st);
+    case 3: return project_launch<E, 3>(X, stride, count, U, D, T, Tpad, P, st);
+    default: return project_launch<E, 4>(X, stride, count, U, D, T, Tpad, P, st);
   }
-  return hipGetLastError();
 }
 
 }  // namespace

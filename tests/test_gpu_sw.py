@@ -90,10 +90,10 @@ def test_sw_long_rows_take_the_global_merge_steps():
 
 def test_sw_many_submissions_span_several_groups():
     sv, ver = _ver(256)
-    T, D, L = 256, 64, 128                                # 8 submissions per group with a shared reference, 4 with own ones
+    T, D, L = 256, 64, 128                                # 32 submissions per group with a shared reference, 16 with own ones
     u = si.make_directions(D, L, seed=3)
-    refs = [_signal(T, D, "bf16", 100 + i) for i in range(21)]
-    claims = [si.make_claim(KINDS[i % len(KINDS)], refs[i], "bf16", seed=i) for i in range(21)]
+    refs = [_signal(T, D, "bf16", 100 + i) for i in range(45)]
+    claims = [si.make_claim(KINDS[i % len(KINDS)], refs[i], "bf16", seed=i) for i in range(45)]
     import torch
     cl = torch.stack([dev(c, "bf16") for c in claims])
     sw = ver.sliced_wasserstein(cl, torch.stack([dev(r, "bf16") for r in refs]), dev(u, "bf16"), 1.0)
