@@ -196,17 +196,65 @@ __global__ __launch_bounds__(1024) void sw_sort_chunk_kernel(float* __restrict__
   float* row = P + (int64_t)blockIdx.y * Tpad + gbase;
   for (int i = tid * 4; i < ch; i += nt * 4) *reinterpret_cast<f32x4*>(s + i) = *reinterpret_cast<const f32x4*>(row + i);
   __syncthreads();
+  // Stages with j >= 8 exchange whole float4 vectors between LDS positions i and i + j (the direction bit k is the
+  // same for the four lanes of a vector); the stages j = 4, 2, 1 of a level -- and all of the levels k <= 8 -- run on 8
+  // consecutive elements held in registers, one LDS round trip for three (six) stages.
+  auto cx = [](float& a, float& b, bool asc) {
+    const bool swap = (a > b) == asc;              // same decision rule as the vector stages
+    const float na = swap ? b : a, nb = swap ? a : b;
+    a = na; b = nb;
+  };
+  auto tail8 = [&](int64_t k, bool first_levels) {
+    for (int v = tid; v < (ch >> 3); v += nt) {
+      float e[8];
+      const f32x4 p0 = *reinterpret_cast<const f32x4*>(s + v * 8), p1 = *reinterpret_cast<const f32x4*>(s + v * 8 + 4);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { e[i] = p0[i]; e[4 + i] = p1[i]; }
+      const int64_t g0 = gbase + (int64_t)v * 8;
+      if (first_levels) {                            // levels k = 2, 4 (direction varies inside the block), then k = 8
+#pragma unroll
+        for (int i = 0; i < 8; i += 2) cx(e[i], e[i + 1], ((i & 2) == 0));
+#pragma unroll
+        for (int i = 0; i < 8; ++i) if ((i & 2) == 0) cx(e[i], e[i + 2], ((i & 4) == 0));
+#pragma unroll
+        for (int i = 0; i < 8; i += 2) cx(e[i], e[i + 1], ((i & 4) == 0));
+      }
+      const bool asc = (g0 & k) == 0;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) cx(e[i], e[i + 4], asc);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) if ((i & 2) == 0) cx(e[i], e[i + 2], asc);
+#pragma unroll
+      for (int i = 0; i < 8; i += 2) cx(e[i], e[i + 1], asc);
+      f32x4 q0, q1;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { q0[i] = e[i]; q1[i] = e[4 + i]; }
+      *reinterpret_cast<f32x4*>(s + v * 8) = q0;
+      *reinterpret_cast<f32x4*>(s + v * 8 + 4) = q1;
+    }
+    __syncthreads();
+  };
   const int half = ch >> 1;
   for (int64_t k = k_first; k <= k_last; k <<= 1) {
-    for (int j = (int)min(k >> 1, (int64_t)half); j > 0; j >>= 1) {
-      for (int p = tid; p < half; p += nt) {
-        const int i = 2 * p - (p & (j - 1));
-        const bool asc = ((gbase + i) & k) == 0;
-        const float a = s[i], b = s[i + j];
-        if ((a > b) == asc) { s[i] = b; s[i + j] = a; }
+    if (k < 8) continue;                             // levels 2 and 4 are part of the k = 8 register pass
+    for (int j = (int)min(k >> 1, (int64_t)half); j >= 8; j >>= 1) {
+      const int jv = j >> 2;                          // stride in float4 vectors
+      for (int p = tid; p < (ch >> 3); p += nt) {
+        const int v = 2 * p - (p & (jv - 1));
+        const bool asc = ((gbase + (int64_t)v * 4) & k) == 0;
+        f32x4 a = *reinterpret_cast<const f32x4*>(s + v * 4), b = *reinterpret_cast<const f32x4*>(s + (v + jv) * 4);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const bool swap = (a[i] > b[i]) == asc;
+          const float na = swap ? b[i] : a[i], nb = swap ? a[i] : b[i];
+          a[i] = na; b[i] = nb;
+        }
+        *reinterpret_cast<f32x4*>(s + v * 4) = a;
+        *reinterpret_cast<f32x4*>(s + (v + jv) * 4) = b;
       }
       __syncthreads();
     }
+    tail8(k, k == 8 && k_first <= 2);
   }
   if (ref == nullptr) {
     for (int i = tid * 4; i < ch; i += nt * 4) *reinterpret_cast<f32x4*>(row + i) = *reinterpret_cast<const f32x4*>(s + i);
