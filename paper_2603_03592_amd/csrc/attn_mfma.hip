@@ -18,16 +18,24 @@ namespace {
 
 constexpr int BQ = 128, BKV = 64;
 
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
 __device__ __forceinline__ int swz8(int row) { return (row ^ (row >> 3)) & 7; }
+
+// Positions of the 16-byte chunks inside a row of the forward kernel's K and V tiles (both are involutions in the
+// chunk index, so the staging side uses the same function to pick the chunk that belongs at a position).  The LDS
+// serves 256 bytes per clock: 16 lanes reading 16 bytes (K fragments: 16 consecutive rows, one chunk index) or 32
+// lanes reading 8 bytes through the transposing read (V: 4 consecutive rows x 4 consecutive chunks) must fall into
+// 16 different 16-byte slots modulo 256 bytes.
+template <int HD> __device__ __forceinline__ int k_pos(int c, int row) { return HD == 128 ? (c ^ (row & 15)) : (c ^ swz8(row)); }
+template <int HD> __device__ __forceinline__ int v_pos(int c, int key) { return HD == 128 ? (c ^ ((key & 3) << 2)) : (c ^ ((key & 2) << 1)); }
 
 template <int HD, bool CAUSAL>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_fwd_mfma_kernel(const bf16* __restrict__ qkv, int64_t ld, bf16* __restrict__ o,
                                                             float* __restrict__ lse, int S, int H, int Hkv, float scale_log2e) {
   constexpr int KCH = HD / 8;                       // 16-byte chunks per K row
   constexpr int KROW = HD * 2;                      // bytes per K row in LDS
-  constexpr int KSTAGE = BKV * KROW, VSTAGE = HD * 128, STAGE = KSTAGE + VSTAGE;
-  constexpr int KPT = BKV * KCH / 256;              // K chunks per thread
-  constexpr int VUNITS = (BKV / 4) * KCH;           // (key quad, d group) units of the V tile
+  constexpr int KSTAGE = BKV * KROW, VSTAGE = BKV * KROW, STAGE = KSTAGE + VSTAGE;
   constexpr int NKK = HD / 16, NDB = HD / 32;
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
@@ -51,49 +59,32 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int nkv = (S + BKV - 1) / BKV;
   const int ntiles = CAUSAL ? min((q0 + BQ + BKV - 1) / BKV, nkv) : nkv;
 
-  bf16x8 kreg[KPT], vreg[4];
-  const bool vactive = tid < VUNITS;
-  const int v_dg = tid % KCH, v_kq = tid / KCH;     // d group (8 wide), key quad (4 keys)
-  auto load_tile = [&](int j) {
+  // Staging: the K and V tiles go global -> LDS row-major with global_load_lds, no registers and no LDS write
+  // instructions.  One wave instruction moves 1 KB = RPI rows; lane (row, position p) fetches the 16-byte chunk
+  // that belongs at position p of its row under the tile's XOR swizzle.
+  constexpr int RPI = 1024 / KROW;                   // rows per wave instruction
+  constexpr int NIK = BKV / RPI;                     // instructions per tile and operand
+  constexpr int IPW = NIK / 4;                       // ... per wave
+  const int s_row = lane / KCH, s_pos = lane % KCH;
+  auto stage_tile = [&](int j, int stage) {
     const int k0 = j * BKV;
-#pragma unroll
-    for (int i = 0; i < KPT; ++i) {
-      const int e = tid + i * 256, r = e / KCH, c = e % KCH;
-      kreg[i] = *reinterpret_cast<const bf16x8*>(kbase + (int64_t)min(k0 + r, S - 1) * ld + c * 8);
-    }
-    if (vactive) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        vreg[i] = *reinterpret_cast<const bf16x8*>(vbase + (int64_t)min(k0 + v_kq * 4 + i, S - 1) * ld + v_dg * 8);
-    }
-  };
-  auto store_tile = [&](int stage) {
     char* ks = smem + stage * STAGE;
     char* vs = ks + KSTAGE;
 #pragma unroll
-    for (int i = 0; i < KPT; ++i) {
-      const int e = tid + i * 256, r = e / KCH, c = e % KCH;
-      *reinterpret_cast<bf16x8*>(ks + r * KROW + (((c & ~7) | ((c ^ r) & 7)) << 4)) = kreg[i];
-    }
-    if (vactive) {
-      typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-      typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
-      u32x4 in[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) in[i] = __builtin_bit_cast(u32x4, vreg[i]);
-      const int g = v_kq >> 2, qd = v_kq & 3;
-      const int chunk = 2 * g + (qd & 1), sub = (qd >> 1) * 8;
-#pragma unroll
-      for (int dd = 0; dd < 8; ++dd) {               // feature v_dg*8 + dd: 4 keys -> 8 bytes
-        const uint32_t sel = (dd & 1) ? 0x07060302u : 0x05040100u;
-        u32x2 ov;
-        ov[0] = __builtin_amdgcn_perm(in[1][dd >> 1], in[0][dd >> 1], sel);
-        ov[1] = __builtin_amdgcn_perm(in[3][dd >> 1], in[2][dd >> 1], sel);
-        const int d = v_dg * 8 + dd;
-        *reinterpret_cast<u32x2*>(vs + d * 128 + ((chunk ^ swz8(d)) << 4) + sub) = ov;
-      }
+    for (int i = 0; i < IPW; ++i) {
+      const int ii = wave * IPW + i, r = ii * RPI + s_row;
+      const int64_t grow = (int64_t)min(k0 + r, S - 1) * ld;      // keys past the end re-read the last one (masked later)
+      const int ck = k_pos<HD>(s_pos, r), cv = v_pos<HD>(s_pos, r);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kbase + grow + ck * 8),
+                                       (__attribute__((address_space(3))) void*)(ks + ii * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vbase + grow + cv * 8),
+                                       (__attribute__((address_space(3))) void*)(vs + ii * 1024), 16, 0, 0);
     }
   };
+  // V^T fragments come out of the row-major tile through the transposing LDS read: in each group of 16 lanes, lane
+  // 4 e + q names 8 bytes (4 features) of key row e, and lane i of the group receives feature i of the four rows.
+  // Group (lane >> 4): feature sub-block (group & 1) * 16, key half group >> 1 -- the MFMA operand's own lane map.
+  const int tr_e = (lane & 15) >> 2, tr_q = lane & 3, tr_nb = (lane >> 4) & 1;
 
   f32x16 oacc[NDB];
 #pragma unroll
@@ -103,31 +94,52 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   float m_run = -INFINITY, l_run = 0.0f;             // in units of log2: scores are scaled by scale*log2(e)
   const int myq = wq0 + l31;
 
-  load_tile(0);
-  store_tile(0);
+  stage_tile(0, 0);
   __syncthreads();
 
   for (int j = 0; j < ntiles; ++j) {
     const bool more = j + 1 < ntiles;
-    if (more) load_tile(j + 1);
+    if (more) stage_tile(j + 1, (j + 1) & 1);
     const int k0 = j * BKV;
     const bool wave_active = !CAUSAL || k0 <= wq0 + 31;
     if (wave_active) {
       const char* ks = smem + (j & 1) * STAGE;
       const char* vs = ks + KSTAGE;
-      f32x16 s[2];
+      // All K fragments of the tile are requested before the first MFMA (one LDS latency instead of sixteen), and the
+      // V^T fragments right after the score MFMAs are queued, so that they arrive while the softmax runs.
+      bf16x8 kf[2][NKK];
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[t][r] = 0.0f;
-        const int krow = t * 32 + l31;
+      for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int kk = 0; kk < NKK; ++kk) {
-          const int c = kk * 2 + half;
-          const bf16x8 kf = *reinterpret_cast<const bf16x8*>(ks + krow * KROW + (((c & ~7) | ((c ^ krow) & 7)) << 4));
-          s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s[t], 0, 0, 0);
+          const int krow = t * 32 + l31, c = kk * 2 + half;
+          kf[t][kk] = *reinterpret_cast<const bf16x8*>(ks + krow * KROW + (k_pos<HD>(c, krow) << 4));
         }
-      }
+      f32x16 s[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[t][r] = 0.0f;
+#pragma unroll
+      for (int kk = 0; kk < NKK; ++kk)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t][kk], qf[kk], s[t], 0, 0, 0);
+      bf16x8 vf[4][NDB];
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) {
+          // keys of MFMA g in operand order: {0-3, 8-11} for the lower lane half, {4-7, 12-15} for the upper one
+#pragma unroll
+          for (int r2 = 0; r2 < 2; ++r2) {
+            const int key = (g >> 1) * 32 + (g & 1) * 16 + r2 * 8 + half * 4 + tr_e;
+            const int chunk = db * 4 + tr_nb * 2 + (tr_q >> 1);
+            const bf16x4 t4 = __builtin_bit_cast(bf16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) s16x4*)(vs + key * KROW + (v_pos<HD>(chunk, key) << 4) + (tr_q & 1) * 8)));
+#pragma unroll
+            for (int i = 0; i < 4; ++i) vf[g][db][r2 * 4 + i] = t4[i];
+          }
+        }
       // mask (diagonal tiles and the ragged key tail), then the online softmax update
       const bool need_mask = (CAUSAL && k0 + BKV - 1 > wq0) || (k0 + BKV > S);
       float mx = -INFINITY;
@@ -165,14 +177,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
       for (int g = 0; g < 4; ++g)
 #pragma unroll
-        for (int db = 0; db < NDB; ++db) {
-          const int d = db * 32 + l31;
-          const bf16x8 vf = *reinterpret_cast<const bf16x8*>(vs + d * 128 + (((2 * g + half) ^ swz8(d)) << 4));
-          oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[g], oacc[db], 0, 0, 0);
-        }
+        for (int db = 0; db < NDB; ++db) oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[g][db], pf[g], oacc[db], 0, 0, 0);
     }
-    if (more) store_tile((j + 1) & 1);
-    __syncthreads();
+    __syncthreads();                                  // fence + barrier: the next tile has landed for everybody
   }
 
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
