@@ -219,9 +219,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
 
-// row-major tile: rows of HD bf16, 16-byte chunks swizzled by the row
+// row-major tile: rows of HD bf16, 16-byte chunks swizzled by the row (16 consecutive rows of one chunk index fall into
+// 16 different slots modulo 256 bytes)
 template <int HD>
-__device__ __forceinline__ int rm_off(int row, int chunk) { return row * (HD * 2) + (((chunk & ~7) | ((chunk ^ row) & 7)) << 4); }
+__device__ __forceinline__ int rm_off(int row, int chunk) { return row * (HD * 2) + (k_pos<HD>(chunk, row) << 4); }
 // transposed tile: row = feature d (128 bytes = 64 rows of the source, in the MFMA key order), 8-byte piece of source-row quad rq
 __device__ __forceinline__ int tr_off(int d, int rq) {
   const int g = rq >> 2, qd = rq & 3;
