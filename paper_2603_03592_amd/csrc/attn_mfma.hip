@@ -22,13 +22,55 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 
 __device__ __forceinline__ int swz8(int row) { return (row ^ (row >> 3)) & 7; }
 
-// Positions of the 16-byte chunks inside a row of the forward kernel's K and V tiles (both are involutions in the
-// chunk index, so the staging side uses the same function to pick the chunk that belongs at a position).  The LDS
-// serves 256 bytes per clock: 16 lanes reading 16 bytes (K fragments: 16 consecutive rows, one chunk index) or 32
-// lanes reading 8 bytes through the transposing read (V: 4 consecutive rows x 4 consecutive chunks) must fall into
-// 16 different 16-byte slots modulo 256 bytes.
-template <int HD> __device__ __forceinline__ int k_pos(int c, int row) { return HD == 128 ? (c ^ (row & 15)) : (c ^ swz8(row)); }
-template <int HD> __device__ __forceinline__ int v_pos(int c, int key) { return HD == 128 ? (c ^ ((key & 3) << 2)) : (c ^ ((key & 2) << 1)); }
+// Position of 16-byte chunk c inside row `row` of a row-major LDS tile (an involution in c, so the staging side uses
+// the same function to pick the chunk that belongs at a position).  The LDS serves 256 bytes per clock, and a tile is
+// read in two ways: fragments along the rows (16 consecutive rows, one chunk index, 16 bytes per lane) and transposed
+// fragments through ds_read_b64_tr_b16 (32 lanes: 4 consecutive rows x 4 consecutive chunks, 8 bytes per lane).  With
+// the two 2-bit fields of the row number swapped into the XOR mask both patterns fall into 16 different 16-byte slots
+// modulo 256 bytes (rows of 128 bytes, head_dim 64: the row parity is one slot bit, the mask has three bits).
+template <int HD> __device__ __forceinline__ int rm_pos(int c, int row) {
+  return HD == 128 ? (c ^ (((row & 3) << 2) | ((row >> 2) & 3))) : (c ^ ((((row >> 1) & 1) << 2) | ((row >> 2) & 3)));
+}
+
+// Two 64-row tiles (rows r0 .. r0 + 63 of a and of b, HD bf16 each, clamped to the last valid row) go global -> LDS
+// row-major with global_load_lds: no registers, no LDS write instructions.  One wave instruction moves 1 KB = RPI rows;
+// lane (row, position p) fetches the 16-byte chunk that belongs at position p of its row under rm_pos.  256 threads.
+template <int HD>
+__device__ __forceinline__ void stage_two_tiles(const bf16* a, const bf16* b, int64_t ld, int r0, int last_row, char* ta, char* tb, int wave,
+                                                int lane) {
+  constexpr int KCH = HD / 8, KROW = HD * 2, RPI = 1024 / KROW, IPW = (64 / RPI) / 4;
+  const int s_row = lane / KCH, s_pos = lane % KCH;
+#pragma unroll
+  for (int i = 0; i < IPW; ++i) {
+    const int ii = wave * IPW + i, r = ii * RPI + s_row;
+    const int64_t g = (int64_t)min(r0 + r, last_row) * ld + rm_pos<HD>(s_pos, r) * 8;
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a + g),
+                                     (__attribute__((address_space(3))) void*)(ta + ii * 1024), 16, 0, 0);
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(b + g),
+                                     (__attribute__((address_space(3))) void*)(tb + ii * 1024), 16, 0, 0);
+  }
+}
+
+// A-operand fragment of the TRANSPOSE of a row-major 64-row tile, for MFMA g (0..3) of the tile's 64 rows and feature
+// block db: the lane gets features db * 32 + (lane & 31) of 8 rows, in the order the score accumulators hold them
+// ({0-3, 8-11} of the 16 rows for the lower lane half, {4-7, 12-15} for the upper one).  Transposing LDS read: in each
+// group of 16 lanes, lane 4 e + q names 8 bytes (4 features) of row e, and lane i of the group receives feature i of the
+// four rows.  Group (lane >> 4): feature sub-block (group & 1) * 16, row half group >> 1 -- the operand's own lane map.
+template <int HD>
+__device__ __forceinline__ bf16x8 tr_fragment(const char* tile, int g, int db, int lane) {
+  const int tr_e = (lane & 15) >> 2, tr_q = lane & 3, tr_nb = (lane >> 4) & 1, half = lane >> 5;
+  bf16x8 f;
+#pragma unroll
+  for (int r2 = 0; r2 < 2; ++r2) {
+    const int row = (g >> 1) * 32 + (g & 1) * 16 + r2 * 8 + half * 4 + tr_e;
+    const int chunk = db * 4 + tr_nb * 2 + (tr_q >> 1);
+    const bf16x4 t4 = __builtin_bit_cast(bf16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) s16x4*)(tile + row * (HD * 2) + (rm_pos<HD>(chunk, row) << 4) + (tr_q & 1) * 8)));
+#pragma unroll
+    for (int i = 0; i < 4; ++i) f[r2 * 4 + i] = t4[i];
+  }
+  return f;
+}
 
 template <int HD, bool CAUSAL>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_fwd_mfma_kernel(const bf16* __restrict__ qkv, int64_t ld, bf16* __restrict__ o,
@@ -59,32 +101,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int nkv = (S + BKV - 1) / BKV;
   const int ntiles = CAUSAL ? min((q0 + BQ + BKV - 1) / BKV, nkv) : nkv;
 
-  // Staging: the K and V tiles go global -> LDS row-major with global_load_lds, no registers and no LDS write
-  // instructions.  One wave instruction moves 1 KB = RPI rows; lane (row, position p) fetches the 16-byte chunk
-  // that belongs at position p of its row under the tile's XOR swizzle.
-  constexpr int RPI = 1024 / KROW;                   // rows per wave instruction
-  constexpr int NIK = BKV / RPI;                     // instructions per tile and operand
-  constexpr int IPW = NIK / 4;                       // ... per wave
-  const int s_row = lane / KCH, s_pos = lane % KCH;
   auto stage_tile = [&](int j, int stage) {
-    const int k0 = j * BKV;
     char* ks = smem + stage * STAGE;
-    char* vs = ks + KSTAGE;
-#pragma unroll
-    for (int i = 0; i < IPW; ++i) {
-      const int ii = wave * IPW + i, r = ii * RPI + s_row;
-      const int64_t grow = (int64_t)min(k0 + r, S - 1) * ld;      // keys past the end re-read the last one (masked later)
-      const int ck = k_pos<HD>(s_pos, r), cv = v_pos<HD>(s_pos, r);
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kbase + grow + ck * 8),
-                                       (__attribute__((address_space(3))) void*)(ks + ii * 1024), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vbase + grow + cv * 8),
-                                       (__attribute__((address_space(3))) void*)(vs + ii * 1024), 16, 0, 0);
-    }
+    stage_two_tiles<HD>(kbase, vbase, ld, j * BKV, S - 1, ks, ks + KSTAGE, wave, lane);   // keys past the end: masked later
   };
-  // V^T fragments come out of the row-major tile through the transposing LDS read: in each group of 16 lanes, lane
-  // 4 e + q names 8 bytes (4 features) of key row e, and lane i of the group receives feature i of the four rows.
-  // Group (lane >> 4): feature sub-block (group & 1) * 16, key half group >> 1 -- the MFMA operand's own lane map.
-  const int tr_e = (lane & 15) >> 2, tr_q = lane & 3, tr_nb = (lane >> 4) & 1;
 
   f32x16 oacc[NDB];
 #pragma unroll
@@ -113,7 +133,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
         for (int kk = 0; kk < NKK; ++kk) {
           const int krow = t * 32 + l31, c = kk * 2 + half;
-          kf[t][kk] = *reinterpret_cast<const bf16x8*>(ks + krow * KROW + (k_pos<HD>(c, krow) << 4));
+          kf[t][kk] = *reinterpret_cast<const bf16x8*>(ks + krow * KROW + (rm_pos<HD>(c, krow) << 4));
         }
       f32x16 s[2];
 #pragma unroll
@@ -128,18 +148,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
       for (int g = 0; g < 4; ++g)
 #pragma unroll
-        for (int db = 0; db < NDB; ++db) {
-          // keys of MFMA g in operand order: {0-3, 8-11} for the lower lane half, {4-7, 12-15} for the upper one
-#pragma unroll
-          for (int r2 = 0; r2 < 2; ++r2) {
-            const int key = (g >> 1) * 32 + (g & 1) * 16 + r2 * 8 + half * 4 + tr_e;
-            const int chunk = db * 4 + tr_nb * 2 + (tr_q >> 1);
-            const bf16x4 t4 = __builtin_bit_cast(bf16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (__attribute__((address_space(3))) s16x4*)(vs + key * KROW + (v_pos<HD>(chunk, key) << 4) + (tr_q & 1) * 8)));
-#pragma unroll
-            for (int i = 0; i < 4; ++i) vf[g][db][r2 * 4 + i] = t4[i];
-          }
-        }
+        for (int db = 0; db < NDB; ++db) vf[g][db] = tr_fragment<HD>(vs, g, db, lane);
       // mask (diagonal tiles and the ragged key tail), then the online softmax update
       const bool need_mask = (CAUSAL && k0 + BKV - 1 > wq0) || (k0 + BKV > S);
       float mx = -INFINITY;
@@ -222,7 +231,7 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
 // row-major tile: rows of HD bf16, 16-byte chunks swizzled by the row (16 consecutive rows of one chunk index fall into
 // 16 different slots modulo 256 bytes)
 template <int HD>
-__device__ __forceinline__ int rm_off(int row, int chunk) { return row * (HD * 2) + (k_pos<HD>(chunk, row) << 4); }
+__device__ __forceinline__ int rm_off(int row, int chunk) { return row * (HD * 2) + (rm_pos<HD>(chunk, row) << 4); }
 // transposed tile: row = feature d (128 bytes = 64 rows of the source, in the MFMA key order), 8-byte piece of source-row quad rq
 __device__ __forceinline__ int tr_off(int d, int rq) {
   const int g = rq >> 2, qd = rq & 3;
@@ -270,8 +279,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                                                                float scale, const float* __restrict__ rope_cs) {
   constexpr int KCH = HD / 8, NKK = HD / 16, NDB = HD / 32;
   constexpr int TILE = BKV * HD * 2;                 // bytes of one 64-row tile (row-major or transposed)
-  constexpr int STAGE = 3 * TILE;                    // K row-major, V row-major, K transposed
-  constexpr int UNITS = (BKV / 4) * KCH;
+  constexpr int STAGE = 2 * TILE;                    // K and V, both row-major (K is read along its rows and transposed)
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int nqt = (S + BQ - 1) / BQ;
   const int qt = nqt - 1 - (int)blockIdx.x;
@@ -306,23 +314,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
   const int nkv = (S + BKV - 1) / BKV;
   const int ntiles = CAUSAL ? min((q0 + BQ + BKV - 1) / BKV, nkv) : nkv;
-  const bool active = tid < UNITS;
-  const int u_dg = tid % KCH, u_rq = tid / KCH;
-  bf16x8 kreg[4], vreg[4];
-  auto load_tile = [&](int j) {
-    if (!active) return;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int64_t row = min(j * BKV + u_rq * 4 + i, S - 1);
-      kreg[i] = *reinterpret_cast<const bf16x8*>(kbase + row * ld + u_dg * 8);
-      vreg[i] = *reinterpret_cast<const bf16x8*>(vbase + row * ld + u_dg * 8);
-    }
-  };
-  auto store_tile = [&](int stage) {
-    if (!active) return;
+  auto stage_tile = [&](int j, int stage) {
     char* base = smem + stage * STAGE;
-    stage_quad<HD, true, true>(base, base + 2 * TILE, kreg, u_rq, u_dg);
-    stage_quad<HD, true, false>(base + TILE, nullptr, vreg, u_rq, u_dg);
+    stage_two_tiles<HD>(kbase, vbase, ld, j * BKV, S - 1, base, base + TILE, wave, lane);
   };
 
   f32x16 dq[NDB];
@@ -331,17 +325,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
     for (int r = 0; r < 16; ++r) dq[i][r] = 0.0f;
 
-  load_tile(0);
-  store_tile(0);
+  stage_tile(0, 0);
   __syncthreads();
   for (int j = 0; j < ntiles; ++j) {
     const bool more = j + 1 < ntiles;
-    if (more) load_tile(j + 1);
+    if (more) stage_tile(j + 1, (j + 1) & 1);
     const int k0 = j * BKV;
     if (!CAUSAL || k0 <= wq0 + 31) {
       const char* ks = smem + (j & 1) * STAGE;
       const char* vs = ks + TILE;
-      const char* kt = ks + 2 * TILE;
       const bool need_mask = (CAUSAL && k0 + BKV - 1 > wq0) || (k0 + BKV > S);
       // one 32-key block at a time, to keep only 32 score registers live
 #pragma unroll
@@ -371,13 +363,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         for (int g2 = 0; g2 < 2; ++g2)
 #pragma unroll
           for (int db = 0; db < NDB; ++db) {
-            const bf16x8 ktf = *reinterpret_cast<const bf16x8*>(kt + tr_frag_off(db * 32 + l31, t * 2 + g2, half));
+            const bf16x8 ktf = tr_fragment<HD>(ks, t * 2 + g2, db, lane);
             dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf, dsf[g2], dq[db], 0, 0, 0);
           }
       }
     }
-    if (more) store_tile((j + 1) & 1);
-    __syncthreads();
+    __syncthreads();                                  // fence + barrier: the next tile has landed for everybody
   }
   if (myq < S) {
     bf16* out = dqkv + ((int64_t)b * S + myq) * ld + (int64_t)h * HD;
@@ -587,7 +578,7 @@ hipError_t mfma_attn_bwd(const void* qkv, int64_t ld, const void* o, const void*
   do {                                                                                                                  \
     auto kq = attn_bwd_dq_mfma_kernel<HDV, CZ>;                                                                         \
     auto kk = attn_bwd_dkv_mfma_kernel<HDV, CZ>;                                                                        \
-    constexpr int lq = 2 * 3 * (64 * HDV * 2), lk = 2 * (4 * 64 * HDV * 2 + 512);                                       \
+    constexpr int lq = 2 * 2 * (64 * HDV * 2), lk = 2 * (4 * 64 * HDV * 2 + 512);                                       \
     static bool configured = false;                                                                                     \
     if (!configured) {                                                                                                  \
       hipError_t e = hipFuncSetAttribute((const void*)kq, hipFuncAttributeMaxDynamicSharedMemorySize, lq);              \
