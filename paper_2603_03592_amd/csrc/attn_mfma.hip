@@ -20,8 +20,6 @@ constexpr int BQ = 128, BKV = 64;
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 
-__device__ __forceinline__ int swz8(int row) { return (row ^ (row >> 3)) & 7; }
-
 // Position of 16-byte chunk c inside row `row` of a row-major LDS tile (an involution in c, so the staging side uses
 // the same function to pick the chunk that belongs at a position).  The LDS serves 256 bytes per clock, and a tile is
 // read in two ways: fragments along the rows (16 consecutive rows, one chunk index, 16 bytes per lane) and transposed
@@ -32,21 +30,23 @@ template <int HD> __device__ __forceinline__ int rm_pos(int c, int row) {
   return HD == 128 ? (c ^ (((row & 3) << 2) | ((row >> 2) & 3))) : (c ^ ((((row >> 1) & 1) << 2) | ((row >> 2) & 3)));
 }
 
-// Two 64-row tiles (rows r0 .. r0 + 63 of a and of b, HD bf16 each, clamped to the last valid row) go global -> LDS
+// Two 64-row tiles (rows r0 .. r0 + 63 of a and of b, HD bf16 each, row pitches lda / ldb, clamped to the last valid
+// row) go global -> LDS
 // row-major with global_load_lds: no registers, no LDS write instructions.  One wave instruction moves 1 KB = RPI rows;
 // lane (row, position p) fetches the 16-byte chunk that belongs at position p of its row under rm_pos.  256 threads.
 template <int HD>
-__device__ __forceinline__ void stage_two_tiles(const bf16* a, const bf16* b, int64_t ld, int r0, int last_row, char* ta, char* tb, int wave,
-                                                int lane) {
+__device__ __forceinline__ void stage_two_tiles(const bf16* a, int64_t lda, const bf16* b, int64_t ldb, int r0, int last_row, char* ta,
+                                                char* tb, int wave, int lane) {
   constexpr int KCH = HD / 8, KROW = HD * 2, RPI = 1024 / KROW, IPW = (64 / RPI) / 4;
   const int s_row = lane / KCH, s_pos = lane % KCH;
 #pragma unroll
   for (int i = 0; i < IPW; ++i) {
     const int ii = wave * IPW + i, r = ii * RPI + s_row;
-    const int64_t g = (int64_t)min(r0 + r, last_row) * ld + rm_pos<HD>(s_pos, r) * 8;
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a + g),
+    const int64_t row = min(r0 + r, last_row);
+    const int col = rm_pos<HD>(s_pos, r) * 8;
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a + row * lda + col),
                                      (__attribute__((address_space(3))) void*)(ta + ii * 1024), 16, 0, 0);
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(b + g),
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(b + row * ldb + col),
                                      (__attribute__((address_space(3))) void*)(tb + ii * 1024), 16, 0, 0);
   }
 }
@@ -103,7 +103,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
   auto stage_tile = [&](int j, int stage) {
     char* ks = smem + stage * STAGE;
-    stage_two_tiles<HD>(kbase, vbase, ld, j * BKV, S - 1, ks, ks + KSTAGE, wave, lane);   // keys past the end: masked later
+    stage_two_tiles<HD>(kbase, ld, vbase, ld, j * BKV, S - 1, ks, ks + KSTAGE, wave, lane);   // keys past the end: masked later
   };
 
   f32x16 oacc[NDB];
@@ -225,19 +225,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 // Staging pattern shared by both: a thread loads 4 consecutive rows x 8 features (4 x 16 bytes),
 // writes them row-major as they are and transposed as 8 x 8-byte pieces.
 
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
-typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
-
-// row-major tile: rows of HD bf16, 16-byte chunks swizzled by the row (16 consecutive rows of one chunk index fall into
-// 16 different slots modulo 256 bytes)
+// byte offset of 16-byte chunk `chunk` of row `row` in a row-major tile
 template <int HD>
 __device__ __forceinline__ int rm_off(int row, int chunk) { return row * (HD * 2) + (rm_pos<HD>(chunk, row) << 4); }
-// transposed tile: row = feature d (128 bytes = 64 rows of the source, in the MFMA key order), 8-byte piece of source-row quad rq
-__device__ __forceinline__ int tr_off(int d, int rq) {
-  const int g = rq >> 2, qd = rq & 3;
-  return d * 128 + (((2 * g + (qd & 1)) ^ swz8(d)) << 4) + (qd >> 1) * 8;
-}
-__device__ __forceinline__ int tr_frag_off(int d, int g, int half) { return d * 128 + (((2 * g + half) ^ swz8(d)) << 4); }
 
 // Inverse RoPE of 4 consecutive features d..d+3 (two pairs) of the token at in-sequence position p:
 // (a, b) -> (a cos + b sin, -a sin + b cos), the transpose of the forward rotation.
@@ -249,27 +239,6 @@ __device__ __forceinline__ void unrope4(float (&v)[4], const float* __restrict__
   v[1] = b0 * t[0] - a0 * t[1];
   v[2] = a1 * t[2] + b1 * t[3];
   v[3] = b1 * t[2] - a1 * t[3];
-}
-
-template <int HD, bool ROWMAJOR, bool TRANSPOSED>
-__device__ __forceinline__ void stage_quad(char* rm, char* tr, const bf16x8 (&reg)[4], int rq, int dg) {
-  if (ROWMAJOR) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) *reinterpret_cast<bf16x8*>(rm + rm_off<HD>(rq * 4 + i, dg)) = reg[i];
-  }
-  if (TRANSPOSED) {
-    u32x4_t in[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) in[i] = __builtin_bit_cast(u32x4_t, reg[i]);
-#pragma unroll
-    for (int dd = 0; dd < 8; ++dd) {
-      const uint32_t sel = (dd & 1) ? 0x07060302u : 0x05040100u;
-      u32x2_t ov;
-      ov[0] = __builtin_amdgcn_perm(in[1][dd >> 1], in[0][dd >> 1], sel);
-      ov[1] = __builtin_amdgcn_perm(in[3][dd >> 1], in[2][dd >> 1], sel);
-      *reinterpret_cast<u32x2_t*>(tr + tr_off(dg * 8 + dd, rq)) = ov;
-    }
-  }
 }
 
 template <int HD, bool CAUSAL>
@@ -316,7 +285,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int ntiles = CAUSAL ? min((q0 + BQ + BKV - 1) / BKV, nkv) : nkv;
   auto stage_tile = [&](int j, int stage) {
     char* base = smem + stage * STAGE;
-    stage_two_tiles<HD>(kbase, vbase, ld, j * BKV, S - 1, base, base + TILE, wave, lane);
+    stage_two_tiles<HD>(kbase, ld, vbase, ld, j * BKV, S - 1, base, base + TILE, wave, lane);
   };
 
   f32x16 dq[NDB];
@@ -395,8 +364,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
                                                                 const float* __restrict__ rope_cs) {
   constexpr int KCH = HD / 8, NKK = HD / 16, NDB = HD / 32;
   constexpr int TILE = 64 * HD * 2;
-  constexpr int STAGE = 4 * TILE + 512;              // Q rm, dO rm, Q^T, dO^T, lse2[64], delta[64]
-  constexpr int UNITS = 16 * KCH;
+  constexpr int STAGE = 2 * TILE + 512;              // Q and dO row-major (read along the rows and transposed), lse2[64], delta[64]
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int kvh = blockIdx.y, b = blockIdx.z, G = H / Hkv;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l31 = lane & 31, half = lane >> 5;
@@ -417,35 +385,23 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
   const int qstart = CAUSAL ? (k0 / 64) * 64 : 0;
   const int nq = (S - qstart + 63) / 64;             // query tiles per head
   const int ntiles = nq * G;
-  const bool active = tid < UNITS;
-  const int u_dg = tid % KCH, u_rq = tid / KCH;
-  bf16x8 qreg[4], dreg[4];
   float lreg = 0.0f, dlreg = 0.0f;
-  auto load_tile = [&](int j) {
+  auto stage_tile = [&](int j, int stage) {            // Q and dO tiles straight to LDS; the two per-query scalars via registers
     const int h = kvh * G + j / nq, q0 = qstart + (j % nq) * 64;
-    if (active) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int64_t tok = (int64_t)b * S + min(q0 + u_rq * 4 + i, S - 1);
-        qreg[i] = *reinterpret_cast<const bf16x8*>(qkv + tok * ld + (int64_t)h * HD + u_dg * 8);
-        dreg[i] = *reinterpret_cast<const bf16x8*>(dout + tok * Dq + (int64_t)h * HD + u_dg * 8);
-      }
-    }
+    char* base = smem + stage * STAGE;
+    stage_two_tiles<HD>(qkv + (int64_t)b * S * ld + (int64_t)h * HD, ld, dout + (int64_t)b * S * Dq + (int64_t)h * HD, Dq, q0, S - 1, base,
+                        base + TILE, wave, lane);
     if (tid < 64) {
       const int64_t li = ((int64_t)b * H + h) * S + min(q0 + tid, S - 1);
       lreg = lse[li] * 1.4426950408889634f;
       dlreg = delta[li];
     }
   };
-  auto store_tile = [&](int stage) {
-    char* base = smem + stage * STAGE;
-    if (active) {
-      stage_quad<HD, true, true>(base, base + 2 * TILE, qreg, u_rq, u_dg);
-      stage_quad<HD, true, true>(base + TILE, base + 3 * TILE, dreg, u_rq, u_dg);
-    }
+  auto store_scalars = [&](int stage) {
     if (tid < 64) {
-      reinterpret_cast<float*>(base + 4 * TILE)[tid] = lreg;
-      reinterpret_cast<float*>(base + 4 * TILE + 256)[tid] = dlreg;
+      char* base = smem + stage * STAGE;
+      reinterpret_cast<float*>(base + 2 * TILE)[tid] = lreg;
+      reinterpret_cast<float*>(base + 2 * TILE + 256)[tid] = dlreg;
     }
   };
 
@@ -456,20 +412,18 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
     for (int r = 0; r < 16; ++r) { dk[i][r] = 0.0f; dv[i][r] = 0.0f; }
 
   if (ntiles > 0) {
-    load_tile(0);
-    store_tile(0);
+    stage_tile(0, 0);
+    store_scalars(0);
   }
   __syncthreads();
   for (int j = 0; j < ntiles; ++j) {
     const bool more = j + 1 < ntiles;
-    if (more) load_tile(j + 1);
+    if (more) stage_tile(j + 1, (j + 1) & 1);
     const int q0 = qstart + (j % nq) * 64;
     if (!CAUSAL || q0 + 63 >= wk0) {
       const char* qs = smem + (j & 1) * STAGE;
       const char* ds_ = qs + TILE;
-      const char* qt = qs + 2 * TILE;
-      const char* dt = qs + 3 * TILE;
-      const float* ls = reinterpret_cast<const float*>(qs + 4 * TILE);
+      const float* ls = reinterpret_cast<const float*>(qs + 2 * TILE);
       const float* dls = ls + 64;
       f32x16 s[2], dp[2];
 #pragma unroll
@@ -510,14 +464,14 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
       for (int g = 0; g < 4; ++g)
 #pragma unroll
         for (int db = 0; db < NDB; ++db) {
-          const bf16x8 dtf = *reinterpret_cast<const bf16x8*>(dt + tr_frag_off(db * 32 + l31, g, half));
-          const bf16x8 qtf = *reinterpret_cast<const bf16x8*>(qt + tr_frag_off(db * 32 + l31, g, half));
+          const bf16x8 dtf = tr_fragment<HD>(ds_, g, db, lane);
+          const bf16x8 qtf = tr_fragment<HD>(qs, g, db, lane);
           dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dtf, pf[g], dv[db], 0, 0, 0);
           dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qtf, dsf[g], dk[db], 0, 0, 0);
         }
     }
-    if (more) store_tile((j + 1) & 1);
-    __syncthreads();
+    if (more) store_scalars((j + 1) & 1);
+    __syncthreads();                                  // fence + barrier: the next tiles have landed for everybody
   }
   if (mykey < S) {
     bf16* out = dqkv + ((int64_t)b * S + mykey) * ld + Dq + (int64_t)kvh * HD;
@@ -578,7 +532,7 @@ hipError_t mfma_attn_bwd(const void* qkv, int64_t ld, const void* o, const void*
   do {                                                                                                                  \
     auto kq = attn_bwd_dq_mfma_kernel<HDV, CZ>;                                                                         \
     auto kk = attn_bwd_dkv_mfma_kernel<HDV, CZ>;                                                                        \
-    constexpr int lq = 2 * 2 * (64 * HDV * 2), lk = 2 * (4 * 64 * HDV * 2 + 512);                                       \
+    constexpr int lq = 2 * 2 * (64 * HDV * 2), lk = 2 * (2 * 64 * HDV * 2 + 512);                                       \
     static bool configured = false;                                                                                     \
     if (!configured) {                                                                                                  \
       hipError_t e = hipFuncSetAttribute((const void*)kq, hipFuncAttributeMaxDynamicSharedMemorySize, lq);              \
