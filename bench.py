@@ -381,6 +381,28 @@ def main():
                       "per_op_ms": {k: round(v["ms"] / a.steps, 4) for k, v in prof.items() if v["launches"]},
                       "per_op_tflops": {k: round(v["flop"] / (v["ms"] * 1e-3) / 1e12, 1) for k, v in prof.items() if v["flop"] and v["ms"] > 0}},
     }
+    if wl.name.startswith("sweep"):
+        # many workers per stage: up to 128 concurrent submissions of the stage output scored in one call against the
+        # recomputation they share (submissions made on the device from the recomputed output; capped at 16 GiB)
+        n_sub = int(max(1, min(128, (16 << 30) // (T * desc.d_model * 2))))
+        ref_out = first["h_hat"].reshape(T, desc.d_model)
+        subs = torch.empty((n_sub, T, desc.d_model), dtype=ref_out.dtype, device="cuda")
+        for i in range(n_sub):
+            subs[i] = ref_out * (1.5 if i % 8 == 3 else 1.0)
+        ver.score_and_flag(subs, ref_out, tau=tau)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            r = ver.score_and_flag(subs, ref_out, tau=tau)
+        e1.record()
+        torch.cuda.synchronize()
+        ms_sc = e0.elapsed_time(e1) / 5
+        fl = ver.read_results(r["result"])["flag"]
+        assert [int(f) for f in fl] == [int(i % 8 == 3) for i in range(n_sub)]
+        by = (n_sub + 1) * T * desc.d_model * 2
+        out["concurrent_scoring"] = {"submissions": n_sub, "ms": ms_sc, "achieved_GBs": by / (ms_sc * 1e-3) / 1e9,
+                                     "frac_of_hbm_peak": by / (ms_sc * 1e-3) / 1e9 / PEAK_HBM_GBS}
+        del subs
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, wdev, h_in, g_out, backward)
     ver.close()
