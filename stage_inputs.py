@@ -219,6 +219,52 @@ def attack_tokens(x: np.ndarray, frac: float, kind: str, seed: int, dtype: str) 
     return to_stage_dtype(x, dtype), tok
 
 
+# --- the remaining attack variants of the paper's "Attack Variants" paragraph and its adaptive attack --------------
+def attack_constant(x: np.ndarray, value: float, dtype: str) -> np.ndarray:
+    """Constant attack: every element is `value` (the paper names zeros and negative ones)."""
+    return to_stage_dtype(np.full_like(x, value, dtype=np.float32), dtype)
+
+
+def attack_random_value(x: np.ndarray, seed: int, dtype: str) -> np.ndarray:
+    """Random value attack: every element drawn from N(0, 1)."""
+    return to_stage_dtype(_rng(seed, 23).standard_normal(x.shape).astype(np.float32), dtype)
+
+
+def attack_sign_elements(x: np.ndarray, p: float, seed: int, dtype: str) -> np.ndarray:
+    """Random sign attack: each element's sign is flipped with probability p."""
+    flip = _rng(seed, 24).random(x.shape) < p
+    return to_stage_dtype(np.where(flip, -x, x).astype(np.float32), dtype)
+
+
+def invisible_noise_zmax(p: float) -> float:
+    """z_max = sqrt(2) erfinv(2 p - 1): the p-quantile of the standard normal."""
+    from scipy.special import erfinv
+    return float(math.sqrt(2.0) * erfinv(2.0 * p - 1.0))
+
+
+def attack_invisible_noise(x: np.ndarray, p: float, seed: int, dtype: str) -> np.ndarray:
+    """Invisible noise attack: mu + z_max (sigma * eps) with mu, sigma the per-feature mean and standard deviation of
+    the signal over its tokens (the element-wise statistics a single signal [.., D] offers) and eps ~ N(0, I)."""
+    x2 = x.reshape(-1, x.shape[-1]).astype(np.float64)
+    mu, sd = x2.mean(axis=0), x2.std(axis=0)
+    eps = _rng(seed, 25).standard_normal(x2.shape)
+    return to_stage_dtype((mu + invisible_noise_zmax(p) * sd * eps).reshape(x.shape).astype(np.float32), dtype)
+
+
+def attack_drift(m_stale: np.ndarray, target: np.ndarray, alpha: float, sigma: float, seed: int, dtype: str) -> np.ndarray:
+    """Adaptive attack: m + alpha (target - m) / ||m|| + eps, with m the attacker's stale EMA of the signals it sent
+    and eps ~ N(0, sigma^2)."""
+    m = m_stale.astype(np.float64)
+    out = m + alpha * (target.astype(np.float64) - m) / max(float(np.linalg.norm(m)), 1e-30)
+    out = out + sigma * _rng(seed, 26).standard_normal(m.shape)
+    return to_stage_dtype(out.astype(np.float32), dtype)
+
+
+def drift_delay(beta: float) -> int:
+    """delta = ceil(log 0.1 / log beta): how stale the attacker's EMA is."""
+    return int(math.ceil(math.log(0.1) / math.log(beta)))
+
+
 def small_claim_plan(n_claims: int = 64, seed: int = 0) -> List[str]:
     """Small config: 10 % scaled by 1.5, 10 % sign-flipped on 5 % of channels, rest honest."""
     n_bad = int(round(0.1 * n_claims))
@@ -245,4 +291,12 @@ def make_claim(kind: str, reference: np.ndarray, dtype: str, seed: int) -> np.nd
         return attack_zero(reference, dtype)
     if kind.startswith("tok_"):
         return attack_tokens(reference, 0.01, kind[4:], seed, dtype)[0]
+    if kind == "const_neg1":
+        return attack_constant(reference, -1.0, dtype)
+    if kind == "random":
+        return attack_random_value(reference, seed, dtype)
+    if kind == "sign_p":
+        return attack_sign_elements(reference, 0.1, seed, dtype)
+    if kind == "invisible":
+        return attack_invisible_noise(reference, 0.99, seed, dtype)
     raise ValueError(kind)

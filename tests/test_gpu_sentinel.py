@@ -86,6 +86,31 @@ def test_verifier_loop_matches_oracle(dtype):
     lib.close(); ver.close()
 
 
+def test_verifier_loop_value_replacing_and_delay_attacks():
+    """The paper's remaining attack variants through both implementations: constant, random value, element-wise random
+    sign and invisible noise are caught where they happen; a delayed honest signal passes."""
+    dtype = "bf16"
+    torch, ver, lib, ref = _pair(dtype)
+    for t in range(WARM):
+        _iteration(torch, lib, ref, t, True, dtype)
+    t = WARM
+    for w, kind in enumerate(("const_neg1", "random", "sign_p", "invisible")):
+        _iteration(torch, lib, ref, t, False, dtype, attack_h=(0, w, kind), attack_g=(2, w + 1, kind)); t += 1
+        assert ref.pol["h"][0].v[w] >= 1 and ref.pol["g"][2].v[w + 1] >= 1, kind
+    # delay attack, k = 20: worker 5 of stage 1 re-sends what it sent 20 iterations ago
+    lib.begin_iteration(False); ref.begin_iteration(False)
+    for s in range(P):
+        sig = [si.to_stage_dtype(x, dtype) for x in _signals("h", s, t)]
+        if s == 1:
+            sig[5] = si.to_stage_dtype(si.stream_signal("h", 1, 5, t - 20, T, D, "f32"), dtype)
+        want, wg = ref.forward(s, sig)
+        got, gg = lib.forward(s, torch.stack([dev(x, dtype) for x in sig]))
+        assert got == want == [], (s, got, want)
+        _gamma_close(gg, wg)
+    _state_close(lib, ref)
+    lib.close(); ver.close()
+
+
 def test_replace_with_ema_entry_point():
     import torch
     import paper_2603_03592_amd as sv

@@ -349,3 +349,47 @@ def test_stream_majority_deviation_is_a_distribution_shift():
     # ... and the listing's clean set then lets nobody in that was flagged: only the two un-flagged enter the EMA? No:
     # the set was emptied, so every worker of the stage is clean again.
     np.testing.assert_allclose(st.m["h"][0], 0.9 * m0 + 0.1 * np.mean([np.float64(x) for x in h], axis=0), rtol=1e-12, atol=1e-15)
+
+
+# ------------------------------------------------------------------ the remaining attack generators
+def test_attack_generators_have_the_stated_statistics():
+    x = si.stream_signal("h", 0, 0, 0, 512, 64, "f32")
+    assert si.invisible_noise_zmax(0.99) == pytest.approx(2.3263478740, rel=1e-9)      # 99 % quantile of N(0, 1)
+    assert si.invisible_noise_zmax(0.5) == pytest.approx(0.0, abs=1e-12)
+    y = si.attack_invisible_noise(x, 0.99, 1, "f32").astype(np.float64)
+    np.testing.assert_allclose(y.mean(axis=0), x.mean(axis=0), atol=0.4)
+    assert np.mean(y.std(axis=0) / x.std(axis=0)) == pytest.approx(2.3263, rel=0.03)
+    s = si.attack_sign_elements(x, 0.25, 2, "f32")
+    assert np.all(np.abs(s) == np.abs(x)) and np.mean(s != x) == pytest.approx(0.25, abs=0.02)
+    assert np.all(si.attack_constant(x, -1.0, "bf16") == -1.0)
+    r = si.attack_random_value(x, 3, "f32")
+    assert abs(r.mean()) < 0.02 and r.std() == pytest.approx(1.0, rel=0.02)
+    m, tgt = x.astype(np.float64), np.ones_like(x, dtype=np.float64)
+    d = si.attack_drift(m, tgt, alpha=0.5, sigma=0.0, seed=0, dtype="f32")
+    np.testing.assert_allclose(d, m + 0.5 * (tgt - m) / np.linalg.norm(m), rtol=1e-6, atol=1e-7)
+    assert si.drift_delay(0.9) == 22 and si.drift_delay(0.8) == 11
+
+
+def test_stream_detects_value_replacing_attacks_and_not_the_delay_attack():
+    """Against the EMA reference: constant, random-value and invisible-noise submissions move every statistic far out
+    of the fences; a delayed (stale but honest) signal of this slowly drifting stream is statistically a clean one."""
+    st = _stream()
+    _warm(st)
+    t = WARM
+    for w, kind in enumerate(("constant", "random", "invisible")):      # one worker each: a gross deviation bans at once
+        st.begin_iteration(False)
+        h = _signals("h", 0, t)
+        if kind == "constant":
+            h[w] = si.attack_constant(h[w], -1.0, "f32")
+        elif kind == "random":
+            h[w] = si.attack_random_value(h[w], t, "f32")
+        else:
+            h[w] = si.attack_invisible_noise(h[w], 0.99, t, "f32")
+        here, _ = st.forward(0, h)
+        assert here == [w], kind
+        t += 1
+    st.begin_iteration(False)
+    h = _signals("h", 0, t)
+    h[3] = si.stream_signal("h", 0, 3, t - 20, T, D, "f32")          # delay attack, k = 20
+    here, _ = st.forward(0, h)
+    assert here == []
