@@ -15,6 +15,15 @@ rounded in between):
   with RMSNorm + RoPE + SwiGLU (Llama style) or LayerNorm + exact-erf GELU (GPT style).
   This is what a duplicate-work verifier recomputes (the recompute-and-compare
   baseline of the paper's "Proposed Method" paragraph and FAQ Q9).
+  The paper's "Alternative Architectures" paragraph also trains two mixture-of-experts
+  stacks and Table model_config gives their expert count, shared-expert count and top-k,
+  but no formula for the layer.  With desc.n_experts > 0 the MLP of a block is the generic
+  routed layer those architectures share:
+      l = n Wr^T,   s = sigmoid(l) or softmax(l),   S_t = the top_k experts of token t by s
+      (ties to the lower index),   g = s on S_t, divided by its sum over S_t if router_norm,
+      MLP(n) = sum_{e in S_t} g_e SwiGLU_e(n) + sum_{shared experts} SwiGLU_sh(n),
+  every expert a SwiGLU feed-forward of width ffn_hidden; no capacity limit, no token is
+  dropped, no load-balancing term (none of them changes the forward value).
 * the test statistic Gamma = Omega(signal, reference) and the flag rule Gamma > tau
   (Eq. test_statistic), with the distance family of the paragraph "Choice of Distance
   Measure": mean absolute difference, normalised (z-scored) Euclidean distance and sign
@@ -29,7 +38,11 @@ the attack variants.  Parts with no pin are listed as "parity unpinned": none he
 
 Array conventions: activations [B, S, D] (or [T, D] per sequence), weights [out, in].
 `desc` is any object with attributes n_blocks, d_model, n_heads, n_kv_heads, ffn_hidden,
-mlp ("swiglu"|"gelu"), norm ("rms"|"ln"), rope, causal, norm_eps, rope_theta.
+mlp ("swiglu"|"gelu"), norm ("rms"|"ln"), rope, causal, norm_eps, rope_theta and, optionally,
+n_experts (0 = dense MLP), top_k, n_shared, router_score ("sigmoid"|"softmax"), router_norm.
+Mixture-of-experts weights: w_router [E, D], w_gate / w_up [E, F, D], w_down [E, D, F] and, with
+shared experts, ws_gate / ws_up [n_shared * F, D], ws_down [D, n_shared * F] (the shared experts
+side by side: expert i owns rows / columns i*F .. (i+1)*F).
 """
 from __future__ import annotations
 
@@ -151,9 +164,130 @@ def gelu_grad(z):
     return 0.5 * (1.0 + _erf(z / math.sqrt(2.0))) + z * np.exp(-0.5 * z * z) / math.sqrt(2.0 * math.pi)
 
 
+
+# ----------------------------------------------------------------------------- mixture of experts
+def _round_to_bf16_f64(a):
+    """Nearest bf16 (ties to even) of float64 values, returned as float64."""
+    f = np.ascontiguousarray(a, dtype=np.float32)
+    u = f.view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).reshape(f.shape).astype(F64)
+
+
+def router_scores_from_logits(logits, kind):
+    if kind == "sigmoid":
+        return 1.0 / (1.0 + np.exp(-logits))
+    if kind == "softmax":
+        e = np.exp(logits - np.max(logits, axis=-1, keepdims=True))
+        return e / np.sum(e, axis=-1, keepdims=True)
+    raise ValueError(kind)
+
+
+def router_scores(n, w_router, kind):
+    """Router scores [S, E] of the tokens n [S, D]: sigmoid or softmax of the logits n Wr^T."""
+    return router_scores_from_logits(_f64(n) @ _f64(w_router).T, kind)
+
+
+def moe_route(n, w_router, desc, decision="f64"):
+    """Which experts each token uses and with what weight.
+
+    Returns (sel [S, k] expert indices in decreasing score order, gates [S, k], scores [S, E],
+    margin [S]).  The DECISION (which experts) is an integer outcome of floating-point scores;
+    with decision="bf16" it is taken the way a bf16 stage takes it -- from the tokens rounded to
+    bf16 and float32 logits -- so that a comparison with such a stage does not hinge on ties the
+    two precisions break differently.  The gate VALUES always come from the float64 scores.
+    margin is the gap between the k-th and (k+1)-th decision score (inf when k = E): how far the
+    token is from a different routing."""
+    n = _f64(n)
+    E, k = desc.n_experts, desc.top_k
+    scores = router_scores(n, w_router, desc.router_score)
+    if decision == "bf16":
+        lg = (_round_to_bf16_f64(n).astype(np.float32) @ np.asarray(w_router, dtype=np.float32).T).astype(F64)
+        dec = router_scores_from_logits(lg, desc.router_score)
+    elif decision == "f64":
+        dec = scores
+    else:
+        raise ValueError(decision)
+    order = np.argsort(-dec, axis=-1, kind="stable")            # decreasing score, ties to the lower index
+    sel = order[:, :k]
+    srt = np.take_along_axis(dec, order, axis=-1)
+    margin = srt[:, k - 1] - srt[:, k] if k < E else np.full(n.shape[0], np.inf)
+    gates = np.take_along_axis(scores, sel, axis=-1)
+    if desc.router_norm:
+        gates = gates / np.sum(gates, axis=-1, keepdims=True)
+    return sel, gates, scores, margin
+
+
+def _shared_slices(w, desc):
+    F = desc.ffn_hidden
+    return [slice(i * F, (i + 1) * F) for i in range(getattr(desc, "n_shared", 0))]
+
+
+def moe_forward(n, w, desc, decision="f64", keep=False):
+    """The routed MLP of the tokens n [S, D] -> [S, D] (without the residual)."""
+    n = _f64(n)
+    sel, gates, scores, margin = moe_route(n, w["w_router"], desc, decision)
+    Wg, Wu, Wd = _f64(w["w_gate"]), _f64(w["w_up"]), _f64(w["w_down"])
+    out = np.zeros_like(n)
+    for e in range(desc.n_experts):
+        tok, slot = np.nonzero(sel == e)                       # the tokens routed to expert e
+        if tok.size == 0:
+            continue
+        x = n[tok]
+        y = (silu(x @ Wg[e].T) * (x @ Wu[e].T)) @ Wd[e].T
+        np.add.at(out, tok, gates[tok, slot][:, None] * y)
+    for sl in _shared_slices(w, desc):
+        out += (silu(n @ _f64(w["ws_gate"])[sl].T) * (n @ _f64(w["ws_up"])[sl].T)) @ _f64(w["ws_down"])[:, sl].T
+    if keep:
+        return out, dict(n=n, sel=sel, gates=gates, scores=scores, margin=margin)
+    return out
+
+
+def moe_backward(dy, st, w, desc):
+    """Gradient of moe_forward with respect to its input tokens, for the routing kept in `st`
+    (the routing is piecewise constant; its decision carries no gradient, its gate values do)."""
+    dy = _f64(dy)
+    n, sel, gates, scores = st["n"], st["sel"], st["gates"], st["scores"]
+    Wg, Wu, Wd, Wr = _f64(w["w_gate"]), _f64(w["w_up"]), _f64(w["w_down"]), _f64(w["w_router"])
+    dn = np.zeros_like(n)
+    dgates = np.zeros_like(gates)
+    for e in range(desc.n_experts):
+        tok, slot = np.nonzero(sel == e)
+        if tok.size == 0:
+            continue
+        x, d = n[tok], dy[tok]
+        gt, up = x @ Wg[e].T, x @ Wu[e].T
+        y = (silu(gt) * up) @ Wd[e].T
+        dgates[tok, slot] = np.sum(d * y, axis=-1)
+        da = (gates[tok, slot][:, None] * d) @ Wd[e]
+        np.add.at(dn, tok, (da * up * silu_grad(gt)) @ Wg[e] + (da * silu(gt)) @ Wu[e])
+    # gate values -> selected scores
+    ssel = np.take_along_axis(scores, sel, axis=-1)
+    if desc.router_norm:
+        z = np.sum(ssel, axis=-1, keepdims=True)
+        dssel = (dgates - np.sum(dgates * gates, axis=-1, keepdims=True)) / z
+    else:
+        dssel = dgates
+    dscores = np.zeros_like(scores)
+    np.put_along_axis(dscores, sel, dssel, axis=-1)
+    # scores -> logits
+    if desc.router_score == "sigmoid":
+        dlogits = dscores * scores * (1.0 - scores)
+    else:
+        dlogits = scores * (dscores - np.sum(dscores * scores, axis=-1, keepdims=True))
+    dn += dlogits @ Wr
+    for sl in _shared_slices(w, desc):
+        Wsg, Wsu, Wsd = _f64(w["ws_gate"])[sl], _f64(w["ws_up"])[sl], _f64(w["ws_down"])[:, sl]
+        gt, up = n @ Wsg.T, n @ Wsu.T
+        da = dy @ Wsd
+        dn += (da * up * silu_grad(gt)) @ Wsg + (da * silu(gt)) @ Wsu
+    return dn
+
+
 # ----------------------------------------------------------------------------- one block, one sequence
-def block_forward(x, w, desc, keep=False):
-    """x [S, D] of ONE sequence -> y [S, D]; with keep=True also the tensors backward needs."""
+def block_forward(x, w, desc, keep=False, decision="f64"):
+    """x [S, D] of ONE sequence -> y [S, D]; with keep=True also the tensors backward needs.
+    `decision` is moe_route's (mixture-of-experts blocks only)."""
     x = _f64(x)
     S, D = x.shape
     H, Hkv = desc.n_heads, desc.n_kv_heads
@@ -167,6 +301,11 @@ def block_forward(x, w, desc, keep=False):
     o = attention_forward(q, k, v, desc.causal).reshape(S, H * hd)
     x1 = x + o @ _f64(w["wo"]).T
     n2 = norm_forward(x1, _f64(w["norm2_g"]), _f64(w["norm2_b"]), desc.norm, desc.norm_eps)
+    if getattr(desc, "n_experts", 0) > 0:
+        mo = moe_forward(n2, w, desc, decision, keep)
+        if keep:
+            return x1 + mo[0], dict(x=x, q=q, k=k, v=v, x1=x1, moe=mo[1])
+        return x1 + mo
     u = n2 @ _f64(w["w_up"]).T
     if desc.mlp == "swiglu":
         gt = n2 @ _f64(w["w_gate"]).T
@@ -186,12 +325,15 @@ def block_backward(dy, st, w, desc):
     S, D = dy.shape
     H, Hkv = desc.n_heads, desc.n_kv_heads
     hd = D // H
-    da = dy @ _f64(w["w_down"])
-    if desc.mlp == "swiglu":
+    if "moe" in st:
+        dn2 = moe_backward(dy, st["moe"], w, desc)
+    elif desc.mlp == "swiglu":
+        da = dy @ _f64(w["w_down"])
         dgate = da * st["up"] * silu_grad(st["gate"])
         dup = da * silu(st["gate"])
         dn2 = dgate @ _f64(w["w_gate"]) + dup @ _f64(w["w_up"])
     else:
+        da = dy @ _f64(w["w_down"])
         dn2 = (da * gelu_grad(st["up"])) @ _f64(w["w_up"])
     dx1 = dy + norm_backward(dn2, st["x1"], _f64(w["norm2_g"]), desc.norm, desc.norm_eps)
     do = (dx1 @ _f64(w["wo"])).reshape(S, H, hd)
@@ -205,19 +347,34 @@ def block_backward(dy, st, w, desc):
 
 
 # ----------------------------------------------------------------------------- the stage
-def stage_forward(h, weights, desc):
+def stage_forward(h, weights, desc, decision="f64"):
     """h^(s-1) [B, S, D] -> h^(s) [B, S, D]: n_blocks blocks applied to each sequence."""
     h = _f64(h)
     out = np.empty_like(h)
     for b in range(h.shape[0]):
         x = h[b]
         for w in weights:
-            x = block_forward(x, w, desc)
+            x = block_forward(x, w, desc, decision=decision)
         out[b] = x
     return out
 
 
-def stage_backward(h, g_next, weights, desc):
+def stage_routing_margin(h, weights, desc, decision="f64"):
+    """Mixture-of-experts stages: per token [B, S], the smallest routing margin over the blocks of
+    the stage (see moe_route).  Tokens with a small margin are those whose expert set a
+    recomputation in another precision may legitimately choose differently."""
+    h = _f64(h)
+    out = np.empty(h.shape[:2], dtype=F64)
+    for b in range(h.shape[0]):
+        x, m = h[b], np.full(h.shape[1], np.inf)
+        for w in weights:
+            x, st = block_forward(x, w, desc, keep=True, decision=decision)
+            m = np.minimum(m, st["moe"]["margin"])
+        out[b] = m
+    return out
+
+
+def stage_backward(h, g_next, weights, desc, decision="f64"):
     """(h^(s-1), dL/dh^(s)) -> (h^(s), g^(s) = dL/dh^(s-1)); the forward is recomputed and
     kept per sequence, then the blocks are walked in reverse."""
     h, g_next = _f64(h), _f64(g_next)
@@ -225,7 +382,7 @@ def stage_backward(h, g_next, weights, desc):
     for b in range(h.shape[0]):
         x, kept = h[b], []
         for w in weights:
-            x, st = block_forward(x, w, desc, keep=True)
+            x, st = block_forward(x, w, desc, keep=True, decision=decision)
             kept.append(st)
         h_out[b] = x
         d = g_next[b]

@@ -39,6 +39,13 @@ class StageDesc:
     norm_eps: float = 1e-5
     rope_theta: float = 500000.0
     dtype: str = "bf16"          # "bf16" | "f32"
+    # mixture-of-experts MLP (n_experts = 0: dense).  Every expert, routed or shared, is a SwiGLU
+    # feed-forward of width ffn_hidden; each token uses its top_k routed experts and all shared ones.
+    n_experts: int = 0
+    top_k: int = 0
+    n_shared: int = 0
+    router_score: str = "sigmoid"   # "sigmoid" | "softmax"
+    router_norm: bool = False       # divide the selected scores by their sum
 
     @property
     def head_dim(self) -> int:
@@ -62,6 +69,14 @@ SMALL = Workload("small", StageDesc(2, 1024, 16, 16, 2816), batch=8, seq=512, ta
 MEDIUM = Workload("medium", StageDesc(4, 2048, 16, 16, 5632), batch=8, seq=1024, tau=2e-2,
                   n_claims=10, backward=True)
 LARGE = Workload("large", StageDesc(4, 4096, 32, 8, 14336), batch=4, seq=2048, tau=2e-2, n_claims=32)
+# The two mixture-of-experts shapes of the paper's Table model_config (hidden size, heads, KV heads, experts, shared
+# experts, top-k as printed; expert width from its "multiplier 1.3, multiple of 1024" rule; the table gives the second
+# model no KV-head count, so it gets one KV head per query head).  One block per stage and sequence length 1024 as in
+# the paper's setup; the micro-batch is ours.
+MOE_TOP1 = Workload("moe_top1", StageDesc(1, 512, 32, 8, 2048, n_experts=8, top_k=1, n_shared=1), batch=8, seq=1024,
+                    tau=2e-2, n_claims=8, backward=True)
+MOE_TOP6 = Workload("moe_top6", StageDesc(1, 1024, 16, 16, 4096, n_experts=8, top_k=6, n_shared=2, router_norm=True),
+                    batch=8, seq=1024, tau=2e-2, n_claims=8, backward=True)
 
 
 def sweep_point(seq: int, batch: int) -> Workload:
@@ -69,7 +84,7 @@ def sweep_point(seq: int, batch: int) -> Workload:
                     tau=2e-2, n_claims=128, backward=True)
 
 
-WORKLOADS: Dict[str, Workload] = {w.name: w for w in (TINY, SMALL, MEDIUM, LARGE)}
+WORKLOADS: Dict[str, Workload] = {w.name: w for w in (TINY, SMALL, MEDIUM, LARGE, MOE_TOP1, MOE_TOP6)}
 
 
 # --------------------------------------------------------------------------- bf16 helpers
@@ -117,7 +132,13 @@ def make_weights(desc: StageDesc, seed: int = 0) -> List[Dict[str, Optional[np.n
             return to_stage_dtype(mean + std * g.standard_normal(n, dtype=np.float32), desc.dtype)
 
         w = dict(wq=mat(Hq, D), wk=mat(Hkv, D), wv=mat(Hkv, D), wo=mat(D, Hq))
-        if desc.mlp == "swiglu":
+        if desc.n_experts > 0:
+            E, Fs = desc.n_experts, desc.n_shared * F
+            w.update(w_gate=mat(E * F, D).reshape(E, F, D), w_up=mat(E * F, D).reshape(E, F, D),
+                     w_down=mat(E * D, F).reshape(E, D, F), w_router=mat(E, D))
+            if Fs:
+                w.update(ws_gate=mat(Fs, D), ws_up=mat(Fs, D), ws_down=mat(D, Fs))
+        elif desc.mlp == "swiglu":
             w.update(w_gate=mat(F, D), w_up=mat(F, D), w_down=mat(D, F))
         else:
             w.update(w_gate=None, w_up=mat(F, D), w_down=mat(D, F))
