@@ -48,6 +48,7 @@ typedef enum { SV_F32 = 0, SV_BF16 = 1 } sv_dtype;
 typedef enum { SV_MLP_GELU = 0, SV_MLP_SWIGLU = 1 } sv_mlp;
 typedef enum { SV_NORM_LN = 0, SV_NORM_RMS = 1 } sv_norm;
 typedef enum { SV_REDUCE_GLOBAL = 0, SV_REDUCE_MAX_TOKEN = 1 } sv_reduce;
+typedef enum { SV_ROUTER_SIGMOID = 0, SV_ROUTER_SOFTMAX = 1 } sv_router;
 
 /* metric indices into score[] / tau[] and their mask bits (1 << index) */
 enum { SV_IDX_RELL2 = 0, SV_IDX_L1 = 1, SV_IDX_ZL2 = 2, SV_IDX_SFR = 3 };
@@ -77,6 +78,18 @@ typedef struct {
   float   norm_eps;
   float   rope_theta;
   int32_t dtype;      /* sv_dtype: storage type of activations, weights, claims */
+  /* Mixture-of-experts MLP (the second model family of the paragraph "Alternative Architectures"; expert,
+   * shared-expert and top-k counts as in Table model_config).  n_experts = 0: the dense MLP above.  Otherwise
+   *   l = n Wr^T,  s = sigmoid(l) or softmax(l) over the experts,  S_t = the top_k experts of token t by s
+   *   (decided on l, which orders the experts as s does; ties to the lower index),  g = s on S_t, divided by its sum over S_t if router_norm,
+   *   MLP(n) = sum_{e in S_t} g_e SwiGLU_e(n) + SwiGLU_shared(n),
+   * every routed expert a SwiGLU MLP of width ffn_hidden, the shared experts side by side as one SwiGLU MLP of
+   * width ffn_shared.  No capacity limit: no token is dropped.  Needs mlp = SV_MLP_SWIGLU.                  */
+  int32_t n_experts;    /* 0 | 1..16 */
+  int32_t top_k;        /* 1..min(8, n_experts) */
+  int32_t ffn_shared;   /* 0 = no shared expert */
+  int32_t router_score; /* sv_router */
+  int32_t router_norm;  /* 0 | 1 */
 } sv_stage_desc;
 
 /* Weights of one block, device pointers in the stage dtype, matrices [out, in] row-major. */
@@ -92,6 +105,12 @@ typedef struct {
   const void *norm1_b; /* [d_model] LayerNorm only; NULL for RMSNorm              */
   const void *norm2_g;
   const void *norm2_b;
+  /* mixture-of-experts blocks only (else NULL): then w_gate / w_up are [n_experts, ffn, d_model] and w_down is
+   * [n_experts, d_model, ffn], expert after expert                                                        */
+  const void *w_router; /* [n_experts, d_model]  */
+  const void *ws_gate;  /* [ffn_shared, d_model] shared experts; NULL when ffn_shared = 0 */
+  const void *ws_up;    /* [ffn_shared, d_model] */
+  const void *ws_down;  /* [d_model, ffn_shared] */
 } sv_block_weights;
 
 /* Verdict for one submission (device memory, 32 bytes). */
@@ -135,6 +154,14 @@ sv_status sv_verify_backward(sv_ctx *ctx, const sv_block_weights *w, const void 
                              int32_t B, int32_t S, const void *claimed_g, uint32_t metric_mask,
                              const float *tau, int32_t reduce, void *g_hat_out, void *h_hat_out,
                              float *token_scores_out, sv_result *result_dev, void *stream);
+
+/* Mixture-of-experts stages: copy out the routing that the most recent sv_verify_forward / sv_verify_backward call
+ * on this context used in block `block`: experts_out [B*S, top_k] int32 in decreasing score order, gates_out
+ * [B*S, top_k] float (device pointers, either may be NULL), enqueued on `stream`.  A forward-only context keeps the
+ * routing of its last block only (SV_EINVAL for others); a backward context keeps every block's.  A recomputation
+ * in another precision may choose differently for a token whose k-th and (k+1)-th scores nearly tie; this call
+ * lets a caller tell such tokens from a deviation.                                                         */
+sv_status sv_last_routing(sv_ctx *ctx, int32_t block, int32_t *experts_out, float *gates_out, void *stream);
 
 /* Optional, backward contexts on the bf16 matrix-core path: transpose the stage's weight matrices to
  * [in, out] once (on `stream`) and keep the copies in the context, so that later sv_verify_backward calls
@@ -291,7 +318,8 @@ sv_status sv_sentinel_read_ema(sv_sentinel *s, int32_t stage, int32_t kind, floa
 enum {
   SV_OP_NORM = 0, SV_OP_GEMM_QKV, SV_OP_ROPE, SV_OP_ATTN, SV_OP_GEMM_O, SV_OP_GEMM_GATEUP, SV_OP_GEMM_DOWN,
   SV_OP_SCORE, SV_OP_BWD_GEMM_DA, SV_OP_BWD_GEMM_DN2, SV_OP_BWD_NORM, SV_OP_BWD_GEMM_DO, SV_OP_BWD_ATTN,
-  SV_OP_BWD_ROPE, SV_OP_BWD_GEMM_DN1, SV_OP_BWD_WTRANSPOSE, SV_OP_SW_PROJECT, SV_OP_SW_SORT, SV_OP_COUNT
+  SV_OP_BWD_ROPE, SV_OP_BWD_GEMM_DN1, SV_OP_BWD_WTRANSPOSE, SV_OP_SW_PROJECT, SV_OP_SW_SORT, SV_OP_MOE_ROUTE,
+  SV_OP_MOE_PERMUTE, SV_OP_BWD_MOE, SV_OP_COUNT
 };
 typedef struct {
   double  ms[SV_OP_COUNT];

@@ -20,7 +20,7 @@ rounded in between):
   but no formula for the layer.  With desc.n_experts > 0 the MLP of a block is the generic
   routed layer those architectures share:
       l = n Wr^T,   s = sigmoid(l) or softmax(l),   S_t = the top_k experts of token t by s
-      (ties to the lower index),   g = s on S_t, divided by its sum over S_t if router_norm,
+      (decided on l, which orders the experts as s does; ties to the lower index),   g = s on S_t, divided by its sum over S_t if router_norm,
       MLP(n) = sum_{e in S_t} g_e SwiGLU_e(n) + sum_{shared experts} SwiGLU_sh(n),
   every expert a SwiGLU feed-forward of width ffn_hidden; no capacity limit, no token is
   dropped, no load-balancing term (none of them changes the forward value).
@@ -192,23 +192,23 @@ def moe_route(n, w_router, desc, decision="f64"):
     """Which experts each token uses and with what weight.
 
     Returns (sel [S, k] expert indices in decreasing score order, gates [S, k], scores [S, E],
-    margin [S]).  The DECISION (which experts) is an integer outcome of floating-point scores;
-    with decision="bf16" it is taken the way a bf16 stage takes it -- from the tokens rounded to
-    bf16 and float32 logits -- so that a comparison with such a stage does not hinge on ties the
-    two precisions break differently.  The gate VALUES always come from the float64 scores.
-    margin is the gap between the k-th and (k+1)-th decision score (inf when k = E): how far the
-    token is from a different routing."""
+    margin [S]).  Both score functions increase with the logit, so "the k highest scores" is decided
+    on the logits (which do not saturate).  The DECISION (which experts) is an integer outcome of
+    floating-point numbers; with decision="bf16" it is taken the way a bf16 stage takes it -- from the
+    tokens rounded to bf16 and float32 logits -- so that a comparison with such a stage does not hinge
+    on ties the two precisions break differently.  The gate VALUES always come from the float64 scores.
+    margin is the gap between the k-th and (k+1)-th decision logit (inf when k = E): how far the token
+    is from a different routing."""
     n = _f64(n)
     E, k = desc.n_experts, desc.top_k
     scores = router_scores(n, w_router, desc.router_score)
     if decision == "bf16":
-        lg = (_round_to_bf16_f64(n).astype(np.float32) @ np.asarray(w_router, dtype=np.float32).T).astype(F64)
-        dec = router_scores_from_logits(lg, desc.router_score)
+        dec = (_round_to_bf16_f64(n).astype(np.float32) @ np.asarray(w_router, dtype=np.float32).T).astype(F64)
     elif decision == "f64":
-        dec = scores
+        dec = n @ _f64(w_router).T
     else:
         raise ValueError(decision)
-    order = np.argsort(-dec, axis=-1, kind="stable")            # decreasing score, ties to the lower index
+    order = np.argsort(-dec, axis=-1, kind="stable")            # decreasing logit, ties to the lower index
     sel = order[:, :k]
     srt = np.take_along_axis(dec, order, axis=-1)
     margin = srt[:, k - 1] - srt[:, k] if k < E else np.full(n.shape[0], np.inf)

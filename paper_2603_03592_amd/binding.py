@@ -30,10 +30,13 @@ class SVError(RuntimeError):
 class StageDescC(C.Structure):
     _fields_ = [("n_blocks", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32), ("n_kv_heads", C.c_int32),
                 ("ffn_hidden", C.c_int32), ("mlp", C.c_int32), ("norm", C.c_int32), ("rope", C.c_int32),
-                ("causal", C.c_int32), ("norm_eps", C.c_float), ("rope_theta", C.c_float), ("dtype", C.c_int32)]
+                ("causal", C.c_int32), ("norm_eps", C.c_float), ("rope_theta", C.c_float), ("dtype", C.c_int32),
+                ("n_experts", C.c_int32), ("top_k", C.c_int32), ("ffn_shared", C.c_int32), ("router_score", C.c_int32),
+                ("router_norm", C.c_int32)]
 
 
-_WNAMES = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "norm1_g", "norm1_b", "norm2_g", "norm2_b")
+_WNAMES = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "norm1_g", "norm1_b", "norm2_g", "norm2_b",
+           "w_router", "ws_gate", "ws_up", "ws_down")
 
 
 class BlockWeightsC(C.Structure):
@@ -42,7 +45,7 @@ class BlockWeightsC(C.Structure):
 
 OP_NAMES = ("norm", "gemm_qkv", "rope", "attn", "gemm_o", "gemm_gateup", "gemm_down", "score", "bwd_gemm_da",
             "bwd_gemm_dn2", "bwd_norm", "bwd_gemm_do", "bwd_attn", "bwd_rope", "bwd_gemm_dn1", "bwd_wtranspose",
-            "sw_project", "sw_sort")
+            "sw_project", "sw_sort", "moe_route", "moe_permute", "bwd_moe")
 
 
 class PolicyCfgC(C.Structure):
@@ -83,6 +86,8 @@ def _load():
     L.sv_destroy.argtypes = [vp]
     L.sv_last_error.restype = C.c_char_p
     L.sv_last_error.argtypes = [vp]
+    L.sv_last_routing.restype = C.c_int
+    L.sv_last_routing.argtypes = [vp, i32, vp, vp, vp]
     L.sv_verify_forward.restype = C.c_int
     L.sv_verify_forward.argtypes = [vp, C.POINTER(BlockWeightsC), vp, i32, i32, vp, u32, C.POINTER(f32), i32, vp, vp, vp, vp]
     L.sv_verify_backward.restype = C.c_int
@@ -236,7 +241,11 @@ def _desc_c(desc) -> StageDescC:
     return StageDescC(int(desc.n_blocks), int(desc.d_model), int(desc.n_heads), int(desc.n_kv_heads), int(desc.ffn_hidden),
                       SV_MLP_SWIGLU if desc.mlp == "swiglu" else SV_MLP_GELU,
                       SV_NORM_RMS if desc.norm == "rms" else SV_NORM_LN, int(bool(desc.rope)), int(bool(desc.causal)),
-                      float(desc.norm_eps), float(desc.rope_theta), SV_BF16 if desc.dtype == "bf16" else SV_F32)
+                      float(desc.norm_eps), float(desc.rope_theta), SV_BF16 if desc.dtype == "bf16" else SV_F32,
+                      int(getattr(desc, "n_experts", 0)), int(getattr(desc, "top_k", 0)),
+                      int(getattr(desc, "n_shared", 0)) * int(desc.ffn_hidden) if getattr(desc, "n_experts", 0) else 0,
+                      1 if getattr(desc, "router_score", "sigmoid") == "softmax" and getattr(desc, "n_experts", 0) else 0,
+                      int(bool(getattr(desc, "router_norm", False))) if getattr(desc, "n_experts", 0) else 0)
 
 
 def sv_check_desc(desc, flags: int = 0):
@@ -327,6 +336,15 @@ class Verifier:
                     assert t.is_cuda and t.is_contiguous() and t.dtype == self.tdtype, n
                 setattr(arr[i], n, _ptr(t))
         return arr
+
+    def last_routing(self, block: int, n_tokens: int):
+        """(experts [T, top_k] int32, gates [T, top_k] float32) that the latest verify call used in `block`."""
+        torch = self.torch
+        k = int(self.desc.top_k)
+        ex = torch.empty((n_tokens, k), dtype=torch.int32, device="cuda")
+        gt = torch.empty((n_tokens, k), dtype=torch.float32, device="cuda")
+        self._check(lib.sv_last_routing(self._ctx, block, _ptr(ex), _ptr(gt), self._stream()))
+        return ex, gt
 
     def prepare_weights(self, weights_c):
         """Make the backward pass's transposed weight copies once; valid until the weights change (then call again)."""

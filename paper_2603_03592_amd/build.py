@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libstageverify.so")
-SOURCES = ["api.hip", "score.hip", "sw.hip", "kernels_plain.hip", "gemm_mfma.hip", "attn_mfma.hip", "sentinel.hip", "policy.cpp"]
+SOURCES = ["api.hip", "score.hip", "sw.hip", "moe.hip", "kernels_plain.hip", "gemm_mfma.hip", "attn_mfma.hip", "sentinel.hip", "policy.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -18,8 +18,11 @@ namespace {
 thread_local char g_create_error[256] = "";
 
 struct BlockStash {   // what one block's backward reads (backward mode only)
-  void *x1, *qkv, *o, *gate, *up;
+  void *x1, *qkv, *o, *gate, *up;   // gate / up: pre-activations of the dense MLP, or of the shared experts
   float* lse;
+  // mixture of experts: the routing and, in expert-sorted rows, the routed experts' pre-activations and outputs
+  sv::MoeRoute route;
+  void *gate_p, *up_p, *yp;
 };
 
 struct Arena {
@@ -47,16 +50,22 @@ struct sv_ctx {
   int device;
   int es;            // element size of the stage dtype
   int hd, Dq, Dkv, Dqkv;
+  bool moe;          // mixture-of-experts MLP
+  int Fd;            // width of the dense-path MLP: ffn_hidden, or ffn_shared (possibly 0) for a mixture of experts
   void* ws;
   size_t ws_bytes;
   // forward
   void *xbuf[2], *n, *qkv, *o, *x1, *act;
   float* lse;
+  // mixture of experts (expert-sorted rows, moe_padded_rows(max_tokens) of them)
+  MoeRoute route;      // forward-only contexts: one routing, reused by every block
+  void *xp, *actp, *yp, *dup_p;
+  int last_T = 0;      // tokens of the most recent verify call (for sv_last_routing)
   // backward
   std::vector<void*> xs;           // outputs of blocks 0..L-2 (inputs of blocks 1..L-1)
   std::vector<BlockStash> stash;
   void *dres[2], *dn, *dx1, *dgate, *dup, *dout, *dqkv;
-  struct WT { void *wq, *wk, *wv, *wo, *wg, *wu, *wd; };
+  struct WT { void *wq, *wk, *wv, *wo, *wg, *wu, *wd, *wsg, *wsu, *wsd; };
   std::vector<WT> wT;                   // per block: the weights transposed to [in, out] (bf16 MFMA path, backward mode)
   std::vector<sv_block_weights> prepared;   // the weights sv_prepare_weights transposed (empty: none)
   float* delta;
@@ -103,6 +112,17 @@ sv_status check_desc_impl(const sv_stage_desc* d, uint32_t flags, char* msg, int
   if (hd != 8 && hd != 16 && hd != 32 && hd != 64 && hd != 128)
     return fail(SV_EUNSUPPORTED, "head_dim must be one of 8, 16, 32, 64, 128");
   if (d->d_model % 8 || d->ffn_hidden % 8) return fail(SV_EUNSUPPORTED, "d_model and ffn_hidden must be multiples of 8");
+  if (d->n_experts < 0 || d->ffn_shared < 0) return fail(SV_EINVAL, "n_experts and ffn_shared must be >= 0");
+  if (d->n_experts == 0 && (d->top_k || d->ffn_shared || d->router_score || d->router_norm))
+    return fail(SV_EINVAL, "top_k, ffn_shared, router_score and router_norm must be 0 for a dense MLP");
+  if (d->n_experts > 0) {
+    if (d->mlp != SV_MLP_SWIGLU) return fail(SV_EUNSUPPORTED, "a mixture of experts needs the SwiGLU MLP");
+    if (d->top_k < 1 || d->top_k > d->n_experts) return fail(SV_EINVAL, "top_k must be in 1..n_experts");
+    if (d->router_score != SV_ROUTER_SIGMOID && d->router_score != SV_ROUTER_SOFTMAX) return fail(SV_EINVAL, "unknown router_score");
+    if (d->router_norm != 0 && d->router_norm != 1) return fail(SV_EINVAL, "router_norm must be 0 or 1");
+    if (d->n_experts > kMoeMaxExperts || d->top_k > kMoeMaxTopK) return fail(SV_EUNSUPPORTED, "at most 16 experts and top_k <= 8");
+    if (d->ffn_shared % 8) return fail(SV_EUNSUPPORTED, "ffn_shared must be a multiple of 8");
+  }
   if (msg && msg_len > 0) msg[0] = 0;
   return SV_OK;
 }
@@ -112,6 +132,9 @@ size_t carve(sv_ctx* c, char* base) {
   const sv_stage_desc& d = c->d;
   const size_t T = (size_t)c->max_tokens, es = (size_t)c->es;
   const size_t D = d.d_model, F = d.ffn_hidden, L = d.n_blocks;
+  const size_t Fd = (size_t)c->Fd;                     // dense-path MLP width (the shared experts of a mixture)
+  const size_t E = d.n_experts, K = d.top_k;
+  const size_t Mp = c->moe ? (size_t)moe_padded_rows(c->max_tokens, d.top_k, d.n_experts) : 0;
   const size_t lse_n = (size_t)d.n_heads * T;
   const bool bwd = c->flags & SV_FLAG_BACKWARD;
   Arena a; a.base = base;
@@ -126,7 +149,21 @@ size_t carve(sv_ctx* c, char* base) {
   c->xbuf[0] = a.take(T * D * es);
   c->xbuf[1] = a.take(T * D * es);
   c->n = a.take(T * D * es);
-  c->act = a.take(T * F * es);
+  c->act = a.take(T * Fd * es);
+  auto take_route = [&](MoeRoute& r) {
+    const size_t n_chunks = (T * K + kMoeChunk - 1) / kMoeChunk;
+    r.sel = (int32_t*)a.take(T * K * 4); r.gate = (float*)a.take(T * K * 4); r.score = (float*)a.take(T * E * 4);
+    r.pos = (int32_t*)a.take(T * K * 4); r.row_token = (int32_t*)a.take(Mp * 4); r.row_gate = (float*)a.take(Mp * 4);
+    r.tile_expert = (int32_t*)a.take(Mp / 256 * 4); r.meta = (int32_t*)a.take((1 + 2 * E) * 4);
+    r.chunk_counts = (int32_t*)a.take(n_chunks * E * 4); r.chunk_base = (int32_t*)a.take(n_chunks * E * 4);
+  };
+  c->xp = c->actp = c->yp = c->dup_p = nullptr;
+  if (c->moe) {
+    c->xp = a.take(Mp * D * es);
+    c->actp = a.take(Mp * F * es);
+    if (!bwd) { take_route(c->route); c->yp = a.take(Mp * D * es); }
+    else c->dup_p = a.take(Mp * F * es);
+  }
   c->xs.clear(); c->stash.clear();
   if (!bwd) {
     c->qkv = a.take(T * c->Dqkv * es);
@@ -140,9 +177,14 @@ size_t carve(sv_ctx* c, char* base) {
       s.x1 = a.take(T * D * es);
       s.qkv = a.take(T * c->Dqkv * es);
       s.o = a.take(T * c->Dq * es);
-      s.gate = d.mlp == SV_MLP_SWIGLU ? a.take(T * F * es) : nullptr;
-      s.up = a.take(T * F * es);
+      s.gate = d.mlp == SV_MLP_SWIGLU ? a.take(T * Fd * es) : nullptr;
+      s.up = a.take(T * Fd * es);
       s.lse = (float*)a.take(lse_n * sizeof(float));
+      s.gate_p = s.up_p = s.yp = nullptr;
+      if (c->moe) {
+        take_route(s.route);
+        s.gate_p = a.take(Mp * F * es); s.up_p = a.take(Mp * F * es); s.yp = a.take(Mp * D * es);
+      }
       c->stash.push_back(s);
     }
     c->qkv = c->stash[0].qkv; c->o = c->stash[0].o; c->x1 = c->stash[0].x1; c->lse = c->stash[0].lse;
@@ -150,8 +192,8 @@ size_t carve(sv_ctx* c, char* base) {
     c->dres[1] = a.take(T * D * es);
     c->dn = a.take(T * D * es);
     c->dx1 = a.take(T * D * es);
-    c->dgate = a.take(T * F * es);
-    c->dup = d.mlp == SV_MLP_SWIGLU ? a.take(T * F * es) : nullptr;
+    c->dgate = a.take(T * Fd * es);
+    c->dup = d.mlp == SV_MLP_SWIGLU ? a.take(T * Fd * es) : nullptr;
     c->dout = a.take(T * c->Dq * es);
     c->dqkv = a.take(T * c->Dqkv * es);
     c->delta = (float*)a.take(lse_n * sizeof(float));
@@ -160,8 +202,11 @@ size_t carve(sv_ctx* c, char* base) {
       for (size_t l = 0; l < L; ++l) {
         sv_ctx::WT t;
         t.wq = a.take(D * c->Dq * es); t.wk = a.take(D * c->Dkv * es); t.wv = a.take(D * c->Dkv * es);
-        t.wo = a.take(D * c->Dq * es); t.wu = a.take(D * F * es); t.wd = a.take(D * F * es);
-        t.wg = d.mlp == SV_MLP_SWIGLU ? a.take(D * F * es) : nullptr;
+        const size_t ne = c->moe ? E : 1;              // routed experts one after the other
+        t.wo = a.take(D * c->Dq * es); t.wu = a.take(ne * D * F * es); t.wd = a.take(ne * D * F * es);
+        t.wg = d.mlp == SV_MLP_SWIGLU ? a.take(ne * D * F * es) : nullptr;
+        t.wsg = t.wsu = t.wsd = nullptr;
+        if (c->moe && Fd) { t.wsg = a.take(D * Fd * es); t.wsu = a.take(D * Fd * es); t.wsd = a.take(D * Fd * es); }
         c->wT.push_back(t);
       }
     }
@@ -176,6 +221,8 @@ void init_ctx_fields(sv_ctx* c, const sv_stage_desc* desc, int64_t max_tokens, i
   c->Dq = desc->n_heads * c->hd;
   c->Dkv = desc->n_kv_heads * c->hd;
   c->Dqkv = c->Dq + 2 * c->Dkv;
+  c->moe = desc->n_experts > 0;
+  c->Fd = c->moe ? desc->ffn_shared : desc->ffn_hidden;
   c->ws = nullptr; c->ws_bytes = 0; c->err[0] = 0;
 }
 
@@ -281,6 +328,40 @@ sv_status block_forward(sv_ctx* c, const sv_block_weights& w, const void* x, voi
     SV_OP(c, SV_OP_GEMM_O, 2.0 * Td * D * c->Dq, st, gemm(c, g, st));
   }
   SV_OP(c, SV_OP_NORM, 0, st, plain_norm_fwd(x1, w.norm2_g, w.norm2_b, c->n, T, D, d.norm, d.norm_eps, dt, st));
+  if (c->moe) {
+    // shared experts on the dense path (their output lands in y on top of the residual), then the routed experts:
+    // route, gather the token rows expert by expert, two grouped products, weighted sum back into token order
+    const int E = d.n_experts, K = d.top_k, Fs = d.ffn_shared;
+    const MoeRoute& r = keep ? keep->route : c->route;
+    void* yp = keep ? keep->yp : c->yp;
+    const int64_t Mp = moe_padded_rows(T, K, E);
+    const double rows = Td * K;
+    const void* base = x1;
+    if (Fs > 0) {
+      GemmArgs g = nt(T, Fs, D, c->n, D, w.ws_gate, c->act, Fs, EPI_SWIGLU);
+      g.B2 = w.ws_up; g.ldb2 = D;
+      if (keep) { g.C2 = keep->gate; g.C3 = keep->up; }
+      SV_OP(c, SV_OP_GEMM_GATEUP, 4.0 * Td * Fs * D, st, gemm(c, g, st));
+      GemmArgs h = nt(T, D, Fs, c->act, Fs, w.ws_down, y, D, EPI_RESID);
+      h.R = x1; h.ldr = D;
+      SV_OP(c, SV_OP_GEMM_DOWN, 2.0 * Td * D * Fs, st, gemm(c, h, st));
+      base = y;
+    }
+    SV_OP(c, SV_OP_MOE_ROUTE, 2.0 * Td * E * D, st, launch_moe_route(c->n, w.w_router, T, D, E, K, d.router_score, d.router_norm, dt, r, st));
+    SV_OP(c, SV_OP_MOE_PERMUTE, 0, st, launch_moe_gather(c->n, D, Mp, E, r, 0, c->xp, dt, st));
+    {
+      GemmArgs g = nt((int)Mp, F, D, c->xp, D, w.w_gate, c->actp, F, EPI_SWIGLU);
+      g.B2 = w.w_up; g.ldb2 = D;
+      g.tile_group = r.tile_expert; g.group_stride = (int64_t)F * D; g.m_dev = r.meta;
+      if (keep) { g.C2 = keep->gate_p; g.C3 = keep->up_p; }
+      SV_OP(c, SV_OP_GEMM_GATEUP, 4.0 * rows * F * D, st, gemm(c, g, st));
+      GemmArgs h = nt((int)Mp, D, F, c->actp, F, w.w_down, yp, D, EPI_STORE);
+      h.tile_group = r.tile_expert; h.group_stride = (int64_t)D * F; h.m_dev = r.meta;
+      SV_OP(c, SV_OP_GEMM_DOWN, 2.0 * rows * D * F, st, gemm(c, h, st));
+    }
+    SV_OP(c, SV_OP_MOE_PERMUTE, 0, st, launch_moe_combine(base, yp, T, D, K, r, y, dt, st));
+    return SV_OK;
+  }
   if (d.mlp == SV_MLP_SWIGLU) {
     GemmArgs g = nt(T, F, D, c->n, D, w.w_gate, c->act, F, EPI_SWIGLU);
     g.B2 = w.w_up; g.ldb2 = D;
@@ -311,10 +392,18 @@ void add_seg(GemmArgs& g, const void* A, int64_t lda, const void* W, int64_t ldw
 // One block backward: dy = dL/dy -> dx = dL/dx, reading the block input x and its stash.
 sv_status transpose_block_weights(sv_ctx* c, const sv_block_weights& w, const sv_ctx::WT& t, hipStream_t st) {
   const sv_stage_desc& d = c->d;
-  const int D = d.d_model, F = d.ffn_hidden, dt = d.dtype;
-  SV_OP(c, SV_OP_BWD_WTRANSPOSE, 0, st, plain_transpose(w.w_down, t.wd, D, F, dt, st));
-  SV_OP(c, SV_OP_BWD_WTRANSPOSE, 0, st, plain_transpose(w.w_up, t.wu, F, D, dt, st));
-  if (d.mlp == SV_MLP_SWIGLU) SV_OP(c, SV_OP_BWD_WTRANSPOSE, 0, st, plain_transpose(w.w_gate, t.wg, F, D, dt, st));
+  const int D = d.d_model, F = d.ffn_hidden, dt = d.dtype, es = c->es;
+  for (int e = 0; e < (c->moe ? d.n_experts : 1); ++e) {
+    const int64_t off = (int64_t)e * D * F;
+    SV_OP(c, SV_OP_BWD_WTRANSPOSE, 0, st, plain_transpose(at(w.w_down, off, es), at(t.wd, off, es), D, F, dt, st));
+    SV_OP(c, SV_OP_BWD_WTRANSPOSE, 0, st, plain_transpose(at(w.w_up, off, es), at(t.wu, off, es), F, D, dt, st));
+    if (d.mlp == SV_MLP_SWIGLU) SV_OP(c, SV_OP_BWD_WTRANSPOSE, 0, st, plain_transpose(at(w.w_gate, off, es), at(t.wg, off, es), F, D, dt, st));
+  }
+  if (c->moe && c->Fd) {
+    SV_OP(c, SV_OP_BWD_WTRANSPOSE, 0, st, plain_transpose(w.ws_down, t.wsd, D, c->Fd, dt, st));
+    SV_OP(c, SV_OP_BWD_WTRANSPOSE, 0, st, plain_transpose(w.ws_up, t.wsu, c->Fd, D, dt, st));
+    SV_OP(c, SV_OP_BWD_WTRANSPOSE, 0, st, plain_transpose(w.ws_gate, t.wsg, c->Fd, D, dt, st));
+  }
   SV_OP(c, SV_OP_BWD_WTRANSPOSE, 0, st, plain_transpose(w.wo, t.wo, D, c->Dq, dt, st));
   SV_OP(c, SV_OP_BWD_WTRANSPOSE, 0, st, plain_transpose(w.wq, t.wq, c->Dq, D, dt, st));
   SV_OP(c, SV_OP_BWD_WTRANSPOSE, 0, st, plain_transpose(w.wk, t.wk, c->Dkv, D, dt, st));
@@ -350,7 +439,42 @@ sv_status block_backward(sv_ctx* c, int l, const sv_block_weights& w, const void
     g.b_is_kn = wt ? 0 : 1;
     return g;
   };
-  if (d.mlp == SV_MLP_SWIGLU) {
+  if (c->moe) {
+    const int E = d.n_experts, K = d.top_k, Fs = d.ffn_shared;
+    const MoeRoute& r = k.route;
+    const int64_t Mp = moe_padded_rows(T, K, E);
+    const double rows = Td * K;
+    auto grouped = [&](GemmArgs& g) {
+      g.M = (int)Mp; g.tile_group = r.tile_expert; g.group_stride = (int64_t)D * F; g.m_dev = r.meta;
+    };
+    if (Fs > 0) {                                                // shared experts: the dense backward into dn
+      GemmArgs g = args(Fs, c->dgate, Fs, EPI_SWIGLU_BWD);
+      seg(g, dy, D, w.ws_down, t.wsd, D, Fs);
+      g.C2 = c->dup; g.R = k.gate; g.R2 = k.up; g.ldr = Fs;
+      SV_OP(c, SV_OP_BWD_GEMM_DA, 2.0 * Td * Fs * D, st, gemm(c, g, st));
+      GemmArgs h = args(D, c->dn, D, EPI_STORE);
+      seg(h, c->dgate, Fs, w.ws_gate, t.wsg, Fs, D);
+      seg(h, c->dup, Fs, w.ws_up, t.wsu, Fs, D);
+      SV_OP(c, SV_OP_BWD_GEMM_DN2, 4.0 * Td * Fs * D, st, gemm(c, h, st));
+    }
+    // routed experts: rows gate * dy in expert order, back through down / SwiGLU / gate and up, then per token the sum
+    // over its experts plus the gradient that reaches n through the gate values (router)
+    SV_OP(c, SV_OP_BWD_MOE, 0, st, launch_moe_gather(dy, D, Mp, E, r, 1, c->xp, dt, st));
+    {
+      GemmArgs g = args(F, c->actp, F, EPI_SWIGLU_BWD);
+      seg(g, c->xp, D, w.w_down, t.wd, D, F);
+      g.C2 = c->dup_p; g.R = k.gate_p; g.R2 = k.up_p; g.ldr = F;
+      grouped(g);
+      SV_OP(c, SV_OP_BWD_GEMM_DA, 2.0 * rows * F * D, st, gemm(c, g, st));
+      GemmArgs h = args(D, c->xp, D, EPI_STORE);                 // overwrites the gathered rows, which are dead by now
+      seg(h, c->actp, F, w.w_gate, t.wg, F, D);
+      seg(h, c->dup_p, F, w.w_up, t.wu, F, D);
+      grouped(h);
+      SV_OP(c, SV_OP_BWD_GEMM_DN2, 4.0 * rows * F * D, st, gemm(c, h, st));
+    }
+    SV_OP(c, SV_OP_BWD_MOE, 2.0 * Td * (K + E) * D, st,
+          launch_moe_combine_bwd(dy, k.yp, c->xp, w.w_router, T, D, E, K, d.router_score, d.router_norm, r, Fs > 0, c->dn, dt, st));
+  } else if (d.mlp == SV_MLP_SWIGLU) {
     GemmArgs g = args(F, c->dgate, F, EPI_SWIGLU_BWD);           // da = dy Wd, then through silu(g)*u
     seg(g, dy, D, w.w_down, t.wd, D, F);
     g.C2 = c->dup; g.R = k.gate; g.R2 = k.up; g.ldr = F;
@@ -404,7 +528,8 @@ sv_status check_call(sv_ctx* c, const sv_block_weights* w, const void* h_in, int
     const bool mats = b.wq && b.wk && b.wv && b.wo && b.w_up && b.w_down && b.norm1_g && b.norm2_g;
     const bool gate = c->d.mlp == SV_MLP_SWIGLU ? b.w_gate != nullptr : true;
     const bool bias = c->d.norm == SV_NORM_LN ? (b.norm1_b && b.norm2_b) : true;
-    if (!mats || !gate || !bias) { set_err(c, "block %d: a required weight pointer is NULL", l); return SV_EINVAL; }
+    const bool moe_ok = !c->moe || (b.w_router && (c->Fd == 0 || (b.ws_gate && b.ws_up && b.ws_down)));
+    if (!mats || !gate || !bias || !moe_ok) { set_err(c, "block %d: a required weight pointer is NULL", l); return SV_EINVAL; }
   }
   return SV_OK;
 }
@@ -431,6 +556,10 @@ sv_status sv_create(const sv_stage_desc* desc, int64_t max_tokens, int32_t max_s
   sv_status s = check_desc_impl(desc, flags, msg, sizeof(msg));
   if (s != SV_OK) { set_err(nullptr, "%s", msg); return s; }
   if (max_tokens < 1 || max_seq < 1 || max_tokens > 0x7fffffffLL) { set_err(nullptr, "max_tokens / max_seq out of range"); return SV_EINVAL; }
+  if (desc->n_experts > 0 && moe_padded_rows(max_tokens, desc->top_k, desc->n_experts) > 0x7fffffffLL) {
+    set_err(nullptr, "max_tokens * top_k is out of range");
+    return SV_EINVAL;
+  }
   sv_ctx* c = new sv_ctx();
   init_ctx_fields(c, desc, max_tokens, max_seq, flags);
   c->ws_bytes = carve(c, nullptr);
@@ -505,6 +634,7 @@ sv_status sv_verify_forward(sv_ctx* c, const sv_block_weights* w, const void* h_
   hipStream_t st = (hipStream_t)stream;
   const int L = c->d.n_blocks;
   const bool bwd = c->flags & SV_FLAG_BACKWARD;
+  c->last_T = B * S;
   const void* x = h_in;
   void* y = nullptr;
   for (int l = 0; l < L; ++l) {
@@ -529,6 +659,7 @@ sv_status sv_verify_backward(sv_ctx* c, const sv_block_weights* w, const void* h
   if (!g_out) { set_err(c, "g_out must be non-NULL"); return SV_EINVAL; }
   hipStream_t st = (hipStream_t)stream;
   const int L = c->d.n_blocks;
+  c->last_T = B * S;
   const void* x = h_in;
   for (int l = 0; l < L; ++l) {
     void* y = (l == L - 1) ? (h_hat_out ? h_hat_out : c->xbuf[0]) : c->xs[l];
@@ -551,6 +682,22 @@ sv_status sv_verify_backward(sv_ctx* c, const sv_block_weights* w, const void* h
   return SV_OK;
 }
 
+sv_status sv_last_routing(sv_ctx* c, int32_t block, int32_t* experts_out, float* gates_out, void* stream) {
+  if (!c) return SV_EINVAL;
+  if (!c->moe) { set_err(c, "the stage has no mixture-of-experts MLP"); return SV_EINVAL; }
+  if (c->last_T < 1) { set_err(c, "no verify call has run on this context"); return SV_EINVAL; }
+  const bool bwd = c->flags & SV_FLAG_BACKWARD;
+  if (block < 0 || block >= c->d.n_blocks || (!bwd && block != c->d.n_blocks - 1)) {
+    set_err(c, "block %d: a forward-only context keeps the routing of its last block only", block);
+    return SV_EINVAL;
+  }
+  const MoeRoute& r = bwd ? c->stash[block].route : c->route;
+  const size_t n = (size_t)c->last_T * c->d.top_k;
+  if (experts_out) SV_HIP(c, hipMemcpyAsync(experts_out, r.sel, n * sizeof(int32_t), hipMemcpyDeviceToDevice, (hipStream_t)stream));
+  if (gates_out) SV_HIP(c, hipMemcpyAsync(gates_out, r.gate, n * sizeof(float), hipMemcpyDeviceToDevice, (hipStream_t)stream));
+  return SV_OK;
+}
+
 sv_status sv_prepare_weights(sv_ctx* c, const sv_block_weights* w, void* stream) {
   if (!c) return SV_EINVAL;
   c->prepared.clear();
@@ -558,7 +705,8 @@ sv_status sv_prepare_weights(sv_ctx* c, const sv_block_weights* w, void* stream)
   if (c->wT.empty()) return SV_OK;                     // this context transposes nothing (forward only, fp32 or plain kernels)
   for (int l = 0; l < c->d.n_blocks; ++l) {
     const sv_block_weights& b = w[l];
-    if (!(b.wq && b.wk && b.wv && b.wo && b.w_up && b.w_down) || (c->d.mlp == SV_MLP_SWIGLU && !b.w_gate)) {
+    if (!(b.wq && b.wk && b.wv && b.wo && b.w_up && b.w_down) || (c->d.mlp == SV_MLP_SWIGLU && !b.w_gate) ||
+        (c->moe && (!b.w_router || (c->Fd > 0 && !(b.ws_gate && b.ws_up && b.ws_down))))) {
       set_err(c, "block %d: a required weight pointer is NULL", l);
       return SV_EINVAL;
     }

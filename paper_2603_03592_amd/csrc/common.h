@@ -147,6 +147,11 @@ struct GemmArgs {
   int nbcol; const void* Bcol[3]; int ncol[3];
   // EPI_ROPE: (cos, sin) table [rope_S][rope_hd / 2][2] of floats
   const float* rope_cs; int rope_S, rope_hd, rope_cols;
+  // optional grouped form (mixture of experts): rows [256 i, 256 i + 256) of the product use the weight matrices of
+  // group tile_group[i], found group_stride elements apart behind every seg[].B and B2; with m_dev the row count is
+  // read from device memory (*m_dev <= M, a multiple of 256) and M only bounds the launch
+  const int32_t* tile_group; int64_t group_stride;
+  const int32_t* m_dev;
 };
 
 // kernels_plain.hip: any shape, fp32 math, E = float | bf16 by `dtype`
@@ -165,6 +170,32 @@ hipError_t plain_attn_bwd(const void* qkv, int64_t ld, const void* o, const void
                           void* dqkv, int B, int S, int H, int Hkv, int hd, int causal, int dtype, hipStream_t st);
 
 hipError_t plain_transpose(const void* src, void* dst, int R, int C, int dtype, hipStream_t st);
+
+// moe.hip: routing of a mixture-of-experts MLP.  All buffers are device memory of one block.
+constexpr int kMoeMaxExperts = 16, kMoeMaxTopK = 8, kMoeChunk = 1024;
+struct MoeRoute {
+  int32_t* sel;          // [T, K] chosen experts, decreasing score
+  float* gate;           // [T, K] their weights
+  float* score;          // [T, E] router scores
+  int32_t* pos;          // [T, K] row of (token, choice) in the expert-sorted buffers
+  int32_t* row_token;    // [Mp]   token of a row (rows of one expert are contiguous, padded to a multiple of 256)
+  float* row_gate;       // [Mp]   gate of a row
+  int32_t* tile_expert;  // [Mp / 256] expert of each 256-row block
+  int32_t* meta;         // [0] rows in use (multiple of 256), [1 + e] first row of expert e, [1 + E + e] its row count
+  int32_t* chunk_counts; // [n_chunks, E] scratch of the counting sort, n_chunks = ceil(T K / kMoeChunk)
+  int32_t* chunk_base;   // [n_chunks, E]
+};
+int64_t moe_padded_rows(int64_t T, int K, int E);   // upper bound Mp of the rows in use
+hipError_t launch_moe_route(const void* n, const void* w_router, int64_t T, int D, int E, int K, int score_kind, int norm, int dtype,
+                            const MoeRoute& r, hipStream_t st);
+// dst[p, :] = scale_p * src[row_token[p], :] for the rows in use (zeros for padding rows); scale_p = row_gate[p] if scaled
+hipError_t launch_moe_gather(const void* src, int D, int64_t Mp, int E, const MoeRoute& r, int scaled, void* dst, int dtype, hipStream_t st);
+// y[t, :] = base[t, :] + sum_j gate[t, j] * yp[pos[t, j], :]      (y may alias base)
+hipError_t launch_moe_combine(const void* base, const void* yp, int64_t T, int D, int K, const MoeRoute& r, void* y, int dtype, hipStream_t st);
+// dn[t, :] = (accumulate ? dn[t, :] : 0) + sum_j dxp[pos[t, j], :] + sum_e dlogit[t, e] Wr[e, :], where dlogit follows
+// from dgate[t, j] = <dy[t, :], yp[pos[t, j], :]> through the gate normalisation and the score function
+hipError_t launch_moe_combine_bwd(const void* dy, const void* yp, const void* dxp, const void* w_router, int64_t T, int D, int E, int K,
+                                  int score_kind, int norm, const MoeRoute& r, int accumulate, void* dn, int dtype, hipStream_t st);
 
 // gemm_mfma.hip: bf16 only; returns hipErrorInvalidValue if the shape is outside its limits
 bool mfma_gemm_supported(const GemmArgs& a);

@@ -127,8 +127,8 @@ __device__ __forceinline__ void epilogue_apply4(const GemmArgs& a, int m, int n,
 // accumulator blocks is the `up` product of a dual launch).  Per feature block: its four loads first,
 // then compute and store.
 template <int EPI, int NIO, int NI, int MI>
-__device__ __forceinline__ void epilogue_rows(const GemmArgs& a, const f32x16 (&acc)[NI][MI], int mi, int m, int nbase) {
-  if (m >= a.M) return;
+__device__ __forceinline__ void epilogue_rows(const GemmArgs& a, int M, const f32x16 (&acc)[NI][MI], int mi, int m, int nbase) {
+  if (m >= M) return;
 #pragma unroll
   for (int ni = 0; ni < NIO; ++ni) {
     EpiIn in[4];
@@ -153,6 +153,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(GemmA
   using C = Cfg<BM, BN, WAVES_M, WAVES_N, KN, DUAL>;
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
+  // grouped form: the row count lives in device memory and the launch covers its bound
+  const int M = a.m_dev ? *a.m_dev : a.M;
+  if (a.m_dev) tiles_m = (M + BM - 1) / BM;
   // ---- tile assignment (XCD-contiguous, grouped raster)
   const int nblk = tiles_m * tiles_n;
   const int per_xcd = (nblk + 7) >> 3;
@@ -164,6 +167,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(GemmA
   const int tile_m = first_m + (pid % in_group) % gsz;
   const int tile_n = (pid % in_group) / gsz;
   const int m0 = tile_m * BM, n0 = tile_n * C::NOUT;
+  const int64_t goff = a.tile_group ? (int64_t)a.tile_group[m0 >> 8] * a.group_stride : 0;   // this row block's weight matrices
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave % WAVES_M, wn = wave / WAVES_M;
@@ -177,7 +181,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(GemmA
 #pragma unroll
     for (int i = 0; i < C::XCH; ++i) {
       const int e = tid + i * C::NT, r = e >> 3, c = e & 7;
-      const int m = min(m0 + r, a.M - 1);
+      const int m = min(m0 + r, M - 1);
       xreg[i] = *reinterpret_cast<const bf16x8*>(A + (int64_t)m * lda + kin + c * 8);
     }
     if (!KN) {
@@ -186,14 +190,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(GemmA
         const int e = tid + i * C::NT, r = e >> 3, c = e & 7;
         const bf16* B;
         int n;
-        if (DUAL && r >= BN / 2) { B = (const bf16*)a.B2; n = n0 + r - BN / 2; }
-        else { B = (const bf16*)a.seg[seg].B; n = n0 + r; }
+        if (DUAL && r >= BN / 2) { B = (const bf16*)a.B2 + goff; n = n0 + r - BN / 2; }
+        else { B = (const bf16*)a.seg[seg].B + goff; n = n0 + r; }
         const int64_t ld = (DUAL && r >= BN / 2) ? a.ldb2 : ldb;
         wreg[i] = *reinterpret_cast<const bf16x8*>(B + (int64_t)n * ld + kin + c * 8);
       }
     } else {
       // thread owns 8x8 blocks: 8 consecutive k rows x 8 consecutive n columns
-      const bf16* B = (const bf16*)a.seg[seg].B;
+      const bf16* B = (const bf16*)a.seg[seg].B + goff;
 #pragma unroll
       for (int b = 0; b < C::WCH / 8; ++b) {
         const int blk = tid + b * C::NT, ng = blk % (BN / 8), kg = blk / (BN / 8);
@@ -294,7 +298,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(GemmA
   constexpr int NIO = DUAL ? C::NI / 2 : C::NI;
 #pragma unroll
   for (int mi = 0; mi < C::MI; ++mi)
-    epilogue_rows<EPI, NIO, C::NI, C::MI>(a, acc, mi, m0 + wm * C::WTM + mi * 32 + l31, n0 + wn * (DUAL ? C::WTN / 2 : C::WTN) + lhi * 4);
+    epilogue_rows<EPI, NIO, C::NI, C::MI>(a, M, acc, mi, m0 + wm * C::WTM + mi * 32 + l31, n0 + wn * (DUAL ? C::WTN / 2 : C::WTN) + lhi * 4);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -316,6 +320,9 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
   constexpr int NOUT = DUAL ? 128 : 256;
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
+  // grouped form: the row count lives in device memory and the launch covers its bound
+  const int M = a.m_dev ? *a.m_dev : a.M;
+  if (a.m_dev) tiles_m = (M + BM - 1) / BM;
   // Persistent workgroups: workgroup b works on the virtual block ids b, b + gridDim.x, ...; a virtual id
   // maps to a tile so that ids congruent mod 8 (one XCD) walk a contiguous run of tiles in groups of
   // kGroupM row tiles.  gridDim.x is a multiple of 8, so a workgroup stays on its XCD's run.
@@ -345,18 +352,19 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
   auto set_segment = [&]() {
     const GemmSeg& sg = a.seg[dseg];
     gA = (const char*)((const bf16*)sg.A + (int64_t)d_m0 * sg.lda);
+    const int64_t goff = a.tile_group ? (int64_t)a.tile_group[d_m0 >> 8] * a.group_stride : 0;
     if (!DUAL && a.nbcol > 0) {
       int start = 0, j = 0;
       while (j + 1 < a.nbcol && d_n0 >= start + a.ncol[j]) { start += a.ncol[j]; ++j; }
       gB = (const char*)((const bf16*)a.Bcol[j] + (int64_t)(d_n0 - start) * sg.ldb);
     } else {
-      gB = (const char*)((const bf16*)sg.B + (int64_t)d_n0 * sg.ldb);
+      gB = (const char*)((const bf16*)sg.B + goff + (int64_t)d_n0 * sg.ldb);
     }
-    gB2 = DUAL ? (const char*)((const bf16*)a.B2 + (int64_t)d_n0 * a.ldb2) : gB;
+    gB2 = DUAL ? (const char*)((const bf16*)a.B2 + goff + (int64_t)d_n0 * a.ldb2) : gB;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int r = (wave + 4 * i) * 8 + (lane >> 3), c = (lane & 7) ^ swz(r);
-      const int ra = min(r, a.M - 1 - d_m0);                  // ragged row tail: re-read the last row
+      const int ra = min(r, M - 1 - d_m0);                  // ragged row tail: re-read the last row
       voffA[i] = (unsigned)((int64_t)ra * sg.lda + c * 8) * 2u;
       if (DUAL) voffB[i] = (unsigned)((int64_t)(r & 127) * (i >= 4 ? a.ldb2 : sg.ldb) + c * 8) * 2u;
       else voffB[i] = (unsigned)((int64_t)r * sg.ldb + c * 8) * 2u;
@@ -490,7 +498,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
         for (int k = 0; k < 2; ++k) {
           const int row = (it + k) * 4 + er;
           int m = m0 + wm * 128 + mi * 32 + row;
-          if (CHECK) m = min(m, a.M - 1);                // rows past the end read the last row (never stored)
+          if (CHECK) m = min(m, M - 1);                // rows past the end read the last row (never stored)
           if (EPI == EPI_ROPE) {
             // position of the row in its sequence without a division per row: the wave's first row is reduced once
             // per tile, the rows of the tile follow it consecutively
@@ -536,7 +544,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
           float lo[4], hi[4];
 #pragma unroll
           for (int i = 0; i < 4; ++i) { lo[i] = a_lo[i]; hi[i] = a_hi[i]; }
-          if (CHECK && m >= a.M) continue;
+          if (CHECK && m >= M) continue;
           if (DUAL) epilogue_apply4<EPI>(a, m, n0 + wn * 64 + ec4 * 4, lo, hi, in_lo[trip & 1][k]);   // patch columns 0..63: gate, 64..127: up
           else {
             epilogue_apply4<EPI>(a, m, n0 + wn * 128 + ec4 * 4, lo, hi, in_lo[trip & 1][k]);
@@ -545,7 +553,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
         }
       }
     };
-    if (m0 + 256 <= a.M) run_epilogue(std::false_type{});
+    if (m0 + 256 <= M) run_epilogue(std::false_type{});
     else run_epilogue(std::true_type{});
   }
   // A finished stream keeps re-reading its last slice into the free stage (the loop has no branch for it): every
@@ -621,6 +629,8 @@ bool mfma_gemm_supported(const GemmArgs& a) {
     if (a.nbcol > 0 && tot != a.N) return false;
     if (a.epi == EPI_ROPE && (!a.rope_cs || a.rope_hd % 4 || a.rope_cols % 4 || a.rope_S < 1)) return false;
   }
+  if (a.tile_group && (a.nbcol > 0 || a.group_stride % 8)) return false;
+  if (a.m_dev && a.M % 256) return false;
   if (a.b_is_kn && (a.epi == EPI_RESID || a.epi == EPI_GELU || a.epi == EPI_SWIGLU)) return false;
   if ((a.epi == EPI_RESID || a.epi == EPI_SWIGLU_BWD || a.epi == EPI_GELU_BWD) && !a.R) return false;
   if (a.epi == EPI_SWIGLU_BWD && (!a.R2 || !a.C2)) return false;

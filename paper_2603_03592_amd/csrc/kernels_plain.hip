@@ -16,12 +16,15 @@ __global__ __launch_bounds__(256) void gemm_plain_kernel(GemmArgs a) {
   __shared__ float Bs2[DUAL ? 16 : 1][68];
   const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
   const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+  const int M = a.m_dev ? *a.m_dev : a.M;   // grouped form: row count from device memory (the launch covers its bound)
+  if (m0 >= M) return;
+  const int64_t goff = a.tile_group ? (int64_t)a.tile_group[m0 >> 8] * a.group_stride : 0;
   float acc[4][4] = {}, acc2[4][4] = {};
 
   for (int s = 0; s < a.nseg; ++s) {
     const E* A = (const E*)a.seg[s].A;
-    const E* B = (const E*)a.seg[s].B;
-    const E* B2 = (const E*)a.B2;
+    const E* B = (const E*)a.seg[s].B + goff;
+    const E* B2 = a.B2 ? (const E*)a.B2 + goff : nullptr;
     const int64_t lda = a.seg[s].lda, ldb = a.seg[s].ldb;
     const int K = a.seg[s].K;
     for (int k0 = 0; k0 < K; k0 += 16) {
@@ -31,7 +34,7 @@ __global__ __launch_bounds__(256) void gemm_plain_kernel(GemmArgs a) {
         const int e = tid + i * 256;
         {
           const int r = e >> 4, k = e & 15;
-          const bool ok = (m0 + r < a.M) && (k0 + k < K);
+          const bool ok = (m0 + r < M) && (k0 + k < K);
           As[k][r] = ok ? to_f32(A[(int64_t)(m0 + r) * lda + k0 + k]) : 0.0f;
         }
         if (!a.b_is_kn) {
@@ -68,7 +71,7 @@ __global__ __launch_bounds__(256) void gemm_plain_kernel(GemmArgs a) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int r = m0 + ty * 4 + i;
-    if (r >= a.M) continue;
+    if (r >= M) continue;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int c = n0 + tx * 4 + j;

@@ -1,0 +1,198 @@
+"""GPU parity of the mixture-of-experts recompute (the second workload family: the paper's "Alternative
+Architectures" paragraph, shapes from Table model_config) against the CPU oracle.
+
+The routing is an integer decision taken from floating-point scores.  Both sides take it in the stage's precision
+(the oracle with decision="bf16" for bf16 stages); a token whose k-th and (k+1)-th router logits are closer than DELTA may
+still be routed differently by the two, legitimately.  What is compared: for tokens outside that band, the chosen
+experts exactly and the activations / gradients to the usual tolerance (relative L2 <= 1e-4 fp32, <= 2e-2 bf16); for
+tokens inside it, only that every chosen expert is within DELTA of the top-k threshold."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+import stage_inputs as si
+from oracle import stage_oracle as so
+from gpu_util import dev, dev_weights, host, rel_l2
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+DELTA = {"f32": 2e-5, "bf16": 4e-2}      # in logits; router logits here have a standard deviation of about 1.5
+
+
+def moe_weights(desc, seed, router_gain=5.0, mlp_gain=4.0):
+    w = si.make_weights(desc, seed)
+    for b in w:
+        b["w_router"] = si.to_stage_dtype(b["w_router"] * np.float32(router_gain), desc.dtype)
+        for k in ("w_gate", "w_up", "w_down", "ws_gate", "ws_up", "ws_down"):
+            if b.get(k) is not None:
+                b[k] = si.to_stage_dtype(b[k] * np.float32(mlp_gain), desc.dtype)
+    return w
+
+
+def oracle_run(h, g, w, desc):
+    """Oracle outputs plus, per block, the routing record of every sequence."""
+    decision = "bf16" if desc.dtype == "bf16" else "f64"
+    B = h.shape[0]
+    out_h, out_g = np.empty(h.shape), (np.empty(h.shape) if g is not None else None)
+    routes = [[None] * B for _ in w]
+    for b in range(B):
+        x, kept = h[b].astype(np.float64), []
+        for l, blk in enumerate(w):
+            x, st = so.block_forward(x, blk, desc, keep=True, decision=decision)
+            kept.append(st)
+            routes[l][b] = st["moe"]
+        out_h[b] = x
+        if g is not None:
+            d = g[b].astype(np.float64)
+            for blk, st in zip(reversed(w), reversed(kept)):
+                d = so.block_backward(d, st, blk, desc)
+            out_g[b] = d
+    return out_h, out_g, routes
+
+
+def check_routing(ver, routes, desc, B, S, delta, backward, w_router0):
+    """Chosen experts: equal to the oracle's outside the tie band, within the band of the threshold inside it.
+    Returns the mask [B*S] of tokens that are outside the band in every block the context kept."""
+    clear = np.ones(B * S, dtype=bool)
+    blocks = range(desc.n_blocks) if backward else [desc.n_blocks - 1]
+    for l in range(desc.n_blocks):
+        margin = np.concatenate([routes[l][b]["margin"] for b in range(B)])
+        clear &= margin >= delta
+    for l in blocks:
+        ex, gt = ver.last_routing(l, B * S)
+        ex, gt = ex.cpu().numpy(), gt.cpu().numpy().astype(np.float64)
+        sel = np.concatenate([routes[l][b]["sel"] for b in range(B)])
+        gates = np.concatenate([routes[l][b]["gates"] for b in range(B)])
+        scores = np.concatenate([routes[l][b]["scores"] for b in range(B)])
+        assert ex.min() >= 0 and ex.max() < desc.n_experts
+        assert all(len(set(row)) == desc.top_k for row in ex.tolist())              # no expert twice
+        ok = clear                                                                    # upstream flips move later blocks' inputs
+        assert np.array_equal(np.sort(ex[ok], axis=1), np.sort(sel[ok], axis=1))
+        same_order = np.all(ex == sel, axis=1) & ok
+        np.testing.assert_allclose(gt[same_order], gates[same_order], rtol=3e-2 if desc.dtype == "bf16" else 1e-4, atol=1e-6)
+        if l == 0:                                                                    # block 0 sees identical inputs on both sides
+            logit = np.concatenate([routes[l][b]["n"] for b in range(B)]) @ w_router0.astype(np.float64).T
+            kth = np.sort(logit, axis=1)[:, ::-1][:, desc.top_k - 1]
+            chosen = np.take_along_axis(logit, ex.astype(np.int64), axis=1)
+            assert np.all(chosen >= kth[:, None] - 4 * delta)
+    return clear
+
+
+def run_case(desc, B, S, seed, backward, plain=False, grad_std=1.0):
+    import paper_2603_03592_amd as sv
+    w = moe_weights(desc, seed)
+    h = si.make_activations(desc, B, S, seed)
+    g = si.make_output_grad(desc, B, S, seed, std=grad_std) if backward else None
+    ver = sv.Verifier(desc, B * S, S, backward=backward, plain_kernels=plain)
+    wc = ver.pack_weights(wd := dev_weights(w, desc.dtype))
+    if backward:
+        out = ver.verify_backward(wc, dev(h, desc.dtype), dev(g, desc.dtype), want_g_hat=True, want_h_hat=True)
+        got_h, got_g = host(out["h_hat"]), host(out["g_hat"])
+    else:
+        out = ver.verify_forward(wc, dev(h, desc.dtype), want_h_hat=True)
+        got_h, got_g = host(out["h_hat"]), None
+    want_h, want_g, routes = oracle_run(h, g, w, desc)
+    clear = check_routing(ver, routes, desc, B, S, DELTA[desc.dtype], backward, w[0]["w_router"])
+    ver.close()
+    D = desc.d_model
+    tol = TOL[desc.dtype]
+    frac = clear.mean()
+    print(f"tokens outside the tie band: {frac:.4f}")
+    assert frac > 0.7
+    gh, wh = got_h.reshape(-1, D)[clear], want_h.reshape(-1, D)[clear]
+    assert rel_l2(gh, wh) <= tol
+    assert np.max(so.token_rel_l2(gh, wh)) <= (2 * tol if desc.dtype == "f32" else tol)
+    # the mixture is a visible part of the block: dropping it would not pass
+    assert rel_l2(want_h, h) > 0.05
+    if backward:
+        # a token that is routed differently changes, through attention, the gradients of earlier tokens of its sequence
+        # a little; sequences without any such token are compared at full tolerance, the rest at a looser one
+        seq_clear = clear.reshape(B, S).all(axis=1)
+        for b in range(B):
+            r = rel_l2(got_g[b], want_g[b])
+            assert r <= (tol if seq_clear[b] else 10 * tol), (b, r, bool(seq_clear[b]))
+        assert rel_l2(got_g.reshape(-1, D)[clear], want_g.reshape(-1, D)[clear]) <= 3 * tol
+    return got_h, want_h, clear
+
+
+F32 = si.StageDesc(2, 64, 4, 2, 96, dtype="f32", n_experts=4, top_k=2, n_shared=1, router_norm=True)
+F32_VARIANTS = {
+    "sigmoid_norm_shared": F32,
+    "softmax_top1": dataclasses.replace(F32, router_score="softmax", top_k=1, router_norm=False, n_shared=0),
+    "softmax_norm_top3": dataclasses.replace(F32, router_score="softmax", top_k=3, n_experts=5, n_shared=2),
+    "sigmoid_all_experts": dataclasses.replace(F32, top_k=4, router_norm=False),
+    "sixteen_experts_top8": dataclasses.replace(F32, n_experts=16, top_k=8, n_blocks=1),
+}
+
+
+@pytest.mark.parametrize("name", list(F32_VARIANTS))
+@pytest.mark.parametrize("backward", [False, True], ids=["fwd", "bwd"])
+def test_fp32_moe_stage_matches_oracle(name, backward):
+    run_case(F32_VARIANTS[name], 3, 37, seed=11, backward=backward)
+
+
+def test_fp32_moe_several_sort_chunks_and_an_empty_expert():
+    # 700 tokens x top-2 = 1400 (token, expert) pairs: two chunks of the counting sort.  Expert 3's router row is zero
+    # (score exactly 0.5) while the others share a strong common direction on top of their own, so that nearly every
+    # token scores them above 0.5 or far below it together: expert 3 gets few tokens or none, and its segment is ragged
+    import paper_2603_03592_amd as sv
+    desc = dataclasses.replace(F32, n_blocks=1, n_experts=4, top_k=2)
+    w = moe_weights(desc, 5)
+    w[0]["w_router"][3] = 0.0
+    h = si.make_activations(desc, 2, 350, 5)
+    g = si.make_output_grad(desc, 2, 350, 5, std=1.0)
+    ver = sv.Verifier(desc, 700, 350, backward=True)
+    wc = ver.pack_weights(wd := dev_weights(w, "f32"))
+    out = ver.verify_backward(wc, dev(h, "f32"), dev(g, "f32"), want_g_hat=True, want_h_hat=True)
+    want_h, want_g, routes = oracle_run(h, g, w, desc)
+    clear = check_routing(ver, routes, desc, 2, 350, DELTA["f32"], True, w[0]["w_router"])
+    ver.close()
+    assert clear.mean() > 0.99
+    assert rel_l2(host(out["h_hat"]).reshape(-1, 64)[clear], want_h.reshape(-1, 64)[clear]) <= TOL["f32"]
+    assert rel_l2(host(out["g_hat"]).reshape(-1, 64)[clear], want_g.reshape(-1, 64)[clear]) <= TOL["f32"]
+
+
+def test_fp32_moe_expert_that_no_token_chooses():
+    # top-1 of two experts with identical router rows: every token ties and the lower index wins, so expert 1's segment
+    # is empty (zero rows, zero tiles) and expert 0 holds every token
+    import paper_2603_03592_amd as sv
+    desc = dataclasses.replace(F32, n_blocks=1, n_experts=2, top_k=1, n_shared=0, router_norm=False)
+    w = moe_weights(desc, 6)
+    w[0]["w_router"][1] = w[0]["w_router"][0]
+    h = si.make_activations(desc, 2, 45, 6)
+    ver = sv.Verifier(desc, 90, 45)
+    wc = ver.pack_weights(wd := dev_weights(w, "f32"))
+    out = ver.verify_forward(wc, dev(h, "f32"), want_h_hat=True)
+    ex, _ = ver.last_routing(0, 90)
+    ver.close()
+    assert int(ex.max()) == 0
+    assert rel_l2(host(out["h_hat"]), so.stage_forward(h, w, desc)) <= TOL["f32"]
+
+
+BF16_SMALL = si.StageDesc(2, 256, 4, 2, 256, n_experts=8, top_k=2, n_shared=1, router_norm=True)       # 128x128 tiles
+BF16_TOP1 = si.StageDesc(1, 256, 4, 4, 1024, n_experts=4, top_k=1, n_shared=0)                           # 256x256 direct-to-LDS tiles
+
+
+@pytest.mark.parametrize("desc,B,S", [(BF16_SMALL, 3, 100), (BF16_TOP1, 10, 512), (dataclasses.replace(F32, dtype="bf16"), 3, 37)],
+                         ids=["small_tiles", "big_tiles", "plain_shapes"])
+@pytest.mark.parametrize("backward", [False, True], ids=["fwd", "bwd"])
+def test_bf16_moe_stage_matches_oracle(desc, B, S, backward):
+    run_case(desc, B, S, seed=12, backward=backward, grad_std=1e-3)
+
+
+def test_bf16_moe_plain_kernels_agree_with_matrix_core_path():
+    got_a, want, clear_a = run_case(BF16_SMALL, 2, 96, seed=13, backward=False, plain=True)
+    got_b, _, clear_b = run_case(BF16_SMALL, 2, 96, seed=13, backward=False, plain=False)
+    both = clear_a & clear_b
+    assert rel_l2(got_a.reshape(-1, 256)[both], got_b.reshape(-1, 256)[both]) <= TOL["bf16"]
+
+
+def test_moe_descriptor_checks():
+    import paper_2603_03592_amd as sv
+    ok = dataclasses.replace(F32)
+    assert sv.sv_check_desc(ok)[0] == 0
+    assert sv.sv_check_desc(dataclasses.replace(ok, top_k=5))[0] == 1                 # top_k > n_experts
+    assert sv.sv_check_desc(dataclasses.replace(ok, n_experts=17, top_k=2))[0] == 2   # more experts than the kernels hold
+    assert sv.sv_check_desc(dataclasses.replace(ok, mlp="gelu"))[0] == 2

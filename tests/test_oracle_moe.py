@@ -109,7 +109,7 @@ def test_route_tie_rule_margin_and_gate_normalisation():
     assert sel.tolist() == [[0, 1], [2, 3], [0, 1]]
     np.testing.assert_allclose(gates.sum(-1), 1.0, rtol=1e-15)
     sig = lambda v: 1.0 / (1.0 + math.exp(-v))
-    np.testing.assert_allclose(margin, [sig(2.0) - sig(1.0), sig(3.0) - sig(0.0), 0.0], rtol=1e-13, atol=1e-16)
+    np.testing.assert_allclose(margin, [2.0 - 1.0, 3.0 - 0.0, 0.0], rtol=1e-13, atol=1e-16)       # in logits
     np.testing.assert_allclose(gates[0], [0.5, 0.5], rtol=1e-15)
     # without normalisation the gates are the scores themselves; top_k = E has no margin
     desc2 = dataclasses.replace(desc, router_norm=False, top_k=4)
