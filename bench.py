@@ -29,7 +29,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="large", help="tiny|small|medium|large|sweep_s<S>_b<B>")
+    ap.add_argument("--workload", default="large", help="tiny|small|medium|large|moe_top1|moe_top6|sweep_s<S>_b<B>")
     ap.add_argument("--mode", default=None, choices=[None, "fwd", "fwdbwd"], help="default: the workload's own")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--plain", action="store_true", help="run the plain (non-MFMA) kernels")
@@ -73,10 +73,17 @@ def device_weights(desc, torch):
         return (mean + std * torch.randn(D, generator=g, device="cuda", dtype=torch.float32)).to(dt)
 
     blocks = []
+    E, Fs = desc.n_experts, desc.n_shared * F
     for _ in range(desc.n_blocks):
-        w = dict(wq=mat(Hq, D), wk=mat(Hkv, D), wv=mat(Hkv, D), wo=mat(D, Hq), w_up=mat(F, D), w_down=mat(D, F),
-                 w_gate=mat(F, D) if desc.mlp == "swiglu" else None, norm1_g=vec(1.0, 0.1), norm2_g=vec(1.0, 0.1),
+        w = dict(wq=mat(Hq, D), wk=mat(Hkv, D), wv=mat(Hkv, D), wo=mat(D, Hq), norm1_g=vec(1.0, 0.1), norm2_g=vec(1.0, 0.1),
                  norm1_b=vec(0.0, 0.02) if desc.norm == "ln" else None, norm2_b=vec(0.0, 0.02) if desc.norm == "ln" else None)
+        if E > 0:      # routed experts one after the other, shared experts side by side
+            w.update(w_gate=mat(E * F, D).view(E, F, D), w_up=mat(E * F, D).view(E, F, D), w_down=mat(E * D, F).view(E, D, F),
+                     w_router=mat(E, D))
+            if Fs:
+                w.update(ws_gate=mat(Fs, D), ws_up=mat(Fs, D), ws_down=mat(D, Fs))
+        else:
+            w.update(w_up=mat(F, D), w_down=mat(D, F), w_gate=mat(F, D) if desc.mlp == "swiglu" else None)
         blocks.append(w)
     return blocks
 
@@ -371,7 +378,9 @@ def main():
         "config": {"workload": wl.name, "n_blocks": desc.n_blocks, "d_model": desc.d_model, "n_heads": desc.n_heads,
                    "n_kv_heads": desc.n_kv_heads, "ffn_hidden": desc.ffn_hidden, "micro_batch": B, "seq_len": S,
                    "check": "fwd+bwd" if backward else "fwd", "claims_per_step": 1, "kernels": "plain" if a.plain else "mfma",
-                   "weight_prepare_ms_once": prepare_ms},
+                   "weight_prepare_ms_once": prepare_ms,
+                   **({"n_experts": desc.n_experts, "top_k": desc.top_k, "n_shared": desc.n_shared, "router_score": desc.router_score,
+                       "router_norm": desc.router_norm} if desc.n_experts else {})},
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": measured_traffic(wl.name, dom),
                      "launch_ms": d["ms"] / max(d["launches"], 1), "flop_per_launch": d["flop"] / max(d["launches"], 1)},

@@ -80,9 +80,9 @@ def check_routing(ver, routes, desc, B, S, delta, backward, w_router0):
     return clear
 
 
-def run_case(desc, B, S, seed, backward, plain=False, grad_std=1.0):
+def run_case(desc, B, S, seed, backward, plain=False, grad_std=1.0, gains=(5.0, 4.0), delta=None, min_clear=0.7, visible=True):
     import paper_2603_03592_amd as sv
-    w = moe_weights(desc, seed)
+    w = moe_weights(desc, seed, *gains)
     h = si.make_activations(desc, B, S, seed)
     g = si.make_output_grad(desc, B, S, seed, std=grad_std) if backward else None
     ver = sv.Verifier(desc, B * S, S, backward=backward, plain_kernels=plain)
@@ -94,18 +94,19 @@ def run_case(desc, B, S, seed, backward, plain=False, grad_std=1.0):
         out = ver.verify_forward(wc, dev(h, desc.dtype), want_h_hat=True)
         got_h, got_g = host(out["h_hat"]), None
     want_h, want_g, routes = oracle_run(h, g, w, desc)
-    clear = check_routing(ver, routes, desc, B, S, DELTA[desc.dtype], backward, w[0]["w_router"])
+    clear = check_routing(ver, routes, desc, B, S, DELTA[desc.dtype] if delta is None else delta, backward, w[0]["w_router"])
     ver.close()
     D = desc.d_model
     tol = TOL[desc.dtype]
     frac = clear.mean()
-    print(f"tokens outside the tie band: {frac:.4f}")
-    assert frac > 0.7
+    print(f"tokens outside the tie band: {frac:.4f}; relative L2 over ALL tokens: h {rel_l2(got_h, want_h):.3e}"
+          + (f" g {rel_l2(got_g, want_g):.3e}" if backward else ""))
+    assert frac > min_clear
     gh, wh = got_h.reshape(-1, D)[clear], want_h.reshape(-1, D)[clear]
     assert rel_l2(gh, wh) <= tol
     assert np.max(so.token_rel_l2(gh, wh)) <= (2 * tol if desc.dtype == "f32" else tol)
     # the mixture is a visible part of the block: dropping it would not pass
-    assert rel_l2(want_h, h) > 0.05
+    assert not visible or rel_l2(want_h, h) > 0.05
     if backward:
         # a token that is routed differently changes, through attention, the gradients of earlier tokens of its sequence
         # a little; sequences without any such token are compared at full tolerance, the rest at a looser one
@@ -187,6 +188,16 @@ def test_bf16_moe_plain_kernels_agree_with_matrix_core_path():
     got_b, _, clear_b = run_case(BF16_SMALL, 2, 96, seed=13, backward=False, plain=False)
     both = clear_a & clear_b
     assert rel_l2(got_a.reshape(-1, 256)[both], got_b.reshape(-1, 256)[both]) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("name", ["moe_top1", "moe_top6"])
+def test_full_size_moe_workloads(name):
+    """The two mixture-of-experts shapes of Table model_config at the size bench.py times (8 x 1024 tokens, forward and
+    backward, N(0, 0.02^2) weights as generated): every sequence against the oracle.  Router logits have a standard
+    deviation of about 0.45 here, so the tie band is narrower in absolute terms."""
+    wl = si.WORKLOADS[name]
+    run_case(wl.desc, wl.batch, wl.seq, seed=0, backward=True, grad_std=1e-3, gains=(1.0, 1.0), delta=1.5e-2, min_clear=0.6,
+             visible=False)
 
 
 def test_moe_descriptor_checks():
