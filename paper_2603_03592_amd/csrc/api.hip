@@ -38,6 +38,7 @@ struct Arena {
 
 constexpr int64_t kScoreScratchElems = 1 << 18;   // ScorePartial records (20 MiB)
 constexpr int kSwMaxDirs = 128, kSwMaxClaims = 4096;
+constexpr int kAttnPadHd = 64;                    // narrower heads are zero-padded to this width for the matrix-core attention
 constexpr int kSwSlots = 33;                      // projected tensors (kSwMaxDirs rows each) the scratch holds at max_tokens
 
 }  // namespace
@@ -60,6 +61,8 @@ struct sv_ctx {
   // mixture of experts (expert-sorted rows, moe_padded_rows(max_tokens) of them)
   MoeRoute route;      // forward-only contexts: one routing, reused by every block
   void *xp, *actp, *yp, *dup_p;
+  // heads narrower than the matrix-core attention kernels' 64 columns: zero-padded copies [T, heads * 64]
+  void *qkv_pad, *o_pad, *dout_pad, *dqkv_pad;
   int last_T = 0;      // tokens of the most recent verify call (for sv_last_routing)
   // backward
   std::vector<void*> xs;           // outputs of blocks 0..L-2 (inputs of blocks 1..L-1)
@@ -163,6 +166,13 @@ size_t carve(sv_ctx* c, char* base) {
     c->actp = a.take(Mp * F * es);
     if (!bwd) { take_route(c->route); c->yp = a.take(Mp * D * es); }
     else c->dup_p = a.take(Mp * F * es);
+  }
+  c->qkv_pad = c->o_pad = c->dout_pad = c->dqkv_pad = nullptr;
+  if (d.dtype == SV_BF16 && !(c->flags & SV_FLAG_PLAIN_KERNELS) && c->hd < kAttnPadHd) {
+    const size_t hq = (size_t)d.n_heads * kAttnPadHd, hall = (size_t)(d.n_heads + 2 * d.n_kv_heads) * kAttnPadHd;
+    c->qkv_pad = a.take(T * hall * es);
+    c->o_pad = a.take(T * hq * es);
+    if (bwd) { c->dout_pad = a.take(T * hq * es); c->dqkv_pad = a.take(T * hall * es); }
   }
   c->xs.clear(); c->stash.clear();
   if (!bwd) {
@@ -268,10 +278,25 @@ hipError_t gemm(sv_ctx* c, const GemmArgs& a, hipStream_t st) {
   return plain_gemm(a, c->d.dtype, st);
 }
 
+// Heads of 8, 16 or 32 columns run on the 64-column matrix-core kernels through zero-padded copies (the products are
+// unchanged by zero columns; the softmax scale stays 1/sqrt(hd)); three quarters or more of those MFMAs multiply zeros,
+// which is still several times faster than the scalar kernels.
+bool attn_padded(const sv_ctx* c, int S) {
+  const sv_stage_desc& d = c->d;
+  return c->qkv_pad != nullptr && mfma_attn_supported(S, d.n_heads, d.n_kv_heads, kAttnPadHd, (int64_t)(d.n_heads + 2 * d.n_kv_heads) * kAttnPadHd);
+}
+
 hipError_t attn_fwd(sv_ctx* c, const void* qkv, void* o, float* lse, int B, int S, hipStream_t st) {
   const sv_stage_desc& d = c->d;
   if (d.dtype == SV_BF16 && !(c->flags & SV_FLAG_PLAIN_KERNELS) && mfma_attn_supported(S, d.n_heads, d.n_kv_heads, c->hd, c->Dqkv))
     return mfma_attn_fwd(qkv, c->Dqkv, o, lse, B, S, d.n_heads, d.n_kv_heads, c->hd, d.causal, st);
+  if (attn_padded(c, S)) {
+    const int64_t T = (int64_t)B * S, ldp = (int64_t)(d.n_heads + 2 * d.n_kv_heads) * kAttnPadHd, ldo = (int64_t)d.n_heads * kAttnPadHd;
+    hipError_t e = plain_pad_heads(qkv, c->Dqkv, c->qkv_pad, ldp, T, d.n_heads + 2 * d.n_kv_heads, c->hd, kAttnPadHd, 1, st);
+    if (e == hipSuccess) e = mfma_attn_fwd(c->qkv_pad, ldp, c->o_pad, lse, B, S, d.n_heads, d.n_kv_heads, kAttnPadHd, d.causal, st, c->hd);
+    if (e == hipSuccess) e = plain_pad_heads(c->o_pad, ldo, o, c->Dq, T, d.n_heads, c->hd, kAttnPadHd, 0, st);
+    return e;
+  }
   return plain_attn_fwd(qkv, c->Dqkv, o, lse, B, S, d.n_heads, d.n_kv_heads, c->hd, d.causal, d.dtype, st);
 }
 
@@ -280,12 +305,24 @@ bool attn_on_mfma(const sv_ctx* c, int S) {
   return d.dtype == SV_BF16 && !(c->flags & SV_FLAG_PLAIN_KERNELS) && mfma_attn_supported(S, d.n_heads, d.n_kv_heads, c->hd, c->Dqkv);
 }
 
-// the MFMA kernels also undo RoPE on dq, dk; the plain ones leave that to a separate pass
+// the MFMA kernels also undo RoPE on dq, dk; the plain ones (and the padded form) leave that to a separate pass
 hipError_t attn_bwd(sv_ctx* c, const BlockStash& k, int B, int S, hipStream_t st) {
   const sv_stage_desc& d = c->d;
   if (attn_on_mfma(c, S))
     return mfma_attn_bwd(k.qkv, c->Dqkv, k.o, c->dout, k.lse, c->delta, c->dqkv, B, S, d.n_heads, d.n_kv_heads, c->hd, d.causal,
                          d.rope ? c->rope_cs : nullptr, st);
+  if (attn_padded(c, S) && c->dout_pad) {
+    const int nh = d.n_heads + 2 * d.n_kv_heads;
+    const int64_t T = (int64_t)B * S, ldp = (int64_t)nh * kAttnPadHd, ldo = (int64_t)d.n_heads * kAttnPadHd;
+    hipError_t e = plain_pad_heads(k.qkv, c->Dqkv, c->qkv_pad, ldp, T, nh, c->hd, kAttnPadHd, 1, st);
+    if (e == hipSuccess) e = plain_pad_heads(k.o, c->Dq, c->o_pad, ldo, T, d.n_heads, c->hd, kAttnPadHd, 1, st);
+    if (e == hipSuccess) e = plain_pad_heads(c->dout, c->Dq, c->dout_pad, ldo, T, d.n_heads, c->hd, kAttnPadHd, 1, st);
+    if (e == hipSuccess)
+      e = mfma_attn_bwd(c->qkv_pad, ldp, c->o_pad, c->dout_pad, k.lse, c->delta, c->dqkv_pad, B, S, d.n_heads, d.n_kv_heads, kAttnPadHd, d.causal,
+                        nullptr, st, c->hd);
+    if (e == hipSuccess) e = plain_pad_heads(c->dqkv_pad, ldp, c->dqkv, c->Dqkv, T, nh, c->hd, kAttnPadHd, 0, st);
+    return e;
+  }
   return plain_attn_bwd(k.qkv, c->Dqkv, k.o, c->dout, k.lse, c->delta, c->dqkv, B, S, d.n_heads, d.n_kv_heads, c->hd, d.causal, d.dtype, st);
 }
 

@@ -498,11 +498,12 @@ bool mfma_attn_supported(int S, int H, int Hkv, int hd, int64_t ld) {
   return (hd == 64 || hd == 128) && S >= 1 && H % Hkv == 0 && ld % 8 == 0;
 }
 
-hipError_t mfma_attn_fwd(const void* qkv, int64_t ld, void* o, float* lse, int B, int S, int H, int Hkv, int hd, int causal, hipStream_t st) {
+hipError_t mfma_attn_fwd(const void* qkv, int64_t ld, void* o, float* lse, int B, int S, int H, int Hkv, int hd, int causal, hipStream_t st,
+                         int scale_hd) {
   if (!mfma_attn_supported(S, H, Hkv, hd, ld)) return hipErrorInvalidValue;
   if (B <= 0) return hipSuccess;
   const dim3 grid((S + BQ - 1) / BQ, H, B), block(256);
-  const float c = 1.4426950408889634f / sqrtf((float)hd);
+  const float c = 1.4426950408889634f / sqrtf((float)(scale_hd > 0 ? scale_hd : hd));
 #define SV_ATTN_LAUNCH(HDV, CZ)                                                                                         \
   do {                                                                                                                  \
     auto kern = attn_fwd_mfma_kernel<HDV, CZ>;                                                                          \
@@ -523,11 +524,11 @@ hipError_t mfma_attn_fwd(const void* qkv, int64_t ld, void* o, float* lse, int B
 
 
 hipError_t mfma_attn_bwd(const void* qkv, int64_t ld, const void* o, const void* dout, const float* lse, float* delta, void* dqkv, int B,
-                         int S, int H, int Hkv, int hd, int causal, const float* rope_cs, hipStream_t st) {
+                         int S, int H, int Hkv, int hd, int causal, const float* rope_cs, hipStream_t st, int scale_hd) {
   if (!mfma_attn_supported(S, H, Hkv, hd, ld)) return hipErrorInvalidValue;
   if (B <= 0) return hipSuccess;
   const dim3 gq((S + BQ - 1) / BQ, H, B), gk((S + 127) / 128, Hkv, B), block(256);
-  const float scale = 1.0f / sqrtf((float)hd);
+  const float scale = 1.0f / sqrtf((float)(scale_hd > 0 ? scale_hd : hd));
 #define SV_ATTN_BWD_LAUNCH(HDV, CZ)                                                                                     \
   do {                                                                                                                  \
     auto kq = attn_bwd_dq_mfma_kernel<HDV, CZ>;                                                                         \

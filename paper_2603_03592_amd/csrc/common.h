@@ -170,6 +170,10 @@ hipError_t plain_attn_bwd(const void* qkv, int64_t ld, const void* o, const void
                           void* dqkv, int B, int S, int H, int Hkv, int hd, int causal, int dtype, hipStream_t st);
 
 hipError_t plain_transpose(const void* src, void* dst, int R, int C, int dtype, hipStream_t st);
+// bf16 [T, n_heads * hd] (row stride ld_src) -> [T, n_heads * hd_pad] with zero columns (widen = 1), or back (widen = 0:
+// src has hd_pad columns per head, dst hd); hd, hd_pad and the strides are multiples of 8
+hipError_t plain_pad_heads(const void* src, int64_t ld_src, void* dst, int64_t ld_dst, int64_t T, int n_heads, int hd, int hd_pad, int widen,
+                           hipStream_t st);
 
 // moe.hip: routing of a mixture-of-experts MLP.  All buffers are device memory of one block.
 constexpr int kMoeMaxExperts = 16, kMoeMaxTopK = 8, kMoeChunk = 1024;
@@ -201,12 +205,13 @@ hipError_t launch_moe_combine_bwd(const void* dy, const void* yp, const void* dx
 bool mfma_gemm_supported(const GemmArgs& a);
 hipError_t mfma_gemm(const GemmArgs& a, hipStream_t st, int tile = 0);   // tile: 0 auto, 1 = 256x256, 2 = 128x128
 
-// attn_mfma.hip: bf16, head_dim 64 | 128
+// attn_mfma.hip: bf16, head_dim 64 | 128.  scale_hd (0 = hd): the head dimension the softmax scale 1/sqrt(.) is taken from,
+// for inputs whose heads were zero-padded from scale_hd to hd columns
 bool mfma_attn_supported(int S, int H, int Hkv, int hd, int64_t ld);
 hipError_t mfma_attn_fwd(const void* qkv, int64_t ld, void* o, float* lse, int B, int S, int H, int Hkv, int hd, int causal,
-                         hipStream_t st);
+                         hipStream_t st, int scale_hd = 0);
 // rope_cs != nullptr: dq and dk are rotated back (inverse RoPE) before they are stored
 hipError_t mfma_attn_bwd(const void* qkv, int64_t ld, const void* o, const void* dout, const float* lse, float* delta, void* dqkv,
-                         int B, int S, int H, int Hkv, int hd, int causal, const float* rope_cs, hipStream_t st);
+                         int B, int S, int H, int Hkv, int hd, int causal, const float* rope_cs, hipStream_t st, int scale_hd = 0);
 
 }  // namespace sv

@@ -398,7 +398,39 @@ __global__ __launch_bounds__(256) void transpose_kernel(const E* __restrict__ sr
     if (c0 + i < C && r0 + tx < R) dst[(int64_t)(c0 + i) * R + r0 + tx] = tile[tx][i];
 }
 
+// Head-dimension padding for the matrix-core attention kernels: [T, n_heads * hd] <-> [T, n_heads * hd_pad], bf16, 8 elements per
+// thread.  widen: the columns hd .. hd_pad of every head are zero.
+__global__ __launch_bounds__(256) void pad_heads_kernel(const bf16* __restrict__ src, int64_t ld_src, bf16* __restrict__ dst, int64_t ld_dst,
+                                                        int64_t T, int n_heads, int hd, int hd_pad, int widen) {
+  const int cp = hd_pad / 8, cs = hd / 8;                         // 16-byte chunks per head
+  const int per_row = n_heads * (widen ? cp : cs);
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= T * per_row) return;
+  const int64_t t = i / per_row;
+  const int r = (int)(i % per_row), h = r / (widen ? cp : cs), c = r % (widen ? cp : cs);
+  bf16x8 v;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) v[k] = (bf16)0.0f;
+  if (widen) {
+    if (c < cs) v = *reinterpret_cast<const bf16x8*>(src + t * ld_src + h * hd + c * 8);
+    *reinterpret_cast<bf16x8*>(dst + t * ld_dst + h * hd_pad + c * 8) = v;
+  } else {
+    v = *reinterpret_cast<const bf16x8*>(src + t * ld_src + h * hd_pad + c * 8);
+    *reinterpret_cast<bf16x8*>(dst + t * ld_dst + h * hd + c * 8) = v;
+  }
+}
+
 }  // namespace
+
+hipError_t plain_pad_heads(const void* src, int64_t ld_src, void* dst, int64_t ld_dst, int64_t T, int n_heads, int hd, int hd_pad, int widen,
+                           hipStream_t st) {
+  if (T <= 0 || n_heads <= 0) return hipSuccess;
+  if (hd % 8 || hd_pad % 8 || hd > hd_pad || ld_src % 8 || ld_dst % 8) return hipErrorInvalidValue;
+  const int64_t n = T * n_heads * ((widen ? hd_pad : hd) / 8);
+  hipLaunchKernelGGL(pad_heads_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (const bf16*)src, ld_src, (bf16*)dst, ld_dst, T,
+                     n_heads, hd, hd_pad, widen);
+  return hipGetLastError();
+}
 
 hipError_t plain_transpose(const void* src, void* dst, int R, int C, int dtype, hipStream_t st) {
   if (R <= 0 || C <= 0) return hipSuccess;

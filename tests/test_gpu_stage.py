@@ -51,6 +51,8 @@ MFMA_BF16 = si.StageDesc(2, 256, 4, 2, 384)                                  # e
 MFMA_GELU = si.StageDesc(1, 256, 2, 2, 512, mlp="gelu", norm="ln", rope=False)
 MFMA_HD128 = si.StageDesc(2, 512, 4, 2, 640)                                 # head_dim 128, GQA 2:1
 MFMA_BIDIR = si.StageDesc(1, 256, 2, 1, 384, causal=False)                   # head_dim 128, no mask, multi-query
+PAD_HD32 = si.StageDesc(2, 256, 8, 2, 384)                                   # head_dim 32, GQA 4:1: attention on zero-padded heads
+PAD_HD8 = dataclasses.replace(BIDIR_F32, dtype="bf16")                        # head_dim 8, multi-query, no mask, padded heads
 
 
 @pytest.mark.parametrize("desc,B,S", [(LLAMA_F32, 3, 37), (GPT_F32, 2, 70), (BIDIR_F32, 2, 33), (si.TINY.desc, 2, 64)],
@@ -66,8 +68,10 @@ def test_fp32_stage_matches_oracle(desc, B, S, backward):
 
 
 @pytest.mark.parametrize("desc,B,S", [(MFMA_BF16, 3, 80), (MFMA_GELU, 2, 136), (dataclasses.replace(LLAMA_F32, dtype="bf16"), 3, 37),
-                                      (MFMA_HD128, 2, 200), (MFMA_BIDIR, 2, 150), (MFMA_BF16, 1, 333)],
-                         ids=["mfma_swiglu", "mfma_gelu", "odd_shape_bf16", "hd128_gqa", "hd128_bidir", "hd64_long"])
+                                      (MFMA_HD128, 2, 200), (MFMA_BIDIR, 2, 150), (MFMA_BF16, 1, 333), (PAD_HD32, 2, 170),
+                                      (PAD_HD8, 2, 97)],
+                         ids=["mfma_swiglu", "mfma_gelu", "odd_shape_bf16", "hd128_gqa", "hd128_bidir", "hd64_long", "hd32_padded",
+                              "hd8_padded"])
 @pytest.mark.parametrize("backward", [False, True], ids=["fwd", "bwd"])
 @pytest.mark.parametrize("plain", [False, True], ids=["mfma", "plain"])
 def test_bf16_stage_matches_oracle(desc, B, S, backward, plain):
