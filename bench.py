@@ -30,6 +30,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="large", help="tiny|small|medium|large|moe_top1|moe_top6|sweep_s<S>_b<B>")
+    ap.add_argument("--graph", action="store_true", help="also time the step replayed from a captured HIP graph")
     ap.add_argument("--mode", default=None, choices=[None, "fwd", "fwdbwd"], help="default: the workload's own")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--plain", action="store_true", help="run the plain (non-MFMA) kernels")
@@ -363,6 +364,27 @@ def main():
     ver.profile_enable(False)
     flags = ver.read_results(res)["flag"]
     assert flags[0] == 1 and (not backward or flags[1] == 1), "the corrupted claims must be flagged"
+    graph_ms = None
+    if a.graph:
+        # the step enqueues kernels only, so it can be captured once and replayed per micro-batch: launch latency drops out
+        res.zero_()
+        torch.cuda.synchronize()
+        graph, side = torch.cuda.CUDAGraph(), torch.cuda.Stream()
+        with torch.cuda.graph(graph, stream=side):
+            stream = torch.cuda.current_stream().cuda_stream
+            step()
+        stream = torch.cuda.current_stream().cuda_stream
+        for _ in range(a.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(a.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = 1e3 * (time.perf_counter() - t0) / a.steps
+        flags = ver.read_results(res)["flag"]
+        assert flags[0] == 1 and (not backward or flags[1] == 1), "the corrupted claims must be flagged (graph replay)"
+        del graph
 
     ms_step = 1e3 * wall / a.steps
     tot_flop = sum(p["flop"] for p in prof.values()) / a.steps
@@ -390,6 +412,8 @@ def main():
                       "per_op_ms": {k: round(v["ms"] / a.steps, 4) for k, v in prof.items() if v["launches"]},
                       "per_op_tflops": {k: round(v["flop"] / (v["ms"] * 1e-3) / 1e12, 1) for k, v in prof.items() if v["flop"] and v["ms"] > 0}},
     }
+    if graph_ms is not None:
+        out["graph_replay"] = {"ms_per_step": graph_ms, "value": T / (graph_ms * 1e-3), "unit": "tokens/s"}
     if wl.name.startswith("sweep"):
         # many workers per stage: up to 128 concurrent submissions of the stage output scored in one call against the
         # recomputation they share (submissions made on the device from the recomputed output; capped at 16 GiB)
