@@ -107,25 +107,32 @@ __global__ __launch_bounds__(256) void moe_count_kernel(const int32_t* __restric
 }
 
 // One workgroup: per expert the exclusive prefix of its chunk counts, the padded expert segments, the expert of
-// every 256-row block (blocks behind the rows in use name expert 0; the products never reach them).
+// every 256-row block (blocks behind the rows in use name expert 0; the products never reach them).  Thread
+// (e, s) = (tid / 16, tid % 16) owns the s-th sixteenth of expert e's chunks: sum, prefix over s, then write.
 __global__ __launch_bounds__(256) void moe_offsets_kernel(const int32_t* __restrict__ chunk_counts, int n_chunks, int E, int max_tiles,
                                                           int32_t* __restrict__ chunk_base, int32_t* __restrict__ meta,
                                                           int32_t* __restrict__ tile_expert) {
-  __shared__ int total[kME], start[kME + 1];
-  const int tid = threadIdx.x;
-  if (tid < E) {
+  __shared__ int part[kME][17], total[kME], start[kME + 1];
+  const int tid = threadIdx.x, e = tid >> 4, sgm = tid & 15;
+  const int per = (n_chunks + 15) / 16, c0 = sgm * per, c1 = min(n_chunks, c0 + per);
+  int sum = 0;
+  if (e < E)
+    for (int c = c0; c < c1; ++c) sum += chunk_counts[(int64_t)c * E + e];
+  part[e][sgm] = sum;
+  __syncthreads();
+  if (e < E) {
     int run = 0;
-    for (int c = 0; c < n_chunks; ++c) {
-      const int v = chunk_counts[(int64_t)c * E + tid];
-      chunk_base[(int64_t)c * E + tid] = run;
-      run += v;
+    for (int i = 0; i < sgm; ++i) run += part[e][i];
+    for (int c = c0; c < c1; ++c) {
+      chunk_base[(int64_t)c * E + e] = run;
+      run += chunk_counts[(int64_t)c * E + e];
     }
-    total[tid] = run;
+    if (sgm == 15) total[e] = run;
   }
   __syncthreads();
   if (tid == 0) {
     int s = 0;
-    for (int e = 0; e < E; ++e) { start[e] = s; s += (total[e] + 255) & ~255; }
+    for (int x = 0; x < E; ++x) { start[x] = s; s += (total[x] + 255) & ~255; }
     start[E] = s;
     meta[0] = s;
   }
@@ -133,8 +140,8 @@ __global__ __launch_bounds__(256) void moe_offsets_kernel(const int32_t* __restr
   if (tid < E) { meta[1 + tid] = start[tid]; meta[1 + E + tid] = total[tid]; }
   for (int tile = tid; tile < max_tiles; tile += 256) {
     int e_of = 0;
-    for (int e = 0; e < E; ++e)
-      if (tile * 256 >= start[e] && tile * 256 < start[e + 1]) e_of = e;
+    for (int x = 0; x < E; ++x)
+      if (tile * 256 >= start[x] && tile * 256 < start[x + 1]) e_of = x;
     tile_expert[tile] = e_of;
   }
 }

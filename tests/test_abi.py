@@ -33,7 +33,8 @@ def test_result_struct_is_32_bytes():
     assert sv.RESULT_DTYPE.fields["flag"][1] == 16 and sv.RESULT_DTYPE.fields["argmax_token"][1] == 28
 
 
-@pytest.mark.parametrize("wl", [si.TINY, si.SMALL, si.MEDIUM, si.LARGE, si.sweep_point(4096, 16)], ids=lambda w: w.name)
+@pytest.mark.parametrize("wl", [si.TINY, si.SMALL, si.MEDIUM, si.LARGE, si.sweep_point(4096, 16), si.MOE_TOP1, si.MOE_TOP6],
+                         ids=lambda w: w.name)
 def test_benchmark_stages_are_supported(wl):
     st, msg = sv.sv_check_desc(wl.desc, 1 if wl.backward else 0)
     assert st == 0, msg
@@ -59,3 +60,23 @@ def test_malformed_and_unsupported_descriptors_are_rejected():
         assert sv.sv_workspace_bytes(desc, 128, 64) == -1
     st, msg = sv.sv_check_desc(d, flags=64)
     assert st == 1 and "flag" in msg
+
+
+def test_mixture_of_experts_descriptors():
+    d = si.MOE_TOP6.desc
+    assert sv.sv_check_desc(d)[0] == 0
+    bad = [
+        (dataclasses.replace(d, top_k=9), 1, "top_k"),                       # more than n_experts
+        (dataclasses.replace(d, top_k=0), 1, "top_k"),
+        (dataclasses.replace(d, n_experts=17, top_k=2), 2, "16 experts"),
+        (dataclasses.replace(d, n_experts=16, top_k=9), 2, "top_k <= 8"),
+        (dataclasses.replace(d, mlp="gelu"), 2, "SwiGLU"),
+        (dataclasses.replace(d, n_experts=0), 1, "dense MLP"),               # routing fields without experts
+    ]
+    for desc, status, frag in bad:
+        st, msg = sv.sv_check_desc(desc)
+        assert st == status and frag in msg, (desc, st, msg)
+    # the expert-sorted buffers are part of the workspace: more experts per token, more rows
+    one = sv.sv_workspace_bytes(dataclasses.replace(d, top_k=1), 8192, 1024, 0)
+    six = sv.sv_workspace_bytes(d, 8192, 1024, 0)
+    assert 0 < one < six
