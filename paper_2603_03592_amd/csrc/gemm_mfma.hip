@@ -313,7 +313,11 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(GemmA
 // interleaved the same way, double buffered in registers.  The loop is rotated so that the one
 // full wait + barrier per slice sits at the loop top: after it the compiler's counter tracking
 // is exact and no other wait stalls the MFMA stream.
-template <int EPI>
+//
+// GROUPED: the grouped form (per-row-block weight group, row count from device memory) as its own instantiation, so
+// that the dense form's code -- in particular its waits, which scalar loads in the tile-change path would disturb
+// (they share a counter with the LDS reads) -- is unaffected by it.
+template <int EPI, bool GROUPED>
 __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tiles_m, int tiles_n) {
   constexpr bool DUAL = EPI == EPI_SWIGLU;
   constexpr int BM = 256, BN = 256, STAGE = (BM + BN) * 128, MI = 4, NI = 4;
@@ -321,8 +325,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
   // grouped form: the row count lives in device memory and the launch covers its bound
-  const int M = a.m_dev ? *a.m_dev : a.M;
-  if (a.m_dev) tiles_m = (M + BM - 1) / BM;
+  const int M = GROUPED ? *a.m_dev : a.M;
+  if (GROUPED) tiles_m = (M + BM - 1) / BM;
   // Persistent workgroups: workgroup b works on the virtual block ids b, b + gridDim.x, ...; a virtual id
   // maps to a tile so that ids congruent mod 8 (one XCD) walk a contiguous run of tiles in groups of
   // kGroupM row tiles.  gridDim.x is a multiple of 8, so a workgroup stays on its XCD's run.
@@ -352,7 +356,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
   auto set_segment = [&]() {
     const GemmSeg& sg = a.seg[dseg];
     gA = (const char*)((const bf16*)sg.A + (int64_t)d_m0 * sg.lda);
-    const int64_t goff = a.tile_group ? (int64_t)a.tile_group[d_m0 >> 8] * a.group_stride : 0;
+    const int64_t goff = GROUPED ? (int64_t)a.tile_group[d_m0 >> 8] * a.group_stride : 0;
     if (!DUAL && a.nbcol > 0) {
       int start = 0, j = 0;
       while (j + 1 < a.nbcol && d_n0 >= start + a.ncol[j]) { start += a.ncol[j]; ++j; }
@@ -562,9 +566,9 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
 #undef SV_SB
 }
 
-template <int EPI>
+template <int EPI, bool GROUPED>
 hipError_t launch_dma(const GemmArgs& a, hipStream_t st) {
-  auto kern = gemm_mfma_dma_kernel<EPI>;
+  auto kern = gemm_mfma_dma_kernel<EPI, GROUPED>;
   constexpr int lds = 2 * 512 * 128;
   static bool configured = false;
   if (!configured) {
@@ -629,8 +633,9 @@ bool mfma_gemm_supported(const GemmArgs& a) {
     if (a.nbcol > 0 && tot != a.N) return false;
     if (a.epi == EPI_ROPE && (!a.rope_cs || a.rope_hd % 4 || a.rope_cols % 4 || a.rope_S < 1)) return false;
   }
-  if (a.tile_group && (a.nbcol > 0 || a.group_stride % 8)) return false;
-  if (a.m_dev && a.M % 256) return false;
+  if ((a.tile_group != nullptr) != (a.m_dev != nullptr)) return false;      // the grouped form needs both
+  if (a.tile_group && (a.nbcol > 0 || a.group_stride % 8 || a.M % 256)) return false;
+  if (a.tile_group && a.epi != EPI_STORE && a.epi != EPI_SWIGLU && a.epi != EPI_SWIGLU_BWD) return false;
   if (a.b_is_kn && (a.epi == EPI_RESID || a.epi == EPI_GELU || a.epi == EPI_SWIGLU)) return false;
   if ((a.epi == EPI_RESID || a.epi == EPI_SWIGLU_BWD || a.epi == EPI_GELU_BWD) && !a.R) return false;
   if (a.epi == EPI_SWIGLU_BWD && (!a.R2 || !a.C2)) return false;
@@ -654,14 +659,22 @@ hipError_t mfma_gemm(const GemmArgs& a, hipStream_t st, int tile) {
     bool fits = true;
     for (int s = 0; s < a.nseg; ++s) fits = fits && 256 * a.seg[s].lda * 2 < (int64_t)1 << 32 && 256 * a.seg[s].ldb * 2 < (int64_t)1 << 32;
     if (fits) {
+      if (a.tile_group) {
+        switch (a.epi) {                                   // the epilogues the mixture-of-experts products use
+          case EPI_STORE: return launch_dma<EPI_STORE, true>(a, st);
+          case EPI_SWIGLU: return launch_dma<EPI_SWIGLU, true>(a, st);
+          case EPI_SWIGLU_BWD: return launch_dma<EPI_SWIGLU_BWD, true>(a, st);
+          default: return hipErrorInvalidValue;
+        }
+      }
       switch (a.epi) {
-        case EPI_STORE: return launch_dma<EPI_STORE>(a, st);
-        case EPI_RESID: return launch_dma<EPI_RESID>(a, st);
-        case EPI_GELU: return launch_dma<EPI_GELU>(a, st);
-        case EPI_SWIGLU: return launch_dma<EPI_SWIGLU>(a, st);
-        case EPI_SWIGLU_BWD: return launch_dma<EPI_SWIGLU_BWD>(a, st);
-        case EPI_GELU_BWD: return launch_dma<EPI_GELU_BWD>(a, st);
-        case EPI_ROPE: return launch_dma<EPI_ROPE>(a, st);
+        case EPI_STORE: return launch_dma<EPI_STORE, false>(a, st);
+        case EPI_RESID: return launch_dma<EPI_RESID, false>(a, st);
+        case EPI_GELU: return launch_dma<EPI_GELU, false>(a, st);
+        case EPI_SWIGLU: return launch_dma<EPI_SWIGLU, false>(a, st);
+        case EPI_SWIGLU_BWD: return launch_dma<EPI_SWIGLU_BWD, false>(a, st);
+        case EPI_GELU_BWD: return launch_dma<EPI_GELU_BWD, false>(a, st);
+        case EPI_ROPE: return launch_dma<EPI_ROPE, false>(a, st);
         default: return hipErrorInvalidValue;
       }
     }
