@@ -349,12 +349,15 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
 
   // ---- DMA side: one continuous stream of slices across this workgroup's tiles, always one slice
   // ahead of the multiply.  State: virtual block d_vb (tile d_m0, d_n0), segment dseg, offset dk.
-  int d_vb = blockIdx.x, d_m0 = 0, d_n0 = 0, dseg = 0, dk = 0;
+  int d_vb = blockIdx.x, d_m0 = 0, d_n0 = 0, dseg = 0, dk = 0, d_K = 0;   // d_K: length of segment dseg, kept in a register
+                                                                           // (a per-slice kernel-argument load would share
+                                                                           // its wait counter with the LDS reads)
   bool d_valid = tile_of(d_vb, d_m0, d_n0);
   const char *gA, *gB, *gB2;
   unsigned voffA[8], voffB[8];
   auto set_segment = [&]() {
     const GemmSeg& sg = a.seg[dseg];
+    d_K = sg.K;
     gA = (const char*)((const bf16*)sg.A + (int64_t)d_m0 * sg.lda);
     const int64_t goff = GROUPED ? (int64_t)a.tile_group[d_m0 >> 8] * a.group_stride : 0;
     if (!DUAL && a.nbcol > 0) {
@@ -384,7 +387,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
   };
   auto advance = [&]() {                                      // to the next slice of the stream
     dk += BK;
-    if (dk < a.seg[dseg].K) return;
+    if (dk < d_K) return;
     dk = 0;
     if (dseg + 1 < a.nseg) { ++dseg; set_segment(); return; }
     dseg = 0;
