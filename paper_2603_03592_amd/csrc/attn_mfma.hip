@@ -18,6 +18,24 @@ namespace {
 
 constexpr int BQ = 128, BKV = 64;
 
+// Workgroup id -> (batch, head, tile) for the kernels that stream the keys / values of one (batch, kv head) pair.
+// Workgroup ids go round-robin over the 8 XCDs, each with its own L2; ids congruent mod 8 are therefore given whole
+// (batch, kv head) pairs, so that the G query heads and all tiles that read one pair's K / V run on ONE XCD and find
+// them in its L2 (1 MB per pair at S = 2048, head_dim 128) instead of every XCD streaming every pair from HBM.  Within
+// a pair: tiles in descending order (the longest causal rows first), the G heads of a tile next to each other.
+// Returns false for the padding ids of an XCD with fewer pairs.
+__device__ __forceinline__ bool xcd_map(int w, int n_tiles, int G, int Hkv, int B, int& tile_rank, int& h, int& b) {
+  const int xcd = w & 7, i = w >> 3, per_pair = G * n_tiles;
+  const int pair = (i / per_pair) * 8 + xcd;
+  if (pair >= B * Hkv) return false;
+  const int rem = i % per_pair;
+  tile_rank = rem / G;
+  h = (pair % Hkv) * G + rem % G;
+  b = pair / Hkv;
+  return true;
+}
+inline int xcd_grid(int n_tiles, int G, int Hkv, int B) { return 8 * ((B * Hkv + 7) / 8) * G * n_tiles; }
+
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 
 // Position of 16-byte chunk c inside row `row` of a row-major LDS tile (an involution in c, so the staging side uses
@@ -74,7 +92,7 @@ __device__ __forceinline__ bf16x8 tr_fragment(const char* tile, int g, int db, i
 
 template <int HD, bool CAUSAL>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_fwd_mfma_kernel(const bf16* __restrict__ qkv, int64_t ld, bf16* __restrict__ o,
-                                                            float* __restrict__ lse, int S, int H, int Hkv, float scale_log2e) {
+                                                            float* __restrict__ lse, int B, int S, int H, int Hkv, float scale_log2e) {
   constexpr int KCH = HD / 8;                       // 16-byte chunks per K row
   constexpr int KROW = HD * 2;                      // bytes per K row in LDS
   constexpr int KSTAGE = BKV * KROW, VSTAGE = BKV * KROW, STAGE = KSTAGE + VSTAGE;
@@ -82,8 +100,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
   const int nqt = (S + BQ - 1) / BQ;
-  const int qt = nqt - 1 - (int)blockIdx.x;         // longest rows first
-  const int h = blockIdx.y, b = blockIdx.z, kvh = h / (H / Hkv);
+  int rank, h, b;
+  if (!xcd_map((int)blockIdx.x, nqt, H / Hkv, Hkv, B, rank, h, b)) return;
+  const int qt = nqt - 1 - rank;                    // longest rows first
+  const int kvh = h / (H / Hkv);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l31 = lane & 31, half = lane >> 5;
   const int q0 = qt * BQ, wq0 = q0 + wave * 32;
   const int Dq = H * HD, Dkv = Hkv * HD;
@@ -244,15 +264,17 @@ __device__ __forceinline__ void unrope4(float (&v)[4], const float* __restrict__
 template <int HD, bool CAUSAL>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dq_mfma_kernel(const bf16* __restrict__ qkv, int64_t ld, const bf16* __restrict__ o,
                                                                const bf16* __restrict__ dout, const float* __restrict__ lse,
-                                                               float* __restrict__ delta, bf16* __restrict__ dqkv, int S, int H, int Hkv,
+                                                               float* __restrict__ delta, bf16* __restrict__ dqkv, int B, int S, int H, int Hkv,
                                                                float scale, const float* __restrict__ rope_cs) {
   constexpr int KCH = HD / 8, NKK = HD / 16, NDB = HD / 32;
   constexpr int TILE = BKV * HD * 2;                 // bytes of one 64-row tile (row-major or transposed)
   constexpr int STAGE = 2 * TILE;                    // K and V, both row-major (K is read along its rows and transposed)
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int nqt = (S + BQ - 1) / BQ;
-  const int qt = nqt - 1 - (int)blockIdx.x;
-  const int h = blockIdx.y, b = blockIdx.z, kvh = h / (H / Hkv);
+  int rank, h, b;
+  if (!xcd_map((int)blockIdx.x, nqt, H / Hkv, Hkv, B, rank, h, b)) return;
+  const int qt = nqt - 1 - rank;
+  const int kvh = h / (H / Hkv);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l31 = lane & 31, half = lane >> 5;
   const int q0 = qt * BQ, wq0 = q0 + wave * 32, myq = wq0 + l31;
   const int Dq = H * HD, Dkv = Hkv * HD;
@@ -360,15 +382,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 template <int HD, bool CAUSAL>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __restrict__ qkv, int64_t ld, const bf16* __restrict__ dout,
                                                                 const float* __restrict__ lse, const float* __restrict__ delta,
-                                                                bf16* __restrict__ dqkv, int S, int H, int Hkv, float scale,
+                                                                bf16* __restrict__ dqkv, int B, int S, int H, int Hkv, float scale,
                                                                 const float* __restrict__ rope_cs) {
   constexpr int KCH = HD / 8, NKK = HD / 16, NDB = HD / 32;
   constexpr int TILE = 64 * HD * 2;
   constexpr int STAGE = 2 * TILE + 512;              // Q and dO row-major (read along the rows and transposed), lse2[64], delta[64]
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  const int kvh = blockIdx.y, b = blockIdx.z, G = H / Hkv;
+  const int G = H / Hkv;
+  int kt, kvh, b;                                     // key tiles ascending: the longest causal columns first
+  if (!xcd_map((int)blockIdx.x, (S + 127) / 128, 1, Hkv, B, kt, kvh, b)) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l31 = lane & 31, half = lane >> 5;
-  const int k0 = blockIdx.x * 128, wk0 = k0 + wave * 32, mykey = wk0 + l31;
+  const int k0 = kt * 128, wk0 = k0 + wave * 32, mykey = wk0 + l31;
   const int Dq = H * HD, Dkv = Hkv * HD;
   const float c2 = scale * 1.4426950408889634f;
   const int krow = min(mykey, S - 1);
@@ -502,7 +526,7 @@ hipError_t mfma_attn_fwd(const void* qkv, int64_t ld, void* o, float* lse, int B
                          int scale_hd) {
   if (!mfma_attn_supported(S, H, Hkv, hd, ld)) return hipErrorInvalidValue;
   if (B <= 0) return hipSuccess;
-  const dim3 grid((S + BQ - 1) / BQ, H, B), block(256);
+  const dim3 grid(xcd_grid((S + BQ - 1) / BQ, H / Hkv, Hkv, B)), block(256);
   const float c = 1.4426950408889634f / sqrtf((float)(scale_hd > 0 ? scale_hd : hd));
 #define SV_ATTN_LAUNCH(HDV, CZ)                                                                                         \
   do {                                                                                                                  \
@@ -514,7 +538,7 @@ hipError_t mfma_attn_fwd(const void* qkv, int64_t ld, void* o, float* lse, int B
       if (e != hipSuccess) return e;                                                                                    \
       configured = true;                                                                                                \
     }                                                                                                                   \
-    hipLaunchKernelGGL(kern, grid, block, lds, st, (const bf16*)qkv, ld, (bf16*)o, lse, S, H, Hkv, c);                  \
+    hipLaunchKernelGGL(kern, grid, block, lds, st, (const bf16*)qkv, ld, (bf16*)o, lse, B, S, H, Hkv, c);                  \
   } while (0)
   if (hd == 128) { if (causal) SV_ATTN_LAUNCH(128, true); else SV_ATTN_LAUNCH(128, false); }
   else { if (causal) SV_ATTN_LAUNCH(64, true); else SV_ATTN_LAUNCH(64, false); }
@@ -527,7 +551,7 @@ hipError_t mfma_attn_bwd(const void* qkv, int64_t ld, const void* o, const void*
                          int S, int H, int Hkv, int hd, int causal, const float* rope_cs, hipStream_t st, int scale_hd) {
   if (!mfma_attn_supported(S, H, Hkv, hd, ld)) return hipErrorInvalidValue;
   if (B <= 0) return hipSuccess;
-  const dim3 gq((S + BQ - 1) / BQ, H, B), gk((S + 127) / 128, Hkv, B), block(256);
+  const dim3 gq(xcd_grid((S + BQ - 1) / BQ, H / Hkv, Hkv, B)), gk(xcd_grid((S + 127) / 128, 1, Hkv, B)), block(256);
   const float scale = 1.0f / sqrtf((float)(scale_hd > 0 ? scale_hd : hd));
 #define SV_ATTN_BWD_LAUNCH(HDV, CZ)                                                                                     \
   do {                                                                                                                  \
@@ -542,9 +566,9 @@ hipError_t mfma_attn_bwd(const void* qkv, int64_t ld, const void* o, const void*
       configured = true;                                                                                                \
     }                                                                                                                   \
     hipLaunchKernelGGL(kq, gq, block, lq, st, (const bf16*)qkv, ld, (const bf16*)o, (const bf16*)dout, lse, delta,      \
-                       (bf16*)dqkv, S, H, Hkv, scale, rope_cs);                                                         \
-    hipLaunchKernelGGL(kk, gk, block, lk, st, (const bf16*)qkv, ld, (const bf16*)dout, lse, delta, (bf16*)dqkv, S, H,   \
-                       Hkv, scale, rope_cs);                                                                            \
+                       (bf16*)dqkv, B, S, H, Hkv, scale, rope_cs);                                                      \
+    hipLaunchKernelGGL(kk, gk, block, lk, st, (const bf16*)qkv, ld, (const bf16*)dout, lse, delta, (bf16*)dqkv, B, S,   \
+                       H, Hkv, scale, rope_cs);                                                                         \
   } while (0)
   if (hd == 128) { if (causal) SV_ATTN_BWD_LAUNCH(128, true); else SV_ATTN_BWD_LAUNCH(128, false); }
   else { if (causal) SV_ATTN_BWD_LAUNCH(64, true); else SV_ATTN_BWD_LAUNCH(64, false); }
