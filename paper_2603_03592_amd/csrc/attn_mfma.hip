@@ -69,6 +69,31 @@ __device__ __forceinline__ void stage_two_tiles(const bf16* a, int64_t lda, cons
   }
 }
 
+// The same transfer for tiles that lie inside the valid rows, with the per-lane part of the addresses made once per
+// kernel: 32-bit byte offsets (row within the tile, swizzled chunk) that are added to a wave-uniform tile pointer, so a
+// tile costs its load instructions and a few scalar adds instead of a 64-bit multiply chain per load.
+template <int HD, int NW = 4>
+struct TileOffsets {
+  static constexpr int KCH = HD / 8, KROW = HD * 2, RPI = 1024 / KROW, IPW = (64 / RPI) / NW;
+  unsigned off[IPW];
+  __device__ __forceinline__ void init(int64_t ld, int wave, int lane) {
+    const int s_row = lane / KCH, s_pos = lane % KCH;
+#pragma unroll
+    for (int i = 0; i < IPW; ++i) {
+      const int r = (wave * IPW + i) * RPI + s_row;
+      off[i] = (unsigned)((int64_t)r * ld + rm_pos<HD>(s_pos, r) * 8) * 2u;
+    }
+  }
+};
+template <int HD, int NW = 4>
+__device__ __forceinline__ void stage_tile_fast(const bf16* tile_rows, const TileOffsets<HD, NW>& o, char* dst, int wave) {
+  const char* g = (const char*)tile_rows;           // wave-uniform: first row of the tile
+#pragma unroll
+  for (int i = 0; i < TileOffsets<HD, NW>::IPW; ++i)
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(g + o.off[i]),
+                                     (__attribute__((address_space(3))) void*)(dst + (wave * TileOffsets<HD, NW>::IPW + i) * 1024), 16, 0, 0);
+}
+
 // A-operand fragment of the TRANSPOSE of a row-major 64-row tile, for MFMA g (0..3) of the tile's 64 rows and feature
 // block db: the lane gets features db * 32 + (lane & 31) of 8 rows, in the order the score accumulators hold them
 // ({0-3, 8-11} of the 16 rows for the lower lane half, {4-7, 12-15} for the upper one).  Transposing LDS read: in each
@@ -121,9 +146,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int nkv = (S + BKV - 1) / BKV;
   const int ntiles = CAUSAL ? min((q0 + BQ + BKV - 1) / BKV, nkv) : nkv;
 
+  TileOffsets<HD> toff;
+  toff.init(ld, wave, lane);
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   auto stage_tile = [&](int j, int stage) {
     char* ks = smem + stage * STAGE;
-    stage_two_tiles<HD>(kbase, ld, vbase, ld, j * BKV, S - 1, ks, ks + KSTAGE, wave, lane);   // keys past the end: masked later
+    if ((j + 1) * BKV <= S) {                        // whole tile inside the sequence (uniform)
+      stage_tile_fast<HD>(kbase + (int64_t)j * BKV * ld, toff, ks, wave_u);
+      stage_tile_fast<HD>(vbase + (int64_t)j * BKV * ld, toff, ks + KSTAGE, wave_u);
+    } else {
+      stage_two_tiles<HD>(kbase, ld, vbase, ld, j * BKV, S - 1, ks, ks + KSTAGE, wave, lane);   // keys past the end: masked later
+    }
   };
 
   f32x16 oacc[NDB];
@@ -305,9 +338,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
   const int nkv = (S + BKV - 1) / BKV;
   const int ntiles = CAUSAL ? min((q0 + BQ + BKV - 1) / BKV, nkv) : nkv;
+  TileOffsets<HD> toff;
+  toff.init(ld, wave, lane);
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   auto stage_tile = [&](int j, int stage) {
     char* base = smem + stage * STAGE;
-    stage_two_tiles<HD>(kbase, ld, vbase, ld, j * BKV, S - 1, base, base + TILE, wave, lane);
+    if ((j + 1) * BKV <= S) {                        // whole tile inside the sequence (uniform)
+      stage_tile_fast<HD>(kbase + (int64_t)j * BKV * ld, toff, base, wave_u);
+      stage_tile_fast<HD>(vbase + (int64_t)j * BKV * ld, toff, base + TILE, wave_u);
+    } else {
+      stage_two_tiles<HD>(kbase, ld, vbase, ld, j * BKV, S - 1, base, base + TILE, wave, lane);
+    }
   };
 
   f32x16 dq[NDB];
@@ -410,11 +451,21 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
   const int nq = (S - qstart + 63) / 64;             // query tiles per head
   const int ntiles = nq * G;
   float lreg = 0.0f, dlreg = 0.0f;
+  TileOffsets<HD> toff_q, toff_d;
+  toff_q.init(ld, wave, lane);
+  toff_d.init(Dq, wave, lane);
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   auto stage_tile = [&](int j, int stage) {            // Q and dO tiles straight to LDS; the two per-query scalars via registers
     const int h = kvh * G + j / nq, q0 = qstart + (j % nq) * 64;
     char* base = smem + stage * STAGE;
-    stage_two_tiles<HD>(qkv + (int64_t)b * S * ld + (int64_t)h * HD, ld, dout + (int64_t)b * S * Dq + (int64_t)h * HD, Dq, q0, S - 1, base,
-                        base + TILE, wave, lane);
+    const bf16* qrows = qkv + (int64_t)b * S * ld + (int64_t)h * HD;
+    const bf16* drows = dout + (int64_t)b * S * Dq + (int64_t)h * HD;
+    if (q0 + 64 <= S) {                              // whole tile inside the sequence (uniform)
+      stage_tile_fast<HD>(qrows + (int64_t)q0 * ld, toff_q, base, wave_u);
+      stage_tile_fast<HD>(drows + (int64_t)q0 * Dq, toff_d, base + TILE, wave_u);
+    } else {
+      stage_two_tiles<HD>(qrows, ld, drows, Dq, q0, S - 1, base, base + TILE, wave, lane);
+    }
     if (tid < 64) {
       const int64_t li = ((int64_t)b * H + h) * S + min(q0 + tid, S - 1);
       lreg = lse[li] * 1.4426950408889634f;
