@@ -19,7 +19,13 @@
  *                       normalised Euclidean, sign flip ratio) plus a per-token relative L2;
  *                       the reference is any tensor: a recomputation or the EMA m_{t-1};
  *   sv_ema_update       Eq. momentum_def over the un-flagged submissions (R_clean of
- *                       Alg. momentum_verification).
+ *                       Alg. momentum_verification);
+ *   sv_sliced_wasserstein, sv_adaptive_iqr / sv_policy_*, sv_replace_with_ema, sv_sentinel_*
+ *                       the remaining statistic of that paragraph, the adaptive thresholds and
+ *                       counters, gradient replacement, and the whole verifier loop of
+ *                       Alg. momentum_verification (declared further down).
+ * The stage may carry a dense MLP or a routed mixture of experts (sv_stage_desc); a check only
+ * enqueues kernels, so a caller may capture it into a HIP graph after one eager call.
  *
  * Conventions
  *   - Every tensor pointer is a DEVICE pointer owned by the caller; row-major, the feature
