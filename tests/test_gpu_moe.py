@@ -200,6 +200,26 @@ def test_full_size_moe_workloads(name):
              visible=False)
 
 
+def test_moe_context_reuse_with_shrinking_and_growing_batches():
+    """One context, three checks of different sizes in a row (the routing tables, segment padding and expert-sorted
+    buffers of an earlier, larger call must not leak into a later one)."""
+    import paper_2603_03592_amd as sv
+    desc = dataclasses.replace(F32, n_blocks=1)
+    w = moe_weights(desc, 21)
+    ver = sv.Verifier(desc, 4 * 300, 300, backward=True)
+    wc = ver.pack_weights(wd := dev_weights(w, "f32"))
+    for B, S in ((4, 300), (1, 5), (3, 129)):
+        h = si.make_activations(desc, B, S, 21 + S)
+        g = si.make_output_grad(desc, B, S, 21 + S, std=1.0)
+        out = ver.verify_backward(wc, dev(h, "f32"), dev(g, "f32"), want_g_hat=True, want_h_hat=True)
+        want_h, want_g, routes = oracle_run(h, g, w, desc)
+        clear = check_routing(ver, routes, desc, B, S, DELTA["f32"], True, w[0]["w_router"])
+        assert clear.mean() > 0.99
+        assert rel_l2(host(out["h_hat"]).reshape(-1, 64)[clear], want_h.reshape(-1, 64)[clear]) <= TOL["f32"], (B, S)
+        assert rel_l2(host(out["g_hat"]).reshape(-1, 64)[clear], want_g.reshape(-1, 64)[clear]) <= TOL["f32"], (B, S)
+    ver.close()
+
+
 def test_moe_descriptor_checks():
     import paper_2603_03592_amd as sv
     ok = dataclasses.replace(F32)
