@@ -220,6 +220,28 @@ def test_moe_context_reuse_with_shrinking_and_growing_batches():
     ver.close()
 
 
+def test_last_routing_errors():
+    import paper_2603_03592_amd as sv
+    desc = dataclasses.replace(F32, n_blocks=2)
+    w = moe_weights(desc, 3)
+    ver = sv.Verifier(desc, 64, 32)                                   # forward-only: keeps the last block's routing only
+    wc = ver.pack_weights(wd := dev_weights(w, "f32"))
+    with pytest.raises(sv.SVError):
+        ver.last_routing(1, 64)                                       # nothing has run yet
+    ver.verify_forward(wc, dev(si.make_activations(desc, 2, 32, 3), "f32"))
+    ex, gt = ver.last_routing(1, 64)
+    assert ex.shape == (64, 2) and float(gt.sum(dim=1).min()) > 0.999  # normalised gates
+    with pytest.raises(sv.SVError):
+        ver.last_routing(0, 64)
+    with pytest.raises(sv.SVError):
+        ver.last_routing(2, 64)
+    ver.close()
+    dense = sv.Verifier(si.TINY.desc, 64, 64)
+    with pytest.raises(sv.SVError):
+        dense.last_routing(0, 64)
+    dense.close()
+
+
 def test_moe_descriptor_checks():
     import paper_2603_03592_amd as sv
     ok = dataclasses.replace(F32)
