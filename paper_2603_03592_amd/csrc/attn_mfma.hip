@@ -205,16 +205,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       // mask (diagonal tiles and the ragged key tail), then the online softmax update
       const bool need_mask = (CAUSAL && k0 + BKV - 1 > wq0) || (k0 + BKV > S);
       float mx = -INFINITY;
+      if (need_mask) {                               // one uniform branch: tiles below the diagonal skip all of it
 #pragma unroll
-      for (int t = 0; t < 2; ++t)
+        for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          if (need_mask) {
+          for (int r = 0; r < 16; ++r) {
             const int key = k0 + t * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
             if ((CAUSAL && key > myq) || key >= S) s[t][r] = -INFINITY;
           }
-          mx = fmaxf(mx, s[t][r]);
-        }
+      }
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[t][r]);
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
       const float m_new = fmaxf(m_run, mx * scale_log2e);
       const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
@@ -382,13 +385,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
           dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, dof[kk], dp, 0, 0, 0);
         }
         bf16x8 dsf[2];
+        if (need_mask) {                             // one uniform branch; a masked score of -inf gives p = 0 below
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int key = k0 + t * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+            if ((CAUSAL && key > myq) || key >= S) s[r] = -INFINITY;
+          }
+        }
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          float p = __builtin_amdgcn_exp2f(fmaf(s[r], c2, -lse2));
-          if (need_mask) {
-            const int key = k0 + t * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-            if ((CAUSAL && key > myq) || key >= S) p = 0.0f;
-          }
+          const float p = __builtin_amdgcn_exp2f(fmaf(s[r], c2, -lse2));
           dsf[r >> 3][r & 7] = (bf16)(p * (dp[r] - dl));
         }
 #pragma unroll
@@ -516,6 +522,15 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
       }
       const bool need_mask = (CAUSAL && q0 < wk0 + 31) || (q0 + 64 > S);
       bf16x8 pf[4], dsf[4];
+      if (need_mask) {                               // one uniform branch; a masked score of -inf gives p = 0 below
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int q = q0 + t * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+            if ((CAUSAL && q < mykey) || q >= S) s[t][r] = -INFINITY;
+          }
+      }
 #pragma unroll
       for (int t = 0; t < 2; ++t)
 #pragma unroll
@@ -526,11 +541,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             const int r = r4 * 4 + i;
-            float p = __builtin_amdgcn_exp2f(fmaf(s[t][r], c2, -l4[i]));
-            if (need_mask) {
-              const int q = q0 + qq + i;
-              if ((CAUSAL && q < mykey) || q >= S) p = 0.0f;
-            }
+            const float p = __builtin_amdgcn_exp2f(fmaf(s[t][r], c2, -l4[i]));
             pf[t * 2 + (r >> 3)][r & 7] = (bf16)p;
             dsf[t * 2 + (r >> 3)][r & 7] = (bf16)(p * (dp[t][r] - d4[i]));
           }
