@@ -219,7 +219,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[t][r]);
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m_run, mx * scale_log2e);
+      // Lazy reference: the running reference m only moves when the maximum grew by more than 2^8 (probabilities then
+      // reach at most 256, harmless in bf16 and in the fp32 sums; O / l does not depend on the reference).  With the
+      // exact maximum some query of the wave moves it in most tiles and all 64 output registers get rescaled each time.
+      const float mx_s = mx * scale_log2e;
+      const float m_new = mx_s > m_run + 8.0f ? mx_s : m_run;
       const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
       m_run = m_new;
       float psum = 0.0f;
