@@ -381,12 +381,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
         for (int r = 0; r < 16; ++r) { s[r] = 0.0f; dp[r] = 0.0f; }
         const int krow = t * 32 + l31;
+        // fragments one k step ahead of the MFMAs that use them: a read issued right before its MFMA exposes the LDS latency
+        bf16x8 kf[2], vf[2];
+        kf[0] = *reinterpret_cast<const bf16x8*>(ks + rm_off<HD>(krow, half));
+        vf[0] = *reinterpret_cast<const bf16x8*>(vs + rm_off<HD>(krow, half));
 #pragma unroll
         for (int kk = 0; kk < NKK; ++kk) {
-          const bf16x8 kf = *reinterpret_cast<const bf16x8*>(ks + rm_off<HD>(krow, kk * 2 + half));
-          const bf16x8 vf = *reinterpret_cast<const bf16x8*>(vs + rm_off<HD>(krow, kk * 2 + half));
-          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s, 0, 0, 0);
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, dof[kk], dp, 0, 0, 0);
+          if (kk + 1 < NKK) {
+            kf[(kk + 1) & 1] = *reinterpret_cast<const bf16x8*>(ks + rm_off<HD>(krow, (kk + 1) * 2 + half));
+            vf[(kk + 1) & 1] = *reinterpret_cast<const bf16x8*>(vs + rm_off<HD>(krow, (kk + 1) * 2 + half));
+          }
+          __builtin_amdgcn_sched_barrier(0);           // the scheduler would otherwise sink the reads back to their uses
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk & 1], qf[kk], s, 0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kk & 1], dof[kk], dp, 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
         }
         bf16x8 dsf[2];
         if (need_mask) {                             // one uniform branch; a masked score of -inf gives p = 0 below
@@ -516,12 +524,20 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
 #pragma unroll
         for (int r = 0; r < 16; ++r) { s[t][r] = 0.0f; dp[t][r] = 0.0f; }
         const int row = t * 32 + l31;
+        // fragments one k step ahead of the MFMAs that use them
+        bf16x8 qf[2], df[2];
+        qf[0] = *reinterpret_cast<const bf16x8*>(qs + rm_off<HD>(row, half));
+        df[0] = *reinterpret_cast<const bf16x8*>(ds_ + rm_off<HD>(row, half));
 #pragma unroll
         for (int kk = 0; kk < NKK; ++kk) {
-          const bf16x8 qf = *reinterpret_cast<const bf16x8*>(qs + rm_off<HD>(row, kk * 2 + half));
-          const bf16x8 df = *reinterpret_cast<const bf16x8*>(ds_ + rm_off<HD>(row, kk * 2 + half));
-          s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kf[kk], s[t], 0, 0, 0);
-          dp[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(df, vf[kk], dp[t], 0, 0, 0);
+          if (kk + 1 < NKK) {
+            qf[(kk + 1) & 1] = *reinterpret_cast<const bf16x8*>(qs + rm_off<HD>(row, (kk + 1) * 2 + half));
+            df[(kk + 1) & 1] = *reinterpret_cast<const bf16x8*>(ds_ + rm_off<HD>(row, (kk + 1) * 2 + half));
+          }
+          __builtin_amdgcn_sched_barrier(0);           // the scheduler would otherwise sink the reads back to their uses
+          s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[kk & 1], kf[kk], s[t], 0, 0, 0);
+          dp[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(df[kk & 1], vf[kk], dp[t], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
         }
       }
       const bool need_mask = (CAUSAL && q0 < wk0 + 31) || (q0 + 64 > S);
