@@ -792,7 +792,10 @@ sv_status sv_sliced_wasserstein(sv_ctx* c, const void* claims, int64_t claim_str
   const bool shared = ref_stride == 0;
   const double flop_per = 2.0 * (double)T * D * L;
   const int ces = claim_dtype == SV_BF16 ? 2 : 4, res = ref_dtype == SV_BF16 ? 2 : 4;
-  if (shared) {
+  // A shared reference is projected in the first group's launch, beside the submissions (alone its few token tiles
+  // leave most of the chip idle), where the kernel has that dtype pair.
+  const bool ref_with_first = shared && sw_project_with_ref_supported(claim_dtype, ref_dtype);
+  if (shared && !ref_with_first) {
     SV_OP(c, SV_OP_SW_PROJECT, flop_per, st, launch_sw_project(ref, 0, 1, ref_dtype, directions, L, D, T, Tpad, c->sw_proj, st));
     SV_OP(c, SV_OP_SW_SORT, 0, st, launch_sw_sort(c->sw_proj, L, T, Tpad, nullptr, 0, L, nullptr, 0, st));
   }
@@ -806,8 +809,14 @@ sv_status sv_sliced_wasserstein(sv_ctx* c, const void* claims, int64_t claim_str
             launch_sw_project(at(ref, (int64_t)first * ref_stride, res), ref_stride, n, ref_dtype, directions, L, D, T, Tpad, pref, st));
       SV_OP(c, SV_OP_SW_SORT, 0, st, launch_sw_sort(pref, n * L, T, Tpad, nullptr, 0, L, nullptr, 0, st));
     }
-    SV_OP(c, SV_OP_SW_PROJECT, flop_per * n, st,
-          launch_sw_project(at(claims, (int64_t)first * claim_stride, ces), claim_stride, n, claim_dtype, directions, L, D, T, Tpad, pcl, st));
+    if (ref_with_first && first == 0) {
+      SV_OP(c, SV_OP_SW_PROJECT, flop_per * (n + 1), st,
+            launch_sw_project_with_ref(claims, claim_stride, n, claim_dtype, ref, ref_dtype, directions, L, D, T, Tpad, pcl, pref, st));
+      SV_OP(c, SV_OP_SW_SORT, 0, st, launch_sw_sort(pref, L, T, Tpad, nullptr, 0, L, nullptr, 0, st));
+    } else {
+      SV_OP(c, SV_OP_SW_PROJECT, flop_per * n, st,
+            launch_sw_project(at(claims, (int64_t)first * claim_stride, ces), claim_stride, n, claim_dtype, directions, L, D, T, Tpad, pcl, st));
+    }
     SV_OP(c, SV_OP_SW_SORT, 0, st, launch_sw_sort(pcl, n * L, T, Tpad, pref, shared ? 1 : 0, L, c->sw_w1, first * L, st));
   }
   SV_HIP(c, launch_sw_finalize(c->sw_w1, n_claims, L, T, tau, sw_out, results_dev, st));

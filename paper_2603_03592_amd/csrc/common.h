@@ -115,6 +115,11 @@ hipError_t launch_replace(void* signals, int64_t stride, int n, int dtype, const
 int64_t sw_padded_len(int64_t T);
 hipError_t launch_sw_project(const void* X, int64_t stride, int count, int dtype, const void* U, int L, int D, int64_t T, int64_t Tpad,
                              float* P, hipStream_t st);
+// One launch for a single reference tensor (into Pref) and `count` submissions (into P); only for the dtype pairs
+// sw_project_with_ref_supported names.
+bool sw_project_with_ref_supported(int dtype, int ref_dtype);
+hipError_t launch_sw_project_with_ref(const void* X, int64_t stride, int count, int dtype, const void* ref, int ref_dtype, const void* U,
+                                      int L, int D, int64_t T, int64_t Tpad, float* P, float* Pref, hipStream_t st);
 // Sort n_seg rows; with ref != nullptr also w1[first_seg + s] = sum_t |row_s[t] - ref_row[t]| (ref rows already sorted).
 hipError_t launch_sw_sort(float* P, int n_seg, int64_t T, int64_t Tpad, const float* ref, int ref_shared, int L, float* w1,
                           int first_seg, hipStream_t st);

@@ -25,9 +25,13 @@ __global__ __launch_bounds__(256) void score_tokens_kernel(const EC* __restrict_
                                                            const ER* __restrict__ ref, int64_t ref_stride, int64_t T, int D,
                                                            int n_claims, int tiles_per_claim, float* __restrict__ token_scores,
                                                            ScorePartial* __restrict__ partials) {
-  // claim index varies fastest so that workgroups running together share the reference rows
-  const int claim = blockIdx.x % n_claims;
-  const int tile = blockIdx.x / n_claims;
+  // Workgroup ids go round-robin over the 8 XCDs (each with its own L2): ids congruent mod 8 get a contiguous run of
+  // token tiles, and within a run the claim index varies fastest, so the submissions that share a tile of the
+  // reference run together on one XCD and fetch it from memory once instead of once per XCD.
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int claim = slot % n_claims;
+  const int tile = xcd * ((tiles_per_claim + 7) >> 3) + slot / n_claims;
+  if (tile >= tiles_per_claim) return;               // the last XCD's run may be short (whole workgroup leaves)
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const EC* cbase = claims + (int64_t)claim * claim_stride;
   const ER* rbase = ref + (int64_t)claim * ref_stride;
@@ -101,6 +105,170 @@ __global__ __launch_bounds__(256) void score_tokens_kernel(const EC* __restrict_
     }
     p.max_rel = b; p.argmax = bt; p.bad = bd; p.pad = 0;
     partials[(int64_t)claim * tiles_per_claim + tile] = p;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// The same statistics for several submissions against ONE shared reference whose token rows are short enough to be
+// held in registers (a row of the submission is 2, 4 or 8 KB: NU 16-byte units per lane).  A wave owns a token: it
+// loads the reference row once, forms the reference's own sums and -- for the sign-flip ratio -- one class mask per
+// element, and then streams the same row of every submission of its group past them, the next submission's loads in
+// flight while the current one is reduced.  Compared with score_tokens_kernel the reference is read once per group
+// instead of once per submission, and its share of the arithmetic is paid once: 7 vector instructions per element
+// instead of 16, which moves the all-statistics pass from the vector ALUs' bound to the memory's.
+//   sign test: sign(a) == sign(b), with sign(0) = sign(NaN) = 0, is one v_cmp_class of a against the set of classes
+//   that b's sign allows; the matches are counted on the scalar unit from the lane mask.
+// Lane c of a wave keeps the running sums of the group's submission c (a predicated add after each reduction); the
+// four waves' sums are folded per submission at the end, into the same per-(submission, tile) records as above.
+constexpr int kGroupMax = 32;                 // submissions per group (<= 64: one lane each)
+
+__device__ __forceinline__ float dpp_add(float v, int ctrl_sel) {
+  const int x = __float_as_int(v);
+  int y;
+  switch (ctrl_sel) {                                            // immediate operands
+    case 0: y = __builtin_amdgcn_update_dpp(0, x, 0xB1, 0xF, 0xF, false); break;     // quad_perm [1,0,3,2]
+    case 1: y = __builtin_amdgcn_update_dpp(0, x, 0x4E, 0xF, 0xF, false); break;     // quad_perm [2,3,0,1]
+    case 2: y = __builtin_amdgcn_update_dpp(0, x, 0x141, 0xF, 0xF, false); break;    // row_half_mirror
+    default: y = __builtin_amdgcn_update_dpp(0, x, 0x140, 0xF, 0xF, false); break;   // row_mirror
+  }
+  return v + __int_as_float(y);
+}
+// Sum over the 64 lanes without the LDS crossbar: four exchange steps inside each row of 16 lanes, then the four row
+// sums are read as scalars.  Every lane gets the same value (a fixed order: run-to-run identical).
+__device__ __forceinline__ float wave_sum_rows(float v) {
+  v = dpp_add(v, 0); v = dpp_add(v, 1); v = dpp_add(v, 2); v = dpp_add(v, 3);
+  const int x = __float_as_int(v);
+  const float r0 = __int_as_float(__builtin_amdgcn_readlane(x, 0)), r1 = __int_as_float(__builtin_amdgcn_readlane(x, 16));
+  const float r2 = __int_as_float(__builtin_amdgcn_readlane(x, 32)), r3 = __int_as_float(__builtin_amdgcn_readlane(x, 48));
+  return (r0 + r1) + (r2 + r3);
+}
+
+template <typename E, int N> struct RawUnit;                     // N consecutive elements as they come from memory
+template <> struct RawUnit<bf16, 8> { bf16x8 v; __device__ __forceinline__ void load(const bf16* p) { v = *reinterpret_cast<const bf16x8*>(p); }
+                                      __device__ __forceinline__ float get(int i) const { return static_cast<float>(v[i]); } };
+template <> struct RawUnit<bf16, 4> { bf16x4 v; __device__ __forceinline__ void load(const bf16* p) { v = *reinterpret_cast<const bf16x4*>(p); }
+                                      __device__ __forceinline__ float get(int i) const { return static_cast<float>(v[i]); } };
+template <> struct RawUnit<float, 4> { f32x4 v; __device__ __forceinline__ void load(const float* p) { v = *reinterpret_cast<const f32x4*>(p); }
+                                       __device__ __forceinline__ float get(int i) const { return v[i]; } };
+template <> struct RawUnit<float, 8> { f32x4 a, b; __device__ __forceinline__ void load(const float* p) { a = *reinterpret_cast<const f32x4*>(p); b = *reinterpret_cast<const f32x4*>(p + 4); }
+                                       __device__ __forceinline__ float get(int i) const { return i < 4 ? a[i] : b[i - 4]; } };
+
+template <typename EC, typename ER, int NU, bool FULL>
+__global__ __launch_bounds__(256) void score_group_kernel(const EC* __restrict__ claims, int64_t claim_stride, const ER* __restrict__ ref,
+                                                          int64_t T, int n_claims, int G, int n_groups, int tiles_per_claim,
+                                                          float* __restrict__ token_scores, ScorePartial* __restrict__ partials) {
+  constexpr int EPU = 16 / (int)sizeof(EC);            // elements per 16-byte unit of a submission's row
+  constexpr int D = NU * 64 * EPU;
+  // ids congruent mod 8 (one XCD, one L2) get a contiguous run of token tiles; the groups of a tile follow each other
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int group = slot % n_groups;
+  const int tile = xcd * ((tiles_per_claim + 7) >> 3) + slot / n_groups;
+  if (tile >= tiles_per_claim) return;
+  const int c0 = group * G, nc = min(G, n_claims - c0);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+
+  double acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};            // lane c: submission c0 + c
+  float best = -1.0f;
+  int best_t = 0, bad = 0;
+
+  for (int i = 0; i < kTPW; ++i) {
+    const int64_t t = (int64_t)tile * kScoreTokensPerWG + i * 4 + wave;
+    if (t >= T) break;                                 // uniform per wave
+    const ER* r = ref + t * D + lane * EPU;
+    float rv[NU][EPU];
+    int cls[NU][EPU];
+    float sr = 0, srr = 0;
+#pragma unroll
+    for (int m = 0; m < NU; ++m) {
+      RawUnit<ER, EPU> u;
+      u.load(r + m * 64 * EPU);
+#pragma unroll
+      for (int j = 0; j < EPU; ++j) {
+        const float b = u.get(j);
+        rv[m][j] = b;
+        srr = fmaf(b, b, srr);
+        if (FULL) {
+          sr += b;
+          // classes a may have for sign(a) == sign(b): {+denormal, +normal, +inf}, {-inf, -normal, -denormal}, {NaNs, -0, +0}
+          cls[m][j] = b > 0.0f ? 0x380 : (b < 0.0f ? 0x01C : 0x063);
+        }
+      }
+    }
+    srr = wave_sum_rows(srr);
+    if (FULL) sr = wave_sum_rows(sr);
+    const float rnorm = fmaxf(sqrtf(srr), 1e-30f);
+
+    const EC* cb = claims + (int64_t)c0 * claim_stride + t * D + lane * EPU;
+    RawUnit<EC, EPU> bufA[NU], bufB[NU];
+    auto fetch = [&](RawUnit<EC, EPU> (&buf)[NU], int c) {
+      const EC* p = cb + (int64_t)c * claim_stride;
+#pragma unroll
+      for (int m = 0; m < NU; ++m) buf[m].load(p + m * 64 * EPU);
+    };
+    auto reduce = [&](const RawUnit<EC, EPU> (&buf)[NU], int c) {
+      float sc = 0, scc = 0, sad = 0, sdd = 0;
+      int match = 0;                                    // wave-uniform
+#pragma unroll
+      for (int m = 0; m < NU; ++m)
+#pragma unroll
+        for (int j = 0; j < EPU; ++j) {
+          const float a = buf[m].get(j), d = a - rv[m][j];
+          sdd = fmaf(d, d, sdd);
+          if (FULL) {
+            sc += a; scc = fmaf(a, a, scc); sad += fabsf(d);
+            // the compare's lane mask goes straight to the scalar unit (through the generic ballot the compiler
+            // turns the predicate into a register value and compares again)
+            uint64_t lanes;
+            asm("v_cmp_class_f32_e64 %0, %1, %2" : "=s"(lanes) : "v"(a), "v"(cls[m][j]));
+            match += __builtin_popcountll(lanes);
+            asm volatile("" : "+s"(match));          // count now: otherwise all the masks stay live until the predicated adds below
+          }
+        }
+      sdd = wave_sum_rows(sdd);
+      if (FULL) { sc = wave_sum_rows(sc); scc = wave_sum_rows(scc); sad = wave_sum_rows(sad); }
+      const float rel = sqrtf(sdd) / rnorm;
+      if (lane == 0 && token_scores) token_scores[(int64_t)(c0 + c) * T + t] = rel;
+      if (lane == c) {
+        acc[0] += sc; acc[1] += sr; acc[2] += scc; acc[3] += srr;
+        acc[4] += (double)sc - (double)sr;              // sum of differences (mean of d in the z-scored L2)
+        acc[5] += sad; acc[6] += sdd;
+        if (FULL) acc[7] += (double)(D - match);
+        if (!(rel <= 3.0e38f)) bad = 1;                 // NaN or inf
+        else if (rel > best) { best = rel; best_t = (int)t; }
+      }
+    };
+    fetch(bufA, 0);
+    for (int c = 0; c < nc; c += 2) {
+      if (c + 1 < nc) fetch(bufB, c + 1);
+      reduce(bufA, c);
+      if (c + 1 < nc) {
+        if (c + 2 < nc) fetch(bufA, c + 2);
+        reduce(bufB, c + 1);
+      }
+    }
+  }
+
+  __shared__ double s_acc[4][kGroupMax][8];
+  __shared__ float s_best[4][kGroupMax];
+  __shared__ int s_bt[4][kGroupMax], s_bad[4][kGroupMax];
+  if (lane < nc) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) s_acc[wave][lane][j] = acc[j];
+    s_best[wave][lane] = best; s_bt[wave][lane] = best_t; s_bad[wave][lane] = bad;
+  }
+  __syncthreads();
+  if ((int)threadIdx.x < nc) {
+    const int c = threadIdx.x;
+    ScorePartial p;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) p.s[j] = s_acc[0][c][j] + s_acc[1][c][j] + s_acc[2][c][j] + s_acc[3][c][j];
+    float b = -1.0f; int bt = 0, bd = 0;
+    for (int w = 0; w < 4; ++w) {
+      bd |= s_bad[w][c];
+      if (s_best[w][c] > b || (s_best[w][c] == b && s_best[w][c] >= 0.0f && s_bt[w][c] < bt)) { b = s_best[w][c]; bt = s_bt[w][c]; }
+    }
+    p.max_rel = b; p.argmax = bt; p.bad = bd; p.pad = 0;
+    partials[(int64_t)(c0 + c) * tiles_per_claim + tile] = p;
   }
 }
 
@@ -225,7 +393,7 @@ hipError_t launch_score(const void* claims, int64_t claim_stride, int n_claims, 
   const int64_t tiles = (T + kScoreTokensPerWG - 1) / kScoreTokensPerWG;
   int64_t per_launch = scratch_elems / tiles;
   if (per_launch < 1) return hipErrorInvalidValue;
-  if (per_launch * tiles > 0x7fffffffLL) per_launch = 0x7fffffffLL / tiles;
+  if (per_launch * (tiles + 7) > 0x7fffffffLL) per_launch = 0x7fffffffLL / (tiles + 7);
   Tau4 tau;
   for (int i = 0; i < 4; ++i) tau.v[i] = tau4 ? tau4[i] : 0.0f;
   const int64_t csz = claim_dtype == SV_BF16 ? 2 : 4, rsz = ref_dtype == SV_BF16 ? 2 : 4;
@@ -234,7 +402,34 @@ hipError_t launch_score(const void* claims, int64_t claim_stride, int n_claims, 
     const char* cp = (const char*)claims + c0 * claim_stride * csz;
     const char* rp = (const char*)ref + c0 * ref_stride * rsz;
     float* ts = token_scores ? token_scores + c0 * T : nullptr;
-    const dim3 grid((unsigned)(tiles * nc)), block(256);
+    const dim3 grid((unsigned)(8 * ((tiles + 7) / 8) * nc)), block(256);
+    // shared reference, several submissions, rows of 2, 4 or 8 KB: the kernel that keeps the reference row in registers
+    const int64_t row_bytes = (int64_t)D * csz;
+    if (ref_stride == 0 && nc >= 2 && (row_bytes == 2048 || row_bytes == 4096 || row_bytes == 8192)) {
+      int G = 16;
+      while (G > 4 && tiles * ((nc + G - 1) / G) < 1024) G >>= 1;
+      const int n_groups = (nc + G - 1) / G;
+      const dim3 ggrid((unsigned)(8 * ((tiles + 7) / 8) * n_groups));
+      const bool full = (mask & (SV_M_L1 | SV_M_ZL2 | SV_M_SFR)) != 0;
+#define SV_LAUNCH_GROUP4(EC, ER, NU, FULL)                                                                            \
+  hipLaunchKernelGGL((score_group_kernel<EC, ER, NU, FULL>), ggrid, block, 0, st, (const EC*)cp, claim_stride, (const ER*)rp, T, nc, G, \
+                     n_groups, (int)tiles, ts, scratch)
+#define SV_LAUNCH_GROUP(EC, ER)                                                                                       \
+  do {                                                                                                                \
+    const int nu = (int)(row_bytes / 1024);                                                                           \
+    if (full) { if (nu == 2) SV_LAUNCH_GROUP4(EC, ER, 2, true); else if (nu == 4) SV_LAUNCH_GROUP4(EC, ER, 4, true); else SV_LAUNCH_GROUP4(EC, ER, 8, true); } \
+    else { if (nu == 2) SV_LAUNCH_GROUP4(EC, ER, 2, false); else if (nu == 4) SV_LAUNCH_GROUP4(EC, ER, 4, false); else SV_LAUNCH_GROUP4(EC, ER, 8, false); } \
+  } while (0)
+      if (claim_dtype == SV_BF16 && ref_dtype == SV_BF16) SV_LAUNCH_GROUP(bf16, bf16);
+      else if (claim_dtype == SV_BF16) SV_LAUNCH_GROUP(bf16, float);
+      else if (ref_dtype == SV_BF16) SV_LAUNCH_GROUP(float, bf16);
+      else SV_LAUNCH_GROUP(float, float);
+#undef SV_LAUNCH_GROUP
+#undef SV_LAUNCH_GROUP4
+      hipLaunchKernelGGL(score_finalize_kernel, dim3(nc), dim3(256), 0, st, scratch, (int)tiles, T, D, mask, tau, reduce,
+                         results + c0);
+      continue;
+    }
 #define SV_LAUNCH_SCORE3(EC, ER, L1, Z, SFR)                                                                           \
   hipLaunchKernelGGL((score_tokens_kernel<EC, ER, L1, Z, SFR>), grid, block, 0, st, (const EC*)cp, claim_stride,          \
                      (const ER*)rp, ref_stride, T, D, nc, (int)tiles, ts, scratch)
@@ -260,23 +455,24 @@ hipError_t launch_score(const void* claims, int64_t claim_stride, int n_claims, 
 }
 
 // Alg. gradient_replacement: every signal whose mask byte is set is overwritten with the reference point m
-// (rounded to the signal's dtype); the others are left alone.  One workgroup handles 256 x 8 elements of one signal.
+// (rounded to the signal's dtype); the others are left alone.  The workgroups of a signal stride over its 8-element vectors.
 template <typename E>
 __global__ __launch_bounds__(256) void replace_kernel(E* __restrict__ signals, int64_t stride, const uint8_t* __restrict__ mask,
                                                       const float* __restrict__ m, int64_t n_vec) {
   if (mask[blockIdx.y] == 0) return;
-  const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (v >= n_vec) return;
-  float x[8];
-  load8(m + v * 8, x);
-  store8(signals + (int64_t)blockIdx.y * stride + v * 8, x);
+  for (int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x; v < n_vec; v += (int64_t)gridDim.x * 256) {
+    float x[8];
+    load8(m + v * 8, x);
+    store8(signals + (int64_t)blockIdx.y * stride + v * 8, x);
+  }
 }
 
 hipError_t launch_replace(void* signals, int64_t stride, int n, int dtype, const uint8_t* mask, const float* m, int64_t T, int D,
                           hipStream_t st) {
   if (n <= 0 || T <= 0) return hipSuccess;
   const int64_t n_vec = T * D / 8;
-  const dim3 grid((unsigned)((n_vec + 255) / 256), (unsigned)n), block(256);
+  // few workgroups per signal: most signals are left alone, and a workgroup that only reads its mask byte should be cheap
+  const dim3 grid((unsigned)min((n_vec + 255) / 256, (int64_t)1024), (unsigned)n), block(256);
   if (dtype == SV_BF16) hipLaunchKernelGGL(replace_kernel<bf16>, grid, block, 0, st, (bf16*)signals, stride, mask, m, n_vec);
   else hipLaunchKernelGGL(replace_kernel<float>, grid, block, 0, st, (float*)signals, stride, mask, m, n_vec);
   return hipGetLastError();

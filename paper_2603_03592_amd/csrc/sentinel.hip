@@ -221,7 +221,9 @@ sv_status sv_sentinel_backward(sv_sentinel* s, int32_t stage, void* g, int32_t d
   }
   SN_HIP(s, hipMemcpyAsync(s->mask_dev, s->mask_host, 2 * (size_t)d, hipMemcpyHostToDevice, hs));
   // the EMA reads only signals that are not replaced, and the replacement reads m before it is updated
-  SN_SV(s, sv_replace_with_ema(s->ctx, g, s->cfg.T * s->cfg.D, d, dtype, s->mask_dev, s->m[1][stage], s->cfg.T, s->cfg.D, hs));
+  bool any_repl = false;
+  for (int r = 0; r < d; ++r) any_repl |= repl[r] != 0;
+  if (any_repl) SN_SV(s, sv_replace_with_ema(s->ctx, g, s->cfg.T * s->cfg.D, d, dtype, s->mask_dev, s->m[1][stage], s->cfg.T, s->cfg.D, hs));
   SN_SV(s, sv_ema_update(s->ctx, s->m[1][stage], g, s->cfg.T * s->cfg.D, d, dtype, s->mask_dev + d, s->cfg.T, s->cfg.D, s->cfg.beta_g, hs));
   return SV_OK;
 }

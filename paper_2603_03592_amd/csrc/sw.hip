@@ -56,20 +56,18 @@ __device__ __forceinline__ void mac_f32(const bf16x8 (&u)[LB], const f32x4& x0, 
 constexpr int kSwTile = 256 * 128;     // bytes of one signal tile in LDS
 
 template <typename E, int LB>
-__global__ __launch_bounds__(256) void sw_project_kernel(const E* __restrict__ X, int64_t x_stride, const bf16* __restrict__ U,
-                                                         int D, int64_t T, int64_t Tpad, float* __restrict__ P) {
+__device__ __forceinline__ void sw_project_body(const char* __restrict__ xbase, const bf16* __restrict__ U, int D, int64_t T, int64_t Tpad,
+                                                float* __restrict__ out, char* smem, unsigned sig) {
   constexpr bool kBf16 = sizeof(E) == 2;
   constexpr int KC = 128 / (int)sizeof(E);            // features per chunk
   constexpr int NSTEP = KC / 16;                      // MFMA k steps per chunk
   constexpr int UPIECES = KC / 8;                     // 16-byte pieces per direction row and chunk
   constexpr int UTILE = LB * 32 * 128;                // direction rows keep a 128-byte pitch
   constexpr int ULOADS = (LB * 32 * UPIECES + 255) / 256;
-  extern __shared__ __attribute__((aligned(16))) char smem[];
   char* xs = smem;                                    // 3 signal tiles
   char* us = smem + 3 * kSwTile;                      // 2 direction chunks
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), l31 = lane & 31, lhi = lane >> 5;
   const int64_t tile0 = (int64_t)blockIdx.x * 256;
-  const char* xbase = (const char*)(X + (int64_t)blockIdx.y * x_stride);
   // direct-to-LDS plan: instruction i of this wave covers the tile rows (wave + 4 i) * 8 .. + 7
   int64_t xoff[8];
 #pragma unroll
@@ -80,7 +78,7 @@ __global__ __launch_bounds__(256) void sw_project_kernel(const E* __restrict__ X
   // Workgroups that run together start at different chunks: with a row pitch that is a multiple of the memory
   // channels' interleave, everybody reading column chunk kc of its rows at the same time would camp on few channels.
   const int nchunk = D / KC;
-  const int rot = (int)((blockIdx.x * 5u + blockIdx.y * 3u) % (unsigned)nchunk);
+  const int rot = (int)((blockIdx.x * 5u + sig * 3u) % (unsigned)nchunk);      // sig: index of the signal in its tensor
   auto chunk_of = [&](int kc) { const int c = kc + rot; return c >= nchunk ? c - nchunk : c; };
   auto dma = [&](int kc, int stage) {
     const int ck = chunk_of(kc);
@@ -160,7 +158,6 @@ __global__ __launch_bounds__(256) void sw_project_kernel(const E* __restrict__ X
     st = st + 1 >= 3 ? 0 : st + 1;
   }
   __builtin_amdgcn_s_waitcnt(0);                       // every direct-to-LDS load has landed before the LDS is given back
-  float* out = P + (int64_t)blockIdx.y * (LB * 32) * Tpad;
   const float inf = __builtin_huge_valf();             // padding sorts behind every real sample
   const int64_t t0 = tile0 + wave * 64;
 #pragma unroll
@@ -172,6 +169,25 @@ __global__ __launch_bounds__(256) void sw_project_kernel(const E* __restrict__ X
 #pragma unroll
       for (int i = 0; i < 16; ++i)
         out[(int64_t)(b * 32 + (i >> 2) * 8 + lhi * 4 + (i & 3)) * Tpad + t] = t < T ? acc[tb][b][i] : inf;
+  }
+}
+
+// The launch covers n2 (0 or 1) signals of type E2 at X2 -- projected into P2 -- in the grid rows 0 .. n2 - 1, and behind
+// them the signals X + i * x_stride of type E, projected into the slots P + i * L * Tpad.  A single reference tensor has
+// too few token tiles to fill the chip; in one launch with the submissions it runs beside them.
+template <typename E, typename E2, int LB>
+__global__ __launch_bounds__(256) void sw_project_kernel(const E* __restrict__ X, int64_t x_stride, const E2* __restrict__ X2, int n2,
+                                                         const bf16* __restrict__ U, int D, int64_t T, int64_t Tpad,
+                                                         float* __restrict__ P, float* __restrict__ P2) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int y = blockIdx.y;                           // uniform
+  if constexpr (sizeof(E) == sizeof(E2)) {
+    const char* xb = y < n2 ? (const char*)X2 : (const char*)(X + (int64_t)(y - n2) * x_stride);
+    float* out = y < n2 ? P2 : P + (int64_t)(y - n2) * (LB * 32) * Tpad;
+    sw_project_body<E, LB>(xb, U, D, T, Tpad, out, smem, y < n2 ? y : y - n2);
+  } else {
+    if (y < n2) sw_project_body<E2, LB>((const char*)X2, U, D, T, Tpad, P2, smem, y);
+    else sw_project_body<E, LB>((const char*)(X + (int64_t)(y - n2) * x_stride), U, D, T, Tpad, P + (int64_t)(y - n2) * (LB * 32) * Tpad, smem, y - n2);
   }
 }
 
@@ -314,9 +330,10 @@ __global__ void sw_finalize_kernel(const float* __restrict__ w1, int n_claims, i
   }
 }
 
-template <typename E, int LB>
-hipError_t project_launch(const void* X, int64_t stride, int count, const void* U, int D, int64_t T, int64_t Tpad, float* P, hipStream_t st) {
-  auto kern = sw_project_kernel<E, LB>;
+template <typename E, typename E2, int LB>
+hipError_t project_launch(const void* X, int64_t stride, int count, const void* X2, int n2, const void* U, int D, int64_t T, int64_t Tpad,
+                          float* P, float* P2, hipStream_t st) {
+  auto kern = sw_project_kernel<E, E2, LB>;
   constexpr int lds = 3 * kSwTile + 2 * LB * 32 * 128;
   static bool configured = false;   // per process; the attribute is per function
   if (!configured) {
@@ -324,19 +341,19 @@ hipError_t project_launch(const void* X, int64_t stride, int count, const void* 
     if (e != hipSuccess) return e;
     configured = true;
   }
-  dim3 grid((unsigned)((Tpad + 255) / 256), (unsigned)count);
-  hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, (const E*)X, stride, (const bf16*)U, D, T, Tpad, P);
+  dim3 grid((unsigned)((Tpad + 255) / 256), (unsigned)(count + n2));
+  hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, (const E*)X, stride, (const E2*)X2, n2, (const bf16*)U, D, T, Tpad, P, P2);
   return hipGetLastError();
 }
 
-template <typename E>
-hipError_t project_dispatch(const void* X, int64_t stride, int count, const void* U, int L, int D, int64_t T, int64_t Tpad, float* P,
-                            hipStream_t st) {
+template <typename E, typename E2>
+hipError_t project_dispatch(const void* X, int64_t stride, int count, const void* X2, int n2, const void* U, int L, int D, int64_t T,
+                            int64_t Tpad, float* P, float* P2, hipStream_t st) {
   switch (L / 32) {
-    case 1: return project_launch<E, 1>(X, stride, count, U, D, T, Tpad, P, st);
-    case 2: return project_launch<E, 2>(X, stride, count, U, D, T, Tpad, P, st);
-    case 3: return project_launch<E, 3>(X, stride, count, U, D, T, Tpad, P, st);
-    default: return project_launch<E, 4>(X, stride, count, U, D, T, Tpad, P, st);
+    case 1: return project_launch<E, E2, 1>(X, stride, count, X2, n2, U, D, T, Tpad, P, P2, st);
+    case 2: return project_launch<E, E2, 2>(X, stride, count, X2, n2, U, D, T, Tpad, P, P2, st);
+    case 3: return project_launch<E, E2, 3>(X, stride, count, X2, n2, U, D, T, Tpad, P, P2, st);
+    default: return project_launch<E, E2, 4>(X, stride, count, X2, n2, U, D, T, Tpad, P, P2, st);
   }
 }
 
@@ -351,8 +368,18 @@ int64_t sw_padded_len(int64_t T) {
 hipError_t launch_sw_project(const void* X, int64_t stride, int count, int dtype, const void* U, int L, int D, int64_t T, int64_t Tpad,
                              float* P, hipStream_t st) {
   if (count <= 0) return hipSuccess;
-  return dtype == SV_BF16 ? project_dispatch<bf16>(X, stride, count, U, L, D, T, Tpad, P, st)
-                          : project_dispatch<float>(X, stride, count, U, L, D, T, Tpad, P, st);
+  return dtype == SV_BF16 ? project_dispatch<bf16, bf16>(X, stride, count, nullptr, 0, U, L, D, T, Tpad, P, nullptr, st)
+                          : project_dispatch<float, float>(X, stride, count, nullptr, 0, U, L, D, T, Tpad, P, nullptr, st);
+}
+
+bool sw_project_with_ref_supported(int dtype, int ref_dtype) { return dtype == ref_dtype || (dtype == SV_BF16 && ref_dtype == SV_F32); }
+
+hipError_t launch_sw_project_with_ref(const void* X, int64_t stride, int count, int dtype, const void* ref, int ref_dtype, const void* U,
+                                      int L, int D, int64_t T, int64_t Tpad, float* P, float* Pref, hipStream_t st) {
+  if (count <= 0 || !sw_project_with_ref_supported(dtype, ref_dtype)) return hipErrorInvalidValue;
+  if (dtype == SV_BF16 && ref_dtype == SV_F32) return project_dispatch<bf16, float>(X, stride, count, ref, 1, U, L, D, T, Tpad, P, Pref, st);
+  return dtype == SV_BF16 ? project_dispatch<bf16, bf16>(X, stride, count, ref, 1, U, L, D, T, Tpad, P, Pref, st)
+                          : project_dispatch<float, float>(X, stride, count, ref, 1, U, L, D, T, Tpad, P, Pref, st);
 }
 
 hipError_t launch_sw_sort(float* P, int n_seg, int64_t T, int64_t Tpad, const float* ref, int ref_shared, int L, float* w1,

@@ -169,3 +169,43 @@ def test_score_then_ema_excludes_flagged_claims():
     want = so.ema_update(m0, claims, [0, 1, 0, 1], 0.8)
     np.testing.assert_allclose(host(m), want, rtol=2e-6, atol=2e-7)
     ver.close()
+
+
+# The kernel that holds the shared reference's token row in registers serves submissions whose rows are 2, 4 or 8 KB;
+# groups of up to 16 submissions share a workgroup, one lane of each wave keeping a submission's running sums.
+@pytest.mark.parametrize("cd,rd,D", [("bf16", "bf16", 1024), ("bf16", "f32", 2048), ("bf16", "f32", 4096), ("bf16", "bf16", 4096),
+                                     ("f32", "f32", 512), ("f32", "bf16", 1024), ("f32", "f32", 2048)])
+@pytest.mark.parametrize("n,metrics,reduce", [(2, ("rel_l2", "l1", "zl2", "sfr"), "global"), (9, ("rel_l2",), "max_token"),
+                                              (37, ("rel_l2", "l1", "zl2", "sfr"), "max_token")])
+def test_shared_reference_row_in_registers(cd, rd, D, n, metrics, reduce):
+    sv, ver = _verifier()
+    T = 45                                         # three 16-token tiles, the last one ragged
+    g = np.random.default_rng(D + n)
+    base = si.to_stage_dtype((1.3 * g.standard_normal((T, D)) + 0.1).astype(np.float32), rd)
+    kinds = ["honest", "scale", "sign", "zero", "noise", "tok_scale", "tok_zero"]
+    claims = [si.make_claim(kinds[i % len(kinds)], base.astype(np.float32), cd, seed=7 * i + 1) for i in range(n)]
+    out = ver.score_and_flag(dev(np.stack(claims), cd), dev(base, rd), metrics=metrics, tau=TAU, reduce=reduce, want_token_scores=True)
+    res = ver.read_results(out["result"])
+    _compare(res, host(out["token_scores"]), claims, [base], reduce, metrics)
+    ver.close()
+
+
+@pytest.mark.parametrize("dtype,D", [("f32", 512), ("bf16", 1024)])
+def test_sign_flip_ratio_special_values_in_register_kernel(dtype, D):
+    """sign(0) = sign(-0) = sign(NaN) = 0 and denormals keep their sign: every pairing of the classes, counted exactly."""
+    sv, ver = _verifier()
+    tiny = 1e-40                                   # denormal in both float32 and bfloat16
+    vals = np.array([0.0, -0.0, tiny, -tiny, 1.0, -2.5, np.inf, -np.inf, np.nan], np.float32)
+    T = 18
+    g = np.random.default_rng(0)
+    ref = vals[g.integers(0, len(vals) - 1, size=(T, D))]          # no NaN in the reference: the other sums stay defined
+    claims = np.stack([vals[g.integers(0, len(vals), size=(T, D))] for _ in range(3)] + [ref.copy()])
+    ref, claims = si.to_stage_dtype(ref, dtype), si.to_stage_dtype(claims, dtype)
+    out = ver.score_and_flag(dev(claims, dtype), dev(ref, dtype), metrics=("sfr",), tau={"sfr": 0.5}, reduce="global")
+    res = ver.read_results(out["result"])
+    for i in range(4):
+        c, r = np.asarray(claims[i], np.float64), np.asarray(ref, np.float64)
+        want = np.count_nonzero(so._sgn(c) != so._sgn(r))
+        assert round(float(res["score"][i][3]) * T * D) == want, (i, res["score"][i][3] * T * D, want)
+    assert res["score"][3][3] == 0.0
+    ver.close()
