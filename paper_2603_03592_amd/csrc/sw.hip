@@ -203,83 +203,135 @@ __global__ __launch_bounds__(256) void sw_project_kernel(const E* __restrict__ X
 // workgroup adds up |row[i] - ref_row[i]| over the T real samples in a fixed order and stores the
 // sum in w1[first_seg + segment]; the reference row is row (segment % L) of `ref` when ref_shared,
 // else row `segment`.
-__global__ __launch_bounds__(1024) void sw_sort_chunk_kernel(float* __restrict__ P, int64_t Tpad, int ch, int64_t k_first, int64_t k_last,
-                                                             const float* __restrict__ ref, int ref_shared, int L, int64_t T,
-                                                             float* __restrict__ w1, int first_seg) {
+//
+// The network is LDS-bound when every stage is a round trip, so a thread takes eight float4 vectors
+// v0 + m s (m = 0..7) into registers and runs up to three stages (vector strides 4s, 2s, s) on them
+// per round trip; the last pass of a level (s = 1: 32 consecutive elements) also runs the strides
+// 2 and 1 inside the vectors, and the first pass of a sort from scratch runs all of the levels
+// k = 2 .. 32 (15 stages).  13 levels of an 8192-element row take 24 round trips instead of 91.
+// The comparator and the order of the stages are those of the plain network, so the result is the same for
+// every input.  Vectors are XOR-swizzled in LDS (bits 4, 5, 6 of the vector index folded into bits
+// 1, 2 and 0 + 3) so that 16 neighbouring lanes hit 16 different 16-byte slots at every stride.
+template <int A, int B>
+__device__ __forceinline__ void cx_in(f32x4& v, bool asc) {          // components A and B of one vector
+  const float a = v[A], b = v[B];
+  const bool swap = (a > b) == asc;
+  v[A] = swap ? b : a; v[B] = swap ? a : b;
+}
+__device__ __forceinline__ void cxv(f32x4& a, f32x4& b, bool asc) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const bool swap = (a[i] > b[i]) == asc;
+    const float na = swap ? b[i] : a[i], nb = swap ? a[i] : b[i];
+    a[i] = na; b[i] = nb;
+  }
+}
+// vectors m and m + SM of the eight, direction of vector m
+template <int SM>
+__device__ __forceinline__ void vec_stage(f32x4 (&e)[8], const bool (&asc)[8]) {
+#pragma unroll
+  for (int m = 0; m < 8; ++m)
+    if ((m & SM) == 0) cxv(e[m], e[m + SM], asc[m]);
+}
+// strides 2 and 1 inside every vector
+__device__ __forceinline__ void in_stages(f32x4 (&e)[8], const bool (&asc)[8], bool with_stride2) {
+#pragma unroll
+  for (int m = 0; m < 8; ++m) {
+    if (with_stride2) { cx_in<0, 2>(e[m], asc[m]); cx_in<1, 3>(e[m], asc[m]); }
+    cx_in<0, 1>(e[m], asc[m]); cx_in<2, 3>(e[m], asc[m]);
+  }
+}
+
+__global__ __launch_bounds__(512) void sw_sort_chunk_kernel(float* __restrict__ P, int64_t Tpad, int ch, int64_t k_first, int64_t k_last,
+                                                            const float* __restrict__ ref, int ref_shared, int L, int64_t T,
+                                                            float* __restrict__ w1, int first_seg) {
   extern __shared__ __attribute__((aligned(16))) float s[];
+  f32x4* s4 = reinterpret_cast<f32x4*>(s);
   const int tid = threadIdx.x, nt = blockDim.x;
   const int64_t gbase = (int64_t)blockIdx.x * ch;
   float* row = P + (int64_t)blockIdx.y * Tpad + gbase;
-  for (int i = tid * 4; i < ch; i += nt * 4) *reinterpret_cast<f32x4*>(s + i) = *reinterpret_cast<const f32x4*>(row + i);
+  const int nvec = ch >> 2, ngroups = ch >> 5;
+  const bool swz = nvec >= 128;                       // the swizzle permutes inside blocks of 128 vectors
+  auto phys = [&](int v) { return swz ? v ^ ((((v >> 4) & 3) << 1) | (((v >> 6) & 1) * 9)) : v; };
+  for (int v = tid; v < nvec; v += nt) s4[phys(v)] = *reinterpret_cast<const f32x4*>(row + 4 * v);
   __syncthreads();
-  // Stages with j >= 8 exchange whole float4 vectors between LDS positions i and i + j (the direction bit k is the
-  // same for the four lanes of a vector); the stages j = 4, 2, 1 of a level -- and all of the levels k <= 8 -- run on 8
-  // consecutive elements held in registers, one LDS round trip for three (six) stages.
-  auto cx = [](float& a, float& b, bool asc) {
-    const bool swap = (a > b) == asc;              // same decision rule as the vector stages
-    const float na = swap ? b : a, nb = swap ? a : b;
-    a = na; b = nb;
-  };
-  auto tail8 = [&](int64_t k, bool first_levels) {
-    for (int v = tid; v < (ch >> 3); v += nt) {
-      float e[8];
-      const f32x4 p0 = *reinterpret_cast<const f32x4*>(s + v * 8), p1 = *reinterpret_cast<const f32x4*>(s + v * 8 + 4);
+
+  // one round trip: the stages `mask` (4: stride 4s, 2: stride 2s, 1: stride s, in vectors) of level k, and with
+  // in_vec (s = 1 only) the strides 2 and 1 inside the vectors
+  auto pass = [&](int64_t k, int s_log, int mask, bool in_vec) {
+    for (int g = tid; g < ngroups; g += nt) {
+      const int v0 = ((g >> s_log) << (3 + s_log)) + (g & ((1 << s_log) - 1));
+      f32x4 e[8];
+      bool asc[8];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) { e[i] = p0[i]; e[4 + i] = p1[i]; }
-      const int64_t g0 = gbase + (int64_t)v * 8;
-      if (first_levels) {                            // levels k = 2, 4 (direction varies inside the block), then k = 8
-#pragma unroll
-        for (int i = 0; i < 8; i += 2) cx(e[i], e[i + 1], ((i & 2) == 0));
-#pragma unroll
-        for (int i = 0; i < 8; ++i) if ((i & 2) == 0) cx(e[i], e[i + 2], ((i & 4) == 0));
-#pragma unroll
-        for (int i = 0; i < 8; i += 2) cx(e[i], e[i + 1], ((i & 4) == 0));
+      for (int m = 0; m < 8; ++m) {
+        const int v = v0 + (m << s_log);
+        e[m] = s4[phys(v)];
+        asc[m] = ((gbase + 4 * (int64_t)v) & k) == 0;
       }
-      const bool asc = (g0 & k) == 0;
+      if (mask & 4) vec_stage<4>(e, asc);
+      if (mask & 2) vec_stage<2>(e, asc);
+      if (mask & 1) vec_stage<1>(e, asc);
+      if (in_vec) in_stages(e, asc, true);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) cx(e[i], e[i + 4], asc);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) if ((i & 2) == 0) cx(e[i], e[i + 2], asc);
-#pragma unroll
-      for (int i = 0; i < 8; i += 2) cx(e[i], e[i + 1], asc);
-      f32x4 q0, q1;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) { q0[i] = e[i]; q1[i] = e[4 + i]; }
-      *reinterpret_cast<f32x4*>(s + v * 8) = q0;
-      *reinterpret_cast<f32x4*>(s + v * 8 + 4) = q1;
+      for (int m = 0; m < 8; ++m) s4[phys(v0 + (m << s_log))] = e[m];
     }
     __syncthreads();
   };
-  const int half = ch >> 1;
-  for (int64_t k = k_first; k <= k_last; k <<= 1) {
-    if (k < 8) continue;                             // levels 2 and 4 are part of the k = 8 register pass
-    for (int j = (int)min(k >> 1, (int64_t)half); j >= 8; j >>= 1) {
-      const int jv = j >> 2;                          // stride in float4 vectors
-      for (int p = tid; p < (ch >> 3); p += nt) {
-        const int v = 2 * p - (p & (jv - 1));
-        const bool asc = ((gbase + (int64_t)v * 4) & k) == 0;
-        f32x4 a = *reinterpret_cast<const f32x4*>(s + v * 4), b = *reinterpret_cast<const f32x4*>(s + (v + jv) * 4);
+
+  int64_t k = k_first;
+  if (k_first <= 2) {                                  // levels 2 .. 32 on 32 consecutive elements, one round trip
+    for (int g = tid; g < ngroups; g += nt) {
+      f32x4 e[8];
+      bool asc[8];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const bool swap = (a[i] > b[i]) == asc;
-          const float na = swap ? b[i] : a[i], nb = swap ? a[i] : b[i];
-          a[i] = na; b[i] = nb;
-        }
-        *reinterpret_cast<f32x4*>(s + v * 4) = a;
-        *reinterpret_cast<f32x4*>(s + (v + jv) * 4) = b;
-      }
-      __syncthreads();
+      for (int m = 0; m < 8; ++m) e[m] = s4[phys(8 * g + m)];
+#pragma unroll
+      for (int m = 0; m < 8; ++m) { cx_in<0, 1>(e[m], true); cx_in<2, 3>(e[m], false); }                // level 2
+#pragma unroll
+      for (int m = 0; m < 8; ++m) asc[m] = (m & 1) == 0;                                                  // level 4
+      in_stages(e, asc, true);
+#pragma unroll
+      for (int m = 0; m < 8; ++m) asc[m] = (m & 2) == 0;                                                  // level 8
+      vec_stage<1>(e, asc); in_stages(e, asc, true);
+#pragma unroll
+      for (int m = 0; m < 8; ++m) asc[m] = (m & 4) == 0;                                                  // level 16
+      vec_stage<2>(e, asc); vec_stage<1>(e, asc); in_stages(e, asc, true);
+      const bool a32 = ((gbase + 32 * (int64_t)g) & 32) == 0;                                             // level 32
+#pragma unroll
+      for (int m = 0; m < 8; ++m) asc[m] = a32;
+      vec_stage<4>(e, asc); vec_stage<2>(e, asc); vec_stage<1>(e, asc); in_stages(e, asc, true);
+#pragma unroll
+      for (int m = 0; m < 8; ++m) s4[phys(8 * g + m)] = e[m];
     }
-    tail8(k, k == 8 && k_first <= 2);
+    __syncthreads();
+    k = 64;
+  }
+  for (; k <= k_last; k <<= 1) {
+    // vector-stride stages of this level inside the chunk: strides min(k, ch) / 8 ... 1
+    int cur = 0;
+    for (int64_t j = (k < ch ? k : (int64_t)ch) >> 3; j >= 1; j >>= 1) ++cur;
+    while (cur > 3) {                                  // leading stages: first the remainder, then threes
+      const int g = (cur - 3) % 3 == 0 ? 3 : (cur - 3) % 3;
+      // the eight vectors always span twice the top stride (s = top / 4); a remainder runs the upper stages only
+      pass(k, cur - 3, g == 3 ? 7 : (g == 2 ? 6 : 4), false);
+      cur -= g;
+    }
+    pass(k, 0, cur == 3 ? 7 : (cur == 2 ? 3 : 1), true);
   }
   if (ref == nullptr) {
-    for (int i = tid * 4; i < ch; i += nt * 4) *reinterpret_cast<f32x4*>(row + i) = *reinterpret_cast<const f32x4*>(s + i);
+    for (int v = tid; v < nvec; v += nt) *reinterpret_cast<f32x4*>(row + 4 * v) = s4[phys(v)];
     return;
   }
   const int seg = blockIdx.y;
   const float* rrow = ref + (int64_t)(ref_shared ? seg % L : seg) * Tpad;
   float sum = 0.0f;
-  for (int64_t i = tid; i < T; i += nt) sum += fabsf(s[i] - rrow[i]);
+  for (int v = tid; 4 * (int64_t)v < T; v += nt) {   // the padding (+inf on both sides) is left out
+    const f32x4 a = s4[phys(v)], b = *reinterpret_cast<const f32x4*>(rrow + 4 * v);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (4 * (int64_t)v + i < T) sum += fabsf(a[i] - b[i]);
+  }
   sum = wave_sum(sum);
   __syncthreads();                                  // the row is no longer needed: reuse its first words
   if ((tid & 63) == 0) s[tid >> 6] = sum;
@@ -386,7 +438,7 @@ hipError_t launch_sw_sort(float* P, int n_seg, int64_t T, int64_t Tpad, const fl
                           int first_seg, hipStream_t st) {
   if (n_seg <= 0) return hipSuccess;
   const int ch = (int)min(Tpad, (int64_t)kSortChunkMax);
-  const int nt = min(1024, ch / 2);
+  const int nt = max(64, min(512, ch / 32));      // a thread holds 32 elements in the register passes
   const size_t lds = (size_t)ch * sizeof(float);
   const dim3 grid((unsigned)(Tpad / ch), (unsigned)n_seg);
   if (Tpad == ch) {
