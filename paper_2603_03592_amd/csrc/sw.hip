@@ -54,6 +54,10 @@ __device__ __forceinline__ void mac_f32(const bf16x8 (&u)[LB], const f32x4& x0, 
 }
 
 constexpr int kSwTile = 256 * 128;     // bytes of one signal tile in LDS
+#ifndef SW_DEPTH
+#define SW_DEPTH 3
+#endif
+constexpr int kSwDepth = SW_DEPTH;     // signal tiles in LDS: kSwDepth - 1 chunks in flight
 
 template <typename E, int LB>
 __device__ __forceinline__ void sw_project_body(const char* __restrict__ xbase, const bf16* __restrict__ U, int D, int64_t T, int64_t Tpad,
@@ -65,7 +69,7 @@ __device__ __forceinline__ void sw_project_body(const char* __restrict__ xbase, 
   constexpr int UTILE = LB * 32 * 128;                // direction rows keep a 128-byte pitch
   constexpr int ULOADS = (LB * 32 * UPIECES + 255) / 256;
   char* xs = smem;                                    // 3 signal tiles
-  char* us = smem + 3 * kSwTile;                      // 2 direction chunks
+  char* us = smem + kSwDepth * kSwTile;               // 2 direction chunks
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), l31 = lane & 31, lhi = lane >> 5;
   const int64_t tile0 = (int64_t)blockIdx.x * 256;
   // direct-to-LDS plan: instruction i of this wave covers the tile rows (wave + 4 i) * 8 .. + 7
@@ -111,8 +115,10 @@ __device__ __forceinline__ void sw_project_body(const char* __restrict__ xbase, 
   for (int i = 0; i < ULOADS; ++i)
     if (uon[i]) *reinterpret_cast<bf16x8*>(us + ul[i]) = *reinterpret_cast<const bf16x8*>(ug[i] + (int64_t)chunk_of(0) * KC);
   dma(0, 0);
-  dma(nchunk > 1 ? 1 : 0, 1);                          // a second chunk is always issued: the wait below counts on it
-  asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+#pragma unroll
+  for (int i = 1; i < kSwDepth - 1; ++i) dma(i < nchunk ? i : nchunk - 1, i);     // always issued: the waits below count on them
+  if (kSwDepth == 3) asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  else asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)\n\ts_barrier" ::: "memory");
   int st = 0;                                          // LDS tile of chunk kc
   for (int kc = 0; kc < nchunk; ++kc) {
     const bool more = kc + 1 < nchunk;
@@ -121,8 +127,8 @@ __device__ __forceinline__ void sw_project_body(const char* __restrict__ xbase, 
       for (int i = 0; i < ULOADS; ++i)
         if (uon[i]) ureg[i] = *reinterpret_cast<const bf16x8*>(ug[i] + (int64_t)chunk_of(kc + 1) * KC);
     }
-    const int st2 = st + 2 >= 3 ? st - 1 : st + 2;     // tile of chunk kc + 2: the one chunk kc - 1 was read from
-    dma(kc + 2 < nchunk ? kc + 2 : nchunk - 1, st2);   // past the end: re-read the last chunk (never used)
+    const int st2 = st == 0 ? kSwDepth - 1 : st - 1;   // tile of the youngest chunk: the one chunk kc - 1 was read from
+    dma(kc + kSwDepth - 1 < nchunk ? kc + kSwDepth - 1 : nchunk - 1, st2);   // past the end: re-read the last chunk (never used)
     const char* xt = xs + st * kSwTile;
     const char* ub = us + (kc & 1) * UTILE;
 #pragma unroll
@@ -154,8 +160,9 @@ __device__ __forceinline__ void sw_project_body(const char* __restrict__ xbase, 
     }
     // chunk kc + 1 has landed (only the 8 loads of chunk kc + 2 may still be in flight) and this wave is done with
     // tile st and the directions' buffer; after the barrier that holds for the whole workgroup
-    asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    st = st + 1 >= 3 ? 0 : st + 1;
+    if (kSwDepth == 3) asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    st = st + 1 >= kSwDepth ? 0 : st + 1;
   }
   __builtin_amdgcn_s_waitcnt(0);                       // every direct-to-LDS load has landed before the LDS is given back
   const float inf = __builtin_huge_valf();             // padding sorts behind every real sample
@@ -386,7 +393,7 @@ template <typename E, typename E2, int LB>
 hipError_t project_launch(const void* X, int64_t stride, int count, const void* X2, int n2, const void* U, int D, int64_t T, int64_t Tpad,
                           float* P, float* P2, hipStream_t st) {
   auto kern = sw_project_kernel<E, E2, LB>;
-  constexpr int lds = 3 * kSwTile + 2 * LB * 32 * 128;
+  constexpr int lds = kSwDepth * kSwTile + 2 * LB * 32 * 128;
   static bool configured = false;   // per process; the attribute is per function
   if (!configured) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
