@@ -196,6 +196,25 @@ sv_status sv_ema_update(sv_ctx *ctx, float *m, const void *claims, int64_t claim
                         int32_t claim_dtype, const uint8_t *flags_dev, int64_t T, int32_t D, float beta,
                         void *stream);
 
+/* sv_score_and_flag against ONE shared reference (the momentum of Eq. momentum_def) that also writes what the
+ * EMA update over these submissions needs, so that the update does not have to read them again:
+ *   sum_out [T, D] float (device) <- sum over the submissions i with skip_host[i] == 0, added in index order.
+ * skip_host: n_claims bytes in HOST memory (read during the call), NULL = none skipped: the submissions known to be
+ * excluded before they are scored (banned or tainted workers, Alg. momentum_verification).  If the verdicts then
+ * exclude nobody else, sv_ema_from_sum finishes the update; otherwise call sv_ema_update with the final flags.
+ * Restrictions beyond sv_score_and_flag's: n_claims <= 32 and a row (D elements of the submissions' dtype) must
+ * be a multiple of 2 KB -- SV_EUNSUPPORTED otherwise, nothing enqueued (use the two separate calls).           */
+sv_status sv_score_and_sum(sv_ctx *ctx, const void *claims, int64_t claim_stride, int32_t n_claims,
+                           const void *ref, int32_t claim_dtype, int32_t ref_dtype, int64_t T, int32_t D,
+                           uint32_t metric_mask, const float *tau, int32_t reduce, float *token_scores_out,
+                           sv_result *results_dev, const uint8_t *skip_host, float *sum_out, void *stream);
+
+/* m [T, D] float, in place:  m <- beta m + (1-beta) / n_summed * sum  (Eq. momentum_def with the mean taken from
+ * sv_score_and_sum's sum_out over its n_summed un-skipped submissions); n_summed = 0 leaves m unchanged.
+ * D must be a multiple of 8.                                                                               */
+sv_status sv_ema_from_sum(sv_ctx *ctx, float *m, const float *sum, int32_t n_summed, int64_t T, int32_t D,
+                          float beta, void *stream);
+
 /* Sliced Wasserstein statistic (paragraph "Choice of Distance Measure", Omega_SW): the mean over
  * n_dirs directions u of the 1-Wasserstein distance between the two signals projected on u.  The
  * samples of a signal are its T token vectors in R^D; both sides have T samples, so W1 on the line

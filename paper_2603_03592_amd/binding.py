@@ -94,6 +94,10 @@ def _load():
     L.sv_verify_backward.argtypes = [vp, C.POINTER(BlockWeightsC), vp, vp, i32, i32, vp, u32, C.POINTER(f32), i32, vp, vp, vp, vp, vp]
     L.sv_score_and_flag.restype = C.c_int
     L.sv_score_and_flag.argtypes = [vp, vp, i64, i32, vp, i64, i32, i32, i64, i32, u32, C.POINTER(f32), i32, vp, vp, vp]
+    L.sv_score_and_sum.restype = C.c_int
+    L.sv_score_and_sum.argtypes = [vp, vp, i64, i32, vp, i32, i32, i64, i32, u32, C.POINTER(f32), i32, vp, vp, C.c_char_p, vp, vp]
+    L.sv_ema_from_sum.restype = C.c_int
+    L.sv_ema_from_sum.argtypes = [vp, vp, vp, i32, i64, i32, f32, vp]
     L.sv_ema_update.restype = C.c_int
     L.sv_ema_update.argtypes = [vp, vp, vp, i64, i32, i32, vp, i64, i32, f32, vp]
     L.sv_profile_enable.restype = C.c_int
@@ -405,6 +409,32 @@ class Verifier:
                                           SV_REDUCE_MAX_TOKEN if reduce == "max_token" else SV_REDUCE_GLOBAL,
                                           _ptr(tok), _ptr(res), self._stream()))
         return dict(result=res, token_scores=tok)
+
+    def score_and_sum(self, claims, ref, skip=None, metrics=("rel_l2",), tau=(0, 0, 0, 0), reduce="max_token", want_token_scores=False):
+        """score_and_flag against one shared reference [T, D] that also returns sum [T, D] float32 = the sum of the
+        claims whose entry in `skip` (host sequence of n flags, or None) is zero."""
+        torch = self.torch
+        n, D = claims.shape[0], claims.shape[-1]
+        T = claims[0].numel() // D
+        assert claims.is_contiguous() and ref.is_contiguous() and ref.numel() == T * D
+        tok = torch.empty((n, T), dtype=torch.float32, device=claims.device) if want_token_scores else None
+        res = self._results(n)
+        total = torch.empty((T, D), dtype=torch.float32, device=claims.device)
+        skip_b = None if skip is None else bytes(bytearray(int(bool(x)) for x in skip))
+        assert skip_b is None or len(skip_b) == n
+        self._check(lib.sv_score_and_sum(self._ctx, _ptr(claims), T * D, n, _ptr(ref), _dt(claims), _dt(ref), T, D, _mask(metrics),
+                                         _tau_array(tau), SV_REDUCE_MAX_TOKEN if reduce == "max_token" else SV_REDUCE_GLOBAL,
+                                         _ptr(tok), _ptr(res), skip_b, _ptr(total), self._stream()))
+        return dict(result=res, token_scores=tok, sum=total)
+
+    def ema_from_sum(self, m, total, n_summed: int, beta: float):
+        """m [T, D] float32 updated in place from the sum of n_summed claims that score_and_sum returned."""
+        D = m.shape[-1]
+        T = m.numel() // D
+        assert m.dtype == self.torch.float32 and total.dtype == self.torch.float32 and total.numel() == m.numel()
+        assert m.is_contiguous() and total.is_contiguous()
+        self._check(lib.sv_ema_from_sum(self._ctx, _ptr(m), _ptr(total), int(n_summed), T, D, float(beta), self._stream()))
+        return m
 
     def sliced_wasserstein(self, claims, ref, directions, tau: float, results=None):
         """claims [n, T, D]; ref [T, D] shared or [n, T, D]; directions bf16 [L, D].  Returns sw [n] float32 (device);

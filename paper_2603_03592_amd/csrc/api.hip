@@ -771,6 +771,41 @@ sv_status sv_score_and_flag(sv_ctx* c, const void* claims, int64_t claim_stride,
   return SV_OK;
 }
 
+sv_status sv_score_and_sum(sv_ctx* c, const void* claims, int64_t claim_stride, int32_t n_claims, const void* ref, int32_t claim_dtype,
+                           int32_t ref_dtype, int64_t T, int32_t D, uint32_t metric_mask, const float* tau, int32_t reduce,
+                           float* token_scores_out, sv_result* results_dev, const uint8_t* skip_host, float* sum_out, void* stream) {
+  if (!c) return SV_EINVAL;
+  if (n_claims < 0 || T < 0 || D < 1) { set_err(c, "negative size"); return SV_EINVAL; }
+  if (n_claims == 0 || T == 0) return SV_OK;
+  if (!claims || !ref || !results_dev || !tau || !sum_out) { set_err(c, "claims, ref, tau, results_dev and sum_out must be non-NULL"); return SV_EINVAL; }
+  if ((claim_dtype != SV_F32 && claim_dtype != SV_BF16) || (ref_dtype != SV_F32 && ref_dtype != SV_BF16)) { set_err(c, "unknown dtype"); return SV_EINVAL; }
+  if (reduce != SV_REDUCE_GLOBAL && reduce != SV_REDUCE_MAX_TOKEN) { set_err(c, "unknown reduce"); return SV_EINVAL; }
+  if (T > 0x7fffffffLL || claim_stride < 0) { set_err(c, "T or the stride is out of range"); return SV_EINVAL; }
+  const int64_t tiles = (T + kScoreTokensPerWG - 1) / kScoreTokensPerWG;
+  if (!score_sum_supported(n_claims, 0, claim_dtype, D) || tiles * n_claims > kScoreScratchElems) {
+    set_err(c, "sv_score_and_sum needs at most 32 submissions, rows of a multiple of 2 KB and n_claims * ceil(T / 16) <= %lld",
+            (long long)kScoreScratchElems);
+    return SV_EUNSUPPORTED;
+  }
+  uint32_t skip = 0;
+  for (int i = 0; skip_host && i < n_claims; ++i)
+    if (skip_host[i]) skip |= 1u << i;
+  SV_HIP(c, launch_score(claims, claim_stride, n_claims, ref, 0, claim_dtype, ref_dtype, T, D, metric_mask, tau, reduce, token_scores_out,
+                         results_dev, c->score_scratch, kScoreScratchElems, (hipStream_t)stream, skip, sum_out));
+  return SV_OK;
+}
+
+sv_status sv_ema_from_sum(sv_ctx* c, float* m, const float* sum, int32_t n_summed, int64_t T, int32_t D, float beta, void* stream) {
+  if (!c) return SV_EINVAL;
+  if (n_summed < 0 || T < 0 || D < 1) { set_err(c, "negative size"); return SV_EINVAL; }
+  if (n_summed == 0 || T == 0) return SV_OK;
+  if (!m || !sum) { set_err(c, "m and sum must be non-NULL"); return SV_EINVAL; }
+  if (!(beta >= 0.0f && beta < 1.0f)) { set_err(c, "beta must be in [0, 1)"); return SV_EINVAL; }
+  if (D % 8) { set_err(c, "D must be a multiple of 8"); return SV_EUNSUPPORTED; }
+  SV_HIP(c, launch_ema_from_sum(m, sum, n_summed, T, D, beta, (hipStream_t)stream));
+  return SV_OK;
+}
+
 sv_status sv_sliced_wasserstein(sv_ctx* c, const void* claims, int64_t claim_stride, int32_t n_claims, const void* ref, int64_t ref_stride,
                                 int32_t claim_dtype, int32_t ref_dtype, int64_t T, int32_t D, const void* directions, int32_t L, float tau,
                                 float* sw_out, sv_result* results_dev, void* stream) {

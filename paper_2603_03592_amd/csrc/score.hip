@@ -272,6 +272,173 @@ __global__ __launch_bounds__(256) void score_group_kernel(const EC* __restrict__
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// The same scheme for rows of any multiple of 2 KB, taken in parts of NU KB (NU = 2 or 4): the reference part sits in
+// registers while the same part of every submission of the group streams past; lane c adds up submission c's sums
+// over the parts of a token and closes the token (per-token relative L2, running sums) for all submissions at once.
+// With SUM the kernel also writes, per element, the sum over the group's submissions whose bit in `skip` is clear
+// (added in index order, fp32): the mean the EMA update needs, without another pass over the submissions.  SUM needs
+// the whole set in one group.
+template <typename EC, typename ER, int NU, bool FULL, bool SUM>
+__global__ __launch_bounds__(256) void score_parts_kernel(const EC* __restrict__ claims, int64_t claim_stride, const ER* __restrict__ ref,
+                                                          int64_t T, int D, int n_claims, int G, int n_groups, int tiles_per_claim,
+                                                          float* __restrict__ token_scores, ScorePartial* __restrict__ partials,
+                                                          uint32_t skip, float* __restrict__ sum_out) {
+  constexpr int EPU = 16 / (int)sizeof(EC);            // elements per 16-byte unit of a submission's row
+  constexpr int PE = NU * 64 * EPU;                    // elements per part
+  const int parts = D / PE;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int group = slot % n_groups;
+  const int tile = xcd * ((tiles_per_claim + 7) >> 3) + slot / n_groups;
+  if (tile >= tiles_per_claim) return;
+  const int c0 = group * G, nc = min(G, n_claims - c0);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+
+  double acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};            // lane c: submission c0 + c
+  float best = -1.0f;
+  int best_t = 0, bad = 0;
+
+  for (int i = 0; i < kTPW; ++i) {
+    const int64_t t = (int64_t)tile * kScoreTokensPerWG + i * 4 + wave;
+    if (t >= T) break;                                 // uniform per wave
+    const EC* cb = claims + (int64_t)c0 * claim_stride + t * D + lane * EPU;
+    RawUnit<EC, EPU> bufA[NU], bufB[NU];
+    auto fetch = [&](RawUnit<EC, EPU> (&buf)[NU], int q) {       // q = part * nc + submission
+      const int part = q / nc, c = q - part * nc;
+      const EC* p = cb + (int64_t)c * claim_stride + part * PE;
+#pragma unroll
+      for (int m = 0; m < NU; ++m) buf[m].load(p + m * 64 * EPU);
+    };
+    float sr = 0, srr = 0;                             // the reference's sums: per lane until the token is closed
+    float tsdd = 0, tsc = 0, tscc = 0, tsad = 0;       // lane c: submission c's sums over the parts done so far
+    int tmatch = 0;
+    fetch(bufA, 0);
+    const int nq = parts * nc;
+    for (int part = 0; part < parts; ++part) {
+      const ER* r = ref + t * D + part * PE + lane * EPU;
+      float rv[NU][EPU], ssum[NU][EPU];
+      int cls[NU][EPU];
+#pragma unroll
+      for (int m = 0; m < NU; ++m) {
+        RawUnit<ER, EPU> u;
+        u.load(r + m * 64 * EPU);
+#pragma unroll
+        for (int j = 0; j < EPU; ++j) {
+          const float b = u.get(j);
+          rv[m][j] = b;
+          srr = fmaf(b, b, srr);
+          if (SUM) ssum[m][j] = 0.0f;
+          if (FULL) {
+            sr += b;
+            cls[m][j] = b > 0.0f ? 0x380 : (b < 0.0f ? 0x01C : 0x063);     // see score_group_kernel
+          }
+        }
+      }
+      auto reduce = [&](const RawUnit<EC, EPU> (&buf)[NU], int c) {
+        float sc = 0, scc = 0, sad = 0, sdd = 0;
+        int match = 0;                                  // wave-uniform
+        const bool add = SUM && ((skip >> (c0 + c)) & 1u) == 0;
+#pragma unroll
+        for (int m = 0; m < NU; ++m)
+#pragma unroll
+          for (int j = 0; j < EPU; ++j) {
+            const float a = buf[m].get(j), d = a - rv[m][j];
+            sdd = fmaf(d, d, sdd);
+            if (SUM && add) ssum[m][j] += a;
+            if (FULL) {
+              sc += a; scc = fmaf(a, a, scc); sad += fabsf(d);
+              uint64_t lanes;
+              asm("v_cmp_class_f32_e64 %0, %1, %2" : "=s"(lanes) : "v"(a), "v"(cls[m][j]));
+              match += __builtin_popcountll(lanes);
+              asm volatile("" : "+s"(match));
+            }
+          }
+        sdd = wave_sum_rows(sdd);
+        if (FULL) { sc = wave_sum_rows(sc); scc = wave_sum_rows(scc); sad = wave_sum_rows(sad); }
+        if (lane == c) { tsdd += sdd; tsc += sc; tscc += scc; tsad += sad; tmatch += match; }
+      };
+      const int q0 = part * nc;
+      for (int c = 0; c < nc; c += 2) {
+        if (q0 + c + 1 < nq) fetch(bufB, q0 + c + 1);
+        reduce(bufA, c);
+        if (c + 1 < nc) {
+          if (q0 + c + 2 < nq) fetch(bufA, q0 + c + 2);
+          reduce(bufB, c + 1);
+        } else if (q0 + c + 1 < nq) {                  // odd group: the next part's first submission sits in B
+#pragma unroll
+          for (int m = 0; m < NU; ++m) bufA[m] = bufB[m];
+        }
+      }
+      if (SUM) {
+        float* so = sum_out + t * D + part * PE + lane * EPU;
+#pragma unroll
+        for (int m = 0; m < NU; ++m) {
+          if (EPU == 8) {
+            f32x4 lo, hi;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { lo[j] = ssum[m][j]; hi[j] = ssum[m][(EPU == 8) ? 4 + j : j]; }
+            *reinterpret_cast<f32x4*>(so + m * 64 * EPU) = lo;
+            *reinterpret_cast<f32x4*>(so + m * 64 * EPU + 4) = hi;
+          } else {
+            f32x4 lo;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) lo[j] = ssum[m][j];
+            *reinterpret_cast<f32x4*>(so + m * 64 * EPU) = lo;
+          }
+        }
+      }
+    }
+    // close the token: every lane for its own submission
+    srr = wave_sum_rows(srr);
+    if (FULL) sr = wave_sum_rows(sr);
+    const float rel = sqrtf(tsdd) / fmaxf(sqrtf(srr), 1e-30f);
+    if (lane < nc) {
+      if (token_scores) token_scores[(int64_t)(c0 + lane) * T + t] = rel;
+      acc[0] += tsc; acc[1] += sr; acc[2] += tscc; acc[3] += srr;
+      acc[4] += (double)tsc - (double)sr;
+      acc[5] += tsad; acc[6] += tsdd;
+      if (FULL) acc[7] += (double)(D - tmatch);
+      if (!(rel <= 3.0e38f)) bad = 1;
+      else if (rel > best) { best = rel; best_t = (int)t; }
+    }
+  }
+
+  __shared__ double s_acc[4][kGroupMax][8];
+  __shared__ float s_best[4][kGroupMax];
+  __shared__ int s_bt[4][kGroupMax], s_bad[4][kGroupMax];
+  if (lane < nc) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) s_acc[wave][lane][j] = acc[j];
+    s_best[wave][lane] = best; s_bt[wave][lane] = best_t; s_bad[wave][lane] = bad;
+  }
+  __syncthreads();
+  if ((int)threadIdx.x < nc) {
+    const int c = threadIdx.x;
+    ScorePartial p;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) p.s[j] = s_acc[0][c][j] + s_acc[1][c][j] + s_acc[2][c][j] + s_acc[3][c][j];
+    float b = -1.0f; int bt = 0, bd = 0;
+    for (int w = 0; w < 4; ++w) {
+      bd |= s_bad[w][c];
+      if (s_best[w][c] > b || (s_best[w][c] == b && s_best[w][c] >= 0.0f && s_bt[w][c] < bt)) { b = s_best[w][c]; bt = s_bt[w][c]; }
+    }
+    p.max_rel = b; p.argmax = bt; p.bad = bd; p.pad = 0;
+    partials[(int64_t)(c0 + c) * tiles_per_claim + tile] = p;
+  }
+}
+
+// m <- beta m + (1 - beta) / n * sum: the EMA update from the sum a score_parts_kernel launch has written
+__global__ __launch_bounds__(256) void ema_from_sum_kernel(float* __restrict__ m, const float* __restrict__ sum, int64_t n_vec, float beta, float w) {
+  const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (v >= n_vec) return;
+  float mv[8], sv8[8];
+  load8(m + v * 8, mv);
+  load8(sum + v * 8, sv8);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) mv[j] = beta * mv[j] + w * sv8[j];
+  store8(m + v * 8, mv);
+}
+
 struct Tau4 { float v[4]; };
 
 __global__ __launch_bounds__(256) void score_finalize_kernel(const ScorePartial* __restrict__ partials, int tiles_per_claim,
@@ -385,11 +552,25 @@ __global__ __launch_bounds__(256) void ema_update_kernel(float* __restrict__ m, 
 
 }  // namespace
 
+bool score_sum_supported(int n_claims, int64_t ref_stride, int claim_dtype, int D) {
+  const int64_t row_bytes = (int64_t)D * (claim_dtype == SV_BF16 ? 2 : 4);
+  return n_claims >= 1 && n_claims <= kGroupMax && ref_stride == 0 && row_bytes % 2048 == 0;
+}
+
+hipError_t launch_ema_from_sum(float* m, const float* sum, int n_summed, int64_t T, int D, float beta, hipStream_t st) {
+  if (n_summed <= 0 || T <= 0) return hipSuccess;    // nobody entered the sum: the EMA is left as it is
+  const int64_t n_vec = T * D / 8;
+  hipLaunchKernelGGL(ema_from_sum_kernel, dim3((unsigned)((n_vec + 255) / 256)), dim3(256), 0, st, m, sum, n_vec, beta,
+                     (1.0f - beta) / (float)n_summed);
+  return hipGetLastError();
+}
+
 hipError_t launch_score(const void* claims, int64_t claim_stride, int n_claims, const void* ref, int64_t ref_stride,
                         int claim_dtype, int ref_dtype, int64_t T, int D, uint32_t mask, const float* tau4, int reduce,
                         float* token_scores, sv_result* results, ScorePartial* scratch, int64_t scratch_elems,
-                        hipStream_t st) {
+                        hipStream_t st, uint32_t skip, float* sum_out) {
   if (n_claims <= 0 || T <= 0) return hipSuccess;
+  if (sum_out && !score_sum_supported(n_claims, ref_stride, claim_dtype, D)) return hipErrorInvalidValue;
   const int64_t tiles = (T + kScoreTokensPerWG - 1) / kScoreTokensPerWG;
   int64_t per_launch = scratch_elems / tiles;
   if (per_launch < 1) return hipErrorInvalidValue;
@@ -403,14 +584,44 @@ hipError_t launch_score(const void* claims, int64_t claim_stride, int n_claims, 
     const char* rp = (const char*)ref + c0 * ref_stride * rsz;
     float* ts = token_scores ? token_scores + c0 * T : nullptr;
     const dim3 grid((unsigned)(8 * ((tiles + 7) / 8) * nc)), block(256);
-    // shared reference, several submissions, rows of 2, 4 or 8 KB: the kernel that keeps the reference row in registers
     const int64_t row_bytes = (int64_t)D * csz;
-    if (ref_stride == 0 && nc >= 2 && (row_bytes == 2048 || row_bytes == 4096 || row_bytes == 8192)) {
+    const bool full = (mask & (SV_M_L1 | SV_M_ZL2 | SV_M_SFR)) != 0;
+    const bool whole_rows = row_bytes == 2048 || row_bytes == 4096 || row_bytes == 8192;
+    // shared reference, rows of a multiple of 2 KB other than those three, or the sum over the submissions wanted:
+    // the kernel that takes the rows in parts
+    if (ref_stride == 0 && row_bytes % 2048 == 0 && (sum_out || (nc >= 2 && !whole_rows))) {
+      if (sum_out && (nc != n_claims || nc * tiles > scratch_elems)) return hipErrorInvalidValue;   // one launch, one group
+      int G = sum_out ? nc : 16;
+      while (!sum_out && G > 4 && tiles * ((nc + G - 1) / G) < 1024) G >>= 1;
+      const int n_groups = (nc + G - 1) / G;
+      const dim3 ggrid((unsigned)(8 * ((tiles + 7) / 8) * n_groups));
+#define SV_LAUNCH_PARTS5(EC, ER, NU, FULL, SUM)                                                                       \
+  hipLaunchKernelGGL((score_parts_kernel<EC, ER, NU, FULL, SUM>), ggrid, block, 0, st, (const EC*)cp, claim_stride, (const ER*)rp, T, D, nc, \
+                     G, n_groups, (int)tiles, ts, scratch, skip, sum_out)
+#define SV_LAUNCH_PARTS3(EC, ER, NU)                                                                                  \
+  do {                                                                                                                \
+    if (sum_out) { if (full) SV_LAUNCH_PARTS5(EC, ER, NU, true, true); else SV_LAUNCH_PARTS5(EC, ER, NU, false, true); } \
+    else { if (full) SV_LAUNCH_PARTS5(EC, ER, NU, true, false); else SV_LAUNCH_PARTS5(EC, ER, NU, false, false); }     \
+  } while (0)
+#define SV_LAUNCH_PARTS(EC, ER)                                                                                       \
+  do { if (row_bytes % 4096 == 0) SV_LAUNCH_PARTS3(EC, ER, 4); else SV_LAUNCH_PARTS3(EC, ER, 2); } while (0)
+      if (claim_dtype == SV_BF16 && ref_dtype == SV_BF16) SV_LAUNCH_PARTS(bf16, bf16);
+      else if (claim_dtype == SV_BF16) SV_LAUNCH_PARTS(bf16, float);
+      else if (ref_dtype == SV_BF16) SV_LAUNCH_PARTS(float, bf16);
+      else SV_LAUNCH_PARTS(float, float);
+#undef SV_LAUNCH_PARTS
+#undef SV_LAUNCH_PARTS3
+#undef SV_LAUNCH_PARTS5
+      hipLaunchKernelGGL(score_finalize_kernel, dim3(nc), dim3(256), 0, st, scratch, (int)tiles, T, D, mask, tau, reduce,
+                         results + c0);
+      continue;
+    }
+    // shared reference, several submissions, rows of 2, 4 or 8 KB: the kernel that keeps the whole reference row in registers
+    if (ref_stride == 0 && nc >= 2 && whole_rows) {
       int G = 16;
       while (G > 4 && tiles * ((nc + G - 1) / G) < 1024) G >>= 1;
       const int n_groups = (nc + G - 1) / G;
       const dim3 ggrid((unsigned)(8 * ((tiles + 7) / 8) * n_groups));
-      const bool full = (mask & (SV_M_L1 | SV_M_ZL2 | SV_M_SFR)) != 0;
 #define SV_LAUNCH_GROUP4(EC, ER, NU, FULL)                                                                            \
   hipLaunchKernelGGL((score_group_kernel<EC, ER, NU, FULL>), ggrid, block, 0, st, (const EC*)cp, claim_stride, (const ER*)rp, T, nc, G, \
                      n_groups, (int)tiles, ts, scratch)

@@ -27,6 +27,7 @@ struct sv_sentinel {
   sv_result* res_dev = nullptr;
   float* sw_dev = nullptr;
   uint8_t* mask_dev = nullptr;             // two rows of d bytes: replacement mask, EMA exclusion mask
+  float* sum_dev = nullptr;                // [T, D]: sum over the signals not excluded beforehand, written by the score pass
   // pinned staging
   sv_result* res_host = nullptr;
   float* sw_host = nullptr;
@@ -55,14 +56,24 @@ void set_err(sv_sentinel* s, const char* fmt, ...) {
   } while (0)
 
 // Gamma [d, n_metrics] of the d signals against the reference point m, on the host (waits for the stream).
-sv_status gamma_of(sv_sentinel* s, const void* signals, int dtype, const float* m, std::vector<double>& gamma, hipStream_t st) {
+// `skip` [d]: the signals known to be excluded from the EMA before they are scored.  Where the score pass can do it,
+// it also leaves the sum over the others in sum_dev (*summed = true), which saves the EMA update its own pass over the
+// signals whenever the verdicts exclude nobody else.
+sv_status gamma_of(sv_sentinel* s, const void* signals, int dtype, const float* m, const uint8_t* skip, bool* summed,
+                   std::vector<double>& gamma, hipStream_t st) {
   const sv_sentinel_cfg& c = s->cfg;
   const int d = c.n_workers;
   const int64_t stride = c.T * c.D;
   const float inf = std::numeric_limits<float>::infinity();
   const float tau[4] = {inf, inf, inf, inf};      // nothing is decided on the device here: the fences live in the policy
-  SN_SV(s, sv_score_and_flag(s->ctx, signals, stride, d, m, 0, dtype, SV_F32, c.T, c.D, c.metric_mask & 15u, tau, SV_REDUCE_GLOBAL, nullptr,
-                             s->res_dev, st));
+  sv_status sum_st = s->sum_dev ? sv_score_and_sum(s->ctx, signals, stride, d, m, dtype, SV_F32, c.T, c.D, c.metric_mask & 15u, tau,
+                                                   SV_REDUCE_GLOBAL, nullptr, s->res_dev, skip, s->sum_dev, st)
+                                : SV_EUNSUPPORTED;
+  *summed = sum_st == SV_OK;
+  if (sum_st == SV_EUNSUPPORTED)                  // shapes the summing pass does not take: the plain one
+    SN_SV(s, sv_score_and_flag(s->ctx, signals, stride, d, m, 0, dtype, SV_F32, c.T, c.D, c.metric_mask & 15u, tau, SV_REDUCE_GLOBAL, nullptr,
+                               s->res_dev, st));
+  else if (sum_st != SV_OK) { set_err(s, "sv_score_and_sum: %s", sv_last_error(s->ctx)); return sum_st; }
   SN_HIP(s, hipMemcpyAsync(s->res_host, s->res_dev, sizeof(sv_result) * d, hipMemcpyDeviceToHost, st));
   if (c.metric_mask & SV_M_SW) {
     SN_SV(s, sv_sliced_wasserstein(s->ctx, signals, stride, d, m, 0, dtype, SV_F32, c.T, c.D, c.directions, c.n_dirs, inf, s->sw_dev,
@@ -79,6 +90,24 @@ sv_status gamma_of(sv_sentinel* s, const void* signals, int dtype, const float* 
       else v = s->res_host[r].score[bit == SV_M_RELL2 ? SV_IDX_RELL2 : bit == SV_M_L1 ? SV_IDX_L1 : bit == SV_M_ZL2 ? SV_IDX_ZL2 : SV_IDX_SFR];
       gamma[(size_t)r * s->n_metrics + i] = v;
     }
+  return SV_OK;
+}
+
+// Eq. momentum_def over the signals with excl[r] == 0.  If the score pass has left the sum over the signals with
+// skip[r] == 0 and the verdicts excluded nobody beyond those, the update is one pass over m and that sum; otherwise
+// the update reads the signals itself.
+sv_status update_ema(sv_sentinel* s, float* m, const void* signals, int dtype, const uint8_t* excl, const uint8_t* skip, bool summed,
+                     float beta, hipStream_t hs, bool mask_uploaded = false) {
+  const int d = s->cfg.n_workers;
+  bool same = summed;
+  int n = 0;
+  for (int r = 0; r < d; ++r) { same = same && (excl[r] != 0) == (skip[r] != 0); n += excl[r] == 0; }
+  if (same) {
+    SN_SV(s, sv_ema_from_sum(s->ctx, m, s->sum_dev, n, s->cfg.T, s->cfg.D, beta, hs));
+    return SV_OK;
+  }
+  if (!mask_uploaded) SN_HIP(s, hipMemcpyAsync(s->mask_dev + d, excl, (size_t)d, hipMemcpyHostToDevice, hs));
+  SN_SV(s, sv_ema_update(s->ctx, m, signals, s->cfg.T * s->cfg.D, d, dtype, s->mask_dev + d, s->cfg.T, s->cfg.D, beta, hs));
   return SV_OK;
 }
 
@@ -123,6 +152,9 @@ sv_status sv_sentinel_create(sv_ctx* ctx, const sv_sentinel_cfg* cfg, sv_sentine
   if (st == SV_OK && e == hipSuccess) e = hipMalloc(&s->res_dev, sizeof(sv_result) * d);
   if (st == SV_OK && e == hipSuccess) e = hipMalloc(&s->sw_dev, sizeof(float) * d);
   if (st == SV_OK && e == hipSuccess) e = hipMalloc(&s->mask_dev, 2 * (size_t)d);
+  if (st == SV_OK && e == hipSuccess && d <= 32) {  // optional: without it the EMA update reads the signals itself
+    if (hipMalloc(&s->sum_dev, m_bytes) != hipSuccess) { s->sum_dev = nullptr; (void)hipGetLastError(); }
+  }
   if (st == SV_OK && e == hipSuccess) e = hipHostMalloc((void**)&s->res_host, sizeof(sv_result) * d, hipHostMallocDefault);
   if (st == SV_OK && e == hipSuccess) e = hipHostMalloc((void**)&s->sw_host, sizeof(float) * d, hipHostMallocDefault);
   if (st == SV_OK && e == hipSuccess) e = hipHostMalloc((void**)&s->mask_host, 2 * (size_t)d, hipHostMallocDefault);
@@ -144,6 +176,7 @@ void sv_sentinel_destroy(sv_sentinel* s) {
   if (s->res_dev) (void)hipFree(s->res_dev);
   if (s->sw_dev) (void)hipFree(s->sw_dev);
   if (s->mask_dev) (void)hipFree(s->mask_dev);
+  if (s->sum_dev) (void)hipFree(s->sum_dev);
   if (s->res_host) (void)hipHostFree(s->res_host);
   if (s->sw_host) (void)hipHostFree(s->sw_host);
   if (s->mask_host) (void)hipHostFree(s->mask_host);
@@ -167,18 +200,23 @@ sv_status sv_sentinel_forward(sv_sentinel* s, int32_t stage, const void* h, int3
   hipStream_t hs = (hipStream_t)stream;
   const int d = s->cfg.n_workers, p = s->cfg.n_stages;
   std::vector<double> gamma;
-  st = gamma_of(s, h, dtype, s->m[0][stage], gamma, hs);
+  sv_policy* pol = s->pol[0][stage];
+  std::vector<uint8_t> upstream(d, 0), banned(d, 0), skip(d, 0);
+  if (!s->warm) {                                  // excluded whatever this check says: banned or tainted upstream
+    for (int r = 0; r < d; ++r)
+      for (int s2 = 0; s2 < p; ++s2) upstream[r] |= s->tainted[(size_t)s2 * d + r];
+    SN_SV(s, sv_policy_state(pol, nullptr, banned.data(), nullptr, nullptr, nullptr, nullptr));
+    for (int r = 0; r < d; ++r) skip[r] = banned[r] | upstream[r];
+  }
+  bool summed = false;
+  st = gamma_of(s, h, dtype, s->m[0][stage], skip.data(), &summed, gamma, hs);
   if (st != SV_OK) return st;
   if (gamma_out) memcpy(gamma_out, gamma.data(), gamma.size() * sizeof(double));
-  sv_policy* pol = s->pol[0][stage];
   uint8_t* excl = s->mask_host + d;
   if (s->warm) {
     SN_SV(s, sv_policy_warmup(pol, gamma.data()));
     for (int r = 0; r < d; ++r) { tainted_out[r] = 0; excl[r] = 0; }
   } else {
-    std::vector<uint8_t> upstream(d, 0), banned(d, 0);
-    for (int r = 0; r < d; ++r)
-      for (int s2 = 0; s2 < p; ++s2) upstream[r] |= s->tainted[(size_t)s2 * d + r];
     SN_SV(s, sv_policy_step(pol, gamma.data(), upstream.data(), nullptr, tainted_out));
     SN_SV(s, sv_policy_state(pol, nullptr, banned.data(), nullptr, nullptr, nullptr, nullptr));
     for (int r = 0; r < d; ++r) {
@@ -186,9 +224,7 @@ sv_status sv_sentinel_forward(sv_sentinel* s, int32_t stage, const void* h, int3
       excl[r] = banned[r] | upstream[r] | tainted_out[r];
     }
   }
-  SN_HIP(s, hipMemcpyAsync(s->mask_dev + d, excl, (size_t)d, hipMemcpyHostToDevice, hs));
-  SN_SV(s, sv_ema_update(s->ctx, s->m[0][stage], h, s->cfg.T * s->cfg.D, d, dtype, s->mask_dev + d, s->cfg.T, s->cfg.D, s->cfg.beta_h, hs));
-  return SV_OK;
+  return update_ema(s, s->m[0][stage], h, dtype, excl, skip.data(), summed, s->cfg.beta_h, hs);
 }
 
 sv_status sv_sentinel_backward(sv_sentinel* s, int32_t stage, void* g, int32_t dtype, uint8_t* tainted_out, double* gamma_out, void* stream) {
@@ -198,19 +234,24 @@ sv_status sv_sentinel_backward(sv_sentinel* s, int32_t stage, void* g, int32_t d
   hipStream_t hs = (hipStream_t)stream;
   const int d = s->cfg.n_workers, p = s->cfg.n_stages;
   std::vector<double> gamma;
-  st = gamma_of(s, g, dtype, s->m[1][stage], gamma, hs);
+  sv_policy* pol = s->pol[1][stage];
+  std::vector<uint8_t> down(d, 0), banned(d, 0), skip(d, 0);
+  if (!s->warm) {                                  // excluded whatever this check says: banned, or tainted here on the way forward
+    for (int r = 0; r < d; ++r)
+      for (int s2 = stage + 1; s2 < p; ++s2) down[r] |= s->tainted[(size_t)s2 * d + r];
+    SN_SV(s, sv_policy_state(pol, nullptr, banned.data(), nullptr, nullptr, nullptr, nullptr));
+    for (int r = 0; r < d; ++r) skip[r] = banned[r] | s->tainted[(size_t)stage * d + r];
+  }
+  bool summed = false;
+  st = gamma_of(s, g, dtype, s->m[1][stage], skip.data(), &summed, gamma, hs);
   if (st != SV_OK) return st;
   if (gamma_out) memcpy(gamma_out, gamma.data(), gamma.size() * sizeof(double));
-  sv_policy* pol = s->pol[1][stage];
   uint8_t* repl = s->mask_host;
   uint8_t* excl = s->mask_host + d;
   if (s->warm) {
     SN_SV(s, sv_policy_warmup(pol, gamma.data()));
     for (int r = 0; r < d; ++r) { tainted_out[r] = 0; repl[r] = 0; excl[r] = 0; }
   } else {
-    std::vector<uint8_t> down(d, 0), banned(d, 0);
-    for (int r = 0; r < d; ++r)
-      for (int s2 = stage + 1; s2 < p; ++s2) down[r] |= s->tainted[(size_t)s2 * d + r];
     SN_SV(s, sv_policy_step(pol, gamma.data(), nullptr, down.data(), tainted_out));
     SN_SV(s, sv_policy_state(pol, nullptr, banned.data(), nullptr, nullptr, nullptr, nullptr));
     for (int r = 0; r < d; ++r) {
@@ -224,8 +265,8 @@ sv_status sv_sentinel_backward(sv_sentinel* s, int32_t stage, void* g, int32_t d
   bool any_repl = false;
   for (int r = 0; r < d; ++r) any_repl |= repl[r] != 0;
   if (any_repl) SN_SV(s, sv_replace_with_ema(s->ctx, g, s->cfg.T * s->cfg.D, d, dtype, s->mask_dev, s->m[1][stage], s->cfg.T, s->cfg.D, hs));
-  SN_SV(s, sv_ema_update(s->ctx, s->m[1][stage], g, s->cfg.T * s->cfg.D, d, dtype, s->mask_dev + d, s->cfg.T, s->cfg.D, s->cfg.beta_g, hs));
-  return SV_OK;
+  // (the sum the score pass left was taken before the replacement, over signals that are not replaced)
+  return update_ema(s, s->m[1][stage], g, dtype, excl, skip.data(), summed, s->cfg.beta_g, hs, /*mask_uploaded=*/true);
 }
 
 sv_status sv_sentinel_state(const sv_sentinel* s, int32_t stage, int32_t kind, const float** ema_dev, int32_t* violations, uint8_t* banned,

@@ -174,7 +174,8 @@ def test_score_then_ema_excludes_flagged_claims():
 # The kernel that holds the shared reference's token row in registers serves submissions whose rows are 2, 4 or 8 KB;
 # groups of up to 16 submissions share a workgroup, one lane of each wave keeping a submission's running sums.
 @pytest.mark.parametrize("cd,rd,D", [("bf16", "bf16", 1024), ("bf16", "f32", 2048), ("bf16", "f32", 4096), ("bf16", "bf16", 4096),
-                                     ("f32", "f32", 512), ("f32", "bf16", 1024), ("f32", "f32", 2048)])
+                                     ("f32", "f32", 512), ("f32", "bf16", 1024), ("f32", "f32", 2048),
+                                     ("bf16", "f32", 3072), ("f32", "f32", 3584), ("bf16", "bf16", 8192)])   # rows taken in parts
 @pytest.mark.parametrize("n,metrics,reduce", [(2, ("rel_l2", "l1", "zl2", "sfr"), "global"), (9, ("rel_l2",), "max_token"),
                                               (37, ("rel_l2", "l1", "zl2", "sfr"), "max_token")])
 def test_shared_reference_row_in_registers(cd, rd, D, n, metrics, reduce):
@@ -208,4 +209,50 @@ def test_sign_flip_ratio_special_values_in_register_kernel(dtype, D):
         want = np.count_nonzero(so._sgn(c) != so._sgn(r))
         assert round(float(res["score"][i][3]) * T * D) == want, (i, res["score"][i][3] * T * D, want)
     assert res["score"][3][3] == 0.0
+    ver.close()
+
+
+# sv_score_and_sum: the scores of sv_score_and_flag plus the sum over the un-skipped submissions, and
+# sv_ema_from_sum, which turns that sum into the EMA update.  Rows are taken in parts of 2 or 4 KB.
+@pytest.mark.parametrize("cd,rd,D", [("bf16", "f32", 4096), ("bf16", "bf16", 3072), ("bf16", "f32", 1024), ("f32", "f32", 1024),
+                                     ("f32", "bf16", 512), ("f32", "f32", 3584)])
+@pytest.mark.parametrize("n,skip", [(1, None), (5, [0, 1, 0, 0, 1]), (16, [0] * 16), (32, [i % 3 == 0 for i in range(32)]), (3, [1, 1, 1])])
+def test_score_and_sum_matches_oracle(cd, rd, D, n, skip):
+    sv, ver = _verifier()
+    T, beta = 37, 0.9
+    g = np.random.default_rng(D + n)
+    base = si.to_stage_dtype((1.3 * g.standard_normal((T, D)) + 0.1).astype(np.float32), rd)
+    kinds = ["honest", "scale", "sign", "zero", "noise", "tok_scale", "tok_zero"]
+    claims = [si.make_claim(kinds[i % len(kinds)], base.astype(np.float32), cd, seed=5 * i + 2) for i in range(n)]
+    metrics = ("rel_l2", "l1", "zl2", "sfr") if n != 5 else ("rel_l2",)
+    out = ver.score_and_sum(dev(np.stack(claims), cd), dev(base, rd), skip=skip, metrics=metrics, tau=TAU, reduce="global",
+                            want_token_scores=True)
+    res = ver.read_results(out["result"])
+    _compare(res, host(out["token_scores"]), claims, [base], "global", metrics)
+    keep = [c for i, c in enumerate(claims) if skip is None or not skip[i]]
+    want = np.sum([np.asarray(c, np.float64) for c in keep], axis=0) if keep else np.zeros((T, D))
+    mag = np.sum([np.abs(np.asarray(c, np.float64)) for c in keep], axis=0) if keep else np.zeros((T, D))
+    assert np.all(np.abs(host(out["sum"]) - want) <= 2e-7 * mag * max(len(keep), 1) + 1e-30)
+    # the EMA update from the sum against the definition over the same clean set
+    m0 = g.standard_normal((T, D)).astype(np.float32)
+    m = dev(m0, "f32")
+    ver.ema_from_sum(m, out["sum"], len(keep), beta)
+    flags = [0] * n if skip is None else [int(bool(x)) for x in skip]
+    np.testing.assert_allclose(host(m), so.ema_update(m0, claims, flags, beta), rtol=2e-6, atol=2e-6)
+    if not keep:
+        assert np.array_equal(host(m), m0.astype(np.float64))
+    ver.close()
+
+
+def test_score_and_sum_limits():
+    import torch
+    sv, ver = _verifier()
+    T, D = 16, 1024
+    c = torch.zeros((33, T, D), dtype=torch.bfloat16, device="cuda")
+    r = torch.zeros((T, D), dtype=torch.float32, device="cuda")
+    with pytest.raises(sv.SVError):                              # more than 32 submissions
+        ver.score_and_sum(c, r)
+    with pytest.raises(sv.SVError):                              # a row of 1.5 KB
+        ver.score_and_sum(torch.zeros((2, T, 768), dtype=torch.bfloat16, device="cuda"), torch.zeros((T, 768), dtype=torch.float32, device="cuda"))
+    ver.score_and_sum(c[:32], r)                                 # the limit itself
     ver.close()
