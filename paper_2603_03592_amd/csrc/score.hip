@@ -109,17 +109,21 @@ __global__ __launch_bounds__(256) void score_tokens_kernel(const EC* __restrict_
 }
 
 // ---------------------------------------------------------------------------------------------
-// The same statistics for several submissions against ONE shared reference whose token rows are short enough to be
-// held in registers (a row of the submission is 2, 4 or 8 KB: NU 16-byte units per lane).  A wave owns a token: it
-// loads the reference row once, forms the reference's own sums and -- for the sign-flip ratio -- one class mask per
-// element, and then streams the same row of every submission of its group past them, the next submission's loads in
-// flight while the current one is reduced.  Compared with score_tokens_kernel the reference is read once per group
-// instead of once per submission, and its share of the arithmetic is paid once: 7 vector instructions per element
-// instead of 16, which moves the all-statistics pass from the vector ALUs' bound to the memory's.
+// The same statistics for several submissions against ONE shared reference, rows of any multiple of 2 KB.  A wave
+// owns a token and takes its row in parts of NU KB (NU = 2 or 4): it loads the reference part into registers once,
+// forms the reference's own sums and -- for the sign-flip ratio -- one class mask per element, and then streams the
+// same part of every submission of its group past them, the next submission's loads in flight while the current one
+// is reduced.  Compared with score_tokens_kernel the reference is read once per group instead of once per submission,
+// and its share of the arithmetic is paid once: 7-8 vector instructions per element instead of 16, which moves the
+// all-statistics pass from the vector ALUs' bound to the memory's.
 //   sign test: sign(a) == sign(b), with sign(0) = sign(NaN) = 0, is one v_cmp_class of a against the set of classes
 //   that b's sign allows; the matches are counted on the scalar unit from the lane mask.
-// Lane c of a wave keeps the running sums of the group's submission c (a predicated add after each reduction); the
-// four waves' sums are folded per submission at the end, into the same per-(submission, tile) records as above.
+// Lane c of a wave adds up submission c's sums over the parts of a token (a predicated add after each wave
+// reduction) and closes the token -- per-token relative L2, running sums -- for all submissions at once; the four
+// waves' sums are folded per submission at the end, into the same per-(submission, tile) records as above.
+// With SUM the kernel also writes, per element, the sum over the group's submissions whose bit in `skip` is clear
+// (added in index order, fp32): the mean the EMA update needs, without another pass over the submissions.  SUM needs
+// the whole set in one group.
 constexpr int kGroupMax = 32;                 // submissions per group (<= 64: one lane each)
 
 __device__ __forceinline__ float dpp_add(float v, int ctrl_sel) {
@@ -153,132 +157,6 @@ template <> struct RawUnit<float, 4> { f32x4 v; __device__ __forceinline__ void 
 template <> struct RawUnit<float, 8> { f32x4 a, b; __device__ __forceinline__ void load(const float* p) { a = *reinterpret_cast<const f32x4*>(p); b = *reinterpret_cast<const f32x4*>(p + 4); }
                                        __device__ __forceinline__ float get(int i) const { return i < 4 ? a[i] : b[i - 4]; } };
 
-template <typename EC, typename ER, int NU, bool FULL>
-__global__ __launch_bounds__(256) void score_group_kernel(const EC* __restrict__ claims, int64_t claim_stride, const ER* __restrict__ ref,
-                                                          int64_t T, int n_claims, int G, int n_groups, int tiles_per_claim,
-                                                          float* __restrict__ token_scores, ScorePartial* __restrict__ partials) {
-  constexpr int EPU = 16 / (int)sizeof(EC);            // elements per 16-byte unit of a submission's row
-  constexpr int D = NU * 64 * EPU;
-  // ids congruent mod 8 (one XCD, one L2) get a contiguous run of token tiles; the groups of a tile follow each other
-  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int group = slot % n_groups;
-  const int tile = xcd * ((tiles_per_claim + 7) >> 3) + slot / n_groups;
-  if (tile >= tiles_per_claim) return;
-  const int c0 = group * G, nc = min(G, n_claims - c0);
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-
-  double acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};            // lane c: submission c0 + c
-  float best = -1.0f;
-  int best_t = 0, bad = 0;
-
-  for (int i = 0; i < kTPW; ++i) {
-    const int64_t t = (int64_t)tile * kScoreTokensPerWG + i * 4 + wave;
-    if (t >= T) break;                                 // uniform per wave
-    const ER* r = ref + t * D + lane * EPU;
-    float rv[NU][EPU];
-    int cls[NU][EPU];
-    float sr = 0, srr = 0;
-#pragma unroll
-    for (int m = 0; m < NU; ++m) {
-      RawUnit<ER, EPU> u;
-      u.load(r + m * 64 * EPU);
-#pragma unroll
-      for (int j = 0; j < EPU; ++j) {
-        const float b = u.get(j);
-        rv[m][j] = b;
-        srr = fmaf(b, b, srr);
-        if (FULL) {
-          sr += b;
-          // classes a may have for sign(a) == sign(b): {+denormal, +normal, +inf}, {-inf, -normal, -denormal}, {NaNs, -0, +0}
-          cls[m][j] = b > 0.0f ? 0x380 : (b < 0.0f ? 0x01C : 0x063);
-        }
-      }
-    }
-    srr = wave_sum_rows(srr);
-    if (FULL) sr = wave_sum_rows(sr);
-    const float rnorm = fmaxf(sqrtf(srr), 1e-30f);
-
-    const EC* cb = claims + (int64_t)c0 * claim_stride + t * D + lane * EPU;
-    RawUnit<EC, EPU> bufA[NU], bufB[NU];
-    auto fetch = [&](RawUnit<EC, EPU> (&buf)[NU], int c) {
-      const EC* p = cb + (int64_t)c * claim_stride;
-#pragma unroll
-      for (int m = 0; m < NU; ++m) buf[m].load(p + m * 64 * EPU);
-    };
-    auto reduce = [&](const RawUnit<EC, EPU> (&buf)[NU], int c) {
-      float sc = 0, scc = 0, sad = 0, sdd = 0;
-      int match = 0;                                    // wave-uniform
-#pragma unroll
-      for (int m = 0; m < NU; ++m)
-#pragma unroll
-        for (int j = 0; j < EPU; ++j) {
-          const float a = buf[m].get(j), d = a - rv[m][j];
-          sdd = fmaf(d, d, sdd);
-          if (FULL) {
-            sc += a; scc = fmaf(a, a, scc); sad += fabsf(d);
-            // the compare's lane mask goes straight to the scalar unit (through the generic ballot the compiler
-            // turns the predicate into a register value and compares again)
-            uint64_t lanes;
-            asm("v_cmp_class_f32_e64 %0, %1, %2" : "=s"(lanes) : "v"(a), "v"(cls[m][j]));
-            match += __builtin_popcountll(lanes);
-            asm volatile("" : "+s"(match));          // count now: otherwise all the masks stay live until the predicated adds below
-          }
-        }
-      sdd = wave_sum_rows(sdd);
-      if (FULL) { sc = wave_sum_rows(sc); scc = wave_sum_rows(scc); sad = wave_sum_rows(sad); }
-      const float rel = sqrtf(sdd) / rnorm;
-      if (lane == 0 && token_scores) token_scores[(int64_t)(c0 + c) * T + t] = rel;
-      if (lane == c) {
-        acc[0] += sc; acc[1] += sr; acc[2] += scc; acc[3] += srr;
-        acc[4] += (double)sc - (double)sr;              // sum of differences (mean of d in the z-scored L2)
-        acc[5] += sad; acc[6] += sdd;
-        if (FULL) acc[7] += (double)(D - match);
-        if (!(rel <= 3.0e38f)) bad = 1;                 // NaN or inf
-        else if (rel > best) { best = rel; best_t = (int)t; }
-      }
-    };
-    fetch(bufA, 0);
-    for (int c = 0; c < nc; c += 2) {
-      if (c + 1 < nc) fetch(bufB, c + 1);
-      reduce(bufA, c);
-      if (c + 1 < nc) {
-        if (c + 2 < nc) fetch(bufA, c + 2);
-        reduce(bufB, c + 1);
-      }
-    }
-  }
-
-  __shared__ double s_acc[4][kGroupMax][8];
-  __shared__ float s_best[4][kGroupMax];
-  __shared__ int s_bt[4][kGroupMax], s_bad[4][kGroupMax];
-  if (lane < nc) {
-#pragma unroll
-    for (int j = 0; j < 8; ++j) s_acc[wave][lane][j] = acc[j];
-    s_best[wave][lane] = best; s_bt[wave][lane] = best_t; s_bad[wave][lane] = bad;
-  }
-  __syncthreads();
-  if ((int)threadIdx.x < nc) {
-    const int c = threadIdx.x;
-    ScorePartial p;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) p.s[j] = s_acc[0][c][j] + s_acc[1][c][j] + s_acc[2][c][j] + s_acc[3][c][j];
-    float b = -1.0f; int bt = 0, bd = 0;
-    for (int w = 0; w < 4; ++w) {
-      bd |= s_bad[w][c];
-      if (s_best[w][c] > b || (s_best[w][c] == b && s_best[w][c] >= 0.0f && s_bt[w][c] < bt)) { b = s_best[w][c]; bt = s_bt[w][c]; }
-    }
-    p.max_rel = b; p.argmax = bt; p.bad = bd; p.pad = 0;
-    partials[(int64_t)(c0 + c) * tiles_per_claim + tile] = p;
-  }
-}
-
-// ---------------------------------------------------------------------------------------------
-// The same scheme for rows of any multiple of 2 KB, taken in parts of NU KB (NU = 2 or 4): the reference part sits in
-// registers while the same part of every submission of the group streams past; lane c adds up submission c's sums
-// over the parts of a token and closes the token (per-token relative L2, running sums) for all submissions at once.
-// With SUM the kernel also writes, per element, the sum over the group's submissions whose bit in `skip` is clear
-// (added in index order, fp32): the mean the EMA update needs, without another pass over the submissions.  SUM needs
-// the whole set in one group.
 template <typename EC, typename ER, int NU, bool FULL, bool SUM>
 __global__ __launch_bounds__(256) void score_parts_kernel(const EC* __restrict__ claims, int64_t claim_stride, const ER* __restrict__ ref,
                                                           int64_t T, int D, int n_claims, int G, int n_groups, int tiles_per_claim,
@@ -330,7 +208,8 @@ __global__ __launch_bounds__(256) void score_parts_kernel(const EC* __restrict__
           if (SUM) ssum[m][j] = 0.0f;
           if (FULL) {
             sr += b;
-            cls[m][j] = b > 0.0f ? 0x380 : (b < 0.0f ? 0x01C : 0x063);     // see score_group_kernel
+            // classes a may have for sign(a) == sign(b): {+denormal, +normal, +inf}, {-inf, -normal, -denormal}, {NaNs, -0, +0}
+            cls[m][j] = b > 0.0f ? 0x380 : (b < 0.0f ? 0x01C : 0x063);
           }
         }
       }
@@ -347,10 +226,12 @@ __global__ __launch_bounds__(256) void score_parts_kernel(const EC* __restrict__
             if (SUM && add) ssum[m][j] += a;
             if (FULL) {
               sc += a; scc = fmaf(a, a, scc); sad += fabsf(d);
+              // the compare's lane mask goes straight to the scalar unit (through the generic ballot the compiler
+              // turns the predicate into a register value and compares again)
               uint64_t lanes;
               asm("v_cmp_class_f32_e64 %0, %1, %2" : "=s"(lanes) : "v"(a), "v"(cls[m][j]));
               match += __builtin_popcountll(lanes);
-              asm volatile("" : "+s"(match));
+              asm volatile("" : "+s"(match));        // count now: otherwise all the masks stay live until the predicated adds
             }
           }
         sdd = wave_sum_rows(sdd);
@@ -586,10 +467,9 @@ hipError_t launch_score(const void* claims, int64_t claim_stride, int n_claims, 
     const dim3 grid((unsigned)(8 * ((tiles + 7) / 8) * nc)), block(256);
     const int64_t row_bytes = (int64_t)D * csz;
     const bool full = (mask & (SV_M_L1 | SV_M_ZL2 | SV_M_SFR)) != 0;
-    const bool whole_rows = row_bytes == 2048 || row_bytes == 4096 || row_bytes == 8192;
-    // shared reference, rows of a multiple of 2 KB other than those three, or the sum over the submissions wanted:
-    // the kernel that takes the rows in parts
-    if (ref_stride == 0 && row_bytes % 2048 == 0 && (sum_out || (nc >= 2 && !whole_rows))) {
+    // shared reference and several submissions (or their sum wanted), rows of a multiple of 2 KB: the kernel that
+    // keeps the reference in registers
+    if (ref_stride == 0 && row_bytes % 2048 == 0 && (sum_out || nc >= 2)) {
       if (sum_out && (nc != n_claims || nc * tiles > scratch_elems)) return hipErrorInvalidValue;   // one launch, one group
       int G = sum_out ? nc : 16;
       while (!sum_out && G > 4 && tiles * ((nc + G - 1) / G) < 1024) G >>= 1;
@@ -612,31 +492,6 @@ hipError_t launch_score(const void* claims, int64_t claim_stride, int n_claims, 
 #undef SV_LAUNCH_PARTS
 #undef SV_LAUNCH_PARTS3
 #undef SV_LAUNCH_PARTS5
-      hipLaunchKernelGGL(score_finalize_kernel, dim3(nc), dim3(256), 0, st, scratch, (int)tiles, T, D, mask, tau, reduce,
-                         results + c0);
-      continue;
-    }
-    // shared reference, several submissions, rows of 2, 4 or 8 KB: the kernel that keeps the whole reference row in registers
-    if (ref_stride == 0 && nc >= 2 && whole_rows) {
-      int G = 16;
-      while (G > 4 && tiles * ((nc + G - 1) / G) < 1024) G >>= 1;
-      const int n_groups = (nc + G - 1) / G;
-      const dim3 ggrid((unsigned)(8 * ((tiles + 7) / 8) * n_groups));
-#define SV_LAUNCH_GROUP4(EC, ER, NU, FULL)                                                                            \
-  hipLaunchKernelGGL((score_group_kernel<EC, ER, NU, FULL>), ggrid, block, 0, st, (const EC*)cp, claim_stride, (const ER*)rp, T, nc, G, \
-                     n_groups, (int)tiles, ts, scratch)
-#define SV_LAUNCH_GROUP(EC, ER)                                                                                       \
-  do {                                                                                                                \
-    const int nu = (int)(row_bytes / 1024);                                                                           \
-    if (full) { if (nu == 2) SV_LAUNCH_GROUP4(EC, ER, 2, true); else if (nu == 4) SV_LAUNCH_GROUP4(EC, ER, 4, true); else SV_LAUNCH_GROUP4(EC, ER, 8, true); } \
-    else { if (nu == 2) SV_LAUNCH_GROUP4(EC, ER, 2, false); else if (nu == 4) SV_LAUNCH_GROUP4(EC, ER, 4, false); else SV_LAUNCH_GROUP4(EC, ER, 8, false); } \
-  } while (0)
-      if (claim_dtype == SV_BF16 && ref_dtype == SV_BF16) SV_LAUNCH_GROUP(bf16, bf16);
-      else if (claim_dtype == SV_BF16) SV_LAUNCH_GROUP(bf16, float);
-      else if (ref_dtype == SV_BF16) SV_LAUNCH_GROUP(float, bf16);
-      else SV_LAUNCH_GROUP(float, float);
-#undef SV_LAUNCH_GROUP
-#undef SV_LAUNCH_GROUP4
       hipLaunchKernelGGL(score_finalize_kernel, dim3(nc), dim3(256), 0, st, scratch, (int)tiles, T, D, mask, tau, reduce,
                          results + c0);
       continue;
