@@ -260,8 +260,8 @@ def loop_bench(a):
     ms = (time.perf_counter() - t0) * 1e3 / a.steps
     signals = 2 * P_ * d
     # bytes one iteration moves by design: every signal is read by the score pass and by the projection; per stage call
-    # the EMA is read by both, the sum over the signals is written and read back, and the EMA is read and written
-    alg = signals * T * D * 2 * 2 + 2 * P_ * T * D * 4 * 6
+    # the EMA is read by the score pass, the sum over the signals is written and read back, and the EMA is read and written
+    alg = signals * T * D * 2 * 2 + 2 * P_ * T * D * 4 * 5
     print(json.dumps({
         "metric": "verified tokens/sec (EMA-reference verifier loop, 4 stages x 16 workers, fwd+bwd signals)",
         "value": signals * T / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": max(a.warmup, 12),

@@ -239,6 +239,25 @@ sv_status sv_sliced_wasserstein(sv_ctx *ctx, const void *claims, int64_t claim_s
                                 int64_t T, int32_t D, const void *directions, int32_t n_dirs, float tau,
                                 float *sw_out, sv_result *results_dev, void *stream);
 
+/* The sliced Wasserstein statistic against a reference that is known only through its projections, for a caller
+ * that keeps the EMA of Eq. momentum_def: the projection is linear, so the projections of the EMA follow from those
+ * of the submissions and the reference itself never has to be projected.
+ *   sv_sw_row_len(T)            row length Tpad >= T of the projection arrays below (a power of two)
+ *   sv_sw_against_projection    ref_proj [n_dirs, Tpad] float (device, unsorted <u_l, ref_t>; entries t >= T are
+ *                               ignored) stands for the reference; claim_proj_out [n_claims, n_dirs, Tpad] float
+ *                               (device) receives the submissions' unsorted projections; otherwise as
+ *                               sv_sliced_wasserstein.  Needs Tpad <= 16384 and n_claims <= 256 (SV_EUNSUPPORTED beyond).
+ *   sv_sw_projection_ema        ref_proj <- beta ref_proj + (1-beta) mean_{i: skip_host[i]==0} claim_proj_i over the
+ *                               T samples (skip_host: n_claims bytes in HOST memory, NULL = none; nobody left:
+ *                               unchanged); n_claims <= 32.                                                  */
+int64_t sv_sw_row_len(int64_t T);
+sv_status sv_sw_against_projection(sv_ctx *ctx, const void *claims, int64_t claim_stride, int32_t n_claims,
+                                   int32_t claim_dtype, int64_t T, int32_t D, const void *directions, int32_t n_dirs,
+                                   const float *ref_proj, float *claim_proj_out, float tau, float *sw_out,
+                                   sv_result *results_dev, void *stream);
+sv_status sv_sw_projection_ema(sv_ctx *ctx, float *ref_proj, const float *claim_proj, int32_t n_claims,
+                               const uint8_t *skip_host, int64_t T, int32_t n_dirs, float beta, void *stream);
+
 /* ---- decision policy (host side: plain double arithmetic on the scalar statistics the kernels emit;
  *      every pointer below is a HOST pointer and no call touches the GPU) -------------------------
  * Tukey fences around the median of a history window (Eq. tukey_fences) with the multiplier k
@@ -307,7 +326,11 @@ sv_status sv_replace_with_ema(sv_ctx *ctx, void *signals, int64_t stride, int32_
  * signals: device, [n_workers, T, D] contiguous; tainted_out: HOST, n_workers bytes; gamma_out: HOST,
  * nullable, [n_workers, n_metrics] doubles.  `directions` (device, bf16 [n_dirs, D]) must stay valid
  * while the object lives; SV_M_SW needs a context created with SV_FLAG_SLICED_W and max_tokens >= T.
- * The context must outlive the object; calls on one object must not overlap.                        */
+ * The context must outlive the object; calls on one object must not overlap.
+ * Device memory the object holds: two EMAs [T, D] float per stage, and -- with at most 32 workers -- one more
+ * [T, D] float (the score pass leaves the sum over the signals there: sv_score_and_sum) and, with SV_M_SW and
+ * sv_sw_row_len(T) <= 16384, the projections of the EMAs and of the current signals
+ * ((2 n_stages + n_workers) [n_dirs, sv_sw_row_len(T)] floats: sv_sw_against_projection).             */
 typedef struct {
   int32_t n_stages, n_workers;
   int64_t T;

@@ -98,6 +98,12 @@ def _load():
     L.sv_score_and_sum.argtypes = [vp, vp, i64, i32, vp, i32, i32, i64, i32, u32, C.POINTER(f32), i32, vp, vp, C.c_char_p, vp, vp]
     L.sv_ema_from_sum.restype = C.c_int
     L.sv_ema_from_sum.argtypes = [vp, vp, vp, i32, i64, i32, f32, vp]
+    L.sv_sw_row_len.restype = i64
+    L.sv_sw_row_len.argtypes = [i64]
+    L.sv_sw_against_projection.restype = C.c_int
+    L.sv_sw_against_projection.argtypes = [vp, vp, i64, i32, i32, i64, i32, vp, i32, vp, vp, f32, vp, vp, vp]
+    L.sv_sw_projection_ema.restype = C.c_int
+    L.sv_sw_projection_ema.argtypes = [vp, vp, vp, i32, C.c_char_p, i64, i32, f32, vp]
     L.sv_ema_update.restype = C.c_int
     L.sv_ema_update.argtypes = [vp, vp, vp, i64, i32, i32, vp, i64, i32, f32, vp]
     L.sv_profile_enable.restype = C.c_int
@@ -450,6 +456,29 @@ class Verifier:
                                               T, D, _ptr(directions), directions.shape[0], float(tau), _ptr(sw), _ptr(results),
                                               self._stream()))
         return sw
+
+    def sw_against_projection(self, claims, ref_proj, directions, tau: float, results=None):
+        """claims [n, T, D]; ref_proj [L, Tpad] float32: unsorted projections of the reference; directions bf16 [L, D].
+        Returns (sw [n] float32, claim_proj [n, L, Tpad] float32), both on the device."""
+        torch = self.torch
+        n, D = claims.shape[0], claims.shape[-1]
+        T = claims[0].numel() // D
+        L, Tpad = directions.shape[0], lib.sv_sw_row_len(T)
+        assert claims.is_contiguous() and ref_proj.is_contiguous() and directions.is_contiguous()
+        assert directions.dtype == torch.bfloat16 and ref_proj.dtype == torch.float32 and tuple(ref_proj.shape) == (L, Tpad)
+        sw = torch.empty((n,), dtype=torch.float32, device=claims.device)
+        proj = torch.empty((n, L, Tpad), dtype=torch.float32, device=claims.device)
+        self._check(lib.sv_sw_against_projection(self._ctx, _ptr(claims), T * D, n, _dt(claims), T, D, _ptr(directions), L, _ptr(ref_proj),
+                                                 _ptr(proj), float(tau), _ptr(sw), _ptr(results), self._stream()))
+        return sw, proj
+
+    def sw_projection_ema(self, ref_proj, claim_proj, T: int, skip, beta: float):
+        """ref_proj [L, Tpad] updated in place from claim_proj [n, L, Tpad]; skip: host sequence of n flags or None."""
+        n, L = claim_proj.shape[0], claim_proj.shape[1]
+        skip_b = None if skip is None else bytes(bytearray(int(bool(x)) for x in skip))
+        assert ref_proj.is_contiguous() and claim_proj.is_contiguous() and (skip_b is None or len(skip_b) == n)
+        self._check(lib.sv_sw_projection_ema(self._ctx, _ptr(ref_proj), _ptr(claim_proj), n, skip_b, int(T), L, float(beta), self._stream()))
+        return ref_proj
 
     def replace_with_ema(self, signals, mask_dev, m):
         """signals [n, T, D] updated in place: signal i becomes m (rounded) where mask_dev[i] != 0."""

@@ -858,6 +858,54 @@ sv_status sv_sliced_wasserstein(sv_ctx* c, const void* claims, int64_t claim_str
   return SV_OK;
 }
 
+int64_t sv_sw_row_len(int64_t T) { return T < 0 ? 0 : sw_padded_len(T); }
+
+sv_status sv_sw_against_projection(sv_ctx* c, const void* claims, int64_t claim_stride, int32_t n_claims, int32_t claim_dtype, int64_t T,
+                                   int32_t D, const void* directions, int32_t L, const float* ref_proj, float* claim_proj_out, float tau,
+                                   float* sw_out, sv_result* results_dev, void* stream) {
+  if (!c) return SV_EINVAL;
+  if (n_claims < 0 || T < 0 || D < 1 || L < 1) { set_err(c, "negative size"); return SV_EINVAL; }
+  if (!(c->flags & SV_FLAG_SLICED_W)) { set_err(c, "context was created without SV_FLAG_SLICED_W"); return SV_EINVAL; }
+  if (n_claims == 0 || T == 0) return SV_OK;
+  if (!claims || !directions || !ref_proj || !claim_proj_out) { set_err(c, "claims, directions, ref_proj and claim_proj_out must be non-NULL"); return SV_EINVAL; }
+  if (claim_dtype != SV_F32 && claim_dtype != SV_BF16) { set_err(c, "unknown dtype"); return SV_EINVAL; }
+  if (claim_stride < 0) { set_err(c, "negative stride"); return SV_EINVAL; }
+  if (L % 32 || L > kSwMaxDirs) { set_err(c, "n_dirs must be a multiple of 32, at most %d", kSwMaxDirs); return SV_EUNSUPPORTED; }
+  if (D % 64) { set_err(c, "D must be a multiple of 64"); return SV_EUNSUPPORTED; }
+  if (n_claims > 256) { set_err(c, "at most 256 submissions per call"); return SV_EUNSUPPORTED; }       // one launch: grid rows
+  if (T > c->max_tokens) { set_err(c, "T=%lld exceeds the context's max_tokens %lld", (long long)T, (long long)c->max_tokens); return SV_EUNSUPPORTED; }
+  const int64_t Tpad = sw_padded_len(T);
+  if (Tpad > kSwSortChunkMax) { set_err(c, "rows longer than %lld are sorted in place: use sv_sliced_wasserstein", (long long)kSwSortChunkMax); return SV_EUNSUPPORTED; }
+  hipStream_t st = (hipStream_t)stream;
+  SV_HIP(c, launch_sw_copy_pad(c->sw_proj, ref_proj, L, T, Tpad, st));
+  SV_OP(c, SV_OP_SW_SORT, 0, st, launch_sw_sort(c->sw_proj, L, T, Tpad, nullptr, 0, L, nullptr, 0, st));
+  SV_OP(c, SV_OP_SW_PROJECT, 2.0 * (double)T * D * L * n_claims, st,
+        launch_sw_project(claims, claim_stride, n_claims, claim_dtype, directions, L, D, T, Tpad, claim_proj_out, st));
+  // rows of one LDS chunk: the last sort pass adds up |a - b| against the reference and leaves the projections as they are
+  SV_OP(c, SV_OP_SW_SORT, 0, st, launch_sw_sort(claim_proj_out, n_claims * L, T, Tpad, c->sw_proj, 1, L, c->sw_w1, 0, st));
+  SV_HIP(c, launch_sw_finalize(c->sw_w1, n_claims, L, T, tau, sw_out, results_dev, st));
+  return SV_OK;
+}
+
+sv_status sv_sw_projection_ema(sv_ctx* c, float* ref_proj, const float* claim_proj, int32_t n_claims, const uint8_t* skip_host, int64_t T,
+                               int32_t L, float beta, void* stream) {
+  if (!c) return SV_EINVAL;
+  if (n_claims < 0 || T < 0 || L < 1) { set_err(c, "negative size"); return SV_EINVAL; }
+  if (n_claims == 0 || T == 0) return SV_OK;
+  if (!ref_proj || !claim_proj) { set_err(c, "ref_proj and claim_proj must be non-NULL"); return SV_EINVAL; }
+  if (!(beta >= 0.0f && beta < 1.0f)) { set_err(c, "beta must be in [0, 1)"); return SV_EINVAL; }
+  if (n_claims > 32) { set_err(c, "at most 32 submissions"); return SV_EUNSUPPORTED; }
+  uint32_t skip = 0;
+  int n = 0;
+  for (int i = 0; i < n_claims; ++i) {
+    if (skip_host && skip_host[i]) skip |= 1u << i;
+    else ++n;
+  }
+  if (n == 0) return SV_OK;
+  SV_HIP(c, launch_sw_proj_ema(ref_proj, claim_proj, n_claims, skip, L, T, sw_padded_len(T), beta, (1.0f - beta) / (float)n, (hipStream_t)stream));
+  return SV_OK;
+}
+
 sv_status sv_ema_update(sv_ctx* c, float* m, const void* claims, int64_t claim_stride, int32_t n_claims, int32_t claim_dtype,
                         const uint8_t* flags_dev, int64_t T, int32_t D, float beta, void* stream) {
   if (!c) return SV_EINVAL;

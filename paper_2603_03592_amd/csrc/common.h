@@ -127,6 +127,10 @@ hipError_t launch_sw_project_with_ref(const void* X, int64_t stride, int count, 
 // Sort n_seg rows; with ref != nullptr also w1[first_seg + s] = sum_t |row_s[t] - ref_row[t]| (ref rows already sorted).
 hipError_t launch_sw_sort(float* P, int n_seg, int64_t T, int64_t Tpad, const float* ref, int ref_shared, int L, float* w1,
                           int first_seg, hipStream_t st);
+hipError_t launch_sw_copy_pad(float* dst, const float* src, int L, int64_t T, int64_t Tpad, hipStream_t st);
+hipError_t launch_sw_proj_ema(float* pm, const float* P, int n, uint32_t skip, int L, int64_t T, int64_t Tpad, float beta, float w,
+                              hipStream_t st);
+constexpr int64_t kSwSortChunkMax = 16384;   // longest row one workgroup sorts in LDS (longer rows are sorted in place in global memory)
 hipError_t launch_sw_finalize(const float* w1, int n_claims, int L, int64_t T, float tau, float* sw_out, sv_result* results,
                               hipStream_t st);
 

@@ -28,6 +28,9 @@ struct sv_sentinel {
   float* sw_dev = nullptr;
   uint8_t* mask_dev = nullptr;             // two rows of d bytes: replacement mask, EMA exclusion mask
   float* sum_dev = nullptr;                // [T, D]: sum over the signals not excluded beforehand, written by the score pass
+  // sliced Wasserstein against the EMA without projecting the EMA: its projections follow from the signals' (linearity)
+  std::vector<float*> pm[2];               // [kind][stage] device fp32 [n_dirs, Tpad]: <u_l, m_t>, kept up to date with m
+  float* cproj = nullptr;                  // [d, n_dirs, Tpad]: the current signals' projections
   // pinned staging
   sv_result* res_host = nullptr;
   float* sw_host = nullptr;
@@ -59,7 +62,7 @@ void set_err(sv_sentinel* s, const char* fmt, ...) {
 // `skip` [d]: the signals known to be excluded from the EMA before they are scored.  Where the score pass can do it,
 // it also leaves the sum over the others in sum_dev (*summed = true), which saves the EMA update its own pass over the
 // signals whenever the verdicts exclude nobody else.
-sv_status gamma_of(sv_sentinel* s, const void* signals, int dtype, const float* m, const uint8_t* skip, bool* summed,
+sv_status gamma_of(sv_sentinel* s, const void* signals, int dtype, const float* m, const float* pm, const uint8_t* skip, bool* summed,
                    std::vector<double>& gamma, hipStream_t st) {
   const sv_sentinel_cfg& c = s->cfg;
   const int d = c.n_workers;
@@ -76,8 +79,12 @@ sv_status gamma_of(sv_sentinel* s, const void* signals, int dtype, const float* 
   else if (sum_st != SV_OK) { set_err(s, "sv_score_and_sum: %s", sv_last_error(s->ctx)); return sum_st; }
   SN_HIP(s, hipMemcpyAsync(s->res_host, s->res_dev, sizeof(sv_result) * d, hipMemcpyDeviceToHost, st));
   if (c.metric_mask & SV_M_SW) {
-    SN_SV(s, sv_sliced_wasserstein(s->ctx, signals, stride, d, m, 0, dtype, SV_F32, c.T, c.D, c.directions, c.n_dirs, inf, s->sw_dev,
-                                   nullptr, st));
+    if (pm)
+      SN_SV(s, sv_sw_against_projection(s->ctx, signals, stride, d, dtype, c.T, c.D, c.directions, c.n_dirs, pm, s->cproj, inf, s->sw_dev,
+                                        nullptr, st));
+    else
+      SN_SV(s, sv_sliced_wasserstein(s->ctx, signals, stride, d, m, 0, dtype, SV_F32, c.T, c.D, c.directions, c.n_dirs, inf, s->sw_dev,
+                                     nullptr, st));
     SN_HIP(s, hipMemcpyAsync(s->sw_host, s->sw_dev, sizeof(float) * d, hipMemcpyDeviceToHost, st));
   }
   SN_HIP(s, hipStreamSynchronize(st));
@@ -96,9 +103,10 @@ sv_status gamma_of(sv_sentinel* s, const void* signals, int dtype, const float* 
 // Eq. momentum_def over the signals with excl[r] == 0.  If the score pass has left the sum over the signals with
 // skip[r] == 0 and the verdicts excluded nobody beyond those, the update is one pass over m and that sum; otherwise
 // the update reads the signals itself.
-sv_status update_ema(sv_sentinel* s, float* m, const void* signals, int dtype, const uint8_t* excl, const uint8_t* skip, bool summed,
-                     float beta, hipStream_t hs, bool mask_uploaded = false) {
+sv_status update_ema(sv_sentinel* s, float* m, float* pm, const void* signals, int dtype, const uint8_t* excl, const uint8_t* skip,
+                     bool summed, float beta, hipStream_t hs, bool mask_uploaded = false) {
   const int d = s->cfg.n_workers;
+  if (pm) SN_SV(s, sv_sw_projection_ema(s->ctx, pm, s->cproj, d, excl, s->cfg.T, s->cfg.n_dirs, beta, hs));
   bool same = summed;
   int n = 0;
   for (int r = 0; r < d; ++r) { same = same && (excl[r] != 0) == (skip[r] != 0); n += excl[r] == 0; }
@@ -152,6 +160,22 @@ sv_status sv_sentinel_create(sv_ctx* ctx, const sv_sentinel_cfg* cfg, sv_sentine
   if (st == SV_OK && e == hipSuccess) e = hipMalloc(&s->res_dev, sizeof(sv_result) * d);
   if (st == SV_OK && e == hipSuccess) e = hipMalloc(&s->sw_dev, sizeof(float) * d);
   if (st == SV_OK && e == hipSuccess) e = hipMalloc(&s->mask_dev, 2 * (size_t)d);
+  if (st == SV_OK && e == hipSuccess && (cfg->metric_mask & SV_M_SW) && d <= 32 && cfg->n_dirs % 32 == 0 && cfg->D % 64 == 0 &&
+      sv_sw_row_len(cfg->T) <= 16384) {               // optional: without them the EMA itself is projected in every check
+    const size_t p_bytes = (size_t)cfg->n_dirs * (size_t)sv_sw_row_len(cfg->T) * sizeof(float);
+    bool ok = hipMalloc(&s->cproj, p_bytes * d) == hipSuccess;
+    for (int kind = 0; kind < 2 && ok; ++kind)
+      for (int i = 0; i < cfg->n_stages && ok; ++i) {
+        float* p = nullptr;
+        ok = hipMalloc(&p, p_bytes) == hipSuccess;
+        if (ok) { s->pm[kind].push_back(p); ok = hipMemset(p, 0, p_bytes) == hipSuccess; }     // projections of m_0 = 0
+      }
+    if (!ok) {
+      (void)hipGetLastError();
+      for (int kind = 0; kind < 2; ++kind) { for (float* p : s->pm[kind]) (void)hipFree(p); s->pm[kind].clear(); }
+      if (s->cproj) { (void)hipFree(s->cproj); s->cproj = nullptr; }
+    }
+  }
   if (st == SV_OK && e == hipSuccess && d <= 32) {  // optional: without it the EMA update reads the signals itself
     if (hipMalloc(&s->sum_dev, m_bytes) != hipSuccess) { s->sum_dev = nullptr; (void)hipGetLastError(); }
   }
@@ -177,6 +201,9 @@ void sv_sentinel_destroy(sv_sentinel* s) {
   if (s->sw_dev) (void)hipFree(s->sw_dev);
   if (s->mask_dev) (void)hipFree(s->mask_dev);
   if (s->sum_dev) (void)hipFree(s->sum_dev);
+  for (int kind = 0; kind < 2; ++kind)
+    for (float* p : s->pm[kind]) (void)hipFree(p);
+  if (s->cproj) (void)hipFree(s->cproj);
   if (s->res_host) (void)hipHostFree(s->res_host);
   if (s->sw_host) (void)hipHostFree(s->sw_host);
   if (s->mask_host) (void)hipHostFree(s->mask_host);
@@ -209,7 +236,8 @@ sv_status sv_sentinel_forward(sv_sentinel* s, int32_t stage, const void* h, int3
     for (int r = 0; r < d; ++r) skip[r] = banned[r] | upstream[r];
   }
   bool summed = false;
-  st = gamma_of(s, h, dtype, s->m[0][stage], skip.data(), &summed, gamma, hs);
+  float* pm = s->pm[0].empty() ? nullptr : s->pm[0][stage];
+  st = gamma_of(s, h, dtype, s->m[0][stage], pm, skip.data(), &summed, gamma, hs);
   if (st != SV_OK) return st;
   if (gamma_out) memcpy(gamma_out, gamma.data(), gamma.size() * sizeof(double));
   uint8_t* excl = s->mask_host + d;
@@ -224,7 +252,7 @@ sv_status sv_sentinel_forward(sv_sentinel* s, int32_t stage, const void* h, int3
       excl[r] = banned[r] | upstream[r] | tainted_out[r];
     }
   }
-  return update_ema(s, s->m[0][stage], h, dtype, excl, skip.data(), summed, s->cfg.beta_h, hs);
+  return update_ema(s, s->m[0][stage], pm, h, dtype, excl, skip.data(), summed, s->cfg.beta_h, hs);
 }
 
 sv_status sv_sentinel_backward(sv_sentinel* s, int32_t stage, void* g, int32_t dtype, uint8_t* tainted_out, double* gamma_out, void* stream) {
@@ -243,7 +271,8 @@ sv_status sv_sentinel_backward(sv_sentinel* s, int32_t stage, void* g, int32_t d
     for (int r = 0; r < d; ++r) skip[r] = banned[r] | s->tainted[(size_t)stage * d + r];
   }
   bool summed = false;
-  st = gamma_of(s, g, dtype, s->m[1][stage], skip.data(), &summed, gamma, hs);
+  float* pm = s->pm[1].empty() ? nullptr : s->pm[1][stage];
+  st = gamma_of(s, g, dtype, s->m[1][stage], pm, skip.data(), &summed, gamma, hs);
   if (st != SV_OK) return st;
   if (gamma_out) memcpy(gamma_out, gamma.data(), gamma.size() * sizeof(double));
   uint8_t* repl = s->mask_host;
@@ -266,7 +295,7 @@ sv_status sv_sentinel_backward(sv_sentinel* s, int32_t stage, void* g, int32_t d
   for (int r = 0; r < d; ++r) any_repl |= repl[r] != 0;
   if (any_repl) SN_SV(s, sv_replace_with_ema(s->ctx, g, s->cfg.T * s->cfg.D, d, dtype, s->mask_dev, s->m[1][stage], s->cfg.T, s->cfg.D, hs));
   // (the sum the score pass left was taken before the replacement, over signals that are not replaced)
-  return update_ema(s, s->m[1][stage], g, dtype, excl, skip.data(), summed, s->cfg.beta_g, hs, /*mask_uploaded=*/true);
+  return update_ema(s, s->m[1][stage], pm, g, dtype, excl, skip.data(), summed, s->cfg.beta_g, hs, /*mask_uploaded=*/true);
 }
 
 sv_status sv_sentinel_state(const sv_sentinel* s, int32_t stage, int32_t kind, const float** ema_dev, int32_t* violations, uint8_t* banned,

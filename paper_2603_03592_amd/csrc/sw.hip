@@ -13,7 +13,7 @@
 namespace sv {
 namespace {
 
-constexpr int kSortChunkMax = 16384;   // floats sorted in LDS by one workgroup (64 KB)
+constexpr int kSortChunkMax = (int)kSwSortChunkMax;   // floats sorted in LDS by one workgroup (64 KB)
 
 // ---------------------------------------------------------------------------------------------
 // Projection.  A workgroup of 4 waves owns 256 tokens (64 per wave, two blocks of 32) and all
@@ -389,6 +389,28 @@ __global__ void sw_finalize_kernel(const float* __restrict__ w1, int n_claims, i
   }
 }
 
+// A reference that is only known through its projections (kept up to date by sw_proj_ema_kernel): copy the L rows
+// into the slot the sort works on, with the padding behind the T samples set to +inf.
+__global__ __launch_bounds__(256) void sw_copy_pad_kernel(float* __restrict__ dst, const float* __restrict__ src, int64_t T, int64_t Tpad) {
+  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (t >= Tpad) return;
+  const int64_t i = (int64_t)blockIdx.y * Tpad + t;
+  dst[i] = t < T ? src[i] : __builtin_huge_valf();
+}
+
+// The projection is linear, so the projections of m <- beta m + (1 - beta) mean_clean(x) are the same combination of
+// the projections: pm <- beta pm + w sum_{c not skipped} P_c (index order, fp32), per direction and token.
+__global__ __launch_bounds__(256) void sw_proj_ema_kernel(float* __restrict__ pm, const float* __restrict__ P, int n, uint32_t skip,
+                                                          int64_t slot, int64_t T, int64_t Tpad, float beta, float w) {
+  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (t >= T) return;
+  const int64_t i = (int64_t)blockIdx.y * Tpad + t;
+  float acc = 0.0f;
+  for (int c = 0; c < n; ++c)
+    if (((skip >> c) & 1u) == 0) acc += P[(int64_t)c * slot + i];
+  pm[i] = beta * pm[i] + w * acc;
+}
+
 template <typename E, typename E2, int LB>
 hipError_t project_launch(const void* X, int64_t stride, int count, const void* X2, int n2, const void* U, int D, int64_t T, int64_t Tpad,
                           float* P, float* P2, hipStream_t st) {
@@ -459,6 +481,17 @@ hipError_t launch_sw_sort(float* P, int n_seg, int64_t T, int64_t Tpad, const fl
     sw_sort_chunk_kernel<<<grid, nt, lds, st>>>(P, Tpad, ch, k, k, nullptr, 0, L, T, nullptr, 0);
   }
   if (ref) sw_w1_kernel<<<n_seg, 256, 0, st>>>(P, ref, ref_shared, L, T, Tpad, w1, first_seg);
+  return hipGetLastError();
+}
+
+hipError_t launch_sw_copy_pad(float* dst, const float* src, int L, int64_t T, int64_t Tpad, hipStream_t st) {
+  sw_copy_pad_kernel<<<dim3((unsigned)((Tpad + 255) / 256), (unsigned)L), 256, 0, st>>>(dst, src, T, Tpad);
+  return hipGetLastError();
+}
+
+hipError_t launch_sw_proj_ema(float* pm, const float* P, int n, uint32_t skip, int L, int64_t T, int64_t Tpad, float beta, float w,
+                              hipStream_t st) {
+  sw_proj_ema_kernel<<<dim3((unsigned)((T + 255) / 256), (unsigned)L), 256, 0, st>>>(pm, P, n, skip, (int64_t)L * Tpad, T, Tpad, beta, w);
   return hipGetLastError();
 }
 

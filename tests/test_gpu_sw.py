@@ -130,3 +130,39 @@ def test_sw_non_finite_submission_is_flagged_and_limits():
     with pytest.raises(sv.SVError):
         plain.sliced_wasserstein(cl, dev(r, "bf16"), u, 1.0)                      # context without the scratch
     plain.close()
+
+
+def test_sw_against_projection_and_projection_ema():
+    """The statistic against a reference known only through its projections equals the statistic against the reference,
+    and the projections of the EMA follow from those of the submissions (linearity of the projection)."""
+    import torch
+    sv, ver = _ver(1024)
+    T, D, L, beta = 700, 256, 64, 0.8
+    u = si.make_directions(D, L, seed=5)
+    g = np.random.default_rng(5)
+    m = (0.7 * g.standard_normal((T, D))).astype(np.float32)
+    claims = [si.make_claim(k, m, "bf16", seed=i) for i, k in enumerate(KINDS)]
+    Tpad = sv.lib.sv_sw_row_len(T)
+    assert Tpad == 1024
+    uq = np.asarray(si.to_stage_dtype(u, "bf16"), np.float64)
+    pm = np.zeros((L, Tpad), np.float32)
+    pm[:, :T] = (m.astype(np.float64) @ uq.T).T
+    pm[:, T:] = -123.0                                  # padding of the caller's array is ignored
+    pm_dev = dev(pm, "f32")
+    cl = torch.stack([dev(c, "bf16") for c in claims])
+    sw, proj = ver.sw_against_projection(cl, pm_dev, dev(u, "bf16"), 1.0)
+    _check(host(sw), claims, [m], u)
+    direct = ver.sliced_wasserstein(cl, dev(m, "f32"), dev(u, "bf16"), 1.0)
+    np.testing.assert_allclose(host(sw), host(direct), rtol=1e-4, atol=1e-6)
+    want_p = np.stack([(np.asarray(c, np.float64) @ uq.T).T for c in claims])
+    np.testing.assert_allclose(host(proj)[:, :, :T], want_p, rtol=1e-5, atol=1e-5)
+    # EMA over the submissions 0, 2, 3 (1, 4, 5 skipped): projections of the new EMA
+    skip = [0, 1, 0, 0, 1, 1]
+    ver.sw_projection_ema(pm_dev, proj, T, skip, beta)
+    m_new = beta * m.astype(np.float64) + (1 - beta) * np.mean([np.asarray(c, np.float64) for c, k in zip(claims, skip) if not k], axis=0)
+    np.testing.assert_allclose(host(pm_dev)[:, :T], (m_new @ uq.T).T, rtol=1e-5, atol=1e-5)
+    # nobody left: unchanged
+    before = host(pm_dev).copy()
+    ver.sw_projection_ema(pm_dev, proj, T, [1] * 6, beta)
+    assert np.array_equal(host(pm_dev), before)
+    ver.close()
