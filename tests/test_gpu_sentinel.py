@@ -15,14 +15,28 @@ from test_oracle_sentinel import D, DW, P, POLICY, T, WARM, _signals
 METRICS = ("rel_l2", "l1", "zl2", "sfr", "sw")
 
 
-def _pair(dtype):
+def _pair(dtype, Dv=D):
     import torch
     import paper_2603_03592_amd as sv
-    u = si.make_directions(D, 32, 0)
+    u = si.make_directions(Dv, 32, 0)
     ver = sv.Verifier(si.TINY.desc, T, 64, sliced_w=True)
-    lib = sv.Sentinel(ver, P, DW, T, D, METRICS, dev(u, "bf16"), 0.9, 0.8, POLICY, POLICY)
-    ref = sn.SentinelStream(P, DW, (T, D), METRICS, u, 0.9, 0.8, POLICY, POLICY)
+    lib = sv.Sentinel(ver, P, DW, T, Dv, METRICS, dev(u, "bf16"), 0.9, 0.8, POLICY, POLICY)
+    ref = sn.SentinelStream(P, DW, (T, Dv), METRICS, u, 0.9, 0.8, POLICY, POLICY)
     return torch, ver, lib, ref
+
+
+def _sig(kind, s, t, attack, Dv):
+    """_signals of the oracle's own test at another feature width."""
+    if Dv == D:
+        return _signals(kind, s, t, attack)
+    out = [si.stream_signal(kind, s, r, t, T, Dv, "f32") for r in range(DW)]
+    if attack is not None:
+        a_s, a_r, a_kind = attack
+        if s == a_s:
+            out[a_r] = si.make_claim(a_kind, out[a_r], "f32", seed=t)
+        elif kind == "h" and s > a_s:
+            out[a_r] = si.make_claim("noise", out[a_r] * 1.2, "f32", seed=t)
+    return out
 
 
 def _gamma_close(got, want):
@@ -30,16 +44,16 @@ def _gamma_close(got, want):
     np.testing.assert_allclose(got, want, rtol=2e-4, atol=1e-7)
 
 
-def _iteration(torch, lib, ref, t, warm, dtype, attack_h=None, attack_g=None):
+def _iteration(torch, lib, ref, t, warm, dtype, attack_h=None, attack_g=None, Dv=D):
     lib.begin_iteration(warm); ref.begin_iteration(warm)
     for s in range(P):
-        sig = [si.to_stage_dtype(x, dtype) for x in _signals("h", s, t, attack_h)]
+        sig = [si.to_stage_dtype(x, dtype) for x in _sig("h", s, t, attack_h, Dv)]
         want, wg = ref.forward(s, sig)
         got, gg = lib.forward(s, torch.stack([dev(x, dtype) for x in sig]))
         assert got == want, (t, "h", s, got, want)
         _gamma_close(gg, wg)
     for s in reversed(range(P)):
-        sig = [si.to_stage_dtype(x, dtype) for x in _signals("g", s, t, attack_g)]
+        sig = [si.to_stage_dtype(x, dtype) for x in _sig("g", s, t, attack_g, Dv)]
         m_before = lib.ema(s, "g")
         want, wg, wout = ref.backward(s, sig)
         g_dev = torch.stack([dev(x, dtype) for x in sig])
@@ -83,6 +97,32 @@ def test_verifier_loop_matches_oracle(dtype):
     _iteration(torch, lib, ref, t, False, dtype, attack_h=(0, 5, "zero"), attack_g=(0, 1, "sign")); t += 1
     _state_close(lib, ref)
     assert sum(ref.pol["g"][1].v) > 0 and sum(ref.pol["h"][0].v) > 0
+    lib.close(); ver.close()
+
+
+@pytest.mark.parametrize("dtype,Dv", [("bf16", 1024), ("f32", 512)])
+def test_verifier_loop_with_the_sum_from_the_score_pass(dtype, Dv):
+    """Rows of 2 KB: the loop takes the statistics and the sum over the signals in one pass (sv_score_and_sum) and
+    finishes the EMA from that sum whenever the verdicts exclude nobody beyond the workers known beforehand; an
+    iteration with a new flag falls back to the update that reads the signals.  Same stream, same decisions, same EMAs."""
+    torch, ver, lib, ref = _pair(dtype, Dv)
+    import paper_2603_03592_amd as sv
+    x = torch.zeros((DW, T, Dv), dtype=torch.bfloat16 if dtype == "bf16" else torch.float32, device="cuda")
+    ver.score_and_sum(x, torch.zeros((T, Dv), dtype=torch.float32, device="cuda"))       # the shape is one the summing pass takes
+    for t in range(WARM):
+        _iteration(torch, lib, ref, t, True, dtype, Dv=Dv)
+    _state_close(lib, ref)
+    t = WARM
+    for _ in range(2):                                   # honest: the sum covers everybody
+        _iteration(torch, lib, ref, t, False, dtype, Dv=Dv); t += 1
+    for _ in range(6):                                   # new flags (fallback), then a banned worker skipped beforehand
+        _iteration(torch, lib, ref, t, False, dtype, attack_h=(1, 2, "sign"), Dv=Dv); t += 1
+    assert ref.pol["h"][1].banned[2] and lib.state(1, "h")["banned"][2]
+    for _ in range(2):                                   # the ban stands: sums without that worker
+        _iteration(torch, lib, ref, t, False, dtype, Dv=Dv); t += 1
+    _iteration(torch, lib, ref, t, False, dtype, attack_g=(1, 4, "scale"), Dv=Dv); t += 1
+    _iteration(torch, lib, ref, t, False, dtype, attack_h=(0, 5, "zero"), attack_g=(0, 1, "sign"), Dv=Dv); t += 1
+    _state_close(lib, ref)
     lib.close(); ver.close()
 
 
