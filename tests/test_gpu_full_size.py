@@ -9,6 +9,7 @@ submissions from the oracle's output for those:
   Medium : 1 micro-batch, forward + backward; 10 gradient submissions, 2 corrupted (zeroed / noise)
   Large  : 1 micro-batch; 32 submissions, 8 corrupted on 1 % of the tokens only
   Sweep  : the S=512, B=1 point, forward + backward
+  Loop   : one stage call of the verifier loop (16 workers x [8192, 4096]): statistics + sum, EMA, projections
 """
 import numpy as np
 import pytest
@@ -178,4 +179,61 @@ def test_large_shape_sliced_wasserstein_32_submissions():
         assert abs(sw[i] - want) <= 1e-3 * want + 1e-5 * scale, (i, kinds[i], sw[i], want)
         worst = max(worst, abs(sw[i] - want) / max(want, 1e-30))
     print(f"large-shape SW: worst relative difference {worst:.2e}; honest {sw[0]:.3e}, scaled {sw[5]:.3e}")
+    ver.close()
+
+
+def test_loop_shape_stage_call_16_workers():
+    """One stage call of the verifier loop at the shape bench.py --loop-bench times (16 workers x [8192, 4096] bf16
+    against an fp32 EMA, 64 directions): the statistics and the sum from one pass, the EMA from that sum, the sliced
+    Wasserstein statistic against the EMA's projections and their update -- sampled submissions against the oracle,
+    the sum and both updates element by element."""
+    import torch
+    import paper_2603_03592_amd as sv
+    from oracle import sentinel_oracle as sn
+    T, D, L, n, beta = 8192, 4096, 64, 16, 0.9
+    ver = sv.Verifier(si.TINY.desc, T, 64, sliced_w=True)
+    g = np.random.default_rng(7)
+    m = (0.9 * g.standard_normal((T, D))).astype(np.float32)
+    claims_np = []
+    for r in range(n):                                     # workers scatter around the EMA; two of them attack
+        x = m + 0.5 * g.standard_normal((T, D)).astype(np.float32)
+        kind = {5: "scale", 11: "sign"}.get(r, "honest")
+        claims_np.append(si.make_claim(kind, x, "bf16", seed=r))
+    skip = [int(r == 3) for r in range(n)]
+    claims = torch.stack([dev(c, "bf16") for c in claims_np])
+    m_dev = dev(m, "f32")
+    metrics = ("rel_l2", "l1", "zl2", "sfr")
+    out = ver.score_and_sum(claims, m_dev, skip=skip, metrics=metrics, tau={k: 1e9 for k in metrics}, reduce="global")
+    res = ver.read_results(out["result"])
+    for i in (0, 5, 11, 15):
+        want = so.scores(claims_np[i], m, "global")
+        got = dict(zip(so.METRICS, res["score"][i]))
+        for k in metrics:
+            tol = dict(rel=1e-4, abs=5e-6) if k == "zl2" else dict(rel=3e-5, abs=2e-7)
+            assert got[k] == pytest.approx(want[k], **tol), (i, k, got, want)
+    total = np.zeros((T, D)); mag = np.zeros((T, D))
+    for c, k in zip(claims_np, skip):
+        if not k:
+            c64 = np.asarray(c, np.float64); total += c64; mag += np.abs(c64)
+    assert np.all(np.abs(host(out["sum"]) - total) <= 2e-7 * 15 * mag + 1e-30)
+    # sliced Wasserstein against the EMA's projections
+    u = si.make_directions(D, L, 0)
+    uq = np.asarray(si.to_stage_dtype(u, "bf16"), np.float64)
+    assert sv.lib.sv_sw_row_len(T) == T
+    pm = (m.astype(np.float64) @ uq.T).T.astype(np.float32)
+    pm_dev = dev(pm, "f32")
+    sw, proj = ver.sw_against_projection(claims, pm_dev, dev(u, "bf16"), 1e9)
+    sw = host(sw)
+    pr = np.sort(m.astype(np.float64) @ uq.T, axis=0)
+    scale = float(np.mean(np.abs(pr)))
+    for i in (0, 5, 11):
+        want = float(np.mean(np.abs(np.sort(np.asarray(claims_np[i], np.float64) @ uq.T, axis=0) - pr)))
+        assert abs(sw[i] - want) <= 1e-3 * want + 1e-5 * scale, (i, sw[i], want)
+    assert sn.sliced_wasserstein(claims_np[0][:64], m[:64], u) >= 0.0      # (the oracle's own routine, on a slice)
+    # both updates over the 15 un-skipped workers
+    ver.ema_from_sum(m_dev, out["sum"], 15, beta)
+    m_new = beta * m.astype(np.float64) + (1 - beta) * total / 15
+    np.testing.assert_allclose(host(m_dev), m_new, rtol=2e-6, atol=2e-6)
+    ver.sw_projection_ema(pm_dev, proj, T, skip, beta)
+    np.testing.assert_allclose(host(pm_dev), (m_new @ uq.T).T, rtol=1e-4, atol=1e-4 * scale)
     ver.close()
