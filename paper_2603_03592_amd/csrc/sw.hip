@@ -24,8 +24,8 @@ constexpr int kSortChunkMax = (int)kSwSortChunkMax;   // floats sorted in LDS by
 // [256 rows x 128 B] tile goes global -> LDS with global_load_lds (8 lanes fetch one row's 128
 // contiguous bytes; the 16-byte pieces are XOR-swizzled by choosing which piece a lane fetches),
 // three tiles deep, so that two chunks are always in flight and the wait at the end of a chunk
-// leaves the youngest one outstanding.  The matching [L x chunk] piece of the directions is staged
-// through registers.  Fragments are 16-byte LDS reads, conflict-free with the swizzle.
+// leaves the youngest one outstanding.  The matching [L x chunk] piece of the directions takes the same
+// road.  Fragments are 16-byte LDS reads, conflict-free with the swizzle.
 // fp32 signals are split into three bf16 terms (x = hi + mid + lo exactly), three MFMAs per step:
 // every product is exact in fp32, so the result has fp32-accumulation accuracy.
 __device__ __forceinline__ int sw_swz(int row) { return (row ^ (row >> 3)) & 7; }
@@ -54,10 +54,15 @@ __device__ __forceinline__ void mac_f32(const bf16x8 (&u)[LB], const f32x4& x0, 
 }
 
 constexpr int kSwTile = 256 * 128;     // bytes of one signal tile in LDS
-#ifndef SW_DEPTH
-#define SW_DEPTH 3
-#endif
-constexpr int kSwDepth = SW_DEPTH;     // signal tiles in LDS: kSwDepth - 1 chunks in flight
+constexpr int kSwDepth = 3;            // signal tiles (and direction chunks) in LDS: two chunks in flight
+
+template <int N> __device__ __forceinline__ void wait_vm_lds_barrier() {      // wait until at most N vector-memory loads are in flight
+  static_assert(N >= 9 && N <= 12, "8 signal loads + 1..4 direction loads per chunk");
+  if (N == 9) asm volatile("s_waitcnt vmcnt(9) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  else if (N == 10) asm volatile("s_waitcnt vmcnt(10) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  else if (N == 11) asm volatile("s_waitcnt vmcnt(11) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  else asm volatile("s_waitcnt vmcnt(12) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
 
 template <typename E, int LB>
 __device__ __forceinline__ void sw_project_body(const char* __restrict__ xbase, const bf16* __restrict__ U, int D, int64_t T, int64_t Tpad,
@@ -65,11 +70,13 @@ __device__ __forceinline__ void sw_project_body(const char* __restrict__ xbase, 
   constexpr bool kBf16 = sizeof(E) == 2;
   constexpr int KC = 128 / (int)sizeof(E);            // features per chunk
   constexpr int NSTEP = KC / 16;                      // MFMA k steps per chunk
-  constexpr int UPIECES = KC / 8;                     // 16-byte pieces per direction row and chunk
-  constexpr int UTILE = LB * 32 * 128;                // direction rows keep a 128-byte pitch
-  constexpr int ULOADS = (LB * 32 * UPIECES + 255) / 256;
-  char* xs = smem;                                    // 3 signal tiles
-  char* us = smem + kSwDepth * kSwTile;               // 2 direction chunks
+  constexpr int UPITCH = KC * 2;                      // bytes of a direction row per chunk: 128 (bf16 signal) or 64 (fp32 signal)
+  constexpr int UTILE = LB * 32 * UPITCH;
+  constexpr int UINSTR = UTILE / 1024;                // direct-to-LDS instructions per directions' chunk
+  constexpr int UW = (UINSTR + 3) / 4;                // ... per wave (every wave issues the same number: the waits count them)
+  constexpr int RPI = 1024 / UPITCH;                  // direction rows per instruction: 8 or 16
+  char* xs = smem;                                    // kSwDepth signal tiles
+  char* us = smem + kSwDepth * kSwTile;               // kSwDepth direction chunks
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), l31 = lane & 31, lhi = lane >> 5;
   const int64_t tile0 = (int64_t)blockIdx.x * 256;
   // direct-to-LDS plan: instruction i of this wave covers the tile rows (wave + 4 i) * 8 .. + 7
@@ -79,6 +86,21 @@ __device__ __forceinline__ void sw_project_body(const char* __restrict__ xbase, 
     const int r = (wave + 4 * i) * 8 + (lane >> 3), c = (lane & 7) ^ sw_swz(r);
     xoff[i] = min(tile0 + r, T - 1) * (int64_t)D * (int64_t)sizeof(E) + c * 16;     // rows past the end re-read the last one
   }
+  // The directions' chunk [L rows x UPITCH bytes] goes the same way (no registers, so the only vector-memory
+  // operations in flight are direct-to-LDS loads and the waits can count them exactly; staged through registers, the
+  // compiler's wait before the LDS write also waited for the youngest signal chunk).  Instruction j of this wave covers
+  // the rows RPI * i .. + RPI - 1, i = min(wave + 4 j, UINSTR - 1) (a repeated instruction rewrites the same bytes).
+  // 16-byte pieces are XOR-swizzled by the row so that the 32 rows a fragment read touches spread over the banks.
+  auto u_swz = [](int r) { return kBf16 ? sw_swz(r) : ((r >> 2) & 3); };
+  int64_t uoff[UW];
+  int ulds[UW];
+#pragma unroll
+  for (int j = 0; j < UW; ++j) {
+    const int i = min(wave + 4 * j, UINSTR - 1);
+    const int r = i * RPI + lane / (UPITCH / 16), c = (lane % (UPITCH / 16)) ^ u_swz(r);
+    uoff[j] = (int64_t)r * D * 2 + c * 16;
+    ulds[j] = i * 1024;
+  }
   // Workgroups that run together start at different chunks: with a row pitch that is a multiple of the memory
   // channels' interleave, everybody reading column chunk kc of its rows at the same time would camp on few channels.
   const int nchunk = D / KC;
@@ -87,21 +109,14 @@ __device__ __forceinline__ void sw_project_body(const char* __restrict__ xbase, 
   auto dma = [&](int kc, int stage) {
     const int ck = chunk_of(kc);
 #pragma unroll
+    for (int j = 0; j < UW; ++j)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)((const char*)U + uoff[j] + (int64_t)ck * UPITCH),
+                                       (__attribute__((address_space(3))) void*)(us + stage * UTILE + ulds[j]), 16, 0, 0);
+#pragma unroll
     for (int i = 0; i < 8; ++i)
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(xbase + xoff[i] + (int64_t)ck * 128),
                                        (__attribute__((address_space(3))) void*)(xs + stage * kSwTile + (wave + 4 * i) * 1024), 16, 0, 0);
   };
-  // staging of the directions' chunk: thread e owns the 16-byte pieces e, e + 256, ... of the [L, KC] tile
-  const bf16* ug[ULOADS];
-  int ul[ULOADS];
-  bool uon[ULOADS];
-#pragma unroll
-  for (int i = 0; i < ULOADS; ++i) {
-    const int e = tid + 256 * i, r = e / UPIECES, c = e % UPIECES;
-    uon[i] = e < LB * 32 * UPIECES;
-    ug[i] = U + (int64_t)(uon[i] ? r : 0) * D + c * 8;
-    ul[i] = r * 128 + ((c ^ sw_swz(r)) << 4);
-  }
   f32x16 acc[2][LB];
 #pragma unroll
   for (int tb = 0; tb < 2; ++tb)
@@ -110,34 +125,22 @@ __device__ __forceinline__ void sw_project_body(const char* __restrict__ xbase, 
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[tb][b][i] = 0.0f;
 
-  bf16x8 ureg[ULOADS];
-#pragma unroll
-  for (int i = 0; i < ULOADS; ++i)
-    if (uon[i]) *reinterpret_cast<bf16x8*>(us + ul[i]) = *reinterpret_cast<const bf16x8*>(ug[i] + (int64_t)chunk_of(0) * KC);
   dma(0, 0);
-#pragma unroll
-  for (int i = 1; i < kSwDepth - 1; ++i) dma(i < nchunk ? i : nchunk - 1, i);     // always issued: the waits below count on them
-  if (kSwDepth == 3) asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-  else asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  dma(nchunk > 1 ? 1 : 0, 1);                          // a second chunk is always issued: the waits below count on it
+  wait_vm_lds_barrier<8 + UW>();
   int st = 0;                                          // LDS tile of chunk kc
   for (int kc = 0; kc < nchunk; ++kc) {
-    const bool more = kc + 1 < nchunk;
-    if (more) {
-#pragma unroll
-      for (int i = 0; i < ULOADS; ++i)
-        if (uon[i]) ureg[i] = *reinterpret_cast<const bf16x8*>(ug[i] + (int64_t)chunk_of(kc + 1) * KC);
-    }
-    const int st2 = st == 0 ? kSwDepth - 1 : st - 1;   // tile of the youngest chunk: the one chunk kc - 1 was read from
-    dma(kc + kSwDepth - 1 < nchunk ? kc + kSwDepth - 1 : nchunk - 1, st2);   // past the end: re-read the last chunk (never used)
+    const int st2 = st == 0 ? kSwDepth - 1 : st - 1;   // tile of chunk kc + 2: the one chunk kc - 1 was read from
+    dma(kc + 2 < nchunk ? kc + 2 : nchunk - 1, st2);   // past the end: re-read the last chunk (never used)
     const char* xt = xs + st * kSwTile;
-    const char* ub = us + (kc & 1) * UTILE;
+    const char* ub = us + st * UTILE;
 #pragma unroll
     for (int s = 0; s < NSTEP; ++s) {
       bf16x8 u[LB];
 #pragma unroll
       for (int b = 0; b < LB; ++b) {
         const int r = b * 32 + l31;
-        u[b] = *reinterpret_cast<const bf16x8*>(ub + r * 128 + (((2 * s + lhi) ^ sw_swz(r)) << 4));
+        u[b] = *reinterpret_cast<const bf16x8*>(ub + r * UPITCH + (((2 * s + lhi) ^ u_swz(r)) << 4));
       }
 #pragma unroll
       for (int tb = 0; tb < 2; ++tb) {
@@ -153,15 +156,9 @@ __device__ __forceinline__ void sw_project_body(const char* __restrict__ xbase, 
         }
       }
     }
-    if (more) {
-#pragma unroll
-      for (int i = 0; i < ULOADS; ++i)
-        if (uon[i]) *reinterpret_cast<bf16x8*>(us + ((kc + 1) & 1) * UTILE + ul[i]) = ureg[i];
-    }
-    // chunk kc + 1 has landed (only the 8 loads of chunk kc + 2 may still be in flight) and this wave is done with
-    // tile st and the directions' buffer; after the barrier that holds for the whole workgroup
-    if (kSwDepth == 3) asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    // chunk kc + 1 has landed (only the loads of chunk kc + 2 may still be in flight) and this wave is done with
+    // tile st; after the barrier that holds for the whole workgroup
+    wait_vm_lds_barrier<8 + UW>();
     st = st + 1 >= kSwDepth ? 0 : st + 1;
   }
   __builtin_amdgcn_s_waitcnt(0);                       // every direct-to-LDS load has landed before the LDS is given back
@@ -415,7 +412,7 @@ template <typename E, typename E2, int LB>
 hipError_t project_launch(const void* X, int64_t stride, int count, const void* X2, int n2, const void* U, int D, int64_t T, int64_t Tpad,
                           float* P, float* P2, hipStream_t st) {
   auto kern = sw_project_kernel<E, E2, LB>;
-  constexpr int lds = kSwDepth * kSwTile + 2 * LB * 32 * 128;
+  constexpr int lds = kSwDepth * (kSwTile + LB * 32 * 128);   // direction chunks of 128 (bf16 signal) or 64 bytes per row
   static bool configured = false;   // per process; the attribute is per function
   if (!configured) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
