@@ -238,14 +238,17 @@ __global__ __launch_bounds__(256) void score_parts_kernel(const EC* __restrict__
         if (FULL) { sc = wave_sum_rows(sc); scc = wave_sum_rows(scc); sad = wave_sum_rows(sad); }
         if (lane == c) { tsdd += sdd; tsc += sc; tscc += scc; tsad += sad; tmatch += match; }
       };
+      // The next (part, submission) is fetched before the current one is reduced -- unconditionally (past the end:
+      // the last one again, never used), because a fetch behind a branch makes the compiler's wait for the current
+      // buffer cover the younger loads too, and nothing would be in flight during the reduction.
       const int q0 = part * nc;
       for (int c = 0; c < nc; c += 2) {
-        if (q0 + c + 1 < nq) fetch(bufB, q0 + c + 1);
+        fetch(bufB, min(q0 + c + 1, nq - 1));
         reduce(bufA, c);
         if (c + 1 < nc) {
-          if (q0 + c + 2 < nq) fetch(bufA, q0 + c + 2);
+          fetch(bufA, min(q0 + c + 2, nq - 1));
           reduce(bufB, c + 1);
-        } else if (q0 + c + 1 < nq) {                  // odd group: the next part's first submission sits in B
+        } else {                                       // odd group: the next part's first submission sits in B
 #pragma unroll
           for (int m = 0; m < NU; ++m) bufA[m] = bufB[m];
         }
