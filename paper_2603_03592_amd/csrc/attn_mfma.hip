@@ -48,6 +48,39 @@ template <int HD> __device__ __forceinline__ int rm_pos(int c, int row) {
   return HD == 128 ? (c ^ (((row & 3) << 2) | ((row >> 2) & 3))) : (c ^ ((((row >> 1) & 1) << 2) | ((row >> 2) & 3)));
 }
 
+// One direct-to-LDS load of 16 bytes per lane: lane l's bytes go to lds + 16 l (lds wave-uniform).  Issued as inline
+// assembly so that it stays outside the compiler's model of memory: with the builtin, the compiler makes every
+// transposing LDS read wait (vmcnt(0)) for all direct-to-LDS loads in flight -- it cannot tell that they fill the OTHER
+// stage -- and the next tile's loads, issued at the top of a tile, were waited for in the middle of that tile's work.
+// The kernels wait for these loads themselves (dma_wait_all) before the barrier that hands a stage over; waits the
+// compiler computes for its own loads can only become stricter by loads it does not know of.
+#ifndef ATT_ASM_DMA
+#define ATT_ASM_DMA 1
+#endif
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"      // m0 is a reserved register: nothing else in these kernels uses it
+__device__ __forceinline__ void dma16(const char* g, unsigned off, char* lds) {       // g wave-uniform, off per lane
+#if ATT_ASM_DMA
+  const unsigned l = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(__attribute__((address_space(3))) char*)lds);
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(off), "s"(g), "s"(l) : "memory", "m0");
+#else
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(g + off), (__attribute__((address_space(3))) void*)lds, 16, 0, 0);
+#endif
+}
+__device__ __forceinline__ void dma16(const char* g_lane, char* lds) {                // per-lane address
+#if ATT_ASM_DMA
+  const unsigned l = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(__attribute__((address_space(3))) char*)lds);
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g_lane), "s"(l) : "memory", "m0");
+#else
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g_lane, (__attribute__((address_space(3))) void*)lds, 16, 0, 0);
+#endif
+}
+#pragma clang diagnostic pop
+// Every direct-to-LDS load of this wave has landed (to be followed by the barrier that publishes the stage).  The builtin,
+// not assembly: the compiler then also knows that its own earlier loads have landed and plans no waits for them later,
+// which the loads it does not know of would turn into waits for the next tile.
+__device__ __forceinline__ void dma_wait_all() { __builtin_amdgcn_s_waitcnt(0x0F70); }     // vmcnt(0) only
+
 // Two 64-row tiles (rows r0 .. r0 + 63 of a and of b, HD bf16 each, row pitches lda / ldb, clamped to the last valid
 // row) go global -> LDS
 // row-major with global_load_lds: no registers, no LDS write instructions.  One wave instruction moves 1 KB = RPI rows;
@@ -60,12 +93,10 @@ __device__ __forceinline__ void stage_two_tiles(const bf16* a, int64_t lda, cons
 #pragma unroll
   for (int i = 0; i < IPW; ++i) {
     const int ii = wave * IPW + i, r = ii * RPI + s_row;
-    const int64_t row = min(r0 + r, last_row);
+    const int rr = min(r, last_row - r0);                       // row within the tile, clamped to the last valid one
     const int col = rm_pos<HD>(s_pos, r) * 8;
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a + row * lda + col),
-                                     (__attribute__((address_space(3))) void*)(ta + ii * 1024), 16, 0, 0);
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(b + row * ldb + col),
-                                     (__attribute__((address_space(3))) void*)(tb + ii * 1024), 16, 0, 0);
+    dma16((const char*)(a + (int64_t)r0 * lda), (unsigned)((int64_t)rr * lda + col) * 2u, ta + ii * 1024);
+    dma16((const char*)(b + (int64_t)r0 * ldb), (unsigned)((int64_t)rr * ldb + col) * 2u, tb + ii * 1024);
   }
 }
 
@@ -90,8 +121,7 @@ __device__ __forceinline__ void stage_tile_fast(const bf16* tile_rows, const Til
   const char* g = (const char*)tile_rows;           // wave-uniform: first row of the tile
 #pragma unroll
   for (int i = 0; i < TileOffsets<HD, NW>::IPW; ++i)
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(g + o.off[i]),
-                                     (__attribute__((address_space(3))) void*)(dst + (wave * TileOffsets<HD, NW>::IPW + i) * 1024), 16, 0, 0);
+    dma16(g, o.off[i], dst + (wave * TileOffsets<HD, NW>::IPW + i) * 1024);
 }
 
 // A-operand fragment of the TRANSPOSE of a row-major 64-row tile, for MFMA g (0..3) of the tile's 64 rows and feature
@@ -168,6 +198,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int myq = wq0 + l31;
 
   stage_tile(0, 0);
+  dma_wait_all();
   __syncthreads();
 
   for (int j = 0; j < ntiles; ++j) {
@@ -248,6 +279,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
         for (int db = 0; db < NDB; ++db) oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[g][db], pf[g], oacc[db], 0, 0, 0);
     }
+    dma_wait_all();
     __syncthreads();                                  // fence + barrier: the next tile has landed for everybody
   }
 
@@ -365,6 +397,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     for (int r = 0; r < 16; ++r) dq[i][r] = 0.0f;
 
   stage_tile(0, 0);
+  dma_wait_all();
   __syncthreads();
   for (int j = 0; j < ntiles; ++j) {
     const bool more = j + 1 < ntiles;
@@ -418,6 +451,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
           }
       }
     }
+    dma_wait_all();
     __syncthreads();                                  // fence + barrier: the next tile has landed for everybody
   }
   if (myq < S) {
@@ -478,22 +512,24 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
     char* base = smem + stage * STAGE;
     const bf16* qrows = qkv + (int64_t)b * S * ld + (int64_t)h * HD;
     const bf16* drows = dout + (int64_t)b * S * Dq + (int64_t)h * HD;
+    // the two scalar loads go first: they are waited for when the tile is nearly done, and a wait for a load also
+    // waits for every older one -- behind the tile loads they would drag those along
+    if (tid < 64) {
+      const int64_t li = ((int64_t)b * H + h) * S + min(q0 + tid, S - 1);
+      lreg = lse[li];
+      dlreg = delta[li];
+    }
     if (q0 + 64 <= S) {                              // whole tile inside the sequence (uniform)
       stage_tile_fast<HD>(qrows + (int64_t)q0 * ld, toff_q, base, wave_u);
       stage_tile_fast<HD>(drows + (int64_t)q0 * Dq, toff_d, base + TILE, wave_u);
     } else {
       stage_two_tiles<HD>(qrows, ld, drows, Dq, q0, S - 1, base, base + TILE, wave, lane);
     }
-    if (tid < 64) {
-      const int64_t li = ((int64_t)b * H + h) * S + min(q0 + tid, S - 1);
-      lreg = lse[li] * 1.4426950408889634f;
-      dlreg = delta[li];
-    }
   };
   auto store_scalars = [&](int stage) {
     if (tid < 64) {
       char* base = smem + stage * STAGE;
-      reinterpret_cast<float*>(base + 2 * TILE)[tid] = lreg;
+      reinterpret_cast<float*>(base + 2 * TILE)[tid] = lreg * 1.4426950408889634f;
       reinterpret_cast<float*>(base + 2 * TILE + 256)[tid] = dlreg;
     }
   };
@@ -508,6 +544,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
     stage_tile(0, 0);
     store_scalars(0);
   }
+  dma_wait_all();
   __syncthreads();
   for (int j = 0; j < ntiles; ++j) {
     const bool more = j + 1 < ntiles;
@@ -577,6 +614,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
         }
     }
     if (more) store_scalars((j + 1) & 1);
+    dma_wait_all();
     __syncthreads();                                  // fence + barrier: the next tiles have landed for everybody
   }
   if (mykey < S) {
