@@ -20,6 +20,11 @@
  *                       the reference is any tensor: a recomputation or the EMA m_{t-1};
  *   sv_ema_update       Eq. momentum_def over the un-flagged submissions (R_clean of
  *                       Alg. momentum_verification);
+ *   sv_score_and_sum, sv_ema_from_sum, sv_sw_against_projection, sv_sw_projection_ema
+ *                       the same statistics and update arranged so that a verifier that keeps the
+ *                       EMA reads every submission twice instead of three times and never projects
+ *                       the EMA (the sum over the clean set from the score pass; the EMA's
+ *                       projections carried along by linearity);
  *   sv_sliced_wasserstein, sv_adaptive_iqr / sv_policy_*, sv_replace_with_ema, sv_sentinel_*
  *                       the remaining statistic of that paragraph, the adaptive thresholds and
  *                       counters, gradient replacement, and the whole verifier loop of
