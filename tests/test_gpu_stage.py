@@ -82,6 +82,16 @@ def test_bf16_stage_matches_oracle(desc, B, S, backward, plain):
         assert rel_l2(gg, wg) <= TOL["bf16"]
 
 
+@pytest.mark.parametrize("desc,S", [(MFMA_HD128, 4000), (MFMA_BF16, 4090)], ids=["hd128", "hd64"])
+def test_long_sequence_single_micro_batch(desc, S):
+    """One sequence of ~4096 tokens (the sweep's longest), ragged: 63-64 key tiles per query tile, a causal diagonal far
+    from the start, and fewer (batch, kv head) pairs than XCDs for the workgroup-id mapping; forward and backward."""
+    (gh, gg), (wh, wg), h = run_stage(desc, 1, S, seed=5, backward=True, weight_scale=2.0)
+    assert rel_l2(gh, wh) <= TOL["bf16"]
+    assert np.max(so.token_rel_l2(gh, wh)) <= TOL["bf16"]
+    assert rel_l2(gg, wg) <= TOL["bf16"]
+
+
 def test_forward_on_a_backward_context_and_sequence_independence():
     import paper_2603_03592_amd as sv
     desc = MFMA_BF16
