@@ -166,3 +166,26 @@ def test_sw_against_projection_and_projection_ema():
     ver.sw_projection_ema(pm_dev, proj, T, [1] * 6, beta)
     assert np.array_equal(host(pm_dev), before)
     ver.close()
+
+
+def test_sw_against_projection_limits():
+    """256 submissions x 128 directions in one call (32768 rows in one sort launch); 257 submissions and rows beyond one
+    LDS chunk are refused."""
+    import torch
+    sv, ver = _ver(20000)
+    T, D, L, n = 128, 64, 128, 256
+    u = si.make_directions(D, L, seed=6)
+    uq = np.asarray(si.to_stage_dtype(u, "bf16"), np.float64)
+    g = np.random.default_rng(6)
+    m = g.standard_normal((T, D)).astype(np.float32)
+    claims = [si.to_stage_dtype(m + np.float32(0.01 * (i % 7)) * g.standard_normal((T, D)).astype(np.float32), "bf16") for i in range(n)]
+    pm = dev((m.astype(np.float64) @ uq.T).T.astype(np.float32), "f32")
+    cl = torch.stack([dev(c, "bf16") for c in claims])
+    sw, proj = ver.sw_against_projection(cl, pm, dev(u, "bf16"), 1.0)
+    _check(host(sw)[::37], claims[::37], [m], u)
+    with pytest.raises(sv.SVError):
+        ver.sw_against_projection(torch.cat([cl, cl[:1]]), pm, dev(u, "bf16"), 1.0)
+    big = torch.zeros((1, 20000, D), dtype=torch.bfloat16, device="cuda")            # row length 32768 > 16384
+    with pytest.raises(sv.SVError):
+        ver.sw_against_projection(big, torch.zeros((L, 32768), dtype=torch.float32, device="cuda"), dev(u, "bf16"), 1.0)
+    ver.close()
