@@ -393,3 +393,36 @@ def test_stream_detects_value_replacing_attacks_and_not_the_delay_attack():
     h[3] = si.stream_signal("h", 0, 3, t - 20, T, D, "f32")          # delay attack, k = 20
     here, _ = st.forward(0, h)
     assert here == []
+
+
+# ------------------------------------------------------------------ identities the device loop's arrangement rests on
+def test_ema_from_the_sum_and_projections_by_linearity():
+    """Two rearrangements the library makes of Alg. momentum_verification's arithmetic, pinned on the oracle's own
+    routines: (i) Eq. momentum_def from the SUM over the clean set equals the update from the clean set itself;
+    (ii) the projections <u_l, m_t> of the updated EMA equal the same recurrence applied to the projections, so
+    Omega_SW against the EMA can be formed from projections that were never recomputed from the EMA."""
+    from oracle import stage_oracle as st
+    rng = np.random.default_rng(11)
+    T, D, L, n, beta = 40, 24, 8, 7, 0.9
+    u = _dirs(L, D, 5)
+    m = rng.standard_normal((T, D))
+    pm = m @ u.T                                              # [T, L]
+    for it in range(4):
+        x = [m + 0.3 * rng.standard_normal((T, D)) for _ in range(n)]
+        flags = [int(rng.random() < 0.3) for _ in range(n)]
+        if it == 3:
+            flags = [1] * n                                   # nobody clean: everything stays
+        clean = [xi for xi, f in zip(x, flags) if not f]
+        want = st.ema_update(m, x, flags, beta)
+        if clean:
+            total = np.sum(clean, axis=0)
+            np.testing.assert_allclose(beta * m + (1 - beta) * total / len(clean), want, rtol=1e-13, atol=1e-13)
+            pm = beta * pm + (1 - beta) * np.mean([xi @ u.T for xi in clean], axis=0)
+        else:
+            assert np.array_equal(want, m)
+        m = want
+        np.testing.assert_allclose(pm, m @ u.T, rtol=1e-12, atol=1e-12)
+        # the statistic from the carried projections is the oracle's statistic against the EMA
+        probe = m + 0.5 * rng.standard_normal((T, D))
+        from_proj = float(np.mean(np.mean(np.abs(np.sort(probe @ u.T, axis=0) - np.sort(pm, axis=0)), axis=0)))
+        assert from_proj == pytest.approx(so.sliced_wasserstein(probe, m, u), rel=1e-12)
