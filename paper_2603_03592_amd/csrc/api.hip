@@ -38,7 +38,8 @@ struct Arena {
 
 constexpr int64_t kScoreScratchElems = 1 << 18;   // ScorePartial records (20 MiB)
 constexpr int kSwMaxDirs = 128, kSwMaxClaims = 4096;
-constexpr int kAttnPadHd = 64;                    // narrower heads are zero-padded to this width for the matrix-core attention
+// Heads narrower than the matrix-core attention's widths (32, 64, 128) are zero-padded to the next one: 0 = no padding
+inline int attn_pad_width(int hd) { return hd < 32 ? 32 : (hd > 32 && hd < 64 ? 64 : 0); }
 constexpr int kSwSlots = 33;                      // projected tensors (kSwMaxDirs rows each) the scratch holds at max_tokens
 
 }  // namespace
@@ -63,6 +64,7 @@ struct sv_ctx {
   void *xp, *actp, *yp, *dup_p;
   // heads narrower than the matrix-core attention kernels' 64 columns: zero-padded copies [T, heads * 64]
   void *qkv_pad, *o_pad, *dout_pad, *dqkv_pad;
+  int pad_hd;          // width the heads are padded to for the matrix-core attention (0: none)
   int last_T = 0;      // tokens of the most recent verify call (for sv_last_routing)
   // backward
   std::vector<void*> xs;           // outputs of blocks 0..L-2 (inputs of blocks 1..L-1)
@@ -168,8 +170,10 @@ size_t carve(sv_ctx* c, char* base) {
     else c->dup_p = a.take(Mp * F * es);
   }
   c->qkv_pad = c->o_pad = c->dout_pad = c->dqkv_pad = nullptr;
-  if (d.dtype == SV_BF16 && !(c->flags & SV_FLAG_PLAIN_KERNELS) && c->hd < kAttnPadHd) {
-    const size_t hq = (size_t)d.n_heads * kAttnPadHd, hall = (size_t)(d.n_heads + 2 * d.n_kv_heads) * kAttnPadHd;
+  c->pad_hd = 0;
+  if (d.dtype == SV_BF16 && !(c->flags & SV_FLAG_PLAIN_KERNELS) && attn_pad_width(c->hd)) {
+    c->pad_hd = attn_pad_width(c->hd);
+    const size_t hq = (size_t)d.n_heads * c->pad_hd, hall = (size_t)(d.n_heads + 2 * d.n_kv_heads) * c->pad_hd;
     c->qkv_pad = a.take(T * hall * es);
     c->o_pad = a.take(T * hq * es);
     if (bwd) { c->dout_pad = a.take(T * hq * es); c->dqkv_pad = a.take(T * hall * es); }
@@ -283,7 +287,7 @@ hipError_t gemm(sv_ctx* c, const GemmArgs& a, hipStream_t st) {
 // which is still several times faster than the scalar kernels.
 bool attn_padded(const sv_ctx* c, int S) {
   const sv_stage_desc& d = c->d;
-  return c->qkv_pad != nullptr && mfma_attn_supported(S, d.n_heads, d.n_kv_heads, kAttnPadHd, (int64_t)(d.n_heads + 2 * d.n_kv_heads) * kAttnPadHd);
+  return c->qkv_pad != nullptr && mfma_attn_supported(S, d.n_heads, d.n_kv_heads, c->pad_hd, (int64_t)(d.n_heads + 2 * d.n_kv_heads) * c->pad_hd);
 }
 
 hipError_t attn_fwd(sv_ctx* c, const void* qkv, void* o, float* lse, int B, int S, hipStream_t st) {
@@ -291,10 +295,10 @@ hipError_t attn_fwd(sv_ctx* c, const void* qkv, void* o, float* lse, int B, int 
   if (d.dtype == SV_BF16 && !(c->flags & SV_FLAG_PLAIN_KERNELS) && mfma_attn_supported(S, d.n_heads, d.n_kv_heads, c->hd, c->Dqkv))
     return mfma_attn_fwd(qkv, c->Dqkv, o, lse, B, S, d.n_heads, d.n_kv_heads, c->hd, d.causal, st);
   if (attn_padded(c, S)) {
-    const int64_t T = (int64_t)B * S, ldp = (int64_t)(d.n_heads + 2 * d.n_kv_heads) * kAttnPadHd, ldo = (int64_t)d.n_heads * kAttnPadHd;
-    hipError_t e = plain_pad_heads(qkv, c->Dqkv, c->qkv_pad, ldp, T, d.n_heads + 2 * d.n_kv_heads, c->hd, kAttnPadHd, 1, st);
-    if (e == hipSuccess) e = mfma_attn_fwd(c->qkv_pad, ldp, c->o_pad, lse, B, S, d.n_heads, d.n_kv_heads, kAttnPadHd, d.causal, st, c->hd);
-    if (e == hipSuccess) e = plain_pad_heads(c->o_pad, ldo, o, c->Dq, T, d.n_heads, c->hd, kAttnPadHd, 0, st);
+    const int64_t T = (int64_t)B * S, ldp = (int64_t)(d.n_heads + 2 * d.n_kv_heads) * c->pad_hd, ldo = (int64_t)d.n_heads * c->pad_hd;
+    hipError_t e = plain_pad_heads(qkv, c->Dqkv, c->qkv_pad, ldp, T, d.n_heads + 2 * d.n_kv_heads, c->hd, c->pad_hd, 1, st);
+    if (e == hipSuccess) e = mfma_attn_fwd(c->qkv_pad, ldp, c->o_pad, lse, B, S, d.n_heads, d.n_kv_heads, c->pad_hd, d.causal, st, c->hd);
+    if (e == hipSuccess) e = plain_pad_heads(c->o_pad, ldo, o, c->Dq, T, d.n_heads, c->hd, c->pad_hd, 0, st);
     return e;
   }
   return plain_attn_fwd(qkv, c->Dqkv, o, lse, B, S, d.n_heads, d.n_kv_heads, c->hd, d.causal, d.dtype, st);
@@ -313,14 +317,14 @@ hipError_t attn_bwd(sv_ctx* c, const BlockStash& k, int B, int S, hipStream_t st
                          d.rope ? c->rope_cs : nullptr, st);
   if (attn_padded(c, S) && c->dout_pad) {
     const int nh = d.n_heads + 2 * d.n_kv_heads;
-    const int64_t T = (int64_t)B * S, ldp = (int64_t)nh * kAttnPadHd, ldo = (int64_t)d.n_heads * kAttnPadHd;
-    hipError_t e = plain_pad_heads(k.qkv, c->Dqkv, c->qkv_pad, ldp, T, nh, c->hd, kAttnPadHd, 1, st);
-    if (e == hipSuccess) e = plain_pad_heads(k.o, c->Dq, c->o_pad, ldo, T, d.n_heads, c->hd, kAttnPadHd, 1, st);
-    if (e == hipSuccess) e = plain_pad_heads(c->dout, c->Dq, c->dout_pad, ldo, T, d.n_heads, c->hd, kAttnPadHd, 1, st);
+    const int64_t T = (int64_t)B * S, ldp = (int64_t)nh * c->pad_hd, ldo = (int64_t)d.n_heads * c->pad_hd;
+    hipError_t e = plain_pad_heads(k.qkv, c->Dqkv, c->qkv_pad, ldp, T, nh, c->hd, c->pad_hd, 1, st);
+    if (e == hipSuccess) e = plain_pad_heads(k.o, c->Dq, c->o_pad, ldo, T, d.n_heads, c->hd, c->pad_hd, 1, st);
+    if (e == hipSuccess) e = plain_pad_heads(c->dout, c->Dq, c->dout_pad, ldo, T, d.n_heads, c->hd, c->pad_hd, 1, st);
     if (e == hipSuccess)
-      e = mfma_attn_bwd(c->qkv_pad, ldp, c->o_pad, c->dout_pad, k.lse, c->delta, c->dqkv_pad, B, S, d.n_heads, d.n_kv_heads, kAttnPadHd, d.causal,
+      e = mfma_attn_bwd(c->qkv_pad, ldp, c->o_pad, c->dout_pad, k.lse, c->delta, c->dqkv_pad, B, S, d.n_heads, d.n_kv_heads, c->pad_hd, d.causal,
                         nullptr, st, c->hd);
-    if (e == hipSuccess) e = plain_pad_heads(c->dqkv_pad, ldp, c->dqkv, c->Dqkv, T, nh, c->hd, kAttnPadHd, 0, st);
+    if (e == hipSuccess) e = plain_pad_heads(c->dqkv_pad, ldp, c->dqkv, c->Dqkv, T, nh, c->hd, c->pad_hd, 0, st);
     return e;
   }
   return plain_attn_bwd(k.qkv, c->Dqkv, k.o, c->dout, k.lse, c->delta, c->dqkv, B, S, d.n_heads, d.n_kv_heads, c->hd, d.causal, d.dtype, st);

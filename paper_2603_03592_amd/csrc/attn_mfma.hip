@@ -43,8 +43,10 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 // read in two ways: fragments along the rows (16 consecutive rows, one chunk index, 16 bytes per lane) and transposed
 // fragments through ds_read_b64_tr_b16 (32 lanes: 4 consecutive rows x 4 consecutive chunks, 8 bytes per lane).  With
 // the two 2-bit fields of the row number swapped into the XOR mask both patterns fall into 16 different 16-byte slots
-// modulo 256 bytes (rows of 128 bytes, head_dim 64: the row parity is one slot bit, the mask has three bits).
+// modulo 256 bytes (rows of 128 bytes, head_dim 64: the row parity is one slot bit, the mask has three bits; rows of
+// 64 bytes, head_dim 32: two slot bits, two mask bits).
 template <int HD> __device__ __forceinline__ int rm_pos(int c, int row) {
+  if (HD == 32) return c ^ ((row >> 2) & 3);        // rows of 64 bytes: the low two row bits are slot bits already
   return HD == 128 ? (c ^ (((row & 3) << 2) | ((row >> 2) & 3))) : (c ^ ((((row >> 1) & 1) << 2) | ((row >> 2) & 3)));
 }
 
@@ -639,7 +641,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
 }  // namespace
 
 bool mfma_attn_supported(int S, int H, int Hkv, int hd, int64_t ld) {
-  return (hd == 64 || hd == 128) && S >= 1 && H % Hkv == 0 && ld % 8 == 0;
+  return (hd == 32 || hd == 64 || hd == 128) && S >= 1 && H % Hkv == 0 && ld % 8 == 0;
 }
 
 hipError_t mfma_attn_fwd(const void* qkv, int64_t ld, void* o, float* lse, int B, int S, int H, int Hkv, int hd, int causal, hipStream_t st,
@@ -661,7 +663,8 @@ hipError_t mfma_attn_fwd(const void* qkv, int64_t ld, void* o, float* lse, int B
     hipLaunchKernelGGL(kern, grid, block, lds, st, (const bf16*)qkv, ld, (bf16*)o, lse, B, S, H, Hkv, c);                  \
   } while (0)
   if (hd == 128) { if (causal) SV_ATTN_LAUNCH(128, true); else SV_ATTN_LAUNCH(128, false); }
-  else { if (causal) SV_ATTN_LAUNCH(64, true); else SV_ATTN_LAUNCH(64, false); }
+  else if (hd == 64) { if (causal) SV_ATTN_LAUNCH(64, true); else SV_ATTN_LAUNCH(64, false); }
+  else { if (causal) SV_ATTN_LAUNCH(32, true); else SV_ATTN_LAUNCH(32, false); }
 #undef SV_ATTN_LAUNCH
   return hipGetLastError();
 }
@@ -691,7 +694,8 @@ hipError_t mfma_attn_bwd(const void* qkv, int64_t ld, const void* o, const void*
                        H, Hkv, scale, rope_cs);                                                                         \
   } while (0)
   if (hd == 128) { if (causal) SV_ATTN_BWD_LAUNCH(128, true); else SV_ATTN_BWD_LAUNCH(128, false); }
-  else { if (causal) SV_ATTN_BWD_LAUNCH(64, true); else SV_ATTN_BWD_LAUNCH(64, false); }
+  else if (hd == 64) { if (causal) SV_ATTN_BWD_LAUNCH(64, true); else SV_ATTN_BWD_LAUNCH(64, false); }
+  else { if (causal) SV_ATTN_BWD_LAUNCH(32, true); else SV_ATTN_BWD_LAUNCH(32, false); }
 #undef SV_ATTN_BWD_LAUNCH
   return hipGetLastError();
 }
