@@ -277,7 +277,7 @@ def main():
     a = parse()
     if a.gpus != 1:
         raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path (every stage check is "
-                         "independent per micro-batch; see DESIGN.md for how it would shard). Use --gpus 1.")
+                         "independent per micro-batch, so submissions would be dealt round-robin to GPUs that each hold the stage weights). Use --gpus 1.")
     if a.score_bench:
         return score_bench(a)
     if a.loop_bench:
