@@ -362,6 +362,11 @@ sv_status sv_sentinel_state(const sv_sentinel *s, int32_t stage, int32_t kind, c
 
 /* Copies the EMA of (stage, kind) to out_host (HOST, T*D floats) after the work queued on `stream`.   */
 sv_status sv_sentinel_read_ema(sv_sentinel *s, int32_t stage, int32_t kind, float *out_host, void *stream);
+/* How the stage calls so far were served: counts[0] stage calls, counts[1] EMA updates finished from the score pass's
+ * sum, counts[2] EMA updates that read the signals themselves (shape not taken by the summing pass, no buffer, or a
+ * verdict that excluded somebody beyond the workers known beforehand), counts[3] sliced Wasserstein checks against
+ * carried projections of the EMA.  counts: HOST, 4 entries.                                                */
+sv_status sv_sentinel_counters(const sv_sentinel *s, int64_t *counts);
 
 /* Per-operation timing with HIP events recorded on the caller's stream around each launch.
  * sv_profile_enable(ctx, 1) clears the accumulators and starts recording; (ctx, 0) stops.

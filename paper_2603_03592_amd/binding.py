@@ -141,6 +141,8 @@ def _load():
     L.sv_sentinel_backward.argtypes = [vp, i32, vp, i32, u8p, dp, vp]
     L.sv_sentinel_state.restype = C.c_int
     L.sv_sentinel_state.argtypes = [vp, i32, i32, C.POINTER(vp), C.POINTER(i32), u8p, dp, dp, dp]
+    L.sv_sentinel_counters.restype = C.c_int
+    L.sv_sentinel_counters.argtypes = [vp, C.POINTER(C.c_int64)]
     L.sv_sentinel_read_ema.restype = C.c_int
     L.sv_sentinel_read_ema.argtypes = [vp, i32, i32, C.POINTER(f32), vp]
     L.sv_prepare_weights.restype = C.c_int
@@ -561,6 +563,13 @@ class Sentinel:
         self._check(lib.sv_sentinel_state(self._s, stage, 0 if kind == "h" else 1, C.byref(ema), v.ctypes.data_as(ip), b.ctypes.data_as(u8p),
                                           lo.ctypes.data_as(dp), up.ctypes.data_as(dp), k.ctypes.data_as(dp)))
         return dict(ema_ptr=ema.value, violations=v, banned=b.astype(bool), lower=lo, upper=up, k=k)
+
+    def counters(self) -> dict:
+        """How the stage calls were served: calls, EMA updates from the score pass's sum / from the signals, sliced
+        Wasserstein checks against carried projections."""
+        c = (C.c_int64 * 4)()
+        self._check(lib.sv_sentinel_counters(self._s, c))
+        return dict(calls=c[0], ema_from_sum=c[1], ema_from_signals=c[2], sw_carried=c[3])
 
     def ema(self, stage: int, kind: str) -> np.ndarray:
         """A host copy of the stage's EMA, [T, D] float32."""

@@ -31,6 +31,7 @@ struct sv_sentinel {
   // sliced Wasserstein against the EMA without projecting the EMA: its projections follow from the signals' (linearity)
   std::vector<float*> pm[2];               // [kind][stage] device fp32 [n_dirs, Tpad]: <u_l, m_t>, kept up to date with m
   float* cproj = nullptr;                  // [d, n_dirs, Tpad]: the current signals' projections
+  int64_t n_calls = 0, n_from_sum = 0, n_from_signals = 0, n_sw_carried = 0;
   // pinned staging
   sv_result* res_host = nullptr;
   float* sw_host = nullptr;
@@ -79,6 +80,7 @@ sv_status gamma_of(sv_sentinel* s, const void* signals, int dtype, const float* 
   else if (sum_st != SV_OK) { set_err(s, "sv_score_and_sum: %s", sv_last_error(s->ctx)); return sum_st; }
   SN_HIP(s, hipMemcpyAsync(s->res_host, s->res_dev, sizeof(sv_result) * d, hipMemcpyDeviceToHost, st));
   if (c.metric_mask & SV_M_SW) {
+    if (pm) ++s->n_sw_carried;
     if (pm)
       SN_SV(s, sv_sw_against_projection(s->ctx, signals, stride, d, dtype, c.T, c.D, c.directions, c.n_dirs, pm, s->cproj, inf, s->sw_dev,
                                         nullptr, st));
@@ -110,10 +112,13 @@ sv_status update_ema(sv_sentinel* s, float* m, float* pm, const void* signals, i
   bool same = summed;
   int n = 0;
   for (int r = 0; r < d; ++r) { same = same && (excl[r] != 0) == (skip[r] != 0); n += excl[r] == 0; }
+  ++s->n_calls;
   if (same) {
+    ++s->n_from_sum;
     SN_SV(s, sv_ema_from_sum(s->ctx, m, s->sum_dev, n, s->cfg.T, s->cfg.D, beta, hs));
     return SV_OK;
   }
+  ++s->n_from_signals;
   if (!mask_uploaded) SN_HIP(s, hipMemcpyAsync(s->mask_dev + d, excl, (size_t)d, hipMemcpyHostToDevice, hs));
   SN_SV(s, sv_ema_update(s->ctx, m, signals, s->cfg.T * s->cfg.D, d, dtype, s->mask_dev + d, s->cfg.T, s->cfg.D, beta, hs));
   return SV_OK;
@@ -264,11 +269,12 @@ sv_status sv_sentinel_backward(sv_sentinel* s, int32_t stage, void* g, int32_t d
   std::vector<double> gamma;
   sv_policy* pol = s->pol[1][stage];
   std::vector<uint8_t> down(d, 0), banned(d, 0), skip(d, 0);
-  if (!s->warm) {                                  // excluded whatever this check says: banned, or tainted here on the way forward
+  if (!s->warm) {                                  // excluded whatever this check says (short of a majority reset): banned,
+                                                   // tainted here on the way forward, or tainted at a later stage
     for (int r = 0; r < d; ++r)
       for (int s2 = stage + 1; s2 < p; ++s2) down[r] |= s->tainted[(size_t)s2 * d + r];
     SN_SV(s, sv_policy_state(pol, nullptr, banned.data(), nullptr, nullptr, nullptr, nullptr));
-    for (int r = 0; r < d; ++r) skip[r] = banned[r] | s->tainted[(size_t)stage * d + r];
+    for (int r = 0; r < d; ++r) skip[r] = banned[r] | s->tainted[(size_t)stage * d + r] | down[r];
   }
   bool summed = false;
   float* pm = s->pm[1].empty() ? nullptr : s->pm[1][stage];
@@ -303,6 +309,12 @@ sv_status sv_sentinel_state(const sv_sentinel* s, int32_t stage, int32_t kind, c
   if (!s || stage < 0 || stage >= s->cfg.n_stages || (kind != 0 && kind != 1)) return SV_EINVAL;
   if (ema_dev) *ema_dev = s->m[kind][stage];
   return sv_policy_state(s->pol[kind][stage], violations, banned, lower, upper, k, nullptr);
+}
+
+sv_status sv_sentinel_counters(const sv_sentinel* s, int64_t* counts) {
+  if (!s || !counts) return SV_EINVAL;
+  counts[0] = s->n_calls; counts[1] = s->n_from_sum; counts[2] = s->n_from_signals; counts[3] = s->n_sw_carried;
+  return SV_OK;
 }
 
 sv_status sv_sentinel_read_ema(sv_sentinel* s, int32_t stage, int32_t kind, float* out_host, void* stream) {

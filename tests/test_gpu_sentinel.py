@@ -123,6 +123,9 @@ def test_verifier_loop_with_the_sum_from_the_score_pass(dtype, Dv):
     _iteration(torch, lib, ref, t, False, dtype, attack_g=(1, 4, "scale"), Dv=Dv); t += 1
     _iteration(torch, lib, ref, t, False, dtype, attack_h=(0, 5, "zero"), attack_g=(0, 1, "sign"), Dv=Dv); t += 1
     _state_close(lib, ref)
+    c = lib.counters()                                    # both ways of updating the EMA were taken, every SW check carried
+    assert c["calls"] == 2 * P * t and c["ema_from_sum"] + c["ema_from_signals"] == c["calls"]
+    assert c["ema_from_signals"] >= 7 and c["ema_from_sum"] > c["calls"] // 2 and c["sw_carried"] == c["calls"]
     lib.close(); ver.close()
 
 
