@@ -499,6 +499,56 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
     // wait insertion falls back to waiting for (nearly) everything in flight, one memory round trip per store.
     auto run_epilogue = [&](auto check_tag) {
       constexpr bool CHECK = decltype(check_tag)::value;
+      if constexpr (DUAL) {
+        if (!a.C2 && !a.C3) {
+          // Forward-only check (no stash of g and u).  Gate and up of one feature sit in the same lane and register
+          // index, so SiLU(g) * u is taken in the accumulator layout and only its bf16 result goes through the patch:
+          // 128 token rows x 64 features x 2 bytes = the 16 KB patch in one piece (16-byte chunks XOR-swizzled by bits
+          // 1..3 of the row), a quarter of the fp32 way's LDS traffic, and the read-back gives every lane 16 bytes of a
+          // row, so 8 lanes store one full 128-byte line.  (With the stashes, three such passes measured slower than
+          // the fp32 way below, which serves them.)
+          // The lane's row and chunk numbers are made opaque once per tile: otherwise every address below is loop
+          // invariant, gets hoisted out of the tile loop and spilled, and its reloads cost a memory round trip each.
+          int r31 = l31, rhi = lhi, ln = lane;
+          asm volatile("" : "+v"(r31), "+v"(rhi), "+v"(ln));
+          // The accumulators are read where they are, in the accumulation registers, by an instruction the compiler
+          // cannot merge with the reads of the other way: left to it, it keeps copies of whole accumulator blocks in
+          // ordinary registers from one use to the next and spills them.  The matrix pipe's last write is long
+          // finished (a workgroup barrier lies in between); the wait states make that formal, since the compiler's
+          // own hazard handling does not look into assembly.
+          asm volatile("s_nop 15\n\ts_nop 15");
+          auto rd = [&](int ni, int mi, int r) {
+            float x;
+            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x) : "a"(acc[ni][mi][r]));
+            return x;
+          };
+#pragma unroll
+          for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+              for (int q = 0; q < 4; ++q) {
+                bf16x4 pk;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) pk[i] = (bf16)(silu_f(rd(ni, mi, q * 4 + i)) * rd(ni + 2, mi, q * 4 + i));
+                const int row = mi * 32 + r31;
+                *reinterpret_cast<bf16x4*>(patch + row * 128 + (((ni * 4 + q) ^ ((r31 >> 1) & 7)) << 4) + rhi * 8) = pk;
+                if (q == 3) SV_SB;                       // one feature block at a time
+              }
+          __builtin_amdgcn_s_waitcnt(0xc07f);            // lgkmcnt(0): the patch is complete before it is read back
+          __builtin_amdgcn_wave_barrier();
+#pragma unroll
+          for (int it = 0; it < 16; ++it) {
+            const int row = it * 8 + (ln >> 3), cc = ln & 7;
+            const bf16x8 v = *reinterpret_cast<const bf16x8*>(patch + row * 128 + ((cc ^ ((row >> 1) & 7)) << 4));
+            const int m = m0 + wm * 128 + row;
+            if (CHECK && m >= M) continue;
+            *reinterpret_cast<bf16x8*>((bf16*)a.C + (int64_t)m * a.ldc + n0 + wn * 64 + cc * 8) = v;
+            if ((it & 3) == 3) SV_SB;
+          }
+          return;
+        }
+      }
       auto load_inputs = [&](int trip, EpiIn (&in_lo)[2], EpiIn (&in_hi)[2]) {
         const int mi = trip >> 2, it = (trip & 3) * 2;
 #pragma unroll
@@ -661,6 +711,7 @@ hipError_t mfma_gemm(const GemmArgs& a, hipStream_t st, int tile) {
     // the DMA offsets are 32-bit byte offsets within a 256-row panel
     bool fits = true;
     for (int s = 0; s < a.nseg; ++s) fits = fits && 256 * a.seg[s].lda * 2 < (int64_t)1 << 32 && 256 * a.seg[s].ldb * 2 < (int64_t)1 << 32;
+    if (a.epi == EPI_SWIGLU && a.ldc % 8) fits = false;       // its epilogue stores 16 bytes per lane
     if (fits) {
       if (a.tile_group) {
         switch (a.epi) {                                   // the epilogues the mixture-of-experts products use
