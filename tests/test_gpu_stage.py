@@ -92,6 +92,18 @@ def test_long_sequence_single_micro_batch(desc, S):
     assert rel_l2(gg, wg) <= TOL["bf16"]
 
 
+@pytest.mark.parametrize("backward", [False, True], ids=["fwd", "bwd"])
+def test_wide_mlp_on_the_large_tile_with_a_ragged_row_tail(backward):
+    """9 row tiles of 256 (the last with 52 rows) x 24 column tiles: every product of the MLP runs on the 256 x 256
+    kernel.  Forward-only and with the stash for backward, the gate/up epilogue takes two different ways."""
+    desc = si.StageDesc(1, 256, 4, 2, 3072)
+    (gh, gg), (wh, wg), h = run_stage(desc, 3, 700, seed=7, backward=backward, weight_scale=2.0)
+    assert rel_l2(gh, wh) <= TOL["bf16"]
+    assert np.max(so.token_rel_l2(gh, wh)) <= TOL["bf16"]
+    if backward:
+        assert rel_l2(gg, wg) <= TOL["bf16"]
+
+
 def test_forward_on_a_backward_context_and_sequence_independence():
     import paper_2603_03592_amd as sv
     desc = MFMA_BF16
