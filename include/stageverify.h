@@ -390,7 +390,8 @@ sv_status sv_profile_read(sv_ctx *ctx, sv_profile *out);
 /* Tuning and test aid: one bf16 product C[M,N] = A[M,K] * op(B) on the MFMA GEMM kernels that
  * the block recompute uses (fp32 accumulation, bf16 result).  b_is_kn = 0: B stored [N,K]
  * (C = A B^T); 1: B stored [K,N] (C = A B).  tile: 0 = automatic, 1 = 256x256 (direct-to-LDS
- * loads when B is [N,K]), 2 = 128x128, 3 = 256x256 with register-staged loads.
+ * loads when B is [N,K]), 2 = 128x128, 3 = 256x256 with register-staged loads, 4 = 128 rows x 64
+ * columns (B stored [N,K] only; what the automatic choice takes when 128x128 tiles would leave CUs idle).
  * Returns SV_EUNSUPPORTED for shapes outside the kernels' limits (N % 128, K % 64, 16-byte
  * aligned rows).  No context is needed.                                                      */
 sv_status sv_gemm_bf16(const void *A, int64_t lda, const void *B, int64_t ldb, int32_t b_is_kn, void *C, int64_t ldc,

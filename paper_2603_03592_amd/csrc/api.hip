@@ -940,11 +940,11 @@ sv_status sv_replace_with_ema(sv_ctx* c, void* signals, int64_t stride, int32_t 
 
 sv_status sv_gemm_bf16(const void* A, int64_t lda, const void* B, int64_t ldb, int32_t b_is_kn, void* Cout, int64_t ldc, int32_t M,
                        int32_t N, int32_t K, int32_t tile, void* stream) {
-  if (!A || !B || !Cout || M < 1 || N < 1 || K < 1 || tile < 0 || tile > 3) return SV_EINVAL;
+  if (!A || !B || !Cout || M < 1 || N < 1 || K < 1 || tile < 0 || tile > 4) return SV_EINVAL;
   GemmArgs g; memset(&g, 0, sizeof(g));
   g.M = M; g.N = N; g.nseg = 1; g.seg[0] = GemmSeg{A, lda, B, ldb, K};
   g.b_is_kn = b_is_kn ? 1 : 0; g.epi = EPI_STORE; g.C = Cout; g.ldc = ldc;
-  if (!mfma_gemm_supported(g) || ((tile == 1 || tile == 3) && N % 256)) return SV_EUNSUPPORTED;
+  if (!mfma_gemm_supported(g) || ((tile == 1 || tile == 3) && N % 256) || (tile == 4 && b_is_kn)) return SV_EUNSUPPORTED;
   return mfma_gemm(g, (hipStream_t)stream, tile) == hipSuccess ? SV_OK : SV_EHIP;
 }
 

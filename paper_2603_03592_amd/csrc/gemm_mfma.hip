@@ -173,9 +173,15 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(GemmA
   const int wm = wave % WAVES_M, wn = wave / WAVES_M;
 
   // ---- global -> register staging
-  bf16x8 xreg[C::XCH], wreg[C::WCH];
+  // Small tiles keep TWO slices in flight in registers (PF2): with at most two workgroups of four waves on a CU, one
+  // slice of multiplies (~500 cycles) does not cover a global load's latency.  Large tiles have no registers for that.
+  constexpr bool PF2 = BM * BN <= 128 * 128;
+  constexpr int NSET = PF2 ? 2 : 1;
+  bf16x8 xregs[NSET][C::XCH], wregs[NSET][C::WCH];
   int seg = 0, kin = 0;       // position of the slice being loaded
-  auto load_slice = [&]() {
+  auto load_slice = [&](auto set_tag) {
+    bf16x8 (&xreg)[C::XCH] = xregs[decltype(set_tag)::value];
+    bf16x8 (&wreg)[C::WCH] = wregs[decltype(set_tag)::value];
     const bf16* A = (const bf16*)a.seg[seg].A;
     const int64_t lda = a.seg[seg].lda, ldb = a.seg[seg].ldb;
 #pragma unroll
@@ -206,10 +212,17 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(GemmA
           wreg[b * 8 + j] = *reinterpret_cast<const bf16x8*>(B + (int64_t)(kin + kg * 8 + j) * ldb + n0 + ng * 8);
       }
     }
-    kin += BK;
-    if (kin >= a.seg[seg].K) { kin = 0; ++seg; }
+    if (PF2) {                 // branch-free callers load past the end: stay on the last slice then
+      if (kin + BK < a.seg[seg].K) kin += BK;
+      else if (seg + 1 < a.nseg) { kin = 0; ++seg; }
+    } else {
+      kin += BK;
+      if (kin >= a.seg[seg].K) { kin = 0; ++seg; }
+    }
   };
-  auto store_slice = [&](int stage) {
+  auto store_slice = [&](int stage, auto set_tag) {
+    bf16x8 (&xreg)[C::XCH] = xregs[decltype(set_tag)::value];
+    bf16x8 (&wreg)[C::WCH] = wregs[decltype(set_tag)::value];
     char* xs = smem + stage * C::STAGE;
     char* ws = xs + BM * 128;
 #pragma unroll
@@ -265,14 +278,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(GemmA
     else wrow[ni] = wn * C::WTN + ni * 32 + l31;
   }
 
-  load_slice();
-  store_slice(0);
-  __syncthreads();
-
-  for (int kt = 0; kt < nslices; ++kt) {
-    const bool more = kt + 1 < nslices;
-    if (more) load_slice();
-    const char* xs = smem + (kt & 1) * C::STAGE;
+  auto multiply = [&](int stage) {
+    const char* xs = smem + stage * C::STAGE;
     const char* ws = xs + BM * 128;
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
@@ -289,8 +296,45 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(GemmA
         for (int mi = 0; mi < C::MI; ++mi)
           acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ni], xf[mi], acc[ni][mi], 0, 0, 0);
     }
-    if (more) store_slice((kt + 1) & 1);
+  };
+  using Set0 = std::integral_constant<int, 0>;
+  using Set1 = std::integral_constant<int, NSET - 1>;
+  if constexpr (PF2) {
+    // Slice kt is multiplied from LDS stage kt & 1 while slice kt + 1 sits in register set (kt + 1) & 1 (stored to the
+    // other stage at the end of the step) and slice kt + 2 is being loaded into set kt & 1.  No branch in a step: loads
+    // past the end re-read the last slice, the store after the last multiply fills a stage nobody reads -- so the
+    // compiler's wait before a store counts exactly the newer loads still in flight.
+    load_slice(Set0{});
+    load_slice(Set1{});
+    store_slice(0, Set0{});
     __syncthreads();
+    int kt = 0;
+    for (; kt + 1 < nslices; kt += 2) {
+      load_slice(Set0{});
+      __builtin_amdgcn_sched_barrier(0);     // the loads stay at the top of the step: sunk below the multiply they
+      multiply(0);                           // would be issued one step late
+      __builtin_amdgcn_sched_barrier(0);
+      store_slice(1, Set1{});
+      __syncthreads();
+      load_slice(Set1{});
+      __builtin_amdgcn_sched_barrier(0);
+      multiply(1);
+      __builtin_amdgcn_sched_barrier(0);
+      store_slice(0, Set0{});
+      __syncthreads();
+    }
+    if (kt < nslices) multiply(0);
+  } else {
+    load_slice(Set0{});
+    store_slice(0, Set0{});
+    __syncthreads();
+    for (int kt = 0; kt < nslices; ++kt) {
+      const bool more = kt + 1 < nslices;
+      if (more) load_slice(Set0{});
+      multiply(kt & 1);
+      if (more) store_slice((kt + 1) & 1, Set0{});
+      __syncthreads();
+    }
   }
 
   // ---- epilogue: lane owns token row (lane & 31) of each 32-row block and, per register
@@ -735,6 +779,20 @@ hipError_t mfma_gemm(const GemmArgs& a, hipStream_t st, int tile) {
   }
   if (a.nbcol > 0 || a.epi == EPI_ROPE) return hipErrorInvalidValue;   // only the direct-to-LDS kernel implements these
   if (!a.b_is_kn) {
+    // Few rows (a 512-token micro-batch against a 4096-wide projection is 128 tiles of 128 x 128 for 256 CUs):
+    // 128 x 64 tiles double the workgroups.
+    const bool narrow = !big && !a.tile_group && a.epi != EPI_SWIGLU &&
+                        (tile == 4 || (tile == 0 && (int64_t)((a.M + 127) / 128) * (a.N / 128) < 160));
+    if (narrow) {
+      switch (a.epi) {
+        case EPI_STORE: return launch_cfg<128, 64, 2, 2, false, EPI_STORE>(a, st);
+        case EPI_RESID: return launch_cfg<128, 64, 2, 2, false, EPI_RESID>(a, st);
+        case EPI_GELU: return launch_cfg<128, 64, 2, 2, false, EPI_GELU>(a, st);
+        case EPI_SWIGLU_BWD: return launch_cfg<128, 64, 2, 2, false, EPI_SWIGLU_BWD>(a, st);
+        case EPI_GELU_BWD: return launch_cfg<128, 64, 2, 2, false, EPI_GELU_BWD>(a, st);
+        default: return hipErrorInvalidValue;
+      }
+    }
     switch (a.epi) {
       case EPI_STORE: return big ? launch_cfg<256, 256, 2, 2, false, EPI_STORE>(a, st) : launch_cfg<128, 128, 2, 2, false, EPI_STORE>(a, st);
       case EPI_RESID: return big ? launch_cfg<256, 256, 2, 2, false, EPI_RESID>(a, st) : launch_cfg<128, 128, 2, 2, false, EPI_RESID>(a, st);
