@@ -75,6 +75,8 @@ struct sv_ctx {
   std::vector<sv_block_weights> prepared;   // the weights sv_prepare_weights transposed (empty: none)
   float* delta;
   ScorePartial* score_scratch;
+  float* split_ws;     // fp32 partial products of the split-k GEMMs (bf16 matrix-core path, few tokens against a long k)
+  size_t split_ws_floats;
   float* sw_w1;        // [kSwMaxClaims, kSwMaxDirs] per-direction sums (SV_FLAG_SLICED_W)
   float* sw_proj;      // kSwSlots * kSwMaxDirs rows of sw_padded_len(max_tokens) floats
   size_t sw_proj_floats;
@@ -145,6 +147,14 @@ size_t carve(sv_ctx* c, char* base) {
   Arena a; a.base = base;
   c->rope_cs = (float*)a.take((size_t)c->max_seq * (c->hd / 2) * 2 * sizeof(float));
   c->score_scratch = (ScorePartial*)a.take(kScoreScratchElems * sizeof(ScorePartial));
+  c->split_ws = nullptr; c->split_ws_floats = 0;
+  if (d.dtype == SV_BF16 && !(c->flags & SV_FLAG_PLAIN_KERNELS)) {
+    // up to 8 partial products of the widest product a split can serve (below 160 tiles of 128 x 128), and no more
+    // than this context's token bound allows
+    const size_t widest = std::max(std::max(D, (size_t)c->Dq), std::max(Fd, (size_t)d.ffn_hidden));
+    c->split_ws_floats = std::min((size_t)8 * 160 * 128 * 128, (size_t)8 * T * widest);
+    c->split_ws = (float*)a.take(c->split_ws_floats * sizeof(float));
+  }
   c->sw_w1 = nullptr; c->sw_proj = nullptr; c->sw_proj_floats = 0;
   if (c->flags & SV_FLAG_SLICED_W) {
     c->sw_w1 = (float*)a.take((size_t)kSwMaxClaims * kSwMaxDirs * sizeof(float));
@@ -278,7 +288,11 @@ inline char* at(void* p, int64_t elems, int es) { return (char*)p + elems * es; 
 inline const char* at(const void* p, int64_t elems, int es) { return (const char*)p + elems * es; }
 
 hipError_t gemm(sv_ctx* c, const GemmArgs& a, hipStream_t st) {
-  if (c->d.dtype == SV_BF16 && !(c->flags & SV_FLAG_PLAIN_KERNELS) && mfma_gemm_supported(a)) return mfma_gemm(a, st);
+  if (c->d.dtype == SV_BF16 && !(c->flags & SV_FLAG_PLAIN_KERNELS) && mfma_gemm_supported(a)) {
+    GemmArgs g = a;
+    g.split_ws = c->split_ws; g.split_ws_floats = (int64_t)c->split_ws_floats;
+    return mfma_gemm(g, st);
+  }
   return plain_gemm(a, c->d.dtype, st);
 }
 

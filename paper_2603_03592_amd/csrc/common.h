@@ -168,6 +168,8 @@ struct GemmArgs {
   // read from device memory (*m_dev <= M, a multiple of 256) and M only bounds the launch
   const int32_t* tile_group; int64_t group_stride;
   const int32_t* m_dev;
+  // optional: fp32 scratch for split-k partial products (small row counts against a long k); none = never split
+  float* split_ws; int64_t split_ws_floats;
 };
 
 // kernels_plain.hip: any shape, fp32 math, E = float | bf16 by `dtype`

@@ -19,6 +19,7 @@
 //
 // Workgroup ids are remapped so that each XCD (ids congruent mod 8) works on a contiguous run
 // of tiles, ordered in groups of GROUP_M row tiles, to keep operand panels hot in its L2.
+#include <algorithm>
 #include <type_traits>
 
 #include "common.h"
@@ -147,9 +148,12 @@ __device__ __forceinline__ void epilogue_rows(const GemmArgs& a, int M, const f3
   }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool KN, int EPI>
+// SPLIT: blockIdx.y takes one of gridDim.y contiguous runs of k slices and leaves its fp32 partial product in
+// a.split_ws[blockIdx.y][M][N]; splitk_reduce_kernel adds the runs in a fixed order and applies the epilogue.
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool KN, int EPI, bool SPLIT = false>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(GemmArgs a, int tiles_m, int tiles_n) {
   constexpr bool DUAL = EPI == EPI_SWIGLU;
+  static_assert(!SPLIT || (!DUAL && !KN && BM * BN <= 128 * 128), "split-k serves the small [N,K] tiles");
   using C = Cfg<BM, BN, WAVES_M, WAVES_N, KN, DUAL>;
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
@@ -260,6 +264,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(GemmA
 
   int nslices = 0;
   for (int s = 0; s < a.nseg; ++s) nslices += a.seg[s].K / BK;
+  if (SPLIT) {                                       // this workgroup's run of slices; the loads start at its first
+    const int first = (int)((int64_t)nslices * blockIdx.y / gridDim.y);
+    nslices = (int)((int64_t)nslices * (blockIdx.y + 1) / gridDim.y) - first;
+    int skip = first;
+    while (skip >= a.seg[seg].K / BK) { skip -= a.seg[seg].K / BK; ++seg; }
+    kin = skip * BK;
+  }
 
   f32x16 acc[C::NI][C::MI];
 #pragma unroll
@@ -340,9 +351,50 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(GemmA
   // ---- epilogue: lane owns token row (lane & 31) of each 32-row block and, per register
   // quad q, output features 8q + 4*(lane>>5) .. +3 of each 32-feature block.
   constexpr int NIO = DUAL ? C::NI / 2 : C::NI;
+  if constexpr (SPLIT) {
+    float* part = a.split_ws + (int64_t)blockIdx.y * M * a.N;
 #pragma unroll
-  for (int mi = 0; mi < C::MI; ++mi)
-    epilogue_rows<EPI, NIO, C::NI, C::MI>(a, M, acc, mi, m0 + wm * C::WTM + mi * 32 + l31, n0 + wn * (DUAL ? C::WTN / 2 : C::WTN) + lhi * 4);
+    for (int mi = 0; mi < C::MI; ++mi) {
+      const int m = m0 + wm * C::WTM + mi * 32 + l31;
+      if (m >= M) continue;
+#pragma unroll
+      for (int ni = 0; ni < C::NI; ++ni)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          f32x4 v;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) v[i] = acc[ni][mi][q * 4 + i];
+          *reinterpret_cast<f32x4*>(part + (int64_t)m * a.N + n0 + wn * C::WTN + ni * 32 + q * 8 + lhi * 4) = v;
+        }
+    }
+  } else {
+#pragma unroll
+    for (int mi = 0; mi < C::MI; ++mi)
+      epilogue_rows<EPI, NIO, C::NI, C::MI>(a, M, acc, mi, m0 + wm * C::WTM + mi * 32 + l31, n0 + wn * (DUAL ? C::WTN / 2 : C::WTN) + lhi * 4);
+  }
+}
+
+// Sum of the split-k partial products, in the order of the splits, then the epilogue: one thread per 4 consecutive
+// output features of a row.
+template <int EPI>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmArgs a, int nsplit) {
+  const int n4 = a.N >> 2;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (int64_t)a.M * n4) return;
+  const int m = (int)(idx / n4), n = (int)(idx % n4) * 4;
+  const float* p = a.split_ws + (int64_t)m * a.N + n;
+  f32x4 sum = *reinterpret_cast<const f32x4*>(p);
+  for (int s = 1; s < nsplit; ++s) {
+    const f32x4 v = *reinterpret_cast<const f32x4*>(p + (int64_t)s * a.M * a.N);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) sum[i] += v[i];
+  }
+  float v[4], u[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) v[i] = sum[i];
+  EpiIn in;
+  epilogue_load4<EPI>(a, m, n, in);
+  epilogue_apply4<EPI>(a, m, n, v, u, in);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -704,6 +756,27 @@ hipError_t launch_cfg(const GemmArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
+// 128 x 64 tiles, nsplit runs of k slices each, then the reduction with the epilogue
+template <int EPI>
+hipError_t launch_split(const GemmArgs& a, int nsplit, hipStream_t st) {
+  using C = Cfg<128, 64, 2, 2, false, false>;
+  auto kern = gemm_mfma_kernel<128, 64, 2, 2, false, EPI_STORE, true>;
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  const int tiles_m = (a.M + 127) / 128, tiles_n = a.N / 64;
+  const int per_xcd = (tiles_m * tiles_n + 7) / 8;
+  hipLaunchKernelGGL(kern, dim3(per_xcd * 8, nsplit), dim3(C::NT), C::LDS, st, a, tiles_m, tiles_n);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int64_t threads = (int64_t)a.M * (a.N / 4);
+  hipLaunchKernelGGL(splitk_reduce_kernel<EPI>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, a, nsplit);
+  return hipGetLastError();
+}
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
 // Tile choice: the 256x256 tile has the best LDS-traffic-to-MFMA ratio; fall back to 128x128
@@ -784,6 +857,23 @@ hipError_t mfma_gemm(const GemmArgs& a, hipStream_t st, int tile) {
     const bool narrow = !big && !a.tile_group && a.epi != EPI_SWIGLU &&
                         (tile == 4 || (tile == 0 && (int64_t)((a.M + 127) / 128) * (a.N / 128) < 160));
     if (narrow) {
+      // Long k with few workgroups (the down-projection of a 512-token micro-batch: 256 workgroups x 224 slices):
+      // split k so that about three workgroups share a CU and cover each other's load-to-multiply latency.
+      int slices = 0;
+      for (int s = 0; s < a.nseg; ++s) slices += a.seg[s].K / BK;
+      const int64_t wgs = (int64_t)((a.M + 127) / 128) * (a.N / 64);
+      int nsplit = (int)std::min<int64_t>(std::min<int64_t>(8, slices / 8), (768 + wgs - 1) / wgs);
+      if (a.split_ws) nsplit = (int)std::min<int64_t>(nsplit, a.split_ws_floats / ((int64_t)a.M * a.N));
+      if (a.split_ws && tile == 0 && nsplit >= 2) {
+        switch (a.epi) {
+          case EPI_STORE: return launch_split<EPI_STORE>(a, nsplit, st);
+          case EPI_RESID: return launch_split<EPI_RESID>(a, nsplit, st);
+          case EPI_GELU: return launch_split<EPI_GELU>(a, nsplit, st);
+          case EPI_SWIGLU_BWD: return launch_split<EPI_SWIGLU_BWD>(a, nsplit, st);
+          case EPI_GELU_BWD: return launch_split<EPI_GELU_BWD>(a, nsplit, st);
+          default: return hipErrorInvalidValue;
+        }
+      }
       switch (a.epi) {
         case EPI_STORE: return launch_cfg<128, 64, 2, 2, false, EPI_STORE>(a, st);
         case EPI_RESID: return launch_cfg<128, 64, 2, 2, false, EPI_RESID>(a, st);
