@@ -75,6 +75,8 @@ struct sv_ctx {
   std::vector<sv_block_weights> prepared;   // the weights sv_prepare_weights transposed (empty: none)
   float* delta;
   ScorePartial* score_scratch;
+  float* attn_part;    // fp32 dk | dv contributions per query head of a group (backward, bf16 matrix-core path, one long sequence)
+  size_t attn_part_floats;
   float* split_ws;     // fp32 partial products of the split-k GEMMs (bf16 matrix-core path, few tokens against a long k)
   size_t split_ws_floats;
   float* sw_w1;        // [kSwMaxClaims, kSwMaxDirs] per-direction sums (SV_FLAG_SLICED_W)
@@ -154,6 +156,15 @@ size_t carve(sv_ctx* c, char* base) {
     const size_t widest = std::max(std::max(D, (size_t)c->Dq), std::max(Fd, (size_t)d.ffn_hidden));
     c->split_ws_floats = std::min((size_t)8 * 160 * 128 * 128, (size_t)8 * T * widest);
     c->split_ws = (float*)a.take(c->split_ws_floats * sizeof(float));
+  }
+  c->attn_part = nullptr; c->attn_part_floats = 0;
+  if (bwd && d.dtype == SV_BF16 && !(c->flags & SV_FLAG_PLAIN_KERNELS) && d.n_heads > d.n_kv_heads) {
+    // the head split is taken below kDkvSplitTriples (batch, kv head, key tile of 128) triples, i.e. below that many
+    // times 128 / Hkv tokens per call
+    const size_t tcap = std::min(T, (size_t)kDkvSplitTriples * 128 / (size_t)d.n_kv_heads);
+    const size_t hd_eff = attn_pad_width(c->hd) ? (size_t)attn_pad_width(c->hd) : (size_t)c->hd;   // narrow heads run zero-padded
+    c->attn_part_floats = (size_t)(d.n_heads / d.n_kv_heads) * tcap * 2 * (size_t)d.n_kv_heads * hd_eff;
+    c->attn_part = (float*)a.take(c->attn_part_floats * sizeof(float));
   }
   c->sw_w1 = nullptr; c->sw_proj = nullptr; c->sw_proj_floats = 0;
   if (c->flags & SV_FLAG_SLICED_W) {
@@ -328,7 +339,7 @@ hipError_t attn_bwd(sv_ctx* c, const BlockStash& k, int B, int S, hipStream_t st
   const sv_stage_desc& d = c->d;
   if (attn_on_mfma(c, S))
     return mfma_attn_bwd(k.qkv, c->Dqkv, k.o, c->dout, k.lse, c->delta, c->dqkv, B, S, d.n_heads, d.n_kv_heads, c->hd, d.causal,
-                         d.rope ? c->rope_cs : nullptr, st);
+                         d.rope ? c->rope_cs : nullptr, st, 0, c->attn_part, (int64_t)c->attn_part_floats);
   if (attn_padded(c, S) && c->dout_pad) {
     const int nh = d.n_heads + 2 * d.n_kv_heads;
     const int64_t T = (int64_t)B * S, ldp = (int64_t)nh * c->pad_hd, ldo = (int64_t)d.n_heads * c->pad_hd;
@@ -337,7 +348,7 @@ hipError_t attn_bwd(sv_ctx* c, const BlockStash& k, int B, int S, hipStream_t st
     if (e == hipSuccess) e = plain_pad_heads(c->dout, c->Dq, c->dout_pad, ldo, T, d.n_heads, c->hd, c->pad_hd, 1, st);
     if (e == hipSuccess)
       e = mfma_attn_bwd(c->qkv_pad, ldp, c->o_pad, c->dout_pad, k.lse, c->delta, c->dqkv_pad, B, S, d.n_heads, d.n_kv_heads, c->pad_hd, d.causal,
-                        nullptr, st, c->hd);
+                        nullptr, st, c->hd, c->attn_part, (int64_t)c->attn_part_floats);
     if (e == hipSuccess) e = plain_pad_heads(c->dqkv_pad, ldp, c->dqkv, c->Dqkv, T, nh, c->hd, c->pad_hd, 0, st);
     return e;
   }

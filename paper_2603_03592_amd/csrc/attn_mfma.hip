@@ -478,14 +478,20 @@ template <int HD, bool CAUSAL>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __restrict__ qkv, int64_t ld, const bf16* __restrict__ dout,
                                                                 const float* __restrict__ lse, const float* __restrict__ delta,
                                                                 bf16* __restrict__ dqkv, int B, int S, int H, int Hkv, float scale,
-                                                                const float* __restrict__ rope_cs) {
+                                                                const float* __restrict__ rope_cs, float* __restrict__ part) {
   constexpr int KCH = HD / 8, NKK = HD / 16, NDB = HD / 32;
   constexpr int TILE = 64 * HD * 2;
   constexpr int STAGE = 2 * TILE + 512;              // Q and dO row-major (read along the rows and transposed), lse2[64], delta[64]
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int G = H / Hkv;
   int kt, kvh, b;                                     // key tiles ascending: the longest causal columns first
-  if (!xcd_map((int)blockIdx.x, (S + 127) / 128, 1, Hkv, B, kt, kvh, b)) return;
+  // part != nullptr: one workgroup per (key tile, QUERY head); its dk / dv contribution goes to
+  // part[head within the group][token][dk | dv columns of all kv heads] in fp32 and attn_dkv_sum_kernel adds the group.
+  int hsel = 0;
+  if (part) {
+    if (!xcd_map((int)blockIdx.x, (S + 127) / 128, G, Hkv, B, kt, hsel, b)) return;
+    kvh = hsel / G;
+  } else if (!xcd_map((int)blockIdx.x, (S + 127) / 128, 1, Hkv, B, kt, kvh, b)) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l31 = lane & 31, half = lane >> 5;
   const int k0 = kt * 128, wk0 = k0 + wave * 32, mykey = wk0 + l31;
   const int Dq = H * HD, Dkv = Hkv * HD;
@@ -503,14 +509,14 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
   }
   const int qstart = CAUSAL ? (k0 / 64) * 64 : 0;
   const int nq = (S - qstart + 63) / 64;             // query tiles per head
-  const int ntiles = nq * G;
+  const int ntiles = part ? nq : nq * G;
   float lreg = 0.0f, dlreg = 0.0f;
   TileOffsets<HD> toff_q, toff_d;
   toff_q.init(ld, wave, lane);
   toff_d.init(Dq, wave, lane);
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   auto stage_tile = [&](int j, int stage) {            // Q and dO tiles straight to LDS; the two per-query scalars via registers
-    const int h = kvh * G + j / nq, q0 = qstart + (j % nq) * 64;
+    const int h = part ? hsel : kvh * G + j / nq, q0 = qstart + (j % nq) * 64;
     char* base = smem + stage * STAGE;
     const bf16* qrows = qkv + (int64_t)b * S * ld + (int64_t)h * HD;
     const bf16* drows = dout + (int64_t)b * S * Dq + (int64_t)h * HD;
@@ -619,7 +625,23 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
     dma_wait_all();
     __syncthreads();                                  // fence + barrier: the next tiles have landed for everybody
   }
-  if (mykey < S) {
+  if (mykey < S && part) {                           // the rotation is linear: undone per contribution
+    float* out = part + (((int64_t)(hsel - kvh * G) * B + b) * S + mykey) * (2 * Dkv) + (int64_t)kvh * HD;
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        float v[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = dk[db][g4 * 4 + i] * scale;
+        if (rope_cs) unrope4<HD>(v, rope_cs, mykey, db * 32 + g4 * 8 + half * 4);
+        f32x4 ok, ov;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { ok[i] = v[i]; ov[i] = dv[db][g4 * 4 + i]; }
+        *reinterpret_cast<f32x4*>(out + db * 32 + g4 * 8 + half * 4) = ok;
+        *reinterpret_cast<f32x4*>(out + Dkv + db * 32 + g4 * 8 + half * 4) = ov;
+      }
+  } else if (mykey < S) {
     bf16* out = dqkv + ((int64_t)b * S + mykey) * ld + Dq + (int64_t)kvh * HD;
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
@@ -636,6 +658,27 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
         *reinterpret_cast<bf16x4*>(out + Dkv + db * 32 + g4 * 8 + half * 4) = pv;
       }
   }
+}
+
+// dk | dv of the G query heads of every group, added in the order of the heads: one thread per 4 columns of a token
+__global__ __launch_bounds__(256) void attn_dkv_sum_kernel(const float* __restrict__ part, bf16* __restrict__ dqkv, int64_t ld, int Dq,
+                                                           int Dkv, int G, int64_t T) {
+  const int c4 = (2 * Dkv) >> 2;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= T * c4) return;
+  const int64_t t = idx / c4;
+  const int col = (int)(idx % c4) * 4;
+  const float* p = part + t * (2 * Dkv) + col;
+  f32x4 sum = *reinterpret_cast<const f32x4*>(p);
+  for (int g = 1; g < G; ++g) {
+    const f32x4 v = *reinterpret_cast<const f32x4*>(p + (int64_t)g * T * (2 * Dkv));
+#pragma unroll
+    for (int i = 0; i < 4; ++i) sum[i] += v[i];
+  }
+  bf16x4 o;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) o[i] = (bf16)sum[i];
+  *reinterpret_cast<bf16x4*>(dqkv + t * ld + Dq + col) = o;
 }
 
 }  // namespace
@@ -671,10 +714,19 @@ hipError_t mfma_attn_fwd(const void* qkv, int64_t ld, void* o, float* lse, int B
 
 
 hipError_t mfma_attn_bwd(const void* qkv, int64_t ld, const void* o, const void* dout, const float* lse, float* delta, void* dqkv, int B,
-                         int S, int H, int Hkv, int hd, int causal, const float* rope_cs, hipStream_t st, int scale_hd) {
+                         int S, int H, int Hkv, int hd, int causal, const float* rope_cs, hipStream_t st, int scale_hd, float* part_ws,
+                         int64_t part_floats) {
   if (!mfma_attn_supported(S, H, Hkv, hd, ld)) return hipErrorInvalidValue;
   if (B <= 0) return hipSuccess;
-  const dim3 gq(xcd_grid((S + BQ - 1) / BQ, H / Hkv, Hkv, B)), gk(xcd_grid((S + 127) / 128, 1, Hkv, B)), block(256);
+  // Few (batch, kv head, key tile) triples -- one long sequence -- leave CUs idle and, under the causal mask, make the
+  // first key tiles' workgroups several times longer than the average: then every query head of a group gets its own
+  // workgroup and the group is added afterwards.
+  const int G = H / Hkv, ktiles = (S + 127) / 128;
+  const int64_t triples = (int64_t)ktiles * Hkv * B;
+  const bool split = G > 1 && part_ws && (triples < kDkvSplitTriples / 2 || (triples < kDkvSplitTriples && ktiles >= 16)) &&
+                     (int64_t)G * B * S * 2 * Hkv * hd <= part_floats;
+  float* part = split ? part_ws : nullptr;
+  const dim3 gq(xcd_grid((S + BQ - 1) / BQ, G, Hkv, B)), gk(xcd_grid(ktiles, split ? G : 1, Hkv, B)), block(256);
   const float scale = 1.0f / sqrtf((float)(scale_hd > 0 ? scale_hd : hd));
 #define SV_ATTN_BWD_LAUNCH(HDV, CZ)                                                                                     \
   do {                                                                                                                  \
@@ -691,12 +743,17 @@ hipError_t mfma_attn_bwd(const void* qkv, int64_t ld, const void* o, const void*
     hipLaunchKernelGGL(kq, gq, block, lq, st, (const bf16*)qkv, ld, (const bf16*)o, (const bf16*)dout, lse, delta,      \
                        (bf16*)dqkv, B, S, H, Hkv, scale, rope_cs);                                                      \
     hipLaunchKernelGGL(kk, gk, block, lk, st, (const bf16*)qkv, ld, (const bf16*)dout, lse, delta, (bf16*)dqkv, B, S,   \
-                       H, Hkv, scale, rope_cs);                                                                         \
+                       H, Hkv, scale, rope_cs, part);                                                                   \
   } while (0)
   if (hd == 128) { if (causal) SV_ATTN_BWD_LAUNCH(128, true); else SV_ATTN_BWD_LAUNCH(128, false); }
   else if (hd == 64) { if (causal) SV_ATTN_BWD_LAUNCH(64, true); else SV_ATTN_BWD_LAUNCH(64, false); }
   else { if (causal) SV_ATTN_BWD_LAUNCH(32, true); else SV_ATTN_BWD_LAUNCH(32, false); }
 #undef SV_ATTN_BWD_LAUNCH
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || !split) return e;
+  const int64_t T = (int64_t)B * S, threads = T * (2 * Hkv * hd / 4);
+  hipLaunchKernelGGL(attn_dkv_sum_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, part, (bf16*)dqkv, ld, H * hd, Hkv * hd,
+                     G, T);
   return hipGetLastError();
 }
 
