@@ -142,7 +142,13 @@ sv_status sv_check_desc(const sv_stage_desc *desc, uint32_t flags, char *msg, in
 int64_t sv_workspace_bytes(const sv_stage_desc *desc, int64_t max_tokens, int32_t max_seq, uint32_t flags);
 
 /* Create a context on the current device for micro-batches of at most max_tokens = B*S
- * tokens and sequences of at most max_seq tokens.  Allocates the workspace (hipMalloc).   */
+ * tokens and sequences of at most max_seq tokens.  Allocates the workspace (hipMalloc): the
+ * intermediates of one block (and, in backward mode, what every block stashes and the
+ * transposed weights), the score pass's partial records, and for bf16 stages two fp32 scratch
+ * areas that only small micro-batches use -- partial products of GEMMs split along k (at most
+ * 84 MB) and, in backward mode with grouped-query attention, per-query-head dk | dv
+ * contributions (n_heads / n_kv_heads x min(max_tokens, 131072 / n_kv_heads) x 2 x kv width
+ * floats).  sv_workspace_bytes gives the total.                                              */
 sv_status sv_create(const sv_stage_desc *desc, int64_t max_tokens, int32_t max_seq, uint32_t flags,
                     sv_ctx **out);
 void sv_destroy(sv_ctx *ctx);
