@@ -115,6 +115,17 @@ def test_grouped_query_backward_both_decompositions(B):
     assert rel_l2(gg, wg) <= TOL["bf16"]
 
 
+def test_small_micro_batch_is_run_to_run_identical():
+    """500 tokens against a 3072-wide MLP: the products are split along k and the dk / dv kernel over the query heads of a
+    group; both add their parts in a fixed order, so two runs agree bit for bit (and with the oracle to tolerance)."""
+    desc = si.StageDesc(1, 512, 16, 8, 3072)
+    (h1, g1), (wh, wg), _ = run_stage(desc, 2, 250, seed=4, backward=True, weight_scale=2.0)
+    (h2, g2), _, _ = run_stage(desc, 2, 250, seed=4, backward=True, weight_scale=2.0)
+    np.testing.assert_array_equal(h1, h2)
+    np.testing.assert_array_equal(g1, g2)
+    assert rel_l2(h1, wh) <= TOL["bf16"] and rel_l2(g1, wg) <= TOL["bf16"]
+
+
 def test_forward_on_a_backward_context_and_sequence_independence():
     import paper_2603_03592_amd as sv
     desc = MFMA_BF16
