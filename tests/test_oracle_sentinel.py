@@ -228,6 +228,85 @@ def test_policy_window_and_adaptation_track_a_drifting_statistic():
     assert p.step(g) == [5]
 
 
+# ------------------------------------------------------------------ the whole-signal statistics of the loop
+def test_global_scores_closed_forms_for_every_column():
+    """Paragraph "Choice of Distance Measure": each column of global_scores against a value that follows from the
+    definition for a constructed pair, so that a slip in any one column (a missing square root, the wrong
+    denominator, a sample instead of a population deviation, a sign convention) fails here."""
+    rng = np.random.default_rng(21)
+    r = rng.standard_normal((7, 33)) + 0.4                 # a reference with a mean, so centring matters
+    n = r.size
+    # the signal itself: every statistic is 0
+    assert so.global_scores(r, r) == {"rel_l2": 0.0, "l1": 0.0, "zl2": 0.0, "sfr": 0.0}
+    # claim = alpha r: relative L2 |alpha - 1|, mean absolute difference |alpha - 1| mean|r|; the z-scores coincide
+    # for alpha > 0 and are mirrored for alpha < 0 (mean of (2 z)^2 = 4); every sign kept / flipped
+    for alpha in (1.5, 0.25, -1.0, -3.0):
+        sc = so.global_scores(alpha * r, r)
+        assert sc["rel_l2"] == pytest.approx(abs(alpha - 1.0), rel=1e-12)
+        assert sc["l1"] == pytest.approx(abs(alpha - 1.0) * np.mean(np.abs(r)), rel=1e-12)
+        assert sc["zl2"] == pytest.approx(0.0 if alpha > 0 else 4.0, abs=1e-12)
+        assert sc["sfr"] == (0.0 if alpha > 0 else 1.0)
+    # a zeroed claim: relative L2 exactly 1, and sign(0) = 0 differs from every non-zero sign
+    z = so.global_scores(np.zeros_like(r), r)
+    assert z["rel_l2"] == pytest.approx(1.0, rel=1e-15) and z["sfr"] == 1.0 and z["l1"] == pytest.approx(np.mean(np.abs(r)))
+    # a perturbation orthogonal to r with a chosen norm: relative L2 is the ratio of the two norms (Pythagoras does
+    # not enter: the numerator is the difference alone)
+    d = rng.standard_normal(r.shape)
+    d -= r * np.sum(d * r) / np.sum(r * r)
+    d *= 0.3 * np.linalg.norm(r) / np.linalg.norm(d)
+    assert so.global_scores(r + d, r)["rel_l2"] == pytest.approx(0.3, rel=1e-12)
+    # the relative L2 is NOT symmetric: the denominator is the reference's norm
+    assert so.global_scores(r, 2.0 * r)["rel_l2"] == pytest.approx(0.5, rel=1e-12)
+    assert so.global_scores(2.0 * r, r)["rel_l2"] == pytest.approx(1.0, rel=1e-12)
+
+
+def test_global_scores_zscore_column_is_two_minus_two_rho():
+    """Both signals whitened by their own scalar mean and POPULATION deviation over the flattened tensor: the mean
+    squared difference is 2 (1 - rho) with Pearson's rho, here from numpy's corrcoef (a covariance-matrix routine)
+    and from a scalar loop; with sample deviations (n - 1) the value would be (n - 1) / n times that, which the
+    last-but-one group of assertions separates from the exact identity at these sizes."""
+    rng = np.random.default_rng(22)
+    for shape in ((4, 5), (3, 11, 6)):
+        r = 2.0 + rng.standard_normal(shape)
+        c = 0.7 * r + 0.6 * rng.standard_normal(shape) - 1.0
+        rho = np.corrcoef(c.ravel(), r.ravel())[0, 1]
+        got = so.global_scores(c, r)["zl2"]
+        assert got == pytest.approx(2.0 * (1.0 - rho), rel=1e-12)
+        # scalar loop of the definition
+        cf, rf = c.ravel().tolist(), r.ravel().tolist()
+        n = len(cf)
+        mc, mr = sum(cf) / n, sum(rf) / n
+        sc_, sr_ = (sum((x - mc) ** 2 for x in cf) / n) ** 0.5, (sum((x - mr) ** 2 for x in rf) / n) ** 0.5
+        loop = sum(((x - mc) / sc_ - (y - mr) / sr_) ** 2 for x, y in zip(cf, rf)) / n
+        assert got == pytest.approx(loop, rel=1e-12)
+        # with sample deviations the value would be smaller by (n - 1) / n: the pin tells the two apart
+        assert abs(got - loop * (n - 1) / n) > 1e-3 * got
+        # whitening removes any positive affine map of either side; a negative scale mirrors the z-scores
+        assert so.global_scores(3.0 * c + 7.0, r)["zl2"] == pytest.approx(got, rel=1e-12)
+        assert so.global_scores(c, 0.1 * r - 2.0)["zl2"] == pytest.approx(got, rel=1e-12)
+        assert so.global_scores(-c, r)["zl2"] == pytest.approx(2.0 * (1.0 + rho), rel=1e-12)
+        # uncorrelated by construction: exactly 2
+        e = rng.standard_normal(shape)
+        e -= e.mean()
+        rc = r - r.mean()
+        e -= rc * np.sum(e * rc) / np.sum(rc * rc)
+        assert so.global_scores(e, r)["zl2"] == pytest.approx(2.0, rel=1e-12)
+
+
+def test_global_scores_constant_signals_have_no_zscore():
+    """A constant tensor has deviation 0 and no z-score: both constant -> 0 (nothing to tell apart), exactly one
+    constant -> 2 (the value of an uncorrelated pair); the other columns keep their plain definitions."""
+    r = np.random.default_rng(23).standard_normal((5, 8))
+    k3, k5 = np.full((5, 8), 3.0), np.full((5, 8), 5.0)
+    assert so.global_scores(k3, k5)["zl2"] == 0.0 and so.global_scores(k3, k3)["zl2"] == 0.0
+    assert so.global_scores(k3, r)["zl2"] == 2.0 and so.global_scores(r, k3)["zl2"] == 2.0
+    sc = so.global_scores(k3, k5)
+    assert sc["rel_l2"] == pytest.approx(2.0 / 5.0) and sc["l1"] == pytest.approx(2.0) and sc["sfr"] == 0.0
+    # the first warm-up step compares against m_0 = 0: the guarded denominator, every sign differs from sign(0)
+    sc0 = so.global_scores(r, np.zeros_like(r))
+    assert sc0["rel_l2"] == pytest.approx(np.linalg.norm(r) / 1e-30) and sc0["sfr"] == 1.0 and sc0["zl2"] == 2.0
+
+
 # ------------------------------------------------------------------ Alg. momentum_verification end to end
 import stage_inputs as si
 
