@@ -33,7 +33,12 @@ Readings where the paper is silent or at odds with itself (the same list is in t
   - "outside [lower, upper]" is strict (x < lower or x > upper);
   - "FP-rate << alpha" is read as FP-rate < alpha / 10;
   - the multiplier carried into a call is the one the previous call returned (k_0 on the first);
-  - the history is cut to its last l VALUES (the algorithm's slice), not l iterations;
+  - the history is cut to its last l VALUES (the algorithm's slice), not l iterations, and it is cut
+    where Alg. activation_verification / Alg. gradient_verification cut it: at the START of a
+    verified call, so that Alg. adaptive_iqr at the end of the call sees the l kept values plus
+    this call's clean ones (up to l + d values).  The warm-up listing neither cuts nor adapts; here
+    a warm-up iteration appends its values, keeps the last l, and adapts, so that fences exist
+    when the first verified call tests against them;
   - the flag test uses the bounds Alg. adaptive_iqr returned: flagged iff
     Gamma <= lower or Gamma >= upper (the ">=" of Eq. tukey_fences); before any history exists
     nothing is flagged;
@@ -134,9 +139,12 @@ class StagePolicy:
         self.q2 = [0.0] * n_metrics
         self.iqr = [np.inf] * n_metrics
 
-    def _update_fences(self):
+    def _truncate(self):
         for i in range(self.m):
             self.hist[i] = self.hist[i][-self.window:]
+
+    def _update_fences(self):
+        for i in range(self.m):
             if not self.hist[i]:
                 continue
             lo, up, k = adaptive_iqr(self.hist[i], self.k[i], self.alpha, self.grow, self.shrink,
@@ -151,6 +159,7 @@ class StagePolicy:
         for r in range(self.d):
             for i in range(self.m):
                 self.hist[i].append(float(g[r, i]))
+        self._truncate()
         self._update_fences()
 
     def step(self, gamma, skip=None, pre_tainted=None):
@@ -160,6 +169,7 @@ class StagePolicy:
         the backward pass).  Returns the list of workers tainted at this stage."""
         g = np.asarray(gamma, dtype=F64)
         tainted = []
+        self._truncate()                               # the listing's second line: before anything is examined
         for r in range(self.d):
             if self.banned[r]:
                 continue

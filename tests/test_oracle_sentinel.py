@@ -208,6 +208,31 @@ def test_policy_history_takes_clean_values_only_and_majority_flag_clears_taint()
     assert p.v[2] == 1 and len(p.hist[1]) == n1 + 3
 
 
+def test_policy_history_is_cut_at_the_start_of_a_call_not_before_the_fences_are_adapted():
+    """Alg. activation_verification cuts the history to its last l values in its second line, then appends this call's
+    clean values, then runs Alg. adaptive_iqr: the quartiles at the end of a call come from up to l + d values.
+    Hand-worked with l = 4, d = 4, k frozen at 100 (n_max = 0) so that nothing is flagged:
+      warm-up (1, 2, 3, 4)              -> q2 = 2.5, IQR = 1.5, fences 2.5 -/+ 150
+      call 1 adds (10, 11, 12, 13)      -> the EIGHT values 1, 2, 3, 4, 10, 11, 12, 13: positions 1.75 / 3.5 / 5.25 give
+                                           q1 = 2.75, q2 = 7, q3 = 11.25, IQR = 8.5, fences 7 -/+ 850
+                                           (cutting before adapting would leave 10..13: q2 = 11.5, IQR = 1.5)
+      call 2 cuts to (10, 11, 12, 13), adds (20, 21, 22, 23) -> q1 = 11.75, q2 = 16.5, q3 = 21.25, IQR = 9.5."""
+    p = so.StagePolicy(4, 1, window=4, k0=100.0, n_max=0, eps=1e-9, min_dist_mult=0.0)
+    p.warmup(np.array([[1.0], [2.0], [3.0], [4.0]]))
+    assert (p.q2[0], p.iqr[0]) == (2.5, 1.5) and (p.lower[0], p.upper[0]) == (-147.5, 152.5)
+    assert p.step(np.array([[10.0], [11.0], [12.0], [13.0]])) == []
+    assert p.hist[0] == [1.0, 2.0, 3.0, 4.0, 10.0, 11.0, 12.0, 13.0]
+    assert (p.q2[0], p.iqr[0]) == (7.0, 8.5) and (p.lower[0], p.upper[0]) == (-843.0, 857.0)
+    assert p.step(np.array([[20.0], [21.0], [22.0], [23.0]])) == []
+    assert p.hist[0] == [10.0, 11.0, 12.0, 13.0, 20.0, 21.0, 22.0, 23.0]
+    assert (p.q2[0], p.iqr[0]) == (16.5, 9.5)
+    # a warm-up iteration keeps at most l values (it has no later call to cut for it)
+    w = so.StagePolicy(4, 1, window=4, k0=100.0, n_max=0, eps=1e-9)
+    w.warmup(np.array([[1.0], [2.0], [3.0], [4.0]]))
+    w.warmup(np.array([[5.0], [6.0], [7.0], [8.0]]))
+    assert w.hist[0] == [5.0, 6.0, 7.0, 8.0] and w.q2[0] == 6.5
+
+
 def test_policy_window_and_adaptation_track_a_drifting_statistic():
     # the minimum-distance multiplier (0.15 |median|, as in the paper's configuration table) keeps the
     # fences from collapsing onto a history that only ever receives un-flagged values
