@@ -275,7 +275,9 @@ sv_status sv_sw_projection_ema(sv_ctx *ctx, float *ref_proj, const float *claim_
  * adapted to a target false-positive rate (Alg. adaptive_iqr), and the per-stage bookkeeping of
  * Alg. activation_verification / Alg. gradient_verification.  Readings: percentiles interpolate
  * linearly between order statistics; "outside" the fences is strict; the narrowing loop runs while
- * the outside fraction is below alpha / 10; the history keeps its last `window` VALUES; a deviation
+ * the outside fraction is below alpha / 10; the history is cut to its last `window` VALUES at the start of a
+ * verified step (so the fences adapted at its end see up to window + n_workers values) and at the end of a warm-up
+ * step; a deviation
  * of `severe` (paper: 100) times k * IQR from the median bans at once; after t_forgive consecutive
  * clean steps a worker's counter drops by one and the streak restarts.                          */
 typedef struct {

@@ -10,55 +10,66 @@
 #include <algorithm>
 #include <limits>
 #include <new>
+#include <utility>
 #include <vector>
 
 #include "stageverify.h"
 
 namespace {
 
-struct Quartiles { double q1, q2, q3; };
-
-// 25th / 50th / 75th percentile with linear interpolation between order statistics.
-Quartiles quartiles(std::vector<double> h) {
-  std::sort(h.begin(), h.end());
-  const size_t n = h.size();
-  auto at = [&](double p) {
-    const double pos = (double)(n - 1) * p;
+// A history window sorted once: order statistics and "how many values lie outside an interval" are then index
+// arithmetic and two binary searches, whatever the number of multipliers tried.
+struct SortedWindow {
+  std::vector<double> v;
+  explicit SortedWindow(std::vector<double> h) : v(std::move(h)) { std::sort(v.begin(), v.end()); }
+  // percentile p in [0, 1], linear interpolation between the order statistics around position (n - 1) p
+  double percentile(double p) const {
+    const double pos = (double)(v.size() - 1) * p;
     const size_t lo = (size_t)floor(pos);
-    const size_t hi = std::min(lo + 1, n - 1);
-    return h[lo] + (h[hi] - h[lo]) * (pos - (double)lo);
-  };
-  return Quartiles{at(0.25), at(0.5), at(0.75)};
-}
-
-double outside_fraction(const std::vector<double>& h, double lower, double upper) {
-  size_t cnt = 0;
-  for (double x : h) cnt += (x < lower) || (x > upper);
-  return (double)cnt / (double)h.size();
-}
+    const size_t hi = std::min(lo + 1, v.size() - 1);
+    return v[lo] + (v[hi] - v[lo]) * (pos - (double)lo);
+  }
+  // fraction of the window strictly below `lower` or strictly above `upper`
+  double outside(double lower, double upper) const {
+    const size_t below = (size_t)(std::lower_bound(v.begin(), v.end(), lower) - v.begin());
+    const size_t above = (size_t)(v.end() - std::upper_bound(v.begin(), v.end(), upper));
+    return (double)(below + above) / (double)v.size();
+  }
+};
 
 struct Fences { double lower, upper, k, q2, iqr; };
 
+// Alg. adaptive_iqr.  The widening and the narrowing search are the same walk along k <- k * factor with a different
+// factor and stopping test, so they are one routine called twice; the fences follow k as median -/+ k * IQR.
 Fences adapt(const std::vector<double>& h, double k_prev, const sv_policy_cfg& cfg) {
-  const Quartiles q = quartiles(h);
-  const double iqr = std::max(q.q3 - q.q1, cfg.eps);
-  double k = k_prev;
-  double lower = q.q2 - k * iqr, upper = q.q2 + k * iqr;
-  double fp = outside_fraction(h, lower, upper);
-  for (int it = 0; fp > cfg.alpha && it < cfg.n_max; ++it) {          // too many benign values outside: widen
-    k *= cfg.grow;
-    lower = q.q2 - k * iqr; upper = q.q2 + k * iqr;
-    fp = outside_fraction(h, lower, upper);
-  }
-  for (int it = 0; fp < cfg.alpha / 10.0 && it < cfg.n_max; ++it) {   // far fewer than the target: narrow
-    k *= cfg.shrink;
-    lower = q.q2 - k * iqr; upper = q.q2 + k * iqr;
-    fp = outside_fraction(h, lower, upper);
-  }
-  const double d_min = fabs(q.q2) * cfg.min_dist_mult;
-  lower = std::min(lower, q.q2 - d_min);
-  upper = std::max(upper, q.q2 + d_min);
-  return Fences{lower, upper, k, q.q2, iqr};
+  const SortedWindow w(h);
+  const double q1 = w.percentile(0.25), q2 = w.percentile(0.5), q3 = w.percentile(0.75);
+  const double iqr = std::max(q3 - q1, cfg.eps);
+  Fences f{0.0, 0.0, k_prev, q2, iqr};
+  double frac = 0.0;
+  auto place = [&]() {
+    f.lower = q2 - f.k * iqr; f.upper = q2 + f.k * iqr;
+    frac = w.outside(f.lower, f.upper);
+  };
+  enum Dir { kWiden, kNarrow };
+  auto walk = [&](Dir dir) {
+    const double factor = dir == kWiden ? cfg.grow : cfg.shrink;
+    for (int it = 0; it < cfg.n_max; ++it) {
+      // widen while more than the target fraction of (benign) history lies outside; narrow while far fewer do
+      const bool go = dir == kWiden ? frac > cfg.alpha : frac < cfg.alpha / 10.0;
+      if (!go) break;
+      f.k *= factor;
+      place();
+    }
+  };
+  place();
+  walk(kWiden);
+  walk(kNarrow);
+  // optional floor on the fences' distance from the median (Lambda of the metric)
+  const double d_min = fabs(q2) * cfg.min_dist_mult;
+  f.lower = std::min(f.lower, q2 - d_min);
+  f.upper = std::max(f.upper, q2 + d_min);
+  return f;
 }
 
 bool cfg_ok(const sv_policy_cfg* c) {
@@ -76,13 +87,14 @@ struct sv_policy {
   std::vector<std::vector<double>> hist;
   std::vector<Fences> f;
 
-  void update_fences() {
-    for (int i = 0; i < m; ++i) {
-      auto& h = hist[i];
+  // keep the last `window` values of every history
+  void truncate() {
+    for (auto& h : hist)
       if ((int64_t)h.size() > cfg.window) h.erase(h.begin(), h.end() - cfg.window);
-      if (h.empty()) continue;
-      f[i] = adapt(h, f[i].k, cfg);
-    }
+  }
+  void update_fences() {
+    for (int i = 0; i < m; ++i)
+      if (!hist[i].empty()) f[i] = adapt(hist[i], f[i].k, cfg);
   }
 };
 
@@ -117,6 +129,7 @@ sv_status sv_policy_warmup(sv_policy* p, const double* gamma) {
   if (!p || !gamma) return SV_EINVAL;
   for (int r = 0; r < p->d; ++r)
     for (int i = 0; i < p->m; ++i) p->hist[i].push_back(gamma[(size_t)r * p->m + i]);
+  p->truncate();        // the warm-up listing has no later call that would cut for it
   p->update_fences();
   return SV_OK;
 }
@@ -124,6 +137,9 @@ sv_status sv_policy_warmup(sv_policy* p, const double* gamma) {
 sv_status sv_policy_step(sv_policy* p, const double* gamma, const uint8_t* skip, const uint8_t* pre_tainted, uint8_t* tainted_out) {
   if (!p || !gamma || !tainted_out) return SV_EINVAL;
   int n_tainted = 0;
+  // Alg. activation_verification / Alg. gradient_verification cut the window before anybody is examined; the fences
+  // adapted at the end of the call therefore see the kept values plus this call's clean ones (up to window + d)
+  p->truncate();
   for (int r = 0; r < p->d; ++r) {
     tainted_out[r] = 0;
     if (p->banned[r]) continue;

@@ -45,6 +45,42 @@ def test_adaptive_iqr_hand_worked_example():
     assert k == pytest.approx(0.9) and lo == pytest.approx(5.0) and up == pytest.approx(95.0)
 
 
+def test_adaptive_iqr_closed_form_quartile_cases():
+    """What the routine MEANS, independent of the oracle's own arithmetic: textbook quartiles decide the fences, the
+    outside test is strict, and each search stops at the first multiplier that satisfies its side of the band."""
+    kw = dict(grow=2.0, shrink=0.5, min_dist_mult=0.0, eps=1e-9)
+    # 1..9: q1, q2, q3 = 3, 5, 7.  k = 1 -> [1, 9]: nothing strictly outside (1 and 9 sit ON the fences)
+    assert sv.adaptive_iqr(np.arange(1.0, 10.0), 1.0, alpha=0.5, n_max=0, **kw) == (1.0, 9.0, 1.0)
+    # k = 0.25 -> [4, 6]: 6 of 9 outside > 0.5 -> doubled once -> [3, 7]: 4 of 9 <= 0.5, and 4/9 >= 0.05: stays
+    assert sv.adaptive_iqr(np.arange(1.0, 10.0), 0.25, alpha=0.5, n_max=10, **kw) == (3.0, 7.0, 0.5)
+    # k = 4 -> [-11, 21], none outside < 0.05: halved until somebody is: 2 -> [-3, 13], 1 -> [1, 9] (on the fence: inside),
+    # 0.5 -> [3, 7]: 4/9 outside, stop
+    assert sv.adaptive_iqr(np.arange(1.0, 10.0), 4.0, alpha=0.5, n_max=10, **kw) == (3.0, 7.0, 0.5)
+    # the cap binds each search separately: two halvings only
+    assert sv.adaptive_iqr(np.arange(1.0, 10.0), 4.0, alpha=0.5, n_max=2, **kw) == (1.0, 9.0, 1.0)
+    # a single value: all quartiles equal it, IQR = eps
+    lo, up, k = sv.adaptive_iqr(np.array([2.0]), 3.0, alpha=0.5, n_max=0, grow=2.0, shrink=0.5, min_dist_mult=0.25, eps=0.1)
+    assert (lo, up, k) == (1.5, 2.5, 3.0)                      # 2 -/+ max(3 * 0.1, 0.25 * 2)
+
+
+def test_policy_history_is_cut_at_the_start_of_a_verified_step():
+    """The hand-worked l = 4, d = 4 run of Alg. activation_verification's order (window cut first, fences adapted on the
+    kept values plus this step's clean ones): the values are worked out in tests/test_oracle_sentinel.py."""
+    p = sv.Policy(4, 1, window=4, k0=100.0, n_max=0, eps=1e-9, min_dist_mult=0.0)
+    p.warmup(np.array([[1.0], [2.0], [3.0], [4.0]]))
+    st = p.state()
+    assert (st["lower"][0], st["upper"][0], st["history_len"][0]) == (-147.5, 152.5, 4)
+    assert p.step(np.array([[10.0], [11.0], [12.0], [13.0]])) == []
+    st = p.state()
+    assert (st["lower"][0], st["upper"][0], st["history_len"][0]) == (-843.0, 857.0, 8)
+    assert p.step(np.array([[20.0], [21.0], [22.0], [23.0]])) == []
+    st = p.state()
+    assert (st["lower"][0], st["upper"][0], st["history_len"][0]) == (16.5 - 950.0, 16.5 + 950.0, 8)
+    p.warmup(np.array([[5.0], [6.0], [7.0], [8.0]]))
+    assert p.state()["history_len"][0] == 4
+    p.close()
+
+
 @pytest.mark.parametrize("seed", range(9))
 def test_policy_stream_matches_oracle(seed):
     """A synthetic stream of per-worker statistics: benign noise with a slow drift, transient glitches, one worker
