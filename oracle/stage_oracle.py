@@ -166,14 +166,6 @@ def gelu_grad(z):
 
 
 # ----------------------------------------------------------------------------- mixture of experts
-def _round_to_bf16_f64(a):
-    """Nearest bf16 (ties to even) of float64 values, returned as float64."""
-    f = np.ascontiguousarray(a, dtype=np.float32)
-    u = f.view(np.uint32).astype(np.uint64)
-    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
-    return u.astype(np.uint32).view(np.float32).reshape(f.shape).astype(F64)
-
-
 def router_scores_from_logits(logits, kind):
     if kind == "sigmoid":
         return 1.0 / (1.0 + np.exp(-logits))
@@ -188,34 +180,28 @@ def router_scores(n, w_router, kind):
     return router_scores_from_logits(_f64(n) @ _f64(w_router).T, kind)
 
 
-def moe_route(n, w_router, desc, decision="f64"):
+def moe_route(n, w_router, desc):
     """Which experts each token uses and with what weight.
 
     Returns (sel [S, k] expert indices in decreasing score order, gates [S, k], scores [S, E],
-    margin [S]).  Both score functions increase with the logit, so "the k highest scores" is decided
-    on the logits (which do not saturate).  The DECISION (which experts) is an integer outcome of
-    floating-point numbers; with decision="bf16" it is taken the way a bf16 stage takes it -- from the
-    tokens rounded to bf16 and float32 logits -- so that a comparison with such a stage does not hinge
-    on ties the two precisions break differently.  The gate VALUES always come from the float64 scores.
-    margin is the gap between the k-th and (k+1)-th decision logit (inf when k = E): how far the token
-    is from a different routing."""
+    margin [S], logits [S, E]).  Both score functions increase with the logit, so "the k highest
+    scores" is decided on the logits (which do not saturate); ties go to the lower index.  margin is
+    the gap between the k-th and (k+1)-th logit (inf when k = E): how far the token is from a
+    different routing.  Everything is float64; a recomputation in a lower precision may legitimately
+    choose differently for a token whose margin is within that precision's error of the logits --
+    what counts as legitimate is for the comparing test to state, not for this function."""
     n = _f64(n)
     E, k = desc.n_experts, desc.top_k
-    scores = router_scores(n, w_router, desc.router_score)
-    if decision == "bf16":
-        dec = (_round_to_bf16_f64(n).astype(np.float32) @ np.asarray(w_router, dtype=np.float32).T).astype(F64)
-    elif decision == "f64":
-        dec = n @ _f64(w_router).T
-    else:
-        raise ValueError(decision)
-    order = np.argsort(-dec, axis=-1, kind="stable")            # decreasing logit, ties to the lower index
+    logits = n @ _f64(w_router).T
+    scores = router_scores_from_logits(logits, desc.router_score)
+    order = np.argsort(-logits, axis=-1, kind="stable")         # decreasing logit, ties to the lower index
     sel = order[:, :k]
-    srt = np.take_along_axis(dec, order, axis=-1)
+    srt = np.take_along_axis(logits, order, axis=-1)
     margin = srt[:, k - 1] - srt[:, k] if k < E else np.full(n.shape[0], np.inf)
     gates = np.take_along_axis(scores, sel, axis=-1)
     if desc.router_norm:
         gates = gates / np.sum(gates, axis=-1, keepdims=True)
-    return sel, gates, scores, margin
+    return sel, gates, scores, margin, logits
 
 
 def _shared_slices(w, desc):
@@ -223,10 +209,10 @@ def _shared_slices(w, desc):
     return [slice(i * F, (i + 1) * F) for i in range(getattr(desc, "n_shared", 0))]
 
 
-def moe_forward(n, w, desc, decision="f64", keep=False):
+def moe_forward(n, w, desc, keep=False):
     """The routed MLP of the tokens n [S, D] -> [S, D] (without the residual)."""
     n = _f64(n)
-    sel, gates, scores, margin = moe_route(n, w["w_router"], desc, decision)
+    sel, gates, scores, margin, logits = moe_route(n, w["w_router"], desc)
     Wg, Wu, Wd = _f64(w["w_gate"]), _f64(w["w_up"]), _f64(w["w_down"])
     out = np.zeros_like(n)
     for e in range(desc.n_experts):
@@ -239,7 +225,7 @@ def moe_forward(n, w, desc, decision="f64", keep=False):
     for sl in _shared_slices(w, desc):
         out += (silu(n @ _f64(w["ws_gate"])[sl].T) * (n @ _f64(w["ws_up"])[sl].T)) @ _f64(w["ws_down"])[:, sl].T
     if keep:
-        return out, dict(n=n, sel=sel, gates=gates, scores=scores, margin=margin)
+        return out, dict(n=n, sel=sel, gates=gates, scores=scores, margin=margin, logits=logits)
     return out
 
 
@@ -285,9 +271,8 @@ def moe_backward(dy, st, w, desc):
 
 
 # ----------------------------------------------------------------------------- one block, one sequence
-def block_forward(x, w, desc, keep=False, decision="f64"):
-    """x [S, D] of ONE sequence -> y [S, D]; with keep=True also the tensors backward needs.
-    `decision` is moe_route's (mixture-of-experts blocks only)."""
+def block_forward(x, w, desc, keep=False):
+    """x [S, D] of ONE sequence -> y [S, D]; with keep=True also the tensors backward needs."""
     x = _f64(x)
     S, D = x.shape
     H, Hkv = desc.n_heads, desc.n_kv_heads
@@ -302,7 +287,7 @@ def block_forward(x, w, desc, keep=False, decision="f64"):
     x1 = x + o @ _f64(w["wo"]).T
     n2 = norm_forward(x1, _f64(w["norm2_g"]), _f64(w["norm2_b"]), desc.norm, desc.norm_eps)
     if getattr(desc, "n_experts", 0) > 0:
-        mo = moe_forward(n2, w, desc, decision, keep)
+        mo = moe_forward(n2, w, desc, keep)
         if keep:
             return x1 + mo[0], dict(x=x, q=q, k=k, v=v, x1=x1, moe=mo[1])
         return x1 + mo
@@ -347,19 +332,19 @@ def block_backward(dy, st, w, desc):
 
 
 # ----------------------------------------------------------------------------- the stage
-def stage_forward(h, weights, desc, decision="f64"):
+def stage_forward(h, weights, desc):
     """h^(s-1) [B, S, D] -> h^(s) [B, S, D]: n_blocks blocks applied to each sequence."""
     h = _f64(h)
     out = np.empty_like(h)
     for b in range(h.shape[0]):
         x = h[b]
         for w in weights:
-            x = block_forward(x, w, desc, decision=decision)
+            x = block_forward(x, w, desc)
         out[b] = x
     return out
 
 
-def stage_routing_margin(h, weights, desc, decision="f64"):
+def stage_routing_margin(h, weights, desc):
     """Mixture-of-experts stages: per token [B, S], the smallest routing margin over the blocks of
     the stage (see moe_route).  Tokens with a small margin are those whose expert set a
     recomputation in another precision may legitimately choose differently."""
@@ -368,13 +353,13 @@ def stage_routing_margin(h, weights, desc, decision="f64"):
     for b in range(h.shape[0]):
         x, m = h[b], np.full(h.shape[1], np.inf)
         for w in weights:
-            x, st = block_forward(x, w, desc, keep=True, decision=decision)
+            x, st = block_forward(x, w, desc, keep=True)
             m = np.minimum(m, st["moe"]["margin"])
         out[b] = m
     return out
 
 
-def stage_backward(h, g_next, weights, desc, decision="f64"):
+def stage_backward(h, g_next, weights, desc):
     """(h^(s-1), dL/dh^(s)) -> (h^(s), g^(s) = dL/dh^(s-1)); the forward is recomputed and
     kept per sequence, then the blocks are walked in reverse."""
     h, g_next = _f64(h), _f64(g_next)
@@ -382,7 +367,7 @@ def stage_backward(h, g_next, weights, desc, decision="f64"):
     for b in range(h.shape[0]):
         x, kept = h[b], []
         for w in weights:
-            x, st = block_forward(x, w, desc, keep=True, decision=decision)
+            x, st = block_forward(x, w, desc, keep=True)
             kept.append(st)
         h_out[b] = x
         d = g_next[b]

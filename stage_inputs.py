@@ -164,6 +164,43 @@ def make_output_grad(desc: StageDesc, batch: int, seq: int, seed: int, micro_bat
     return to_stage_dtype(std * g.standard_normal((batch, seq, desc.d_model), dtype=np.float32), desc.dtype)
 
 
+def make_moe_case_with_routing_features(desc: StageDesc, batch: int, seq: int, seed: int, level: float = 0.5,
+                                        mlp_gain: float = 1.0):
+    """A mixture-of-experts stage and its input whose routing is decided far from any tie, BY CONSTRUCTION of the inputs
+    (no arithmetic of the layer happens here): the first E features of the residual stream are "routing features".
+
+    * input: token t carries in features 0 .. E-1 the values level * (1 .. E) in a seeded order of its own; the other
+      features are the usual N(0, 1) draws.  Multiples of 0.5 up to 8 are exact in bf16.
+    * every block: the rows of Wo, of every expert's down projection and of the shared experts' down projection that
+      write features 0 .. E-1 are zero, so those features pass through every block unchanged (the residual adds an
+      exact zero); the second norm's gain is 1 on them; router row e is the unit vector of feature p_l(e), with p_l a
+      seeded permutation per block (so the blocks of a stage route the same token differently).
+
+    With these inputs the router logit of expert e for token t is (its routing feature) / rms(x1_t): the token's E
+    logits are level * (1 .. E) / rms_t in some order, neighbouring logits are level / rms_t apart, every expert is
+    used equally often, and the gate values differ from token to token.  Returns (weights, h)."""
+    E = desc.n_experts
+    assert E > 0 and E * level <= 8.0 and desc.d_model > E
+    w = make_weights(desc, seed)
+    g = _rng(seed, 8000)
+    for l, b in enumerate(w):
+        for k in ("w_gate", "w_up", "w_down", "ws_gate", "ws_up", "ws_down"):
+            if b.get(k) is not None and mlp_gain != 1.0:
+                b[k] = to_stage_dtype(b[k] * np.float32(mlp_gain), desc.dtype)
+        b["wo"][:E, :] = 0.0
+        b["w_down"][:, :E, :] = 0.0
+        if b.get("ws_down") is not None:
+            b["ws_down"][:E, :] = 0.0
+        b["norm2_g"][:E] = 1.0
+        r = np.zeros((E, desc.d_model), dtype=np.float32)
+        r[np.arange(E), g.permutation(E)] = 1.0
+        b["w_router"] = r
+    h = make_activations(desc, batch, seq, seed)
+    ranks = np.argsort(g.random((batch, seq, E)), axis=-1)              # a permutation of 0 .. E-1 per token
+    h[..., :E] = np.float32(level) * (ranks + 1).astype(np.float32)
+    return w, to_stage_dtype(h, desc.dtype)
+
+
 # --------------------------------------------------------------------------- submissions
 def make_directions(d_model: int, n_dirs: int, seed: int = 0) -> np.ndarray:
     """Projection directions for the sliced Wasserstein statistic: n_dirs draws from N(0, I_D),

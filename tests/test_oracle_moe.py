@@ -105,38 +105,22 @@ def test_route_tie_rule_margin_and_gate_normalisation():
     n = np.array([[2.0, 1.0, 0.5, 0.0],      # experts 0 and 1 tie at the top: the lower indices win, in index order
                   [0.0, 3.0, 3.0, 0.0],      # experts 2 and 3 tie at the top
                   [1.0, 1.0, 1.0, 0.0]])     # all four tie
-    sel, gates, scores, margin = so.moe_route(n, wr, desc)
+    sel, gates, scores, margin, logits = so.moe_route(n, wr, desc)
     assert sel.tolist() == [[0, 1], [2, 3], [0, 1]]
     np.testing.assert_allclose(gates.sum(-1), 1.0, rtol=1e-15)
     sig = lambda v: 1.0 / (1.0 + math.exp(-v))
     np.testing.assert_allclose(margin, [2.0 - 1.0, 3.0 - 0.0, 0.0], rtol=1e-13, atol=1e-16)       # in logits
+    np.testing.assert_allclose(logits, [[2.0, 2.0, 1.0, 0.5], [0.0, 0.0, 3.0, 3.0], [1.0, 1.0, 1.0, 1.0]], rtol=1e-15)
     np.testing.assert_allclose(gates[0], [0.5, 0.5], rtol=1e-15)
     # without normalisation the gates are the scores themselves; top_k = E has no margin
     desc2 = dataclasses.replace(desc, router_norm=False, top_k=4)
-    sel, gates, scores, margin = so.moe_route(n, wr, desc2)
+    sel, gates, scores, margin, _ = so.moe_route(n, wr, desc2)
     np.testing.assert_allclose(gates[0], sorted([sig(2.0), sig(2.0), sig(1.0), sig(0.5)], reverse=True), rtol=1e-15)
     assert np.all(np.isinf(margin))
     # softmax scores sum to one over ALL experts
     desc3 = dataclasses.replace(desc, router_score="softmax", router_norm=False)
-    _, _, scores, _ = so.moe_route(n, wr, desc3)
+    _, _, scores, _, _ = so.moe_route(n, wr, desc3)
     np.testing.assert_allclose(scores.sum(-1), 1.0, rtol=1e-15)
-
-
-def test_bf16_decision_uses_rounded_tokens_and_keeps_f64_gates():
-    desc = si.StageDesc(1, 2, 1, 1, 8, n_experts=2, top_k=1, dtype="bf16")
-    wr = np.array([[1.0, 0.0], [0.0, 1.0]], dtype=np.float32)
-    # 1 + 2^-9 rounds to 1 in bf16 (8 significand bits), 1 + 2^-7 is representable: in float64 expert 0 wins the first
-    # token by 2^-9; after rounding the two logits tie and the lower index still wins; the second token flips to expert 1
-    n = np.array([[1.0 + 2.0 ** -9, 1.0], [1.0 + 2.0 ** -9, 1.0 + 2.0 ** -7]])
-    sel64, g64, _, m64 = so.moe_route(n, wr, desc, decision="f64")
-    selbf, gbf, _, mbf = so.moe_route(n, wr, desc, decision="bf16")
-    assert sel64.ravel().tolist() == [0, 1] and selbf.ravel().tolist() == [0, 1]
-    assert m64[0] > 0 and mbf[0] == 0.0
-    n2 = np.array([[1.0 + 2.0 ** -9, 1.0 + 2.0 ** -10]])      # f64: expert 0; bf16: both round to 1 -> tie -> expert 0
-    n3 = np.array([[1.0 + 2.0 ** -10, 1.0 + 2.0 ** -9 + 2.0 ** -8]])
-    assert so.moe_route(n3, wr, desc, "bf16")[0].item() == 1
-    sel, g, sc, _ = so.moe_route(n2, wr, desc, "bf16")
-    assert sel.item() == 0 and g.item() == sc[0, 0] == 1.0 / (1.0 + math.exp(-(1.0 + 2.0 ** -9)))
 
 
 @pytest.mark.parametrize("score,norm,k", [("sigmoid", False, 1), ("sigmoid", True, 3), ("softmax", False, 2), ("softmax", True, 2)])
@@ -182,3 +166,27 @@ def test_backward_gate_gradient_is_not_dropped():
             num[i] = np.sum(g_out[0, t] * (gt(n2[t] + dvec) - gt(n2[t] - dvec))) / (2 * eps) * sc[t]
         np.testing.assert_allclose(dn[t], num + router_part, rtol=2e-6, atol=1e-9)
     assert np.linalg.norm(g) > 0
+
+
+def test_routing_feature_inputs_decide_every_token_far_from_a_tie():
+    """The constructed case the GPU parity tests use to compare ALL tokens (stage_inputs.make_moe_case_with_routing_features):
+    in every block of the stage the oracle's logits of a token are level * (1 .. E) / rms(x1_t) in some order, so the
+    routing margin is level / rms_t -- one E-th of the largest logit -- and every expert is chosen equally often."""
+    desc = si.StageDesc(2, 64, 4, 2, 48, n_experts=8, top_k=3, n_shared=1, router_norm=True, dtype="bf16")
+    w, h = si.make_moe_case_with_routing_features(desc, 3, 50, seed=4)
+    counts = np.zeros((desc.n_blocks, desc.n_experts), dtype=int)
+    for b in range(h.shape[0]):
+        x = h[b].astype(np.float64)
+        for l, blk in enumerate(w):
+            y, st = so.block_forward(x, blk, desc, keep=True)
+            m = st["moe"]
+            rms = np.sqrt(np.mean(st["x1"] ** 2, axis=1) + desc.norm_eps)
+            np.testing.assert_allclose(np.sort(m["logits"], axis=1), 0.5 * np.arange(1, 9)[None, :] / rms[:, None], rtol=1e-12)
+            np.testing.assert_allclose(m["margin"], 0.5 / rms, rtol=1e-9)
+            assert np.all(m["margin"] >= 0.124 * np.max(np.abs(m["logits"]), axis=1))       # 1/E of the largest logit
+            assert np.array_equal(y[:, :8], x[:, :8])                                       # the features pass through unchanged
+            counts[l] += np.bincount(m["sel"].ravel(), minlength=8)
+            x = y
+    assert counts.min() > 0.7 * counts.mean()                                               # every expert used about equally
+    # the two blocks route the same token through different experts (their own permutations of the features)
+    assert not np.array_equal(w[0]["w_router"], w[1]["w_router"])
