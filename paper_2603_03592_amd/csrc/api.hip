@@ -362,8 +362,11 @@ GemmArgs nt(int M, int N, int K, const void* A, int64_t lda, const void* W, void
   return g;
 }
 
-// One block forward: x -> y.  st_ (nullable) receives what backward needs.
-sv_status block_forward(sv_ctx* c, const sv_block_weights& w, const void* x, void* y, int B, int S, BlockStash* keep, hipStream_t st) {
+// One block forward: x -> y.  keep (nullable) receives what backward needs.  Mixture-of-experts blocks write their routing
+// record and the expert outputs to keep's, else to `route` / `route_yp` (which the caller picks: the context's single
+// record on a forward-only context, block l's own on a backward context, so that sv_last_routing reads what ran last).
+sv_status block_forward(sv_ctx* c, const sv_block_weights& w, const void* x, void* y, int B, int S, BlockStash* keep, hipStream_t st,
+                        const MoeRoute* route = nullptr, void* route_yp = nullptr) {
   const sv_stage_desc& d = c->d;
   const int T = B * S, D = d.d_model, F = d.ffn_hidden, es = c->es, dt = d.dtype;
   void* qkv = keep ? keep->qkv : c->qkv;
@@ -398,8 +401,14 @@ sv_status block_forward(sv_ctx* c, const sv_block_weights& w, const void* x, voi
     // shared experts on the dense path (their output lands in y on top of the residual), then the routed experts:
     // route, gather the token rows expert by expert, two grouped products, weighted sum back into token order
     const int E = d.n_experts, K = d.top_k, Fs = d.ffn_shared;
-    const MoeRoute& r = keep ? keep->route : c->route;
-    void* yp = keep ? keep->yp : c->yp;
+    const MoeRoute& r = keep ? keep->route : (route ? *route : c->route);
+    void* yp = keep ? keep->yp : (route ? route_yp : c->yp);
+    // every launch below dereferences these: a context that did not carve them must never get here
+    if (!r.sel || !r.gate || !r.score || !r.pos || !r.row_token || !r.row_gate || !r.tile_expert || !r.meta || !r.chunk_counts ||
+        !r.chunk_base || !yp || !c->xp || !c->actp) {
+      set_err(c, "internal: the routing record of this block was not allocated");
+      return SV_EINVAL;
+    }
     const int64_t Mp = moe_padded_rows(T, K, E);
     const double rows = Td * K;
     const void* base = x1;
@@ -706,7 +715,9 @@ sv_status sv_verify_forward(sv_ctx* c, const sv_block_weights* w, const void* h_
   for (int l = 0; l < L; ++l) {
     if (l == L - 1) y = h_hat_out ? h_hat_out : c->xbuf[l & 1];
     else y = bwd ? c->xs[l] : c->xbuf[l & 1];
-    s = block_forward(c, w[l], x, y, B, S, nullptr, st);
+    // a backward context owns one routing record per block and none of its own
+    const bool own = c->moe && bwd;
+    s = block_forward(c, w[l], x, y, B, S, nullptr, st, own ? &c->stash[l].route : nullptr, own ? c->stash[l].yp : nullptr);
     if (s != SV_OK) return s;
     x = y;
   }
