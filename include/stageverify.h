@@ -152,7 +152,7 @@ int64_t sv_workspace_bytes(const sv_stage_desc *desc, int64_t max_tokens, int32_
 sv_status sv_create(const sv_stage_desc *desc, int64_t max_tokens, int32_t max_seq, uint32_t flags,
                     sv_ctx **out);
 void sv_destroy(sv_ctx *ctx);
-const char *sv_last_error(const sv_ctx *ctx);  /* ctx may be NULL: last error of a failed sv_create */
+const char *sv_last_error(const sv_ctx *ctx);  /* ctx may be NULL: last error, on this thread, of a call that takes no context */
 
 /* Forward check.  w: host array of n_blocks sv_block_weights (device pointers inside).
  * h_in [B,S,D] stage input.  claimed_h (nullable) [B,S,D]: scored against the recomputation
@@ -199,6 +199,21 @@ sv_status sv_score_and_flag(sv_ctx *ctx, const void *claims, int64_t claim_strid
                             const void *ref, int64_t ref_stride, int32_t claim_dtype, int32_t ref_dtype,
                             int64_t T, int32_t D, uint32_t metric_mask, const float *tau, int32_t reduce,
                             float *token_scores_out, sv_result *results_dev, void *stream);
+
+/* sv_score_and_flag for callers that cannot allocate device memory and so cannot call sv_create: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without the context, same kernels, same
+ * results; the partial records (one per submission and 16 tokens) live in a device array that is part of the library's
+ * code object: 65536 records = 5 MiB per GPU the library runs on, held until the process ends.  Calls no hipMalloc,
+ * hipFree or allocating library routine.  Limit: n_claims * ceil(T / 16) <= 65536 (e.g. 128 submissions of 8192
+ * tokens), SV_EUNSUPPORTED beyond it with nothing enqueued; the other limits are sv_score_and_flag's.  The first call
+ * on a device looks the array's address up (hipGetSymbolAddress): make it outside a stream capture.  All calls on one
+ * GPU share the one array: calls that overlap in time on the same GPU (two streams, two threads) race -- serialise
+ * them on one stream.  Nothing has to be cleared between calls: a call writes every record it later reads.
+ * Error text: sv_last_error(NULL) on the calling thread.                                                          */
+sv_status sv_score_and_flag_noalloc(const void *claims, int64_t claim_stride, int32_t n_claims, const void *ref,
+                                    int64_t ref_stride, int32_t claim_dtype, int32_t ref_dtype, int64_t T, int32_t D,
+                                    uint32_t metric_mask, const float *tau, int32_t reduce, float *token_scores_out,
+                                    sv_result *results_dev, void *stream);
 
 /* m [T, D] float, in place:  m <- beta m + (1-beta) mean_{i: flags[i]==0} claim_i ; unchanged
  * when every claim is flagged.  flags_dev: n_claims bytes on the device (e.g. copied from

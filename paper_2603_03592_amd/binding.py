@@ -94,6 +94,8 @@ def _load():
     L.sv_verify_backward.argtypes = [vp, C.POINTER(BlockWeightsC), vp, vp, i32, i32, vp, u32, C.POINTER(f32), i32, vp, vp, vp, vp, vp]
     L.sv_score_and_flag.restype = C.c_int
     L.sv_score_and_flag.argtypes = [vp, vp, i64, i32, vp, i64, i32, i32, i64, i32, u32, C.POINTER(f32), i32, vp, vp, vp]
+    L.sv_score_and_flag_noalloc.restype = C.c_int
+    L.sv_score_and_flag_noalloc.argtypes = [vp, i64, i32, vp, i64, i32, i32, i64, i32, u32, C.POINTER(f32), i32, vp, vp, vp]
     L.sv_score_and_sum.restype = C.c_int
     L.sv_score_and_sum.argtypes = [vp, vp, i64, i32, vp, i32, i32, i64, i32, u32, C.POINTER(f32), i32, vp, vp, C.c_char_p, vp, vp]
     L.sv_ema_from_sum.restype = C.c_int
@@ -300,6 +302,26 @@ def _dt(t) -> int:
     if t.dtype == torch.float32:
         return SV_F32
     raise TypeError(f"unsupported tensor dtype {t.dtype}")
+
+
+def score_and_flag_noalloc(claims, ref, results, metrics=("rel_l2",), tau=(0, 0, 0, 0), reduce="max_token", token_scores=None):
+    """sv_score_and_flag_noalloc: the statistic without a context and without any allocation, here or in the library.
+    claims [n, T, D]; ref [T, D] shared or [n, T, D]; results: caller's uint8 [n, 32] device tensor (one sv_result per
+    submission); token_scores: caller's float32 [n, T] device tensor or None.  Enqueued on the current stream."""
+    import torch
+    n, D = claims.shape[0], claims.shape[-1]
+    T = claims[0].numel() // D
+    shared = ref.numel() == T * D
+    assert claims.is_contiguous() and ref.is_contiguous() and results.is_contiguous()
+    assert results.dtype == torch.uint8 and results.numel() == 32 * n
+    assert token_scores is None or (token_scores.dtype == torch.float32 and token_scores.numel() == n * T and token_scores.is_contiguous())
+    st = lib.sv_score_and_flag_noalloc(_ptr(claims), T * D, n, _ptr(ref), 0 if shared else T * D, _dt(claims), _dt(ref), T, D,
+                                       _mask(metrics), _tau_array(tau),
+                                       SV_REDUCE_MAX_TOKEN if reduce == "max_token" else SV_REDUCE_GLOBAL,
+                                       _ptr(token_scores), _ptr(results), torch.cuda.current_stream().cuda_stream)
+    if st != SV_OK:
+        raise SVError(st, lib.sv_last_error(None).decode())
+    return results
 
 
 class Verifier:

@@ -92,6 +92,14 @@ struct sv_ctx {
   sv_profile prof_acc;
 };
 
+// error text of calls that take no context (read back through sv_last_error(NULL) on the same thread)
+void sv::set_global_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_create_error, sizeof(g_create_error), fmt, ap);
+  va_end(ap);
+}
+
 namespace {
 
 void set_err(sv_ctx* c, const char* fmt, ...) {

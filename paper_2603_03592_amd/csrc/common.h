@@ -105,6 +105,8 @@ hipError_t launch_score(const void* claims, int64_t claim_stride, int n_claims, 
                         int claim_dtype, int ref_dtype, int64_t T, int D, uint32_t mask, const float* tau4,
                         int reduce, float* token_scores, sv_result* results, ScorePartial* scratch,
                         int64_t scratch_elems, hipStream_t st, uint32_t skip = 0, float* sum_out = nullptr);
+// api.hip: error text for entry points without a context (sv_last_error(NULL) returns it on the same thread)
+void set_global_error(const char* fmt, ...);
 // With sum_out the score pass also writes sum_out[t, :] = sum of the submissions whose bit in `skip` is clear (fp32, index
 // order); only for the cases score_sum_supported names (one shared reference, at most 32 submissions, rows of a multiple of 2 KB).
 bool score_sum_supported(int n_claims, int64_t ref_stride, int claim_dtype, int D);

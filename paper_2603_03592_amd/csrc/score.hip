@@ -9,6 +9,8 @@
 //                         scores, and the flag Gamma > tau (Eq. test_statistic; a submission
 //                         is flagged when any enabled metric exceeds its threshold).
 //   ema_update_kernel   : Eq. momentum_def over the un-flagged submissions.
+#include <mutex>
+
 #include "common.h"
 
 namespace sv {
@@ -560,3 +562,69 @@ hipError_t launch_ema(float* m, const void* claims, int64_t claim_stride, int n_
 }
 
 }  // namespace sv
+
+// ---------------------------------------------------------------------------------------------------------------
+// The statistic for callers that cannot allocate.  sv_score_and_flag keeps its per-(submission, token tile) partial
+// records in the context's workspace, which sv_create allocates; here the same records live in a file-scope device
+// array that exists once per GPU from the moment the library's code object is loaded on it until the process ends.
+namespace {
+
+constexpr int64_t kStaticScoreRecords = 1 << 16;          // 5 MiB: e.g. 128 submissions of 8192 tokens
+static __device__ __align__(256) unsigned char scratch[kStaticScoreRecords * sizeof(sv::ScorePartial)];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mutex;
+sv::ScorePartial* g_static_ptr[kMaxDevices] = {};          // device address of `scratch` on each GPU, asked for once
+
+// The array's name is a host-side handle, not a device address: the address on the CURRENT device comes from the
+// runtime, once per device, and only that pointer is ever handed to a kernel.
+hipError_t static_score_scratch(sv::ScorePartial** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_static_mutex);
+  if (!g_static_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_static_ptr[dev] = (sv::ScorePartial*)p;
+  }
+  *out = g_static_ptr[dev];
+  return hipSuccess;
+}
+
+}  // namespace
+
+extern "C" sv_status sv_score_and_flag_noalloc(const void* claims, int64_t claim_stride, int32_t n_claims, const void* ref,
+                                               int64_t ref_stride, int32_t claim_dtype, int32_t ref_dtype, int64_t T, int32_t D,
+                                               uint32_t metric_mask, const float* tau, int32_t reduce, float* token_scores_out,
+                                               sv_result* results_dev, void* stream) {
+  using sv::set_global_error;
+  if (n_claims < 0 || T < 0 || D < 1) { set_global_error("negative size"); return SV_EINVAL; }
+  if (n_claims == 0 || T == 0) return SV_OK;
+  if (!claims || !ref || !results_dev || !tau) { set_global_error("claims, ref, tau and results_dev must be non-NULL"); return SV_EINVAL; }
+  if ((claim_dtype != SV_F32 && claim_dtype != SV_BF16) || (ref_dtype != SV_F32 && ref_dtype != SV_BF16)) {
+    set_global_error("unknown dtype");
+    return SV_EINVAL;
+  }
+  if (reduce != SV_REDUCE_GLOBAL && reduce != SV_REDUCE_MAX_TOKEN) { set_global_error("unknown reduce"); return SV_EINVAL; }
+  if (D % 8) { set_global_error("D must be a multiple of 8"); return SV_EUNSUPPORTED; }
+  if (T > 0x7fffffffLL || claim_stride < 0 || ref_stride < 0) { set_global_error("T or a stride is out of range"); return SV_EINVAL; }
+  const int64_t tiles = (T + sv::kScoreTokensPerWG - 1) / sv::kScoreTokensPerWG;
+  if (tiles * (int64_t)n_claims > kStaticScoreRecords) {
+    set_global_error("n_claims * ceil(T / %d) = %lld exceeds the %lld partial records of the static scratch: split the call or use "
+                     "sv_score_and_flag with a context", sv::kScoreTokensPerWG, (long long)(tiles * n_claims), (long long)kStaticScoreRecords);
+    return SV_EUNSUPPORTED;
+  }
+  sv::ScorePartial* records = nullptr;
+  hipError_t e = static_score_scratch(&records);
+  if (e != hipSuccess) { set_global_error("hipGetSymbolAddress of the static scratch failed: %s", hipGetErrorString(e)); return SV_EHIP; }
+  // every record the finalize step reads is written by the pass before it in this same call, so nothing has to be
+  // cleared between calls; the records of an earlier, larger call beyond this call's range are simply not read
+  e = sv::launch_score(claims, claim_stride, n_claims, ref, ref_stride, claim_dtype, ref_dtype, T, D, metric_mask, tau, reduce,
+                       token_scores_out, results_dev, records, kStaticScoreRecords, (hipStream_t)stream);
+  if (e != hipSuccess) { set_global_error("launching the score pass failed: %s", hipGetErrorString(e)); return SV_EHIP; }
+  return SV_OK;
+}
