@@ -44,7 +44,8 @@ def parse():
                     help="run the throughput sweep (single block, d_model 4096, seq x micro-batch grid, fwd+bwd) and print one "
                          "JSON line per point")
     ap.add_argument("--no-extra", action="store_true",
-                    help="default run only: skip the second measurement (the medium stage's forward + backward check)")
+                    help="default run only: skip the further legs (forward + backward on the medium stage and on the large shape, "
+                         "the 128-submission score pass against the HBM roofline)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three 1 GiB device copies (a kernel of known traffic, to scale rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
@@ -123,7 +124,8 @@ def cpu_baseline(wl, wdev, h_in, g_out, backward):
 
 def measured_traffic(workload, kernel):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary (FETCH_SIZE and
-    WRITE_SIZE runs scaled by a copy of known size), or None when no summary covers this workload/kernel."""
+    WRITE_SIZE runs scaled by a copy of known size), or None when no summary covers this workload/kernel.
+    `workload` carries the suffix _fwdbwd when a forward-only configuration is run forward + backward."""
     path = os.path.join(ROOT, "profiles", f"{workload}_{kernel}_hbm_traffic.txt")
     try:
         for line in open(path):
@@ -404,7 +406,8 @@ def main():
                    **({"n_experts": desc.n_experts, "top_k": desc.top_k, "n_shared": desc.n_shared, "router_score": desc.router_score,
                        "router_norm": desc.router_norm} if desc.n_experts else {})},
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": measured_traffic(wl.name, dom),
+                     "frac": achieved / PEAK_BF16_TFLOPS,
+                     "traffic": measured_traffic(wl.name + ("_fwdbwd" if backward and not wl.backward else ""), dom),
                      "launch_ms": d["ms"] / max(d["launches"], 1), "flop_per_launch": d["flop"] / max(d["launches"], 1)},
         "recompute": {"flop_per_step": tot_flop, "tflops": tot_flop / (ms_step * 1e-3) / 1e12,
                       "frac_of_bf16_mfma_peak": tot_flop / (ms_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
@@ -440,19 +443,32 @@ def main():
         out["cpu_baseline"] = cpu_baseline(wl, wdev, h_in, g_out, backward)
     ver.close()
     if wl.name == "large" and a.mode is None and not a.plain and not a.no_extra:
-        # the forward + backward form of the check, on the configuration that defines it (medium stage), in a child process
+        # Further legs of the same measurement, each in a child process of its own (one context at a time on the GPU):
+        #   fwd_bwd_check  the forward + backward form of the check on the configuration that defines it (medium stage);
+        #   fwd_bwd_large  the same form on the LARGEST shape (the large stage's four blocks, 8192 tokens);
+        #   score_roofline the HBM-bound half: 128 submissions of [8192, 4096] scored against one shared reference.
         import subprocess
         del wdev, h_in, first, claim_h, wc
         torch.cuda.empty_cache()
-        r = subprocess.run([sys.executable, os.path.abspath(__file__), "--workload", "medium", "--steps", str(a.steps), "--warmup",
-                            str(a.warmup), "--no-cpu-baseline"], capture_output=True, text=True)
-        if r.returncode == 0:
-            m = json.loads(r.stdout.strip().splitlines()[-1])
-            out["fwd_bwd_check"] = {"metric": m["metric"], "value": m["value"], "unit": m["unit"], "ms_per_step": m["ms_per_step"],
-                                    "config": m["config"], "roofline": m["roofline"],
-                                    "recompute_tflops": m["recompute"]["tflops"], "per_op_ms": m["recompute"]["per_op_ms"]}
-        else:
-            out["fwd_bwd_check"] = {"error": r.stderr[-300:]}
+
+        def child(extra):
+            r = subprocess.run([sys.executable, os.path.abspath(__file__), *extra, "--steps", str(a.steps), "--warmup", str(a.warmup),
+                                "--no-cpu-baseline"], capture_output=True, text=True)
+            if r.returncode != 0:
+                return None, r.stderr[-300:]
+            return json.loads(r.stdout.strip().splitlines()[-1]), None
+
+        for key, extra in (("fwd_bwd_check", ["--workload", "medium"]), ("fwd_bwd_large", ["--workload", "large", "--mode", "fwdbwd"])):
+            m, err = child(extra)
+            out[key] = {"error": err} if m is None else {
+                "metric": m["metric"], "value": m["value"], "unit": m["unit"], "ms_per_step": m["ms_per_step"], "config": m["config"],
+                "roofline": m["roofline"], "recompute_tflops": m["recompute"]["tflops"],
+                "frac_of_bf16_mfma_peak": m["recompute"]["frac_of_bf16_mfma_peak"], "per_op_ms": m["recompute"]["per_op_ms"],
+                "per_op_tflops": m["recompute"]["per_op_tflops"]}
+        m, err = child(["--score-bench"])
+        out["score_roofline"] = {"error": err} if m is None else {
+            "metric": m["metric"], "value": m["value"], "unit": m["unit"], "ms_per_step": m["ms_per_step"], "config": m["config"],
+            **m["roofline"], "rel_l2_only": m["rel_l2_only"], "ema": m["ema"]}
     print(json.dumps(out))
 
 

@@ -56,26 +56,15 @@ template <int HD> __device__ __forceinline__ int rm_pos(int c, int row) {
 // stage -- and the next tile's loads, issued at the top of a tile, were waited for in the middle of that tile's work.
 // The kernels wait for these loads themselves (dma_wait_all) before the barrier that hands a stage over; waits the
 // compiler computes for its own loads can only become stricter by loads it does not know of.
-#ifndef ATT_ASM_DMA
-#define ATT_ASM_DMA 1
-#endif
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Winline-asm"      // m0 is a reserved register: nothing else in these kernels uses it
 __device__ __forceinline__ void dma16(const char* g, unsigned off, char* lds) {       // g wave-uniform, off per lane
-#if ATT_ASM_DMA
   const unsigned l = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(__attribute__((address_space(3))) char*)lds);
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(off), "s"(g), "s"(l) : "memory", "m0");
-#else
-  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(g + off), (__attribute__((address_space(3))) void*)lds, 16, 0, 0);
-#endif
 }
 __device__ __forceinline__ void dma16(const char* g_lane, char* lds) {                // per-lane address
-#if ATT_ASM_DMA
   const unsigned l = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(__attribute__((address_space(3))) char*)lds);
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g_lane), "s"(l) : "memory", "m0");
-#else
-  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g_lane, (__attribute__((address_space(3))) void*)lds, 16, 0, 0);
-#endif
 }
 #pragma clang diagnostic pop
 // Every direct-to-LDS load of this wave has landed (to be followed by the barrier that publishes the stage).  The builtin,

@@ -1,6 +1,7 @@
 """GPU parity of the recompute (sv_verify_forward / sv_verify_backward) against the CPU oracle
-on small stages: element-wise relative L2 of the recomputed activations / gradients, and flag
-decisions bit-exact outside a +-5 % band around the threshold.
+on small stages: relative L2 of the recomputed activations / gradients over the whole tensor and per
+token, an element-by-element bound (gpu_util.assert_close), and flag decisions bit-exact outside a
++-5 % band around the threshold.
 
 Tolerances are the ones the benchmark definition states: relative L2 <= 1e-4 for fp32 stages
 and <= 2e-2 for bf16 stages (the oracle keeps fp64 throughout, the bf16 path rounds every
@@ -14,7 +15,7 @@ pytestmark = pytest.mark.gpu
 
 import stage_inputs as si
 from oracle import stage_oracle as so
-from gpu_util import dev, dev_weights, host, rel_l2
+from gpu_util import assert_close, dev, dev_weights, host, rel_l2
 
 TOL = {"f32": 1e-4, "bf16": 2e-2}
 
@@ -60,11 +61,10 @@ PAD_HD8 = dataclasses.replace(BIDIR_F32, dtype="bf16")                        # 
 @pytest.mark.parametrize("backward", [False, True], ids=["fwd", "bwd"])
 def test_fp32_stage_matches_oracle(desc, B, S, backward):
     (gh, gg), (wh, wg), h = run_stage(desc, B, S, seed=1, backward=backward, weight_scale=4.0, grad_std=1.0)
-    assert rel_l2(gh, wh) <= TOL["f32"]
-    assert np.max(so.token_rel_l2(gh, wh)) <= 2 * TOL["f32"]
+    assert_close(gh, wh, TOL["f32"], "h")
     assert rel_l2(wh, h) > 0.05                       # the stage is not close to the identity
     if backward:
-        assert rel_l2(gg, wg) <= TOL["f32"]
+        assert_close(gg, wg, TOL["f32"], "g")
 
 
 @pytest.mark.parametrize("desc,B,S", [(MFMA_BF16, 3, 80), (MFMA_GELU, 2, 136), (dataclasses.replace(LLAMA_F32, dtype="bf16"), 3, 37),
@@ -76,10 +76,9 @@ def test_fp32_stage_matches_oracle(desc, B, S, backward):
 @pytest.mark.parametrize("plain", [False, True], ids=["mfma", "plain"])
 def test_bf16_stage_matches_oracle(desc, B, S, backward, plain):
     (gh, gg), (wh, wg), h = run_stage(desc, B, S, seed=2, backward=backward, plain=plain, weight_scale=2.0)
-    assert rel_l2(gh, wh) <= TOL["bf16"]
-    assert np.max(so.token_rel_l2(gh, wh)) <= TOL["bf16"]
+    assert_close(gh, wh, TOL["bf16"], "h")
     if backward:
-        assert rel_l2(gg, wg) <= TOL["bf16"]
+        assert_close(gg, wg, TOL["bf16"], "g")
 
 
 @pytest.mark.parametrize("desc,S", [(MFMA_HD128, 4000), (MFMA_BF16, 4090)], ids=["hd128", "hd64"])
@@ -87,9 +86,8 @@ def test_long_sequence_single_micro_batch(desc, S):
     """One sequence of ~4096 tokens (the sweep's longest), ragged: 63-64 key tiles per query tile, a causal diagonal far
     from the start, and fewer (batch, kv head) pairs than XCDs for the workgroup-id mapping; forward and backward."""
     (gh, gg), (wh, wg), h = run_stage(desc, 1, S, seed=5, backward=True, weight_scale=2.0)
-    assert rel_l2(gh, wh) <= TOL["bf16"]
-    assert np.max(so.token_rel_l2(gh, wh)) <= TOL["bf16"]
-    assert rel_l2(gg, wg) <= TOL["bf16"]
+    assert_close(gh, wh, TOL["bf16"], "h")
+    assert_close(gg, wg, TOL["bf16"], "g")
 
 
 @pytest.mark.parametrize("backward", [False, True], ids=["fwd", "bwd"])
@@ -98,10 +96,9 @@ def test_wide_mlp_on_the_large_tile_with_a_ragged_row_tail(backward):
     kernel.  Forward-only and with the stash for backward, the gate/up epilogue takes two different ways."""
     desc = si.StageDesc(1, 256, 4, 2, 3072)
     (gh, gg), (wh, wg), h = run_stage(desc, 3, 700, seed=7, backward=backward, weight_scale=2.0)
-    assert rel_l2(gh, wh) <= TOL["bf16"]
-    assert np.max(so.token_rel_l2(gh, wh)) <= TOL["bf16"]
+    assert_close(gh, wh, TOL["bf16"], "h")
     if backward:
-        assert rel_l2(gg, wg) <= TOL["bf16"]
+        assert_close(gg, wg, TOL["bf16"], "g")
 
 
 @pytest.mark.parametrize("B", [4, 32], ids=["one_workgroup_per_query_head", "one_workgroup_per_kv_head"])
@@ -111,8 +108,8 @@ def test_grouped_query_backward_both_decompositions(B):
     triples) one workgroup loops over the group."""
     desc = si.StageDesc(1, 512, 16, 8, 768)
     (gh, gg), (wh, wg), h = run_stage(desc, B, 250, seed=9, backward=True, weight_scale=2.0)
-    assert rel_l2(gh, wh) <= TOL["bf16"]
-    assert rel_l2(gg, wg) <= TOL["bf16"]
+    assert_close(gh, wh, TOL["bf16"], "h")
+    assert_close(gg, wg, TOL["bf16"], "g")
 
 
 def test_small_micro_batch_is_run_to_run_identical():
@@ -123,7 +120,8 @@ def test_small_micro_batch_is_run_to_run_identical():
     (h2, g2), _, _ = run_stage(desc, 2, 250, seed=4, backward=True, weight_scale=2.0)
     np.testing.assert_array_equal(h1, h2)
     np.testing.assert_array_equal(g1, g2)
-    assert rel_l2(h1, wh) <= TOL["bf16"] and rel_l2(g1, wg) <= TOL["bf16"]
+    assert_close(h1, wh, TOL["bf16"], "h")
+    assert_close(g1, wg, TOL["bf16"], "g")
 
 
 def test_forward_on_a_backward_context_and_sequence_independence():
