@@ -468,7 +468,7 @@ def main():
         m, err = child(["--score-bench"])
         out["score_roofline"] = {"error": err} if m is None else {
             "metric": m["metric"], "value": m["value"], "unit": m["unit"], "ms_per_step": m["ms_per_step"], "config": m["config"],
-            **m["roofline"], "rel_l2_only": m["rel_l2_only"], "ema": m["ema"]}
+            "roofline": m["roofline"], "rel_l2_only": m["rel_l2_only"], "ema": m["ema"]}
     print(json.dumps(out))
 
 
