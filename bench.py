@@ -40,6 +40,9 @@ def parse():
     ap.add_argument("--loop-bench", action="store_true",
                     help="instead of the recompute check, time the paper's own verifier loop (statistics against the EMA, policy, "
                          "gradient replacement, EMA update) for 4 stages x 16 workers of the large stage's signal shape")
+    ap.add_argument("--gemm-bench", action="store_true",
+                    help="instead of the stage check, time the plain bf16 product on the large stage's four GEMM shapes: this "
+                         "library's kernel (sv_gemm_bf16) and, as a diagnostic yardstick only, the vendor BLAS behind torch.matmul")
     ap.add_argument("--sweep", action="store_true",
                     help="run the throughput sweep (single block, d_model 4096, seq x micro-batch grid, fwd+bwd) and print one "
                          "JSON line per point")
@@ -219,6 +222,54 @@ def score_bench(a):
     print(json.dumps(res))
 
 
+def gemm_bench(a):
+    """C = A B^T in bf16 (fp32 accumulation) on the four product shapes of the large stage, 8192 tokens: this library's
+    256 x 256 direct-to-LDS kernel without any fused epilogue, and beside it the vendor BLAS that torch.matmul calls.
+    The vendor figure is a diagnostic of what the chip sustains on these shapes under its power management (it is given
+    the same operands right after ours); no product path of the library calls it."""
+    import torch
+    import paper_2603_03592_amd as sv
+    torch.cuda.set_device(0)
+    shapes = [("qkv", 8192, 6144, 4096), ("out", 8192, 4096, 4096), ("gate_or_up", 8192, 14336, 4096), ("down", 8192, 4096, 14336)]
+    g = torch.Generator(device="cuda").manual_seed(0)
+    rows = []
+    for name, M, N, K in shapes:
+        x = torch.randn((M, K), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        w = (0.02 * torch.randn((N, K), generator=g, device="cuda", dtype=torch.float32)).to(torch.bfloat16)
+        out = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        wt = w.t()
+
+        def timed(fn):
+            for _ in range(a.warmup):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(a.steps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / a.steps
+
+        ms_own = timed(lambda: sv.sv_gemm_bf16(x, w, tile=1, out=out))
+        ref = torch.matmul(x, wt)
+        err = float((out.float() - ref.float()).norm() / ref.float().norm())
+        assert err < 1e-2, err
+        ms_lib = timed(lambda: torch.matmul(x, wt, out=ref))
+        fl = 2.0 * M * N * K
+        rows.append({"product": name, "M": M, "N": N, "K": K, "own_ms": ms_own, "own_tflops": fl / ms_own / 1e9,
+                     "own_frac": fl / ms_own / 1e9 / PEAK_BF16_TFLOPS, "vendor_ms": ms_lib, "vendor_tflops": fl / ms_lib / 1e9,
+                     "vendor_frac": fl / ms_lib / 1e9 / PEAK_BF16_TFLOPS, "rel_diff": err})
+    tot = sum(2.0 * r["M"] * r["N"] * r["K"] for r in rows)
+    own = sum(r["own_ms"] for r in rows)
+    print(json.dumps({
+        "metric": "bf16 GEMM TFLOP/s on the large stage's product shapes (plain product, no fused epilogue)", "value": tot / own / 1e9,
+        "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": own, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic", "config": {"workload": "gemm_large_shapes"},
+        "roofline": {"bound": "mfma", "kernel": "gemm_mfma_dma_kernel", "achieved": tot / own / 1e9, "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": tot / own / 1e9 / PEAK_BF16_TFLOPS, "traffic": None},
+        "products": rows}))
+
+
 def loop_bench(a):
     """The paper's verifier loop (EMA reference instead of recomputation): 4 stages x 16 workers, signals [8192, 4096] bf16,
     all five statistics (64 directions for the sliced Wasserstein distance).  A step is one iteration: forward over the
@@ -284,6 +335,8 @@ def main():
         return score_bench(a)
     if a.loop_bench:
         return loop_bench(a)
+    if a.gemm_bench:
+        return gemm_bench(a)
     if a.sweep:
         import subprocess
         for s_ in (512, 2048, 4096):

@@ -398,15 +398,18 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmArgs a, int nspl
 }
 
 // ------------------------------------------------------------------------------------------
-// 256x256x64 NT kernel with direct global->LDS loads (global_load_lds, 16 bytes per lane).
+// 256x256x64 NT kernel with direct global->LDS loads (buffer_load_dwordx4 ... lds, 16 bytes per lane).
 //
 // Each wave instruction copies 64 x 16 bytes to one contiguous 1 KB block of LDS = 8 tile rows;
 // the XOR swizzle is applied by choosing WHICH global chunk each lane fetches, so the LDS image
 // is the same swizzled layout the fragment reads expect and no VGPR staging or ds_write is
-// needed.  Two LDS stages; the 16 loads a wave owes for slice k+1 are issued two at a time
-// between groups of four MFMAs during the first half of slice k (an issue burst would idle the
-// matrix pipe: one wave per SIMD), and fragment reads for the next 16-wide k step are
-// interleaved the same way, double buffered in registers.  The loop is rotated so that the one
+// needed.  The loads are buffer loads: a descriptor per operand panel in scalar registers, the
+// lane's byte offset in one vector register, the slice's k offset as the scalar offset -- no
+// 64-bit address arithmetic per slice.  Two LDS stages; the 16 loads a wave owes for slice k+1 and
+// the 8 fragment reads of the next 16-wide k step are issued ONE AT A TIME BEHIND AN MFMA, in the
+// 32 cycles the matrix pipe is busy with it (one wave per SIMD: whatever is issued between two
+// MFMAs after the pipe has drained idles it; grouping them between blocks of four MFMAs measured
+// 1-3 % slower), fragments double buffered in registers.  The loop is rotated so that the one
 // full wait + barrier per slice sits at the loop top: after it the compiler's counter tracking
 // is exact and no other wait stalls the MFMA stream.
 //
@@ -450,6 +453,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
                                                                            // its wait counter with the LDS reads)
   bool d_valid = tile_of(d_vb, d_m0, d_n0);
   const char *gA, *gB, *gB2;
+  __amdgpu_buffer_rsrc_t rA, rB, rB2;     // buffer descriptors of the panels the stream reads: base = first row, no bound
   unsigned voffA[8], voffB[8];
   auto set_segment = [&]() {
     const GemmSeg& sg = a.seg[dseg];
@@ -464,6 +468,9 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
       gB = (const char*)((const bf16*)sg.B + goff + (int64_t)d_n0 * sg.ldb);
     }
     gB2 = DUAL ? (const char*)((const bf16*)a.B2 + goff + (int64_t)d_n0 * a.ldb2) : gB;
+    rA = __builtin_amdgcn_make_buffer_rsrc((void*)gA, (short)0, -1, 0x00020000);
+    rB = __builtin_amdgcn_make_buffer_rsrc((void*)gB, (short)0, -1, 0x00020000);
+    rB2 = __builtin_amdgcn_make_buffer_rsrc((void*)gB2, (short)0, -1, 0x00020000);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int r = (wave + 4 * i) * 8 + (lane >> 3), c = (lane & 7) ^ swz(r);
@@ -475,11 +482,11 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
   };
   auto dma = [&](int stage, int j) {                          // j: 0..7 activation rows, 8..15 weight rows
     const int i = j & 7;
-    const char* g = (j < 8 ? gA : ((DUAL && i >= 4) ? gB2 : gB)) + (int64_t)dk * 2;
     const unsigned off = j < 8 ? voffA[i] : voffB[i];
     char* dst = smem + stage * STAGE + (j < 8 ? 0 : BM * 128) + (wave + 4 * i) * 1024;
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(g + off),
-                                     (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+    // buffer form of the direct-to-LDS load: per-lane byte offset in a register, the slice's offset k * 2 as the scalar offset
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(j < 8 ? rA : ((DUAL && i >= 4) ? rB2 : rB), (__attribute__((address_space(3))) void*)dst, 16,
+                                             (int)off, dk * 2, 0, 0);
   };
   auto advance = [&]() {                                      // to the next slice of the stream
     dk += BK;
@@ -516,14 +523,22 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
     SV_SB;
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-      if (do_read) {
-        xn[g] = *reinterpret_cast<const bf16x8*>(xs + lds_off(xrow[g], rkk * 2 + lhi));
-        wn_[g] = *reinterpret_cast<const bf16x8*>(ws + lds_off(wrow[g], rkk * 2 + lhi));
-      }
-      if (do_dma) { dma(dstage, d0 + 2 * g); dma(dstage, d0 + 2 * g + 1); }
+      // every other instruction of the group is issued behind an MFMA, in the 32 cycles the matrix pipe is busy with it
+      acc[g][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wc[g], xc[0], acc[g][0], 0, 0, 0);
       SV_SB;
-#pragma unroll
-      for (int mi = 0; mi < MI; ++mi) acc[g][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wc[g], xc[mi], acc[g][mi], 0, 0, 0);
+      if (do_read) xn[g] = *reinterpret_cast<const bf16x8*>(xs + lds_off(xrow[g], rkk * 2 + lhi));
+      SV_SB;
+      acc[g][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wc[g], xc[1], acc[g][1], 0, 0, 0);
+      SV_SB;
+      if (do_read) wn_[g] = *reinterpret_cast<const bf16x8*>(ws + lds_off(wrow[g], rkk * 2 + lhi));
+      SV_SB;
+      acc[g][2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wc[g], xc[2], acc[g][2], 0, 0, 0);
+      SV_SB;
+      if (do_dma) dma(dstage, d0 + 2 * g);
+      SV_SB;
+      acc[g][3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wc[g], xc[3], acc[g][3], 0, 0, 0);
+      SV_SB;
+      if (do_dma) dma(dstage, d0 + 2 * g + 1);
       SV_SB;
     }
   };
