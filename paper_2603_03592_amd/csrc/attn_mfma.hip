@@ -463,40 +463,71 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   }
 }
 
+// A-operand fragment of v_mfma_f32_16x16x32_bf16 for the TRANSPOSE of a row-major 64-row tile: 16 features
+// (16 fb .. 16 fb + 15) in the row dimension, the 32 rows 32 jj .. 32 jj + 31 in the contraction.  Lane (feature lane & 15,
+// group g = lane >> 4) gets the feature's values in rows 4 g .. 4 g + 3 of the first and then of the second 16-row block
+// -- the order in which a lane of the score blocks holds its 8 probabilities (two blocks of 16 rows x 16 keys, rows
+// 4 g + r).  Two transposing reads: each group of 16 lanes takes a block of 4 rows x 16 features.
+template <int HD>
+__device__ __forceinline__ bf16x8 tr16_fragment(const char* tile, int jj, int fb, int lane) {
+  const int tr_e = (lane & 15) >> 2, tr_q = lane & 3, g = lane >> 4;
+  bf16x8 f;
+#pragma unroll
+  for (int h2 = 0; h2 < 2; ++h2) {
+    const int row = 32 * jj + 16 * h2 + 4 * g + tr_e;
+    const int chunk = 2 * fb + (tr_q >> 1);
+    const bf16x4 t4 = __builtin_bit_cast(bf16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) s16x4*)(tile + row * (HD * 2) + (rm_pos<HD>(chunk, row) << 4) + (tr_q & 1) * 8)));
+#pragma unroll
+    for (int i = 0; i < 4; ++i) f[h2 * 4 + i] = t4[i];
+  }
+  return f;
+}
+
+// dk / dv kernel.  One workgroup = 64 keys of one (sequence, kv head), 16 per wave, on v_mfma_f32_16x16x32_bf16: the
+// accumulators dK^T, dV^T of 16 keys x head_dim are 2 x head_dim / 4 registers (64 at head_dim 128), so two workgroups
+// share a CU and one wave's exponentials and LDS waits run under the other's MFMAs (with 32 keys per wave on the
+// 32x32x16 shape the kernel needed 128 accumulator registers, ran one wave per SIMD and executed its phases --
+// score products, exponentials, accumulating products, each waiting for its own LDS reads -- strictly one after the
+// other: matrix pipe busy 14 % of the cycles).  Per query tile of 64 (four blocks of 16 queries) a wave forms
+// S = Q K^T and dP = dO V^T with the QUERIES in the row dimension, so each lane owns one key column and four queries
+// per block; P and dS of two blocks are, as they sit in the lane, one B operand (32 queries deep) for
+// dV^T += dO^T P and dK^T += Q^T dS, whose A operands come out of the same row-major LDS tiles by transposing reads.
 template <int HD, bool CAUSAL>
-__global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __restrict__ qkv, int64_t ld, const bf16* __restrict__ dout,
-                                                                const float* __restrict__ lse, const float* __restrict__ delta,
-                                                                bf16* __restrict__ dqkv, int B, int S, int H, int Hkv, float scale,
-                                                                const float* __restrict__ rope_cs, float* __restrict__ part) {
-  constexpr int KCH = HD / 8, NKK = HD / 16, NDB = HD / 32;
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dkv_mfma_kernel(
+    const bf16* __restrict__ qkv, int64_t ld, const bf16* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ delta,
+    bf16* __restrict__ dqkv, int B, int S, int H, int Hkv, float scale, const float* __restrict__ rope_cs, float* __restrict__ part) {
+  constexpr int NK = HD / 32;                        // 32-deep contraction steps over the head dimension
+  constexpr int NFB = HD / 16;                       // 16-feature blocks of dK^T / dV^T
   constexpr int TILE = 64 * HD * 2;
   constexpr int STAGE = 2 * TILE + 512;              // Q and dO row-major (read along the rows and transposed), lse2[64], delta[64]
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int G = H / Hkv;
+  const int nkt = (S + 63) / 64;
   int kt, kvh, b;                                     // key tiles ascending: the longest causal columns first
   // part != nullptr: one workgroup per (key tile, QUERY head); its dk / dv contribution goes to
   // part[head within the group][token][dk | dv columns of all kv heads] in fp32 and attn_dkv_sum_kernel adds the group.
   int hsel = 0;
   if (part) {
-    if (!xcd_map((int)blockIdx.x, (S + 127) / 128, G, Hkv, B, kt, hsel, b)) return;
+    if (!xcd_map((int)blockIdx.x, nkt, G, Hkv, B, kt, hsel, b)) return;
     kvh = hsel / G;
-  } else if (!xcd_map((int)blockIdx.x, (S + 127) / 128, 1, Hkv, B, kt, kvh, b)) return;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l31 = lane & 31, half = lane >> 5;
-  const int k0 = kt * 128, wk0 = k0 + wave * 32, mykey = wk0 + l31;
+  } else if (!xcd_map((int)blockIdx.x, nkt, 1, Hkv, B, kt, kvh, b)) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l15 = lane & 15, lg = lane >> 4;
+  const int k0 = kt * 64, wk0 = k0 + wave * 16, mykey = wk0 + l15;
   const int Dq = H * HD, Dkv = Hkv * HD;
   const float c2 = scale * 1.4426950408889634f;
   const int krow = min(mykey, S - 1);
 
-  bf16x8 kf[NKK], vf[NKK];
+  bf16x8 kf[NK], vf[NK];                              // this lane's key / value row, 8 features of every 32
   {
     const bf16* kp = qkv + ((int64_t)b * S + krow) * ld + Dq + (int64_t)kvh * HD;
 #pragma unroll
-    for (int kk = 0; kk < NKK; ++kk) {
-      kf[kk] = *reinterpret_cast<const bf16x8*>(kp + kk * 16 + half * 8);
-      vf[kk] = *reinterpret_cast<const bf16x8*>(kp + Dkv + kk * 16 + half * 8);
+    for (int kk = 0; kk < NK; ++kk) {
+      kf[kk] = *reinterpret_cast<const bf16x8*>(kp + kk * 32 + lg * 8);
+      vf[kk] = *reinterpret_cast<const bf16x8*>(kp + Dkv + kk * 32 + lg * 8);
     }
   }
-  const int qstart = CAUSAL ? (k0 / 64) * 64 : 0;
+  const int qstart = CAUSAL ? k0 : 0;                // a multiple of 64
   const int nq = (S - qstart + 63) / 64;             // query tiles per head
   const int ntiles = part ? nq : nq * G;
   float lreg = 0.0f, dlreg = 0.0f;
@@ -531,11 +562,11 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
     }
   };
 
-  f32x16 dk[NDB], dv[NDB];
+  f32x4 dk[NFB], dv[NFB];
 #pragma unroll
-  for (int i = 0; i < NDB; ++i)
+  for (int i = 0; i < NFB; ++i)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { dk[i][r] = 0.0f; dv[i][r] = 0.0f; }
+    for (int r = 0; r < 4; ++r) { dk[i][r] = 0.0f; dv[i][r] = 0.0f; }
 
   if (ntiles > 0) {
     stage_tile(0, 0);
@@ -547,105 +578,85 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
     const bool more = j + 1 < ntiles;
     if (more) stage_tile(j + 1, (j + 1) & 1);
     const int q0 = qstart + (j % nq) * 64;
-    if (!CAUSAL || q0 + 63 >= wk0) {
-      const char* qs = smem + (j & 1) * STAGE;
-      const char* ds_ = qs + TILE;
-      const float* ls = reinterpret_cast<const float*>(qs + 2 * TILE);
-      const float* dls = ls + 64;
-      f32x16 s[2], dp[2];
+    const char* qs = smem + (j & 1) * STAGE;
+    const char* ds_ = qs + TILE;
+    const float* ls = reinterpret_cast<const float*>(qs + 2 * TILE);
+    const float* dls = ls + 64;
+    const bool need_mask = (CAUSAL && q0 < wk0 + 15) || (q0 + 64 > S);
+    bf16x8 pf[2], dsf[2];                            // P and dS of the tile: [32-query half], as the B operands below
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
+    for (int jj = 0; jj < 2; ++jj) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { s[t][r] = 0.0f; dp[t][r] = 0.0f; }
-        const int row = t * 32 + l31;
-        // fragments one k step ahead of the MFMAs that use them
-        bf16x8 qf[2], df[2];
-        qf[0] = *reinterpret_cast<const bf16x8*>(qs + rm_off<HD>(row, half));
-        df[0] = *reinterpret_cast<const bf16x8*>(ds_ + rm_off<HD>(row, half));
+      for (int h2 = 0; h2 < 2; ++h2) {
+        const int qb = 2 * jj + h2, row = qb * 16 + l15;
+        f32x4 s = {0.0f, 0.0f, 0.0f, 0.0f}, dp = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-        for (int kk = 0; kk < NKK; ++kk) {
-          if (kk + 1 < NKK) {
-            qf[(kk + 1) & 1] = *reinterpret_cast<const bf16x8*>(qs + rm_off<HD>(row, (kk + 1) * 2 + half));
-            df[(kk + 1) & 1] = *reinterpret_cast<const bf16x8*>(ds_ + rm_off<HD>(row, (kk + 1) * 2 + half));
+        for (int kk = 0; kk < NK; ++kk) {
+          const bf16x8 qf = *reinterpret_cast<const bf16x8*>(qs + rm_off<HD>(row, kk * 4 + lg));
+          const bf16x8 df = *reinterpret_cast<const bf16x8*>(ds_ + rm_off<HD>(row, kk * 4 + lg));
+          s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf, kf[kk], s, 0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_16x16x32_bf16(df, vf[kk], dp, 0, 0, 0);
+        }
+        // this lane: key mykey, queries q0 + 16 qb + 4 lg + r
+        if (need_mask) {                             // one uniform branch; a masked score of -inf gives p = 0 below
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int q = q0 + qb * 16 + 4 * lg + r;
+            if ((CAUSAL && q < mykey) || q >= S) s[r] = -INFINITY;
           }
-          __builtin_amdgcn_sched_barrier(0);           // the scheduler would otherwise sink the reads back to their uses
-          s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[kk & 1], kf[kk], s[t], 0, 0, 0);
-          dp[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(df[kk & 1], vf[kk], dp[t], 0, 0, 0);
-          __builtin_amdgcn_sched_barrier(0);
+        }
+        const f32x4 l4 = *reinterpret_cast<const f32x4*>(ls + qb * 16 + 4 * lg);
+        const f32x4 d4 = *reinterpret_cast<const f32x4*>(dls + qb * 16 + 4 * lg);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float p = __builtin_amdgcn_exp2f(fmaf(s[r], c2, -l4[r]));
+          pf[jj][h2 * 4 + r] = (bf16)p;
+          dsf[jj][h2 * 4 + r] = (bf16)(p * (dp[r] - d4[r]));
         }
       }
-      const bool need_mask = (CAUSAL && q0 < wk0 + 31) || (q0 + 64 > S);
-      bf16x8 pf[4], dsf[4];
-      if (need_mask) {                               // one uniform branch; a masked score of -inf gives p = 0 below
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int q = q0 + t * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-            if ((CAUSAL && q < mykey) || q >= S) s[t][r] = -INFINITY;
-          }
-      }
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          const int qq = t * 32 + 8 * r4 + 4 * half;           // 4 consecutive queries of this register quad
-          const f32x4 l4 = *reinterpret_cast<const f32x4*>(ls + qq);
-          const f32x4 d4 = *reinterpret_cast<const f32x4*>(dls + qq);
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const int r = r4 * 4 + i;
-            const float p = __builtin_amdgcn_exp2f(fmaf(s[t][r], c2, -l4[i]));
-            pf[t * 2 + (r >> 3)][r & 7] = (bf16)p;
-            dsf[t * 2 + (r >> 3)][r & 7] = (bf16)(p * (dp[t][r] - d4[i]));
-          }
-        }
-#pragma unroll
-      for (int g = 0; g < 4; ++g)
-#pragma unroll
-        for (int db = 0; db < NDB; ++db) {
-          const bf16x8 dtf = tr_fragment<HD>(ds_, g, db, lane);
-          const bf16x8 qtf = tr_fragment<HD>(qs, g, db, lane);
-          dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dtf, pf[g], dv[db], 0, 0, 0);
-          dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qtf, dsf[g], dk[db], 0, 0, 0);
-        }
     }
+#pragma unroll
+    for (int fb = 0; fb < NFB; ++fb)
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj) {
+        const bf16x8 dtf = tr16_fragment<HD>(ds_, jj, fb, lane);
+        const bf16x8 qtf = tr16_fragment<HD>(qs, jj, fb, lane);
+        dv[fb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dtf, pf[jj], dv[fb], 0, 0, 0);
+        dk[fb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qtf, dsf[jj], dk[fb], 0, 0, 0);
+      }
     if (more) store_scalars((j + 1) & 1);
     dma_wait_all();
     __syncthreads();                                  // fence + barrier: the next tiles have landed for everybody
   }
+  // this lane: key mykey, features 16 fb + 4 lg .. + 3 of dK and dV
   if (mykey < S && part) {                           // the rotation is linear: undone per contribution
     float* out = part + (((int64_t)(hsel - kvh * G) * B + b) * S + mykey) * (2 * Dkv) + (int64_t)kvh * HD;
 #pragma unroll
-    for (int db = 0; db < NDB; ++db)
+    for (int fb = 0; fb < NFB; ++fb) {
+      float v[4];
 #pragma unroll
-      for (int g4 = 0; g4 < 4; ++g4) {
-        float v[4];
+      for (int i = 0; i < 4; ++i) v[i] = dk[fb][i] * scale;
+      if (rope_cs) unrope4<HD>(v, rope_cs, mykey, fb * 16 + lg * 4);
+      f32x4 ok;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) v[i] = dk[db][g4 * 4 + i] * scale;
-        if (rope_cs) unrope4<HD>(v, rope_cs, mykey, db * 32 + g4 * 8 + half * 4);
-        f32x4 ok, ov;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) { ok[i] = v[i]; ov[i] = dv[db][g4 * 4 + i]; }
-        *reinterpret_cast<f32x4*>(out + db * 32 + g4 * 8 + half * 4) = ok;
-        *reinterpret_cast<f32x4*>(out + Dkv + db * 32 + g4 * 8 + half * 4) = ov;
-      }
+      for (int i = 0; i < 4; ++i) ok[i] = v[i];
+      *reinterpret_cast<f32x4*>(out + fb * 16 + lg * 4) = ok;
+      *reinterpret_cast<f32x4*>(out + Dkv + fb * 16 + lg * 4) = dv[fb];
+    }
   } else if (mykey < S) {
     bf16* out = dqkv + ((int64_t)b * S + mykey) * ld + Dq + (int64_t)kvh * HD;
 #pragma unroll
-    for (int db = 0; db < NDB; ++db)
+    for (int fb = 0; fb < NFB; ++fb) {
+      float v[4];
 #pragma unroll
-      for (int g4 = 0; g4 < 4; ++g4) {
-        float v[4];
+      for (int i = 0; i < 4; ++i) v[i] = dk[fb][i] * scale;
+      if (rope_cs) unrope4<HD>(v, rope_cs, mykey, fb * 16 + lg * 4);
+      bf16x4 pk, pv;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) v[i] = dk[db][g4 * 4 + i] * scale;
-        if (rope_cs) unrope4<HD>(v, rope_cs, mykey, db * 32 + g4 * 8 + half * 4);
-        bf16x4 pk, pv;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) { pk[i] = (bf16)v[i]; pv[i] = (bf16)dv[db][g4 * 4 + i]; }
-        *reinterpret_cast<bf16x4*>(out + db * 32 + g4 * 8 + half * 4) = pk;
-        *reinterpret_cast<bf16x4*>(out + Dkv + db * 32 + g4 * 8 + half * 4) = pv;
-      }
+      for (int i = 0; i < 4; ++i) { pk[i] = (bf16)v[i]; pv[i] = (bf16)dv[fb][i]; }
+      *reinterpret_cast<bf16x4*>(out + fb * 16 + lg * 4) = pk;
+      *reinterpret_cast<bf16x4*>(out + Dkv + fb * 16 + lg * 4) = pv;
+    }
   }
 }
 
@@ -715,7 +726,7 @@ hipError_t mfma_attn_bwd(const void* qkv, int64_t ld, const void* o, const void*
   const bool split = G > 1 && part_ws && (triples < kDkvSplitTriples / 2 || (triples < kDkvSplitTriples && ktiles >= 16)) &&
                      (int64_t)G * B * S * 2 * Hkv * hd <= part_floats;
   float* part = split ? part_ws : nullptr;
-  const dim3 gq(xcd_grid((S + BQ - 1) / BQ, G, Hkv, B)), gk(xcd_grid(ktiles, split ? G : 1, Hkv, B)), block(256);
+  const dim3 gq(xcd_grid((S + BQ - 1) / BQ, G, Hkv, B)), gk(xcd_grid((S + 63) / 64, split ? G : 1, Hkv, B)), block(256);
   const float scale = 1.0f / sqrtf((float)(scale_hd > 0 ? scale_hd : hd));
 #define SV_ATTN_BWD_LAUNCH(HDV, CZ)                                                                                     \
   do {                                                                                                                  \
