@@ -167,9 +167,9 @@ size_t carve(sv_ctx* c, char* base) {
   }
   c->attn_part = nullptr; c->attn_part_floats = 0;
   if (bwd && d.dtype == SV_BF16 && !(c->flags & SV_FLAG_PLAIN_KERNELS) && d.n_heads > d.n_kv_heads) {
-    // the head split is taken below kDkvSplitTriples (batch, kv head, key tile of 128) triples, i.e. below that many
-    // times 128 / Hkv tokens per call
-    const size_t tcap = std::min(T, (size_t)kDkvSplitTriples * 128 / (size_t)d.n_kv_heads);
+    // the head split is taken below kDkvSplitWorkgroups workgroups of at most 128 keys per (batch, kv head), i.e. below
+    // that many times 128 / Hkv tokens per call
+    const size_t tcap = std::min(T, (size_t)kDkvSplitWorkgroups * 128 / (size_t)d.n_kv_heads);
     const size_t hd_eff = attn_pad_width(c->hd) ? (size_t)attn_pad_width(c->hd) : (size_t)c->hd;   // narrow heads run zero-padded
     c->attn_part_floats = (size_t)(d.n_heads / d.n_kv_heads) * tcap * 2 * (size_t)d.n_kv_heads * hd_eff;
     c->attn_part = (float*)a.take(c->attn_part_floats * sizeof(float));

@@ -36,6 +36,15 @@ __device__ __forceinline__ bool xcd_map(int w, int n_tiles, int G, int Hkv, int 
 }
 inline int xcd_grid(int n_tiles, int G, int Hkv, int B) { return 8 * ((B * Hkv + 7) / 8) * G * n_tiles; }
 
+// Under the causal mask the work of a tile grows linearly with its index, and a launch of one workgroup per tile ends
+// with most CUs waiting for the few longest ones (at 8 x 1024 tokens, 16 heads, half of the wave slots were empty on
+// average).  A workgroup therefore takes TWO tiles, r and n - 1 - r, one after the other, so that every workgroup does
+// the same amount of work.  Workgroups per (batch, head) -- the middle tile of an odd count stands alone -- and tiles
+// of workgroup r:
+inline bool pair_tiles(int causal, int n_tiles) { return causal && n_tiles > 1; }
+__host__ __device__ __forceinline__ int paired_tiles(bool pair, int n) { return pair ? (n + 1) / 2 : n; }
+__device__ __forceinline__ int n_passes(bool pair, int n, int r) { return pair && 2 * r != n - 1 ? 2 : 1; }
+
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 
 // Position of 16-byte chunk c inside row `row` of a row-major LDS tile (an involution in c, so the staging side uses
@@ -45,7 +54,17 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 // the two 2-bit fields of the row number swapped into the XOR mask both patterns fall into 16 different 16-byte slots
 // modulo 256 bytes (rows of 128 bytes, head_dim 64: the row parity is one slot bit, the mask has three bits; rows of
 // 64 bytes, head_dim 32: two slot bits, two mask bits).
-template <int HD> __device__ __forceinline__ int rm_pos(int c, int row) {
+//
+// SW = 1 is the layout of the kernel on the 16x16x32 shape, whose reads group the lanes differently: fragments along the
+// rows take 16 consecutive rows x one chunk per 16 lanes, and a transposing read takes, per 32 lanes, 8 consecutive rows x
+// 2 consecutive chunks.  There the row's low bits go to the mask's upper bits (bit 0 of the chunk index tells the two
+// chunks of a transposing read apart and must not meet a row bit that varies among its 8 rows) and row bit 3 to bit 0.
+template <int HD, int SW = 0> __device__ __forceinline__ int rm_pos(int c, int row) {
+  if (SW == 1) {
+    if (HD == 128) return c ^ (((row & 7) << 1) | ((row >> 3) & 1));
+    if (HD == 64) return c ^ ((((row >> 1) & 3) << 1) | ((row >> 3) & 1));     // rows of 128 bytes: row bit 0 is a slot bit
+    return c ^ ((((row >> 2) & 1) << 1) | ((row >> 3) & 1));                    // rows of 64 bytes: row bits 0, 1 are slot bits
+  }
   if (HD == 32) return c ^ ((row >> 2) & 3);        // rows of 64 bytes: the low two row bits are slot bits already
   return HD == 128 ? (c ^ (((row & 3) << 2) | ((row >> 2) & 3))) : (c ^ ((((row >> 1) & 1) << 2) | ((row >> 2) & 3)));
 }
@@ -76,7 +95,7 @@ __device__ __forceinline__ void dma_wait_all() { __builtin_amdgcn_s_waitcnt(0x0F
 // row) go global -> LDS
 // row-major with global_load_lds: no registers, no LDS write instructions.  One wave instruction moves 1 KB = RPI rows;
 // lane (row, position p) fetches the 16-byte chunk that belongs at position p of its row under rm_pos.  256 threads.
-template <int HD>
+template <int HD, int SW = 0>
 __device__ __forceinline__ void stage_two_tiles(const bf16* a, int64_t lda, const bf16* b, int64_t ldb, int r0, int last_row, char* ta,
                                                 char* tb, int wave, int lane) {
   constexpr int KCH = HD / 8, KROW = HD * 2, RPI = 1024 / KROW, IPW = (64 / RPI) / 4;
@@ -85,7 +104,7 @@ __device__ __forceinline__ void stage_two_tiles(const bf16* a, int64_t lda, cons
   for (int i = 0; i < IPW; ++i) {
     const int ii = wave * IPW + i, r = ii * RPI + s_row;
     const int rr = min(r, last_row - r0);                       // row within the tile, clamped to the last valid one
-    const int col = rm_pos<HD>(s_pos, r) * 8;
+    const int col = rm_pos<HD, SW>(s_pos, r) * 8;
     dma16((const char*)(a + (int64_t)r0 * lda), (unsigned)((int64_t)rr * lda + col) * 2u, ta + ii * 1024);
     dma16((const char*)(b + (int64_t)r0 * ldb), (unsigned)((int64_t)rr * ldb + col) * 2u, tb + ii * 1024);
   }
@@ -94,7 +113,7 @@ __device__ __forceinline__ void stage_two_tiles(const bf16* a, int64_t lda, cons
 // The same transfer for tiles that lie inside the valid rows, with the per-lane part of the addresses made once per
 // kernel: 32-bit byte offsets (row within the tile, swizzled chunk) that are added to a wave-uniform tile pointer, so a
 // tile costs its load instructions and a few scalar adds instead of a 64-bit multiply chain per load.
-template <int HD, int NW = 4>
+template <int HD, int NW = 4, int SW = 0>
 struct TileOffsets {
   static constexpr int KCH = HD / 8, KROW = HD * 2, RPI = 1024 / KROW, IPW = (64 / RPI) / NW;
   unsigned off[IPW];
@@ -103,16 +122,16 @@ struct TileOffsets {
 #pragma unroll
     for (int i = 0; i < IPW; ++i) {
       const int r = (wave * IPW + i) * RPI + s_row;
-      off[i] = (unsigned)((int64_t)r * ld + rm_pos<HD>(s_pos, r) * 8) * 2u;
+      off[i] = (unsigned)((int64_t)r * ld + rm_pos<HD, SW>(s_pos, r) * 8) * 2u;
     }
   }
 };
-template <int HD, int NW = 4>
-__device__ __forceinline__ void stage_tile_fast(const bf16* tile_rows, const TileOffsets<HD, NW>& o, char* dst, int wave) {
+template <int HD, int NW = 4, int SW = 0>
+__device__ __forceinline__ void stage_tile_fast(const bf16* tile_rows, const TileOffsets<HD, NW, SW>& o, char* dst, int wave) {
   const char* g = (const char*)tile_rows;           // wave-uniform: first row of the tile
 #pragma unroll
-  for (int i = 0; i < TileOffsets<HD, NW>::IPW; ++i)
-    dma16(g, o.off[i], dst + (wave * TileOffsets<HD, NW>::IPW + i) * 1024);
+  for (int i = 0; i < TileOffsets<HD, NW, SW>::IPW; ++i)
+    dma16(g, o.off[i], dst + (wave * TileOffsets<HD, NW, SW>::IPW + i) * 1024);
 }
 
 // A-operand fragment of the TRANSPOSE of a row-major 64-row tile, for MFMA g (0..3) of the tile's 64 rows and feature
@@ -138,7 +157,7 @@ __device__ __forceinline__ bf16x8 tr_fragment(const char* tile, int g, int db, i
 
 template <int HD, bool CAUSAL>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_fwd_mfma_kernel(const bf16* __restrict__ qkv, int64_t ld, bf16* __restrict__ o,
-                                                            float* __restrict__ lse, int B, int S, int H, int Hkv, float scale_log2e) {
+                                                            float* __restrict__ lse, int B, int S, int H, int Hkv, float scale_log2e, int pair) {
   constexpr int KCH = HD / 8;                       // 16-byte chunks per K row
   constexpr int KROW = HD * 2;                      // bytes per K row in LDS
   constexpr int KSTAGE = BKV * KROW, VSTAGE = BKV * KROW, STAGE = KSTAGE + VSTAGE;
@@ -147,12 +166,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
   const int nqt = (S + BQ - 1) / BQ;
   int rank, h, b;
-  if (!xcd_map((int)blockIdx.x, nqt, H / Hkv, Hkv, B, rank, h, b)) return;
-  const int qt = nqt - 1 - rank;                    // longest rows first
+  if (!xcd_map((int)blockIdx.x, paired_tiles(pair, nqt), H / Hkv, Hkv, B, rank, h, b)) return;
   const int kvh = h / (H / Hkv);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l31 = lane & 31, half = lane >> 5;
-  const int q0 = qt * BQ, wq0 = q0 + wave * 32;
   const int Dq = H * HD, Dkv = Hkv * HD;
+  TileOffsets<HD> toff;
+  toff.init(ld, wave, lane);
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  for (int pass = 0; pass < n_passes(pair, nqt, rank); ++pass) {
+  const int qt = pass == 0 ? nqt - 1 - rank : rank;
+  const int q0 = qt * BQ, wq0 = q0 + wave * 32;
   const bf16* qbase = qkv + (int64_t)b * S * ld + (int64_t)h * HD;
   const bf16* kbase = qkv + (int64_t)b * S * ld + Dq + (int64_t)kvh * HD;
   const bf16* vbase = kbase + Dkv;
@@ -167,9 +190,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int nkv = (S + BKV - 1) / BKV;
   const int ntiles = CAUSAL ? min((q0 + BQ + BKV - 1) / BKV, nkv) : nkv;
 
-  TileOffsets<HD> toff;
-  toff.init(ld, wave, lane);
-  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   auto stage_tile = [&](int j, int stage) {
     char* ks = smem + stage * STAGE;
     if ((j + 1) * BKV <= S) {                        // whole tile inside the sequence (uniform)
@@ -200,25 +220,34 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     if (wave_active) {
       const char* ks = smem + (j & 1) * STAGE;
       const char* vs = ks + KSTAGE;
-      // All K fragments of the tile are requested before the first MFMA (one LDS latency instead of sixteen), and the
-      // V^T fragments right after the score MFMAs are queued, so that they arrive while the softmax runs.
-      bf16x8 kf[2][NKK];
+      // K fragments two contraction steps ahead of the MFMAs that use them (an LDS read takes longer than the two MFMAs
+      // of a step), in an order the compiler may not change: left alone it moves between "all reads first" and "read,
+      // wait, multiply" with the register pressure of the code around the loop, which measured 4 % apart.
+      auto kread = [&](int t, int kk) {
+        const int krow = t * 32 + l31, c = kk * 2 + half;
+        return *reinterpret_cast<const bf16x8*>(ks + krow * KROW + (rm_pos<HD>(c, krow) << 4));
+      };
+      bf16x8 kf[3][2];
 #pragma unroll
-      for (int t = 0; t < 2; ++t)
+      for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
-        for (int kk = 0; kk < NKK; ++kk) {
-          const int krow = t * 32 + l31, c = kk * 2 + half;
-          kf[t][kk] = *reinterpret_cast<const bf16x8*>(ks + krow * KROW + (rm_pos<HD>(c, krow) << 4));
-        }
+        for (int t = 0; t < 2; ++t) kf[kk][t] = kread(t, kk);
       f32x16 s[2];
 #pragma unroll
       for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[t][r] = 0.0f;
 #pragma unroll
-      for (int kk = 0; kk < NKK; ++kk)
+      for (int kk = 0; kk < NKK; ++kk) {
+        if (kk + 2 < NKK) {
 #pragma unroll
-        for (int t = 0; t < 2; ++t) s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t][kk], qf[kk], s[t], 0, 0, 0);
+          for (int t = 0; t < 2; ++t) kf[(kk + 2) % 3][t] = kread(t, kk + 2);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk % 3][t], qf[kk], s[t], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
       bf16x8 vf[4][NDB];
 #pragma unroll
       for (int g = 0; g < 4; ++g)
@@ -289,6 +318,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       }
     if (half == 0) lse[((int64_t)b * H + h) * S + myq] = (m_run + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994531f;
   }
+  }  // pass
 }
 
 
@@ -300,17 +330,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 //               dP^T = V dO^T are formed with keys in the MFMA row dimension so that lse and
 //               delta are per-lane scalars; dS^T feeds dQ^T += K^T dS^T from registers (K is
 //               also kept transposed in LDS, same key order trick as V in the forward).
-//   dkv kernel: one workgroup per 128 keys of a kv head, walks the query tiles of every query
-//               head of the group.  Here S = Q K^T and dP = dO V^T are formed with QUERIES in
-//               the row dimension, so each lane owns a key column and P, dS feed
-//               dV^T += dO^T P and dK^T += Q^T dS from registers; Q and dO are staged in LDS
-//               both row-major and transposed.
-// Staging pattern shared by both: a thread loads 4 consecutive rows x 8 features (4 x 16 bytes),
-// writes them row-major as they are and transposed as 8 x 8-byte pieces.
+//   dkv kernel: one workgroup per 64 keys of a kv head (16 per wave, v_mfma_f32_16x16x32_bf16), walks
+//               the query tiles of every query head of the group.  Here S = Q K^T and dP = dO V^T
+//               are formed with QUERIES in the row dimension, so each lane owns a key column and
+//               P, dS feed dV^T += dO^T P and dK^T += Q^T dS from registers.
+// Both stream their tiles (K and V; Q and dO) global -> LDS row-major with direct-to-LDS loads and take
+// the transposed operands out of the same tiles with transposing LDS reads.
 
 // byte offset of 16-byte chunk `chunk` of row `row` in a row-major tile
-template <int HD>
-__device__ __forceinline__ int rm_off(int row, int chunk) { return row * (HD * 2) + (rm_pos<HD>(chunk, row) << 4); }
+template <int HD, int SW = 0>
+__device__ __forceinline__ int rm_off(int row, int chunk) { return row * (HD * 2) + (rm_pos<HD, SW>(chunk, row) << 4); }
 
 // Inverse RoPE of 4 consecutive features d..d+3 (two pairs) of the token at in-sequence position p:
 // (a, b) -> (a cos + b sin, -a sin + b cos), the transpose of the forward rotation.
@@ -328,23 +357,27 @@ template <int HD, bool CAUSAL>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dq_mfma_kernel(const bf16* __restrict__ qkv, int64_t ld, const bf16* __restrict__ o,
                                                                const bf16* __restrict__ dout, const float* __restrict__ lse,
                                                                float* __restrict__ delta, bf16* __restrict__ dqkv, int B, int S, int H, int Hkv,
-                                                               float scale, const float* __restrict__ rope_cs) {
+                                                               float scale, const float* __restrict__ rope_cs, int pair) {
   constexpr int KCH = HD / 8, NKK = HD / 16, NDB = HD / 32;
   constexpr int TILE = BKV * HD * 2;                 // bytes of one 64-row tile (row-major or transposed)
   constexpr int STAGE = 2 * TILE;                    // K and V, both row-major (K is read along its rows and transposed)
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int nqt = (S + BQ - 1) / BQ;
   int rank, h, b;
-  if (!xcd_map((int)blockIdx.x, nqt, H / Hkv, Hkv, B, rank, h, b)) return;
-  const int qt = nqt - 1 - rank;
+  if (!xcd_map((int)blockIdx.x, paired_tiles(pair, nqt), H / Hkv, Hkv, B, rank, h, b)) return;
   const int kvh = h / (H / Hkv);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l31 = lane & 31, half = lane >> 5;
-  const int q0 = qt * BQ, wq0 = q0 + wave * 32, myq = wq0 + l31;
   const int Dq = H * HD, Dkv = Hkv * HD;
   const float c2 = scale * 1.4426950408889634f;
-  const int qrow = min(myq, S - 1);
   const bf16* kbase = qkv + (int64_t)b * S * ld + Dq + (int64_t)kvh * HD;
   const bf16* vbase = kbase + Dkv;
+  TileOffsets<HD> toff;
+  toff.init(ld, wave, lane);
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  for (int pass = 0; pass < n_passes(pair, nqt, rank); ++pass) {
+  const int qt = pass == 0 ? nqt - 1 - rank : rank;
+  const int q0 = qt * BQ, wq0 = q0 + wave * 32, myq = wq0 + l31;
+  const int qrow = min(myq, S - 1);
 
   bf16x8 qf[NKK], dof[NKK];
   float dl = 0.0f;
@@ -368,9 +401,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
   const int nkv = (S + BKV - 1) / BKV;
   const int ntiles = CAUSAL ? min((q0 + BQ + BKV - 1) / BKV, nkv) : nkv;
-  TileOffsets<HD> toff;
-  toff.init(ld, wave, lane);
-  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   auto stage_tile = [&](int j, int stage) {
     char* base = smem + stage * STAGE;
     if ((j + 1) * BKV <= S) {                        // whole tile inside the sequence (uniform)
@@ -409,7 +439,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         bf16x8 kf[2], vf[2];
         kf[0] = *reinterpret_cast<const bf16x8*>(ks + rm_off<HD>(krow, half));
         vf[0] = *reinterpret_cast<const bf16x8*>(vs + rm_off<HD>(krow, half));
-#pragma unroll
+  #pragma unroll
         for (int kk = 0; kk < NKK; ++kk) {
           if (kk + 1 < NKK) {
             kf[(kk + 1) & 1] = *reinterpret_cast<const bf16x8*>(ks + rm_off<HD>(krow, (kk + 1) * 2 + half));
@@ -420,7 +450,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
           dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kk & 1], dof[kk], dp, 0, 0, 0);
           __builtin_amdgcn_sched_barrier(0);
         }
-        bf16x8 dsf[2];
+          bf16x8 dsf[2];
         if (need_mask) {                             // one uniform branch; a masked score of -inf gives p = 0 below
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
@@ -433,14 +463,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
           const float p = __builtin_amdgcn_exp2f(fmaf(s[r], c2, -lse2));
           dsf[r >> 3][r & 7] = (bf16)(p * (dp[r] - dl));
         }
-#pragma unroll
+  #pragma unroll
         for (int g2 = 0; g2 < 2; ++g2)
 #pragma unroll
           for (int db = 0; db < NDB; ++db) {
             const bf16x8 ktf = tr_fragment<HD>(ks, t * 2 + g2, db, lane);
             dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf, dsf[g2], dq[db], 0, 0, 0);
           }
-      }
+        }
     }
     dma_wait_all();
     __syncthreads();                                  // fence + barrier: the next tile has landed for everybody
@@ -461,6 +491,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         *reinterpret_cast<bf16x4*>(out + db * 32 + g4 * 8 + half * 4) = pk;
       }
   }
+  }  // pass
 }
 
 // A-operand fragment of v_mfma_f32_16x16x32_bf16 for the TRANSPOSE of a row-major 64-row tile: 16 features
@@ -477,7 +508,7 @@ __device__ __forceinline__ bf16x8 tr16_fragment(const char* tile, int jj, int fb
     const int row = 32 * jj + 16 * h2 + 4 * g + tr_e;
     const int chunk = 2 * fb + (tr_q >> 1);
     const bf16x4 t4 = __builtin_bit_cast(bf16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-        (__attribute__((address_space(3))) s16x4*)(tile + row * (HD * 2) + (rm_pos<HD>(chunk, row) << 4) + (tr_q & 1) * 8)));
+        (__attribute__((address_space(3))) s16x4*)(tile + row * (HD * 2) + (rm_pos<HD, 1>(chunk, row) << 4) + (tr_q & 1) * 8)));
 #pragma unroll
     for (int i = 0; i < 4; ++i) f[h2 * 4 + i] = t4[i];
   }
@@ -496,7 +527,7 @@ __device__ __forceinline__ bf16x8 tr16_fragment(const char* tile, int jj, int fb
 template <int HD, bool CAUSAL>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dkv_mfma_kernel(
     const bf16* __restrict__ qkv, int64_t ld, const bf16* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ delta,
-    bf16* __restrict__ dqkv, int B, int S, int H, int Hkv, float scale, const float* __restrict__ rope_cs, float* __restrict__ part) {
+    bf16* __restrict__ dqkv, int B, int S, int H, int Hkv, float scale, const float* __restrict__ rope_cs, float* __restrict__ part, int pair) {
   constexpr int NK = HD / 32;                        // 32-deep contraction steps over the head dimension
   constexpr int NFB = HD / 16;                       // 16-feature blocks of dK^T / dV^T
   constexpr int TILE = 64 * HD * 2;
@@ -504,18 +535,24 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int G = H / Hkv;
   const int nkt = (S + 63) / 64;
-  int kt, kvh, b;                                     // key tiles ascending: the longest causal columns first
+  int rank, kvh, b;
   // part != nullptr: one workgroup per (key tile, QUERY head); its dk / dv contribution goes to
   // part[head within the group][token][dk | dv columns of all kv heads] in fp32 and attn_dkv_sum_kernel adds the group.
   int hsel = 0;
   if (part) {
-    if (!xcd_map((int)blockIdx.x, nkt, G, Hkv, B, kt, hsel, b)) return;
+    if (!xcd_map((int)blockIdx.x, paired_tiles(pair, nkt), G, Hkv, B, rank, hsel, b)) return;
     kvh = hsel / G;
-  } else if (!xcd_map((int)blockIdx.x, nkt, 1, Hkv, B, kt, kvh, b)) return;
+  } else if (!xcd_map((int)blockIdx.x, paired_tiles(pair, nkt), 1, Hkv, B, rank, kvh, b)) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l15 = lane & 15, lg = lane >> 4;
-  const int k0 = kt * 64, wk0 = k0 + wave * 16, mykey = wk0 + l15;
   const int Dq = H * HD, Dkv = Hkv * HD;
   const float c2 = scale * 1.4426950408889634f;
+  TileOffsets<HD, 4, 1> toff_q, toff_d;
+  toff_q.init(ld, wave, lane);
+  toff_d.init(Dq, wave, lane);
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  for (int pass = 0; pass < n_passes(pair, nkt, rank); ++pass) {
+  const int kt = pass == 0 ? rank : nkt - 1 - rank;  // under the causal mask the first key tiles have the longest columns
+  const int k0 = kt * 64, wk0 = k0 + wave * 16, mykey = wk0 + l15;
   const int krow = min(mykey, S - 1);
 
   bf16x8 kf[NK], vf[NK];                              // this lane's key / value row, 8 features of every 32
@@ -531,10 +568,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int nq = (S - qstart + 63) / 64;             // query tiles per head
   const int ntiles = part ? nq : nq * G;
   float lreg = 0.0f, dlreg = 0.0f;
-  TileOffsets<HD> toff_q, toff_d;
-  toff_q.init(ld, wave, lane);
-  toff_d.init(Dq, wave, lane);
-  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   auto stage_tile = [&](int j, int stage) {            // Q and dO tiles straight to LDS; the two per-query scalars via registers
     const int h = part ? hsel : kvh * G + j / nq, q0 = qstart + (j % nq) * 64;
     char* base = smem + stage * STAGE;
@@ -548,10 +581,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       dlreg = delta[li];
     }
     if (q0 + 64 <= S) {                              // whole tile inside the sequence (uniform)
-      stage_tile_fast<HD>(qrows + (int64_t)q0 * ld, toff_q, base, wave_u);
-      stage_tile_fast<HD>(drows + (int64_t)q0 * Dq, toff_d, base + TILE, wave_u);
+      stage_tile_fast<HD, 4, 1>(qrows + (int64_t)q0 * ld, toff_q, base, wave_u);
+      stage_tile_fast<HD, 4, 1>(drows + (int64_t)q0 * Dq, toff_d, base + TILE, wave_u);
     } else {
-      stage_two_tiles<HD>(qrows, ld, drows, Dq, q0, S - 1, base, base + TILE, wave, lane);
+      stage_two_tiles<HD, 1>(qrows, ld, drows, Dq, q0, S - 1, base, base + TILE, wave, lane);
     }
   };
   auto store_scalars = [&](int stage) {
@@ -590,14 +623,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       for (int h2 = 0; h2 < 2; ++h2) {
         const int qb = 2 * jj + h2, row = qb * 16 + l15;
         f32x4 s = {0.0f, 0.0f, 0.0f, 0.0f}, dp = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
+  #pragma unroll
         for (int kk = 0; kk < NK; ++kk) {
-          const bf16x8 qf = *reinterpret_cast<const bf16x8*>(qs + rm_off<HD>(row, kk * 4 + lg));
-          const bf16x8 df = *reinterpret_cast<const bf16x8*>(ds_ + rm_off<HD>(row, kk * 4 + lg));
+          const bf16x8 qf = *reinterpret_cast<const bf16x8*>(qs + rm_off<HD, 1>(row, kk * 4 + lg));
+          const bf16x8 df = *reinterpret_cast<const bf16x8*>(ds_ + rm_off<HD, 1>(row, kk * 4 + lg));
           s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf, kf[kk], s, 0, 0, 0);
           dp = __builtin_amdgcn_mfma_f32_16x16x32_bf16(df, vf[kk], dp, 0, 0, 0);
         }
-        // this lane: key mykey, queries q0 + 16 qb + 4 lg + r
+          // this lane: key mykey, queries q0 + 16 qb + 4 lg + r
         if (need_mask) {                             // one uniform branch; a masked score of -inf gives p = 0 below
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
@@ -658,6 +691,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       *reinterpret_cast<bf16x4*>(out + Dkv + fb * 16 + lg * 4) = pv;
     }
   }
+  }  // pass
 }
 
 // dk | dv of the G query heads of every group, added in the order of the heads: one thread per 4 columns of a token
@@ -691,7 +725,9 @@ hipError_t mfma_attn_fwd(const void* qkv, int64_t ld, void* o, float* lse, int B
                          int scale_hd) {
   if (!mfma_attn_supported(S, H, Hkv, hd, ld)) return hipErrorInvalidValue;
   if (B <= 0) return hipSuccess;
-  const dim3 grid(xcd_grid((S + BQ - 1) / BQ, H / Hkv, Hkv, B)), block(256);
+  const int nqt = (S + BQ - 1) / BQ;
+  const int pair = pair_tiles(causal, nqt);
+  const dim3 grid(xcd_grid(paired_tiles(pair, nqt), H / Hkv, Hkv, B)), block(256);
   const float c = 1.4426950408889634f / sqrtf((float)(scale_hd > 0 ? scale_hd : hd));
 #define SV_ATTN_LAUNCH(HDV, CZ)                                                                                         \
   do {                                                                                                                  \
@@ -703,7 +739,7 @@ hipError_t mfma_attn_fwd(const void* qkv, int64_t ld, void* o, float* lse, int B
       if (e != hipSuccess) return e;                                                                                    \
       configured = true;                                                                                                \
     }                                                                                                                   \
-    hipLaunchKernelGGL(kern, grid, block, lds, st, (const bf16*)qkv, ld, (bf16*)o, lse, B, S, H, Hkv, c);                  \
+    hipLaunchKernelGGL(kern, grid, block, lds, st, (const bf16*)qkv, ld, (bf16*)o, lse, B, S, H, Hkv, c, pair);                  \
   } while (0)
   if (hd == 128) { if (causal) SV_ATTN_LAUNCH(128, true); else SV_ATTN_LAUNCH(128, false); }
   else if (hd == 64) { if (causal) SV_ATTN_LAUNCH(64, true); else SV_ATTN_LAUNCH(64, false); }
@@ -718,15 +754,15 @@ hipError_t mfma_attn_bwd(const void* qkv, int64_t ld, const void* o, const void*
                          int64_t part_floats) {
   if (!mfma_attn_supported(S, H, Hkv, hd, ld)) return hipErrorInvalidValue;
   if (B <= 0) return hipSuccess;
-  // Few (batch, kv head, key tile) triples -- one long sequence -- leave CUs idle and, under the causal mask, make the
-  // first key tiles' workgroups several times longer than the average: then every query head of a group gets its own
-  // workgroup and the group is added afterwards.
-  const int G = H / Hkv, ktiles = (S + 127) / 128;
-  const int64_t triples = (int64_t)ktiles * Hkv * B;
-  const bool split = G > 1 && part_ws && (triples < kDkvSplitTriples / 2 || (triples < kDkvSplitTriples && ktiles >= 16)) &&
+  // A launch that leaves workgroup slots empty (two per CU) -- one long sequence, few kv heads -- gives every query head
+  // of a group its own workgroup, and the group is added afterwards; fuller launches keep the group in one workgroup
+  // and save the fp32 partial results their round trip through memory.
+  const int G = H / Hkv, nqt = (S + BQ - 1) / BQ, nkt = (S + 63) / 64;
+  const int pair_q = pair_tiles(causal, nqt), pair_k = pair_tiles(causal, nkt);
+  const bool split = G > 1 && part_ws && (int64_t)paired_tiles(pair_k, nkt) * Hkv * B < kDkvSplitWorkgroups &&
                      (int64_t)G * B * S * 2 * Hkv * hd <= part_floats;
   float* part = split ? part_ws : nullptr;
-  const dim3 gq(xcd_grid((S + BQ - 1) / BQ, G, Hkv, B)), gk(xcd_grid((S + 63) / 64, split ? G : 1, Hkv, B)), block(256);
+  const dim3 gq(xcd_grid(paired_tiles(pair_q, nqt), G, Hkv, B)), gk(xcd_grid(paired_tiles(pair_k, nkt), split ? G : 1, Hkv, B)), block(256);
   const float scale = 1.0f / sqrtf((float)(scale_hd > 0 ? scale_hd : hd));
 #define SV_ATTN_BWD_LAUNCH(HDV, CZ)                                                                                     \
   do {                                                                                                                  \
@@ -741,9 +777,9 @@ hipError_t mfma_attn_bwd(const void* qkv, int64_t ld, const void* o, const void*
       configured = true;                                                                                                \
     }                                                                                                                   \
     hipLaunchKernelGGL(kq, gq, block, lq, st, (const bf16*)qkv, ld, (const bf16*)o, (const bf16*)dout, lse, delta,      \
-                       (bf16*)dqkv, B, S, H, Hkv, scale, rope_cs);                                                      \
+                       (bf16*)dqkv, B, S, H, Hkv, scale, rope_cs, pair_q);                                              \
     hipLaunchKernelGGL(kk, gk, block, lk, st, (const bf16*)qkv, ld, (const bf16*)dout, lse, delta, (bf16*)dqkv, B, S,   \
-                       H, Hkv, scale, rope_cs, part);                                                                   \
+                       H, Hkv, scale, rope_cs, part, pair_k);                                                           \
   } while (0)
   if (hd == 128) { if (causal) SV_ATTN_BWD_LAUNCH(128, true); else SV_ATTN_BWD_LAUNCH(128, false); }
   else if (hd == 64) { if (causal) SV_ATTN_BWD_LAUNCH(64, true); else SV_ATTN_BWD_LAUNCH(64, false); }

@@ -230,9 +230,9 @@ hipError_t mfma_gemm(const GemmArgs& a, hipStream_t st, int tile = 0);   // tile
 bool mfma_attn_supported(int S, int H, int Hkv, int hd, int64_t ld);
 hipError_t mfma_attn_fwd(const void* qkv, int64_t ld, void* o, float* lse, int B, int S, int H, int Hkv, int hd, int causal,
                          hipStream_t st, int scale_hd = 0);
-// the dk / dv kernel splits the query heads of a group over workgroups below half this many (batch, kv head, key tile of
-// 128) triples, and below this many when the sequence has 16 key tiles or more (long causal columns: measured)
-constexpr int kDkvSplitTriples = 1024;
+// the dk / dv kernel gives every query head of a group its own workgroup when one workgroup per (batch, kv head, key
+// tile of 64 -- two tiles under the causal mask) would be fewer than this many: two per CU
+constexpr int kDkvSplitWorkgroups = 512;
 // rope_cs != nullptr: dq and dk are rotated back (inverse RoPE) before they are stored.  part_ws: optional fp32 scratch of
 // part_floats floats; with G * B * S * 2 * Hkv * hd of them and few (batch, kv head, key tile) triples the dk / dv kernel
 // runs one workgroup per query head and a second kernel adds each group's heads in a fixed order

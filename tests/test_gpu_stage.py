@@ -103,9 +103,9 @@ def test_wide_mlp_on_the_large_tile_with_a_ragged_row_tail(backward):
 
 @pytest.mark.parametrize("B", [4, 32], ids=["one_workgroup_per_query_head", "one_workgroup_per_kv_head"])
 def test_grouped_query_backward_both_decompositions(B):
-    """8 kv heads of 2 query heads, 2 key tiles per sequence: with 4 sequences the dk / dv kernel gives every query head
-    a workgroup of its own and a second kernel adds each group; with 32 sequences (512 (batch, kv head, key tile)
-    triples) one workgroup loops over the group."""
+    """8 kv heads of 2 query heads, 4 key tiles -- 2 workgroups -- per (sequence, kv head): with 4 sequences the dk / dv
+    kernel gives every query head a workgroup of its own and a second kernel adds each group; with 32 sequences (512
+    workgroups, two for every CU) one workgroup loops over the group."""
     desc = si.StageDesc(1, 512, 16, 8, 768)
     (gh, gg), (wh, wg), h = run_stage(desc, B, 250, seed=9, backward=True, weight_scale=2.0)
     assert_close(gh, wh, TOL["bf16"], "h")
