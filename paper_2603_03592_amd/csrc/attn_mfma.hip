@@ -9,9 +9,11 @@
 // per-lane scalars and only one cross-lane exchange (lane ^ 32) per tile is needed.  The
 // probabilities then feed O^T += V^T P^T directly from registers: the accumulator layout of
 // S^T is a valid B-operand layout once the 16 keys of an MFMA are taken in the order
-// {0-3, 8-11 | 4-7, 12-15}; V is transposed into LDS in exactly that key order (4x8 register
-// transposes on the way in), so a V^T fragment is one 16-byte LDS read.
+// {0-3, 8-11 | 4-7, 12-15}; the V^T fragments come out of the row-major V tile in exactly that key
+// order by transposing LDS reads.  The 64 keys of a tile are taken as two halves whose matrix and
+// vector instructions are interleaved in the wave's instruction stream (see the tile body).
 #include "common.h"
+#include <type_traits>
 
 namespace sv {
 namespace {
@@ -46,6 +48,7 @@ __host__ __device__ __forceinline__ int paired_tiles(bool pair, int n) { return 
 __device__ __forceinline__ int n_passes(bool pair, int n, int r) { return pair && 2 * r != n - 1 ? 2 : 1; }
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
+#define LDS __attribute__((address_space(3)))
 
 // Position of 16-byte chunk c inside row `row` of a row-major LDS tile (an involution in c, so the staging side uses
 // the same function to pick the chunk that belongs at a position).  The LDS serves 256 bytes per clock, and a tile is
@@ -173,6 +176,22 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   TileOffsets<HD> toff;
   toff.init(ld, wave, lane);
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  // Per-lane LDS byte offsets of the fragment reads, made once: the swizzle only looks at the low four bits of a row, so
+  // the second 32 keys of a K fragment and the MFMA index of a V^T fragment are immediate offsets from these.
+  LDS char* const lds0 = (LDS char*)smem;
+  unsigned kbase_l[NKK], vbase_l[NDB][2];
+#pragma unroll
+  for (int kk = 0; kk < NKK; ++kk) kbase_l[kk] = l31 * KROW + (rm_pos<HD>(kk * 2 + half, l31) << 4);
+  {
+    const int tr_e = (lane & 15) >> 2, tr_q = lane & 3, tr_nb = (lane >> 4) & 1;
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+      for (int r2 = 0; r2 < 2; ++r2) {
+        const int row = r2 * 8 + half * 4 + tr_e, chunk = db * 4 + tr_nb * 2 + (tr_q >> 1);
+        vbase_l[db][r2] = row * KROW + (rm_pos<HD>(chunk, row) << 4) + (tr_q & 1) * 8;
+      }
+  }
   for (int pass = 0; pass < n_passes(pair, nqt, rank); ++pass) {
   const int qt = pass == 0 ? nqt - 1 - rank : rank;
   const int q0 = qt * BQ, wq0 = q0 + wave * 32;
@@ -214,90 +233,151 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
   for (int j = 0; j < ntiles; ++j) {
     const bool more = j + 1 < ntiles;
-    if (more) stage_tile(j + 1, (j + 1) & 1);
     const int k0 = j * BKV;
     const bool wave_active = !CAUSAL || k0 <= wq0 + 31;
-    if (wave_active) {
-      const char* ks = smem + (j & 1) * STAGE;
-      const char* vs = ks + KSTAGE;
-      // K fragments two contraction steps ahead of the MFMAs that use them (an LDS read takes longer than the two MFMAs
-      // of a step), in an order the compiler may not change: left alone it moves between "all reads first" and "read,
-      // wait, multiply" with the register pressure of the code around the loop, which measured 4 % apart.
-      auto kread = [&](int t, int kk) {
-        const int krow = t * 32 + l31, c = kk * 2 + half;
-        return *reinterpret_cast<const bf16x8*>(ks + krow * KROW + (rm_pos<HD>(c, krow) << 4));
+    // The next tile's loads: a wave that computes issues them one behind each MFMA of its first phase, where it would
+    // otherwise wait for the matrix pipe (issued in a row they held the wave for some 450 cycles per tile: the
+    // instruction stream of a wave is in order, and the load path takes a 1 KB instruction every 16 cycles at best).
+    // Causal kernels only: the unmasked kernel's loop is laid out differently by the compiler, and there the second
+    // copy of the tile body that this takes costs registers it does not have (spills inside the loop).
+    const bool spread = CAUSAL && more && wave_active && (j + 2) * BKV <= S;
+    if (more && !spread) stage_tile(j + 1, (j + 1) & 1);
+    auto tile_body = [&](auto spread_c) {
+      constexpr bool SPREAD = decltype(spread_c)::value;
+      const unsigned so = (unsigned)(j & 1) * STAGE;   // this tile's stage: K at so, V at so + KSTAGE
+      const bool need_mask = (CAUSAL && k0 + BKV - 1 > wq0) || (k0 + BKV > S);
+      // The tile's 64 keys are taken as two halves t of 32, and a wave issues its instructions in order, so the vector
+      // work of one half is written BETWEEN the matrix instructions of the other: each MFMA (32 cycles in the matrix
+      // pipe) is followed by a slice of about as many cycles of softmax, with scheduling barriers that keep this order.
+      //   phase 0: S(0)                      with the next tile's global -> LDS loads
+      //   phase A: S(1)  | softmax(0)        with the V^T reads of PV(0)
+      //   phase B: PV(0) | softmax(1)        with the V^T reads of PV(1)
+      //   phase 3: PV(1)
+      // K fragments run two MFMAs ahead through phases 0 and A.
+      auto kread = [&](int i) {                        // i = t * NKK + kk
+        return *reinterpret_cast<const LDS bf16x8*>(lds0 + (kbase_l[i % NKK] + so + (i / NKK) * 32 * KROW));
       };
-      bf16x8 kf[3][2];
+      auto vread = [&](int g, int db) {                // the V^T fragment of MFMA g, feature block db (see tr_fragment)
+        bf16x8 f;
 #pragma unroll
-      for (int kk = 0; kk < 2; ++kk)
+        for (int r2 = 0; r2 < 2; ++r2) {
+          const bf16x4 t4 = __builtin_bit_cast(bf16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (LDS s16x4*)(lds0 + (vbase_l[db][r2] + so + KSTAGE + g * 16 * KROW))));
 #pragma unroll
-        for (int t = 0; t < 2; ++t) kf[kk][t] = kread(t, kk);
+          for (int e = 0; e < 4; ++e) f[r2 * 4 + e] = t4[e];
+        }
+        return f;
+      };
       f32x16 s[2];
 #pragma unroll
       for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[t][r] = 0.0f;
+      bf16x8 pf[4];
+      float psum = 0.0f;
+      // slice i of NS of the softmax of half t: slice 0 masks, takes the maximum and moves the reference if it must,
+      // the others take the exponentials of an even share of the 8 element pairs
+      float corr = 1.0f;
+      auto soft_slice = [&](int t, int i, int NS) {
+        if (i == 0) {
+          if (need_mask) {                             // one uniform branch: tiles below the diagonal skip all of it
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int key = k0 + t * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+              if ((CAUSAL && key > myq) || key >= S) s[t][r] = -INFINITY;
+            }
+          }
+          float mx = s[t][0];
+#pragma unroll
+          for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[t][r]);
+          const auto sw = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(unsigned, mx), __builtin_bit_cast(unsigned, mx), false, false);
+          mx = fmaxf(__builtin_bit_cast(float, sw[0]), __builtin_bit_cast(float, sw[1]));     // both lane halves of the query
+          // Lazy reference: the running reference m only moves when the maximum grew by more than 2^8 (probabilities
+          // then reach at most 256, harmless in bf16 and in the fp32 sums; O / l does not depend on the reference).
+          // With the exact maximum some query of the wave moves it in most tiles and all output registers get rescaled.
+          const float mx_s = mx * scale_log2e;
+          const bool moved = mx_s > m_run + 8.0f;
+          corr = 1.0f;
+          if (__builtin_amdgcn_ballot_w64(moved) != 0) {
+            const float m_new = moved ? mx_s : m_run;
+            corr = __builtin_amdgcn_exp2f(m_run - m_new);
+            m_run = m_new;
+          }
+          psum = 0.0f;
+        } else {
+          const int p_lo = (8 * (i - 1)) / (NS - 1), p_hi = (8 * i) / (NS - 1);
+#pragma unroll
+          for (int r = 2 * p_lo; r < 2 * p_hi; ++r) {
+            const float p = __builtin_amdgcn_exp2f(fmaf(s[t][r], scale_log2e, -m_run));
+            psum += p;
+            pf[t * 2 + (r >> 3)][r & 7] = (bf16)p;
+          }
+        }
+        // Arithmetic has no place of its own in the instruction order the compiler starts from, and the scheduling
+        // barriers only hold what already sits between them: the slice is tied down by passing what it made, and what
+        // the next slice reads, through an empty volatile statement.
+        asm volatile("" : "+v"(m_run), "+v"(psum));
+      };
+      // after the phase: the products that were issued between the slices belong to the old reference
+      auto soft_end = [&]() {
+        if (__builtin_amdgcn_ballot_w64(corr != 1.0f) != 0) {
+          l_run *= corr;
+#pragma unroll
+          for (int i = 0; i < NDB; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[i][r] *= corr;
+        }
+        l_run += psum;
+      };
+      constexpr int NPV = 2 * NDB;                    // MFMAs of one half's P V product
+      constexpr int KD = 2;                           // K fragments this many MFMAs ahead
+      bf16x8 kf[KD + 1], vf[2][NPV];
+#pragma unroll
+      for (int i = 0; i < KD; ++i) kf[i] = kread(i);
+      // phase 0
 #pragma unroll
       for (int kk = 0; kk < NKK; ++kk) {
-        if (kk + 2 < NKK) {
-#pragma unroll
-          for (int t = 0; t < 2; ++t) kf[(kk + 2) % 3][t] = kread(t, kk + 2);
+        kf[(kk + KD) % (KD + 1)] = kread(kk + KD);
+        __builtin_amdgcn_sched_barrier(0);
+        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk % (KD + 1)], qf[kk], s[0], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (SPREAD) {                                  // NKK = the wave's load instructions per tile: K then V
+          constexpr int IPW = TileOffsets<HD>::IPW;
+          const bf16* src = (kk / IPW ? vbase : kbase) + (int64_t)(j + 1) * BKV * ld;
+          dma16((const char*)src, toff.off[kk % IPW], smem + ((j + 1) & 1) * STAGE + (kk / IPW) * KSTAGE + (wave_u * IPW + kk % IPW) * 1024);
+          __builtin_amdgcn_sched_barrier(0);
         }
+      }
+      // phase A
+#pragma unroll
+      for (int kk = 0; kk < NKK; ++kk) {
+        if (kk + KD < NKK) kf[(NKK + kk + KD) % (KD + 1)] = kread(NKK + kk + KD);
+        __builtin_amdgcn_sched_barrier(0);
+        s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[(NKK + kk) % (KD + 1)], qf[kk], s[1], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int t = 0; t < 2; ++t) s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk % 3][t], qf[kk], s[t], 0, 0, 0);
+        for (int u = kk * NPV / NKK; u < (kk + 1) * NPV / NKK; ++u) vf[0][u] = vread(u / NDB, u % NDB);
+        soft_slice(0, kk, NKK);
         __builtin_amdgcn_sched_barrier(0);
       }
-      bf16x8 vf[4][NDB];
+      soft_end();
+      // phase B
 #pragma unroll
-      for (int g = 0; g < 4; ++g)
-#pragma unroll
-        for (int db = 0; db < NDB; ++db) vf[g][db] = tr_fragment<HD>(vs, g, db, lane);
-      // mask (diagonal tiles and the ragged key tail), then the online softmax update
-      const bool need_mask = (CAUSAL && k0 + BKV - 1 > wq0) || (k0 + BKV > S);
-      float mx = -INFINITY;
-      if (need_mask) {                               // one uniform branch: tiles below the diagonal skip all of it
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int key = k0 + t * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-            if ((CAUSAL && key > myq) || key >= S) s[t][r] = -INFINITY;
-          }
+      for (int u = 0; u < NPV; ++u) {
+        oacc[u % NDB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[0][u], pf[u / NDB], oacc[u % NDB], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        vf[1][u] = vread(2 + u / NDB, u % NDB);
+        soft_slice(1, u, NPV);
+        __builtin_amdgcn_sched_barrier(0);
       }
+      soft_end();
+      // phase 3
 #pragma unroll
-      for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[t][r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      // Lazy reference: the running reference m only moves when the maximum grew by more than 2^8 (probabilities then
-      // reach at most 256, harmless in bf16 and in the fp32 sums; O / l does not depend on the reference).  With the
-      // exact maximum some query of the wave moves it in most tiles and all 64 output registers get rescaled each time.
-      const float mx_s = mx * scale_log2e;
-      const float m_new = mx_s > m_run + 8.0f ? mx_s : m_run;
-      const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
-      m_run = m_new;
-      float psum = 0.0f;
-      bf16x8 pf[4];
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const float p = __builtin_amdgcn_exp2f(fmaf(s[t][r], scale_log2e, -m_new));
-          psum += p;
-          pf[t * 2 + (r >> 3)][r & 7] = (bf16)p;
-        }
-      l_run = l_run * corr + psum;
-      if (__builtin_amdgcn_ballot_w64(corr != 1.0f) != 0) {     // the running maximum of some query moved: rescale
-#pragma unroll
-        for (int i = 0; i < NDB; ++i)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) oacc[i][r] *= corr;
-      }
-#pragma unroll
-      for (int g = 0; g < 4; ++g)
-#pragma unroll
-        for (int db = 0; db < NDB; ++db) oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[g][db], pf[g], oacc[db], 0, 0, 0);
+      for (int u = 0; u < NPV; ++u)
+        oacc[u % NDB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[1][u], pf[2 + u / NDB], oacc[u % NDB], 0, 0, 0);
+    };
+    if (wave_active) {
+      if (spread) tile_body(std::true_type{}); else tile_body(std::false_type{});
     }
     dma_wait_all();
     __syncthreads();                                  // fence + barrier: the next tile has landed for everybody
