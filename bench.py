@@ -34,6 +34,9 @@ def parse():
     ap.add_argument("--mode", default=None, choices=[None, "fwd", "fwdbwd"], help="default: the workload's own")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--plain", action="store_true", help="run the plain (non-MFMA) kernels")
+    ap.add_argument("--fuse-norm", default="auto", choices=["auto", "on", "off"],
+                    help="run the two RMSNorms of a block inside the neighbouring products (SV_FLAG_FUSE_NORM); auto: where it "
+                         "measured faster (paper_2603_03592_amd.fuse_norm_pays)")
     ap.add_argument("--score-bench", action="store_true",
                     help="instead of the stage check, time the stand-alone scoring pass (128 submissions against one shared "
                          "reference) and the EMA update, and report them against the HBM roofline")
@@ -358,12 +361,14 @@ def main():
     h_in = torch.randn((B, S, desc.d_model), generator=g, device="cuda", dtype=torch.float32).to(dt)
     g_out = (1e-3 * torch.randn((B, S, desc.d_model), generator=g, device="cuda", dtype=torch.float32)).to(dt)
 
-    ver = sv.Verifier(desc, T, S, backward=backward, plain_kernels=a.plain)
+    fuse_norm = a.fuse_norm == "on" or (a.fuse_norm == "auto" and sv.fuse_norm_pays(desc))
+    ver = sv.Verifier(desc, T, S, backward=backward, plain_kernels=a.plain, fuse_norm=fuse_norm)
     wc = ver.pack_weights(wdev)
     prepare_ms = None
-    if backward:
-        # the stage parameters stay fixed while the micro-batches of an iteration are checked: their transposed copies
-        # for the backward products are made once, outside the timed steps, and the cost is reported
+    if backward or fuse_norm:
+        # the stage parameters stay fixed while the micro-batches of an iteration are checked: the context's copies of
+        # them (transposed for the backward products, with the norm gains folded in for the products that follow a
+        # norm) are made once, outside the timed steps, and the cost is reported
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         ver.prepare_weights(wc)
@@ -454,7 +459,7 @@ def main():
         "dtype": desc.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "n_blocks": desc.n_blocks, "d_model": desc.d_model, "n_heads": desc.n_heads,
                    "n_kv_heads": desc.n_kv_heads, "ffn_hidden": desc.ffn_hidden, "micro_batch": B, "seq_len": S,
-                   "check": "fwd+bwd" if backward else "fwd", "claims_per_step": 1, "kernels": "plain" if a.plain else "mfma",
+                   "check": "fwd+bwd" if backward else "fwd", "claims_per_step": 1, "kernels": "plain" if a.plain else "mfma", "norms": "inside the products" if fuse_norm else "own passes",
                    "weight_prepare_ms_once": prepare_ms,
                    **({"n_experts": desc.n_experts, "top_k": desc.top_k, "n_shared": desc.n_shared, "router_score": desc.router_score,
                        "router_norm": desc.router_norm} if desc.n_experts else {})},

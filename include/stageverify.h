@@ -71,7 +71,15 @@ enum { SV_M_SW = 16 };
 enum {
   SV_FLAG_BACKWARD = 1,       /* also allocate what sv_verify_backward needs                       */
   SV_FLAG_PLAIN_KERNELS = 2,  /* run the plain fp32-math kernels for every dtype (validation aid)  */
-  SV_FLAG_SLICED_W = 4        /* also allocate the projection scratch of sv_sliced_wasserstein       */
+  SV_FLAG_SLICED_W = 4,       /* also allocate the projection scratch of sv_sliced_wasserstein       */
+  SV_FLAG_FUSE_NORM = 8       /* bf16 stages with RMSNorm: the two norms of a block run inside the products
+                                 around them (the product before leaves each row's sum of squares, the product
+                                 after reads the residual stream itself against a copy of its weights with the
+                                 norm's gain folded in and scales its rows by 1 / rms); the context then holds
+                                 that copy of wq, wk, wv and of the dense MLP's first weights (a mixture of
+                                 experts keeps its second norm as a pass of its own).  sv_prepare_weights makes
+                                 the copies once; without it every call makes them.  Ignored for fp32 stages,
+                                 LayerNorm and SV_FLAG_PLAIN_KERNELS.                                  */
 };
 
 /* One pipeline stage = n_blocks identical pre-norm decoder blocks
@@ -180,13 +188,13 @@ sv_status sv_verify_backward(sv_ctx *ctx, const sv_block_weights *w, const void 
  * lets a caller tell such tokens from a deviation.                                                         */
 sv_status sv_last_routing(sv_ctx *ctx, int32_t block, int32_t *experts_out, float *gates_out, void *stream);
 
-/* Optional, backward contexts on the bf16 matrix-core path: transpose the stage's weight matrices to
- * [in, out] once (on `stream`) and keep the copies in the context, so that later sv_verify_backward calls
- * with the SAME sv_block_weights (same pointers) skip their per-call transposes.  The stage parameters
- * are fixed for a whole training iteration while many micro-batches are checked against them.  The caller
- * promises that the weight contents do not change until the next sv_prepare_weights call; w = NULL
- * forgets the copies.  A call with other pointers than the prepared ones transposes per call as before.
- * No-op for contexts that need no transposed copies.                                               */
+/* Optional, the bf16 matrix-core path: make the context's copies of the stage's weight matrices once (on `stream`)
+ * -- for a backward context the matrices transposed to [in, out], with SV_FLAG_FUSE_NORM the gain-folded ones -- so that
+ * later sv_verify_forward / sv_verify_backward calls with the SAME sv_block_weights (same pointers) skip making them
+ * per call.  The stage parameters are fixed for a whole training iteration while many micro-batches are checked
+ * against them.  The caller promises that the weight contents do not change until the next sv_prepare_weights
+ * call; w = NULL forgets the copies.  A call with other pointers than the prepared ones makes its copies per call
+ * as before.  No-op for contexts that keep no copies.                                                */
 sv_status sv_prepare_weights(sv_ctx *ctx, const sv_block_weights *w, void *stream);
 
 /* Stand-alone statistic for n_claims submissions [T, D] (claim i at claims + i*claim_stride

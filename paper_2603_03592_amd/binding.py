@@ -14,7 +14,7 @@ SV_F32, SV_BF16 = 0, 1
 SV_MLP_GELU, SV_MLP_SWIGLU = 0, 1
 SV_NORM_LN, SV_NORM_RMS = 0, 1
 SV_REDUCE_GLOBAL, SV_REDUCE_MAX_TOKEN = 0, 1
-SV_FLAG_BACKWARD, SV_FLAG_PLAIN_KERNELS, SV_FLAG_SLICED_W = 1, 2, 4
+SV_FLAG_BACKWARD, SV_FLAG_PLAIN_KERNELS, SV_FLAG_SLICED_W, SV_FLAG_FUSE_NORM = 1, 2, 4, 8
 SV_M_SW = 16
 METRIC_NAMES = ("rel_l2", "l1", "zl2", "sfr")
 METRIC_BITS = {n: 1 << i for i, n in enumerate(METRIC_NAMES)}
@@ -324,17 +324,27 @@ def score_and_flag_noalloc(claims, ref, results, metrics=("rel_l2",), tau=(0, 0,
     return results
 
 
+def fuse_norm_pays(desc) -> bool:
+    """Whether SV_FLAG_FUSE_NORM made the stage check faster where it was measured (one MI355X): it saves the norm
+    passes' HBM traffic and adds work to four epilogues, and the chip runs the products at its power limit either way.
+    d_model 2048 (k loops of 32 slices, epilogues a tenth of a product): 0.6-0.9 % faster.  d_model 4096: 1.3 % slower
+    (0.11 ms of norm passes saved, 0.2 ms more in the products, a third of it in their code and the rest with the
+    unnormalised operand and without the pauses between products).  Dense bf16 stages with RMSNorm only (a mixture of
+    experts can fold its first norm; that was not timed)."""
+    return desc.dtype == "bf16" and desc.norm == "rms" and desc.n_experts == 0 and desc.d_model <= 2048
+
+
 class Verifier:
     """One sv_ctx.  Tensors are torch tensors on the context's device, contiguous, in the stage dtype."""
 
     def __init__(self, desc, max_tokens: int, max_seq: int, backward: bool = False, plain_kernels: bool = False,
-                 sliced_w: bool = False):
+                 sliced_w: bool = False, fuse_norm: bool = False):
         import torch
         self.torch = torch
         self.desc = desc
         self.tdtype = torch.bfloat16 if desc.dtype == "bf16" else torch.float32
         self.flags = ((SV_FLAG_BACKWARD if backward else 0) | (SV_FLAG_PLAIN_KERNELS if plain_kernels else 0)
-                      | (SV_FLAG_SLICED_W if sliced_w else 0))
+                      | (SV_FLAG_SLICED_W if sliced_w else 0) | (SV_FLAG_FUSE_NORM if fuse_norm else 0))
         self._ctx = C.c_void_p()
         d = _desc_c(desc)
         st = lib.sv_create(C.byref(d), max_tokens, max_seq, self.flags, C.byref(self._ctx))
@@ -381,7 +391,8 @@ class Verifier:
         return ex, gt
 
     def prepare_weights(self, weights_c):
-        """Make the backward pass's transposed weight copies once; valid until the weights change (then call again)."""
+        """Make the context's weight copies once (transposed for backward, gain-folded with fuse_norm); valid until the
+        weights change (then call again)."""
         self._check(lib.sv_prepare_weights(self._ctx, weights_c, self._stream()))
 
     def _results(self, n: int):

@@ -73,6 +73,15 @@ struct sv_ctx {
   struct WT { void *wq, *wk, *wv, *wo, *wg, *wu, *wd, *wsg, *wsu, *wsd; };
   std::vector<WT> wT;                   // per block: the weights transposed to [in, out] (bf16 MFMA path, backward mode)
   std::vector<sv_block_weights> prepared;   // the weights sv_prepare_weights transposed (empty: none)
+  // RMSNorm inside the neighbouring products (SV_FLAG_FUSE_NORM, bf16 matrix-core path): per block the [out, in] weights
+  // that follow a norm with its gain folded in, the rows' 1 / rms, and the partial sums of squares that the product which
+  // writes a residual stream leaves for the norm that reads it (rowsq_of: the stream they belong to)
+  struct WF { void *wq, *wk, *wv, *wg, *wu; };
+  std::vector<WF> wF;
+  float* rstd = nullptr;
+  float* rowsq = nullptr;
+  int rowsq_planes = 0;   // d_model / 128
+  const void* rowsq_of = nullptr;
   float* delta;
   ScorePartial* score_scratch;
   float* attn_part;    // fp32 dk | dv contributions per query head of a group (backward, bf16 matrix-core path, one long sequence)
@@ -122,7 +131,7 @@ sv_status check_desc_impl(const sv_stage_desc* d, uint32_t flags, char* msg, int
   if (d->dtype != SV_F32 && d->dtype != SV_BF16) return fail(SV_EINVAL, "unknown dtype");
   if (!(d->norm_eps >= 0.0f)) return fail(SV_EINVAL, "norm_eps must be >= 0");
   if (d->rope && !(d->rope_theta > 0.0f)) return fail(SV_EINVAL, "rope_theta must be > 0");
-  if (flags & ~(uint32_t)(SV_FLAG_BACKWARD | SV_FLAG_PLAIN_KERNELS | SV_FLAG_SLICED_W)) return fail(SV_EINVAL, "unknown flag bits");
+  if (flags & ~(uint32_t)(SV_FLAG_BACKWARD | SV_FLAG_PLAIN_KERNELS | SV_FLAG_SLICED_W | SV_FLAG_FUSE_NORM)) return fail(SV_EINVAL, "unknown flag bits");
   if (d->d_model % d->n_heads) return fail(SV_EINVAL, "d_model must be a multiple of n_heads");
   if (d->n_heads % d->n_kv_heads) return fail(SV_EINVAL, "n_heads must be a multiple of n_kv_heads");
   const int hd = d->d_model / d->n_heads;
@@ -179,6 +188,21 @@ size_t carve(sv_ctx* c, char* base) {
     c->sw_w1 = (float*)a.take((size_t)kSwMaxClaims * kSwMaxDirs * sizeof(float));
     c->sw_proj_floats = (size_t)kSwSlots * kSwMaxDirs * (size_t)sw_padded_len(c->max_tokens);
     c->sw_proj = (float*)a.take(c->sw_proj_floats * sizeof(float));
+  }
+  c->wF.clear(); c->rstd = nullptr; c->rowsq = nullptr; c->rowsq_planes = 0;
+  if ((c->flags & SV_FLAG_FUSE_NORM) && d.dtype == SV_BF16 && d.norm == SV_NORM_RMS && !(c->flags & SV_FLAG_PLAIN_KERNELS)) {
+    c->rstd = (float*)a.take(T * sizeof(float));
+    c->rowsq_planes = (int)((D + 127) / 128);
+    c->rowsq = (float*)a.take(T * c->rowsq_planes * sizeof(float));
+    for (size_t l = 0; l < L; ++l) {
+      sv_ctx::WF f{};
+      f.wq = a.take(D * c->Dq * es); f.wk = a.take(D * c->Dkv * es); f.wv = a.take(D * c->Dkv * es);
+      if (!c->moe) {                                   // a mixture's second norm also feeds its router: it stays a pass of its own
+        f.wu = a.take(D * F * es);
+        f.wg = d.mlp == SV_MLP_SWIGLU ? a.take(D * F * es) : nullptr;
+      }
+      c->wF.push_back(f);
+    }
   }
   c->xbuf[0] = a.take(T * D * es);
   c->xbuf[1] = a.take(T * D * es);
@@ -373,7 +397,20 @@ GemmArgs nt(int M, int N, int K, const void* A, int64_t lda, const void* W, void
 // One block forward: x -> y.  keep (nullable) receives what backward needs.  Mixture-of-experts blocks write their routing
 // record and the expert outputs to keep's, else to `route` / `route_yp` (which the caller picks: the context's single
 // record on a forward-only context, block l's own on a backward context, so that sv_last_routing reads what ran last).
-sv_status block_forward(sv_ctx* c, const sv_block_weights& w, const void* x, void* y, int B, int S, BlockStash* keep, hipStream_t st,
+// The weights that follow the two norms of a block, with the norm's gain folded in: W'[n][k] = W[n][k] g[k].
+sv_status fold_block_weights(sv_ctx* c, const sv_block_weights& w, const sv_ctx::WF& f, hipStream_t st) {
+  const sv_stage_desc& d = c->d;
+  const int D = d.d_model, F = d.ffn_hidden;
+  SV_OP(c, SV_OP_NORM, 0, st, fold_gain(w.wq, w.norm1_g, f.wq, c->Dq, D, st));
+  SV_OP(c, SV_OP_NORM, 0, st, fold_gain(w.wk, w.norm1_g, f.wk, c->Dkv, D, st));
+  SV_OP(c, SV_OP_NORM, 0, st, fold_gain(w.wv, w.norm1_g, f.wv, c->Dkv, D, st));
+  if (f.wu) SV_OP(c, SV_OP_NORM, 0, st, fold_gain(w.w_up, w.norm2_g, f.wu, F, D, st));
+  if (f.wg) SV_OP(c, SV_OP_NORM, 0, st, fold_gain(w.w_gate, w.norm2_g, f.wg, F, D, st));
+  return SV_OK;
+}
+
+// l: the block's index (its folded weights), or -1 for weights that have none
+sv_status block_forward(sv_ctx* c, int l, const sv_block_weights& w, const void* x, void* y, int B, int S, BlockStash* keep, hipStream_t st,
                         const MoeRoute* route = nullptr, void* route_yp = nullptr) {
   const sv_stage_desc& d = c->d;
   const int T = B * S, D = d.d_model, F = d.ffn_hidden, es = c->es, dt = d.dtype;
@@ -382,9 +419,49 @@ sv_status block_forward(sv_ctx* c, const sv_block_weights& w, const void* x, voi
   void* x1 = keep ? keep->x1 : c->x1;
   float* lse = keep ? keep->lse : c->lse;
 
+  // RMSNorm inside the products: the product after a norm reads the residual stream itself, against weights that carry the
+  // gain, and scales its rows by their 1 / rms; that comes from the sums of squares the product which wrote the stream
+  // left behind, or from one read of the stream (the stage input; streams written by the small-tile kernels).
+  const bool fuse = !c->wF.empty() && l >= 0;
+  sv_ctx::WF wf{};
+  if (fuse) {
+    wf = c->wF[l];
+    const bool ready = (int)c->prepared.size() == d.n_blocks && memcmp(&c->prepared[l], &w, sizeof(w)) == 0;
+    if (!ready) {
+      sv_status s = fold_block_weights(c, w, wf, st);
+      if (s != SV_OK) return s;
+    }
+  }
+  auto row_rstd = [&](const void* stream) -> sv_status {
+    if (c->rowsq_of == stream) SV_OP(c, SV_OP_NORM, 0, st, rms_rstd_from_partials(c->rowsq, c->rowsq_planes, T, c->rstd, T, D, d.norm_eps, st));
+    else SV_OP(c, SV_OP_NORM, 0, st, rms_rstd(stream, c->rstd, T, D, d.norm_eps, st));
+    return SV_OK;
+  };
+  // a product that writes a residual stream leaves the sums of squares of its rows when the kernel it runs on can
+  auto leave_rowsq = [&](GemmArgs& g) {
+    c->rowsq_of = nullptr;
+    if (!fuse) return;
+    g.rowsq = c->rowsq; g.rowsq_ld = T;                // planes of T floats
+    if (dt == SV_BF16 && !(c->flags & SV_FLAG_PLAIN_KERNELS) && mfma_gemm_emits_rowsq(g)) c->rowsq_of = g.C;
+    else { g.rowsq = nullptr; g.rowsq_ld = 0; }
+  };
+
   const double Td = T, attn_flop = (d.causal ? 2.0 : 4.0) * B * d.n_heads * (double)S * S * c->hd;
-  SV_OP(c, SV_OP_NORM, 0, st, plain_norm_fwd(x, w.norm1_g, w.norm1_b, c->n, T, D, d.norm, d.norm_eps, dt, st));
-  {
+  bool fused1 = false;
+  if (fuse) {
+    GemmArgs f = nt(T, c->Dqkv, D, x, D, wf.wq, qkv, c->Dqkv, d.rope ? EPI_ROPE : EPI_STORE);
+    f.nbcol = 3; f.Bcol[0] = wf.wq; f.Bcol[1] = wf.wk; f.Bcol[2] = wf.wv; f.ncol[0] = c->Dq; f.ncol[1] = c->Dkv; f.ncol[2] = c->Dkv;
+    f.rope_cs = c->rope_cs; f.rope_S = S; f.rope_hd = c->hd; f.rope_cols = c->Dq + c->Dkv;
+    f.rscale = c->rstd;
+    if (mfma_gemm_supported(f)) {                      // the one-launch q | k | v product: the large tile only
+      sv_status s = row_rstd(x);
+      if (s != SV_OK) return s;
+      SV_OP(c, SV_OP_GEMM_QKV, 2.0 * Td * c->Dqkv * D, st, mfma_gemm(f, st));
+      fused1 = true;
+    }
+  }
+  if (!fused1) {
+    SV_OP(c, SV_OP_NORM, 0, st, plain_norm_fwd(x, w.norm1_g, w.norm1_b, c->n, T, D, d.norm, d.norm_eps, dt, st));
     // one launch over the concatenated [q | k | v] columns with RoPE in the epilogue when the kernel can do it
     GemmArgs f = nt(T, c->Dqkv, D, c->n, D, w.wq, qkv, c->Dqkv, d.rope ? EPI_ROPE : EPI_STORE);
     f.nbcol = 3; f.Bcol[0] = w.wq; f.Bcol[1] = w.wk; f.Bcol[2] = w.wv; f.ncol[0] = c->Dq; f.ncol[1] = c->Dkv; f.ncol[2] = c->Dkv;
@@ -399,11 +476,39 @@ sv_status block_forward(sv_ctx* c, const sv_block_weights& w, const void* x, voi
     }
   }
   SV_OP(c, SV_OP_ATTN, attn_flop, st, attn_fwd(c, qkv, o, lse, B, S, st));
+  // the second norm runs inside the MLP's first product when that product can scale its rows
+  GemmArgs up{};
+  bool fused2 = false;
+  if (fuse && !c->moe) {
+    if (d.mlp == SV_MLP_SWIGLU) { up = nt(T, F, D, x1, D, wf.wg, c->act, F, EPI_SWIGLU); up.B2 = wf.wu; up.ldb2 = D; }
+    else up = nt(T, F, D, x1, D, wf.wu, c->act, F, EPI_GELU);
+    up.rscale = c->rstd;
+    fused2 = mfma_gemm_supported(up);
+  }
   {
     GemmArgs g = nt(T, D, c->Dq, o, c->Dq, w.wo, x1, D, EPI_RESID);
     g.R = x; g.ldr = D;
+    if (fused2) leave_rowsq(g); else c->rowsq_of = nullptr;
     SV_OP(c, SV_OP_GEMM_O, 2.0 * Td * D * c->Dq, st, gemm(c, g, st));
   }
+  if (fused2) {
+    sv_status s = row_rstd(x1);
+    if (s != SV_OK) return s;
+    if (d.mlp == SV_MLP_SWIGLU) {
+      if (keep) { up.C2 = keep->gate; up.C3 = keep->up; }
+      SV_OP(c, SV_OP_GEMM_GATEUP, 4.0 * Td * F * D, st, gemm(c, up, st));
+    } else {
+      if (keep) up.C2 = keep->up;
+      SV_OP(c, SV_OP_GEMM_GATEUP, 2.0 * Td * F * D, st, gemm(c, up, st));
+    }
+    GemmArgs g = nt(T, D, F, c->act, F, w.w_down, y, D, EPI_RESID);
+    g.R = x1; g.ldr = D;
+    if (l + 1 < d.n_blocks) leave_rowsq(g);            // for the first norm of the next block
+    else c->rowsq_of = nullptr;
+    SV_OP(c, SV_OP_GEMM_DOWN, 2.0 * Td * D * F, st, gemm(c, g, st));
+    return SV_OK;
+  }
+  c->rowsq_of = nullptr;
   SV_OP(c, SV_OP_NORM, 0, st, plain_norm_fwd(x1, w.norm2_g, w.norm2_b, c->n, T, D, d.norm, d.norm_eps, dt, st));
   if (c->moe) {
     // shared experts on the dense path (their output lands in y on top of the residual), then the routed experts:
@@ -718,6 +823,7 @@ sv_status sv_verify_forward(sv_ctx* c, const sv_block_weights* w, const void* h_
   const int L = c->d.n_blocks;
   const bool bwd = c->flags & SV_FLAG_BACKWARD;
   c->last_T = B * S;
+  c->rowsq_of = nullptr;
   const void* x = h_in;
   void* y = nullptr;
   for (int l = 0; l < L; ++l) {
@@ -725,7 +831,7 @@ sv_status sv_verify_forward(sv_ctx* c, const sv_block_weights* w, const void* h_
     else y = bwd ? c->xs[l] : c->xbuf[l & 1];
     // a backward context owns one routing record per block and none of its own
     const bool own = c->moe && bwd;
-    s = block_forward(c, w[l], x, y, B, S, nullptr, st, own ? &c->stash[l].route : nullptr, own ? c->stash[l].yp : nullptr);
+    s = block_forward(c, l, w[l], x, y, B, S, nullptr, st, own ? &c->stash[l].route : nullptr, own ? c->stash[l].yp : nullptr);
     if (s != SV_OK) return s;
     x = y;
   }
@@ -745,10 +851,11 @@ sv_status sv_verify_backward(sv_ctx* c, const sv_block_weights* w, const void* h
   hipStream_t st = (hipStream_t)stream;
   const int L = c->d.n_blocks;
   c->last_T = B * S;
+  c->rowsq_of = nullptr;
   const void* x = h_in;
   for (int l = 0; l < L; ++l) {
     void* y = (l == L - 1) ? (h_hat_out ? h_hat_out : c->xbuf[0]) : c->xs[l];
-    s = block_forward(c, w[l], x, y, B, S, &c->stash[l], st);
+    s = block_forward(c, l, w[l], x, y, B, S, &c->stash[l], st);
     if (s != SV_OK) return s;
     x = y;
   }
@@ -787,15 +894,16 @@ sv_status sv_prepare_weights(sv_ctx* c, const sv_block_weights* w, void* stream)
   if (!c) return SV_EINVAL;
   c->prepared.clear();
   if (!w) return SV_OK;                               // forget the prepared copies
-  if (c->wT.empty()) return SV_OK;                     // this context transposes nothing (forward only, fp32 or plain kernels)
+  if (c->wT.empty() && c->wF.empty()) return SV_OK;   // this context keeps no copies (fp32, plain kernels, or forward only without SV_FLAG_FUSE_NORM)
   for (int l = 0; l < c->d.n_blocks; ++l) {
     const sv_block_weights& b = w[l];
-    if (!(b.wq && b.wk && b.wv && b.wo && b.w_up && b.w_down) || (c->d.mlp == SV_MLP_SWIGLU && !b.w_gate) ||
+    if (!(b.wq && b.wk && b.wv && b.wo && b.w_up && b.w_down && b.norm1_g && b.norm2_g) || (c->d.mlp == SV_MLP_SWIGLU && !b.w_gate) ||
         (c->moe && (!b.w_router || (c->Fd > 0 && !(b.ws_gate && b.ws_up && b.ws_down))))) {
       set_err(c, "block %d: a required weight pointer is NULL", l);
       return SV_EINVAL;
     }
-    sv_status s = transpose_block_weights(c, b, c->wT[l], (hipStream_t)stream);
+    sv_status s = c->wT.empty() ? SV_OK : transpose_block_weights(c, b, c->wT[l], (hipStream_t)stream);
+    if (s == SV_OK && !c->wF.empty()) s = fold_block_weights(c, b, c->wF[l], (hipStream_t)stream);
     if (s != SV_OK) return s;
   }
   c->prepared.assign(w, w + c->d.n_blocks);

@@ -172,12 +172,26 @@ struct GemmArgs {
   const int32_t* m_dev;
   // optional: fp32 scratch for split-k partial products (small row counts against a long k); none = never split
   float* split_ws; int64_t split_ws_floats;
+  // optional, the two ends of an RMSNorm that runs inside its neighbouring products (its gain folded into the weights of
+  // the product that follows):
+  //   rscale: row m of the accumulators is multiplied by rscale[m] -- the row's 1 / rms -- before the epilogue's own
+  //           function (EPI_STORE, EPI_GELU, EPI_SWIGLU, EPI_ROPE)
+  //   rowsq : EPI_RESID on the 256 x 256 direct-to-LDS kernel (mfma_gemm_emits_rowsq) also writes, for every row m and
+  //           every 128 columns j, rowsq[j * rowsq_ld + m] = the sum of squares of the 128 values it stored (rowsq_ld >= M)
+  const float* rscale;
+  float* rowsq; int rowsq_ld;
 };
 
 // kernels_plain.hip: any shape, fp32 math, E = float | bf16 by `dtype`
 hipError_t plain_gemm(const GemmArgs& a, int dtype, hipStream_t st);
 hipError_t plain_norm_fwd(const void* x, const void* g, const void* b, void* out, int64_t T, int D, int kind, float eps,
                           int dtype, hipStream_t st);
+// RMSNorm in pieces, bf16 rows: rstd[t] = 1 / sqrt(mean_k x[t][k]^2 + eps) straight from the rows, or from the P partial sums of
+// squares per row that a product's epilogue left (GemmArgs::rowsq: P planes of ld floats); out[n][k] = W[n][k] * g[k] folds the gain into the [N, K]
+// weights of the product that follows the norm
+hipError_t rms_rstd(const void* x, float* rstd, int64_t T, int D, float eps, hipStream_t st);
+hipError_t rms_rstd_from_partials(const float* part, int P, int64_t ld, float* rstd, int64_t T, int D, float eps, hipStream_t st);
+hipError_t fold_gain(const void* W, const void* g, void* out, int64_t N, int K, hipStream_t st);
 // out = dres + d/dx [ Norm(x) ] applied to dn
 hipError_t plain_norm_bwd_add(const void* dn, const void* x, const void* g, const void* dres, void* out, int64_t T, int D,
                               int kind, float eps, int dtype, hipStream_t st);
@@ -223,6 +237,7 @@ hipError_t launch_moe_combine_bwd(const void* dy, const void* yp, const void* dx
 
 // gemm_mfma.hip: bf16 only; returns hipErrorInvalidValue if the shape is outside its limits
 bool mfma_gemm_supported(const GemmArgs& a);
+bool mfma_gemm_emits_rowsq(const GemmArgs& a);          // would mfma_gemm(a, st) fill a.rowsq?
 hipError_t mfma_gemm(const GemmArgs& a, hipStream_t st, int tile = 0);   // tile: 0 auto, 1 = 256x256, 2 = 128x128
 
 // attn_mfma.hip: bf16, head_dim 64 | 128.  scale_hd (0 = hd): the head dimension the softmax scale 1/sqrt(.) is taken from,

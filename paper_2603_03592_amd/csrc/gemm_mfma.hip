@@ -49,6 +49,11 @@ struct Cfg {
   static_assert(!KN || WCH % 8 == 0, "a [K,N] operand is staged in whole 8x8 blocks per thread");
 };
 
+// x of the lane N places further on in its row of 16 lanes (cyclic)
+template <int N> __device__ __forceinline__ float dpp_row_ror(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x120 + N, 0xf, 0xf, false));
+}
+
 // Epilogue on 4 consecutive output features of one token row, in two phases so that a caller can
 // issue all loads of a row block before the first store (the output and the residual / gate / up
 // buffers may alias as far as the compiler knows, so loads are never hoisted over stores for us).
@@ -65,11 +70,18 @@ __device__ __forceinline__ void epilogue_load4(const GemmArgs& a, int m, int n, 
   }
 }
 
+// rs multiplies the accumulators first (GemmArgs::rscale; the kinds that can follow a norm).  Returns the sum of squares of
+// the four values as stored.
 template <int EPI>
-__device__ __forceinline__ void epilogue_apply4(const GemmArgs& a, int m, int n, const float (&v)[4], const float (&u)[4], const EpiIn& in) {
+__device__ __forceinline__ float epilogue_apply4(const GemmArgs& a, int m, int n, const float (&v_in)[4], const float (&u_in)[4], const EpiIn& in,
+                                                 float rs = 1.0f) {
   const int64_t ic = (int64_t)m * a.ldc + n;
   const bf16x4& r = in.r;
   const bf16x4& r2 = in.r2;
+  constexpr bool kScaled = EPI == EPI_STORE || EPI == EPI_GELU || EPI == EPI_SWIGLU || EPI == EPI_ROPE;
+  float v[4], u[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { v[i] = kScaled ? v_in[i] * rs : v_in[i]; u[i] = kScaled ? u_in[i] * rs : u_in[i]; }
   float o[4];
   switch (EPI) {
     case EPI_STORE:
@@ -119,10 +131,15 @@ __device__ __forceinline__ void epilogue_apply4(const GemmArgs& a, int m, int n,
       break;
   }
   bf16x4 p;
+  float sq = 0.0f;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) p[i] = (bf16)o[i];
+  for (int i = 0; i < 4; ++i) { p[i] = (bf16)o[i]; sq = fmaf((float)p[i], (float)p[i], sq); }
   *reinterpret_cast<bf16x4*>((bf16*)a.C + ic) = p;
+  return sq;
 }
+
+// does this kind of epilogue take GemmArgs::rscale?
+template <int EPI> constexpr bool kEpiScaled = EPI == EPI_STORE || EPI == EPI_GELU || EPI == EPI_SWIGLU || EPI == EPI_ROPE;
 
 // The accumulators of one 32-row block of a wave tile: NIO feature blocks of 32 (the second half of the
 // accumulator blocks is the `up` product of a dual launch).  Per feature block: its four loads first,
@@ -130,6 +147,7 @@ __device__ __forceinline__ void epilogue_apply4(const GemmArgs& a, int m, int n,
 template <int EPI, int NIO, int NI, int MI>
 __device__ __forceinline__ void epilogue_rows(const GemmArgs& a, int M, const f32x16 (&acc)[NI][MI], int mi, int m, int nbase) {
   if (m >= M) return;
+  const float rs = kEpiScaled<EPI> && a.rscale ? a.rscale[m] : 1.0f;
 #pragma unroll
   for (int ni = 0; ni < NIO; ++ni) {
     EpiIn in[4];
@@ -143,7 +161,7 @@ __device__ __forceinline__ void epilogue_rows(const GemmArgs& a, int M, const f3
         v[i] = acc[ni][mi][q * 4 + i];
         u[i] = (EPI == EPI_SWIGLU) ? acc[ni + (NIO < NI ? NIO : 0)][mi][q * 4 + i] : 0.0f;
       }
-      epilogue_apply4<EPI>(a, m, nbase + ni * 32 + q * 8, v, u, in[q]);
+      epilogue_apply4<EPI>(a, m, nbase + ni * 32 + q * 8, v, u, in[q], rs);
     }
   }
 }
@@ -394,7 +412,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmArgs a, int nspl
   for (int i = 0; i < 4; ++i) v[i] = sum[i];
   EpiIn in;
   epilogue_load4<EPI>(a, m, n, in);
-  epilogue_apply4<EPI>(a, m, n, v, u, in);
+  epilogue_apply4<EPI>(a, m, n, v, u, in, kEpiScaled<EPI> && a.rscale ? a.rscale[m] : 1.0f);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -416,9 +434,13 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmArgs a, int nspl
 // GROUPED: the grouped form (per-row-block weight group, row count from device memory) as its own instantiation, so
 // that the dense form's code -- in particular its waits, which scalar loads in the tile-change path would disturb
 // (they share a counter with the LDS reads) -- is unaffected by it.
-template <int EPI, bool GROUPED>
+//
+// NF: the forms that stand at the two ends of an RMSNorm run inside the products (their own instantiations, for the same
+// reason): the kinds that can follow a norm multiply every row by GemmArgs::rscale, EPI_RESID also writes GemmArgs::rowsq.
+template <int EPI, bool GROUPED, bool NF = false>
 __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tiles_m, int tiles_n) {
   constexpr bool DUAL = EPI == EPI_SWIGLU;
+  constexpr bool RS = NF && kEpiScaled<EPI>, SQ = NF && EPI == EPI_RESID;
   constexpr int BM = 256, BN = 256, STAGE = (BM + BN) * 128, MI = 4, NI = 4;
   constexpr int NOUT = DUAL ? 128 : 256;
   extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -563,6 +585,13 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     SV_SB;
+    // the row factors of the wave's 128 rows are asked for here, a whole k loop before the epilogue wants them (its
+    // first loads would otherwise start with a memory round trip per tile); the next wait for memory is a slice away
+    float rs_pre0 = 1.0f, rs_pre1 = 1.0f;
+    if (RS) {
+      rs_pre0 = a.rscale[min(m0 + wm * 128 + lane, M - 1)];
+      rs_pre1 = a.rscale[min(m0 + wm * 128 + 64 + lane, M - 1)];
+    }
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       xf0[g] = *reinterpret_cast<const bf16x8*>(smem + par * STAGE + lds_off(xrow[g], lhi));
@@ -597,6 +626,11 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
     __syncthreads();                                   // everybody is done reading stage sl
     char* patch = smem + sl * STAGE + wave * 16384;
     const int er = lane >> 4, ec4 = lane & 15;         // read-back: row er of each group of 4 rows, 16-byte chunk ec4 (and 16 + ec4)
+    // per wave, behind the two stages: the row factors of its 128 rows (each lane of the read-back needs those of the
+    // rows it serves) and the rows' sums of squares (stored in one piece when the tile is done)
+    float* rsbuf = reinterpret_cast<float*>(smem + 2 * STAGE) + wave * 256;
+    float* sqbuf = rsbuf + 128;
+    if (RS) { rsbuf[lane] = rs_pre0; rsbuf[64 + lane] = rs_pre1; }
     int rope_p0 = 0, rope_i0_lo = 0, rope_i0_hi = 0;
     if (EPI == EPI_ROPE) {
       const int nlo = n0 + wn * 128 + ec4 * 4, nhi = nlo + 64;
@@ -627,6 +661,10 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
           // ordinary registers from one use to the next and spills them.  The matrix pipe's last write is long
           // finished (a workgroup barrier lies in between); the wait states make that formal, since the compiler's
           // own hazard handling does not look into assembly.
+          float rsv[MI];
+          if (RS) { __builtin_amdgcn_s_waitcnt(0xc07f); __builtin_amdgcn_wave_barrier(); }   // the factors are in LDS
+#pragma unroll
+          for (int mi = 0; mi < MI; ++mi) rsv[mi] = RS ? rsbuf[mi * 32 + r31] : 1.0f;
           asm volatile("s_nop 15\n\ts_nop 15");
           auto rd = [&](int ni, int mi, int r) {
             float x;
@@ -641,7 +679,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
               for (int q = 0; q < 4; ++q) {
                 bf16x4 pk;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) pk[i] = (bf16)(silu_f(rd(ni, mi, q * 4 + i)) * rd(ni + 2, mi, q * 4 + i));
+                for (int i = 0; i < 4; ++i) pk[i] = (bf16)(silu_f(rd(ni, mi, q * 4 + i) * rsv[mi]) * (rd(ni + 2, mi, q * 4 + i) * rsv[mi]));
                 const int row = mi * 32 + r31;
                 *reinterpret_cast<bf16x4*>(patch + row * 128 + (((ni * 4 + q) ^ ((r31 >> 1) & 7)) << 4) + rhi * 8) = pk;
                 if (q == 3) SV_SB;                       // one feature block at a time
@@ -713,12 +751,26 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
 #pragma unroll
           for (int i = 0; i < 4; ++i) { lo[i] = a_lo[i]; hi[i] = a_hi[i]; }
           if (CHECK && m >= M) continue;
-          if (DUAL) epilogue_apply4<EPI>(a, m, n0 + wn * 64 + ec4 * 4, lo, hi, in_lo[trip & 1][k]);   // patch columns 0..63: gate, 64..127: up
+          const float rs = RS ? rsbuf[mi * 32 + row] : 1.0f;
+          if (DUAL) epilogue_apply4<EPI>(a, m, n0 + wn * 64 + ec4 * 4, lo, hi, in_lo[trip & 1][k], rs);   // patch columns 0..63: gate, 64..127: up
           else {
-            epilogue_apply4<EPI>(a, m, n0 + wn * 128 + ec4 * 4, lo, hi, in_lo[trip & 1][k]);
-            epilogue_apply4<EPI>(a, m, n0 + wn * 128 + 64 + ec4 * 4, hi, lo, in_hi[trip & 1][k]);
+            float sq = epilogue_apply4<EPI>(a, m, n0 + wn * 128 + ec4 * 4, lo, hi, in_lo[trip & 1][k], rs);
+            sq += epilogue_apply4<EPI>(a, m, n0 + wn * 128 + 64 + ec4 * 4, hi, lo, in_hi[trip & 1][k], rs);
+            if (SQ) {
+              // the 16 lanes of a row hold its 128 stored values: rotate-and-add within the row of 16 lanes leaves the
+              // sum in all of them, and all of them write it (one LDS address per row, no per-lane condition)
+              sq += dpp_row_ror<8>(sq); sq += dpp_row_ror<4>(sq); sq += dpp_row_ror<2>(sq); sq += dpp_row_ror<1>(sq);
+              sqbuf[mi * 32 + row] = sq;
+            }
           }
         }
+      }
+      if (SQ) {                                          // 128 consecutive floats of plane (n0 / 128 + wn): two full-line stores
+        __builtin_amdgcn_s_waitcnt(0xc07f);
+        __builtin_amdgcn_wave_barrier();
+        float* plane = a.rowsq + (int64_t)((n0 >> 7) + wn) * a.rowsq_ld + m0 + wm * 128;
+        if (!CHECK || m0 + wm * 128 + lane < M) plane[lane] = sqbuf[lane];
+        if (!CHECK || m0 + wm * 128 + 64 + lane < M) plane[64 + lane] = sqbuf[64 + lane];
       }
     };
     if (m0 + 256 <= M) run_epilogue(std::false_type{});
@@ -730,10 +782,10 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
 #undef SV_SB
 }
 
-template <int EPI, bool GROUPED>
+template <int EPI, bool GROUPED, bool NF = false>
 hipError_t launch_dma(const GemmArgs& a, hipStream_t st) {
-  auto kern = gemm_mfma_dma_kernel<EPI, GROUPED>;
-  constexpr int lds = 2 * 512 * 128;
+  auto kern = gemm_mfma_dma_kernel<EPI, GROUPED, NF>;
+  constexpr int lds = 2 * 512 * 128 + 4 * 1024;           // two stages, and per wave 128 row factors + 128 row sums
   static bool configured = false;
   if (!configured) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
@@ -805,8 +857,24 @@ bool use_big_tile(const GemmArgs& a) {
 
 }  // namespace
 
+namespace {
+// the 256 x 256 direct-to-LDS kernel serves this product (the DMA offsets are 32-bit byte offsets within a 256-row panel)
+bool takes_dma_kernel(const GemmArgs& a) {
+  if (a.b_is_kn || !use_big_tile(a)) return false;
+  for (int s = 0; s < a.nseg; ++s)
+    if (!(256 * a.seg[s].lda * 2 < (int64_t)1 << 32 && 256 * a.seg[s].ldb * 2 < (int64_t)1 << 32)) return false;
+  return !(a.epi == EPI_SWIGLU && a.ldc % 8);            // its epilogue stores 16 bytes per lane
+}
+}  // namespace
+
+bool mfma_gemm_emits_rowsq(const GemmArgs& a) {
+  return a.rowsq && a.epi == EPI_RESID && !a.tile_group && mfma_gemm_supported(a) && takes_dma_kernel(a);
+}
+
 bool mfma_gemm_supported(const GemmArgs& a) {
   if (a.M < 1 || a.nseg < 1 || a.nseg > 3) return false;
+  if (a.rscale && (a.tile_group || (a.epi != EPI_STORE && a.epi != EPI_GELU && a.epi != EPI_SWIGLU && a.epi != EPI_ROPE))) return false;
+  if (a.rowsq && (a.epi != EPI_RESID || a.rowsq_ld < a.M)) return false;
   const bool dual = a.epi == EPI_SWIGLU;
   if (dual && (a.b_is_kn || a.nseg != 1 || !a.B2 || a.ldb2 % 8 || !aligned16(a.B2))) return false;
   if (a.epi < EPI_STORE || a.epi > EPI_ROPE) return false;
@@ -840,8 +908,7 @@ hipError_t mfma_gemm(const GemmArgs& a, hipStream_t st, int tile) {
   if ((tile == 1 || tile == 3) && a.N % (a.epi == EPI_SWIGLU ? 128 : 256)) return hipErrorInvalidValue;
   const bool big = tile == 1 || tile == 3 || (tile == 0 && use_big_tile(a));
   if (!a.b_is_kn && big && tile != 3) {
-    // the DMA offsets are 32-bit byte offsets within a 256-row panel
-    bool fits = true;
+    bool fits = true;                                      // as in takes_dma_kernel, for a forced tile too
     for (int s = 0; s < a.nseg; ++s) fits = fits && 256 * a.seg[s].lda * 2 < (int64_t)1 << 32 && 256 * a.seg[s].ldb * 2 < (int64_t)1 << 32;
     if (a.epi == EPI_SWIGLU && a.ldc % 8) fits = false;       // its epilogue stores 16 bytes per lane
     if (fits) {
@@ -850,6 +917,16 @@ hipError_t mfma_gemm(const GemmArgs& a, hipStream_t st, int tile) {
           case EPI_STORE: return launch_dma<EPI_STORE, true>(a, st);
           case EPI_SWIGLU: return launch_dma<EPI_SWIGLU, true>(a, st);
           case EPI_SWIGLU_BWD: return launch_dma<EPI_SWIGLU_BWD, true>(a, st);
+          default: return hipErrorInvalidValue;
+        }
+      }
+      if (a.rscale || a.rowsq) {
+        switch (a.epi) {                                   // the ends of a norm that runs inside the products
+          case EPI_STORE: return launch_dma<EPI_STORE, false, true>(a, st);
+          case EPI_RESID: return launch_dma<EPI_RESID, false, true>(a, st);
+          case EPI_GELU: return launch_dma<EPI_GELU, false, true>(a, st);
+          case EPI_SWIGLU: return launch_dma<EPI_SWIGLU, false, true>(a, st);
+          case EPI_ROPE: return launch_dma<EPI_ROPE, false, true>(a, st);
           default: return hipErrorInvalidValue;
         }
       }

@@ -133,6 +133,39 @@ __global__ __launch_bounds__(256) void norm_fwd_kernel(const E* __restrict__ x, 
   }
 }
 
+// The pieces of an RMSNorm that runs inside its neighbouring products.
+__global__ __launch_bounds__(256) void rms_rstd_kernel(const bf16* __restrict__ x, float* __restrict__ rstd, int64_t T, int D, float eps) {
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);          // one wave per row
+  if (row >= T) return;
+  const bf16* xr = x + row * D;
+  float ss = 0.0f;
+  for (int k = (threadIdx.x & 63) * 8; k < D; k += 512) { float v[8]; load8(xr + k, v);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) ss += v[j] * v[j]; }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+  if ((threadIdx.x & 63) == 0) rstd[row] = rsqrtf(ss / (float)D + eps);
+}
+__global__ __launch_bounds__(256) void rms_rstd_partials_kernel(const float* __restrict__ part, int P, int64_t ld, float* __restrict__ rstd,
+                                                                int64_t T, int D, float eps) {
+  const int64_t row = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (row >= T) return;
+  float ss = 0.0f;
+  for (int j = 0; j < P; ++j) ss += part[j * ld + row];                        // fixed order: run-to-run identical
+  rstd[row] = rsqrtf(ss / (float)D + eps);
+}
+__global__ __launch_bounds__(256) void fold_gain_kernel(const bf16* __restrict__ W, const bf16* __restrict__ g, bf16* __restrict__ out,
+                                                        int64_t n8, int K) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;                  // one thread per 8 consecutive k
+  if (i >= n8) return;
+  const int k = (int)((i * 8) % K);
+  float w[8], gv[8], o[8];
+  load8(W + i * 8, w); load8(g + k, gv);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) o[j] = w[j] * gv[j];
+  store8(out + i * 8, o);
+}
+
 // out = dres + J_norm(x)^T dn.  RMS: gd/r - x * sum(gd*x) / (D r^3).  LN: (gd - mean(gd) - xh*mean(gd*xh)) / sd.
 template <typename E>
 __global__ __launch_bounds__(256) void norm_bwd_add_kernel(const E* __restrict__ dn, const E* __restrict__ x, const E* __restrict__ g,
@@ -462,6 +495,25 @@ hipError_t plain_norm_fwd(const void* x, const void* g, const void* b, void* out
     hipLaunchKernelGGL(norm_fwd_kernel<bf16>, dim3((unsigned)T), dim3(256), 0, st, (const bf16*)x, (const bf16*)g, (const bf16*)b, (bf16*)out, D, kind, eps);
   else
     hipLaunchKernelGGL(norm_fwd_kernel<float>, dim3((unsigned)T), dim3(256), 0, st, (const float*)x, (const float*)g, (const float*)b, (float*)out, D, kind, eps);
+  return hipGetLastError();
+}
+
+hipError_t rms_rstd(const void* x, float* rstd, int64_t T, int D, float eps, hipStream_t st) {
+  if (T <= 0) return hipSuccess;
+  if (D % 8) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(rms_rstd_kernel, dim3((unsigned)((T + 3) / 4)), dim3(256), 0, st, (const bf16*)x, rstd, T, D, eps);
+  return hipGetLastError();
+}
+hipError_t rms_rstd_from_partials(const float* part, int P, int64_t ld, float* rstd, int64_t T, int D, float eps, hipStream_t st) {
+  if (T <= 0) return hipSuccess;
+  hipLaunchKernelGGL(rms_rstd_partials_kernel, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, st, part, P, ld, rstd, T, D, eps);
+  return hipGetLastError();
+}
+hipError_t fold_gain(const void* W, const void* g, void* out, int64_t N, int K, hipStream_t st) {
+  if (N <= 0) return hipSuccess;
+  if (K % 8) return hipErrorInvalidValue;
+  const int64_t n8 = N * K / 8;
+  hipLaunchKernelGGL(fold_gain_kernel, dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, st, (const bf16*)W, (const bf16*)g, (bf16*)out, n8, K);
   return hipGetLastError();
 }
 

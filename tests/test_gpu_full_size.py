@@ -35,9 +35,11 @@ def test_small_config_64_submissions():
     import paper_2603_03592_amd as sv
     wl = si.SMALL
     w = si.make_weights(wl.desc, 0)
-    ver = sv.Verifier(wl.desc, wl.batch * wl.seq, wl.seq)
+    assert sv.fuse_norm_pays(wl.desc)                       # as bench.py runs it: the norms inside the products
+    ver = sv.Verifier(wl.desc, wl.batch * wl.seq, wl.seq, fuse_norm=True)
     wd = dev_weights(w, "bf16")
     wc = ver.pack_weights(wd)
+    ver.prepare_weights(wc)
     kinds = si.small_claim_plan(64, seed=0)
     assert kinds.count("scale") == 6 and kinds.count("sign") == 6
     worst_honest, n = 0.0, 0
@@ -65,9 +67,10 @@ def test_medium_config_forward_backward():
     import paper_2603_03592_amd as sv
     wl = si.MEDIUM
     w = si.make_weights(wl.desc, 0)
-    ver = sv.Verifier(wl.desc, wl.batch * wl.seq, wl.seq, backward=True)
+    ver = sv.Verifier(wl.desc, wl.batch * wl.seq, wl.seq, backward=True, fuse_norm=True)
     wd = dev_weights(w, "bf16")
     wc = ver.pack_weights(wd)
+    ver.prepare_weights(wc)
     for mb in (0, 1):                                      # two distinct micro-batches
         h = si.make_activations(wl.desc, wl.batch, wl.seq, seed=0, micro_batch=mb)
         g = si.make_output_grad(wl.desc, wl.batch, wl.seq, seed=0, micro_batch=mb)
@@ -102,10 +105,19 @@ def test_large_config_32_submissions_token_corruption():
     w = si.make_weights(wl.desc, 0)
     h = si.make_activations(wl.desc, wl.batch, wl.seq, seed=0)
     ref = so.stage_forward(h, w, wl.desc)
-    ver = sv.Verifier(wl.desc, wl.batch * wl.seq, wl.seq)
     wd = dev_weights(w, "bf16")
-    wc = ver.pack_weights(wd)
     hd = dev(h, "bf16")
+    # the other form of the norms first (inside the products: row sums from the large tile's residual epilogue, the
+    # one-launch q | k | v product and the gate / up product scaling their rows), then the one bench.py times here
+    assert not sv.fuse_norm_pays(wl.desc)
+    ver = sv.Verifier(wl.desc, wl.batch * wl.seq, wl.seq, fuse_norm=True)
+    wc = ver.pack_weights(wd)
+    ver.prepare_weights(wc)
+    e = assert_close(host(ver.verify_forward(wc, hd, want_h_hat=True)["h_hat"]), ref, 2e-2, "large, norms inside the products")
+    print(f"large, norms inside the products: rel-L2 {e[0]:.3e} worst token {e[1]:.3e} worst element {e[2]:.2f} of its bound")
+    ver.close()
+    ver = sv.Verifier(wl.desc, wl.batch * wl.seq, wl.seq)
+    wc = ver.pack_weights(wd)
     got = host(ver.verify_forward(wc, hd, want_h_hat=True)["h_hat"])
     e = assert_close(got, ref, 2e-2, "large")
     print(f"large: rel-L2 {e[0]:.3e} worst token {e[1]:.3e} worst element {e[2]:.2f} of its bound")
@@ -138,9 +150,10 @@ def test_sweep_point_forward_backward():
     h = si.make_activations(wl.desc, wl.batch, wl.seq, seed=1)
     g = si.make_output_grad(wl.desc, wl.batch, wl.seq, seed=1)
     ref_h, ref_g = so.stage_backward(h, g, w, wl.desc)
-    ver = sv.Verifier(wl.desc, wl.batch * wl.seq, wl.seq, backward=True)
+    ver = sv.Verifier(wl.desc, wl.batch * wl.seq, wl.seq, backward=True, fuse_norm=sv.fuse_norm_pays(wl.desc))
     wd = dev_weights(w, "bf16")
     wc = ver.pack_weights(wd)
+    ver.prepare_weights(wc)
     out = ver.verify_backward(wc, dev(h, "bf16"), dev(g, "bf16"), want_g_hat=True, want_h_hat=True)
     assert_close(host(out["h_hat"]), ref_h, 2e-2, "sweep 512x1 h")
     assert_close(host(out["g_hat"]), ref_g, 2e-2, "sweep 512x1 g")
@@ -165,19 +178,23 @@ def test_sweep_points_at_size_on_sampled_sequences(S, B, sampled):
     w = si.make_weights(wl.desc, 1)
     h = si.make_activations(wl.desc, B, S, seed=2)
     g = si.make_output_grad(wl.desc, B, S, seed=2)
-    ver = sv.Verifier(wl.desc, B * S, S, backward=True)
+    refs = {b: so.stage_backward(h[b:b + 1], g[b:b + 1], w, wl.desc) for b in sampled}
     wd = dev_weights(w, "bf16")
-    wc = ver.pack_weights(wd)
-    ver.prepare_weights(wc)
-    out = ver.verify_backward(wc, dev(h, "bf16"), dev(g, "bf16"), want_g_hat=True, want_h_hat=True)
-    got_h, got_g = out["h_hat"], out["g_hat"]
-    for b in sampled:
-        ref_h, ref_g = so.stage_backward(h[b:b + 1], g[b:b + 1], w, wl.desc)
-        eh = assert_close(host(got_h[b:b + 1]), ref_h, 2e-2, (S, B, b, "h"))
-        eg = assert_close(host(got_g[b:b + 1]), ref_g, 2e-2, (S, B, b, "g"))
-        print(f"sweep S={S} B={B} sequence {b}: h {eh[0]:.3e} / {eh[1]:.3e} / {eh[2]:.2f}   g {eg[0]:.3e} / {eg[1]:.3e} / {eg[2]:.2f}"
-              "   (whole / worst token / worst element in units of its bound)")
-    ver.close()
+    # one point also with the norms inside the products (forward and backward at the large tile's sizes), which
+    # bench.py does not time at this width
+    for fuse in ((sv.fuse_norm_pays(wl.desc), True) if (S, B) == (2048, 4) else (sv.fuse_norm_pays(wl.desc),)):
+        ver = sv.Verifier(wl.desc, B * S, S, backward=True, fuse_norm=fuse)
+        wc = ver.pack_weights(wd)
+        ver.prepare_weights(wc)
+        out = ver.verify_backward(wc, dev(h, "bf16"), dev(g, "bf16"), want_g_hat=True, want_h_hat=True)
+        got_h, got_g = out["h_hat"], out["g_hat"]
+        for b in sampled:
+            ref_h, ref_g = refs[b]
+            eh = assert_close(host(got_h[b:b + 1]), ref_h, 2e-2, (S, B, b, "h", fuse))
+            eg = assert_close(host(got_g[b:b + 1]), ref_g, 2e-2, (S, B, b, "g", fuse))
+            print(f"sweep S={S} B={B} sequence {b}{', norms inside the products' if fuse else ''}: h {eh[0]:.3e} / {eh[1]:.3e} / {eh[2]:.2f}"
+                  f"   g {eg[0]:.3e} / {eg[1]:.3e} / {eg[2]:.2f}   (whole / worst token / worst element in units of its bound)")
+        ver.close()
 
 
 def test_large_shape_sliced_wasserstein_32_submissions():

@@ -81,10 +81,10 @@ def device_routing(ver, desc, B, S, backward):
     return out
 
 
-def run_device(desc, w, h, g, backward, plain):
+def run_device(desc, w, h, g, backward, plain, fuse=False):
     import paper_2603_03592_amd as sv
     B, S = h.shape[:2]
-    ver = sv.Verifier(desc, B * S, S, backward=backward, plain_kernels=plain)
+    ver = sv.Verifier(desc, B * S, S, backward=backward, plain_kernels=plain, fuse_norm=fuse)
     wc = ver.pack_weights(wd := dev_weights(w, desc.dtype))
     if backward:
         out = ver.verify_backward(wc, dev(h, desc.dtype), dev(g, desc.dtype), want_g_hat=True, want_h_hat=True)
@@ -97,11 +97,11 @@ def run_device(desc, w, h, g, backward, plain):
     return got_h, got_g, routing
 
 
-def run_constructed(desc, B, S, seed, backward, plain=False, grad_std=1.0, mlp_gain=4.0, visible=True):
+def run_constructed(desc, B, S, seed, backward, plain=False, grad_std=1.0, mlp_gain=4.0, visible=True, fuse=False):
     """Case 1: every token, every expert choice, the stated tolerance, no exclusions."""
     w, h = si.make_moe_case_with_routing_features(desc, B, S, seed, mlp_gain=mlp_gain)
     g = si.make_output_grad(desc, B, S, seed, std=grad_std) if backward else None
-    got_h, got_g, routing = run_device(desc, w, h, g, backward, plain)
+    got_h, got_g, routing = run_device(desc, w, h, g, backward, plain, fuse)
     want_h, want_g, routes = oracle_run(h, g, w, desc)
     D, tol = desc.d_model, TOL[desc.dtype]
     for l in range(desc.n_blocks):
@@ -241,6 +241,13 @@ BF16_IDS = ["small_tiles", "big_tiles", "plain_shapes"]
 def test_bf16_moe_stage_matches_oracle_on_every_token(desc, B, S, backward):
     """Both tile paths, forward and forward + backward: chosen experts exact, every token of h and g within 2e-2."""
     run_constructed(desc, B, S, seed=12, backward=backward, grad_std=1e-3)
+
+
+@pytest.mark.parametrize("desc,B,S", BF16_CASES[:2], ids=BF16_IDS[:2])
+def test_bf16_moe_stage_with_the_first_norm_inside_the_products(desc, B, S):
+    """SV_FLAG_FUSE_NORM on a mixture-of-experts stage: the norm before attention runs inside the q | k | v product, the one
+    before the mixture (which also feeds the router) stays a pass of its own.  Same bar as without the flag."""
+    run_constructed(desc, B, S, seed=12, backward=True, grad_std=1e-3, fuse=True)
 
 
 @pytest.mark.parametrize("desc,B,S", [(BF16_SMALL, 16, 25), (BF16_TOP1, 80, 64), (dataclasses.replace(F32, dtype="bf16"), 8, 16)], ids=BF16_IDS)

@@ -20,7 +20,7 @@ from gpu_util import assert_close, dev, dev_weights, host, rel_l2
 TOL = {"f32": 1e-4, "bf16": 2e-2}
 
 
-def run_stage(desc, B, S, seed, backward, plain=False, weight_scale=1.0, grad_std=1e-3):
+def run_stage(desc, B, S, seed, backward, plain=False, weight_scale=1.0, grad_std=1e-3, fuse=False, prepare=False):
     import paper_2603_03592_amd as sv
     w = si.make_weights(desc, seed)
     if weight_scale != 1.0:
@@ -30,9 +30,11 @@ def run_stage(desc, B, S, seed, backward, plain=False, weight_scale=1.0, grad_st
                     b[k] = si.to_stage_dtype(b[k] * np.float32(weight_scale), desc.dtype)
     h = si.make_activations(desc, B, S, seed)
     g = si.make_output_grad(desc, B, S, seed, std=grad_std)
-    ver = sv.Verifier(desc, B * S, S, backward=backward, plain_kernels=plain)
+    ver = sv.Verifier(desc, B * S, S, backward=backward, plain_kernels=plain, fuse_norm=fuse)
     wd = dev_weights(w, desc.dtype)
     wc = ver.pack_weights(wd)
+    if prepare:
+        ver.prepare_weights(wc)
     if backward:
         out = ver.verify_backward(wc, dev(h, desc.dtype), dev(g, desc.dtype), want_g_hat=True, want_h_hat=True)
         want_h, want_g = so.stage_backward(h, g, w, desc)
@@ -76,6 +78,23 @@ def test_fp32_stage_matches_oracle(desc, B, S, backward):
 @pytest.mark.parametrize("plain", [False, True], ids=["mfma", "plain"])
 def test_bf16_stage_matches_oracle(desc, B, S, backward, plain):
     (gh, gg), (wh, wg), h = run_stage(desc, B, S, seed=2, backward=backward, plain=plain, weight_scale=2.0)
+    assert_close(gh, wh, TOL["bf16"], "h")
+    if backward:
+        assert_close(gg, wg, TOL["bf16"], "g")
+
+
+@pytest.mark.parametrize("desc,B,S", [(MFMA_BF16, 3, 80), (MFMA_HD128, 2, 200), (MFMA_BF16, 1, 333), (PAD_HD32, 2, 170),
+                                      (si.StageDesc(1, 512, 16, 8, 3072), 2, 250), (si.StageDesc(1, 256, 4, 2, 3072), 3, 700),
+                                      (dataclasses.replace(MFMA_BF16, mlp="gelu"), 2, 136), (MFMA_GELU, 2, 136)],
+                         ids=["mfma_swiglu", "hd128_gqa", "hd64_long", "hd32_padded", "split_k", "big_tile_mlp", "rms_gelu", "layernorm_unfused"])
+@pytest.mark.parametrize("backward", [False, True], ids=["fwd", "bwd"])
+@pytest.mark.parametrize("prepare", [False, True], ids=["per_call", "prepared"])
+def test_bf16_stage_with_the_norms_inside_the_products(desc, B, S, backward, prepare):
+    """SV_FLAG_FUSE_NORM at sizes the oracle finishes in seconds: the row factors are applied by the small-tile and
+    split-k epilogues (and by the large tile where the MLP is wide enough), they come from one read of the stream, and
+    the gain-folded weights are made per call or once.  A LayerNorm stage ignores the flag.  (The sums of squares from
+    the large tile's residual epilogue and the fused q | k | v launch need more rows: the full-size tests run them.)"""
+    (gh, gg), (wh, wg), h = run_stage(desc, B, S, seed=12, backward=backward, weight_scale=2.0, fuse=True, prepare=prepare)
     assert_close(gh, wh, TOL["bf16"], "h")
     if backward:
         assert_close(gg, wg, TOL["bf16"], "g")
