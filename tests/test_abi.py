@@ -62,6 +62,30 @@ def test_malformed_and_unsupported_descriptors_are_rejected():
     assert st == 1 and "flag" in msg
 
 
+def test_fused_norm_flag_sizes_the_gain_folded_weight_copies():
+    """SV_FLAG_FUSE_NORM: the context holds a copy of wq, wk, wv and of the dense MLP's first weights per block plus the
+    per-row scalars; stages the flag does not apply to (fp32, LayerNorm, plain kernels) are sized as without it, and
+    the rule that says where it paid when measured covers exactly the dense bf16 RMSNorm stages of width <= 2048."""
+    wl = si.LARGE
+    d, T = wl.desc, wl.batch * wl.seq
+    plain = sv.sv_workspace_bytes(d, T, wl.seq, 0)
+    fused = sv.sv_workspace_bytes(d, T, wl.seq, 8)
+    hd = d.d_model // d.n_heads
+    folded = d.n_blocks * 2 * d.d_model * ((d.n_heads + 2 * d.n_kv_heads) * hd + 2 * d.ffn_hidden)      # bf16 bytes
+    scalars = 4 * T * (1 + d.d_model // 128)
+    assert folded + scalars <= fused - plain <= folded + scalars + 64 * 1024
+    assert sv.sv_check_desc(d, flags=8)[0] == 0 and sv.sv_check_desc(d, flags=9)[0] == 0
+    for other in (si.TINY.desc, dataclasses.replace(d, dtype="f32"), dataclasses.replace(d, norm="ln")):
+        assert sv.sv_workspace_bytes(other, 128, 64, 8) == sv.sv_workspace_bytes(other, 128, 64, 0)
+    assert sv.sv_workspace_bytes(d, T, wl.seq, 8 | 2) == sv.sv_workspace_bytes(d, T, wl.seq, 2)
+    m = si.MOE_TOP6.desc                                   # a mixture keeps its second norm: only wq, wk, wv are copied
+    extra = sv.sv_workspace_bytes(m, 8192, 1024, 8) - sv.sv_workspace_bytes(m, 8192, 1024, 0)
+    qkv = m.n_blocks * 2 * m.d_model * 3 * m.d_model
+    assert qkv <= extra <= qkv + 4 * 8192 * (1 + m.d_model // 128) + 64 * 1024
+    assert [sv.fuse_norm_pays(w.desc) for w in (si.TINY, si.SMALL, si.MEDIUM, si.LARGE, si.MOE_TOP1, si.sweep_point(512, 1))] == \
+        [False, True, True, False, False, False]
+
+
 def test_mixture_of_experts_descriptors():
     d = si.MOE_TOP6.desc
     assert sv.sv_check_desc(d)[0] == 0
