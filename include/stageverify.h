@@ -417,6 +417,10 @@ typedef struct {
 } sv_profile;
 sv_status sv_profile_enable(sv_ctx *ctx, int32_t on);
 sv_status sv_profile_read(sv_ctx *ctx, sv_profile *out);
+/* Bracket only the operation classes whose bit (1 << SV_OP_*) is set in op_mask; 0 = all of them again (the
+ * default).  Events around every launch cost a check of many short launches a few per cent; a caller that times
+ * whole checks and wants one kernel's duration from the same run selects that class alone.              */
+sv_status sv_profile_select(sv_ctx *ctx, uint64_t op_mask);
 
 /* Tuning and test aid: one bf16 product C[M,N] = A[M,K] * op(B) on the MFMA GEMM kernels that
  * the block recompute uses (fp32 accumulation, bf16 result).  b_is_kn = 0: B stored [N,K]

@@ -92,6 +92,8 @@ def _load():
     L.sv_verify_forward.argtypes = [vp, C.POINTER(BlockWeightsC), vp, i32, i32, vp, u32, C.POINTER(f32), i32, vp, vp, vp, vp]
     L.sv_verify_backward.restype = C.c_int
     L.sv_verify_backward.argtypes = [vp, C.POINTER(BlockWeightsC), vp, vp, i32, i32, vp, u32, C.POINTER(f32), i32, vp, vp, vp, vp, vp]
+    L.sv_profile_select.restype = C.c_int
+    L.sv_profile_select.argtypes = [vp, C.c_uint64]
     L.sv_score_and_flag.restype = C.c_int
     L.sv_score_and_flag.argtypes = [vp, vp, i64, i32, vp, i64, i32, i32, i64, i32, u32, C.POINTER(f32), i32, vp, vp, vp]
     L.sv_score_and_flag_noalloc.restype = C.c_int
@@ -404,6 +406,11 @@ class Verifier:
 
     def profile_enable(self, on: bool = True):
         self._check(lib.sv_profile_enable(self._ctx, int(on)))
+
+    def profile_select(self, ops=None):
+        """Bracket only these operation classes (names of OP_NAMES) with events; None: all of them."""
+        mask = 0 if ops is None else sum(1 << OP_NAMES.index(o) for o in ops)
+        self._check(lib.sv_profile_select(self._ctx, mask))
 
     def profile_read(self) -> Dict[str, Dict[str, float]]:
         p = ProfileC()

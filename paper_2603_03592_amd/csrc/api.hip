@@ -95,6 +95,7 @@ struct sv_ctx {
   char err[256];
   // optional per-operation event timing
   bool prof_on = false;
+  uint64_t prof_mask = ~0ull;   // operation classes that are bracketed while prof_on (sv_profile_select)
   struct ProfRec { int op; hipEvent_t a, b; };
   std::vector<ProfRec> prof_recs;
   std::vector<hipEvent_t> prof_pool;
@@ -306,13 +307,14 @@ void init_ctx_fields(sv_ctx* c, const sv_stage_desc* desc, int64_t max_tokens, i
 #define SV_OP(c, op, flop_, st, call)                                          \
   do {                                                                         \
     hipEvent_t ea_ = nullptr, eb_ = nullptr;                                   \
-    if ((c)->prof_on) {                                                        \
+    const bool prof_ = (c)->prof_on && (((c)->prof_mask >> (op)) & 1);         \
+    if (prof_) {                                                               \
       ea_ = take_event(c); eb_ = take_event(c);                                \
       if (!ea_ || !eb_) { set_err(c, "hipEventCreate failed"); return SV_EHIP; } \
       SV_HIP(c, hipEventRecord(ea_, st));                                      \
     }                                                                          \
     SV_HIP(c, call);                                                           \
-    if ((c)->prof_on) {                                                        \
+    if (prof_) {                                                               \
       SV_HIP(c, hipEventRecord(eb_, st));                                      \
       (c)->prof_recs.push_back(sv_ctx::ProfRec{op, ea_, eb_});                 \
       (c)->prof_acc.flop[op] += (double)(flop_);                               \
@@ -795,6 +797,12 @@ sv_status sv_profile_enable(sv_ctx* c, int32_t on) {
     memset(&c->prof_acc, 0, sizeof(c->prof_acc));
   }
   c->prof_on = on != 0;
+  return SV_OK;
+}
+
+sv_status sv_profile_select(sv_ctx* c, uint64_t op_mask) {
+  if (!c) return SV_EINVAL;
+  c->prof_mask = op_mask ? op_mask : ~0ull;
   return SV_OK;
 }
 
