@@ -13,6 +13,8 @@ submissions from the oracle's output for those:
            "Threat Model" paragraph), forward + backward
   Loop   : one stage call of the verifier loop (16 workers x [8192, 4096]): statistics + sum, EMA, projections
 """
+import dataclasses
+
 import numpy as np
 import pytest
 
@@ -96,6 +98,35 @@ def test_medium_config_forward_backward():
         claim = si.make_claim("honest", ref_h, "bf16", 0)
         res = ver.read_results(ver.verify_forward(wc, hd, dev(claim, "bf16"), tau={"rel_l2": wl.tau})["result"])[0]
         _flag_check(res, claim, ref_h, wl.tau, False, "h honest")
+    ver.close()
+
+
+def test_norms_inside_the_products_with_a_ragged_row_tail_on_the_large_tile():
+    """5 x 1257 = 6285 tokens against one block of the medium stage's width: every product runs on the 256 x 256 kernel
+    (200 row-by-column tiles and more) and the last of the 25 row tiles has 141 rows, so the row factors are fetched and
+    the rows' sums of squares are stored by the epilogue's row-checked form; two blocks, so that the second block's first
+    norm takes its sums from the first block's down-projection.  Forward and backward."""
+    import paper_2603_03592_amd as sv
+    desc = dataclasses.replace(si.MEDIUM.desc, n_blocks=2)
+    B, S = 5, 1257
+    w = si.make_weights(desc, 4)
+    h = si.make_activations(desc, B, S, seed=4)
+    g = si.make_output_grad(desc, B, S, seed=4)
+    ref_h, ref_g = so.stage_backward(h, g, w, desc)
+    ver = sv.Verifier(desc, B * S, S, backward=True, fuse_norm=True)
+    wc = ver.pack_weights(wd := dev_weights(w, "bf16"))
+    ver.prepare_weights(wc)
+    out = ver.verify_backward(wc, dev(h, "bf16"), dev(g, "bf16"), want_g_hat=True, want_h_hat=True)
+    eh = assert_close(host(out["h_hat"]), ref_h, 2e-2, "ragged fused h")
+    eg = assert_close(host(out["g_hat"]), ref_g, 2e-2, "ragged fused g")
+    print(f"ragged rows, norms inside the products: h {eh[0]:.3e} / {eh[1]:.3e} / {eh[2]:.2f}   g {eg[0]:.3e} / {eg[1]:.3e} / {eg[2]:.2f}")
+    prof_ops = None
+    ver.profile_enable(True)
+    ver.verify_forward(wc, dev(h, "bf16"))
+    prof_ops = ver.profile_read()
+    ver.profile_enable(False)
+    # 2 blocks x 2 norms = 4 row-factor kernels and nothing else in the norm class: no stand-alone norm pass ran
+    assert prof_ops["norm"]["launches"] == 4, prof_ops["norm"]
     ver.close()
 
 
