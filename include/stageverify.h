@@ -408,7 +408,9 @@ enum {
   SV_OP_NORM = 0, SV_OP_GEMM_QKV, SV_OP_ROPE, SV_OP_ATTN, SV_OP_GEMM_O, SV_OP_GEMM_GATEUP, SV_OP_GEMM_DOWN,
   SV_OP_SCORE, SV_OP_BWD_GEMM_DA, SV_OP_BWD_GEMM_DN2, SV_OP_BWD_NORM, SV_OP_BWD_GEMM_DO, SV_OP_BWD_ATTN,
   SV_OP_BWD_ROPE, SV_OP_BWD_GEMM_DN1, SV_OP_BWD_WTRANSPOSE, SV_OP_SW_PROJECT, SV_OP_SW_SORT, SV_OP_MOE_ROUTE,
-  SV_OP_MOE_PERMUTE, SV_OP_BWD_MOE, SV_OP_COUNT
+  SV_OP_MOE_PERMUTE, SV_OP_BWD_MOE,
+  SV_OP_NORM_PIECES,   /* SV_FLAG_FUSE_NORM: the rows' 1 / rms (from the stream or from the partial sums) and gain folding */
+  SV_OP_COUNT
 };
 typedef struct {
   double  ms[SV_OP_COUNT];

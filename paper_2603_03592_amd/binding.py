@@ -45,7 +45,7 @@ class BlockWeightsC(C.Structure):
 
 OP_NAMES = ("norm", "gemm_qkv", "rope", "attn", "gemm_o", "gemm_gateup", "gemm_down", "score", "bwd_gemm_da",
             "bwd_gemm_dn2", "bwd_norm", "bwd_gemm_do", "bwd_attn", "bwd_rope", "bwd_gemm_dn1", "bwd_wtranspose",
-            "sw_project", "sw_sort", "moe_route", "moe_permute", "bwd_moe")
+            "sw_project", "sw_sort", "moe_route", "moe_permute", "bwd_moe", "norm_pieces")
 
 
 class PolicyCfgC(C.Structure):

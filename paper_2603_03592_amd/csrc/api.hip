@@ -403,11 +403,11 @@ GemmArgs nt(int M, int N, int K, const void* A, int64_t lda, const void* W, void
 sv_status fold_block_weights(sv_ctx* c, const sv_block_weights& w, const sv_ctx::WF& f, hipStream_t st) {
   const sv_stage_desc& d = c->d;
   const int D = d.d_model, F = d.ffn_hidden;
-  SV_OP(c, SV_OP_NORM, 0, st, fold_gain(w.wq, w.norm1_g, f.wq, c->Dq, D, st));
-  SV_OP(c, SV_OP_NORM, 0, st, fold_gain(w.wk, w.norm1_g, f.wk, c->Dkv, D, st));
-  SV_OP(c, SV_OP_NORM, 0, st, fold_gain(w.wv, w.norm1_g, f.wv, c->Dkv, D, st));
-  if (f.wu) SV_OP(c, SV_OP_NORM, 0, st, fold_gain(w.w_up, w.norm2_g, f.wu, F, D, st));
-  if (f.wg) SV_OP(c, SV_OP_NORM, 0, st, fold_gain(w.w_gate, w.norm2_g, f.wg, F, D, st));
+  SV_OP(c, SV_OP_NORM_PIECES, 0, st, fold_gain(w.wq, w.norm1_g, f.wq, c->Dq, D, st));
+  SV_OP(c, SV_OP_NORM_PIECES, 0, st, fold_gain(w.wk, w.norm1_g, f.wk, c->Dkv, D, st));
+  SV_OP(c, SV_OP_NORM_PIECES, 0, st, fold_gain(w.wv, w.norm1_g, f.wv, c->Dkv, D, st));
+  if (f.wu) SV_OP(c, SV_OP_NORM_PIECES, 0, st, fold_gain(w.w_up, w.norm2_g, f.wu, F, D, st));
+  if (f.wg) SV_OP(c, SV_OP_NORM_PIECES, 0, st, fold_gain(w.w_gate, w.norm2_g, f.wg, F, D, st));
   return SV_OK;
 }
 
@@ -435,8 +435,8 @@ sv_status block_forward(sv_ctx* c, int l, const sv_block_weights& w, const void*
     }
   }
   auto row_rstd = [&](const void* stream) -> sv_status {
-    if (c->rowsq_of == stream) SV_OP(c, SV_OP_NORM, 0, st, rms_rstd_from_partials(c->rowsq, c->rowsq_planes, T, c->rstd, T, D, d.norm_eps, st));
-    else SV_OP(c, SV_OP_NORM, 0, st, rms_rstd(stream, c->rstd, T, D, d.norm_eps, st));
+    if (c->rowsq_of == stream) SV_OP(c, SV_OP_NORM_PIECES, 0, st, rms_rstd_from_partials(c->rowsq, c->rowsq_planes, T, c->rstd, T, D, d.norm_eps, st));
+    else SV_OP(c, SV_OP_NORM_PIECES, 0, st, rms_rstd(stream, c->rstd, T, D, d.norm_eps, st));
     return SV_OK;
   };
   // a product that writes a residual stream leaves the sums of squares of its rows when the kernel it runs on can

@@ -125,8 +125,8 @@ def test_norms_inside_the_products_with_a_ragged_row_tail_on_the_large_tile():
     ver.verify_forward(wc, dev(h, "bf16"))
     prof_ops = ver.profile_read()
     ver.profile_enable(False)
-    # 2 blocks x 2 norms = 4 row-factor kernels and nothing else in the norm class: no stand-alone norm pass ran
-    assert prof_ops["norm"]["launches"] == 4, prof_ops["norm"]
+    # 2 blocks x 2 norms = 4 row-factor kernels, and no stand-alone norm pass ran
+    assert prof_ops["norm_pieces"]["launches"] == 4 and prof_ops["norm"]["launches"] == 0, (prof_ops["norm_pieces"], prof_ops["norm"])
     ver.close()
 
 
