@@ -34,6 +34,7 @@ __device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
 __device__ __forceinline__ int lds_off(int row, int chunk) { return row * 128 + ((chunk ^ swz(row)) << 4); }
 
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool KN, bool DUAL>
 struct Cfg {
@@ -70,12 +71,12 @@ __device__ __forceinline__ void epilogue_load4(const GemmArgs& a, int m, int n, 
   }
 }
 
-// rs multiplies the accumulators first (GemmArgs::rscale; the kinds that can follow a norm).  Returns the sum of squares of
-// the four values as stored.
-template <int EPI>
-__device__ __forceinline__ float epilogue_apply4(const GemmArgs& a, int m, int n, const float (&v_in)[4], const float (&u_in)[4], const EpiIn& in,
-                                                 float rs = 1.0f) {
-  const int64_t ic = (int64_t)m * a.ldc + n;
+// rs multiplies the accumulators first (GemmArgs::rscale; the kinds that can follow a norm).  put(w, p) stores the four bf16
+// values p into output w (0: C, 1: C2, 2: C3) at the place this call stands for; roped: the features are rotated (EPI_ROPE).
+// Returns the sum of squares of the four values as stored in C.
+template <int EPI, class Put>
+__device__ __forceinline__ float epilogue_math4(const GemmArgs& a, bool roped, const float (&v_in)[4], const float (&u_in)[4], const EpiIn& in,
+                                                float rs, Put&& put) {
   const bf16x4& r = in.r;
   const bf16x4& r2 = in.r2;
   constexpr bool kScaled = EPI == EPI_STORE || EPI == EPI_GELU || EPI == EPI_SWIGLU || EPI == EPI_ROPE;
@@ -93,13 +94,13 @@ __device__ __forceinline__ float epilogue_apply4(const GemmArgs& a, int m, int n
       for (int i = 0; i < 4; ++i) o[i] = v[i] + (float)r[i];
       break;
     case EPI_GELU: {
-      if (a.C2) { bf16x4 p; for (int i = 0; i < 4; ++i) p[i] = (bf16)v[i]; *reinterpret_cast<bf16x4*>((bf16*)a.C2 + ic) = p; }
+      if (a.C2) { bf16x4 p; for (int i = 0; i < 4; ++i) p[i] = (bf16)v[i]; put(1, p); }
 #pragma unroll
       for (int i = 0; i < 4; ++i) o[i] = gelu_f(v[i]);
     } break;
     case EPI_SWIGLU: {
-      if (a.C2) { bf16x4 p; for (int i = 0; i < 4; ++i) p[i] = (bf16)v[i]; *reinterpret_cast<bf16x4*>((bf16*)a.C2 + ic) = p; }
-      if (a.C3) { bf16x4 p; for (int i = 0; i < 4; ++i) p[i] = (bf16)u[i]; *reinterpret_cast<bf16x4*>((bf16*)a.C3 + ic) = p; }
+      if (a.C2) { bf16x4 p; for (int i = 0; i < 4; ++i) p[i] = (bf16)v[i]; put(1, p); }
+      if (a.C3) { bf16x4 p; for (int i = 0; i < 4; ++i) p[i] = (bf16)u[i]; put(2, p); }
 #pragma unroll
       for (int i = 0; i < 4; ++i) o[i] = silu_f(v[i]) * u[i];
     } break;
@@ -111,10 +112,10 @@ __device__ __forceinline__ float epilogue_apply4(const GemmArgs& a, int m, int n
         o[i] = v[i] * (float)r2[i] * silu_grad_f(gf);
         p[i] = (bf16)(v[i] * silu_f(gf));
       }
-      *reinterpret_cast<bf16x4*>((bf16*)a.C2 + ic) = p;
+      put(1, p);
     } break;
     case EPI_ROPE: {
-      if (n < a.rope_cols) {
+      if (roped) {
         const f32x4 cs = in.cs;
         o[0] = v[0] * cs[0] - v[1] * cs[1];
         o[1] = v[0] * cs[1] + v[1] * cs[0];
@@ -134,9 +135,23 @@ __device__ __forceinline__ float epilogue_apply4(const GemmArgs& a, int m, int n
   float sq = 0.0f;
 #pragma unroll
   for (int i = 0; i < 4; ++i) { p[i] = (bf16)o[i]; sq = fmaf((float)p[i], (float)p[i], sq); }
-  *reinterpret_cast<bf16x4*>((bf16*)a.C + ic) = p;
+  put(0, p);
   return sq;
 }
+
+// the same on the output element (m, n), through plain pointers
+template <int EPI>
+__device__ __forceinline__ float epilogue_apply4(const GemmArgs& a, int m, int n, const float (&v_in)[4], const float (&u_in)[4], const EpiIn& in,
+                                                 float rs = 1.0f) {
+  const int64_t ic = (int64_t)m * a.ldc + n;
+  return epilogue_math4<EPI>(a, EPI == EPI_ROPE && n < a.rope_cols, v_in, u_in, in, rs, [&](int w, bf16x4 p) {
+    *reinterpret_cast<bf16x4*>((bf16*)(w == 0 ? a.C : w == 1 ? a.C2 : a.C3) + ic) = p;
+  });
+}
+
+// How many trips ahead of its stores the direct-to-LDS kernel's epilogue reads its inputs (a trip: two rows per lane).  One trip
+// of work is shorter than a memory round trip, so one trip ahead leaves the epilogue waiting once per trip.
+template <int EPI> constexpr int kEpiAhead = EPI == EPI_ROPE ? 2 : EPI == EPI_SWIGLU_BWD ? 3 : 4;   // as far as the registers go
 
 // does this kind of epilogue take GemmArgs::rscale?
 template <int EPI> constexpr bool kEpiScaled = EPI == EPI_STORE || EPI == EPI_GELU || EPI == EPI_SWIGLU || EPI == EPI_ROPE;
@@ -581,6 +596,66 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
       for (int j = 0; j < MI; ++j)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+    // ---- what the epilogue's global accesses need, set up here because a full tile asks for its first inputs a slice early.
+    // In the read-back of the epilogue a lane serves row er of each group of 4 rows, 16-byte chunk ec4 (and 16 + ec4).
+    // One buffer descriptor per tensor, based at the tile's first row and the wave's first column; inside it a lane's
+    // byte offset is (row * ld + column) * 2, of which the lane's part never changes and the row block's part is a scalar:
+    // no 64-bit address arithmetic per access.
+    constexpr bool kHasInputs = EPI == EPI_RESID || EPI == EPI_SWIGLU_BWD || EPI == EPI_GELU_BWD || EPI == EPI_ROPE;
+    constexpr int PD = kEpiAhead<EPI>;                   // trips the epilogue's global reads run ahead of its stores
+    const int er = lane >> 4, ec4 = lane & 15;
+    const int ncol0 = n0 + wn * (DUAL ? 64 : 128);
+    auto desc = [&](const void* base, int ld) {
+      return __builtin_amdgcn_make_buffer_rsrc((void*)((const bf16*)base + (int64_t)m0 * ld + ncol0), (short)0, -1, 0x00020000);
+    };
+    const __amdgpu_buffer_rsrc_t bC = desc(a.C, a.ldc), bC2 = desc(a.C2, a.ldc), bC3 = desc(a.C3, a.ldc);
+    const __amdgpu_buffer_rsrc_t bR = desc(a.R, a.ldr), bR2 = desc(a.R2, a.ldr);
+    const int vC = ((wm * 128 + er) * a.ldc + ec4 * 4) * 2, vR = ((wm * 128 + er) * a.ldr + ec4 * 4) * 2;
+    // offsets of row block rb (rows rb .. rb + 3 of the wave's 128): per lane (vo) and scalar (so).  A ragged tile
+    // re-reads its last row for the rows past the end, which takes the row into the lane's part.
+    auto place = [&](auto check_tag, int rb, int ld, int vlane, int& vo, int& so) {
+      if (decltype(check_tag)::value) { vo = (min(wm * 128 + rb + er, M - 1 - m0) * ld + ec4 * 4) * 2; so = 0; }
+      else { vo = vlane; so = rb * ld * 2; }
+    };
+    int rope_p0 = 0, rope_v_lo = 0, rope_v_hi = 0;      // first row's position; byte offsets of the lane's feature pairs in a table row
+    if (EPI == EPI_ROPE) {
+      rope_p0 = (m0 + wm * 128) % a.rope_S;
+      rope_v_lo = (((ncol0 + ec4 * 4) % a.rope_hd) >> 1) * 8;
+      rope_v_hi = (((ncol0 + 64 + ec4 * 4) % a.rope_hd) >> 1) * 8 - rope_v_lo;
+    }
+    const __amdgpu_buffer_rsrc_t bT = __builtin_amdgcn_make_buffer_rsrc((void*)a.rope_cs, (short)0, -1, 0x00020000);
+    auto ld8 = [&](__amdgpu_buffer_rsrc_t b, int vo, int so) { return __builtin_bit_cast(bf16x4, __builtin_amdgcn_raw_buffer_load_b64(b, vo, so, 0)); };
+    // the inputs of trip `trip` (two rows of row block mi = trip / 4 per lane): residual, gate / up, RoPE table
+    auto load_inputs = [&](auto check_tag, int trip, EpiIn (&lo)[2], EpiIn (&hi)[2]) {
+      const int mi = trip >> 2, it = (trip & 3) * 2;
+#pragma unroll
+      for (int k = 0; k < 2; ++k) {
+        const int rb = mi * 32 + (it + k) * 4;
+        if (EPI == EPI_ROPE) {
+          // position of the row in its sequence without a division per row: the wave's first row is reduced once
+          // per tile, the rows of the tile follow it consecutively
+          int p = rope_p0 + rb + er;
+          if (a.rope_S >= 256) p -= p >= a.rope_S ? a.rope_S : 0; else p %= a.rope_S;
+          const int vo = p * (a.rope_hd >> 1) * 8 + rope_v_lo;      // the table entry (position p, feature pair) is 8 bytes
+          lo[k].cs = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(bT, vo, 0, 0));
+          hi[k].cs = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(bT, vo + rope_v_hi, 0, 0));
+        } else if (kHasInputs) {
+          int vo, so;
+          place(check_tag, rb, a.ldr, vR, vo, so);
+          lo[k].r = ld8(bR, vo, so);
+          hi[k].r = ld8(bR, vo + 128, so);
+          if (EPI == EPI_SWIGLU_BWD) { lo[k].r2 = ld8(bR2, vo, so); hi[k].r2 = ld8(bR2, vo + 128, so); }
+        }
+      }
+    };
+    EpiIn in_lo[PD][2], in_hi[PD][2];                    // [trip mod PD][row of the pair]
+    const bool full_tile = m0 + 256 <= M;
+    auto first_inputs = [&]() {                          // of a full tile, a slice before the epilogue
+      if (kHasInputs && full_tile) {
+#pragma unroll
+        for (int t = 0; t < PD; ++t) load_inputs(std::false_type{}, t, in_lo[t], in_hi[t]);
+      }
+    };
     // ---- slice 0 (its loads were issued during the previous tile's last slice, or above)
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
@@ -592,6 +667,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
       rs_pre0 = a.rscale[min(m0 + wm * 128 + lane, M - 1)];
       rs_pre1 = a.rscale[min(m0 + wm * 128 + 64 + lane, M - 1)];
     }
+    if (nslices == 1) first_inputs();
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       xf0[g] = *reinterpret_cast<const bf16x8*>(smem + par * STAGE + lds_off(xrow[g], lhi));
@@ -605,6 +681,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
       const int st = (par + kt) & 1;
       __builtin_amdgcn_s_waitcnt(0);   // my DMAs of slice kt have landed, my fragment reads of slice kt-1 are done
       __syncthreads();                 // ... and so have everybody's: stage st is complete, stage st^1 is free
+      SV_SB;
+      if (kt == nslices - 1) first_inputs();     // their round trip hides behind the last slice's products
       SV_SB;
       step(xf1, wf1, xf0, wf0, true, st, 0, true, st ^ 1, 0);     // MFMAs of (kt-1, k step 3)
       step(xf0, wf0, xf1, wf1, true, st, 1, true, st ^ 1, 8);
@@ -625,21 +703,15 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
     par = (par + nslices) & 1;
     __syncthreads();                                   // everybody is done reading stage sl
     char* patch = smem + sl * STAGE + wave * 16384;
-    const int er = lane >> 4, ec4 = lane & 15;         // read-back: row er of each group of 4 rows, 16-byte chunk ec4 (and 16 + ec4)
     // per wave, behind the two stages: the row factors of its 128 rows (each lane of the read-back needs those of the
     // rows it serves) and the rows' sums of squares (stored in one piece when the tile is done)
     float* rsbuf = reinterpret_cast<float*>(smem + 2 * STAGE) + wave * 256;
     float* sqbuf = rsbuf + 128;
     if (RS) { rsbuf[lane] = rs_pre0; rsbuf[64 + lane] = rs_pre1; }
-    int rope_p0 = 0, rope_i0_lo = 0, rope_i0_hi = 0;
-    if (EPI == EPI_ROPE) {
-      const int nlo = n0 + wn * 128 + ec4 * 4, nhi = nlo + 64;
-      rope_p0 = (m0 + wm * 128) % a.rope_S;
-      rope_i0_lo = (nlo % a.rope_hd) >> 1; rope_i0_hi = (nhi % a.rope_hd) >> 1;
-    }
-    // The epilogue's global reads (residual, gate / up, RoPE table) run one trip ahead of its stores: the memory
-    // counter retires in order, so a read issued AFTER a store could only be waited for together with that store's
-    // acknowledgement.  Sixteen trips per tile: row block mi = trip / 4, two rows per lane and trip.  Tiles that lie
+    // Sixteen trips per tile: row block mi = trip / 4, two rows per lane and trip.  The epilogue's global reads (residual,
+    // gate / up, RoPE table) run kEpiAhead trips ahead of its stores; the first of them were asked for when the last slice
+    // began.  (The memory counter retires in order: a read is waited for together with every store issued before it, so
+    // the reads of a trip are issued before the stores they must not wait for have piled up.)  Tiles that lie
     // inside the M rows run without any per-lane condition (CHECK = false): around divergent branches the compiler's
     // wait insertion falls back to waiting for (nearly) everything in flight, one memory round trip per store.
     auto run_epilogue = [&](auto check_tag) {
@@ -698,31 +770,14 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
           return;
         }
       }
-      auto load_inputs = [&](int trip, EpiIn (&in_lo)[2], EpiIn (&in_hi)[2]) {
-        const int mi = trip >> 2, it = (trip & 3) * 2;
+      // The lane's row and chunk numbers in the patch are made opaque once per tile, as above: the patch addresses below
+      // are the same for every tile, and kept in registers across the k loop they crowd the epilogue's inputs out.
+      int e31 = l31, eer = er, ec = ec4;
+      asm volatile("" : "+v"(e31), "+v"(eer), "+v"(ec));
+      if (kHasInputs && CHECK) {                         // a ragged tile asks for its first inputs here, a full one did so a slice ago
 #pragma unroll
-        for (int k = 0; k < 2; ++k) {
-          const int row = (it + k) * 4 + er;
-          int m = m0 + wm * 128 + mi * 32 + row;
-          if (CHECK) m = min(m, M - 1);                // rows past the end read the last row (never stored)
-          if (EPI == EPI_ROPE) {
-            // position of the row in its sequence without a division per row: the wave's first row is reduced once
-            // per tile, the rows of the tile follow it consecutively
-            int p = rope_p0 + mi * 32 + row;
-            if (a.rope_S >= 256) p -= p >= a.rope_S ? a.rope_S : 0; else p %= a.rope_S;
-            in_lo[k].cs = *reinterpret_cast<const f32x4*>(a.rope_cs + ((int64_t)p * (a.rope_hd >> 1) + rope_i0_lo) * 2);
-            in_hi[k].cs = *reinterpret_cast<const f32x4*>(a.rope_cs + ((int64_t)p * (a.rope_hd >> 1) + rope_i0_hi) * 2);
-          } else if (DUAL) {
-            epilogue_load4<EPI>(a, m, n0 + wn * 64 + ec4 * 4, in_lo[k]);
-          } else {
-            epilogue_load4<EPI>(a, m, n0 + wn * 128 + ec4 * 4, in_lo[k]);
-            epilogue_load4<EPI>(a, m, n0 + wn * 128 + 64 + ec4 * 4, in_hi[k]);
-          }
-        }
-      };
-      constexpr bool kHasInputs = EPI == EPI_RESID || EPI == EPI_SWIGLU_BWD || EPI == EPI_GELU_BWD || EPI == EPI_ROPE;
-      EpiIn in_lo[2][2], in_hi[2][2];                    // [trip parity][row of the pair]
-      if (kHasInputs) load_inputs(0, in_lo[0], in_hi[0]);
+        for (int t = 0; t < PD; ++t) load_inputs(check_tag, t, in_lo[t], in_hi[t]);
+      }
 #pragma unroll
       for (int trip = 0; trip < 16; ++trip) {
         const int mi = trip >> 2, it = (trip & 3) * 2;
@@ -735,35 +790,44 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
 #pragma unroll
               for (int i = 0; i < 4; ++i) v[i] = acc[ni][mi][q * 4 + i];
               const int chunk = ni * 8 + q * 2 + lhi;    // features 4*chunk .. +3 of the wave's 128
-              *reinterpret_cast<f32x4*>(patch + l31 * 512 + ((chunk ^ l31) << 4)) = v;
+              *reinterpret_cast<f32x4*>(patch + e31 * 512 + ((chunk ^ e31) << 4)) = v;
             }
           __builtin_amdgcn_s_waitcnt(0xc07f);            // lgkmcnt(0): the patch is complete before it is read back
           __builtin_amdgcn_wave_barrier();
         }
-        if (kHasInputs && trip + 1 < 16) load_inputs(trip + 1, in_lo[(trip + 1) & 1], in_hi[(trip + 1) & 1]);
 #pragma unroll
         for (int k = 0; k < 2; ++k) {
-          const int row = (it + k) * 4 + er;
-          const int m = m0 + wm * 128 + mi * 32 + row;
-          const f32x4 a_lo = *reinterpret_cast<const f32x4*>(patch + row * 512 + ((ec4 ^ row) << 4));
-          const f32x4 a_hi = *reinterpret_cast<const f32x4*>(patch + row * 512 + (((16 + ec4) ^ row) << 4));
+          const int row = (it + k) * 4 + eer, rb = mi * 32 + (it + k) * 4;
+          const f32x4 a_lo = *reinterpret_cast<const f32x4*>(patch + row * 512 + ((ec ^ row) << 4));
+          const f32x4 a_hi = *reinterpret_cast<const f32x4*>(patch + row * 512 + (((16 + ec) ^ row) << 4));
           float lo[4], hi[4];
 #pragma unroll
           for (int i = 0; i < 4; ++i) { lo[i] = a_lo[i]; hi[i] = a_hi[i]; }
-          if (CHECK && m >= M) continue;
+          int vo, so;
+          place(check_tag, rb, a.ldc, vC, vo, so);
+          const bool ok = !CHECK || wm * 128 + rb + er < M - m0;
+          auto put_lo = [&](int w, bf16x4 pk) {
+            if (ok) __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, pk), w == 0 ? bC : w == 1 ? bC2 : bC3, vo, so, 0);
+          };
+          auto put_hi = [&](int w, bf16x4 pk) {
+            if (ok) __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, pk), w == 0 ? bC : w == 1 ? bC2 : bC3, vo + 128, so, 0);
+          };
           const float rs = RS ? rsbuf[mi * 32 + row] : 1.0f;
-          if (DUAL) epilogue_apply4<EPI>(a, m, n0 + wn * 64 + ec4 * 4, lo, hi, in_lo[trip & 1][k], rs);   // patch columns 0..63: gate, 64..127: up
+          const EpiIn& i_lo = in_lo[trip % PD][k];
+          const EpiIn& i_hi = in_hi[trip % PD][k];
+          if (DUAL) epilogue_math4<EPI>(a, false, lo, hi, i_lo, rs, put_lo);   // patch columns 0..63: gate, 64..127: up
           else {
-            float sq = epilogue_apply4<EPI>(a, m, n0 + wn * 128 + ec4 * 4, lo, hi, in_lo[trip & 1][k], rs);
-            sq += epilogue_apply4<EPI>(a, m, n0 + wn * 128 + 64 + ec4 * 4, hi, lo, in_hi[trip & 1][k], rs);
+            float sq = epilogue_math4<EPI>(a, EPI == EPI_ROPE && ncol0 + ec4 * 4 < a.rope_cols, lo, hi, i_lo, rs, put_lo);
+            sq += epilogue_math4<EPI>(a, EPI == EPI_ROPE && ncol0 + 64 + ec4 * 4 < a.rope_cols, hi, lo, i_hi, rs, put_hi);
             if (SQ) {
               // the 16 lanes of a row hold its 128 stored values: rotate-and-add within the row of 16 lanes leaves the
               // sum in all of them, and all of them write it (one LDS address per row, no per-lane condition)
               sq += dpp_row_ror<8>(sq); sq += dpp_row_ror<4>(sq); sq += dpp_row_ror<2>(sq); sq += dpp_row_ror<1>(sq);
-              sqbuf[mi * 32 + row] = sq;
+              if (ok) sqbuf[mi * 32 + row] = sq;
             }
           }
         }
+        if (kHasInputs && trip + PD < 16) load_inputs(check_tag, trip + PD, in_lo[trip % PD], in_hi[trip % PD]);
       }
       if (SQ) {                                          // 128 consecutive floats of plane (n0 / 128 + wn): two full-line stores
         __builtin_amdgcn_s_waitcnt(0xc07f);
