@@ -169,8 +169,8 @@ size_t carve(sv_ctx* c, char* base) {
   c->score_scratch = (ScorePartial*)a.take(kScoreScratchElems * sizeof(ScorePartial));
   c->split_ws = nullptr; c->split_ws_floats = 0;
   if (d.dtype == SV_BF16 && !(c->flags & SV_FLAG_PLAIN_KERNELS)) {
-    // up to 8 partial products of the widest product a split can serve (below 160 tiles of 128 x 128), and no more
-    // than this context's token bound allows
+    // up to 8 partial products of the widest product a split can serve (below 160 tiles of 128 x 128, or below 192 tiles
+    // of 256 x 256 with as many runs as this holds), and no more than this context's token bound allows
     const size_t widest = std::max(std::max(D, (size_t)c->Dq), std::max(Fd, (size_t)d.ffn_hidden));
     c->split_ws_floats = std::min((size_t)8 * 160 * 128 * 128, (size_t)8 * T * widest);
     c->split_ws = (float*)a.take(c->split_ws_floats * sizeof(float));
@@ -455,7 +455,8 @@ sv_status block_forward(sv_ctx* c, int l, const sv_block_weights& w, const void*
     f.nbcol = 3; f.Bcol[0] = wf.wq; f.Bcol[1] = wf.wk; f.Bcol[2] = wf.wv; f.ncol[0] = c->Dq; f.ncol[1] = c->Dkv; f.ncol[2] = c->Dkv;
     f.rope_cs = c->rope_cs; f.rope_S = S; f.rope_hd = c->hd; f.rope_cols = c->Dq + c->Dkv;
     f.rscale = c->rstd;
-    if (mfma_gemm_supported(f)) {                      // the one-launch q | k | v product: the large tile only
+    f.split_ws = c->split_ws; f.split_ws_floats = (int64_t)c->split_ws_floats;   // few tokens: runs of k slices per tile
+    if (mfma_gemm_supported(f)) {                      // the one-launch q | k | v product: the large tile (whole, or over runs of k slices)
       sv_status s = row_rstd(x);
       if (s != SV_OK) return s;
       SV_OP(c, SV_OP_GEMM_QKV, 2.0 * Td * c->Dqkv * D, st, mfma_gemm(f, st));
@@ -468,6 +469,7 @@ sv_status block_forward(sv_ctx* c, int l, const sv_block_weights& w, const void*
     GemmArgs f = nt(T, c->Dqkv, D, c->n, D, w.wq, qkv, c->Dqkv, d.rope ? EPI_ROPE : EPI_STORE);
     f.nbcol = 3; f.Bcol[0] = w.wq; f.Bcol[1] = w.wk; f.Bcol[2] = w.wv; f.ncol[0] = c->Dq; f.ncol[1] = c->Dkv; f.ncol[2] = c->Dkv;
     f.rope_cs = c->rope_cs; f.rope_S = S; f.rope_hd = c->hd; f.rope_cols = c->Dq + c->Dkv;
+    f.split_ws = c->split_ws; f.split_ws_floats = (int64_t)c->split_ws_floats;
     if (dt == SV_BF16 && !(c->flags & SV_FLAG_PLAIN_KERNELS) && mfma_gemm_supported(f)) {
       SV_OP(c, SV_OP_GEMM_QKV, 2.0 * Td * c->Dqkv * D, st, mfma_gemm(f, st));
     } else {

@@ -452,8 +452,12 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmArgs a, int nspl
 //
 // NF: the forms that stand at the two ends of an RMSNorm run inside the products (their own instantiations, for the same
 // reason): the kinds that can follow a norm multiply every row by GemmArgs::rscale, EPI_RESID also writes GemmArgs::rowsq.
-template <int EPI, bool GROUPED, bool NF = false>
-__global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tiles_m, int tiles_n) {
+// SPLIT: a tile's k slices are dealt to nsplit workgroups in contiguous runs (virtual block = (run, tile), the tiles of one run
+// next to each other so that an XCD's workgroups share operand panels); each leaves its fp32 partial product in
+// a.split_ws[run][M][N] and splitk_reduce_kernel adds the runs in a fixed order and applies the epilogue.
+template <int EPI, bool GROUPED, bool NF = false, bool SPLIT = false>
+__global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tiles_m, int tiles_n, int nsplit) {
+  static_assert(!SPLIT || (EPI == EPI_STORE && !GROUPED && !NF), "a split run stores bare partial products");
   constexpr bool DUAL = EPI == EPI_SWIGLU;
   constexpr bool RS = NF && kEpiScaled<EPI>, SQ = NF && EPI == EPI_RESID;
   constexpr int BM = 256, BN = 256, STAGE = (BM + BN) * 128, MI = 4, NI = 4;
@@ -466,12 +470,14 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
   // Persistent workgroups: workgroup b works on the virtual block ids b, b + gridDim.x, ...; a virtual id
   // maps to a tile so that ids congruent mod 8 (one XCD) walk a contiguous run of tiles in groups of
   // kGroupM row tiles.  gridDim.x is a multiple of 8, so a workgroup stays on its XCD's run.
-  const int nblk = tiles_m * tiles_n;
-  const int per_xcd = (nblk + 7) >> 3;
-  auto tile_of = [&](int vb, int& m0, int& n0) -> bool {
+  const int nblk = tiles_m * tiles_n, nvb = SPLIT ? nblk * nsplit : nblk;
+  const int per_xcd = (nvb + 7) >> 3;
+  auto tile_of = [&](int vb, int& m0, int& n0, int& run) -> bool {
     if (vb >= per_xcd * 8) return false;
-    const int pid = (vb & 7) * per_xcd + (vb >> 3);
-    if (pid >= nblk) return false;
+    int pid = (vb & 7) * per_xcd + (vb >> 3);
+    if (pid >= nvb) return false;
+    run = 0;
+    if (SPLIT) { run = pid / nblk; pid -= run * nblk; }
     const int in_group = kGroupM * tiles_n;
     const int first_m = (pid / in_group) * kGroupM;
     const int gsz = min(tiles_m - first_m, kGroupM);
@@ -485,10 +491,21 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
 
   // ---- DMA side: one continuous stream of slices across this workgroup's tiles, always one slice
   // ahead of the multiply.  State: virtual block d_vb (tile d_m0, d_n0), segment dseg, offset dk.
-  int d_vb = blockIdx.x, d_m0 = 0, d_n0 = 0, dseg = 0, dk = 0, d_K = 0;   // d_K: length of segment dseg, kept in a register
+  int d_vb = blockIdx.x, d_m0 = 0, d_n0 = 0, d_run = 0, d_left = 0, dseg = 0, dk = 0, d_K = 0;   // d_K: length of segment dseg, kept in a register
                                                                            // (a per-slice kernel-argument load would share
                                                                            // its wait counter with the LDS reads)
-  bool d_valid = tile_of(d_vb, d_m0, d_n0);
+  bool d_valid = tile_of(d_vb, d_m0, d_n0, d_run);
+  int nslices = 0;
+  for (int s = 0; s < a.nseg; ++s) nslices += a.seg[s].K / BK;
+  // SPLIT: run r of a tile takes the slices [r * nslices / nsplit, (r + 1) * nslices / nsplit) of its segments laid end to end
+  auto start_run = [&]() {                                    // the stream's position at the first slice of run d_run
+    const int ks = d_run * nslices / nsplit;
+    d_left = (d_run + 1) * nslices / nsplit - ks;
+    dseg = 0;
+    int k = ks * BK;
+    while (k >= a.seg[dseg].K) { k -= a.seg[dseg].K; ++dseg; }
+    dk = k;
+  };
   const char *gA, *gB, *gB2;
   __amdgpu_buffer_rsrc_t rA, rB, rB2;     // buffer descriptors of the panels the stream reads: base = first row, no bound
   unsigned voffA[8], voffB[8];
@@ -527,17 +544,26 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
   };
   auto advance = [&]() {                                      // to the next slice of the stream
     dk += BK;
+    if (SPLIT) {
+      if (--d_left == 0) {                                    // the run is through: on to the next virtual block
+        d_vb += gridDim.x;
+        d_valid = tile_of(d_vb, d_m0, d_n0, d_run);
+        if (d_valid) { start_run(); set_segment(); }
+        else dk -= BK;                                        // a finished stream re-reads its last slice
+        return;
+      }
+      if (dk < d_K) return;
+      dk = 0; ++dseg; set_segment();
+      return;
+    }
     if (dk < d_K) return;
     dk = 0;
     if (dseg + 1 < a.nseg) { ++dseg; set_segment(); return; }
     dseg = 0;
     d_vb += gridDim.x;
-    d_valid = tile_of(d_vb, d_m0, d_n0);
+    d_valid = tile_of(d_vb, d_m0, d_n0, d_run);
     if (d_valid) set_segment();
   };
-
-  int nslices = 0;
-  for (int s = 0; s < a.nseg; ++s) nslices += a.seg[s].K / BK;
 
   int xrow[MI], wrow[NI];
 #pragma unroll
@@ -582,14 +608,16 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
 
   if (!d_valid) return;
   bf16x8 xf0[MI], wf0[NI], xf1[MI], wf1[NI];
+  if (SPLIT) start_run();
   set_segment();
 #pragma unroll
   for (int j = 0; j < 16; ++j) dma(0, j);                     // slice 0 of the first tile
   advance();
   int par = 0;                                                // LDS stage of the current tile's slice 0
 
-  int m0, n0;
-  for (int vb = blockIdx.x; tile_of(vb, m0, n0); vb += gridDim.x) {
+  int m0, n0, run;
+  for (int vb = blockIdx.x; tile_of(vb, m0, n0, run); vb += gridDim.x) {
+    const int nsl = SPLIT ? (run + 1) * nslices / nsplit - run * nslices / nsplit : nslices;   // slices of this virtual block
 #pragma unroll
     for (int i = 0; i < NI; ++i)
 #pragma unroll
@@ -611,6 +639,10 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
     const __amdgpu_buffer_rsrc_t bC = desc(a.C, a.ldc), bC2 = desc(a.C2, a.ldc), bC3 = desc(a.C3, a.ldc);
     const __amdgpu_buffer_rsrc_t bR = desc(a.R, a.ldr), bR2 = desc(a.R2, a.ldr);
     const int vC = ((wm * 128 + er) * a.ldc + ec4 * 4) * 2, vR = ((wm * 128 + er) * a.ldr + ec4 * 4) * 2;
+    // SPLIT: the run's partial product, fp32 [M][N]
+    const __amdgpu_buffer_rsrc_t bW = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(a.split_ws + ((int64_t)run * M + m0) * a.N + ncol0), (short)0, -1, 0x00020000);
+    const int vW = ((wm * 128 + er) * a.N + ec4 * 4) * 4;
     // offsets of row block rb (rows rb .. rb + 3 of the wave's 128): per lane (vo) and scalar (so).  A ragged tile
     // re-reads its last row for the rows past the end, which takes the row into the lane's part.
     auto place = [&](auto check_tag, int rb, int ld, int vlane, int& vo, int& so) {
@@ -667,7 +699,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
       rs_pre0 = a.rscale[min(m0 + wm * 128 + lane, M - 1)];
       rs_pre1 = a.rscale[min(m0 + wm * 128 + 64 + lane, M - 1)];
     }
-    if (nslices == 1) first_inputs();
+    if (nsl == 1) first_inputs();
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       xf0[g] = *reinterpret_cast<const bf16x8*>(smem + par * STAGE + lds_off(xrow[g], lhi));
@@ -677,12 +709,12 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
     step(xf1, wf1, xf0, wf0, true, par, 2, true, par ^ 1, 8);
     if (d_valid) advance();
     step(xf0, wf0, xf1, wf1, true, par, 3, false, 0, 0);
-    for (int kt = 1; kt < nslices; ++kt) {
+    for (int kt = 1; kt < nsl; ++kt) {
       const int st = (par + kt) & 1;
       __builtin_amdgcn_s_waitcnt(0);   // my DMAs of slice kt have landed, my fragment reads of slice kt-1 are done
       __syncthreads();                 // ... and so have everybody's: stage st is complete, stage st^1 is free
       SV_SB;
-      if (kt == nslices - 1) first_inputs();     // their round trip hides behind the last slice's products
+      if (kt == nsl - 1) first_inputs();     // their round trip hides behind the last slice's products
       SV_SB;
       step(xf1, wf1, xf0, wf0, true, st, 0, true, st ^ 1, 0);     // MFMAs of (kt-1, k step 3)
       step(xf0, wf0, xf1, wf1, true, st, 1, true, st ^ 1, 8);
@@ -699,8 +731,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
     // stage that was just consumed (16-byte chunks XOR-swizzled by the row: conflict-free both ways)
     // and reads it back so that 16 consecutive lanes cover 128 contiguous bytes of an output row;
     // every global access of the epilogue (result, residual, gate / up) becomes a full-line run.
-    const int sl = (par + nslices - 1) & 1;
-    par = (par + nslices) & 1;
+    const int sl = (par + nsl - 1) & 1;
+    par = (par + nsl) & 1;
     __syncthreads();                                   // everybody is done reading stage sl
     char* patch = smem + sl * STAGE + wave * 16384;
     // per wave, behind the two stages: the row factors of its 128 rows (each lane of the read-back needs those of the
@@ -803,9 +835,18 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(GemmArgs a, int tile
           float lo[4], hi[4];
 #pragma unroll
           for (int i = 0; i < 4; ++i) { lo[i] = a_lo[i]; hi[i] = a_hi[i]; }
+          const bool ok = !CHECK || wm * 128 + rb + er < M - m0;
+          if constexpr (SPLIT) {                       // the bare accumulators: 16 lanes x 16 bytes = 256 contiguous bytes of a row, twice
+            int vo = vW, so = rb * a.N * 4;
+            if (CHECK) { vo = (min(wm * 128 + rb + er, M - 1 - m0) * a.N + ec4 * 4) * 4; so = 0; }
+            if (ok) {
+              __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, a_lo), bW, vo, so, 0);
+              __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, a_hi), bW, vo + 256, so, 0);
+            }
+            continue;
+          }
           int vo, so;
           place(check_tag, rb, a.ldc, vC, vo, so);
-          const bool ok = !CHECK || wm * 128 + rb + er < M - m0;
           auto put_lo = [&](int w, bf16x4 pk) {
             if (ok) __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, pk), w == 0 ? bC : w == 1 ? bC2 : bC3, vo, so, 0);
           };
@@ -867,7 +908,28 @@ hipError_t launch_dma(const GemmArgs& a, hipStream_t st) {
     if (n_cu < 8) n_cu = 8;
   }
   const int grid = per_xcd * 8 < n_cu ? per_xcd * 8 : n_cu;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, a, tiles_m, tiles_n);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, a, tiles_m, tiles_n, 1);
+  return hipGetLastError();
+}
+
+// the 256 x 256 kernel over nsplit runs of k slices per tile, then the reduction with the epilogue
+template <int EPI>
+hipError_t launch_dma_split(const GemmArgs& a, int nsplit, hipStream_t st) {
+  auto kern = gemm_mfma_dma_kernel<EPI_STORE, false, false, true>;
+  constexpr int lds = 2 * 512 * 128 + 4 * 1024;
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  const int tiles_m = (a.M + 255) / 256, tiles_n = a.N / 256;
+  const int per_xcd = (tiles_m * tiles_n * nsplit + 7) / 8;
+  hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(256), lds, st, a, tiles_m, tiles_n, nsplit);   // at most one workgroup per CU
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int64_t threads = (int64_t)a.M * (a.N / 4);
+  hipLaunchKernelGGL(splitk_reduce_kernel<EPI>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, a, nsplit);
   return hipGetLastError();
 }
 
@@ -919,6 +981,24 @@ bool use_big_tile(const GemmArgs& a) {
   return tiles >= 192;
 }
 
+
+// Few tiles of 256 x 256 (few tokens against a wide projection): how many runs of k slices per tile bring the direct-to-LDS
+// kernel to about one workgroup per CU, or 0 where that form does not apply (no scratch for the partial products, the
+// dual or grouped product, fewer than 4 slices per run).  A 256-CU part is assumed: the rule only shapes the launch.
+int dma_split_runs(const GemmArgs& a) {
+  if (!a.split_ws || a.b_is_kn || a.tile_group || a.epi == EPI_SWIGLU || a.rowsq || a.N % 256) return 0;
+  const int64_t tiles = (int64_t)((a.M + 255) / 256) * (a.N / 256);
+  if (tiles >= 192) return 0;
+  int slices = 0;
+  for (int s = 0; s < a.nseg; ++s) {
+    slices += a.seg[s].K / BK;
+    if (!(256 * a.seg[s].lda * 2 < (int64_t)1 << 32 && 256 * a.seg[s].ldb * 2 < (int64_t)1 << 32)) return 0;
+  }
+  int64_t n = std::min<int64_t>(std::min<int64_t>(8, 256 / tiles), slices / 4);
+  n = std::min<int64_t>(n, a.split_ws_floats / ((int64_t)a.M * a.N));
+  return n >= 2 ? (int)n : 0;
+}
+
 }  // namespace
 
 namespace {
@@ -943,8 +1023,8 @@ bool mfma_gemm_supported(const GemmArgs& a) {
   if (dual && (a.b_is_kn || a.nseg != 1 || !a.B2 || a.ldb2 % 8 || !aligned16(a.B2))) return false;
   if (a.epi < EPI_STORE || a.epi > EPI_ROPE) return false;
   if (a.nbcol > 0 || a.epi == EPI_ROPE) {
-    // fused QKV form: served by the 256x256 direct-to-LDS kernel only
-    if (a.b_is_kn || a.nseg != 1 || a.nbcol > 3 || a.N % 256 || !use_big_tile(a)) return false;
+    // fused QKV form: served by the 256x256 direct-to-LDS kernel only (whole tiles, or runs of k slices for few tiles)
+    if (a.b_is_kn || a.nseg != 1 || a.nbcol > 3 || a.N % 256 || !(use_big_tile(a) || dma_split_runs(a))) return false;
     int tot = 0;
     for (int j = 0; j < a.nbcol; ++j) { if (a.ncol[j] % 256 || !aligned16(a.Bcol[j])) return false; tot += a.ncol[j]; }
     if (a.nbcol > 0 && tot != a.N) return false;
@@ -1002,6 +1082,21 @@ hipError_t mfma_gemm(const GemmArgs& a, hipStream_t st, int tile) {
         case EPI_SWIGLU_BWD: return launch_dma<EPI_SWIGLU_BWD, false>(a, st);
         case EPI_GELU_BWD: return launch_dma<EPI_GELU_BWD, false>(a, st);
         case EPI_ROPE: return launch_dma<EPI_ROPE, false>(a, st);
+        default: return hipErrorInvalidValue;
+      }
+    }
+  }
+  if (tile == 0) {
+    // few tokens: the large tile over runs of k slices, about one workgroup per CU, instead of small tiles
+    const int runs = dma_split_runs(a);
+    if (runs) {
+      switch (a.epi) {
+        case EPI_STORE: return launch_dma_split<EPI_STORE>(a, runs, st);
+        case EPI_RESID: return launch_dma_split<EPI_RESID>(a, runs, st);
+        case EPI_GELU: return launch_dma_split<EPI_GELU>(a, runs, st);
+        case EPI_SWIGLU_BWD: return launch_dma_split<EPI_SWIGLU_BWD>(a, runs, st);
+        case EPI_GELU_BWD: return launch_dma_split<EPI_GELU_BWD>(a, runs, st);
+        case EPI_ROPE: return launch_dma_split<EPI_ROPE>(a, runs, st);
         default: return hipErrorInvalidValue;
       }
     }
