@@ -93,7 +93,7 @@ def test_bf16_stage_with_the_norms_inside_the_products(desc, B, S, backward, pre
     """SV_FLAG_FUSE_NORM at sizes the oracle finishes in seconds: the row factors are applied by the small-tile and
     split-k epilogues (and by the large tile where the MLP is wide enough), they come from one read of the stream, and
     the gain-folded weights are made per call or once.  A LayerNorm stage ignores the flag.  (The sums of squares from
-    the large tile's residual epilogue and the fused q | k | v launch need more rows: the full-size tests run them.)"""
+    the large tile's residual epilogue need more rows: the full-size tests run them.)"""
     (gh, gg), (wh, wg), h = run_stage(desc, B, S, seed=12, backward=backward, weight_scale=2.0, fuse=True, prepare=prepare)
     assert_close(gh, wh, TOL["bf16"], "h")
     if backward:
@@ -141,6 +141,31 @@ def test_small_micro_batch_is_run_to_run_identical():
     np.testing.assert_array_equal(g1, g2)
     assert_close(h1, wh, TOL["bf16"], "h")
     assert_close(g1, wg, TOL["bf16"], "g")
+
+
+@pytest.mark.parametrize("fuse", [False, True], ids=["norm_pass", "norm_inside"])
+def test_few_tokens_take_the_one_launch_qkv_product_over_runs_of_k(fuse):
+    """500 tokens (a ragged second row tile) against 1024 q | k | v columns: 8 tiles of 256 x 256, so the large kernel
+    takes the fused product over two runs of k slices and the reduction applies RoPE (and the row factors of the first
+    norm when it runs inside the product): one q | k | v operation, no RoPE pass; the out- and down-projection and the
+    backward products (two and three k segments cut by the runs) go the same way."""
+    import paper_2603_03592_amd as sv
+    desc = si.StageDesc(1, 512, 16, 8, 3072)
+    B, S = 2, 250
+    w = si.make_weights(desc, 21)
+    h = si.make_activations(desc, B, S, 21)
+    g = si.make_output_grad(desc, B, S, 21, std=1e-3)
+    want_h, want_g = so.stage_backward(h, g, w, desc)
+    ver = sv.Verifier(desc, B * S, S, backward=True, fuse_norm=fuse)
+    wc = ver.pack_weights(wd := dev_weights(w, desc.dtype))
+    ver.profile_enable(True)
+    out = ver.verify_backward(wc, dev(h, desc.dtype), dev(g, desc.dtype), want_g_hat=True, want_h_hat=True)
+    prof = ver.profile_read()
+    ver.profile_enable(False)
+    assert prof["gemm_qkv"]["launches"] == 1 and prof["rope"]["launches"] == 0, (prof["gemm_qkv"], prof["rope"])
+    assert_close(host(out["h_hat"]), want_h, TOL["bf16"], "h")
+    assert_close(host(out["g_hat"]), want_g, TOL["bf16"], "g")
+    ver.close()
 
 
 def test_forward_on_a_backward_context_and_sequence_independence():
