@@ -153,7 +153,7 @@ int64_t sv_workspace_bytes(const sv_stage_desc *desc, int64_t max_tokens, int32_
  * tokens and sequences of at most max_seq tokens.  Allocates the workspace (hipMalloc): the
  * intermediates of one block (and, in backward mode, what every block stashes and the
  * transposed weights), the score pass's partial records, and for bf16 stages two fp32 scratch
- * areas that only small micro-batches use -- partial products of GEMMs split along k (at most
+ * areas that products with few output tiles use (small micro-batches) -- partial products split along k (at most
  * 84 MB) and, in backward mode with grouped-query attention, per-query-head dk | dv
  * contributions (n_heads / n_kv_heads x min(max_tokens, 131072 / n_kv_heads) x 2 x kv width
  * floats).  sv_workspace_bytes gives the total.                                              */

@@ -384,9 +384,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   }
 
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-  if (myq < S) {
+  {
+    // O leaves through LDS.  In the accumulators a lane holds scattered groups of 4 features of ONE query, so a store from
+    // there touches 32 rows with 16 bytes each (512 requests per wave and tile of queries: ~5 k cycles per pass).  The
+    // wave's 32 x HD block goes, normalised and in bf16, into its own patch of the second stage (free after the loop's last
+    // barrier; the next pass loads its first tile into the first stage), 16-byte chunks XOR-swizzled by the row, and comes
+    // back so that HD / 8 consecutive lanes hold one whole row.
+    constexpr int NCH = HD / 8, RPO = 64 / NCH;       // chunks per row; rows per store instruction
+    LDS char* const patch = lds0 + STAGE + wave_u * (32 * KROW);
     const float inv = 1.0f / l_tot;
-    bf16* orow = o + ((int64_t)b * S + myq) * Dq + (int64_t)h * HD;
+    // the lane numbers are made opaque here: the patch addresses are the same in every pass, and computed ahead of the
+    // tile loop they would live (or spill) across it
+    int e31 = l31, ehalf = half, elane = lane;
+    asm volatile("" : "+v"(e31), "+v"(ehalf), "+v"(elane));
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
 #pragma unroll
@@ -394,9 +404,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         bf16x4 pk;
 #pragma unroll
         for (int i = 0; i < 4; ++i) pk[i] = (bf16)(oacc[db][g4 * 4 + i] * inv);
-        *reinterpret_cast<bf16x4*>(orow + db * 32 + g4 * 8 + half * 4) = pk;
+        *reinterpret_cast<LDS bf16x4*>(patch + e31 * KROW + (((db * 4 + g4) ^ (e31 & (NCH - 1))) << 4) + ehalf * 8) = pk;
       }
-    if (half == 0) lse[((int64_t)b * H + h) * S + myq] = (m_run + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994531f;
+    __builtin_amdgcn_s_waitcnt(0xc07f);               // lgkmcnt(0): the patch is complete before it is read back
+    __builtin_amdgcn_wave_barrier();
+    const int orow = elane / NCH, ochunk = elane % NCH;
+#pragma unroll
+    for (int it = 0; it < 32 / RPO; ++it) {
+      const int row = it * RPO + orow, q = wq0 + row;
+      const bf16x8 v = *reinterpret_cast<const LDS bf16x8*>(patch + row * KROW + ((ochunk ^ (row & (NCH - 1))) << 4));
+      if (q < S) *reinterpret_cast<bf16x8*>(o + ((int64_t)b * S + q) * Dq + (int64_t)h * HD + ochunk * 8) = v;
+    }
+    if (myq < S && half == 0) lse[((int64_t)b * H + h) * S + myq] = (m_run + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994531f;
   }
   }  // pass
 }
