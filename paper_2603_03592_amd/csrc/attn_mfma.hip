@@ -574,8 +574,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     dma_wait_all();
     __syncthreads();                                  // fence + barrier: the next tile has landed for everybody
   }
-  if (myq < S) {
-    bf16* out = dqkv + ((int64_t)b * S + myq) * ld + (int64_t)h * HD;
+  {
+    // dq leaves through LDS as whole rows, like the forward kernel's output: the wave's 32 x HD block, scaled, rotated back
+    // and in bf16, goes into its patch of the second stage (free after the loop's last barrier) and comes back so that
+    // HD / 8 consecutive lanes hold one row.
+    constexpr int RPO = 64 / KCH;                     // rows per store instruction
+    LDS char* const patch = (LDS char*)smem + STAGE + wave_u * (32 * HD * 2);
+    int e31 = l31, ehalf = half, elane = lane;        // opaque: the patch addresses are not to live across the tile loop
+    asm volatile("" : "+v"(e31), "+v"(ehalf), "+v"(elane));
+    const int pq = min(myq, S - 1);                   // rows past the end are made and never stored
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
 #pragma unroll
@@ -583,12 +590,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         float v[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) v[i] = dq[db][g4 * 4 + i] * scale;
-        if (rope_cs) unrope4<HD>(v, rope_cs, myq, db * 32 + g4 * 8 + half * 4);
+        if (rope_cs) unrope4<HD>(v, rope_cs, pq, db * 32 + g4 * 8 + half * 4);
         bf16x4 pk;
 #pragma unroll
         for (int i = 0; i < 4; ++i) pk[i] = (bf16)v[i];
-        *reinterpret_cast<bf16x4*>(out + db * 32 + g4 * 8 + half * 4) = pk;
+        *reinterpret_cast<LDS bf16x4*>(patch + e31 * (HD * 2) + (((db * 4 + g4) ^ (e31 & (KCH - 1))) << 4) + ehalf * 8) = pk;
       }
+    __builtin_amdgcn_s_waitcnt(0xc07f);               // lgkmcnt(0): the patch is complete before it is read back
+    __builtin_amdgcn_wave_barrier();
+    const int orow = elane / KCH, ochunk = elane % KCH;
+#pragma unroll
+    for (int it = 0; it < 32 / RPO; ++it) {
+      const int row = it * RPO + orow, q = wq0 + row;
+      const bf16x8 v = *reinterpret_cast<const LDS bf16x8*>(patch + row * (HD * 2) + ((ochunk ^ (row & (KCH - 1))) << 4));
+      if (q < S) *reinterpret_cast<bf16x8*>(dqkv + ((int64_t)b * S + q) * ld + (int64_t)h * HD + ochunk * 8) = v;
+    }
   }
   }  // pass
 }
@@ -775,19 +791,41 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       *reinterpret_cast<f32x4*>(out + fb * 16 + lg * 4) = ok;
       *reinterpret_cast<f32x4*>(out + Dkv + fb * 16 + lg * 4) = dv[fb];
     }
-  } else if (mykey < S) {
-    bf16* out = dqkv + ((int64_t)b * S + mykey) * ld + Dq + (int64_t)kvh * HD;
+  } else if (!part) {
+    // dk and dv leave through LDS as whole rows: the wave's two 16 x HD blocks (dk scaled and rotated back), in bf16, go
+    // into its patch of the second stage's tiles (free after the loop's last barrier; the next pass loads into the first
+    // stage) with the 16-byte chunks XOR-swizzled by the key, and come back so that HD / 8 consecutive lanes hold one row.
+    constexpr int KCH = HD / 8, RPO = 64 / KCH, ROWB = HD * 2;
+    LDS char* const patch = (LDS char*)smem + STAGE + wave_u * (2 * 16 * ROWB);
+    int e15 = l15, elg = lg, elane = lane;            // opaque: the patch addresses are not to live across the tile loop
+    asm volatile("" : "+v"(e15), "+v"(elg), "+v"(elane));
 #pragma unroll
     for (int fb = 0; fb < NFB; ++fb) {
       float v[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) v[i] = dk[fb][i] * scale;
-      if (rope_cs) unrope4<HD>(v, rope_cs, mykey, fb * 16 + lg * 4);
+      if (rope_cs) unrope4<HD>(v, rope_cs, krow, fb * 16 + lg * 4);
       bf16x4 pk, pv;
 #pragma unroll
       for (int i = 0; i < 4; ++i) { pk[i] = (bf16)v[i]; pv[i] = (bf16)dv[fb][i]; }
-      *reinterpret_cast<bf16x4*>(out + fb * 16 + lg * 4) = pk;
-      *reinterpret_cast<bf16x4*>(out + Dkv + fb * 16 + lg * 4) = pv;
+      LDS char* const at = patch + e15 * ROWB + (((fb * 2 + (elg >> 1)) ^ (e15 & (KCH - 1))) << 4) + (elg & 1) * 8;
+      *reinterpret_cast<LDS bf16x4*>(at) = pk;
+      *reinterpret_cast<LDS bf16x4*>(at + 16 * ROWB) = pv;
+    }
+    __builtin_amdgcn_s_waitcnt(0xc07f);               // lgkmcnt(0): the patch is complete before it is read back
+    __builtin_amdgcn_wave_barrier();
+    const int orow = elane / KCH, ochunk = elane % KCH;
+#pragma unroll
+    for (int it = 0; it < 16 / RPO; ++it) {
+      const int row = it * RPO + orow, key = wk0 + row;
+      LDS const char* const at = patch + row * ROWB + ((ochunk ^ (row & (KCH - 1))) << 4);
+      const bf16x8 vk = *reinterpret_cast<const LDS bf16x8*>(at);
+      const bf16x8 vv = *reinterpret_cast<const LDS bf16x8*>(at + 16 * ROWB);
+      if (key < S) {
+        bf16* out = dqkv + ((int64_t)b * S + key) * ld + Dq + (int64_t)kvh * HD + ochunk * 8;
+        *reinterpret_cast<bf16x8*>(out) = vk;
+        *reinterpret_cast<bf16x8*>(out + Dkv) = vv;
+      }
     }
   }
   }  // pass
