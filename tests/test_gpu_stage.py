@@ -120,6 +120,18 @@ def test_wide_mlp_on_the_large_tile_with_a_ragged_row_tail(backward):
         assert_close(gg, wg, TOL["bf16"], "g")
 
 
+@pytest.mark.parametrize("norm,fuse", [("ln", False), ("rms", False), ("rms", True)], ids=["layernorm", "rmsnorm", "rmsnorm_inside"])
+def test_wide_gelu_mlp_on_the_large_tile_with_a_ragged_row_tail(norm, fuse):
+    """The GELU kinds of the 256 x 256 kernel's epilogue: 9 row tiles (the last with 52 rows) x 22 column tiles for the
+    up-projection (GELU, pre-activation stashed) and for the product that takes the GELU's derivative on the way back
+    (its input read ahead of the stores, row-checked in the last row tile); with the RMSNorm inside, the up-projection
+    also applies the row factors."""
+    desc = si.StageDesc(1, 256, 4, 2, 5632, mlp="gelu", norm=norm, rope=norm == "rms")
+    (gh, gg), (wh, wg), h = run_stage(desc, 3, 700, seed=8, backward=True, weight_scale=2.0, fuse=fuse)
+    assert_close(gh, wh, TOL["bf16"], "h")
+    assert_close(gg, wg, TOL["bf16"], "g")
+
+
 @pytest.mark.parametrize("B", [4, 32], ids=["one_workgroup_per_query_head", "one_workgroup_per_kv_head"])
 def test_grouped_query_backward_both_decompositions(B):
     """8 kv heads of 2 query heads, 4 key tiles -- 2 workgroups -- per (sequence, kv head): with 4 sequences the dk / dv
